@@ -1,0 +1,216 @@
+/*
+ * faar.h -- C ABI of the FAAR (Format-Aware Adaptive Rounding for NVFP4) per-layer
+ * rounding-optimisation path for AMD MI355X (gfx950).
+ *
+ * Conventions, valid for every entry point unless its comment says otherwise
+ * ---------------------------------------------------------------------------
+ *  - A linear layer's weight W is [O, K] row-major (out_features x in_features, K contiguous).
+ *    Calibration activations are [T, K] row-major, layer outputs [T, O] row-major.
+ *    K must be a multiple of 16: a scale block is 16 consecutive weights along K and never
+ *    straddles rows (paper Sec. 3.1: blocks of 16 elements, one FP8-E4M3 scale each, one FP32
+ *    scale per tensor).
+ *  - Every pointer is a DEVICE pointer owned by the caller, except `opt` of faar_layer_step
+ *    (a host pointer, read during the call).  The library never allocates, frees or copies to
+ *    the host, and never synchronises: all work is enqueued on `stream` (a hipStream_t passed
+ *    as void*; NULL is the default stream).  Scalar results are written to device memory.
+ *  - Device buffers must be 16-byte aligned.  Buffers must not overlap unless stated.
+ *  - Scratch memory comes from a caller-provided workspace `ws` of at least
+ *    faar_workspace_bytes(op, ...) bytes; its contents are undefined after the call.
+ *  - Return value: FAAR_OK, or a negative error code, in which case NOTHING was launched.
+ *    FAAR_E_HIP means a HIP call failed; the raw hipError_t is kept per host thread and read
+ *    with faar_last_hip_error().  No other global mutable state exists.
+ *  - E2M1 nibble: bit 3 sign, bits 2..0 magnitude code 0..7 <-> {0, .5, 1, 1.5, 2, 3, 4, 6}
+ *    (the node set of Sec. 3.1).  Packed codes are [O, K/2] bytes, element 2j of a row in the low
+ *    nibble of byte j.  Block scales are [O, K/16] bytes, row-major, un-swizzled, always in
+ *    0x00..0x7E (non-negative, finite).
+ *  - Decision arithmetic (everything that ends in a byte, a nibble or a bit, and V_init) is IEEE
+ *    float32, round-to-nearest-even, in the operation order documented at each entry point, so
+ *    that results are reproducible bit for bit.  NaN/Inf in W are not supported (undefined codes).
+ */
+#ifndef FAAR_H_
+#define FAAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FAAR_F32 = 0, FAAR_BF16 = 1 } faar_dtype;
+
+enum {
+  FAAR_OK = 0,
+  FAAR_E_NULL = -1,      /* a required pointer is NULL */
+  FAAR_E_SHAPE = -2,     /* O, K or T <= 0, K % 16 != 0, or a size beyond a documented limit */
+  FAAR_E_DTYPE = -3,     /* dtype value not supported for that argument */
+  FAAR_E_WORKSPACE = -4, /* ws == NULL or ws_bytes too small */
+  FAAR_E_HIP = -5,       /* a HIP runtime call failed; see faar_last_hip_error() */
+  FAAR_E_ARG = -6,       /* scalar out of domain (beta <= 0, lr < 0, non-finite), unknown flag or
+                            unaligned pointer */
+  FAAR_E_UNSUPPORTED = -7 /* combination of arguments not implemented */
+};
+
+/* flags */
+enum {
+  FAAR_SGLOBAL_GIVEN = 1u << 0, /* faar_quant_rtn: *s_global is an input instead of an output */
+  FAAR_EMIT_DELTA = 1u << 1,    /* faar_softquant_fwd_bwd: Wt receives W_q - W instead of W_q */
+  FAAR_WS_CHAINED = 1u << 2     /* faar_workspace_bytes / faar_layer_step: size the workspace for a
+                                   step that takes dY_ext and/or produces dX */
+};
+
+/* operations, for faar_workspace_bytes */
+enum {
+  FAAR_OP_QUANT_RTN = 0,
+  FAAR_OP_INIT_V = 1,
+  FAAR_OP_SOFTQUANT = 2,
+  FAAR_OP_LAYER_PREPARE = 3,
+  FAAR_OP_LAYER_STEP = 4,
+  FAAR_OP_HARDEN_PACK = 5
+};
+
+/* Library version, MAJOR*10000 + MINOR*100 + PATCH.  Pure host function. */
+int faar_version(void);
+
+/* hipError_t of the last failed HIP call made by this host thread (0 if none). */
+int faar_last_hip_error(void);
+
+/* Workspace size in bytes that `op` needs for these sizes (T is ignored by ops that take no
+ * activations; `flags` as passed to the op).  Pure host function; returns 0 for an unknown op or
+ * invalid sizes. */
+size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags);
+
+/* Padded leading dimension (in elements) of the transposed activations Xt written by
+ * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
+int64_t faar_padded_tokens(int64_t T);
+
+/*
+ * Round-to-nearest NVFP4 quantisation of a tensor -- the baseline rounding of Sec. 3.1/3.2 and
+ * the two-level scaling of Table 2 step 2.
+ *
+ *   amax      = max |w|                         ; s_global = amax / 2688   (2688 = 6 * 448; 1 if amax == 0)
+ *   a_b       = max |w| over the block          ; byte = E4M3_rne_sat((a_b / 6) / s_global)
+ *   s         = E4M3_value(byte) * s_global     ; w~ = |w| / s   (0 if s == 0)
+ *   k_lo      = #{node in {.5,1,1.5,2,3,4} : node <= w~}   (interval [N[k_lo], N[k_lo+1]])
+ *   v_init    = clamp((w~ - N[k_lo]) / (N[k_lo+1] - N[k_lo]), 0, 1)
+ *   nibble    = signbit(w) << 3 | (w == 0 ? 0 : k_lo + (v_init >= 0.5))   -- exact midpoints go up
+ *
+ *   W        in  [O*K] of dtype wdt (FAAR_F32 or FAAR_BF16)
+ *   s_global out float[1] (in, if flags & FAAR_SGLOBAL_GIVEN)
+ *   scales   out uint8[O*K/16]
+ *   codes    out uint8[O*K/2]
+ *   W_dq     out, nullable: dequantised weights sign * N[code] * E4M3_value(byte) * s_global,
+ *            dtype wdt (float32 product rounded once; then to bf16 if wdt is bf16)
+ *   ws       FAAR_OP_QUANT_RTN workspace
+ */
+int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                   float* s_global, uint8_t* scales, uint8_t* codes, void* W_dq,
+                   uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Initial rounding variables -- Eq. 4 / Table 2 steps 2-5: V = v_init as defined above, from W and
+ * the scales produced by faar_quant_rtn.
+ *
+ *   V           out float[O*K]
+ *   floor_codes out, nullable uint8[O*K/2]: packed nibbles signbit(w) << 3 | k_lo
+ */
+int faar_init_v(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                const float* s_global, const uint8_t* scales,
+                float* V, uint8_t* floor_codes, void* stream);
+
+/*
+ * Soft quantisation forward, and (when dWt != NULL) its backward -- Eq. 2, Eq. 3, and the
+ * V-gradient of Eq. 5 (Table 2 steps 6-7 and 11-12).
+ *
+ *   h    = 1 / (1 + exp(-beta (v - 1/2)))
+ *   W_q  = sign(w) (N[k_lo] + h (N[k_lo+1] - N[k_lo])) s          (sign(0) = 0)
+ *   Wt   out bf16[O*K]: W_q, or W_q - W with FAAR_EMIT_DELTA, rounded to bf16
+ *   dV   = dWt * sign(w) s (N[k_lo+1] - N[k_lo]) beta h (1 - h) + lambda_round / (O*K) * (4 - 8 v)
+ *   round_loss = (1 / (O*K)) sum (1 - (2 v - 1)^2)
+ *
+ *   V          in  float[O*K]
+ *   dWt        in, nullable float[O*K]: dL/dW_q; when NULL only the forward runs
+ *   dV         out float[O*K], required iff dWt != NULL
+ *   round_loss out, nullable float[1] (written only when dWt != NULL)
+ *   beta > 0 and finite.  ws: FAAR_OP_SOFTQUANT workspace.  float32 arithmetic.
+ */
+int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                           const float* s_global, const uint8_t* scales,
+                           const float* V, float beta, void* Wt,
+                           const float* dWt, float lambda_round, float* dV, float* round_loss,
+                           uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Per-layer constants of the Stage-1 objective (Eq. 5, Table 2 steps 8-9), computed once before
+ * the first faar_layer_step of a layer:
+ *
+ *   Xt = Xq^T                as bf16 [K, Tp], Tp = faar_padded_tokens(T), columns T..Tp-1 zero
+ *   C  = Y_fp - Xq W^T       as float [T, O]   (bf16 products are exact, float32 accumulation;
+ *                                                a float32 W is split into three bf16 terms)
+ *
+ * The residual of Eq. 5 is then  Xq W_q^T - Y_fp = Xq (W_q - W)^T - C,  which lets the step run its
+ * GEMM on the small perturbation W_q - W without losing it to bf16 rounding of W_q.
+ *
+ *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4)
+ *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T
+ *   ws   FAAR_OP_LAYER_PREPARE workspace
+ */
+int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                       const void* Xq, const void* Y_fp, faar_dtype ydt, int64_t T,
+                       void* Xt, float* C, void* ws, size_t ws_bytes, void* stream);
+
+/* Adam hyper-parameters; t is the 1-based index of the step being taken. */
+typedef struct {
+  float lr, beta1, beta2, eps;
+  int32_t t;
+} faar_adam;
+
+/*
+ * One rounding-optimisation step for one linear layer -- Table 2 steps 6-13, Eq. 5:
+ *
+ *   W_q(V) by Eq. 2-3;  R = Xq W_q^T - Y_fp;  L_mse = mse_scale * ||R||_F^2
+ *   L_round = (1/N) sum (1 - (2 v - 1)^2);  L = L_mse + lambda_round * L_round
+ *   dY = 2 mse_scale R (or dY_ext);  G = dY^T Xq;  dV as in faar_softquant_fwd_bwd with dWt = G
+ *   Adam (bias-corrected, no weight decay) on V with state (adam_m, adam_v), then V clipped to [0, 1].
+ *
+ * GEMMs run on the bf16 matrix cores with float32 accumulation; three tensors are rounded to bf16
+ * where they are stored: W_q - W, dY and dX.  Everything else is float32; loss sums are
+ * accumulated in a fixed order (results are bit-reproducible run to run).
+ *
+ *   V, adam_m, adam_v   in/out float[O*K]
+ *   Xq, Xt, C           as for / from faar_layer_prepare
+ *   dY_ext              in, nullable bf16[T*O]: upstream gradient replacing the locally derived dY
+ *   dX                  out, nullable bf16[T*K]: dY W_q
+ *   opt                 HOST pointer
+ *   losses              out float[3]: L_mse, L_round, L
+ *   ws                  FAAR_OP_LAYER_STEP workspace (queried with FAAR_WS_CHAINED when dY_ext or dX
+ *                       is given; that mode also requires O % 8 == 0)
+ *   flags               0 or FAAR_WS_CHAINED (accepted, no effect on the computation)
+ */
+int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                    const float* s_global, const uint8_t* scales,
+                    float* V, float* adam_m, float* adam_v,
+                    const void* Xq, const void* Xt, const float* C, int64_t T,
+                    const void* dY_ext, void* dX,
+                    float beta, float lambda_round, float mse_scale, const faar_adam* opt,
+                    float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Hardening and NVFP4 packing -- Eq. 7 and Table 2 steps 25-26:
+ *   v_hat = (v >= 0.5) on the stored float32 V;  nibble = signbit(w) << 3 | (w == 0 ? 0 : k_lo + v_hat).
+ *
+ *   codes      out uint8[O*K/2]
+ *   decisions  out, nullable uint8[O*K/8]: bit i of byte j is v_hat of flattened element 8j+i
+ *   W_final    out, nullable, dtype wdt: dequantised final weights (as W_dq of faar_quant_rtn)
+ *   flip_count out, nullable uint64[1]: number of weights whose nibble differs from
+ *              round-to-nearest.  The kernel ADDS to it: the caller zeroes it first.
+ */
+int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                     const float* s_global, const uint8_t* scales, const float* V,
+                     uint8_t* codes, uint8_t* decisions, void* W_final,
+                     unsigned long long* flip_count, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FAAR_H_ */

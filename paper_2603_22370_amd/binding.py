@@ -1,0 +1,202 @@
+"""ctypes binding of libfaar.so: same entry-point names as include/faar.h, argument marshalling
+only.  torch is used for device memory and streams; every step of the method runs in the HIP
+kernels behind the C ABI.  There is no fallback: a missing library raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_float, c_int, c_int32, c_int64, c_size_t, c_uint32, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfaar.so")
+
+FAAR_F32, FAAR_BF16 = 0, 1
+FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED = 1, 2, 4
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK = range(6)
+ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
+          -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
+
+
+class FaarError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        detail = f" (hipError_t {lib().faar_last_hip_error()})" if code == -5 else ""
+        super().__init__(f"{where}: {ERRORS.get(code, code)}{detail}")
+
+
+class faar_adam(ctypes.Structure):
+    _fields_ = [("lr", c_float), ("beta1", c_float), ("beta2", c_float), ("eps", c_float), ("t", c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (python -m paper_2603_22370_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build(); "
+                               "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.faar_version.restype = c_int
+        L.faar_last_hip_error.restype = c_int
+        L.faar_workspace_bytes.restype = c_size_t
+        L.faar_workspace_bytes.argtypes = [c_int, c_int64, c_int64, c_int64, c_uint32]
+        L.faar_padded_tokens.restype = c_int64
+        L.faar_padded_tokens.argtypes = [c_int64]
+        L.faar_quant_rtn.restype = c_int
+        L.faar_quant_rtn.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                                     c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_init_v.restype = c_int
+        L.faar_init_v.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+        L.faar_softquant_fwd_bwd.restype = c_int
+        L.faar_softquant_fwd_bwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float,
+                                             c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p,
+                                             c_size_t, c_void_p]
+        L.faar_layer_prepare.restype = c_int
+        L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_int, c_int64,
+                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_layer_step.restype = c_int
+        L.faar_layer_step.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p,
+                                      c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p, c_uint32,
+                                      c_void_p, c_size_t, c_void_p]
+        L.faar_harden_pack.restype = c_int
+        L.faar_harden_pack.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                                       c_void_p, c_void_p, c_void_p, c_void_p]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else c_void_p(t.data_ptr())
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FAAR_F32
+    if t.dtype == torch.bfloat16:
+        return FAAR_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(*ts):
+    for t in ts:
+        if t is not None and (not t.is_cuda or not t.is_contiguous()):
+            raise ValueError("tensors must be contiguous device tensors")
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise FaarError(rc, where)
+
+
+def faar_workspace_bytes(op: int, O: int, K: int, T: int = 0, flags: int = 0) -> int:
+    return int(lib().faar_workspace_bytes(op, O, K, T, flags))
+
+
+def faar_padded_tokens(T: int) -> int:
+    return int(lib().faar_padded_tokens(T))
+
+
+def _workspace(op, O, K, T=0, flags=0, device="cuda"):
+    n = faar_workspace_bytes(op, O, K, T, flags)
+    if n == 0:
+        raise FaarError(-2, "faar_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def faar_quant_rtn(W, s_global=None, want_dq=False, ws=None):
+    """-> (s_global[1] f32, scales [O,K/16] u8, codes [O,K/2] u8, W_dq or None)."""
+    _dev(W, s_global, ws)
+    O, K = W.shape
+    flags = 0
+    if s_global is None:
+        s_global = torch.empty(1, dtype=torch.float32, device=W.device)
+    else:
+        flags |= FAAR_SGLOBAL_GIVEN
+    scales = torch.empty((O, K // 16), dtype=torch.uint8, device=W.device)
+    codes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
+    W_dq = torch.empty_like(W) if want_dq else None
+    ws = _workspace(OP_QUANT_RTN, O, K, device=W.device) if ws is None else ws
+    _check(lib().faar_quant_rtn(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(codes), _ptr(W_dq),
+                                flags, _ptr(ws), ws.numel(), _stream()), "faar_quant_rtn")
+    return s_global, scales, codes, W_dq
+
+
+def faar_init_v(W, s_global, scales, want_floor_codes=False):
+    """-> (V [O,K] f32, floor_codes [O,K/2] u8 or None)."""
+    _dev(W, s_global, scales)
+    O, K = W.shape
+    V = torch.empty((O, K), dtype=torch.float32, device=W.device)
+    fc = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device) if want_floor_codes else None
+    _check(lib().faar_init_v(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(fc), _stream()),
+           "faar_init_v")
+    return V, fc
+
+
+def faar_softquant_fwd_bwd(W, s_global, scales, V, beta, dWt=None, lambda_round=0.0, emit_delta=False, ws=None):
+    """-> (Wt bf16 [O,K], dV f32 or None, round_loss f32[1] or None)."""
+    _dev(W, s_global, scales, V, dWt, ws)
+    O, K = W.shape
+    Wt = torch.empty((O, K), dtype=torch.bfloat16, device=W.device)
+    dV = torch.empty((O, K), dtype=torch.float32, device=W.device) if dWt is not None else None
+    rl = torch.empty(1, dtype=torch.float32, device=W.device) if dWt is not None else None
+    ws = _workspace(OP_SOFTQUANT, O, K, device=W.device) if ws is None else ws
+    flags = FAAR_EMIT_DELTA if emit_delta else 0
+    _check(lib().faar_softquant_fwd_bwd(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), float(beta),
+                                        _ptr(Wt), _ptr(dWt), float(lambda_round), _ptr(dV), _ptr(rl), flags,
+                                        _ptr(ws), ws.numel(), _stream()), "faar_softquant_fwd_bwd")
+    return Wt, dV, rl
+
+
+def faar_layer_prepare(W, Xq, Y_fp, ws=None):
+    """-> (Xt bf16 [K, Tp], C f32 [T, O])."""
+    _dev(W, Xq, Y_fp, ws)
+    O, K = W.shape
+    T = Xq.shape[0]
+    if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or tuple(Y_fp.shape) != (T, O):
+        raise ValueError("Xq must be bf16 [T,K]; Y_fp must be [T,O]")
+    Xt = torch.empty((K, faar_padded_tokens(T)), dtype=torch.bfloat16, device=W.device)
+    C = torch.empty((T, O), dtype=torch.float32, device=W.device)
+    ws = _workspace(OP_LAYER_PREPARE, O, K, T, device=W.device) if ws is None else ws
+    _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(Xq), _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C),
+                                    _ptr(ws), ws.numel(), _stream()), "faar_layer_prepare")
+    return Xt, C
+
+
+def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, beta, lambda_round, mse_scale,
+                    lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None):
+    """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L)."""
+    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, losses, ws, dY_ext, dX)
+    O, K = W.shape
+    T = Xq.shape[0]
+    opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
+    _check(lib().faar_layer_step(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m),
+                                 _ptr(adam_v), _ptr(Xq), _ptr(Xt), _ptr(C), T, _ptr(dY_ext), _ptr(dX),
+                                 float(beta), float(lambda_round), float(mse_scale), ctypes.byref(opt),
+                                 _ptr(losses), 0, _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
+
+
+def layer_step_workspace(O, K, T, chained=False, device="cuda"):
+    return _workspace(OP_LAYER_STEP, O, K, T, FAAR_WS_CHAINED if chained else 0, device=device)
+
+
+def faar_harden_pack(W, s_global, scales, V, want_decisions=False, want_final=False, want_flips=False):
+    """-> (codes [O,K/2] u8, decisions [O*K/8] u8 or None, W_final or None, flip_count i64[1] or None)."""
+    _dev(W, s_global, scales, V)
+    O, K = W.shape
+    codes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
+    dec = torch.empty(O * K // 8, dtype=torch.uint8, device=W.device) if want_decisions else None
+    Wf = torch.empty_like(W) if want_final else None
+    flips = torch.zeros(1, dtype=torch.int64, device=W.device) if want_flips else None
+    _check(lib().faar_harden_pack(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(codes),
+                                  _ptr(dec), _ptr(Wf), _ptr(flips), _stream()), "faar_harden_pack")
+    return codes, dec, Wf, flips

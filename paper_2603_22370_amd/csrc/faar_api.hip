@@ -1,0 +1,271 @@
+// extern "C" entry points of libfaar (declared and documented in include/faar.h): argument
+// validation, workspace carving and kernel sequencing.  Nothing here allocates or synchronises.
+#include <cmath>
+
+#include "../../include/faar.h"
+#include "faar_internal.h"
+
+using namespace faar;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline int hip_status(hipError_t e) {
+  if (e == hipSuccess) return FAAR_OK;
+  g_last_hip_error = static_cast<int>(e);
+  return FAAR_E_HIP;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+// Largest tensor / activation extents accepted: index arithmetic is 64-bit, grids are 32-bit.
+constexpr int64_t kMaxElems = (int64_t)1 << 36;
+
+int check_shape(int64_t O, int64_t K) {
+  if (O <= 0 || K <= 0 || K % 16 != 0) return FAAR_E_SHAPE;
+  if (O > kMaxElems / K) return FAAR_E_SHAPE;
+  return FAAR_OK;
+}
+int check_wdt(faar_dtype dt) { return (dt == FAAR_F32 || dt == FAAR_BF16) ? FAAR_OK : FAAR_E_DTYPE; }
+
+// Carves 256-byte aligned regions out of the caller's workspace.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  template <typename T> T* take(size_t count) {
+    T* r = reinterpret_cast<T*>(base + off);
+    off += align256(count * sizeof(T));
+    return r;
+  }
+};
+
+struct StepLayout {
+  size_t delta, dYt, G, mse_partials, round_partials, wq_full, wqt, dY, total;
+  int n_split;
+  int64_t Tp, Op;
+};
+
+StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
+  StepLayout L{};
+  L.Tp = padded_tokens(T);
+  L.Op = round_up(O, 64);
+  L.n_split = choose_split(O, K, L.Tp);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align256(bytes); return r; };
+  L.delta = take((size_t)O * K * 2);
+  L.dYt = take((size_t)O * L.Tp * 2);
+  L.G = take((size_t)L.n_split * O * K * 4);
+  L.mse_partials = take((size_t)gemm_residual_tiles(T, O) * 8);
+  L.round_partials = take((size_t)softquant_bwd_blocks(O * K) * 8);
+  if (chained) {
+    L.wq_full = take((size_t)O * K * 2);
+    L.wqt = take((size_t)K * L.Op * 2);
+    L.dY = take((size_t)T * O * 2);
+  }
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+extern "C" {
+
+int faar_version(void) { return 100; }
+
+int faar_last_hip_error(void) { return g_last_hip_error; }
+
+int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
+
+size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags) {
+  if (check_shape(O, K) != FAAR_OK) return 0;
+  switch (op) {
+    case FAAR_OP_QUANT_RTN:
+      return align256(kAmaxPartials * sizeof(float));
+    case FAAR_OP_INIT_V:
+    case FAAR_OP_HARDEN_PACK:
+      return 256;  // none needed; a non-zero size keeps callers' allocation code uniform
+    case FAAR_OP_SOFTQUANT:
+      return align256((size_t)softquant_bwd_blocks(O * K) * sizeof(double));
+    case FAAR_OP_LAYER_PREPARE:
+      if (T <= 0) return 0;
+      return 3 * align256((size_t)O * K * 2);  // hi/mid/lo bf16 terms of a float32 W
+    case FAAR_OP_LAYER_STEP:
+      if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return 0;
+      return step_layout(O, K, T, (flags & FAAR_WS_CHAINED) != 0).total;
+    default:
+      return 0;
+  }
+}
+
+int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K, float* s_global,
+                   uint8_t* scales, uint8_t* codes, void* W_dq, uint32_t flags, void* ws,
+                   size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !codes) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (flags & ~(uint32_t)FAAR_SGLOBAL_GIVEN) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(codes) || !aligned16(W_dq) || (reinterpret_cast<uintptr_t>(s_global) & 3u))
+    return FAAR_E_ARG;
+  const bool given = (flags & FAAR_SGLOBAL_GIVEN) != 0;
+  if (!given && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_QUANT_RTN, O, K, 0, flags))) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = wdt == FAAR_BF16;
+  if (!given)
+    if (int e = hip_status(launch_amax(W, bf, O * K, static_cast<float*>(ws), s_global, st))) return e;
+  return hip_status(launch_quant_rtn(W, bf, O * K, s_global, scales, codes, W_dq, st));
+}
+
+int faar_init_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                const uint8_t* scales, float* V, uint8_t* floor_codes, void* stream) {
+  if (!W || !s_global || !scales || !V) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(floor_codes)) return FAAR_E_ARG;
+  return hip_status(launch_init_v(W, wdt == FAAR_BF16, O * K, s_global, scales, V, floor_codes,
+                                  static_cast<hipStream_t>(stream)));
+}
+
+int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                           const uint8_t* scales, const float* V, float beta, void* Wt,
+                           const float* dWt, float lambda_round, float* dV, float* round_loss,
+                           uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !V || !Wt) return FAAR_E_NULL;
+  if (dWt && !dV) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (flags & ~(uint32_t)FAAR_EMIT_DELTA) return FAAR_E_ARG;
+  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round)) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(Wt) || !aligned16(dWt) || !aligned16(dV)) return FAAR_E_ARG;
+  if (dWt && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_SOFTQUANT, O, K, 0, flags))) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = wdt == FAAR_BF16;
+  const int64_t n = O * K;
+  if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, (flags & FAAR_EMIT_DELTA) != 0,
+                                              static_cast<bf16_t*>(Wt), nullptr, st)))
+    return e;
+  if (!dWt) return FAAR_OK;
+  double* partials = static_cast<double*>(ws);
+  if (int e = hip_status(launch_softquant_bwd(W, bf, n, s_global, scales, V, beta, dWt, 1, 0, lambda_round, dV,
+                                              partials, st)))
+    return e;
+  if (round_loss)
+    return hip_status(launch_finalize_losses(nullptr, 0, 0.0f, partials, softquant_bwd_blocks(n), 1.0 / (double)n,
+                                             lambda_round, nullptr, round_loss, nullptr, st));
+  return FAAR_OK;
+}
+
+int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const void* Xq,
+                       const void* Y_fp, faar_dtype ydt, int64_t T, void* Xt, float* C, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (!W || !Xq || !Y_fp || !Xt || !C) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_wdt(ydt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
+  if (!aligned16(W) || !aligned16(Xq) || !aligned16(Y_fp) || !aligned16(Xt) || !aligned16(C)) return FAAR_E_ARG;
+  const bool bf = wdt == FAAR_BF16;
+  if (!bf && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_LAYER_PREPARE, O, K, T, 0))) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bf16_t* xq = static_cast<const bf16_t*>(Xq);
+  if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), padded_tokens(T), st))) return e;
+  const GemmDims d{T, O, K, K, K};
+  if (bf) return hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, st));
+  Carver cv(ws);
+  bf16_t* term[3];
+  for (auto& t : term) t = cv.take<bf16_t>((size_t)O * K);
+  if (int e = hip_status(launch_split_f32(static_cast<const float*>(W), O * K, term[0], term[1], term[2], st))) return e;
+  for (int i = 0; i < 3; ++i)
+    if (int e = hip_status(launch_gemm_sub(xq, term[i], d, Y_fp, ydt == FAAR_BF16, i == 0, C, st))) return e;
+  return FAAR_OK;
+}
+
+int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                    const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq,
+                    const void* Xt, const float* C, int64_t T, const void* dY_ext, void* dX,
+                    float beta, float lambda_round, float mse_scale, const faar_adam* opt,
+                    float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !opt || !losses)
+    return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
+  const bool chained = dY_ext || dX;
+  if (chained && O % 8 != 0) return FAAR_E_SHAPE;
+  if (flags & ~(uint32_t)FAAR_WS_CHAINED) return FAAR_E_ARG;
+  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
+    return FAAR_E_ARG;
+  if (!(opt->lr >= 0.0f) || !std::isfinite(opt->lr) || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) ||
+      !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) || !std::isfinite(opt->eps) || opt->t < 1)
+    return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(adam_m) || !aligned16(adam_v) || !aligned16(Xq) ||
+      !aligned16(Xt) || !aligned16(C) || !aligned16(dY_ext) || !aligned16(dX) || !aligned16(ws))
+    return FAAR_E_ARG;
+  const StepLayout L = step_layout(O, K, T, chained);
+  if (!ws || ws_bytes < L.total) return FAAR_E_WORKSPACE;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = wdt == FAAR_BF16;
+  const int64_t n = O * K;
+  char* base = static_cast<char*>(ws);
+  bf16_t* delta = reinterpret_cast<bf16_t*>(base + L.delta);
+  bf16_t* dYt = reinterpret_cast<bf16_t*>(base + L.dYt);
+  float* G = reinterpret_cast<float*>(base + L.G);
+  double* mse_p = reinterpret_cast<double*>(base + L.mse_partials);
+  double* round_p = reinterpret_cast<double*>(base + L.round_partials);
+  bf16_t* wq_full = chained && dX ? reinterpret_cast<bf16_t*>(base + L.wq_full) : nullptr;
+  bf16_t* wqt = chained ? reinterpret_cast<bf16_t*>(base + L.wqt) : nullptr;
+  bf16_t* dY = chained ? reinterpret_cast<bf16_t*>(base + L.dY) : nullptr;
+  const bf16_t* xq = static_cast<const bf16_t*>(Xq);
+
+  // s1: W_q - W (bf16), and W_q itself when dX is wanted
+  if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, true, delta, wq_full, st))) return e;
+  // s2: residual GEMM + loss + dY
+  int64_t n_mse = 0;
+  const GemmDims d1{T, O, K, K, K};
+  const bool need_local_dY = dX && !dY_ext;
+  if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, 2.0f * mse_scale, dYt, L.Tp,
+                                              need_local_dY ? dY : nullptr, mse_p, &n_mse, st)))
+    return e;
+  const bf16_t* dY_used = dY;
+  if (dY_ext) {  // upstream gradient replaces the local one: overwrite dY^T
+    dY_used = static_cast<const bf16_t*>(dY_ext);
+    if (int e = hip_status(launch_transpose_bf16(dY_used, T, O, dYt, L.Tp, st))) return e;
+  }
+  // s3: G = dY^T X_q, contraction over tokens, split for occupancy
+  const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
+  if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;
+  // s4: dX = dY W_q
+  if (dX) {
+    if (int e = hip_status(launch_transpose_bf16(wq_full, O, K, wqt, L.Op, st))) return e;
+    const GemmDims d3{T, K, O, O, L.Op};
+    if (int e = hip_status(launch_gemm_bf16(dY_used, wqt, d3, static_cast<bf16_t*>(dX), st))) return e;
+  }
+  // s5 + s6: dV, Round Loss, Adam, clip
+  AdamScalars a;
+  a.lr = opt->lr; a.beta1 = opt->beta1; a.beta2 = opt->beta2; a.eps = opt->eps;
+  a.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));
+  a.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
+  if (int e = hip_status(launch_bwd_adam(W, bf, n, s_global, scales, V, adam_m, adam_v, beta, G, L.n_split,
+                                         (int64_t)O * K, lambda_round, a, round_p, st)))
+    return e;
+  return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, softquant_bwd_blocks(n), 1.0 / (double)n,
+                                           lambda_round, losses, losses + 1, losses + 2, st));
+}
+
+int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                     const uint8_t* scales, const float* V, uint8_t* codes, uint8_t* decisions,
+                     void* W_final, unsigned long long* flip_count, void* stream) {
+  if (!W || !s_global || !scales || !V || !codes) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(codes) || !aligned16(W_final) ||
+      (reinterpret_cast<uintptr_t>(flip_count) & 7u))
+    return FAAR_E_ARG;
+  return hip_status(launch_harden_pack(W, wdt == FAAR_BF16, O * K, s_global, scales, V, codes, decisions, W_final,
+                                       flip_count, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,123 @@
+// Device-side building blocks shared by the FAAR kernels: bf16 <-> float, FP8-E4M3 scale
+// codec, E2M1 interval lookup (paper Sec. 3.1; Table 2 steps 2-4; Eq. 4).
+// All "decision" arithmetic here is plain IEEE float32, one operation at a time; the library is
+// compiled with -ffp-contract=off and without fast-math so that results are bit-reproducible.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace faar {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// float -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+// Eight consecutive weights as float, from bf16 or float storage (16-byte aligned).
+template <typename WT> struct W8;
+template <> struct W8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&w)[8]) {
+    const uint4 q = *reinterpret_cast<const uint4*>(p);
+    const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[2 * i] = __uint_as_float(r[i] << 16);
+      w[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  }
+  // float32 values -> rounded to bf16 -> stored
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&w)[8]) {
+    uint32_t r[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i] = f32_to_bf16(w[2 * i]) | (f32_to_bf16(w[2 * i + 1]) << 16);
+    *reinterpret_cast<uint4*>(p) = make_uint4(r[0], r[1], r[2], r[3]);
+  }
+};
+template <> struct W8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&w)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
+    w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&w)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(w[4], w[5], w[6], w[7]);
+  }
+};
+
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) { W8<float>::load(p, v); }
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) { W8<float>::store(p, v); }
+
+// FP8 E4M3 (1-4-3, bias 7, no inf) value of a non-negative byte 0x00..0x7E.
+__device__ __forceinline__ float e4m3_value(uint32_t b) {
+  const uint32_t e = b >> 3, m = b & 7u;
+  return e == 0 ? static_cast<float>(m) * 0x1p-9f : __uint_as_float(((e + 120u) << 23) | (m << 20));
+}
+
+// Non-negative finite float -> nearest E4M3 byte, ties to even, saturating at 448 (0x7E).
+__device__ __forceinline__ uint32_t e4m3_encode_sat(float t) {
+  if (!(t < 448.0f)) return 0x7Eu;
+  if (t < 0x1p-6f) return static_cast<uint32_t>(rintf(t * 512.0f));  // subnormal grid: m * 2^-9
+  uint32_t u = __float_as_uint(t);
+  u += 0x7FFFFu + ((u >> 20) & 1u);  // round mantissa to 3 bits, nearest even (carry may bump the exponent)
+  return (u >> 20) - (120u << 3);
+}
+
+// Block scale byte from the block's largest magnitude: E4M3((a_b / 6) / s_global).
+__device__ __forceinline__ uint32_t block_scale_byte(float a_b, float s_global) {
+  return e4m3_encode_sat((a_b / 6.0f) / s_global);
+}
+
+// s = E4M3_value(byte) * s_global, one float32 product.
+__device__ __forceinline__ float effective_scale(uint32_t byte, float s_global) {
+  return e4m3_value(byte) * s_global;
+}
+
+// What Eq. 2 needs for one weight.
+struct Interval {
+  int k_lo;      // 0..6
+  float lo;      // N[k_lo]
+  float width;   // N[k_lo+1] - N[k_lo]
+  float v_init;  // Eq. 4, clamped to [0, 1]
+};
+
+// Table 2 steps 2-4 for one weight: w~ = |w| / s (0 when s == 0), interval, relative position.
+__device__ __forceinline__ Interval find_interval(float w, float s) {
+  const float wt = (s == 0.0f) ? 0.0f : fabsf(w) / s;
+  Interval r;
+  r.k_lo = (wt >= 0.5f) + (wt >= 1.0f) + (wt >= 1.5f) + (wt >= 2.0f) + (wt >= 3.0f) + (wt >= 4.0f);
+  r.lo = r.k_lo <= 4 ? 0.5f * static_cast<float>(r.k_lo) : (r.k_lo == 5 ? 3.0f : 4.0f);
+  r.width = r.k_lo <= 3 ? 0.5f : (r.k_lo == 6 ? 2.0f : 1.0f);
+  const float v = (wt - r.lo) / r.width;
+  r.v_init = fminf(fmaxf(v, 0.0f), 1.0f);
+  return r;
+}
+
+// Magnitude value of E2M1 code 0..7.
+__device__ __forceinline__ float e2m1_magnitude(uint32_t c) {
+  return c <= 4u ? 0.5f * static_cast<float>(c) : (c == 5u ? 3.0f : (c == 6u ? 4.0f : 6.0f));
+}
+
+// nibble = signbit(w) << 3 | (w == 0 ? 0 : k_lo + up)
+__device__ __forceinline__ uint32_t nibble(float w, int k_lo, int up) {
+  const uint32_t mag = (w == 0.0f) ? 0u : static_cast<uint32_t>(k_lo + up);
+  return ((__float_as_uint(w) >> 31) << 3) | mag;
+}
+
+// Dequantised value of a nibble: sign * ((N[code] * E4M3_value(byte)) * s_global).
+__device__ __forceinline__ float dequant(uint32_t nib, float sg_value, float s_global) {
+  const float mag = (e2m1_magnitude(nib & 7u) * sg_value) * s_global;
+  return (nib & 8u) ? -mag : mag;
+}
+
+// sign(w) in {-1, 0, +1}
+__device__ __forceinline__ float sign_of(float w) { return w > 0.0f ? 1.0f : (w < 0.0f ? -1.0f : 0.0f); }
+
+}  // namespace faar

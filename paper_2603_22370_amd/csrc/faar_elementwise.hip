@@ -1,0 +1,477 @@
+// HBM-bound elementwise / codec kernels of the FAAR layer step (paper Sec. 3.1, 3.4; Table 2;
+// Eq. 2-5, 7).  Every kernel uses the same mapping: one thread owns 8 consecutive weights (16 B
+// of bf16, 32 B of float32), so a 16-weight scale block is an even/odd lane pair and its amax is
+// one cross-lane exchange.  Loads and stores are 16 B per lane and fully coalesced.
+#include "faar_internal.h"
+
+namespace faar {
+namespace {
+
+__device__ __forceinline__ float pair_max(float a) {
+  return fmaxf(a, __shfl_xor(a, 1));
+}
+
+__device__ __forceinline__ float wave_max(float a) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a = fmaxf(a, __shfl_xor(a, o));
+  return a;
+}
+
+__device__ __forceinline__ double wave_sum(double a) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+  return a;
+}
+
+// Fixed-order block sum of one double per thread (kEltThreads threads); result valid in thread 0.
+__device__ __forceinline__ double block_sum(double a) {
+  __shared__ double s[kEltThreads / 64];
+  a = wave_sum(a);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  double r = 0.0;
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 0; i < kEltThreads / 64; ++i) r += s[i];
+  }
+  return r;
+}
+
+// ---- tensor amax -> s_global (Sec. 3.1: FP32 scale of scales) -------------------------------
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads) k_amax_partial(const WT* __restrict__ W, int64_t n8,
+                                                              float* __restrict__ partials) {
+  float a = 0.0f;
+  for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8;
+       i += (int64_t)gridDim.x * kEltThreads) {
+    float w[8];
+    W8<WT>::load(W + i * 8, w);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(w[j]));
+  }
+  __shared__ float s[kEltThreads / 64];
+  a = wave_max(a);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 1; i < kEltThreads / 64; ++i) a = fmaxf(a, s[i]);
+    partials[blockIdx.x] = a;
+  }
+}
+
+__global__ void __launch_bounds__(kEltThreads) k_amax_final(const float* __restrict__ partials, int n,
+                                                            float* __restrict__ s_global) {
+  float a = 0.0f;
+  for (int i = threadIdx.x; i < n; i += kEltThreads) a = fmaxf(a, partials[i]);
+  __shared__ float s[kEltThreads / 64];
+  a = wave_max(a);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 1; i < kEltThreads / 64; ++i) a = fmaxf(a, s[i]);
+    *s_global = (a == 0.0f) ? 1.0f : a / 2688.0f;  // 2688 = 6 (largest node) * 448 (largest E4M3)
+  }
+}
+
+// ---- round-to-nearest quantisation -----------------------------------------------------------
+template <typename WT, bool kDequant>
+__global__ void __launch_bounds__(kEltThreads)
+k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+            uint8_t* __restrict__ scales, uint32_t* __restrict__ codes, WT* __restrict__ W_dq) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;  // n8 is even: both lanes of a pair leave together
+  const float sg = *s_global_p;
+  float w[8];
+  W8<WT>::load(W + i * 8, w);
+  float a = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(w[j]));
+  a = pair_max(a);
+  const uint32_t byte = block_scale_byte(a, sg);
+  const float sgv = e4m3_value(byte);
+  const float s = sgv * sg;
+  uint32_t packed = 0;
+  float dq[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const Interval iv = find_interval(w[j], s);
+    const uint32_t nib = nibble(w[j], iv.k_lo, iv.v_init >= 0.5f);
+    packed |= nib << (4 * j);
+    if (kDequant) dq[j] = dequant(nib, sgv, sg);
+  }
+  codes[i] = packed;
+  if ((i & 1) == 0) scales[i >> 1] = static_cast<uint8_t>(byte);
+  if (kDequant) W8<WT>::store(W_dq + i * 8, dq);
+}
+
+// ---- V initialisation (Eq. 4) ---------------------------------------------------------------
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_init_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+         const uint8_t* __restrict__ scales, float* __restrict__ V, uint32_t* __restrict__ floor_codes) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float s = effective_scale(scales[i >> 1], *s_global_p);
+  float w[8], v[8];
+  W8<WT>::load(W + i * 8, w);
+  uint32_t packed = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const Interval iv = find_interval(w[j], s);
+    v[j] = iv.v_init;
+    packed |= (((__float_as_uint(w[j]) >> 31) << 3) | static_cast<uint32_t>(iv.k_lo)) << (4 * j);
+  }
+  store8(V + i * 8, v);
+  if (floor_codes) floor_codes[i] = packed;
+}
+
+// ---- hardening + NVFP4 packing (Eq. 7; Table 2 steps 25-26) --------------------------------
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_harden_pack(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+              const uint8_t* __restrict__ scales, const float* __restrict__ V,
+              uint32_t* __restrict__ codes, uint8_t* __restrict__ decisions, WT* __restrict__ W_final,
+              unsigned long long* __restrict__ flip_count) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  unsigned flips = 0;
+  if (i < n8) {
+    const float sg = *s_global_p;
+    const float sgv = e4m3_value(scales[i >> 1]);
+    const float s = sgv * sg;
+    float w[8], v[8], dq[8];
+    W8<WT>::load(W + i * 8, w);
+    load8(V + i * 8, v);
+    uint32_t packed = 0, bits = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const Interval iv = find_interval(w[j], s);
+      const int up = v[j] >= 0.5f;
+      const uint32_t nib = nibble(w[j], iv.k_lo, up);
+      const uint32_t rtn = nibble(w[j], iv.k_lo, iv.v_init >= 0.5f);
+      flips += (nib != rtn);
+      packed |= nib << (4 * j);
+      bits |= static_cast<uint32_t>(up) << j;
+      dq[j] = dequant(nib, sgv, sg);
+    }
+    codes[i] = packed;
+    if (decisions) decisions[i] = static_cast<uint8_t>(bits);
+    if (W_final) W8<WT>::store(W_final + i * 8, dq);
+  }
+  if (flip_count) {  // uniform branch: every lane of the block reaches the reduction
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) flips += __shfl_xor(flips, o);
+    if ((threadIdx.x & 63) == 0 && flips) atomicAdd(flip_count, (unsigned long long)flips);
+  }
+}
+
+// ---- soft quantisation forward (Eq. 2-3) ----------------------------------------------------
+__device__ __forceinline__ float h_beta(float v, float beta) {
+  return 1.0f / (1.0f + __expf(-beta * (v - 0.5f)));
+}
+
+template <typename WT, bool kDelta, bool kFull>
+__global__ void __launch_bounds__(kEltThreads)
+k_softquant_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+                const uint8_t* __restrict__ scales, const float* __restrict__ V, float beta,
+                bf16_t* __restrict__ Wt, bf16_t* __restrict__ Wq_full) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float s = effective_scale(scales[i >> 1], *s_global_p);
+  float w[8], v[8], out[8], full[8];
+  W8<WT>::load(W + i * 8, w);
+  load8(V + i * 8, v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const Interval iv = find_interval(w[j], s);
+    const float wq = sign_of(w[j]) * ((iv.lo + h_beta(v[j], beta) * iv.width) * s);
+    out[j] = kDelta ? wq - w[j] : wq;
+    if (kFull) full[j] = wq;
+  }
+  W8<bf16_t>::store(Wt + i * 8, out);
+  if (kFull) W8<bf16_t>::store(Wq_full + i * 8, full);
+}
+
+// dL/dv of Eq. 5 for one weight given g = dL/dW_q, plus its Round-Loss term.
+__device__ __forceinline__ float grad_v(float g, float w, float s, float v, float beta, float lam_over_n,
+                                        float& round_term) {
+  const Interval iv = find_interval(w, s);
+  const float h = h_beta(v, beta);
+  const float t = 2.0f * v - 1.0f;
+  round_term = 1.0f - t * t;
+  return g * (sign_of(w) * s * iv.width * beta * (h * (1.0f - h))) + lam_over_n * (4.0f - 8.0f * v);
+}
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_softquant_bwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+                const uint8_t* __restrict__ scales, const float* __restrict__ V, float beta,
+                const float* __restrict__ G, int n_split, int64_t split_stride, float lam_over_n,
+                float* __restrict__ dV, double* __restrict__ round_partials) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  float rsum = 0.0f;
+  if (i < n8) {
+    const float s = effective_scale(scales[i >> 1], *s_global_p);
+    float w[8], v[8], g[8], d[8];
+    W8<WT>::load(W + i * 8, w);
+    load8(V + i * 8, v);
+    load8(G + i * 8, g);
+    for (int sp = 1; sp < n_split; ++sp) {
+      float g2[8];
+      load8(G + sp * split_stride + i * 8, g2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) g[j] += g2[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float rt;
+      d[j] = grad_v(g[j], w[j], s, v[j], beta, lam_over_n, rt);
+      rsum += rt;
+    }
+    store8(dV + i * 8, d);
+  }
+  const double bs = block_sum(static_cast<double>(rsum));
+  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
+}
+
+// ---- backward + Adam + clip in one pass (Table 2 steps 11-13) ------------------------------
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_bwd_adam(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+           const uint8_t* __restrict__ scales, float* __restrict__ V, float* __restrict__ M,
+           float* __restrict__ U, float beta, const float* __restrict__ G, int n_split,
+           int64_t split_stride, float lam_over_n, AdamScalars o, double* __restrict__ round_partials) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  float rsum = 0.0f;
+  if (i < n8) {
+    const float s = effective_scale(scales[i >> 1], *s_global_p);
+    float w[8], v[8], g[8], m[8], u[8];
+    W8<WT>::load(W + i * 8, w);
+    load8(V + i * 8, v);
+    load8(M + i * 8, m);
+    load8(U + i * 8, u);
+    load8(G + i * 8, g);
+    for (int sp = 1; sp < n_split; ++sp) {
+      float g2[8];
+      load8(G + sp * split_stride + i * 8, g2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) g[j] += g2[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float rt;
+      const float d = grad_v(g[j], w[j], s, v[j], beta, lam_over_n, rt);
+      rsum += rt;
+      m[j] = o.beta1 * m[j] + (1.0f - o.beta1) * d;
+      u[j] = o.beta2 * u[j] + (1.0f - o.beta2) * (d * d);
+      const float step = o.lr * (m[j] * o.inv_bc1) / (sqrtf(u[j] * o.inv_bc2) + o.eps);
+      v[j] = fminf(fmaxf(v[j] - step, 0.0f), 1.0f);  // V clipped to [0, 1] after every update
+    }
+    store8(V + i * 8, v);
+    store8(M + i * 8, m);
+    store8(U + i * 8, u);
+  }
+  const double bs = block_sum(static_cast<double>(rsum));
+  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
+}
+
+// ---- loss finalisation: fixed-order sums of the per-block partials --------------------------
+__global__ void __launch_bounds__(kEltThreads)
+k_finalize_losses(const double* __restrict__ mse_partials, int64_t n_mse, float mse_scale,
+                  const double* __restrict__ round_partials, int64_t n_round, double inv_n,
+                  float lambda_round, float* loss_mse, float* loss_round, float* loss_total) {
+  double a = 0.0, b = 0.0;
+  for (int64_t i = threadIdx.x; i < n_mse; i += kEltThreads) a += mse_partials[i];
+  for (int64_t i = threadIdx.x; i < n_round; i += kEltThreads) b += round_partials[i];
+  __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64];
+  a = wave_sum(a);
+  b = wave_sum(b);
+  if ((threadIdx.x & 63) == 0) {
+    sa[threadIdx.x >> 6] = a;
+    sb[threadIdx.x >> 6] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = 0.0;
+    b = 0.0;
+    for (int i = 0; i < kEltThreads / 64; ++i) {
+      a += sa[i];
+      b += sb[i];
+    }
+    const double mse = a * static_cast<double>(mse_scale);
+    const double rl = b * inv_n;
+    if (loss_mse) *loss_mse = static_cast<float>(mse);
+    if (loss_round) *loss_round = static_cast<float>(rl);
+    if (loss_total) *loss_total = static_cast<float>(mse + static_cast<double>(lambda_round) * rl);
+  }
+}
+
+// ---- bf16 transpose with zero padding (X_q^T for the dW GEMM) -------------------------------
+__global__ void __launch_bounds__(256)
+k_transpose_bf16(const bf16_t* __restrict__ in, int64_t rows, int64_t cols, bf16_t* __restrict__ out,
+                 int64_t ld_out) {
+  __shared__ bf16_t tile[64][66];
+  const int64_t r0 = blockIdx.y * 64LL, c0 = blockIdx.x * 64LL;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int r = ty; r < 64; r += 4) {
+    const int64_t rr = r0 + r, cc = c0 + tx;
+    tile[r][tx] = (rr < rows && cc < cols) ? in[rr * cols + cc] : bf16_t(0);
+  }
+  __syncthreads();
+  for (int c = ty; c < 64; c += 4) {
+    const int64_t cc = c0 + c, rr = r0 + tx;
+    if (cc < cols && rr < ld_out) out[cc * ld_out + rr] = tile[tx][c];
+  }
+}
+
+// float32 -> hi + mid + lo bf16 terms (24 significand bits covered by 3 x 8).
+__global__ void __launch_bounds__(kEltThreads)
+k_split_f32(const float* __restrict__ in, int64_t n, bf16_t* __restrict__ hi, bf16_t* __restrict__ mid,
+            bf16_t* __restrict__ lo) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n) return;
+  const float x = in[i];
+  const uint32_t h = f32_to_bf16(x);
+  const float r1 = x - bf16_to_f32(h);
+  const uint32_t m = f32_to_bf16(r1);
+  const float r2 = r1 - bf16_to_f32(m);
+  hi[i] = static_cast<bf16_t>(h);
+  mid[i] = static_cast<bf16_t>(m);
+  lo[i] = static_cast<bf16_t>(f32_to_bf16(r2));
+}
+
+inline unsigned blocks_for(int64_t n8) { return static_cast<unsigned>((n8 + kEltThreads - 1) / kEltThreads); }
+
+}  // namespace
+
+hipError_t launch_amax(const void* W, bool w_bf16, int64_t n, float* partials, float* s_global,
+                       hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const int grid = static_cast<int>(std::min<int64_t>(kAmaxPartials, (n8 + kEltThreads - 1) / kEltThreads));
+  if (w_bf16)
+    hipLaunchKernelGGL(k_amax_partial<bf16_t>, dim3(grid), dim3(kEltThreads), 0, st,
+                       static_cast<const bf16_t*>(W), n8, partials);
+  else
+    hipLaunchKernelGGL(k_amax_partial<float>, dim3(grid), dim3(kEltThreads), 0, st,
+                       static_cast<const float*>(W), n8, partials);
+  hipLaunchKernelGGL(k_amax_final, dim3(1), dim3(kEltThreads), 0, st, partials, grid, s_global);
+  return hipGetLastError();
+}
+
+hipError_t launch_quant_rtn(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                            uint8_t* scales, uint8_t* codes, void* W_dq, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  uint32_t* c32 = reinterpret_cast<uint32_t*>(codes);
+#define FAAR_Q(WT, DQ) \
+  hipLaunchKernelGGL((k_quant_rtn<WT, DQ>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, static_cast<WT*>(W_dq))
+  if (w_bf16) { if (W_dq) FAAR_Q(bf16_t, true); else FAAR_Q(bf16_t, false); }
+  else        { if (W_dq) FAAR_Q(float, true);  else FAAR_Q(float, false); }
+#undef FAAR_Q
+  return hipGetLastError();
+}
+
+hipError_t launch_init_v(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                         const uint8_t* scales, float* V, uint8_t* floor_codes, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  uint32_t* c32 = reinterpret_cast<uint32_t*>(floor_codes);
+  if (w_bf16)
+    hipLaunchKernelGGL(k_init_v<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, c32);
+  else
+    hipLaunchKernelGGL(k_init_v<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, c32);
+  return hipGetLastError();
+}
+
+hipError_t launch_harden_pack(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                              const uint8_t* scales, const float* V, uint8_t* codes,
+                              uint8_t* decisions, void* W_final, unsigned long long* flip_count,
+                              hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  uint32_t* c32 = reinterpret_cast<uint32_t*>(codes);
+  if (w_bf16)
+    hipLaunchKernelGGL(k_harden_pack<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V,
+                       c32, decisions, static_cast<bf16_t*>(W_final), flip_count);
+  else
+    hipLaunchKernelGGL(k_harden_pack<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V,
+                       c32, decisions, static_cast<float*>(W_final), flip_count);
+  return hipGetLastError();
+}
+
+hipError_t launch_softquant_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                const uint8_t* scales, const float* V, float beta, bool delta,
+                                bf16_t* Wt, bf16_t* Wq_full, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+#define FAAR_F(WT, D, F) \
+  hipLaunchKernelGGL((k_softquant_fwd<WT, D, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, V, beta, Wt, Wq_full)
+#define FAAR_F2(WT) \
+  do { if (delta) { if (Wq_full) FAAR_F(WT, true, true); else FAAR_F(WT, true, false); } \
+       else       { if (Wq_full) FAAR_F(WT, false, true); else FAAR_F(WT, false, false); } } while (0)
+  if (w_bf16) FAAR_F2(bf16_t); else FAAR_F2(float);
+#undef FAAR_F2
+#undef FAAR_F
+  return hipGetLastError();
+}
+
+int64_t softquant_bwd_blocks(int64_t n) { return (n / 8 + kEltThreads - 1) / kEltThreads; }
+
+hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                const uint8_t* scales, const float* V, float beta, const float* G,
+                                int n_split, int64_t split_stride, float lambda_round, float* dV,
+                                double* round_partials, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
+  if (w_bf16)
+    hipLaunchKernelGGL(k_softquant_bwd<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V,
+                       beta, G, n_split, split_stride, lam_over_n, dV, round_partials);
+  else
+    hipLaunchKernelGGL(k_softquant_bwd<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V,
+                       beta, G, n_split, split_stride, lam_over_n, dV, round_partials);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                           const uint8_t* scales, float* V, float* m, float* u, float beta,
+                           const float* G, int n_split, int64_t split_stride, float lambda_round,
+                           AdamScalars opt, double* round_partials, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
+  if (w_bf16)
+    hipLaunchKernelGGL(k_bwd_adam<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, m, u,
+                       beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
+  else
+    hipLaunchKernelGGL(k_bwd_adam<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, m, u,
+                       beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
+  return hipGetLastError();
+}
+
+hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, float mse_scale,
+                                  const double* round_partials, int64_t n_round, double inv_n,
+                                  float lambda_round, float* loss_mse, float* loss_round,
+                                  float* loss_total, hipStream_t st) {
+  hipLaunchKernelGGL(k_finalize_losses, dim3(1), dim3(kEltThreads), 0, st, mse_partials, n_mse, mse_scale,
+                     round_partials, n_round, inv_n, lambda_round, loss_mse, loss_round, loss_total);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
+                                 int64_t ld_out, hipStream_t st) {
+  // the grid covers rows up to ld_out so that the zero padding is written too
+  const dim3 g(static_cast<unsigned>((cols + 63) / 64), static_cast<unsigned>((ld_out + 63) / 64));
+  hipLaunchKernelGGL(k_transpose_bf16, g, dim3(256), 0, st, in, rows, cols, out, ld_out);
+  return hipGetLastError();
+}
+
+hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
+                            hipStream_t st) {
+  hipLaunchKernelGGL(k_split_f32, dim3(static_cast<unsigned>((n + kEltThreads - 1) / kEltThreads)),
+                     dim3(kEltThreads), 0, st, in, n, hi, mid, lo);
+  return hipGetLastError();
+}
+
+}  // namespace faar

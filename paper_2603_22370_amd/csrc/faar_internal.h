@@ -1,0 +1,82 @@
+// Host-side declarations shared by the translation units of libfaar: kernel launchers and
+// workspace layouts.  Launchers return hipError_t; argument validation lives in faar_api.hip.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "faar_device.h"
+
+namespace faar {
+
+constexpr int kAmaxPartials = 1024;     // partial maxima written by the first amax pass
+constexpr int kEltThreads = 256;        // threads per block of every elementwise kernel
+constexpr int kMaxLossPartials = 1 << 16;
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+inline int64_t padded_tokens(int64_t T) { return round_up(T, 64); }
+
+// ---- elementwise kernels (faar_elementwise.hip) -------------------------------------------
+hipError_t launch_amax(const void* W, bool w_bf16, int64_t n, float* partials, float* s_global,
+                       hipStream_t st);
+hipError_t launch_quant_rtn(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                            uint8_t* scales, uint8_t* codes, void* W_dq, hipStream_t st);
+hipError_t launch_init_v(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                         const uint8_t* scales, float* V, uint8_t* floor_codes, hipStream_t st);
+hipError_t launch_harden_pack(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                              const uint8_t* scales, const float* V, uint8_t* codes,
+                              uint8_t* decisions, void* W_final, unsigned long long* flip_count,
+                              hipStream_t st);
+// Wt = bf16(W_q) or bf16(W_q - W); Wq_full (nullable) additionally receives bf16(W_q).
+hipError_t launch_softquant_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                const uint8_t* scales, const float* V, float beta, bool delta,
+                                bf16_t* Wt, bf16_t* Wq_full, hipStream_t st);
+// dV = sum_s G[s] * dWq/dV + lambda/N (4 - 8 v); per-block Round-Loss partial sums (double).
+hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                const uint8_t* scales, const float* V, float beta, const float* G,
+                                int n_split, int64_t split_stride, float lambda_round, float* dV,
+                                double* round_partials, hipStream_t st);
+int64_t softquant_bwd_blocks(int64_t n);
+// Backward + Adam + clip in one pass; same partial layout as launch_softquant_bwd.
+struct AdamScalars { float lr, beta1, beta2, eps, inv_bc1, inv_bc2; };
+hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                           const uint8_t* scales, float* V, float* m, float* u, float beta,
+                           const float* G, int n_split, int64_t split_stride, float lambda_round,
+                           AdamScalars opt, double* round_partials, hipStream_t st);
+// losses[0] = mse_scale * sum(mse_partials), losses[1] = sum(round_partials) / n,
+// losses[2] = losses[0] + lambda * losses[1].  Either partial array may be empty (count 0).
+hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, float mse_scale,
+                                  const double* round_partials, int64_t n_round, double inv_n,
+                                  float lambda_round, float* loss_mse, float* loss_round,
+                                  float* loss_total, hipStream_t st);
+// out[c * ld_out + r] = in[r * cols + c] for r < rows, c < cols; columns rows..ld_out-1 zeroed.
+hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
+                                 int64_t ld_out, hipStream_t st);
+// float32 -> three bf16 terms hi + mid + lo (each the rounding of the running remainder).
+hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
+                            hipStream_t st);
+
+// ---- bf16 MFMA GEMMs (faar_gemm.hip) ------------------------------------------------------
+// All GEMMs are "NT": acc[m][n] = sum_k A[m][k] * B[n][k], A [M, lda], B [N, ldb] bf16 row-major
+// with the contraction index contiguous, lda/ldb/Kd multiples of 8.
+struct GemmDims { int64_t M, N, Kd, lda, ldb; };
+
+// Residual epilogue (Table 2 steps 9-10): R = acc - C[m][n]; partial sum of R^2 per tile (double);
+// dYt[n][m] = bf16(two_alpha * R) with row stride ldt (rows n < N, columns m < ldt, zero for m >= M);
+// dY (nullable) [M, N] the same values un-transposed.
+hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
+                                float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
+                                double* mse_partials, int64_t* n_partials, hipStream_t st);
+int64_t gemm_residual_tiles(int64_t M, int64_t N);
+// Plain float32 output with the contraction split n_split ways: out[s][m][n] (split stride M*N).
+hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
+                           hipStream_t st);
+int choose_split(int64_t M, int64_t N, int64_t Kd);
+// C_out[m][n] = (first ? Y[m][n] : C_out[m][n]) - acc   (Y bf16 or float32)
+hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
+                           bool first, float* C_out, hipStream_t st);
+// out[m][n] = bf16(acc)
+hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out,
+                            hipStream_t st);
+
+}  // namespace faar

@@ -1,0 +1,91 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every symbol the header
+declares, sizes workspaces consistently, and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_22370_amd import binding as fb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    src = open(os.path.join(ROOT, "include", "faar.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(faar_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_header_declares_the_five_hot_path_calls():
+    names = _declared()
+    for n in ["faar_quant_rtn", "faar_init_v", "faar_softquant_fwd_bwd", "faar_layer_step", "faar_harden_pack"]:
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    L = fb.lib()
+    for n in _declared():
+        assert hasattr(L, n), n
+    assert L.faar_version() >= 100
+
+
+def test_workspace_sizes():
+    assert fb.faar_workspace_bytes(fb.OP_QUANT_RTN, 256, 256) >= 4096
+    assert fb.faar_workspace_bytes(fb.OP_QUANT_RTN, 256, 250) == 0           # K % 16
+    assert fb.faar_workspace_bytes(fb.OP_LAYER_STEP, 256, 256, 0) == 0        # T missing
+    assert fb.faar_workspace_bytes(99, 256, 256, 64) == 0
+    a = fb.faar_workspace_bytes(fb.OP_LAYER_STEP, 2048, 2048, 4096)
+    b = fb.faar_workspace_bytes(fb.OP_LAYER_STEP, 2048, 2048, 4096, fb.FAAR_WS_CHAINED)
+    assert b > a >= 2048 * 2048 * (2 + 4) + 2048 * 4096 * 2
+    assert fb.faar_padded_tokens(64) == 64 and fb.faar_padded_tokens(65) == 128 and fb.faar_padded_tokens(1) == 64
+
+
+def test_error_codes_without_a_gpu():
+    """Every call below must fail validation (negative code) before any kernel launch."""
+    L = fb.lib()
+    p = ctypes.c_void_p(0x1000)          # a non-null, 16-byte aligned dummy; never dereferenced
+    odd = ctypes.c_void_p(0x1004)
+    nul = None
+    q = L.faar_quant_rtn
+    assert q(nul, 1, 16, 16, p, p, p, nul, 0, p, 4096, nul) == -1
+    assert q(p, 1, 16, 24, p, p, p, nul, 0, p, 4096, nul) == -2
+    assert q(p, 1, 0, 16, p, p, p, nul, 0, p, 4096, nul) == -2
+    assert q(p, 7, 16, 16, p, p, p, nul, 0, p, 4096, nul) == -3
+    assert q(p, 1, 16, 16, p, p, p, nul, 0, p, 16, nul) == -4
+    assert q(p, 1, 16, 16, p, p, p, nul, 0, nul, 0, nul) == -4
+    assert q(p, 1, 16, 16, p, p, p, nul, 64, p, 4096, nul) == -6
+    assert q(odd, 1, 16, 16, p, p, p, nul, 0, p, 4096, nul) == -6
+    assert L.faar_init_v(p, 1, 16, 16, p, p, nul, nul, nul) == -1
+    assert L.faar_init_v(p, 1, 16, 8, p, p, p, nul, nul) == -2
+    sq = L.faar_softquant_fwd_bwd
+    assert sq(p, 1, 16, 16, p, p, p, 0.0, p, nul, 0.0, nul, nul, 0, p, 4096, nul) == -6      # beta <= 0
+    assert sq(p, 1, 16, 16, p, p, p, float("inf"), p, nul, 0.0, nul, nul, 0, p, 4096, nul) == -6
+    assert sq(p, 1, 16, 16, p, p, p, 4.0, p, p, 0.0, nul, nul, 0, p, 4096, nul) == -1         # dWt without dV
+    assert sq(p, 1, 16, 16, p, p, p, 4.0, p, p, 0.0, p, nul, 0, p, 1, nul) == -4
+    assert L.faar_layer_prepare(p, 1, 16, 16, p, p, 1, 0, p, p, p, 1 << 20, nul) == -2         # T <= 0
+    assert L.faar_layer_prepare(p, 0, 16, 16, p, p, 1, 8, p, p, nul, 0, nul) == -4             # fp32 W needs ws
+    opt = fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 1)
+    st = L.faar_layer_step
+    big = 1 << 30
+    args = lambda **kw: [kw.get("W", p), 1, kw.get("O", 16), 16, p, p, p, p, p, p, p, p, kw.get("T", 8),
+                         kw.get("dYe", nul), kw.get("dX", nul), kw.get("beta", 4.0), 0.01, 1.0,
+                         ctypes.byref(kw.get("opt", opt)), p, 0, p, kw.get("ws", big), nul]
+    assert st(*args(W=nul)) == -1
+    assert st(*args(T=0)) == -2
+    assert st(*args(beta=-1.0)) == -6
+    assert st(*args(opt=fb.faar_adam(-1.0, 0.9, 0.999, 1e-8, 1))) == -6
+    assert st(*args(opt=fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 0))) == -6
+    assert st(*args(ws=16)) == -4
+    assert st(*args(O=12, dX=p)) == -2                                                     # chained needs O % 8 == 0
+    hp = L.faar_harden_pack
+    assert hp(p, 1, 16, 16, p, p, p, nul, nul, nul, nul, nul) == -1
+    assert hp(p, 2, 16, 16, p, p, p, p, nul, nul, nul, nul) == -3
+    assert L.faar_last_hip_error() == 0
+
+
+def test_missing_library_is_a_loud_error(monkeypatch):
+    monkeypatch.setattr(fb, "_lib", None)
+    monkeypatch.setattr(fb, "LIB_PATH", "/nonexistent/libfaar.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        fb.lib()
