@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the FAAR per-layer rounding-optimisation path on one MI355X.
+
+Workload (N=1): the Llama3-1B-shaped attention projection of the second configuration --
+q_proj, W 2048x2048 bf16 Student-t(4) scaled to std 0.02, calibration X 4096 tokens x 2048 bf16
+with 1% outlier channels x30 -- synthetic, seeded, resident in HBM before the timed region.
+
+Timed region: one whole per-layer job = faar_quant_rtn + faar_init_v + faar_layer_prepare, then
+EXACTLY K faar_layer_step calls (soft-quant, residual GEMM + loss, dW GEMM, dV + Round Loss + Adam +
+clip; beta annealed 4 -> 32), then faar_harden_pack.  value = K / elapsed (steps/s).
+
+Also printed in the same JSON line:
+  roofline      -- the dominant kernel's achieved rate from HIP-event brackets around each of its
+                   launches (library hook faar_time_kernel), against the MI355X published peak
+  kernels       -- the same measurement for every kernel of the path
+  cpu_baseline  -- the CPU oracle timed on this host on a bounded number of steps of the same layer
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+
+# Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale)
+BYTES_PER_WEIGHT = {
+    "softquant_fwd": 2 + 4 + 1 / 16 + 2,          # read W, V, scale; write W_q - W (bf16)
+    "bwd_adam": 4 + 2 + 1 / 16 + 12 + 12,         # read G (one split), W, scale, V, m, u; write V, m, u
+    "quant_rtn": 2 + 0.5 + 1 / 16,                # read W; write codes, scales
+    "init_v": 2 + 1 / 16 + 4,                     # read W, scales; write V
+    "harden_pack": 2 + 4 + 1 / 16 + 0.5,          # read W, V, scales; write codes
+}
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs via the HIP runtime already loaded by torch (plumbing only)."""
+
+    def __init__(self):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        ev = ctypes.c_void_p()
+        rc = self.hip.hipEventCreate(ctypes.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed: {rc}")
+        return ev
+
+    def elapsed_ms(self, a, b) -> float:
+        self.hip.hipEventSynchronize(b)
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--probe-steps", type=int, default=20)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the path has no collectives or sharding "
+              "(see DESIGN.md, 'More than one GPU'). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+    from workloads import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    O, K, T = 2048, 2048, 4096
+    case = synth.llm_linear("q_proj", O, K, T, seed=0)
+    W = torch.from_numpy(case.W).cuda().to(torch.bfloat16)
+    Xq = torch.from_numpy(case.Xq).cuda().to(torch.bfloat16)
+    Y = torch.from_numpy(case.Y_fp).cuda().to(torch.bfloat16)
+    N = O * K
+    alpha, lam, lr = 1.0 / (T * O), 0.01, 5e-4
+    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ws = faar.layer_step_workspace(O, K, T)
+    ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, O, K), dtype=torch.uint8, device="cuda")
+    ws_p = torch.empty(max(256, faar.faar_workspace_bytes(fb.OP_LAYER_PREPARE, O, K, T)), dtype=torch.uint8, device="cuda")
+
+    def beta_at(t, total):
+        return 4.0 + 28.0 * (t - 1) / max(1, total - 1)
+
+    def layer_job(n_steps):
+        sg, scales, codes, _ = faar.faar_quant_rtn(W, ws=ws_q)
+        V, _ = faar.faar_init_v(W, sg, scales)
+        Xt, C = faar.faar_layer_prepare(W, Xq, Y, ws=ws_p)
+        m = torch.zeros_like(V)
+        u = torch.zeros_like(V)
+        for t in range(1, n_steps + 1):
+            faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
+                                 1e-8, t, losses, ws)
+        out, _, _, flips = faar.faar_harden_pack(W, sg, scales, V, want_flips=True)
+        return sg, scales, V, m, u, Xt, C, out, flips
+
+    # warm-up (untimed)
+    layer_job(max(1, args.warmup))
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps inside one whole per-layer job
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    sg, scales, V, m, u, Xt, C, packed, flips = layer_job(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    final_losses = losses.cpu().numpy().tolist()
+    n_flips = int(flips.item())
+
+    # per-kernel durations: HIP events recorded by the library around each launch of one kernel
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    probe = {}
+
+    def timed_kernel(which, call, n):
+        ts = []
+        fb.faar_time_kernel(which, e0.value, e1.value)
+        try:
+            for i in range(n):
+                call(i)
+                ts.append(ev.elapsed_ms(e0, e1))
+        finally:
+            fb.faar_time_kernel(fb.K_NONE)
+        ts = ts[2:] if len(ts) > 4 else ts
+        return sum(ts) / len(ts)
+
+    def step_call(i):
+        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
+                             args.steps + 1 + i, losses, ws)
+
+    n_probe = max(5, args.probe_steps)
+    for name, kid in [("softquant_fwd", fb.K_SOFTQUANT_FWD), ("gemm_residual", fb.K_GEMM_RESIDUAL),
+                      ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
+        probe[name] = timed_kernel(kid, step_call, n_probe)
+    probe["quant_rtn"] = timed_kernel(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(W, ws=ws_q), n_probe)
+    probe["init_v"] = timed_kernel(fb.K_INIT_V, lambda i: faar.faar_init_v(W, sg, scales), n_probe)
+    probe["harden_pack"] = timed_kernel(fb.K_HARDEN_PACK, lambda i: faar.faar_harden_pack(W, sg, scales, V), n_probe)
+
+    gemm_flops = 2.0 * T * O * K
+    kernels = {}
+    for name, ms in probe.items():
+        if name.startswith("gemm"):
+            ach = gemm_flops / (ms * 1e-3) / 1e12
+            kernels[name] = {"ms": round(ms, 5), "bound": "mfma", "achieved": round(ach, 2), "unit": "TFLOP/s",
+                             "frac": round(ach / BF16_PEAK_TFLOPS, 4)}
+        else:
+            ach = BYTES_PER_WEIGHT[name] * N / (ms * 1e-3) / 1e9
+            kernels[name] = {"ms": round(ms, 5), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
+                             "frac": round(ach / HBM_PEAK_GBS, 4)}
+    dom = max(("gemm_residual", "gemm_dw", "softquant_fwd", "bwd_adam"), key=lambda k: probe[k])
+    roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
+                "peak": BF16_PEAK_TFLOPS if kernels[dom]["bound"] == "mfma" else HBM_PEAK_GBS,
+                "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": None,
+                "launch_ms": kernels[dom]["ms"]}
+
+    ms_per_step = elapsed / args.steps * 1e3
+    out = {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama3-1b-shaped q_proj: W 2048x2048 bf16 Student-t(4), X 4096x2048 bf16, "
+                               "NVFP4 block 16; per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
+                   "O": O, "K": K, "T": T},
+        "weight_elems_per_sec": round(N * args.steps / elapsed, 1),
+        "final_losses": final_losses, "flipped_decisions": n_flips,
+        "roofline": roofline, "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import faar_oracle as fo
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        q = fo.quant_rtn(case.W, True)
+        V0 = fo.init_v(case.W, q["s_global"], q["scales"])["V"]
+        m0 = np.zeros_like(V0)
+        u0 = np.zeros_like(V0)
+        n_cpu, t_cpu = 0, 0.0
+        while n_cpu < 1 or (t_cpu < args.cpu_seconds and n_cpu < 20):
+            c0 = time.perf_counter()
+            r = fo.layer_step(case.W, q["s_global"], q["scales"], V0, m0, u0, case.Xq, case.Y_fp,
+                              beta_at(n_cpu + 1, args.steps), lam, alpha, lr, 0.9, 0.999, 1e-8, n_cpu + 1)
+            V0, m0, u0 = r["V"], r["m"], r["u"]
+            t_cpu += time.perf_counter() - c0
+            n_cpu += 1
+        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "cores": int(cores),
+                               "kind": "oracle",
+                               "sample": f"{n_cpu} layer steps of the same q_proj layer (numpy float64, "
+                                         f"{t_cpu:.1f} s)"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

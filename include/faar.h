@@ -69,11 +69,30 @@ enum {
   FAAR_OP_HARDEN_PACK = 5
 };
 
+/* kernels of the path, for faar_time_kernel */
+enum {
+  FAAR_K_NONE = 0,
+  FAAR_K_SOFTQUANT_FWD = 1,  /* W_q - W                                 (faar_layer_step) */
+  FAAR_K_GEMM_RESIDUAL = 2,  /* X_q (W_q - W)^T - C, loss, dY           (faar_layer_step) */
+  FAAR_K_GEMM_DW = 3,        /* dY^T X_q                                (faar_layer_step) */
+  FAAR_K_GEMM_DX = 4,        /* dY W_q                                  (faar_layer_step) */
+  FAAR_K_BWD_ADAM = 5,       /* dV, Round Loss, Adam, clip              (faar_layer_step) */
+  FAAR_K_QUANT_RTN = 6,      /* the quantise kernel of faar_quant_rtn (not its amax pass) */
+  FAAR_K_INIT_V = 7,
+  FAAR_K_HARDEN_PACK = 8
+};
+
 /* Library version, MAJOR*10000 + MINOR*100 + PATCH.  Pure host function. */
 int faar_version(void);
 
 /* hipError_t of the last failed HIP call made by this host thread (0 if none). */
 int faar_last_hip_error(void);
+
+/* Measurement hook for benchmarks: while `which` != FAAR_K_NONE, every launch of that kernel made
+ * by this host thread is bracketed by hipEventRecord(start_event) / hipEventRecord(stop_event) on
+ * the launch stream (hipEvent_t handles created by the caller with timing enabled).  Pass
+ * FAAR_K_NONE to switch it off.  Returns FAAR_E_ARG for an unknown kernel or missing events. */
+int faar_time_kernel(int which, void* start_event, void* stop_event);
 
 /* Workspace size in bytes that `op` needs for these sizes (T is ignored by ops that take no
  * activations; `flags` as passed to the op).  Pure host function; returns 0 for an unknown op or

@@ -45,6 +45,8 @@ def lib() -> ctypes.CDLL:
         L.faar_last_hip_error.restype = c_int
         L.faar_workspace_bytes.restype = c_size_t
         L.faar_workspace_bytes.argtypes = [c_int, c_int64, c_int64, c_int64, c_uint32]
+        L.faar_time_kernel.restype = c_int
+        L.faar_time_kernel.argtypes = [c_int, c_void_p, c_void_p]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -100,6 +102,14 @@ def _check(rc: int, where: str):
 
 def faar_workspace_bytes(op: int, O: int, K: int, T: int = 0, flags: int = 0) -> int:
     return int(lib().faar_workspace_bytes(op, O, K, T, flags))
+
+
+K_NONE, K_SOFTQUANT_FWD, K_GEMM_RESIDUAL, K_GEMM_DW, K_GEMM_DX, K_BWD_ADAM, K_QUANT_RTN, K_INIT_V, K_HARDEN_PACK = range(9)
+
+
+def faar_time_kernel(which: int, start_event=None, stop_event=None) -> None:
+    """start_event / stop_event: raw hipEvent_t handles (integers)."""
+    _check(lib().faar_time_kernel(which, c_void_p(start_event), c_void_p(stop_event)), "faar_time_kernel")
 
 
 def faar_padded_tokens(T: int) -> int:

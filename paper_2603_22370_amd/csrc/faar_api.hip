@@ -17,6 +17,16 @@ inline int hip_status(hipError_t e) {
   return FAAR_E_HIP;
 }
 
+// Optional event bracket around one kernel of the path (faar_time_kernel).
+struct Probe { int which; hipEvent_t start, stop; };
+thread_local Probe g_probe{FAAR_K_NONE, nullptr, nullptr};
+struct Bracket {
+  bool on;
+  hipStream_t st;
+  Bracket(int id, hipStream_t s) : on(g_probe.which == id), st(s) { if (on) (void)hipEventRecord(g_probe.start, st); }
+  ~Bracket() { if (on) (void)hipEventRecord(g_probe.stop, st); }
+};
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
 
@@ -77,6 +87,13 @@ int faar_version(void) { return 100; }
 
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
+int faar_time_kernel(int which, void* start_event, void* stop_event) {
+  if (which < FAAR_K_NONE || which > FAAR_K_HARDEN_PACK) return FAAR_E_ARG;
+  if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
+  g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+  return FAAR_OK;
+}
+
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
 size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags) {
@@ -115,6 +132,7 @@ int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K, float* s
   const bool bf = wdt == FAAR_BF16;
   if (!given)
     if (int e = hip_status(launch_amax(W, bf, O * K, static_cast<float*>(ws), s_global, st))) return e;
+  Bracket b(FAAR_K_QUANT_RTN, st);
   return hip_status(launch_quant_rtn(W, bf, O * K, s_global, scales, codes, W_dq, st));
 }
 
@@ -124,6 +142,7 @@ int faar_init_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_shape(O, K)) return e;
   if (!aligned16(W) || !aligned16(V) || !aligned16(floor_codes)) return FAAR_E_ARG;
+  Bracket b(FAAR_K_INIT_V, static_cast<hipStream_t>(stream));
   return hip_status(launch_init_v(W, wdt == FAAR_BF16, O * K, s_global, scales, V, floor_codes,
                                   static_cast<hipStream_t>(stream)));
 }
@@ -221,14 +240,20 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   const bf16_t* xq = static_cast<const bf16_t*>(Xq);
 
   // s1: W_q - W (bf16), and W_q itself when dX is wanted
-  if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, true, delta, wq_full, st))) return e;
+  {
+    Bracket b(FAAR_K_SOFTQUANT_FWD, st);
+    if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, true, delta, wq_full, st))) return e;
+  }
   // s2: residual GEMM + loss + dY
   int64_t n_mse = 0;
   const GemmDims d1{T, O, K, K, K};
   const bool need_local_dY = dX && !dY_ext;
-  if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, 2.0f * mse_scale, dYt, L.Tp,
-                                              need_local_dY ? dY : nullptr, mse_p, &n_mse, st)))
-    return e;
+  {
+    Bracket b(FAAR_K_GEMM_RESIDUAL, st);
+    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, 2.0f * mse_scale, dYt, L.Tp,
+                                                need_local_dY ? dY : nullptr, mse_p, &n_mse, st)))
+      return e;
+  }
   const bf16_t* dY_used = dY;
   if (dY_ext) {  // upstream gradient replaces the local one: overwrite dY^T
     dY_used = static_cast<const bf16_t*>(dY_ext);
@@ -236,11 +261,15 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   }
   // s3: G = dY^T X_q, contraction over tokens, split for occupancy
   const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
-  if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;
+  {
+    Bracket b(FAAR_K_GEMM_DW, st);
+    if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;
+  }
   // s4: dX = dY W_q
   if (dX) {
     if (int e = hip_status(launch_transpose_bf16(wq_full, O, K, wqt, L.Op, st))) return e;
     const GemmDims d3{T, K, O, O, L.Op};
+    Bracket b(FAAR_K_GEMM_DX, st);
     if (int e = hip_status(launch_gemm_bf16(dY_used, wqt, d3, static_cast<bf16_t*>(dX), st))) return e;
   }
   // s5 + s6: dV, Round Loss, Adam, clip
@@ -248,9 +277,12 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.lr = opt->lr; a.beta1 = opt->beta1; a.beta2 = opt->beta2; a.eps = opt->eps;
   a.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));
   a.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
-  if (int e = hip_status(launch_bwd_adam(W, bf, n, s_global, scales, V, adam_m, adam_v, beta, G, L.n_split,
-                                         (int64_t)O * K, lambda_round, a, round_p, st)))
-    return e;
+  {
+    Bracket b(FAAR_K_BWD_ADAM, st);
+    if (int e = hip_status(launch_bwd_adam(W, bf, n, s_global, scales, V, adam_m, adam_v, beta, G, L.n_split,
+                                           (int64_t)O * K, lambda_round, a, round_p, st)))
+      return e;
+  }
   return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, softquant_bwd_blocks(n), 1.0 / (double)n,
                                            lambda_round, losses, losses + 1, losses + 2, st));
 }
@@ -264,6 +296,7 @@ int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K, const 
   if (!aligned16(W) || !aligned16(V) || !aligned16(codes) || !aligned16(W_final) ||
       (reinterpret_cast<uintptr_t>(flip_count) & 7u))
     return FAAR_E_ARG;
+  Bracket b(FAAR_K_HARDEN_PACK, static_cast<hipStream_t>(stream));
   return hip_status(launch_harden_pack(W, wdt == FAAR_BF16, O * K, s_global, scales, V, codes, decisions, W_final,
                                        flip_count, static_cast<hipStream_t>(stream)));
 }
