@@ -68,7 +68,7 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   L.delta = take((size_t)O * K * 2);
   L.dYt = take((size_t)O * L.Tp * 2);
   L.G = take((size_t)L.n_split * O * K * 4);
-  L.mse_partials = take((size_t)gemm_residual_tiles(T, O) * 8);
+  L.mse_partials = take((size_t)gemm_residual_partials(T, O, K) * 8);
   L.round_partials = take((size_t)softquant_bwd_blocks(O * K) * 8);
   if (chained) {
     L.wq_full = take((size_t)O * K * 2);

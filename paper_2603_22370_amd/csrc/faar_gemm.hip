@@ -7,10 +7,17 @@
 // (X_q^T, dY^T, W_q^T) are produced in that layout by the kernel that writes them, so one tuned
 // main loop serves all of them.
 //
-// Main loop: a BM x BN output tile per 256-thread workgroup (2 x 2 wavefronts), BK = 64 slices
-// staged global -> registers -> LDS with two LDS stages, v_mfma_f32_32x32x16_bf16 with float32
-// accumulators.  LDS rows are padded by 16 B so that the 16-byte fragment reads of 16 consecutive
-// rows fall in distinct banks.
+// Two main loops:
+//  * k_gemm_dma (the fast path, contraction length a multiple of 32): 256x256 or 256x128 output tile
+//    per 512-thread workgroup (8 wavefronts, 2 per SIMD), BK = 32 slices copied global -> LDS by
+//    global_load_lds_dwordx4 (no VGPR staging) into a 4-stage ring; LDS rows are 64 B, un-padded, with
+//    the 16-byte chunk index XOR-swizzled by (row / 4) % 4 so that the fragment reads of 16 consecutive
+//    rows hit 16 distinct bank groups (measured: zero LDS bank conflicts); fragments are prefetched one
+//    MFMA phase ahead, also across the slice boundary, and the ds_reads / DMA issues are interleaved
+//    one by one between the v_mfma_f32_32x32x16_bf16 instructions; workgroups are dealt to the 8 XCDs
+//    in contiguous chunks of a grouped tile order so that each XCD's L2 sees a compact sub-grid.
+//  * k_gemm_nt (generic fallback for ragged contraction lengths): 128x128 tile, register-staged,
+//    padded LDS, bounds-checked loads.
 #include "faar_internal.h"
 
 namespace faar {
@@ -167,14 +174,20 @@ struct EpiResidual {
     }
     *reinterpret_cast<uint2*>(dYt + n * ldt + m) = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
   }
-  __device__ __forceinline__ void finish(int block) {
-    __shared__ double s[GEMM_THREADS / 64];
+  // fixed-order sum over the workgroup's wavefronts (4 or 8)
+  __device__ __forceinline__ void finish(int item) {
+    __shared__ double s[8];
     double a = static_cast<double>(sum);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
     if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
     __syncthreads();
-    if (threadIdx.x == 0) partials[block] = (s[0] + s[1]) + (s[2] + s[3]);
+    if (threadIdx.x == 0) {
+      double t = 0.0;
+      const int nw = blockDim.x >> 6;
+      for (int i = 0; i < nw; ++i) t += s[i];
+      partials[item] = t;
+    }
   }
 };
 
@@ -225,60 +238,289 @@ struct EpiBf16 {
   __device__ __forceinline__ void finish(int) {}
 };
 
+// ---- fast path: direct-to-LDS ring, swizzled LDS, interleaved schedule ------------------------------
+
+constexpr int DBK = 32;   // contraction slice per stage
+constexpr int DNS = 4;    // ring stages
+
+template <int BM_, int BN_, int WGM_, int WGN_>
+struct DmaCfg {
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+  static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int TM = WM / 32, TN = WN / 32;
+  static constexpr int CPR = DBK / 8;            // 16-byte chunks per LDS row (4)
+  static constexpr int RPI = 64 / CPR;           // rows written by one wave-wide DMA instruction (16)
+  static constexpr int RB = 16 / CPR;            // rows per 256-byte bank cycle (4)
+  static constexpr int STAGE = (BM + BN) * DBK;  // elements per stage
+  static constexpr int P = (BM + BN) / RPI / NW; // DMA instructions per wavefront per stage
+  static constexpr int KK = DBK / 16;            // MFMA phases per stage
+  static constexpr int NF = TM + TN, NM = TM * TN;
+  static_assert(NF <= NM, "every phase must have room to prefetch the next phase's fragments");
+  static_assert((BM + BN) % (RPI * NW) == 0 && (KK * NM) / P >= 1, "DMA schedule");
+};
+
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr wave-uniform).
+// Written as inline assembly so that the compiler's wait-count bookkeeping for ordinary LDS reads stays
+// exact; completion is tracked by hand through vmcnt (wait_vmcnt) and the workgroup barrier.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
+}
+#define FAAR_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N)&0xF) | (((N) >> 4) << 14))
+
+// Work item -> (tile, split).  Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; XCD x
+// takes the x-th contiguous chunk of the item list, and the list walks the tile grid in column-major
+// groups of 8 tile rows, so the 32 workgroups resident on an XCD cover a compact 8 x 4 block of tiles.
+__device__ __forceinline__ bool item_coords(int pid, int tiles_m, int tiles_n, int n_split, int& tm, int& tn, int& split,
+                                            int& item) {
+  const int nt = tiles_m * tiles_n, items = nt * n_split;
+  const int chunk = (items + 7) / 8;
+  item = (pid % 8) * chunk + pid / 8;
+  if (pid / 8 >= chunk || item >= items) return false;
+  split = item / nt;
+  const int lin = item - split * nt;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int g = lin / per_group;
+  const int first_m = g * GM;
+  const int gsz = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+  const int r = lin - g * per_group;
+  tm = first_m + r % gsz;
+  tn = r / gsz;
+  return true;
+}
+
+template <class C, class Epi>
+__global__ void __launch_bounds__(C::THREADS)
+k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
+           int ksteps_per_split, Epi epi) {
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[DNS * C::STAGE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
+  int tm, tn, split, item;
+  if (!item_coords(blockIdx.x, tiles_m, tiles_n, n_split, tm, tn, split, item)) return;
+  const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+  const int ksteps = static_cast<int>(d.Kd / DBK);
+  const int kbeg = split * ksteps_per_split;
+  const int kend = kbeg + ksteps_per_split < ksteps ? kbeg + ksteps_per_split : ksteps;
+  const int nk = kend - kbeg;
+  constexpr int P = C::P, KK = C::KK, NF = C::NF, NM = C::NM;
+
+  f32x16 acc[C::TM][C::TN];
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  if (nk > 0) {
+    // DMA instruction q of this wavefront fills rows [(wave*P + q)*RPI, +RPI) of the stacked [A rows; B rows]
+    // stage: lane -> row = base + lane / CPR, LDS slot = lane % CPR, global chunk = slot ^ ((row / RB) % CPR).
+    // Rows beyond M (or N) are clamped to the last valid row: their products are never stored.
+    const bf16_t* gsrc[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+      const int trow = (wave * P + q) * C::RPI + lane / C::CPR;
+      const int chunk = (lane % C::CPR) ^ ((trow / C::RB) % C::CPR);
+      if (trow < C::BM) {
+        const int64_t m = m0 + trow < d.M ? m0 + trow : d.M - 1;
+        gsrc[q] = A + m * d.lda + chunk * 8;
+      } else {
+        const int64_t n = n0 + (trow - C::BM) < d.N ? n0 + (trow - C::BM) : d.N - 1;
+        gsrc[q] = B + n * d.ldb + chunk * 8;
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < DNS - 1; ++s) {
+      const int t = kbeg + (s < nk ? s : nk - 1);
+#pragma unroll
+      for (int q = 0; q < P; ++q)
+        dma16(gsrc[q] + (int64_t)t * DBK,
+              __builtin_amdgcn_readfirstlane(lds_addr_of(lds + s * C::STAGE + (wave * P + q) * C::RPI * DBK)));
+    }
+
+    // fragment addresses: row = w? + i*32 + lane % 32, chunk = 2*kk + lane / 32, slot = chunk ^ ((row / RB) % CPR)
+    const int fr = lane & 31, hi = lane >> 5;
+    const int sw = (fr / C::RB) % C::CPR;
+    int a_off[KK], b_off[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int slot = ((2 * kk + hi) ^ sw) * 8;
+      a_off[kk] = (wm + fr) * DBK + slot;
+      b_off[kk] = C::BM * DBK + (wn + fr) * DBK + slot;
+    }
+    bf16x8 fa[2][C::TM], fb[2][C::TN];
+
+    FAAR_WAIT_VMCNT(P * (DNS - 2));  // slice 0 has landed (mine); barrier: everybody's
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) fa[0][i] = *reinterpret_cast<const bf16x8*>(lds + a_off[0] + i * 32 * DBK);
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) fb[0][j] = *reinterpret_cast<const bf16x8*>(lds + b_off[0] + j * 32 * DBK);
+
+    for (int it = 0; it < nk; ++it) {
+      // slice it+1 must have landed before its first fragments are prefetched at the end of this iteration;
+      // the barrier also guarantees that every wavefront has finished reading the stage refilled below.
+      FAAR_WAIT_VMCNT(P * (DNS - 3));
+      __builtin_amdgcn_s_barrier();
+      const bf16_t* st = lds + (it % DNS) * C::STAGE;
+      const bf16_t* st_next = lds + ((it + 1) % DNS) * C::STAGE;
+      const int dma_k = kbeg + (it + DNS - 1 < nk ? it + DNS - 1 : nk - 1);  // past the end: a harmless reload
+      const bf16_t* dma_base = lds + ((it + DNS - 1) % DNS) * C::STAGE + wave * P * C::RPI * DBK;
+      constexpr int DSTEP = (KK * NM) / P;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const int cur = kk & 1;
+        const bf16_t* src = (kk + 1 < KK) ? st : st_next;
+        const int nkk = (kk + 1 < KK) ? kk + 1 : 0;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          const int mi = m / C::TN, mj = m % C::TN;
+          acc[mi][mj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
+          if (m < NF) {  // fragment m of the next phase, in the order A0, B0..B(TN-1), A1..A(TM-1)
+            if (m == 0) fa[cur ^ 1][0] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk]);
+            else if (m <= C::TN) fb[cur ^ 1][m - 1] = *reinterpret_cast<const bf16x8*>(src + b_off[nkk] + (m - 1) * 32 * DBK);
+            else fa[cur ^ 1][m - C::TN] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk] + (m - C::TN) * 32 * DBK);
+          }
+          const int g = kk * NM + m;
+          if (g % DSTEP == DSTEP / 2 && g / DSTEP < P) {
+            const int q = g / DSTEP;
+            dma16(gsrc[q] + (int64_t)dma_k * DBK, __builtin_amdgcn_readfirstlane(lds_addr_of(dma_base + q * C::RPI * DBK)));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    FAAR_WAIT_VMCNT(0);  // no copy may still be in flight into this workgroup's LDS when it retires
+  }
+
+  const int col = lane & 31, hi2 = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+    for (int j = 0; j < C::TN; ++j) {
+      const int64_t n = n0 + wn + j * 32 + col;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int64_t m = m0 + wm + i * 32 + 8 * g + 4 * hi2;
+        const float r[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        epi.rows4(r, m, n, split, d);
+      }
+    }
+  epi.finish(item);
+}
+
 typedef Tile<128, 128> T128;
+typedef DmaCfg<256, 256, 2, 4> CfgL;  // large problems
+typedef DmaCfg<256, 128, 4, 2> CfgM;  // one tile per compute unit at ~256 tiles
+typedef DmaCfg<128, 128, 2, 2> CfgS;  // small outputs, two workgroups per compute unit
 
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
-template <class T, class Epi>
-hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, int n_split, Epi epi, hipStream_t st) {
-  const int tiles_m = ceil_div(d.M, T::BM), tiles_n = ceil_div(d.N, T::BN);
-  const int64_t k_per_split = round_up((d.Kd + n_split - 1) / n_split, BK);
-  const dim3 grid(static_cast<unsigned>(tiles_m) * tiles_n * n_split);
-  hipLaunchKernelGGL((k_gemm_nt<T, Epi>), grid, dim3(GEMM_THREADS), 0, st, A, B, d, tiles_m, tiles_n, k_per_split, epi);
+enum { KIND_GENERIC = 0, KIND_L = 1, KIND_M = 2, KIND_S = 3 };
+
+struct Plan {
+  int kind, tiles_m, tiles_n, n_split;
+  int64_t items() const { return (int64_t)tiles_m * tiles_n * n_split; }
+};
+
+inline Plan make_plan(int kind, const GemmDims& d, int n_split) {
+  const int bm = kind == KIND_L || kind == KIND_M ? 256 : 128;
+  const int bn = kind == KIND_L ? 256 : 128;
+  return Plan{kind, ceil_div(d.M, bm), ceil_div(d.N, bn), n_split};
+}
+
+// Tile shape and contraction split.  Large tiles cut LDS and L2 traffic per flop but need enough work
+// items to occupy 256 compute units; splitting the contraction (allowed only where partial sums may be
+// written separately) restores occupancy for small outputs with a long contraction.
+Plan plan_gemm(const GemmDims& d, bool may_split) {
+  if (d.Kd % DBK != 0) {
+    Plan p = make_plan(KIND_GENERIC, d, 1);
+    if (may_split)
+      while (p.items() < 256 && d.Kd / (p.n_split * 2) >= 512 && p.n_split < 16) p.n_split *= 2;
+    return p;
+  }
+  const int kinds[3] = {KIND_L, KIND_M, KIND_S};
+  const int64_t want[3] = {384, 192, 0};  // without splitting: L from 1.5 waves of tiles, M from 0.75
+  if (!may_split) {
+    for (int i = 0; i < 3; ++i) {
+      Plan p = make_plan(kinds[i], d, 1);
+      if (p.items() >= want[i]) return p;
+    }
+  }
+  Plan best = make_plan(KIND_S, d, 1);
+  for (int i = 0; i < 3; ++i) {
+    Plan p = make_plan(kinds[i], d, 1);
+    while (p.items() < 200 && d.Kd / (p.n_split * 2) >= 512 && p.n_split < 8) p.n_split *= 2;
+    if (p.items() >= 200) return p;
+    best = p;
+  }
+  return best;
+}
+
+template <class Epi>
+hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hipStream_t st) {
+  if (p.kind == KIND_GENERIC) {
+    const int64_t k_per_split = round_up((d.Kd + p.n_split - 1) / p.n_split, BK);
+    const dim3 grid(static_cast<unsigned>(p.items()));
+    hipLaunchKernelGGL((k_gemm_nt<T128, Epi>), grid, dim3(GEMM_THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, k_per_split, epi);
+    return hipGetLastError();
+  }
+  const int ksteps = static_cast<int>(d.Kd / DBK);
+  const int per_split = (ksteps + p.n_split - 1) / p.n_split;
+  const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
+#define FAAR_LAUNCH(CFG) \
+  hipLaunchKernelGGL((k_gemm_dma<CFG, Epi>), grid, dim3(CFG::THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, p.n_split, per_split, epi)
+  if (p.kind == KIND_L) FAAR_LAUNCH(CfgL);
+  else if (p.kind == KIND_M) FAAR_LAUNCH(CfgM);
+  else FAAR_LAUNCH(CfgS);
+#undef FAAR_LAUNCH
   return hipGetLastError();
 }
 
 }  // namespace
 
-int64_t gemm_residual_tiles(int64_t M, int64_t N) {
-  return (int64_t)ceil_div(M, T128::BM) * ceil_div(N, T128::BN);
+int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {
+  return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, false).items();
 }
 
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, hipStream_t st) {
   EpiResidual e{C, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
-  *n_partials = gemm_residual_tiles(d.M, d.N);
-  return run<T128>(A, B, d, 1, e, st);
+  const Plan p = plan_gemm(d, false);
+  *n_partials = p.items();
+  return run(A, B, d, p, e, st);
 }
 
-int choose_split(int64_t M, int64_t N, int64_t Kd) {
-  // enough workgroups to fill 256 compute units, but at least 512 of contraction per split
-  const int64_t tiles = (int64_t)ceil_div(M, T128::BM) * ceil_div(N, T128::BN);
-  int s = 1;
-  while (tiles * s < 256 && Kd / (s * 2) >= 512 && s < 16) s *= 2;
-  return s;
-}
+int choose_split(int64_t M, int64_t N, int64_t Kd) { return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, true).n_split; }
 
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st) {
   EpiF32 e{out};
-  return run<T128>(A, B, d, n_split, e, st);
+  Plan p = plan_gemm(d, true);
+  if (p.n_split != n_split) return hipErrorInvalidValue;  // the caller sized its workspace with choose_split
+  return run(A, B, d, p, e, st);
 }
 
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
                            bool first, float* C_out, hipStream_t st) {
+  const Plan p = plan_gemm(d, false);
   if (y_bf16) {
     EpiSub<true> e{Y, first, C_out};
-    return run<T128>(A, B, d, 1, e, st);
+    return run(A, B, d, p, e, st);
   }
   EpiSub<false> e{Y, first, C_out};
-  return run<T128>(A, B, d, 1, e, st);
+  return run(A, B, d, p, e, st);
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, hipStream_t st) {
   EpiBf16 e{out};
-  return run<T128>(A, B, d, 1, e, st);
+  return run(A, B, d, plan_gemm(d, false), e, st);
 }
 
 }  // namespace faar

@@ -67,7 +67,8 @@ struct GemmDims { int64_t M, N, Kd, lda, ldb; };
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, hipStream_t st);
-int64_t gemm_residual_tiles(int64_t M, int64_t N);
+// number of per-work-item loss partials the residual GEMM writes for these sizes
+int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 // Plain float32 output with the contraction split n_split ways: out[s][m][n] (split stride M*N).
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st);

@@ -110,6 +110,10 @@ def linear_cases():
     yield c
     yield synth.llm_linear("kproj_slice", 512, 2048, 640, 22)
     yield synth.llm_linear("three_tiles", 320, 256, 300, 23, quantised_acts=True)
+    # tile-shape coverage of the GEMM planner: 384 tiles of 256x256 with only two contraction slices,
+    # and 192 tiles of 256x128; the dW GEMM of both splits its contraction over the tokens
+    yield synth.llm_linear("wide_256x256_tiles", 12288, 64, 2048, 24)
+    yield synth.llm_linear("mid_256x128_tiles", 3072, 96, 2048, 25, quantised_acts=True)
 
 
 LCASES = list(linear_cases())
