@@ -152,6 +152,7 @@ k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d
 
 // R = acc - C; sum R^2; dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
 struct EpiResidual {
+  static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
   const float* C;
   float two_alpha;
   bf16_t* dYt;
@@ -159,20 +160,42 @@ struct EpiResidual {
   bf16_t* dY;
   double* partials;
   float sum;
+  // C[m..m+3][n] (zero outside the matrix); kept separate from value4 so that a whole slab's loads can be
+  // issued before the first dependent store
+  __device__ __forceinline__ float4 load4(int64_t m, int64_t n, const GemmDims& d) const {
+    float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (n < d.N) {
+      const float* p = C + m * d.N + n;
+      if (m < d.M) c.x = p[0];
+      if (m + 1 < d.M) c.y = p[d.N];
+      if (m + 2 < d.M) c.z = p[2 * d.N];
+      if (m + 3 < d.M) c.w = p[3 * d.N];
+    }
+    return c;
+  }
+  // four consecutive rows m..m+3 of column n -> four bf16 dY values (zero outside the matrix)
+  __device__ __forceinline__ uint2 value4(const float (&acc)[4], const float4& c4, int64_t m, int64_t n, const GemmDims& d) {
+    uint32_t b[4] = {0u, 0u, 0u, 0u};
+    const float c[4] = {c4.x, c4.y, c4.z, c4.w};
+    if (n < d.N) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (m + q < d.M) {
+          const float r = acc[q] - c[q];
+          sum += r * r;
+          b[q] = f32_to_bf16(two_alpha * r);
+          if (dY) dY[(m + q) * d.N + n] = static_cast<bf16_t>(b[q]);
+        }
+      }
+    }
+    return make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+  }
+  __device__ __forceinline__ void store_chunk(const uint4& v, int64_t m, int64_t n, const GemmDims& d) {
+    if (n < d.N && m < ldt) *reinterpret_cast<uint4*>(dYt + n * ldt + m) = v;  // m, ldt multiples of 8
+  }
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N || m >= ldt) return;
-    uint32_t b[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float r = 0.0f;
-      if (m + q < d.M) {
-        r = acc[q] - C[(m + q) * d.N + n];
-        sum += r * r;
-      }
-      b[q] = f32_to_bf16(two_alpha * r);
-      if (dY && m + q < d.M) dY[(m + q) * d.N + n] = static_cast<bf16_t>(b[q]);
-    }
-    *reinterpret_cast<uint2*>(dYt + n * ldt + m) = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+    *reinterpret_cast<uint2*>(dYt + n * ldt + m) = value4(acc, load4(m, n, d), m, n, d);
   }
   // fixed-order sum over the workgroup's wavefronts (4 or 8)
   __device__ __forceinline__ void finish(int item) {
@@ -193,6 +216,7 @@ struct EpiResidual {
 
 // out[split][m][n] = acc
 struct EpiF32 {
+  static constexpr bool kTransposedOut = false;
   float* out;
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int split, const GemmDims& d) {
     if (n >= d.N) return;
@@ -207,6 +231,7 @@ struct EpiF32 {
 // C_out[m][n] = (first ? Y[m][n] : C_out[m][n]) - acc
 template <bool kYbf16>
 struct EpiSub {
+  static constexpr bool kTransposedOut = false;
   const void* Y;
   bool first;
   float* C_out;
@@ -228,6 +253,7 @@ struct EpiSub {
 
 // out[m][n] = bf16(acc)
 struct EpiBf16 {
+  static constexpr bool kTransposedOut = false;
   bf16_t* out;
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N) return;
@@ -399,18 +425,53 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
   }
 
   const int col = lane & 31, hi2 = lane >> 5;
-#pragma unroll
-  for (int i = 0; i < C::TM; ++i)
+  if constexpr (Epi::kTransposedOut) {
+    // Output is wanted transposed ([n][m], m contiguous) while a lane holds 4 consecutive m of one n: stage
+    // one 32-column slab per wavefront column through LDS and write whole 2*BM-byte rows with 16 B per lane.
+    constexpr int LDT = C::BM + 8;          // padded staging row, elements
+    constexpr int ROWS = C::WGN * 32;       // staged n-rows per pass
+    constexpr int CPRW = C::BM / 8;         // 16-byte chunks per staged row
+    static_assert(ROWS * LDT <= DNS * C::STAGE, "staging buffer fits in the ring");
+    bf16_t* stg = lds;
+    const int wc = wave % C::WGN;
 #pragma unroll
     for (int j = 0; j < C::TN; ++j) {
+      __syncthreads();                      // ring (or previous slab) no longer read by anybody
       const int64_t n = n0 + wn + j * 32 + col;
+      float4 cv[C::TM][4];
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int64_t m = m0 + wm + i * 32 + 8 * g + 4 * hi2;
-        const float r[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        epi.rows4(r, m, n, split, d);
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) cv[i][g] = epi.load4(m0 + wm + i * 32 + 8 * g + 4 * hi2, n, d);
+#pragma unroll
+      for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int ml = wm + i * 32 + 8 * g + 4 * hi2;
+          const float r[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *reinterpret_cast<uint2*>(stg + (wc * 32 + col) * LDT + ml) = epi.value4(r, cv[i][g], m0 + ml, n, d);
+        }
+      __syncthreads();
+      for (int idx = tid; idx < ROWS * CPRW; idx += C::THREADS) {
+        const int row = idx / CPRW, ch = idx % CPRW;
+        const uint4 v = *reinterpret_cast<const uint4*>(stg + row * LDT + ch * 8);
+        epi.store_chunk(v, m0 + ch * 8, n0 + (row / 32) * C::WN + j * 32 + (row % 32), d);
       }
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i)
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j) {
+        const int64_t n = n0 + wn + j * 32 + col;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int64_t m = m0 + wm + i * 32 + 8 * g + 4 * hi2;
+          const float r[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          epi.rows4(r, m, n, split, d);
+        }
+      }
+  }
   epi.finish(item);
 }
 
