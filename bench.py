@@ -33,8 +33,8 @@ BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
 # Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale)
 BYTES_PER_WEIGHT = {
-    "softquant_fwd": 2 + 4 + 1 / 16 + 2,          # read W, V, scale; write W_q - W (bf16)
-    "bwd_adam": 4 + 2 + 1 / 16 + 12 + 12,         # read G (one split), W, scale, V, m, u; write V, m, u
+    "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,    # read W, V, interval code, scale; write W_q - W (bf16)
+    "bwd_adam": 0.5 + 1 / 16 + 12 + 12,           # read interval code, scale, V, m, u; write V, m, u (+ 4 B per dW split)
     "quant_rtn": 2 + 0.5 + 1 / 16,                # read W; write codes, scales
     "init_v": 2 + 1 / 16 + 4,                     # read W, scales; write V
     "harden_pack": 2 + 4 + 1 / 16 + 0.5,          # read W, V, scales; write codes
@@ -108,14 +108,14 @@ def main() -> int:
     def layer_job(n_steps):
         sg, scales, codes, _ = faar.faar_quant_rtn(W, ws=ws_q)
         V, _ = faar.faar_init_v(W, sg, scales)
-        Xt, C = faar.faar_layer_prepare(W, Xq, Y, ws=ws_p)
+        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y, ws=ws_p)
         m = torch.zeros_like(V)
         u = torch.zeros_like(V)
         for t in range(1, n_steps + 1):
-            faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
+            faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
                                  1e-8, t, losses, ws)
         out, _, _, flips = faar.faar_harden_pack(W, sg, scales, V, want_flips=True)
-        return sg, scales, V, m, u, Xt, C, out, flips
+        return sg, scales, V, m, u, Xt, C, ic, out, flips
 
     # warm-up (untimed)
     layer_job(max(1, args.warmup))
@@ -124,7 +124,7 @@ def main() -> int:
     # timed region: exactly K steps inside one whole per-layer job
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    sg, scales, V, m, u, Xt, C, packed, flips = layer_job(args.steps)
+    sg, scales, V, m, u, Xt, C, ic, packed, flips = layer_job(args.steps)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     final_losses = losses.cpu().numpy().tolist()
@@ -148,7 +148,7 @@ def main() -> int:
         return sum(ts) / len(ts)
 
     def step_call(i):
-        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
+        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
                              args.steps + 1 + i, losses, ws)
 
     n_probe = max(5, args.probe_steps)
@@ -160,6 +160,8 @@ def main() -> int:
     probe["harden_pack"] = timed_kernel(fb.K_HARDEN_PACK, lambda i: faar.faar_harden_pack(W, sg, scales, V), n_probe)
 
     gemm_flops = 2.0 * T * O * K
+    dw_split = fb.faar_dw_split(O, K, T)
+    BYTES_PER_WEIGHT["bwd_adam"] += 4 * dw_split
     kernels = {}
     for name, ms in probe.items():
         if name.startswith("gemm"):
@@ -185,7 +187,7 @@ def main() -> int:
                                "NVFP4 block 16; per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
                    "O": O, "K": K, "T": T},
         "weight_elems_per_sec": round(N * args.steps / elapsed, 1),
-        "final_losses": final_losses, "flipped_decisions": n_flips,
+        "dw_split": dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
         "roofline": roofline, "kernels": kernels,
     }
 

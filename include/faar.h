@@ -99,6 +99,10 @@ int faar_time_kernel(int which, void* start_event, void* stop_event);
  * invalid sizes. */
 size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags);
 
+/* Number of ways faar_layer_step splits the token contraction of the dW GEMM for these sizes (the
+ * float32 partial products are summed by the kernel that consumes them).  Pure host function. */
+int faar_dw_split(int64_t O, int64_t K, int64_t T);
+
 /* Padded leading dimension (in elements) of the transposed activations Xt written by
  * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
 int64_t faar_padded_tokens(int64_t T);
@@ -170,13 +174,20 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K,
  * The residual of Eq. 5 is then  Xq W_q^T - Y_fp = Xq (W_q - W)^T - C,  which lets the step run its
  * GEMM on the small perturbation W_q - W without losing it to bf16 rounding of W_q.
  *
+ * and the interval of every weight (Table 2 step 3; frozen with W and the scales), cached so that the
+ * steps need neither the division nor the node search:
+ *
+ *   icodes = uint8 [O*K/2], element 2j of a row in the low nibble: signbit(w) << 3 | (w == 0 ? 7 : k_lo)
+ *
+ *   s_global, scales  as written by faar_quant_rtn
  *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4)
  *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T
  *   ws   FAAR_OP_LAYER_PREPARE workspace
  */
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                       const float* s_global, const uint8_t* scales,
                        const void* Xq, const void* Y_fp, faar_dtype ydt, int64_t T,
-                       void* Xt, float* C, void* ws, size_t ws_bytes, void* stream);
+                       void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream);
 
 /* Adam hyper-parameters; t is the 1-based index of the step being taken. */
 typedef struct {
@@ -197,7 +208,7 @@ typedef struct {
  * accumulated in a fixed order (results are bit-reproducible run to run).
  *
  *   V, adam_m, adam_v   in/out float[O*K]
- *   Xq, Xt, C           as for / from faar_layer_prepare
+ *   Xq, Xt, C, icodes   as for / from faar_layer_prepare
  *   dY_ext              in, nullable bf16[T*O]: upstream gradient replacing the locally derived dY
  *   dX                  out, nullable bf16[T*K]: dY W_q
  *   opt                 HOST pointer
@@ -209,7 +220,7 @@ typedef struct {
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* s_global, const uint8_t* scales,
                     float* V, float* adam_m, float* adam_v,
-                    const void* Xq, const void* Xt, const float* C, int64_t T,
+                    const void* Xq, const void* Xt, const float* C, const uint8_t* icodes, int64_t T,
                     const void* dY_ext, void* dX,
                     float beta, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);

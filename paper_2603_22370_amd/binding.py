@@ -47,6 +47,8 @@ def lib() -> ctypes.CDLL:
         L.faar_workspace_bytes.argtypes = [c_int, c_int64, c_int64, c_int64, c_uint32]
         L.faar_time_kernel.restype = c_int
         L.faar_time_kernel.argtypes = [c_int, c_void_p, c_void_p]
+        L.faar_dw_split.restype = c_int
+        L.faar_dw_split.argtypes = [c_int64, c_int64, c_int64]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -59,11 +61,11 @@ def lib() -> ctypes.CDLL:
                                              c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p,
                                              c_size_t, c_void_p]
         L.faar_layer_prepare.restype = c_int
-        L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_int, c_int64,
-                                         c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
         L.faar_layer_step.restype = c_int
         L.faar_layer_step.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                      c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p,
                                       c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p, c_uint32,
                                       c_void_p, c_size_t, c_void_p]
         L.faar_harden_pack.restype = c_int
@@ -110,6 +112,10 @@ K_NONE, K_SOFTQUANT_FWD, K_GEMM_RESIDUAL, K_GEMM_DW, K_GEMM_DX, K_BWD_ADAM, K_QU
 def faar_time_kernel(which: int, start_event=None, stop_event=None) -> None:
     """start_event / stop_event: raw hipEvent_t handles (integers)."""
     _check(lib().faar_time_kernel(which, c_void_p(start_event), c_void_p(stop_event)), "faar_time_kernel")
+
+
+def faar_dw_split(O: int, K: int, T: int) -> int:
+    return int(lib().faar_dw_split(O, K, T))
 
 
 def faar_padded_tokens(T: int) -> int:
@@ -167,30 +173,32 @@ def faar_softquant_fwd_bwd(W, s_global, scales, V, beta, dWt=None, lambda_round=
     return Wt, dV, rl
 
 
-def faar_layer_prepare(W, Xq, Y_fp, ws=None):
-    """-> (Xt bf16 [K, Tp], C f32 [T, O])."""
-    _dev(W, Xq, Y_fp, ws)
+def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None):
+    """-> (Xt bf16 [K, Tp], C f32 [T, O], icodes u8 [O, K/2])."""
+    _dev(W, s_global, scales, Xq, Y_fp, ws)
     O, K = W.shape
     T = Xq.shape[0]
     if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or tuple(Y_fp.shape) != (T, O):
         raise ValueError("Xq must be bf16 [T,K]; Y_fp must be [T,O]")
     Xt = torch.empty((K, faar_padded_tokens(T)), dtype=torch.bfloat16, device=W.device)
     C = torch.empty((T, O), dtype=torch.float32, device=W.device)
+    icodes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     ws = _workspace(OP_LAYER_PREPARE, O, K, T, device=W.device) if ws is None else ws
-    _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(Xq), _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C),
-                                    _ptr(ws), ws.numel(), _stream()), "faar_layer_prepare")
-    return Xt, C
+    _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(Y_fp),
+                                    _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(ws), ws.numel(), _stream()),
+           "faar_layer_prepare")
+    return Xt, C, icodes
 
 
-def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, beta, lambda_round, mse_scale,
+def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
                     lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None):
     """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L)."""
-    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, losses, ws, dY_ext, dX)
+    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX)
     O, K = W.shape
     T = Xq.shape[0]
     opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
     _check(lib().faar_layer_step(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m),
-                                 _ptr(adam_v), _ptr(Xq), _ptr(Xt), _ptr(C), T, _ptr(dY_ext), _ptr(dX),
+                                 _ptr(adam_v), _ptr(Xq), _ptr(Xt), _ptr(C), _ptr(icodes), T, _ptr(dY_ext), _ptr(dX),
                                  float(beta), float(lambda_round), float(mse_scale), ctypes.byref(opt),
                                  _ptr(losses), 0, _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
 

@@ -94,6 +94,11 @@ int faar_time_kernel(int which, void* start_event, void* stop_event) {
   return FAAR_OK;
 }
 
+int faar_dw_split(int64_t O, int64_t K, int64_t T) {
+  if (check_shape(O, K) != FAAR_OK || T <= 0) return 0;
+  return choose_split(O, K, padded_tokens(T));
+}
+
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
 size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags) {
@@ -176,19 +181,21 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, 
   return FAAR_OK;
 }
 
-int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const void* Xq,
-                       const void* Y_fp, faar_dtype ydt, int64_t T, void* Xt, float* C, void* ws,
-                       size_t ws_bytes, void* stream) {
-  if (!W || !Xq || !Y_fp || !Xt || !C) return FAAR_E_NULL;
+int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                       const uint8_t* scales, const void* Xq, const void* Y_fp, faar_dtype ydt, int64_t T,
+                       void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !Xq || !Y_fp || !Xt || !C || !icodes) return FAAR_E_NULL;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_wdt(ydt)) return e;
   if (int e = check_shape(O, K)) return e;
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
-  if (!aligned16(W) || !aligned16(Xq) || !aligned16(Y_fp) || !aligned16(Xt) || !aligned16(C)) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(Xq) || !aligned16(Y_fp) || !aligned16(Xt) || !aligned16(C) || !aligned16(icodes))
+    return FAAR_E_ARG;
   const bool bf = wdt == FAAR_BF16;
   if (!bf && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_LAYER_PREPARE, O, K, T, 0))) return FAAR_E_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bf16_t* xq = static_cast<const bf16_t*>(Xq);
+  if (int e = hip_status(launch_interval_codes(W, bf, O * K, s_global, scales, icodes, st))) return e;
   if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), padded_tokens(T), st))) return e;
   const GemmDims d{T, O, K, K, K};
   if (bf) return hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, st));
@@ -203,10 +210,10 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
 
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
                     const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq,
-                    const void* Xt, const float* C, int64_t T, const void* dY_ext, void* dX,
+                    const void* Xt, const float* C, const uint8_t* icodes, int64_t T, const void* dY_ext, void* dX,
                     float beta, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
-  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !opt || !losses)
+  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !icodes || !opt || !losses)
     return FAAR_E_NULL;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_shape(O, K)) return e;
@@ -220,7 +227,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
       !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) || !std::isfinite(opt->eps) || opt->t < 1)
     return FAAR_E_ARG;
   if (!aligned16(W) || !aligned16(V) || !aligned16(adam_m) || !aligned16(adam_v) || !aligned16(Xq) ||
-      !aligned16(Xt) || !aligned16(C) || !aligned16(dY_ext) || !aligned16(dX) || !aligned16(ws))
+      !aligned16(Xt) || !aligned16(C) || !aligned16(icodes) || !aligned16(dY_ext) || !aligned16(dX) || !aligned16(ws))
     return FAAR_E_ARG;
   const StepLayout L = step_layout(O, K, T, chained);
   if (!ws || ws_bytes < L.total) return FAAR_E_WORKSPACE;
@@ -242,7 +249,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   // s1: W_q - W (bf16), and W_q itself when dX is wanted
   {
     Bracket b(FAAR_K_SOFTQUANT_FWD, st);
-    if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, true, delta, wq_full, st))) return e;
+    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, st))) return e;
   }
   // s2: residual GEMM + loss + dY
   int64_t n_mse = 0;
@@ -279,10 +286,12 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
   {
     Bracket b(FAAR_K_BWD_ADAM, st);
-    if (int e = hip_status(launch_bwd_adam(W, bf, n, s_global, scales, V, adam_m, adam_v, beta, G, L.n_split,
-                                           (int64_t)O * K, lambda_round, a, round_p, st)))
+    if (int e = hip_status(launch_step_bwd_adam(n, s_global, scales, icodes, V, adam_m, adam_v, beta, G, L.n_split,
+                                                (int64_t)O * K, lambda_round, a, round_p, st)))
       return e;
   }
+  // Loss sums are finished by a kernel of their own: a "last block finishes" scheme needs device-scope
+  // release/acquire per block, which on this multi-die part means L2 write-backs and costs far more.
   return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, softquant_bwd_blocks(n), 1.0 / (double)n,
                                            lambda_round, losses, losses + 1, losses + 2, st));
 }

@@ -276,6 +276,121 @@ k_bwd_adam(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_glo
   if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
 }
 
+
+// ---- layer-step kernels on cached interval codes -------------------------------------------
+// The interval of a weight (Table 2 step 3) depends only on W and the scales, which are frozen for the
+// whole layer, so faar_layer_prepare stores it once as a nibble  signbit(w) << 3 | (w == 0 ? 7 : k_lo)
+// and the per-step kernels skip the division and the node search.  Code 7 marks a zero weight
+// (sign(0) = 0 in Eq. 2: no contribution to W_q and no data gradient).
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_interval_codes(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+                 const uint8_t* __restrict__ scales, uint32_t* __restrict__ icodes) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float s = effective_scale(scales[i >> 1], *s_global_p);
+  float w[8];
+  W8<WT>::load(W + i * 8, w);
+  uint32_t packed = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t k = (w[j] == 0.0f) ? 7u : static_cast<uint32_t>(find_interval(w[j], s).k_lo);
+    packed |= (((__float_as_uint(w[j]) >> 31) << 3) | k) << (4 * j);
+  }
+  icodes[i] = packed;
+}
+
+// lower node and interval width of magnitude code k in 0..6
+__device__ __forceinline__ float node_lo(uint32_t k) {
+  return k < 2u ? 0.5f * static_cast<float>(k) : __uint_as_float(((126u + (k >> 1)) << 23) | ((k & 1u) << 22));
+}
+__device__ __forceinline__ float node_width(uint32_t k) { return k < 4u ? 0.5f : (k < 6u ? 1.0f : 2.0f); }
+// sigmoid through the hardware exp2 / reciprocal units (about 1 ulp each; not decision arithmetic)
+__device__ __forceinline__ float h_beta_fast(float v, float beta) {
+  return __builtin_amdgcn_rcpf(1.0f + __expf(-beta * (v - 0.5f)));
+}
+// signed scale  sign(w) * s  of a coded weight (0 for a zero weight)
+__device__ __forceinline__ float signed_scale(uint32_t nib, float s) {
+  return (nib & 7u) == 7u ? 0.0f : ((nib & 8u) ? -s : s);
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // round-to-nearest-even pair conversion
+  f32x2_t f = {a, b};
+  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
+  return *reinterpret_cast<uint32_t*>(&h);
+}
+
+template <typename WT, bool kFull>
+__global__ void __launch_bounds__(kEltThreads)
+k_step_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+           const uint8_t* __restrict__ scales, const uint32_t* __restrict__ icodes, const float* __restrict__ V,
+           float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float s = effective_scale(scales[i >> 1], *s_global_p);
+  const uint32_t codes = icodes[i];
+  float w[8], v[8], out[8], full[8];
+  W8<WT>::load(W + i * 8, w);
+  load8(V + i * 8, v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t nib = (codes >> (4 * j)) & 15u, k = nib & 7u;
+    const float wq = signed_scale(nib, s) * (node_lo(k) + h_beta_fast(v[j], beta) * node_width(k));
+    out[j] = wq - w[j];
+    if (kFull) full[j] = wq;
+  }
+  *reinterpret_cast<uint4*>(delta + i * 8) = make_uint4(pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3]),
+                                                         pack_bf16x2(out[4], out[5]), pack_bf16x2(out[6], out[7]));
+  if (kFull)
+    *reinterpret_cast<uint4*>(Wq_full + i * 8) = make_uint4(pack_bf16x2(full[0], full[1]), pack_bf16x2(full[2], full[3]),
+                                                            pack_bf16x2(full[4], full[5]), pack_bf16x2(full[6], full[7]));
+}
+
+__global__ void __launch_bounds__(kEltThreads)
+k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t* __restrict__ scales,
+                const uint32_t* __restrict__ icodes, float* __restrict__ V, float* __restrict__ M,
+                float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
+                float lam_over_n, AdamScalars o, double* __restrict__ round_partials) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  float rsum = 0.0f;
+  if (i < n8) {
+    const float s = effective_scale(scales[i >> 1], *s_global_p);
+    const uint32_t codes = icodes[i];
+    float v[8], g[8], m[8], u[8];
+    load8(V + i * 8, v);
+    load8(M + i * 8, m);
+    load8(U + i * 8, u);
+    load8(G + i * 8, g);
+    for (int sp = 1; sp < n_split; ++sp) {
+      float g2[8];
+      load8(G + sp * split_stride + i * 8, g2);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) g[j] += g2[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t nib = (codes >> (4 * j)) & 15u;
+      const float h = h_beta_fast(v[j], beta);
+      const float t = 2.0f * v[j] - 1.0f;
+      rsum += 1.0f - t * t;
+      const float d = g[j] * (signed_scale(nib, s) * node_width(nib & 7u) * beta * (h * (1.0f - h))) +
+                      lam_over_n * (4.0f - 8.0f * v[j]);
+      m[j] = o.beta1 * m[j] + (1.0f - o.beta1) * d;
+      u[j] = o.beta2 * u[j] + (1.0f - o.beta2) * (d * d);
+      const float step = o.lr * (m[j] * o.inv_bc1) * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(u[j] * o.inv_bc2) + o.eps);
+      v[j] = fminf(fmaxf(v[j] - step, 0.0f), 1.0f);  // V clipped to [0, 1] after every update
+    }
+    store8(V + i * 8, v);
+    store8(M + i * 8, m);
+    store8(U + i * 8, u);
+  }
+  const double bs = block_sum(static_cast<double>(rsum));
+  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
+}
+
 // ---- loss finalisation: fixed-order sums of the per-block partials --------------------------
 __global__ void __launch_bounds__(kEltThreads)
 k_finalize_losses(const double* __restrict__ mse_partials, int64_t n_mse, float mse_scale,
@@ -447,6 +562,45 @@ hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s
   else
     hipLaunchKernelGGL(k_bwd_adam<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, m, u,
                        beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
+  return hipGetLastError();
+}
+
+
+hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                 const uint8_t* scales, uint8_t* icodes, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  uint32_t* c32 = reinterpret_cast<uint32_t*>(icodes);
+  if (w_bf16)
+    hipLaunchKernelGGL(k_interval_codes<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, c32);
+  else
+    hipLaunchKernelGGL(k_interval_codes<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, c32);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                           const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
+                           hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const uint32_t* c32 = reinterpret_cast<const uint32_t*>(icodes);
+#define FAAR_SF(WT, F) \
+  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full)
+  if (w_bf16) { if (Wq_full) FAAR_SF(bf16_t, true); else FAAR_SF(bf16_t, false); }
+  else        { if (Wq_full) FAAR_SF(float, true);  else FAAR_SF(float, false); }
+#undef FAAR_SF
+  return hipGetLastError();
+}
+
+hipError_t launch_step_bwd_adam(int64_t n, const float* s_global, const uint8_t* scales, const uint8_t* icodes,
+                                float* V, float* m, float* u, float beta, const float* G, int n_split,
+                                int64_t split_stride, float lambda_round, AdamScalars opt, double* round_partials,
+                                hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
+  hipLaunchKernelGGL(k_step_bwd_adam, g, b, 0, st, n8, s_global, scales, reinterpret_cast<const uint32_t*>(icodes), V, m, u,
+                     beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
   return hipGetLastError();
 }
 

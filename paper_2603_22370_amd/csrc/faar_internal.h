@@ -43,6 +43,18 @@ hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s
                            const uint8_t* scales, float* V, float* m, float* u, float beta,
                            const float* G, int n_split, int64_t split_stride, float lambda_round,
                            AdamScalars opt, double* round_partials, hipStream_t st);
+// Interval codes signbit(w) << 3 | (w == 0 ? 7 : k_lo), two per byte, for the per-step kernels below.
+hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const float* s_global,
+                                 const uint8_t* scales, uint8_t* icodes, hipStream_t st);
+// Step forward on cached codes: delta = bf16(W_q - W) (+ bf16(W_q) when Wq_full).
+hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                           const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
+                           hipStream_t st);
+// Step backward + Adam + clip on cached codes; per-block Round-Loss partial sums as launch_softquant_bwd.
+hipError_t launch_step_bwd_adam(int64_t n, const float* s_global, const uint8_t* scales, const uint8_t* icodes,
+                                float* V, float* m, float* u, float beta, const float* G, int n_split,
+                                int64_t split_stride, float lambda_round, AdamScalars opt, double* round_partials,
+                                hipStream_t st);
 // losses[0] = mse_scale * sum(mse_partials), losses[1] = sum(round_partials) / n,
 // losses[2] = losses[0] + lambda * losses[1].  Either partial array may be empty (count 0).
 hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, float mse_scale,

@@ -126,13 +126,13 @@ def _setup(c):
     q = fo.quant_rtn(c.W, c.w_is_bf16)
     Xq = dev(c.Xq, True)
     Y = dev(c.Y_fp, True)
-    Xt, C = faar.faar_layer_prepare(Wd, Xq, Y)
-    return Wd, sg, scales, q, Xq, Y, Xt, C
+    Xt, C, ic = faar.faar_layer_prepare(Wd, sg, scales, Xq, Y)
+    return Wd, sg, scales, q, Xq, Y, Xt, (C, ic)
 
 
 @pytest.mark.parametrize("c", LCASES, ids=LIDS)
 def test_layer_prepare(c):
-    Wd, sg, scales, q, Xq, Y, Xt, C = _setup(c)
+    Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
     Tp = faar.faar_padded_tokens(c.T)
     xt = host(Xt)
     assert xt.shape == (c.K, Tp)
@@ -140,9 +140,13 @@ def test_layer_prepare(c):
     C_want = c.Y_fp.astype(np.float64) - c.Xq.astype(np.float64) @ c.W.astype(np.float64).T
     scale = np.abs(c.Xq.astype(np.float64)) @ np.abs(c.W.astype(np.float64)).T      # size of the summed terms
     assert np.all(np.abs(host(C) - C_want) <= 2e-6 * scale + 1e-30)
+    # cached interval codes: sign bit and k_lo (7 for a zero weight)
+    wt = fo.normalised_magnitude(c.W, q["scales"], q["s_global"])
+    want_ic = (np.signbit(c.W).astype(np.uint8) << 3) | np.where(c.W == 0, 7, fo.find_interval(wt)).astype(np.uint8)
+    assert np.array_equal(host(ic), fo.pack_nibbles(want_ic))
     # also with a float32 reference output
-    Xt2, C2 = faar.faar_layer_prepare(Wd, Xq, dev(c.Y_fp))
-    assert torch.equal(C2, C) and torch.equal(Xt2, Xt)
+    Xt2, C2, ic2 = faar.faar_layer_prepare(Wd, sg, scales, Xq, dev(c.Y_fp))
+    assert torch.equal(C2, C) and torch.equal(Xt2, Xt) and torch.equal(ic2, ic)
 
 
 # Two bf16 roundings (unit roundoff u = 2^-9) sit between the inputs and the loss / gradient: the
@@ -164,7 +168,7 @@ def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False):
     chained = dY_ext is not None or want_dX
     ws = faar.layer_step_workspace(c.O, c.K, c.T, chained=chained)
     dX = torch.empty((c.T, c.K), dtype=torch.bfloat16, device="cuda") if want_dX else None
-    faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, C, beta, HYP["lambda_round"], alpha, HYP["lr"],
+    faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, *C, beta, HYP["lambda_round"], alpha, HYP["lr"],
                          HYP["beta1"], HYP["beta2"], HYP["eps"], t, losses, ws,
                          dY_ext=None if dY_ext is None else dev(dY_ext, True), dX=dX)
     torch.cuda.synchronize()
@@ -266,7 +270,7 @@ def test_config1_trajectory_100_adam_steps():
     first = last = None
     for t in range(1, steps + 1):
         beta = 4.0 + 28.0 * (t - 1) / (steps - 1)
-        faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, C, beta, 0.01, alpha, lr, 0.9, 0.999, 1e-8, t, losses, ws)
+        faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, *C, beta, 0.01, alpha, lr, 0.9, 0.999, 1e-8, t, losses, ws)
         r = fo.layer_step(c.W, q["s_global"], q["scales"], Vo, mo, uo, c.Xq, c.Y_fp, beta, 0.01, alpha, lr, 0.9,
                           0.999, 1e-8, t)
         Vo, mo, uo = r["V"], r["m"], r["u"]
@@ -304,7 +308,7 @@ def test_resume_is_bit_exact_and_runs_are_deterministic():
             state = [V, torch.zeros_like(V), torch.zeros_like(V)]
         losses = torch.zeros(3, dtype=torch.float32, device="cuda")
         for t in range(t0 + 1, t0 + n_steps + 1):
-            faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, C, 4.0 + t, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, t,
+            faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, 4.0 + t, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, t,
                                  losses, ws)
         return state, losses.clone()
 
