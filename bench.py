@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the FAAR per-layer rounding-optimisation path on one MI355X.
 
-Workload (N=1): the Llama3-1B-shaped attention projection of the second configuration --
+Default workload (N=1): the Llama3-1B-shaped attention projection of the second configuration --
 q_proj, W 2048x2048 bf16 Student-t(4) scaled to std 0.02, calibration X 4096 tokens x 2048 bf16
 with 1% outlier channels x30 -- synthetic, seeded, resident in HBM before the timed region.
+--workload picks another linear of the Llama3-1B- / Qwen3-1.7B-shaped blocks (see WORKLOADS).
 
 Timed region: one whole per-layer job = faar_quant_rtn + faar_init_v + faar_layer_prepare, then
 EXACTLY K faar_layer_step calls (soft-quant, residual GEMM + loss, dW GEMM, dV + Round Loss + Adam +
@@ -31,14 +32,25 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
-# Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale)
-BYTES_PER_WEIGHT = {
-    "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,    # read W, V, interval code, scale; write W_q - W (bf16)
-    "bwd_adam": 0.5 + 1 / 16 + 12 + 12,           # read interval code, scale, V, m, u; write V, m, u (+ 4 B per dW split)
-    "quant_rtn": 2 + 0.5 + 1 / 16,                # read W; write codes, scales
-    "init_v": 2 + 1 / 16 + 4,                     # read W, scales; write V
-    "harden_pack": 2 + 4 + 1 / 16 + 0.5,          # read W, V, scales; write codes
+# name -> (O, K, T, gated_input): linears of the Llama3-1B-shaped (T = 4096) and Qwen3-1.7B-shaped (T = 8192) blocks
+WORKLOADS = {
+    "q_proj": (2048, 2048, 4096, False), "k_proj": (512, 2048, 4096, False),
+    "gate_proj": (8192, 2048, 4096, False), "down_proj": (2048, 8192, 4096, True),
+    "qwen_k_proj": (1024, 2048, 8192, False), "qwen_q_proj": (2048, 2048, 8192, False),
+    "qwen_gate_proj": (6144, 2048, 8192, False), "qwen_down_proj": (2048, 6144, 8192, True),
 }
+
+
+def bytes_per_weight(dw_split: int) -> dict:
+    """Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale,
+    1/2 B cached interval code), for the design as built: the dV kernel reads one fp32 partial per dW split."""
+    return {
+        "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,             # read W, V, code, scale; write W_q - W (bf16)
+        "bwd_adam": 4 * dw_split + 0.5 + 1 / 16 + 12 + 12,     # read G partials, code, scale, V, m, u; write V, m, u
+        "quant_rtn": 2 + 0.5 + 1 / 16,                         # read W; write codes, scales
+        "init_v": 2 + 1 / 16 + 4,                              # read W, scales; write V
+        "harden_pack": 2 + 4 + 1 / 16 + 0.5,                   # read W, V, scales; write codes
+    }
 
 
 class HipEvents:
@@ -49,7 +61,6 @@ class HipEvents:
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
-        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
 
     def create(self):
         ev = ctypes.c_void_p()
@@ -72,6 +83,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=20)
@@ -90,11 +102,13 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    O, K, T = 2048, 2048, 4096
-    case = synth.llm_linear("q_proj", O, K, T, seed=0)
-    W = torch.from_numpy(case.W).cuda().to(torch.bfloat16)
-    Xq = torch.from_numpy(case.Xq).cuda().to(torch.bfloat16)
-    Y = torch.from_numpy(case.Y_fp).cuda().to(torch.bfloat16)
+    O, K, T, gated = WORKLOADS[args.workload]
+    W_h = synth.student_t_weight(O, K, seed=0)
+    X_h = synth.silu_gated_activations(T, K, seed=0) if gated else synth.activations(T, K, seed=0)
+    W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
+    Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
+    Y = Xq @ W.T                       # the frozen BF16 layer output: an input of the method (input generation only)
+    torch.cuda.synchronize()
     N = O * K
     alpha, lam, lr = 1.0 / (T * O), 0.01, 5e-4
     losses = torch.zeros(3, dtype=torch.float32, device="cuda")
@@ -161,7 +175,7 @@ def main() -> int:
 
     gemm_flops = 2.0 * T * O * K
     dw_split = fb.faar_dw_split(O, K, T)
-    BYTES_PER_WEIGHT["bwd_adam"] += 4 * dw_split
+    bpw = bytes_per_weight(dw_split)
     kernels = {}
     for name, ms in probe.items():
         if name.startswith("gemm"):
@@ -169,7 +183,7 @@ def main() -> int:
             kernels[name] = {"ms": round(ms, 5), "bound": "mfma", "achieved": round(ach, 2), "unit": "TFLOP/s",
                              "frac": round(ach / BF16_PEAK_TFLOPS, 4)}
         else:
-            ach = BYTES_PER_WEIGHT[name] * N / (ms * 1e-3) / 1e9
+            ach = bpw[name] * N / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 5), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
                              "frac": round(ach / HBM_PEAK_GBS, 4)}
     dom = max(("gemm_residual", "gemm_dw", "softquant_fwd", "bwd_adam"), key=lambda k: probe[k])
@@ -183,10 +197,11 @@ def main() -> int:
         "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "llama3-1b-shaped q_proj: W 2048x2048 bf16 Student-t(4), X 4096x2048 bf16, "
-                               "NVFP4 block 16; per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
+        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} bf16, NVFP4 block 16; "
+                               "per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
                    "O": O, "K": K, "T": T},
         "weight_elems_per_sec": round(N * args.steps / elapsed, 1),
+        "step_gemm_tflops": round(2 * gemm_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "dw_split": dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
         "roofline": roofline, "kernels": kernels,
     }
@@ -198,21 +213,22 @@ def main() -> int:
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
-        q = fo.quant_rtn(case.W, True)
-        V0 = fo.init_v(case.W, q["s_global"], q["scales"])["V"]
+        Y_h = Y.float().cpu().numpy()
+        q = fo.quant_rtn(W_h, True)
+        V0 = fo.init_v(W_h, q["s_global"], q["scales"])["V"]
         m0 = np.zeros_like(V0)
         u0 = np.zeros_like(V0)
         n_cpu, t_cpu = 0, 0.0
         while n_cpu < 1 or (t_cpu < args.cpu_seconds and n_cpu < 20):
             c0 = time.perf_counter()
-            r = fo.layer_step(case.W, q["s_global"], q["scales"], V0, m0, u0, case.Xq, case.Y_fp,
+            r = fo.layer_step(W_h, q["s_global"], q["scales"], V0, m0, u0, X_h, Y_h,
                               beta_at(n_cpu + 1, args.steps), lam, alpha, lr, 0.9, 0.999, 1e-8, n_cpu + 1)
             V0, m0, u0 = r["V"], r["m"], r["u"]
             t_cpu += time.perf_counter() - c0
             n_cpu += 1
         out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "cores": int(cores),
                                "kind": "oracle",
-                               "sample": f"{n_cpu} layer steps of the same q_proj layer (numpy float64, "
+                               "sample": f"{n_cpu} layer steps of the same {args.workload} layer (numpy float64, "
                                          f"{t_cpu:.1f} s)"}
     print(json.dumps(out))
     return 0

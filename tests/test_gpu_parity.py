@@ -323,3 +323,39 @@ def test_resume_is_bit_exact_and_runs_are_deterministic():
     for x, y in zip(a, cc):
         assert torch.equal(x, y)
     assert torch.equal(la, lc)
+
+
+def test_full_size_q_proj_step_and_pack():
+    """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
+    X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
+    and bit-exact quantisation / packing of all 4.2 M weights."""
+    c = synth.llm_linear("q_proj", 2048, 2048, 4096, 0)
+    q = fo.quant_rtn(c.W, True)
+    Wd, sg, scales, _, Xq, Y, Xt, C = _setup(c)
+    _, scales_g, codes_g, _ = faar.faar_quant_rtn(Wd)
+    assert np.array_equal(host(scales_g), q["scales"]) and np.array_equal(host(codes_g), q["codes"])
+    V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+    Vg, _ = faar.faar_init_v(Wd, sg, scales)
+    assert np.array_equal(host(Vg).view(np.uint32), V0.view(np.uint32))
+    alpha = 1.0 / (c.T * c.O)
+    m = torch.zeros_like(Vg)
+    u = torch.zeros_like(Vg)
+    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ws = faar.layer_step_workspace(c.O, c.K, c.T)
+    faar.faar_layer_step(Wd, sg, scales, Vg, m, u, Xq, Xt, *C, 8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"],
+                         HYP["beta2"], HYP["eps"], 1, losses, ws)
+    torch.cuda.synchronize()
+    ref = {mode: fo.layer_step(c.W, q["s_global"], q["scales"], V0, np.zeros_like(V0), np.zeros_like(V0), c.Xq, c.Y_fp,
+                               8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 1,
+                               declared_rounding=mode) for mode in (False, True)}
+    L = host(losses)
+    assert L[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
+    assert L[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
+    assert L[1] == pytest.approx(ref[False]["L_round"], rel=1e-5)
+    _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
+    _check_update(host(Vg), host(m), host(u), V0, np.zeros_like(V0), np.zeros_like(V0), 1)
+    hp = fo.harden_pack(c.W, True, q["s_global"], q["scales"], host(Vg))
+    codes2, dec, Wf, flips = faar.faar_harden_pack(Wd, sg, scales, Vg, want_decisions=True, want_final=True, want_flips=True)
+    assert np.array_equal(host(codes2), hp["codes"]) and np.array_equal(host(dec), hp["decisions"])
+    assert np.array_equal(host(Wf).view(np.uint32), hp["W_final"].view(np.uint32))
+    assert int(flips.item()) == hp["flip_count"]
