@@ -87,6 +87,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=20)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy three times (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path has no collectives or sharding "
@@ -186,11 +188,28 @@ def main() -> int:
             ach = bpw[name] * N / (ms * 1e-3) / 1e9
             kernels[name] = {"ms": round(ms, 5), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
                              "frac": round(ach / HBM_PEAK_GBS, 4)}
+    # HBM-side bytes per launch measured with rocprofv3 PMC counters (committed summary; None if not measured)
+    traffic = {}
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if os.path.exists(tpath):
+        for line in open(tpath):
+            f = line.split()
+            if len(f) == 4 and f[0] == args.workload:
+                traffic[f[1]] = int((float(f[2]) + float(f[3])) * 1e6)
+    for name in kernels:
+        kernels[name]["traffic"] = traffic.get(name)
     dom = max(("gemm_residual", "gemm_dw", "softquant_fwd", "bwd_adam"), key=lambda k: probe[k])
     roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
                 "peak": BF16_PEAK_TFLOPS if kernels[dom]["bound"] == "mfma" else HBM_PEAK_GBS,
-                "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": None,
+                "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": kernels[dom]["traffic"],
                 "launch_ms": kernels[dom]["ms"]}
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
 
     ms_per_step = elapsed / args.steps * 1e3
     out = {

@@ -292,7 +292,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   }
   // Loss sums are finished by a kernel of their own: a "last block finishes" scheme needs device-scope
   // release/acquire per block, which on this multi-die part means L2 write-backs and costs far more.
-  return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, softquant_bwd_blocks(n), 1.0 / (double)n,
+  return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, step_bwd_blocks(n), 1.0 / (double)n,
                                            lambda_round, losses, losses + 1, losses + 2, st));
 }
 

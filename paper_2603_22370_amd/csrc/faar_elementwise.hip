@@ -354,10 +354,10 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
                 const uint32_t* __restrict__ icodes, float* __restrict__ V, float* __restrict__ M,
                 float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
                 float lam_over_n, AdamScalars o, double* __restrict__ round_partials) {
-  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
   float rsum = 0.0f;
-  if (i < n8) {
-    const float s = effective_scale(scales[i >> 1], *s_global_p);
+  const float sg = *s_global_p;
+  for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kEltThreads) {
+    const float s = effective_scale(scales[i >> 1], sg);
     const uint32_t codes = icodes[i];
     float v[8], g[8], m[8], u[8];
     load8(V + i * 8, v);
@@ -397,7 +397,10 @@ k_finalize_losses(const double* __restrict__ mse_partials, int64_t n_mse, float 
                   const double* __restrict__ round_partials, int64_t n_round, double inv_n,
                   float lambda_round, float* loss_mse, float* loss_round, float* loss_total) {
   double a = 0.0, b = 0.0;
+  // per-thread partial sums in a fixed order; loads of one batch are independent
+#pragma unroll 4
   for (int64_t i = threadIdx.x; i < n_mse; i += kEltThreads) a += mse_partials[i];
+#pragma unroll 4
   for (int64_t i = threadIdx.x; i < n_round; i += kEltThreads) b += round_partials[i];
   __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64];
   a = wave_sum(a);
@@ -532,6 +535,8 @@ hipError_t launch_softquant_fwd(const void* W, bool w_bf16, int64_t n, const flo
 }
 
 int64_t softquant_bwd_blocks(int64_t n) { return (n / 8 + kEltThreads - 1) / kEltThreads; }
+// the fused step kernel walks its elements with a grid-stride loop so that the partial count stays small
+int64_t step_bwd_blocks(int64_t n) { return std::min<int64_t>(softquant_bwd_blocks(n), kStepBwdMaxBlocks); }
 
 hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
                                 const uint8_t* scales, const float* V, float beta, const float* G,
@@ -597,7 +602,7 @@ hipError_t launch_step_bwd_adam(int64_t n, const float* s_global, const uint8_t*
                                 int64_t split_stride, float lambda_round, AdamScalars opt, double* round_partials,
                                 hipStream_t st) {
   const int64_t n8 = n / 8;
-  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const dim3 g(static_cast<unsigned>(step_bwd_blocks(n))), b(kEltThreads);
   const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
   hipLaunchKernelGGL(k_step_bwd_adam, g, b, 0, st, n8, s_global, scales, reinterpret_cast<const uint32_t*>(icodes), V, m, u,
                      beta, G, n_split, split_stride, lam_over_n, opt, round_partials);

@@ -11,7 +11,7 @@ namespace faar {
 
 constexpr int kAmaxPartials = 1024;     // partial maxima written by the first amax pass
 constexpr int kEltThreads = 256;        // threads per block of every elementwise kernel
-constexpr int kMaxLossPartials = 1 << 16;
+constexpr int kStepBwdMaxBlocks = 2048;  // grid cap of the fused backward + Adam kernel (grid-stride beyond)
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline int64_t padded_tokens(int64_t T) { return round_up(T, 64); }
@@ -37,6 +37,7 @@ hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const flo
                                 int n_split, int64_t split_stride, float lambda_round, float* dV,
                                 double* round_partials, hipStream_t st);
 int64_t softquant_bwd_blocks(int64_t n);
+int64_t step_bwd_blocks(int64_t n);
 // Backward + Adam + clip in one pass; same partial layout as launch_softquant_bwd.
 struct AdamScalars { float lr, beta1, beta2, eps, inv_bc1, inv_bc2; };
 hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s_global,
