@@ -43,10 +43,11 @@ WORKLOADS = {
 
 def bytes_per_weight(dw_split: int) -> dict:
     """Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale,
-    1/2 B cached interval code), for the design as built: the dV kernel reads one fp32 partial per dW split."""
+    1/2 B cached interval code), for the design as built: the dV kernel reads one fp32 partial per dW split
+    and, in every step but a layer's last, also writes the next step's W_q - W."""
     return {
         "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,             # read W, V, code, scale; write W_q - W (bf16)
-        "bwd_adam": 4 * dw_split + 0.5 + 1 / 16 + 12 + 12,     # read G partials, code, scale, V, m, u; write V, m, u
+        "bwd_adam": 4 * dw_split + 0.5 + 1 / 16 + 12 + 12 + 2 + 2,  # read G partials, code, scale, V, m, u, W; write V, m, u, W_q - W
         "quant_rtn": 2 + 0.5 + 1 / 16,                         # read W; write codes, scales
         "init_v": 2 + 1 / 16 + 4,                              # read W, scales; write V
         "harden_pack": 2 + 4 + 1 / 16 + 0.5,                   # read W, V, scales; write codes
@@ -128,8 +129,10 @@ def main() -> int:
         m = torch.zeros_like(V)
         u = torch.zeros_like(V)
         for t in range(1, n_steps + 1):
+            # every step but the last also prepares the next step's soft-quantised weights (beta_next)
             faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
-                                 1e-8, t, losses, ws)
+                                 1e-8, t, losses, ws, beta_next=beta_at(t + 1, n_steps) if t < n_steps else 0.0,
+                                 forward_ready=t > 1)
         out, _, _, flips = faar.faar_harden_pack(W, sg, scales, V, want_flips=True)
         return sg, scales, V, m, u, Xt, C, ic, out, flips
 
@@ -163,13 +166,17 @@ def main() -> int:
         ts = ts[2:] if len(ts) > 4 else ts
         return sum(ts) / len(ts)
 
-    def step_call(i):
+    def first_step_call(i):      # a layer's first step: its own forward kernel, nothing prepared for the next
         faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
                              args.steps + 1 + i, losses, ws)
 
+    def step_call(i):            # every later step: forward taken from / left in the workspace
+        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
+                             args.steps + 1 + i, losses, ws, beta_next=16.0, forward_ready=i > 0)
+
     n_probe = max(5, args.probe_steps)
-    for name, kid in [("softquant_fwd", fb.K_SOFTQUANT_FWD), ("gemm_residual", fb.K_GEMM_RESIDUAL),
-                      ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
+    probe["softquant_fwd"] = timed_kernel(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
+    for name, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
         probe[name] = timed_kernel(kid, step_call, n_probe)
     probe["quant_rtn"] = timed_kernel(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(W, ws=ws_q), n_probe)
     probe["init_v"] = timed_kernel(fb.K_INIT_V, lambda i: faar.faar_init_v(W, sg, scales), n_probe)

@@ -55,8 +55,10 @@ enum {
 enum {
   FAAR_SGLOBAL_GIVEN = 1u << 0, /* faar_quant_rtn: *s_global is an input instead of an output */
   FAAR_EMIT_DELTA = 1u << 1,    /* faar_softquant_fwd_bwd: Wt receives W_q - W instead of W_q */
-  FAAR_WS_CHAINED = 1u << 2     /* faar_workspace_bytes / faar_layer_step: size the workspace for a
+  FAAR_WS_CHAINED = 1u << 2,    /* faar_workspace_bytes / faar_layer_step: size the workspace for a
                                    step that takes dY_ext and/or produces dX */
+  FAAR_WS_FORWARD_READY = 1u << 3 /* faar_layer_step: the workspace already holds this step's soft-quantised
+                                   weights, left there by the previous step (its beta_next) */
 };
 
 /* operations, for faar_workspace_bytes */
@@ -215,14 +217,22 @@ typedef struct {
  *   losses              out float[3]: L_mse, L_round, L
  *   ws                  FAAR_OP_LAYER_STEP workspace (queried with FAAR_WS_CHAINED when dY_ext or dX
  *                       is given; that mode also requires O % 8 == 0)
- *   flags               0 or FAAR_WS_CHAINED (accepted, no effect on the computation)
+ *   beta_next           0, or the beta of the step that follows: the pass that updates V then also
+ *                       evaluates Eq. 2-3 on the updated V at beta_next and leaves W_q - W (and W_q when dX
+ *                       is requested) with that V's Round-Loss partial sums in ws, saving the next step
+ *                       its forward kernel.  Same arithmetic, same results bit for bit.
+ *   flags               FAAR_WS_CHAINED is accepted and has no effect on the computation.
+ *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  The caller
+ *                       vouches that the previous call on this ws was step opt->t - 1 of the same layer
+ *                       (same W, scales, shapes, dX requested or not) with beta_next equal to this call's
+ *                       beta, and that V and ws have not been written since.  Not checked.
  */
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* s_global, const uint8_t* scales,
                     float* V, float* adam_m, float* adam_v,
                     const void* Xq, const void* Xt, const float* C, const uint8_t* icodes, int64_t T,
                     const void* dY_ext, void* dX,
-                    float beta, float lambda_round, float mse_scale, const faar_adam* opt,
+                    float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 
 /*

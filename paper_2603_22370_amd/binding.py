@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfaar.so")
 
 FAAR_F32, FAAR_BF16 = 0, 1
-FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED = 1, 2, 4
+FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY = 1, 2, 4, 8
 OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK = range(6)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
@@ -66,8 +66,8 @@ def lib() -> ctypes.CDLL:
         L.faar_layer_step.restype = c_int
         L.faar_layer_step.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                       c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p,
-                                      c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p, c_uint32,
-                                      c_void_p, c_size_t, c_void_p]
+                                      c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
+                                      c_uint32, c_void_p, c_size_t, c_void_p]
         L.faar_harden_pack.restype = c_int
         L.faar_harden_pack.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                        c_void_p, c_void_p, c_void_p, c_void_p]
@@ -191,16 +191,18 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None):
 
 
 def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
-                    lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None):
-    """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L)."""
+                    lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False):
+    """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L).
+    beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them."""
     _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX)
     O, K = W.shape
     T = Xq.shape[0]
     opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
     _check(lib().faar_layer_step(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m),
                                  _ptr(adam_v), _ptr(Xq), _ptr(Xt), _ptr(C), _ptr(icodes), T, _ptr(dY_ext), _ptr(dX),
-                                 float(beta), float(lambda_round), float(mse_scale), ctypes.byref(opt),
-                                 _ptr(losses), 0, _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
+                                 float(beta), float(beta_next), float(lambda_round), float(mse_scale),
+                                 ctypes.byref(opt), _ptr(losses), FAAR_WS_FORWARD_READY if forward_ready else 0,
+                                 _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
 
 
 def layer_step_workspace(O, K, T, chained=False, device="cuda"):

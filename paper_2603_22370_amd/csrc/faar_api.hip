@@ -69,7 +69,7 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   L.dYt = take((size_t)O * L.Tp * 2);
   L.G = take((size_t)L.n_split * O * K * 4);
   L.mse_partials = take((size_t)gemm_residual_partials(T, O, K) * 8);
-  L.round_partials = take((size_t)softquant_bwd_blocks(O * K) * 8);
+  L.round_partials = take((size_t)2 * kStepBwdMaxBlocks * 8);  // two sets: steps of even / odd index
   if (chained) {
     L.wq_full = take((size_t)O * K * 2);
     L.wqt = take((size_t)K * L.Op * 2);
@@ -211,7 +211,7 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
                     const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq,
                     const void* Xt, const float* C, const uint8_t* icodes, int64_t T, const void* dY_ext, void* dX,
-                    float beta, float lambda_round, float mse_scale, const faar_adam* opt,
+                    float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
   if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !icodes || !opt || !losses)
     return FAAR_E_NULL;
@@ -220,9 +220,10 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
   const bool chained = dY_ext || dX;
   if (chained && O % 8 != 0) return FAAR_E_SHAPE;
-  if (flags & ~(uint32_t)FAAR_WS_CHAINED) return FAAR_E_ARG;
+  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY)) return FAAR_E_ARG;
   if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
     return FAAR_E_ARG;
+  if (!(beta_next >= 0.0f) || !std::isfinite(beta_next)) return FAAR_E_ARG;
   if (!(opt->lr >= 0.0f) || !std::isfinite(opt->lr) || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) ||
       !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) || !std::isfinite(opt->eps) || opt->t < 1)
     return FAAR_E_ARG;
@@ -240,16 +241,20 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   bf16_t* dYt = reinterpret_cast<bf16_t*>(base + L.dYt);
   float* G = reinterpret_cast<float*>(base + L.G);
   double* mse_p = reinterpret_cast<double*>(base + L.mse_partials);
-  double* round_p = reinterpret_cast<double*>(base + L.round_partials);
+  // Round-Loss partials of the V a step starts from: set t % 2, so that a step which also prepares the
+  // next one writes the other set while its last block reads this one
+  double* round_p = reinterpret_cast<double*>(base + L.round_partials) + (opt->t & 1) * kStepBwdMaxBlocks;
+  double* round_next = reinterpret_cast<double*>(base + L.round_partials) + ((opt->t + 1) & 1) * kStepBwdMaxBlocks;
   bf16_t* wq_full = chained && dX ? reinterpret_cast<bf16_t*>(base + L.wq_full) : nullptr;
   bf16_t* wqt = chained ? reinterpret_cast<bf16_t*>(base + L.wqt) : nullptr;
   bf16_t* dY = chained ? reinterpret_cast<bf16_t*>(base + L.dY) : nullptr;
   const bf16_t* xq = static_cast<const bf16_t*>(Xq);
 
-  // s1: W_q - W (bf16), and W_q itself when dX is wanted
-  {
+  // s1: W_q - W (bf16), W_q itself when dX is wanted, Round-Loss partials -- unless the previous step left them
+  if (!(flags & FAAR_WS_FORWARD_READY)) {
     Bracket b(FAAR_K_SOFTQUANT_FWD, st);
-    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, st))) return e;
+    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, round_p, st)))
+      return e;
   }
   // s2: residual GEMM + loss + dY
   int64_t n_mse = 0;
@@ -279,21 +284,21 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     Bracket b(FAAR_K_GEMM_DX, st);
     if (int e = hip_status(launch_gemm_bf16(dY_used, wqt, d3, static_cast<bf16_t*>(dX), st))) return e;
   }
-  // s5 + s6: dV, Round Loss, Adam, clip
-  AdamScalars a;
-  a.lr = opt->lr; a.beta1 = opt->beta1; a.beta2 = opt->beta2; a.eps = opt->eps;
-  a.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));
-  a.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
-  {
-    Bracket b(FAAR_K_BWD_ADAM, st);
-    if (int e = hip_status(launch_step_bwd_adam(n, s_global, scales, icodes, V, adam_m, adam_v, beta, G, L.n_split,
-                                                (int64_t)O * K, lambda_round, a, round_p, st)))
-      return e;
-  }
-  // Loss sums are finished by a kernel of their own: a "last block finishes" scheme needs device-scope
-  // release/acquire per block, which on this multi-die part means L2 write-backs and costs far more.
-  return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, round_p, step_bwd_blocks(n), 1.0 / (double)n,
-                                           lambda_round, losses, losses + 1, losses + 2, st));
+  // s5 + s6: dV, Adam, clip; the same launch sums the losses (both kinds of partials are complete by now:
+  // they come from earlier kernels) and, when asked, runs s1 of the next step on the updated V
+  StepBwdArgs a{};
+  a.W = W; a.w_bf16 = bf; a.n = n;
+  a.s_global = s_global; a.scales = scales; a.icodes = icodes;
+  a.V = V; a.m = adam_m; a.u = adam_v;
+  a.beta = beta; a.G = G; a.n_split = L.n_split; a.split_stride = (int64_t)O * K;
+  a.lambda_round = lambda_round;
+  a.opt.lr = opt->lr; a.opt.beta1 = opt->beta1; a.opt.beta2 = opt->beta2; a.opt.eps = opt->eps;
+  a.opt.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));
+  a.opt.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
+  a.mse_partials = mse_p; a.n_mse = n_mse; a.mse_scale = mse_scale; a.round_partials = round_p; a.losses = losses;
+  a.beta_next = beta_next; a.delta_next = delta; a.wq_full_next = wq_full; a.round_next = round_next;
+  Bracket b(FAAR_K_BWD_ADAM, st);
+  return hip_status(launch_step_bwd_adam(a, st));
 }
 
 int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,

@@ -323,40 +323,116 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // round-to
   return *reinterpret_cast<uint32_t*>(&h);
 }
 
+// soft-quantised weight of one coded element
+__device__ __forceinline__ float soft_weight(uint32_t nib, float s, float v, float beta) {
+  const uint32_t k = nib & 7u;
+  return signed_scale(nib, s) * (node_lo(k) + h_beta_fast(v, beta) * node_width(k));
+}
+
+__device__ __forceinline__ void store_bf16x8(bf16_t* p, const float (&x)[8]) {
+  *reinterpret_cast<uint4*>(p) = make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
+                                            pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+}
+
+// delta = bf16(W_q - W) (and bf16(W_q)) for eight weights, plus their Round-Loss terms sum(1 - (2v - 1)^2)
+template <typename WT, bool kFull>
+__device__ __forceinline__ float forward8(const WT* __restrict__ W, int64_t i, uint32_t codes, float s,
+                                          const float (&v)[8], float beta, bf16_t* __restrict__ delta,
+                                          bf16_t* __restrict__ Wq_full) {
+  float w[8], out[8], full[8];
+  W8<WT>::load(W + i * 8, w);
+  float rsum = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float wq = soft_weight((codes >> (4 * j)) & 15u, s, v[j], beta);
+    out[j] = wq - w[j];
+    if (kFull) full[j] = wq;
+    const float t = 2.0f * v[j] - 1.0f;
+    rsum += 1.0f - t * t;
+  }
+  store_bf16x8(delta + i * 8, out);
+  if (kFull) store_bf16x8(Wq_full + i * 8, full);
+  return rsum;
+}
+
 template <typename WT, bool kFull>
 __global__ void __launch_bounds__(kEltThreads)
 k_step_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
            const uint8_t* __restrict__ scales, const uint32_t* __restrict__ icodes, const float* __restrict__ V,
-           float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full) {
-  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
-  if (i >= n8) return;
-  const float s = effective_scale(scales[i >> 1], *s_global_p);
-  const uint32_t codes = icodes[i];
-  float w[8], v[8], out[8], full[8];
-  W8<WT>::load(W + i * 8, w);
-  load8(V + i * 8, v);
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t nib = (codes >> (4 * j)) & 15u, k = nib & 7u;
-    const float wq = signed_scale(nib, s) * (node_lo(k) + h_beta_fast(v[j], beta) * node_width(k));
-    out[j] = wq - w[j];
-    if (kFull) full[j] = wq;
+           float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_partials) {
+  float rsum = 0.0f;
+  const float sg = *s_global_p;
+  for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kEltThreads) {
+    float v[8];
+    load8(V + i * 8, v);
+    rsum += forward8<WT, kFull>(W, i, icodes[i], effective_scale(scales[i >> 1], sg), v, beta, delta, Wq_full);
   }
-  *reinterpret_cast<uint4*>(delta + i * 8) = make_uint4(pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3]),
-                                                         pack_bf16x2(out[4], out[5]), pack_bf16x2(out[6], out[7]));
-  if (kFull)
-    *reinterpret_cast<uint4*>(Wq_full + i * 8) = make_uint4(pack_bf16x2(full[0], full[1]), pack_bf16x2(full[2], full[3]),
-                                                            pack_bf16x2(full[4], full[5]), pack_bf16x2(full[6], full[7]));
+  const double bs = block_sum(static_cast<double>(rsum));
+  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
 }
 
+// ---- loss finalisation: fixed-order sums of the per-block partials (one block) ---------------
+struct LossSums {
+  const double* mse_partials;
+  int64_t n_mse;
+  float mse_scale;
+  const double* round_partials;
+  int64_t n_round;
+  double inv_n;
+  float lambda_round;
+  float *loss_mse, *loss_round, *loss_total;
+};
+
+__device__ __forceinline__ void finalize_block(const LossSums& f) {
+  double a = 0.0, b = 0.0;
+  // per-thread partial sums in a fixed order; loads of one batch are independent
+#pragma unroll 4
+  for (int64_t i = threadIdx.x; i < f.n_mse; i += kEltThreads) a += f.mse_partials[i];
+#pragma unroll 4
+  for (int64_t i = threadIdx.x; i < f.n_round; i += kEltThreads) b += f.round_partials[i];
+  __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64];
+  a = wave_sum(a);
+  b = wave_sum(b);
+  if ((threadIdx.x & 63) == 0) {
+    sa[threadIdx.x >> 6] = a;
+    sb[threadIdx.x >> 6] = b;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    a = 0.0;
+    b = 0.0;
+    for (int i = 0; i < kEltThreads / 64; ++i) {
+      a += sa[i];
+      b += sb[i];
+    }
+    const double mse = a * static_cast<double>(f.mse_scale);
+    const double rl = b * f.inv_n;
+    if (f.loss_mse) *f.loss_mse = static_cast<float>(mse);
+    if (f.loss_round) *f.loss_round = static_cast<float>(rl);
+    if (f.loss_total) *f.loss_total = static_cast<float>(mse + static_cast<double>(f.lambda_round) * rl);
+  }
+}
+
+__global__ void __launch_bounds__(kEltThreads) k_finalize_losses(LossSums f) { finalize_block(f); }
+
+// Backward + Adam + clip over grid-stride blocks 0..gridDim.x-2.  With kEmit the same pass writes the next
+// step's delta (and W_q) from the updated V at beta_next, with that V's Round-Loss partials.  The last block
+// takes no weights: it finishes this step's losses from partial sums that earlier kernels completed.
+template <typename WT, bool kEmit, bool kFull>
 __global__ void __launch_bounds__(kEltThreads)
 k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t* __restrict__ scales,
                 const uint32_t* __restrict__ icodes, float* __restrict__ V, float* __restrict__ M,
                 float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
-                float lam_over_n, AdamScalars o, double* __restrict__ round_partials) {
+                float lam_over_n, AdamScalars o, LossSums fin, const WT* __restrict__ W, float beta_next,
+                bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_next) {
+  const int workers = static_cast<int>(gridDim.x) - 1;
+  if (static_cast<int>(blockIdx.x) == workers) {
+    finalize_block(fin);
+    return;
+  }
   float rsum = 0.0f;
   const float sg = *s_global_p;
-  for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kEltThreads) {
+  for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)workers * kEltThreads) {
     const float s = effective_scale(scales[i >> 1], sg);
     const uint32_t codes = icodes[i];
     float v[8], g[8], m[8], u[8];
@@ -374,8 +450,6 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
     for (int j = 0; j < 8; ++j) {
       const uint32_t nib = (codes >> (4 * j)) & 15u;
       const float h = h_beta_fast(v[j], beta);
-      const float t = 2.0f * v[j] - 1.0f;
-      rsum += 1.0f - t * t;
       const float d = g[j] * (signed_scale(nib, s) * node_width(nib & 7u) * beta * (h * (1.0f - h))) +
                       lam_over_n * (4.0f - 8.0f * v[j]);
       m[j] = o.beta1 * m[j] + (1.0f - o.beta1) * d;
@@ -386,42 +460,11 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
     store8(V + i * 8, v);
     store8(M + i * 8, m);
     store8(U + i * 8, u);
+    if (kEmit) rsum += forward8<WT, kFull>(W, i, codes, s, v, beta_next, delta, Wq_full);
   }
-  const double bs = block_sum(static_cast<double>(rsum));
-  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
-}
-
-// ---- loss finalisation: fixed-order sums of the per-block partials --------------------------
-__global__ void __launch_bounds__(kEltThreads)
-k_finalize_losses(const double* __restrict__ mse_partials, int64_t n_mse, float mse_scale,
-                  const double* __restrict__ round_partials, int64_t n_round, double inv_n,
-                  float lambda_round, float* loss_mse, float* loss_round, float* loss_total) {
-  double a = 0.0, b = 0.0;
-  // per-thread partial sums in a fixed order; loads of one batch are independent
-#pragma unroll 4
-  for (int64_t i = threadIdx.x; i < n_mse; i += kEltThreads) a += mse_partials[i];
-#pragma unroll 4
-  for (int64_t i = threadIdx.x; i < n_round; i += kEltThreads) b += round_partials[i];
-  __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64];
-  a = wave_sum(a);
-  b = wave_sum(b);
-  if ((threadIdx.x & 63) == 0) {
-    sa[threadIdx.x >> 6] = a;
-    sb[threadIdx.x >> 6] = b;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    a = 0.0;
-    b = 0.0;
-    for (int i = 0; i < kEltThreads / 64; ++i) {
-      a += sa[i];
-      b += sb[i];
-    }
-    const double mse = a * static_cast<double>(mse_scale);
-    const double rl = b * inv_n;
-    if (loss_mse) *loss_mse = static_cast<float>(mse);
-    if (loss_round) *loss_round = static_cast<float>(rl);
-    if (loss_total) *loss_total = static_cast<float>(mse + static_cast<double>(lambda_round) * rl);
+  if (kEmit) {
+    const double bs = block_sum(static_cast<double>(rsum));
+    if (threadIdx.x == 0) round_next[blockIdx.x] = bs;
   }
 }
 
@@ -585,27 +628,35 @@ hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const fl
 
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           hipStream_t st) {
+                           double* round_partials, hipStream_t st) {
   const int64_t n8 = n / 8;
-  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const dim3 g(static_cast<unsigned>(step_bwd_blocks(n))), b(kEltThreads);
   const uint32_t* c32 = reinterpret_cast<const uint32_t*>(icodes);
 #define FAAR_SF(WT, F) \
-  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full)
+  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full, round_partials)
   if (w_bf16) { if (Wq_full) FAAR_SF(bf16_t, true); else FAAR_SF(bf16_t, false); }
   else        { if (Wq_full) FAAR_SF(float, true);  else FAAR_SF(float, false); }
 #undef FAAR_SF
   return hipGetLastError();
 }
 
-hipError_t launch_step_bwd_adam(int64_t n, const float* s_global, const uint8_t* scales, const uint8_t* icodes,
-                                float* V, float* m, float* u, float beta, const float* G, int n_split,
-                                int64_t split_stride, float lambda_round, AdamScalars opt, double* round_partials,
-                                hipStream_t st) {
-  const int64_t n8 = n / 8;
-  const dim3 g(static_cast<unsigned>(step_bwd_blocks(n))), b(kEltThreads);
-  const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
-  hipLaunchKernelGGL(k_step_bwd_adam, g, b, 0, st, n8, s_global, scales, reinterpret_cast<const uint32_t*>(icodes), V, m, u,
-                     beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
+hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st) {
+  const int64_t n8 = a.n / 8;
+  const int64_t workers = step_bwd_blocks(a.n);
+  const dim3 g(static_cast<unsigned>(workers + 1)), b(kEltThreads);  // the extra block finishes the losses
+  const float lam_over_n = static_cast<float>(static_cast<double>(a.lambda_round) / static_cast<double>(a.n));
+  const LossSums fin{a.mse_partials, a.n_mse, a.mse_scale, a.round_partials, workers, 1.0 / static_cast<double>(a.n),
+                     a.lambda_round, a.losses, a.losses + 1, a.losses + 2};
+  const uint32_t* c32 = reinterpret_cast<const uint32_t*>(a.icodes);
+#define FAAR_SB(WT, E, F) \
+  hipLaunchKernelGGL((k_step_bwd_adam<WT, E, F>), g, b, 0, st, n8, a.s_global, a.scales, c32, a.V, a.m, a.u, a.beta, a.G, \
+                     a.n_split, a.split_stride, lam_over_n, a.opt, fin, static_cast<const WT*>(a.W), a.beta_next, \
+                     a.delta_next, a.wq_full_next, a.round_next)
+  const bool emit = a.beta_next > 0.0f;
+  if (!emit) { if (a.w_bf16) FAAR_SB(bf16_t, false, false); else FAAR_SB(float, false, false); }
+  else if (a.wq_full_next) { if (a.w_bf16) FAAR_SB(bf16_t, true, true); else FAAR_SB(float, true, true); }
+  else { if (a.w_bf16) FAAR_SB(bf16_t, true, false); else FAAR_SB(float, true, false); }
+#undef FAAR_SB
   return hipGetLastError();
 }
 
@@ -613,8 +664,9 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
                                   const double* round_partials, int64_t n_round, double inv_n,
                                   float lambda_round, float* loss_mse, float* loss_round,
                                   float* loss_total, hipStream_t st) {
-  hipLaunchKernelGGL(k_finalize_losses, dim3(1), dim3(kEltThreads), 0, st, mse_partials, n_mse, mse_scale,
-                     round_partials, n_round, inv_n, lambda_round, loss_mse, loss_round, loss_total);
+  const LossSums f{mse_partials, n_mse, mse_scale, round_partials, n_round, inv_n, lambda_round,
+                   loss_mse, loss_round, loss_total};
+  hipLaunchKernelGGL(k_finalize_losses, dim3(1), dim3(kEltThreads), 0, st, f);
   return hipGetLastError();
 }
 

@@ -47,15 +47,25 @@ hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s
 // Interval codes signbit(w) << 3 | (w == 0 ? 7 : k_lo), two per byte, for the per-step kernels below.
 hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const float* s_global,
                                  const uint8_t* scales, uint8_t* icodes, hipStream_t st);
-// Step forward on cached codes: delta = bf16(W_q - W) (+ bf16(W_q) when Wq_full).
+// Step forward on cached codes: delta = bf16(W_q - W) (+ bf16(W_q) when Wq_full), and the Round-Loss
+// partial sums of V, one per block (step_bwd_blocks(n) of them).
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           hipStream_t st);
-// Step backward + Adam + clip on cached codes; per-block Round-Loss partial sums as launch_softquant_bwd.
-hipError_t launch_step_bwd_adam(int64_t n, const float* s_global, const uint8_t* scales, const uint8_t* icodes,
-                                float* V, float* m, float* u, float beta, const float* G, int n_split,
-                                int64_t split_stride, float lambda_round, AdamScalars opt, double* round_partials,
-                                hipStream_t st);
+                           double* round_partials, hipStream_t st);
+// Step backward + Adam + clip on cached codes.  One more block sums this step's losses (mse_partials from the
+// residual GEMM, round_partials of the V the step started from) into losses[0..2].  beta_next > 0 also emits
+// the next step's forward outputs from the updated V: delta_next (and wq_full_next when not null) and that
+// V's Round-Loss partials in round_next (must not alias round_partials).
+struct StepBwdArgs {
+  const void* W; bool w_bf16; int64_t n;
+  const float* s_global; const uint8_t* scales; const uint8_t* icodes;
+  float *V, *m, *u;
+  float beta; const float* G; int n_split; int64_t split_stride;
+  float lambda_round; AdamScalars opt;
+  const double* mse_partials; int64_t n_mse; float mse_scale; const double* round_partials; float* losses;
+  float beta_next; bf16_t* delta_next; bf16_t* wq_full_next; double* round_next;
+};
+hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st);
 // losses[0] = mse_scale * sum(mse_partials), losses[1] = sum(round_partials) / n,
 // losses[2] = losses[0] + lambda * losses[1].  Either partial array may be empty (count 0).
 hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, float mse_scale,

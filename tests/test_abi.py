@@ -70,11 +70,14 @@ def test_error_codes_without_a_gpu():
     st = L.faar_layer_step
     big = 1 << 30
     args = lambda **kw: [kw.get("W", p), 1, kw.get("O", 16), 16, p, p, p, p, p, p, p, p, p, kw.get("T", 8),
-                         kw.get("dYe", nul), kw.get("dX", nul), kw.get("beta", 4.0), 0.01, 1.0,
-                         ctypes.byref(kw.get("opt", opt)), p, 0, p, kw.get("ws", big), nul]
+                         kw.get("dYe", nul), kw.get("dX", nul), kw.get("beta", 4.0), kw.get("beta_next", 0.0), 0.01, 1.0,
+                         ctypes.byref(kw.get("opt", opt)), p, kw.get("flags", 0), p, kw.get("ws", big), nul]
     assert st(*args(W=nul)) == -1
     assert st(*args(T=0)) == -2
     assert st(*args(beta=-1.0)) == -6
+    assert st(*args(beta_next=-1.0)) == -6
+    assert st(*args(beta_next=float("nan"))) == -6
+    assert st(*args(flags=16)) == -6                                                       # unknown flag bit
     assert st(*args(opt=fb.faar_adam(-1.0, 0.9, 0.999, 1e-8, 1))) == -6
     assert st(*args(opt=fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 0))) == -6
     assert st(*args(ws=16)) == -4

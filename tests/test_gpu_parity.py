@@ -325,6 +325,51 @@ def test_resume_is_bit_exact_and_runs_are_deterministic():
     assert torch.equal(la, lc)
 
 
+def test_forward_left_by_the_previous_step_gives_identical_results():
+    """A step may leave the next step's soft-quantised weights in the workspace (beta_next) and the next
+    step may consume them (forward_ready): same arithmetic, so losses and state must match the plain
+    sequence bit for bit -- float32 and bf16 weights, with and without dX, odd and even step indices."""
+    rng = np.random.default_rng(17)
+    for c, want_dX in ((synth.config1(0), False), (LCASES[3], False), (LCASES[3], True), (LCASES[1], True)):
+        Wd, sg, scales, q, Xq, Y, Xt, C = _setup(c)
+        alpha = 1.0 / (c.T * c.O)
+        ws = faar.layer_step_workspace(c.O, c.K, c.T, chained=want_dX)
+        betas = [4.0, 7.5, 9.0, 9.0, 16.0, 30.0]
+
+        def run(fused, t0=2):
+            V, _ = faar.faar_init_v(Wd, sg, scales)
+            state = [V, torch.zeros_like(V), torch.zeros_like(V)]
+            losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+            dX = torch.zeros((c.T, c.K), dtype=torch.bfloat16, device="cuda") if want_dX else None
+            ws.zero_()
+            out = []
+            for i, beta in enumerate(betas):
+                nxt = betas[i + 1] if fused and i + 1 < len(betas) else 0.0
+                faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, beta, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8,
+                                     t0 + i, losses, ws, dX=dX, beta_next=nxt, forward_ready=fused and i > 0)
+                out.append((losses.clone(), None if dX is None else dX.clone()))
+            return state, out
+
+        a, oa = run(False)
+        b, ob = run(True)
+        for x, y in zip(a, b):
+            assert torch.equal(x, y), c.name
+        for (la, xa), (lb, xb) in zip(oa, ob):
+            assert torch.equal(la, lb), c.name
+            assert xa is None or torch.equal(xa, xb)
+        # a prepared forward that is not consumed does no harm
+        V, _ = faar.faar_init_v(Wd, sg, scales)
+        state = [V, torch.zeros_like(V), torch.zeros_like(V)]
+        losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+        dX = torch.zeros((c.T, c.K), dtype=torch.bfloat16, device="cuda") if want_dX else None
+        for i, beta in enumerate(betas):
+            faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, beta, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8,
+                                 2 + i, losses, ws, dX=dX, beta_next=float(rng.uniform(1, 40)))
+        for x, y in zip(a, state):
+            assert torch.equal(x, y), c.name
+        assert torch.equal(losses, oa[-1][0])
+
+
 def test_full_size_q_proj_step_and_pack():
     """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
     X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
