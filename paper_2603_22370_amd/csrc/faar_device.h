@@ -88,14 +88,38 @@ struct Interval {
   float v_init;  // Eq. 4, clamped to [0, 1]
 };
 
+// Number of nodes among 0.5, 1, 1.5, 2, 3, 4 that are <= wt, for finite wt >= 0.  From 1 upwards the
+// nodes are exactly the floats with one significand bit, so exponent and leading significand bit index them:
+// (bits >> 22) is 254 at 1.0, 255 at 1.5, 256 at 2.0 ... ; 252 and 253 cover [0.5, 1).
+__device__ __forceinline__ int interval_index(float wt) {
+  const int d = static_cast<int>(__float_as_uint(wt) >> 22) - 252;
+  return d < 0 ? 0 : min(max(d, 1), 6);
+}
+// N[k] for k in 0..6
+__device__ __forceinline__ float interval_lo(int k) {
+  return k < 2 ? 0.5f * static_cast<float>(k)
+               : __uint_as_float(((126u + (static_cast<uint32_t>(k) >> 1)) << 23) | ((static_cast<uint32_t>(k) & 1u) << 22));
+}
+
+// Midpoint of interval k: round-to-nearest goes up exactly when w~ >= midpoint (w~ - lo is exact and
+// the widths are powers of two, so this is the same decision as v_init >= 0.5).
+__device__ __forceinline__ float interval_mid(int k) {
+  return k < 2 ? 0.25f + 0.5f * static_cast<float>(k) : __uint_as_float(__float_as_uint(interval_lo(k)) | (1u << 21));
+}
+// w~ = |w| / s, one correctly rounded division; 0 when the block scale is 0
+__device__ __forceinline__ float normalised(float w, float s) { return (s == 0.0f) ? 0.0f : fabsf(w) / s; }
+
 // Table 2 steps 2-4 for one weight: w~ = |w| / s (0 when s == 0), interval, relative position.
+// (w~ - lo) / width is evaluated as a product with 1 / width: the widths are powers of two, so both are
+// the correctly rounded value of the same real number.
 __device__ __forceinline__ Interval find_interval(float w, float s) {
-  const float wt = (s == 0.0f) ? 0.0f : fabsf(w) / s;
+  const float wt = normalised(w, s);
   Interval r;
-  r.k_lo = (wt >= 0.5f) + (wt >= 1.0f) + (wt >= 1.5f) + (wt >= 2.0f) + (wt >= 3.0f) + (wt >= 4.0f);
-  r.lo = r.k_lo <= 4 ? 0.5f * static_cast<float>(r.k_lo) : (r.k_lo == 5 ? 3.0f : 4.0f);
+  r.k_lo = interval_index(wt);
+  r.lo = interval_lo(r.k_lo);
   r.width = r.k_lo <= 3 ? 0.5f : (r.k_lo == 6 ? 2.0f : 1.0f);
-  const float v = (wt - r.lo) / r.width;
+  const float inv_width = r.k_lo <= 3 ? 2.0f : (r.k_lo == 6 ? 0.5f : 1.0f);
+  const float v = (wt - r.lo) * inv_width;
   r.v_init = fminf(fmaxf(v, 0.0f), 1.0f);
   return r;
 }

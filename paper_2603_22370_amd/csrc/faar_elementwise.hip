@@ -96,8 +96,9 @@ k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_gl
   float dq[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const Interval iv = find_interval(w[j], s);
-    const uint32_t nib = nibble(w[j], iv.k_lo, iv.v_init >= 0.5f);
+    const float wt = normalised(w[j], s);
+    const int k_lo = interval_index(wt);
+    const uint32_t nib = nibble(w[j], k_lo, wt >= interval_mid(k_lo));
     packed |= nib << (4 * j);
     if (kDequant) dq[j] = dequant(nib, sgv, sg);
   }
@@ -146,11 +147,11 @@ k_harden_pack(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_
     uint32_t packed = 0, bits = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const Interval iv = find_interval(w[j], s);
+      const float wt = normalised(w[j], s);
+      const int k_lo = interval_index(wt);
       const int up = v[j] >= 0.5f;
-      const uint32_t nib = nibble(w[j], iv.k_lo, up);
-      const uint32_t rtn = nibble(w[j], iv.k_lo, iv.v_init >= 0.5f);
-      flips += (nib != rtn);
+      const uint32_t nib = nibble(w[j], k_lo, up);
+      flips += (w[j] != 0.0f) & (up != (wt >= interval_mid(k_lo)));  // differs from round-to-nearest
       packed |= nib << (4 * j);
       bits |= static_cast<uint32_t>(up) << j;
       dq[j] = dequant(nib, sgv, sg);
