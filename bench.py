@@ -79,12 +79,188 @@ class HipEvents:
         return float(ms.value)
 
 
+# The seven linears of one Qwen3-1.7B-shaped block: name -> (O, K, input group, gated input)
+QWEN_BLOCK = [("q_proj", 2048, 2048, "attn_in", False), ("k_proj", 1024, 2048, "attn_in", False),
+              ("v_proj", 1024, 2048, "attn_in", False), ("o_proj", 2048, 2048, "attn_out", False),
+              ("gate_proj", 6144, 2048, "mlp_in", False), ("up_proj", 6144, 2048, "mlp_in", False),
+              ("down_proj", 2048, 6144, "mlp_mid", True)]
+QWEN_LAYERS = 28
+
+
+def run_block_chained(args) -> dict:
+    """All seven linears of one Qwen3-1.7B-shaped block stepped back to back at T = 16384, each with an
+    upstream gradient supplied (dY_ext) and its input gradient requested (dX): three GEMMs per linear and step.
+    One timed "step" is one step of every linear; `value` counts linear-layer steps."""
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+    from workloads import synth
+
+    T = 16384
+    steps = min(args.steps, 50)
+    warmup = min(args.warmup, 5)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    X_by_group, lin = {}, []
+    for idx, (name, O, K, group, gated) in enumerate(QWEN_BLOCK):
+        if group not in X_by_group:
+            X_h = synth.silu_gated_activations(T, K, seed=idx) if gated else synth.activations(T, K, seed=idx)
+            X_by_group[group] = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
+        Xq = X_by_group[group]
+        W = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
+        Y = Xq @ W.T                                                     # input generation only
+        dY = (torch.randn((T, O), generator=gen, device="cuda") * 1e-3).to(torch.bfloat16)
+        sg, scales, _, _ = faar.faar_quant_rtn(W)
+        V, _ = faar.faar_init_v(W, sg, scales)
+        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y)
+        del Y
+        lin.append(dict(name=name, O=O, K=K, W=W, sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V),
+                        Xq=Xq, Xt=Xt, C=C, ic=ic, dY=dY, dX=torch.empty((T, K), dtype=torch.bfloat16, device="cuda"),
+                        ws=faar.layer_step_workspace(O, K, T, chained=True),
+                        losses=torch.zeros(3, dtype=torch.float32, device="cuda"), ready=False))
+    lam, lr = 0.01, 5e-4
+
+    def step_linear(L, t, beta=16.0, fused=True):
+        faar.faar_layer_step(L["W"], L["sg"], L["scales"], L["V"], L["m"], L["u"], L["Xq"], L["Xt"], L["C"], L["ic"], beta,
+                             lam, 1.0 / (T * L["O"]), lr, 0.9, 0.999, 1e-8, t, L["losses"], L["ws"], dY_ext=L["dY"],
+                             dX=L["dX"], beta_next=beta if fused else 0.0, forward_ready=fused and L["ready"])
+        L["ready"] = fused
+
+    t = 0
+    for _ in range(warmup):
+        t += 1
+        for L in lin:
+            step_linear(L, t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        t += 1
+        for L in lin:
+            step_linear(L, t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    per_linear = {}
+    total_flops = 0.0
+    for L in lin:
+        O, K = L["O"], L["K"]
+        flops = 2.0 * T * O * K
+        total_flops += 3 * flops
+        row = {}
+        for kname, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("gemm_dx", fb.K_GEMM_DX),
+                           ("bwd_adam", fb.K_BWD_ADAM)]:
+            ts = []
+            fb.faar_time_kernel(kid, e0.value, e1.value)
+            try:
+                for _ in range(6):
+                    t += 1
+                    step_linear(L, t)
+                    ts.append(ev.elapsed_ms(e0, e1))
+            finally:
+                fb.faar_time_kernel(fb.K_NONE)
+            ms = sum(ts[2:]) / len(ts[2:])
+            if kname.startswith("gemm"):
+                row[kname] = {"ms": round(ms, 5), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                              "frac": round(flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)}
+            else:
+                b = bytes_per_weight(fb.faar_dw_split(O, K, T))["bwd_adam"] + 2      # + W_q for the next dX
+                row[kname] = {"ms": round(ms, 5), "gbs": round(b * O * K / (ms * 1e-3) / 1e9, 1),
+                              "frac": round(b * O * K / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        row["dw_split"] = fb.faar_dw_split(O, K, T)
+        per_linear[L["name"]] = row
+    dom_l, dom_k = max(((l, k) for l in per_linear for k in ("gemm_residual", "gemm_dw", "gemm_dx")),
+                       key=lambda lk: per_linear[lk[0]][lk[1]]["ms"])
+    dom = per_linear[dom_l][dom_k]
+    n_lin = len(lin)
+    return {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(n_lin * steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qwen_block_chained: the 7 linears of one Qwen3-1.7B-shaped block (q/o 2048x2048, k/v "
+                               "1024x2048, gate/up 6144x2048, down 2048x6144), T 16384, each stepped once per timed step "
+                               "with dY supplied and dX produced (3 GEMMs per linear); value = linear-layer steps/s",
+                   "T": T, "linears": n_lin},
+        "block_step_gemm_tflops": round(total_flops / (elapsed / steps) / 1e12, 1),
+        "roofline": {"kernel": f"{dom_l}.{dom_k}", "bound": "mfma", "achieved": dom["tflops"], "peak": BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "launch_ms": dom["ms"]},
+        "per_linear": per_linear,
+    }
+
+
+def run_pack_sweep(args) -> dict:
+    """Set-up and tear-down kernels over every linear of a Qwen3-1.7B-shaped model (28 layers x 7 linears,
+    1.409 G weights, each tensor in memory of its own): faar_quant_rtn, faar_init_v and faar_harden_pack,
+    each timed as a sweep over all 196 tensors.  `value` is the harden+pack rate."""
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+    from workloads import synth
+
+    base = {}
+    for idx, (name, O, K, _, _) in enumerate(QWEN_BLOCK):
+        if (O, K) not in base:                       # one seeded draw per shape, copied into every layer's own tensor
+            base[(O, K)] = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(7)
+    tensors = []
+    n_total = 0
+    for layer in range(QWEN_LAYERS):
+        for name, O, K, _, _ in QWEN_BLOCK:
+            W = base[(O, K)].clone()
+            V = torch.rand((O, K), generator=gen, device="cuda", dtype=torch.float32)   # rounding variables mid-optimisation
+            tensors.append([W, V, None, None])
+            n_total += O * K
+    ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, 6144, 2048), dtype=torch.uint8, device="cuda")
+    reps = 5
+
+    def sweep(fn):
+        torch.cuda.synchronize()
+        best = None
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            for rec in tensors:
+                fn(rec)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        return best
+
+    def do_quant(rec):
+        rec[2], rec[3], _, _ = faar.faar_quant_rtn(rec[0], ws=ws_q)
+
+    t_quant = sweep(do_quant)
+    t_init = sweep(lambda rec: faar.faar_init_v(rec[0], rec[2], rec[3]))
+    t_pack = sweep(lambda rec: faar.faar_harden_pack(rec[0], rec[2], rec[3], rec[1]))
+    bpw = bytes_per_weight(1)
+    rows = {}
+    for name, tt, b in (("quant_rtn", t_quant, bpw["quant_rtn"] + 2), ("init_v", t_init, bpw["init_v"]),
+                        ("harden_pack", t_pack, bpw["harden_pack"])):
+        rows[name] = {"ms": round(tt * 1e3, 3), "gbs": round(b * n_total / tt / 1e9, 1),
+                      "frac": round(b * n_total / tt / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_weight": b}
+    return {
+        "metric": "NVFP4 harden+pack weight elements/sec", "value": round(n_total / t_pack, 1), "unit": "elems/s",
+        "n_gpus": 1, "steps": reps, "warmup": 0, "ms_per_step": rows["harden_pack"]["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"qwen_pack_sweep: {len(tensors)} weight tensors of a Qwen3-1.7B-shaped model "
+                               f"({n_total / 1e9:.3f} G weights, bf16 W + float32 V in, NVFP4 codes out); best of {reps} sweeps; "
+                               "times include the allocation of each output by the binding",
+                   "weights": n_total},
+        "roofline": {"kernel": "harden_pack", "bound": "hbm", "achieved": rows["harden_pack"]["gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": rows["harden_pack"]["frac"], "traffic": None},
+        "sweeps": rows,
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=20)
@@ -105,6 +281,12 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.workload == "qwen_block_chained":
+        print(json.dumps(run_block_chained(args)))
+        return 0
+    if args.workload == "qwen_pack_sweep":
+        print(json.dumps(run_pack_sweep(args)))
+        return 0
     O, K, T, gated = WORKLOADS[args.workload]
     W_h = synth.student_t_weight(O, K, seed=0)
     X_h = synth.silu_gated_activations(T, K, seed=0) if gated else synth.activations(T, K, seed=0)

@@ -495,10 +495,16 @@ inline Plan make_plan(int kind, const GemmDims& d, int n_split) {
   return Plan{kind, ceil_div(d.M, bm), ceil_div(d.N, bn), n_split};
 }
 
-// Tile shape and contraction split.  Large tiles cut LDS and L2 traffic per flop but need enough work
-// items to occupy 256 compute units; splitting the contraction (allowed only where partial sums may be
-// written separately) restores occupancy for small outputs with a long contraction.
-Plan plan_gemm(const GemmDims& d, bool may_split) {
+// Tile shape and contraction split, chosen by a small cost model (all times in microseconds, calibrated on
+// MI355X with every compute unit busy).  A compute unit works through one BK-slice of a tile in c_kind;
+// an item's epilogue costs a fixed part plus its global traffic (reads count fully, writes half: they do not
+// stall the wave) at one compute unit's share of the memory bandwidth.  Items are dealt in rounds of 256.
+// Large tiles cut LDS and L2 traffic per flop but quantise badly on small outputs; splitting the contraction
+// (allowed only where partial sums may be written separately) buys back occupancy at the price of one more
+// float32 partial per split, which the consumer has to read.
+struct EpiCost { float read_bytes, write_bytes; };  // per output element
+
+Plan plan_gemm(const GemmDims& d, bool may_split, EpiCost epi) {
   if (d.Kd % DBK != 0) {
     Plan p = make_plan(KIND_GENERIC, d, 1);
     if (may_split)
@@ -506,22 +512,33 @@ Plan plan_gemm(const GemmDims& d, bool may_split) {
     return p;
   }
   const int kinds[3] = {KIND_L, KIND_M, KIND_S};
-  const int64_t want[3] = {384, 192, 0};  // without splitting: L from 1.5 waves of tiles, M from 0.75
-  if (!may_split) {
-    for (int i = 0; i < 3; ++i) {
-      Plan p = make_plan(kinds[i], d, 1);
-      if (p.items() >= want[i]) return p;
-    }
-  }
-  Plan best = make_plan(KIND_S, d, 1);
+  const double slice_us[3] = {0.985, 0.63, 0.36};
+  const double tile_outputs[3] = {256.0 * 256.0, 256.0 * 128.0, 128.0 * 128.0};
+  const double cu_bytes_per_us = 17600.0;   // ~4.5 TB/s over 256 compute units
+  const double slices = static_cast<double>(d.Kd / DBK);
+  Plan best{};
+  double best_cost = 0.0;
   for (int i = 0; i < 3; ++i) {
-    Plan p = make_plan(kinds[i], d, 1);
-    while (p.items() < 200 && d.Kd / (p.n_split * 2) >= 512 && p.n_split < 8) p.n_split *= 2;
-    if (p.items() >= 200) return p;
-    best = p;
+    for (int sp = 1; sp <= (may_split ? 8 : 1); ++sp) {
+      if (sp > 1 && d.Kd / sp < 512) break;
+      const int64_t ksteps = d.Kd / DBK, per = (ksteps + sp - 1) / sp;
+      if ((sp - 1) * per >= ksteps) continue;  // the last split would be empty
+      const Plan p = make_plan(kinds[i], d, sp);
+      const double rounds = static_cast<double>((p.items() + 255) / 256);
+      const double epilogue = 3.0 + tile_outputs[i] * (epi.read_bytes + 0.5 * epi.write_bytes) / cu_bytes_per_us;
+      double cost = rounds * (std::ceil(slices / sp) * slice_us[i] + epilogue);
+      // every extra split is one more float32 partial written here and read back by the consumer
+      cost += (sp - 1) * static_cast<double>(d.M) * static_cast<double>(d.N) * 8.0 / 5.0e6;
+      if (best.kind == 0 || cost < best_cost) {
+        best = p;
+        best_cost = cost;
+      }
+    }
   }
   return best;
 }
+
+constexpr EpiCost kEpiResidual{4.0f, 2.0f}, kEpiF32{0.0f, 4.0f}, kEpiSub{4.0f, 4.0f}, kEpiBf16{0.0f, 2.0f};
 
 template <class Epi>
 hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hipStream_t st) {
@@ -546,31 +563,31 @@ hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hi
 }  // namespace
 
 int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {
-  return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, false).items();
+  return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, false, kEpiResidual).items();
 }
 
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, hipStream_t st) {
   EpiResidual e{C, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
-  const Plan p = plan_gemm(d, false);
+  const Plan p = plan_gemm(d, false, kEpiResidual);
   *n_partials = p.items();
   return run(A, B, d, p, e, st);
 }
 
-int choose_split(int64_t M, int64_t N, int64_t Kd) { return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, true).n_split; }
+int choose_split(int64_t M, int64_t N, int64_t Kd) { return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, true, kEpiF32).n_split; }
 
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st) {
   EpiF32 e{out};
-  Plan p = plan_gemm(d, true);
+  Plan p = plan_gemm(d, true, kEpiF32);
   if (p.n_split != n_split) return hipErrorInvalidValue;  // the caller sized its workspace with choose_split
   return run(A, B, d, p, e, st);
 }
 
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
                            bool first, float* C_out, hipStream_t st) {
-  const Plan p = plan_gemm(d, false);
+  const Plan p = plan_gemm(d, false, kEpiSub);
   if (y_bf16) {
     EpiSub<true> e{Y, first, C_out};
     return run(A, B, d, p, e, st);
@@ -581,7 +598,7 @@ hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const v
 
 hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, hipStream_t st) {
   EpiBf16 e{out};
-  return run(A, B, d, plan_gemm(d, false), e, st);
+  return run(A, B, d, plan_gemm(d, false, kEpiBf16), e, st);
 }
 
 }  // namespace faar
