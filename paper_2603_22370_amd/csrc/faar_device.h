@@ -92,7 +92,7 @@ struct Interval {
 // nodes are exactly the floats with one significand bit, so exponent and leading significand bit index them:
 // (bits >> 22) is 254 at 1.0, 255 at 1.5, 256 at 2.0 ... ; 252 and 253 cover [0.5, 1).
 __device__ __forceinline__ int interval_index(float wt) {
-  const int d = static_cast<int>(__float_as_uint(wt) >> 22) - 252;
+  const int d = (static_cast<int>(__float_as_uint(wt)) >> 22) - 252;  // arithmetic shift: a negative input gives 0
   return d < 0 ? 0 : min(max(d, 1), 6);
 }
 // N[k] for k in 0..6
@@ -108,6 +108,30 @@ __device__ __forceinline__ float interval_mid(int k) {
 }
 // w~ = |w| / s, one correctly rounded division; 0 when the block scale is 0
 __device__ __forceinline__ float normalised(float w, float s) { return (s == 0.0f) ? 0.0f : fabsf(w) / s; }
+
+// |w| / s for several weights of one block, for kernels that need w~ only to DECIDE (interval index,
+// round-to-nearest direction).  With y = 1/s correctly rounded (hardware estimate plus one Newton step; checked
+// against the IEEE quotient for every float32 significand), q0 = a*y, r = fma(-q0, s, a) is the exact remainder
+// and fma(r, y, q0) is the correctly rounded quotient a/s (Markstein's theorem) as long as nothing underflows:
+// guaranteed here for quotients >= 2^-40 because s is kept within [2^-60, 2^60] and the numerators below 2^60.
+// A quotient below 2^-40 may come out inexact but stays far below the first threshold (0.25), so every decision
+// is still that of the IEEE division.  Outside those ranges the plain division is used.
+struct BlockDivider {
+  float s, y;
+  bool fast;
+  __device__ __forceinline__ BlockDivider(float s_, float amax) : s(s_) {
+    fast = (s_ >= 0x1p-60f) && (s_ <= 0x1p60f) && (amax <= 0x1p60f);
+    const float y0 = __builtin_amdgcn_rcpf(s_);
+    y = __builtin_fmaf(__builtin_fmaf(-s_, y0, 1.0f), y0, y0);
+  }
+  template <bool kFast> __device__ __forceinline__ float quotient(float a) const {
+    if (kFast) {
+      const float q0 = a * y;
+      return __builtin_fmaf(__builtin_fmaf(-q0, s, a), y, q0);
+    }
+    return (s == 0.0f) ? 0.0f : a / s;
+  }
+};
 
 // Table 2 steps 2-4 for one weight: w~ = |w| / s (0 when s == 0), interval, relative position.
 // (w~ - lo) / width is evaluated as a product with 1 / width: the widths are powers of two, so both are

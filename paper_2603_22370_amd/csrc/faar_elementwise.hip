@@ -2,6 +2,8 @@
 // Eq. 2-5, 7).  Every kernel uses the same mapping: one thread owns 8 consecutive weights (16 B
 // of bf16, 32 B of float32), so a 16-weight scale block is an even/odd lane pair and its amax is
 // one cross-lane exchange.  Loads and stores are 16 B per lane and fully coalesced.
+#include <type_traits>
+
 #include "faar_internal.h"
 
 namespace faar {
@@ -94,14 +96,18 @@ k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_gl
   const float s = sgv * sg;
   uint32_t packed = 0;
   float dq[8];
+  const BlockDivider div(s, a);
+  auto encode = [&](auto fast) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float wt = normalised(w[j], s);
-    const int k_lo = interval_index(wt);
-    const uint32_t nib = nibble(w[j], k_lo, wt >= interval_mid(k_lo));
-    packed |= nib << (4 * j);
-    if (kDequant) dq[j] = dequant(nib, sgv, sg);
-  }
+    for (int j = 0; j < 8; ++j) {
+      const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
+      const int k_lo = interval_index(wt);
+      const uint32_t nib = nibble(w[j], k_lo, wt >= interval_mid(k_lo));
+      packed |= nib << (4 * j);
+      if (kDequant) dq[j] = dequant(nib, sgv, sg);
+    }
+  };
+  if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
   codes[i] = packed;
   if ((i & 1) == 0) scales[i >> 1] = static_cast<uint8_t>(byte);
   if (kDequant) W8<WT>::store(W_dq + i * 8, dq);
@@ -145,17 +151,24 @@ k_harden_pack(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_
     W8<WT>::load(W + i * 8, w);
     load8(V + i * 8, v);
     uint32_t packed = 0, bits = 0;
+    float amax = 0.0f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float wt = normalised(w[j], s);
-      const int k_lo = interval_index(wt);
-      const int up = v[j] >= 0.5f;
-      const uint32_t nib = nibble(w[j], k_lo, up);
-      flips += (w[j] != 0.0f) & (up != (wt >= interval_mid(k_lo)));  // differs from round-to-nearest
-      packed |= nib << (4 * j);
-      bits |= static_cast<uint32_t>(up) << j;
-      dq[j] = dequant(nib, sgv, sg);
-    }
+    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(w[j]));
+    const BlockDivider div(s, amax);
+    auto encode = [&](auto fast) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
+        const int k_lo = interval_index(wt);
+        const int up = v[j] >= 0.5f;
+        const uint32_t nib = nibble(w[j], k_lo, up);
+        flips += (w[j] != 0.0f) & (up != (wt >= interval_mid(k_lo)));  // differs from round-to-nearest
+        packed |= nib << (4 * j);
+        bits |= static_cast<uint32_t>(up) << j;
+        dq[j] = dequant(nib, sgv, sg);
+      }
+    };
+    if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
     codes[i] = packed;
     if (decisions) decisions[i] = static_cast<uint8_t>(bits);
     if (W_final) W8<WT>::store(W_final + i * 8, dq);
@@ -294,11 +307,19 @@ k_interval_codes(const WT* __restrict__ W, int64_t n8, const float* __restrict__
   float w[8];
   W8<WT>::load(W + i * 8, w);
   uint32_t packed = 0;
+  float amax = 0.0f;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint32_t k = (w[j] == 0.0f) ? 7u : static_cast<uint32_t>(find_interval(w[j], s).k_lo);
-    packed |= (((__float_as_uint(w[j]) >> 31) << 3) | k) << (4 * j);
-  }
+  for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(w[j]));
+  const BlockDivider div(s, amax);
+  auto encode = [&](auto fast) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
+      const uint32_t k = (w[j] == 0.0f) ? 7u : static_cast<uint32_t>(interval_index(wt));
+      packed |= (((__float_as_uint(w[j]) >> 31) << 3) | k) << (4 * j);
+    }
+  };
+  if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
   icodes[i] = packed;
 }
 

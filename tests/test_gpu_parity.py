@@ -35,6 +35,22 @@ WCASES = list(weight_cases())
 WIDS = [c[0] for c in WCASES]
 
 
+def extreme_weight_cases():
+    """Magnitudes far outside anything a network holds: the kernels switch division routines on the size of the
+    block scale and of the weights, and every route must give the decisions of the IEEE quotient."""
+    base = synth.student_t_weight(8, 64, 6)
+    yield "tiny_bf16", (base * np.float32(2.0 ** -80)).astype(np.float32), True          # scales below 2^-60
+    yield "huge_fp32", (synth.config1(1).W[:8, :64] * np.float32(2.0 ** 90)).astype(np.float32), False
+    rows = (2.0 ** (-12.0 * np.arange(8))).astype(np.float32)[:, None]                   # block scales that underflow
+    yield "mixed_range_bf16", (base * rows).astype(np.float32), True
+    w = base.copy()
+    w[3, 5] = np.float32(2.0 ** 70)                                                      # one weight above 2^60
+    yield "one_giant_bf16", w, True
+
+
+XCASES = list(extreme_weight_cases())
+
+
 @pytest.mark.parametrize("name,W,isbf", WCASES, ids=WIDS)
 def test_quant_rtn_bit_exact(name, W, isbf):
     q = fo.quant_rtn(W, isbf)
@@ -76,6 +92,20 @@ def test_init_v_and_harden_pack_bit_exact(name, W, isbf):
         Vc = np.full(W.shape, const, dtype=np.float32)
         c4, _, _, _ = faar.faar_harden_pack(Wd, sg, scales, dev(Vc))
         assert np.array_equal(host(c4), fo.harden_pack(W, isbf, q["s_global"], q["scales"], Vc)["codes"])
+
+
+@pytest.mark.parametrize("name,W,isbf", XCASES, ids=[c[0] for c in XCASES])
+def test_codec_bit_exact_on_extreme_magnitudes(name, W, isbf):
+    test_quant_rtn_bit_exact(name, W, isbf)
+    test_init_v_and_harden_pack_bit_exact(name, W, isbf)
+    q = fo.quant_rtn(W, isbf)
+    Wd = dev(W, isbf)
+    sg, scales, _, _ = faar.faar_quant_rtn(Wd)
+    X = np.ones((4, W.shape[1]), dtype=np.float32)
+    _, _, ic = faar.faar_layer_prepare(Wd, sg, scales, dev(X, True), dev(np.zeros((4, W.shape[0]), dtype=np.float32)))
+    wt = fo.normalised_magnitude(W, q["scales"], q["s_global"])
+    want_ic = (np.signbit(W).astype(np.uint8) << 3) | np.where(W == 0, 7, fo.find_interval(wt)).astype(np.uint8)
+    assert np.array_equal(host(ic), fo.pack_nibbles(want_ic))
 
 
 @pytest.mark.parametrize("name,W,isbf", WCASES, ids=WIDS)
