@@ -491,20 +491,47 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
 }
 
 // ---- bf16 transpose with zero padding (X_q^T for the dW GEMM) -------------------------------
+// 64 x 64 tiles through LDS; 16-byte global accesses on both sides (rows of the tile are 128 contiguous bytes).
+// The LDS row pitch of 33 words makes the transposed 2-byte reads of a wavefront hit 32 distinct banks.
 __global__ void __launch_bounds__(256)
 k_transpose_bf16(const bf16_t* __restrict__ in, int64_t rows, int64_t cols, bf16_t* __restrict__ out,
                  int64_t ld_out) {
-  __shared__ bf16_t tile[64][66];
+  __shared__ uint32_t tile[64][33];
   const int64_t r0 = blockIdx.y * 64LL, c0 = blockIdx.x * 64LL;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int r = ty; r < 64; r += 4) {
-    const int64_t rr = r0 + r, cc = c0 + tx;
-    tile[r][tx] = (rr < rows && cc < cols) ? in[rr * cols + cc] : bf16_t(0);
+  const int sub = threadIdx.x >> 3, ch = threadIdx.x & 7;
+  const bool vec_in = (cols % 8) == 0;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int r = p * 32 + sub;
+    const int64_t rr = r0 + r, cc = c0 + ch * 8;
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (rr < rows) {
+      if (vec_in && cc + 8 <= cols) {
+        v = *reinterpret_cast<const uint4*>(in + rr * cols + cc);
+      } else {
+        uint32_t e[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e[j] = (cc + j < cols) ? in[rr * cols + cc + j] : 0u;
+        v = make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+      }
+    }
+    tile[r][ch * 4 + 0] = v.x;
+    tile[r][ch * 4 + 1] = v.y;
+    tile[r][ch * 4 + 2] = v.z;
+    tile[r][ch * 4 + 3] = v.w;
   }
   __syncthreads();
-  for (int c = ty; c < 64; c += 4) {
-    const int64_t cc = c0 + c, rr = r0 + tx;
-    if (cc < cols && rr < ld_out) out[cc * ld_out + rr] = tile[tx][c];
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int oc = p * 32 + sub;                       // output row within the tile = input column
+    const int64_t cc = c0 + oc, rr = r0 + ch * 8;      // eight consecutive input rows -> 16 contiguous output bytes
+    if (cc < cols && rr < ld_out) {                    // ld_out is a multiple of 64: a chunk is inside or outside as a whole
+      uint32_t e[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) e[j] = (tile[ch * 8 + j][oc >> 1] >> ((oc & 1) * 16)) & 0xFFFFu;
+      *reinterpret_cast<uint4*>(out + cc * ld_out + rr) =
+          make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
+    }
   }
 }
 
@@ -694,6 +721,7 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
 
 hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
                                  int64_t ld_out, hipStream_t st) {
+  if (ld_out % 64 != 0) return hipErrorInvalidValue;  // the kernel stores whole 8-element chunks
   // the grid covers rows up to ld_out so that the zero padding is written too
   const dim3 g(static_cast<unsigned>((cols + 63) / 64), static_cast<unsigned>((ld_out + 63) / 64));
   hipLaunchKernelGGL(k_transpose_bf16, g, dim3(256), 0, st, in, rows, cols, out, ld_out);
