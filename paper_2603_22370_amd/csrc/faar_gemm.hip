@@ -25,6 +25,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BK = 64;            // contraction slice per stage
 constexpr int LDS_LD = BK + 8;    // padded LDS row, elements (144 B)
@@ -475,14 +476,210 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
   epi.finish(item);
 }
 
+// ---- fast path for contractions that are a multiple of 64: 128-byte LDS rows, two stages, 16x16x32 MFMAs ----
+//
+// The chip runs this loop power-limited, and two things lower the energy per flop: global->LDS copies whose
+// eight lanes per row make one 128-byte request (BK = 64) instead of two 64-byte ones, and the 16x16x32 MFMA,
+// which reads and writes a quarter of the accumulator values per instruction of the 32x32x16 form for half
+// its flops.  With BK = 64 only two stages fit next to a 256x256 tile (2 x 64 KB), so a stage is refilled as
+// soon as the workgroup has read it: ONE barrier per slice, placed before the slice's last MFMA phase, at
+// which point every wavefront holds the last fragments of the slice in registers and the copies of the next
+// slice (issued one slice earlier, right after the previous barrier) have landed.
+
+constexpr int DBK64 = 64;
+
+template <int BM_, int BN_, int WGM_, int WGN_>
+struct Dma64Cfg {
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+  static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
+  static constexpr int WM = BM / WGM, WN = BN / WGN;
+  static constexpr int TM = WM / 16, TN = WN / 16;
+  static constexpr int CPR = DBK64 / 8;            // 16-byte chunks per LDS row (8)
+  static constexpr int RPI = 64 / CPR;             // rows written by one wave-wide DMA instruction (8)
+  static constexpr int RB = 2;                     // rows per 256-byte bank cycle
+  static constexpr int STAGE = (BM + BN) * DBK64;  // elements per stage
+  static constexpr int P = (BM + BN) / RPI / NW;   // DMA instructions per wavefront per stage
+  static constexpr int KK = DBK64 / 32;            // MFMA phases per stage (2)
+  static constexpr int NF = TM + TN, NM = TM * TN;
+  static constexpr int FSTEP = NM / NF >= 2 ? 2 : 1;  // one fragment prefetch every FSTEP MFMAs
+  static constexpr int DSTEP = NM / P;                // one DMA issue every DSTEP MFMAs of the last phase
+  static_assert(NF * FSTEP <= NM && P * DSTEP <= NM && DSTEP >= 1, "phase schedule");
+  static_assert((BM + BN) % (RPI * NW) == 0 && TN % 2 == 0, "tile shape");
+};
+
+template <class C, class Epi>
+__global__ void __launch_bounds__(C::THREADS)
+k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
+             int ksteps_per_split, Epi epi) {
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[2 * C::STAGE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
+  int tm, tn, split, item;
+  if (!item_coords(blockIdx.x, tiles_m, tiles_n, n_split, tm, tn, split, item)) return;
+  const int64_t m0 = (int64_t)tm * C::BM, n0 = (int64_t)tn * C::BN;
+  const int ksteps = static_cast<int>(d.Kd / DBK64);
+  const int kbeg = split * ksteps_per_split;
+  const int kend = kbeg + ksteps_per_split < ksteps ? kbeg + ksteps_per_split : ksteps;
+  const int nk = kend - kbeg;
+  constexpr int P = C::P, KK = C::KK, NF = C::NF, NM = C::NM, TM = C::TM, TN = C::TN;
+
+  f32x4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+
+  if (nk > 0) {
+    // DMA instruction q of this wavefront fills rows [(wave*P + q)*RPI, +RPI) of the stacked [A rows; B rows]
+    // stage: lane -> row = base + lane / CPR, LDS slot = lane % CPR, global chunk = slot ^ ((row / RB) % CPR).
+    // Rows beyond M (or N) are clamped to the last valid row: their products are never stored.
+    const bf16_t* gsrc[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+      const int trow = (wave * P + q) * C::RPI + lane / C::CPR;
+      const int chunk = (lane % C::CPR) ^ ((trow / C::RB) % C::CPR);
+      if (trow < C::BM) {
+        const int64_t m = m0 + trow < d.M ? m0 + trow : d.M - 1;
+        gsrc[q] = A + m * d.lda + chunk * 8;
+      } else {
+        const int64_t n = n0 + (trow - C::BM) < d.N ? n0 + (trow - C::BM) : d.N - 1;
+        gsrc[q] = B + n * d.ldb + chunk * 8;
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int t = kbeg + (s < nk ? s : nk - 1);
+#pragma unroll
+      for (int q = 0; q < P; ++q)
+        dma16(gsrc[q] + (int64_t)t * DBK64,
+              __builtin_amdgcn_readfirstlane(lds_addr_of(lds + s * C::STAGE + (wave * P + q) * C::RPI * DBK64)));
+    }
+
+    // fragment addresses: row = w? + i*16 + lane % 16, chunk = 4*kk + lane / 16, slot = chunk ^ ((row / RB) % CPR);
+    // the 16 lanes that share a chunk index then cover 16 distinct 16-byte bank groups
+    const int fr = lane & 15, kc = lane >> 4;
+    const int sw = (fr / C::RB) % C::CPR;
+    int a_off[KK], b_off[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int slot = ((4 * kk + kc) ^ sw) * 8;
+      a_off[kk] = (wm + fr) * DBK64 + slot;
+      b_off[kk] = C::BM * DBK64 + (wn + fr) * DBK64 + slot;
+    }
+    bf16x8 fa[2][TM], fb[2][TN];
+
+    FAAR_WAIT_VMCNT(P);  // slice 0 has landed (mine); barrier: everybody's
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      fa[0][i] = *reinterpret_cast<const bf16x8*>(lds + a_off[0] + i * 16 * DBK64);
+      fa[1][i] = fa[0][i];
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      fb[0][j] = *reinterpret_cast<const bf16x8*>(lds + b_off[0] + j * 16 * DBK64);
+      fb[1][j] = fb[0][j];
+    }
+
+    for (int it = 0; it < nk; ++it) {
+      bf16_t* st = lds + (it & 1) * C::STAGE;
+      const bf16_t* sn = lds + ((it + 1) & 1) * C::STAGE;
+      const bool more = it + 2 < nk;
+      const int64_t goff = (int64_t)(kbeg + it + 2) * DBK64;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const int cur = kk & 1;
+        if (kk == KK - 1) {
+          // this wavefront's copies of slice it+1 have landed and its reads of slice it are complete;
+          // after the barrier that holds for the workgroup: stage `st` may be refilled, `sn` may be read
+          __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+          __builtin_amdgcn_s_barrier();
+        }
+        const bf16_t* src = (kk + 1 < KK) ? st : sn;
+        const int nkk = (kk + 1 < KK) ? kk + 1 : 0;
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+          const int mi = m / TN, mj = m % TN;
+          acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
+          if (m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
+            const int f = m / C::FSTEP;
+            if (f == 0) fa[cur ^ 1][0] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk]);
+            else if (f <= TN) fb[cur ^ 1][f - 1] = *reinterpret_cast<const bf16x8*>(src + b_off[nkk] + (f - 1) * 16 * DBK64);
+            else fa[cur ^ 1][f - TN] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk] + (f - TN) * 16 * DBK64);
+          }
+          if (kk == KK - 1 && m % C::DSTEP == 0 && m / C::DSTEP < P) {
+            // slice it+2 into the stage just released; past the end every lane re-reads one valid address
+            const int q = m / C::DSTEP;
+            const bf16_t* g = more ? gsrc[q] + goff : A;
+            dma16(g, __builtin_amdgcn_readfirstlane(lds_addr_of(st + (wave * P + q) * C::RPI * DBK64)));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    FAAR_WAIT_VMCNT(0);  // no copy may still be in flight into this workgroup's LDS when it retires
+  }
+
+  // accumulator layout of the 16x16 tile: lane -> column lane % 16, rows 4 * (lane / 16) + 0..3
+  const int col = lane & 15, rq = lane >> 4;
+  if constexpr (Epi::kTransposedOut) {
+    // as in k_gemm_dma: stage a 32-column slab (two 16-column tiles) per wavefront column through LDS and
+    // write whole rows of the transposed output with 16 B per lane
+    constexpr int LDT = C::BM + 8;
+    constexpr int ROWS = C::WGN * 32;
+    constexpr int CPRW = C::BM / 8;
+    static_assert(ROWS * LDT <= 2 * C::STAGE, "staging buffer fits in the ring");
+    bf16_t* stg = lds;
+    const int wc = wave % C::WGN;
+#pragma unroll
+    for (int jj = 0; jj < TN / 2; ++jj) {
+      __syncthreads();
+      float4 cv[TM][2];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+          cv[i][h] = epi.load4(m0 + wm + i * 16 + 4 * rq, n0 + wn + (2 * jj + h) * 16 + col, d);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int ml = wm + i * 16 + 4 * rq;
+          const float r[4] = {acc[i][2 * jj + h][0], acc[i][2 * jj + h][1], acc[i][2 * jj + h][2], acc[i][2 * jj + h][3]};
+          *reinterpret_cast<uint2*>(stg + (wc * 32 + h * 16 + col) * LDT + ml) =
+              epi.value4(r, cv[i][h], m0 + ml, n0 + wn + (2 * jj + h) * 16 + col, d);
+        }
+      __syncthreads();
+      for (int idx = tid; idx < ROWS * CPRW; idx += C::THREADS) {
+        const int row = idx / CPRW, ch = idx % CPRW;
+        const uint4 v = *reinterpret_cast<const uint4*>(stg + row * LDT + ch * 8);
+        epi.store_chunk(v, m0 + ch * 8, n0 + (row / 32) * C::WN + jj * 32 + (row % 32), d);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const float r[4] = {acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+        epi.rows4(r, m0 + wm + i * 16 + 4 * rq, n0 + wn + j * 16 + col, split, d);
+      }
+  }
+  epi.finish(item);
+}
+
 typedef Tile<128, 128> T128;
 typedef DmaCfg<256, 256, 2, 4> CfgL;  // large problems
 typedef DmaCfg<256, 128, 4, 2> CfgM;  // one tile per compute unit at ~256 tiles
 typedef DmaCfg<128, 128, 2, 2> CfgS;  // small outputs, two workgroups per compute unit
+typedef Dma64Cfg<256, 256, 2, 4> CfgL64;
+typedef Dma64Cfg<256, 128, 4, 2> CfgM64;
 
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
-enum { KIND_GENERIC = 0, KIND_L = 1, KIND_M = 2, KIND_S = 3 };
+enum { KIND_GENERIC = 0, KIND_L = 1, KIND_M = 2, KIND_S = 3, KIND_L64 = 4, KIND_M64 = 5 };
 
 struct Plan {
   int kind, tiles_m, tiles_n, n_split;
@@ -490,8 +687,8 @@ struct Plan {
 };
 
 inline Plan make_plan(int kind, const GemmDims& d, int n_split) {
-  const int bm = kind == KIND_L || kind == KIND_M ? 256 : 128;
-  const int bn = kind == KIND_L ? 256 : 128;
+  const int bm = kind == KIND_S || kind == KIND_GENERIC ? 128 : 256;
+  const int bn = kind == KIND_L || kind == KIND_L64 ? 256 : 128;
   return Plan{kind, ceil_div(d.M, bm), ceil_div(d.N, bn), n_split};
 }
 
@@ -511,22 +708,23 @@ Plan plan_gemm(const GemmDims& d, bool may_split, EpiCost epi) {
       while (p.items() < 256 && d.Kd / (p.n_split * 2) >= 512 && p.n_split < 16) p.n_split *= 2;
     return p;
   }
-  const int kinds[3] = {KIND_L, KIND_M, KIND_S};
-  const double slice_us[3] = {0.985, 0.63, 0.36};
+  // contractions that are a multiple of 64 take the 128-byte-row kernels for the two large shapes
+  const bool k64 = d.Kd % DBK64 == 0;
+  const int kinds[3] = {k64 ? KIND_L64 : KIND_L, k64 ? KIND_M64 : KIND_M, KIND_S};
+  const double slice_us[3] = {k64 ? 0.833 : 0.985, k64 ? 0.552 : 0.63, 0.36};  // per 32 of the contraction
   const double tile_outputs[3] = {256.0 * 256.0, 256.0 * 128.0, 128.0 * 128.0};
   const double cu_bytes_per_us = 17600.0;   // ~4.5 TB/s over 256 compute units
-  const double slices = static_cast<double>(d.Kd / DBK);
   Plan best{};
   double best_cost = 0.0;
   for (int i = 0; i < 3; ++i) {
     for (int sp = 1; sp <= (may_split ? 8 : 1); ++sp) {
       if (sp > 1 && d.Kd / sp < 512) break;
-      const int64_t ksteps = d.Kd / DBK, per = (ksteps + sp - 1) / sp;
+      const int64_t ksteps = d.Kd / (i < 2 && k64 ? DBK64 : DBK), per = (ksteps + sp - 1) / sp;
       if ((sp - 1) * per >= ksteps) continue;  // the last split would be empty
       const Plan p = make_plan(kinds[i], d, sp);
       const double rounds = static_cast<double>((p.items() + 255) / 256);
       const double epilogue = 3.0 + tile_outputs[i] * (epi.read_bytes + 0.5 * epi.write_bytes) / cu_bytes_per_us;
-      double cost = rounds * (std::ceil(slices / sp) * slice_us[i] + epilogue);
+      double cost = rounds * (static_cast<double>(per) * (i < 2 && k64 ? 2.0 : 1.0) * slice_us[i] + epilogue);
       // every extra split is one more float32 partial written here and read back by the consumer
       cost += (sp - 1) * static_cast<double>(d.M) * static_cast<double>(d.N) * 8.0 / 5.0e6;
       if (best.kind == 0 || cost < best_cost) {
@@ -548,14 +746,17 @@ hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hi
     hipLaunchKernelGGL((k_gemm_nt<T128, Epi>), grid, dim3(GEMM_THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, k_per_split, epi);
     return hipGetLastError();
   }
-  const int ksteps = static_cast<int>(d.Kd / DBK);
+  const bool k64 = p.kind == KIND_L64 || p.kind == KIND_M64;
+  const int ksteps = static_cast<int>(d.Kd / (k64 ? DBK64 : DBK));
   const int per_split = (ksteps + p.n_split - 1) / p.n_split;
   const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
-#define FAAR_LAUNCH(CFG) \
-  hipLaunchKernelGGL((k_gemm_dma<CFG, Epi>), grid, dim3(CFG::THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, p.n_split, per_split, epi)
-  if (p.kind == KIND_L) FAAR_LAUNCH(CfgL);
-  else if (p.kind == KIND_M) FAAR_LAUNCH(CfgM);
-  else FAAR_LAUNCH(CfgS);
+#define FAAR_LAUNCH(KERNEL, CFG) \
+  hipLaunchKernelGGL((KERNEL<CFG, Epi>), grid, dim3(CFG::THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, p.n_split, per_split, epi)
+  if (p.kind == KIND_L64) FAAR_LAUNCH(k_gemm_dma64, CfgL64);
+  else if (p.kind == KIND_M64) FAAR_LAUNCH(k_gemm_dma64, CfgM64);
+  else if (p.kind == KIND_L) FAAR_LAUNCH(k_gemm_dma, CfgL);
+  else if (p.kind == KIND_M) FAAR_LAUNCH(k_gemm_dma, CfgM);
+  else FAAR_LAUNCH(k_gemm_dma, CfgS);
 #undef FAAR_LAUNCH
   return hipGetLastError();
 }
