@@ -481,16 +481,16 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
 // The chip runs this loop power-limited, and two things lower the energy per flop: global->LDS copies whose
 // eight lanes per row make one 128-byte request (BK = 64) instead of two 64-byte ones, and the 16x16x32 MFMA,
 // which reads and writes a quarter of the accumulator values per instruction of the 32x32x16 form for half
-// its flops.  With BK = 64 only two stages fit next to a 256x256 tile (2 x 64 KB), so a stage is refilled as
-// soon as the workgroup has read it: ONE barrier per slice, placed before the slice's last MFMA phase, at
+// its flops.  With BK = 64 only two stages fit next to a 256x256 tile (2 x 64 KB; three for 256x128), so a stage
+// is refilled as soon as the workgroup has read it: ONE barrier per slice, placed before the slice's last MFMA phase, at
 // which point every wavefront holds the last fragments of the slice in registers and the copies of the next
-// slice (issued one slice earlier, right after the previous barrier) have landed.
+// slice (issued NS - 1 slices earlier, right after a barrier) have landed.
 
 constexpr int DBK64 = 64;
 
-template <int BM_, int BN_, int WGM_, int WGN_>
+template <int BM_, int BN_, int WGM_, int WGN_, int NS_>
 struct Dma64Cfg {
-  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_;
+  static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, NS = NS_;  // NS ring stages (2 or 3)
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 16, TN = WN / 16;
@@ -504,14 +504,14 @@ struct Dma64Cfg {
   static constexpr int FSTEP = NM / NF >= 2 ? 2 : 1;  // one fragment prefetch every FSTEP MFMAs
   static constexpr int DSTEP = NM / P;                // one DMA issue every DSTEP MFMAs of the last phase
   static_assert(NF * FSTEP <= NM && P * DSTEP <= NM && DSTEP >= 1, "phase schedule");
-  static_assert((BM + BN) % (RPI * NW) == 0 && TN % 2 == 0, "tile shape");
+  static_assert((BM + BN) % (RPI * NW) == 0 && TN % 2 == 0 && (NS == 2 || NS == 3), "tile shape");
 };
 
 template <class C, class Epi>
 __global__ void __launch_bounds__(C::THREADS)
 k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
              int ksteps_per_split, Epi epi) {
-  __shared__ __attribute__((aligned(1024))) bf16_t lds[2 * C::STAGE];
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[C::NS * C::STAGE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
   int tm, tn, split, item;
@@ -549,7 +549,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       }
     }
 #pragma unroll
-    for (int s = 0; s < 2; ++s) {
+    for (int s = 0; s < C::NS; ++s) {
       const int t = kbeg + (s < nk ? s : nk - 1);
 #pragma unroll
       for (int q = 0; q < P; ++q)
@@ -570,7 +570,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     }
     bf16x8 fa[2][TM], fb[2][TN];
 
-    FAAR_WAIT_VMCNT(P);  // slice 0 has landed (mine); barrier: everybody's
+    FAAR_WAIT_VMCNT(P * (C::NS - 1));  // slice 0 has landed (mine); barrier: everybody's
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -584,24 +584,26 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     }
 
     for (int it = 0; it < nk; ++it) {
-      bf16_t* st = lds + (it & 1) * C::STAGE;
-      const bf16_t* sn = lds + ((it + 1) & 1) * C::STAGE;
-      const bool more = it + 2 < nk;
-      const int64_t goff = (int64_t)(kbeg + it + 2) * DBK64;
+      bf16_t* st = lds + (it % C::NS) * C::STAGE;
+      const bf16_t* sn = lds + ((it + 1) % C::NS) * C::STAGE;
+      const bool more = it + C::NS < nk;
+      const int64_t goff = (int64_t)(kbeg + it + C::NS) * DBK64;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         const int cur = kk & 1;
         if (kk == KK - 1) {
           // this wavefront's copies of slice it+1 have landed and its reads of slice it are complete;
           // after the barrier that holds for the workgroup: stage `st` may be refilled, `sn` may be read
-          __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+          constexpr int kInFlight = P * (C::NS - 2);  // copies of later slices may stay in flight
+          __builtin_amdgcn_s_waitcnt(0x0070 | (kInFlight & 0xF) | ((kInFlight >> 4) << 14));  // vmcnt(kInFlight) lgkmcnt(0)
           __builtin_amdgcn_s_barrier();
         }
         const bf16_t* src = (kk + 1 < KK) ? st : sn;
         const int nkk = (kk + 1 < KK) ? kk + 1 : 0;
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
-          const int mi = m / TN, mj = m % TN;
+          // boustrophedon over the tile grid: consecutive MFMAs share one operand
+          const int mi = m / TN, mj = (mi & 1) ? TN - 1 - m % TN : m % TN;
           acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
           if (m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
             const int f = m / C::FSTEP;
@@ -610,7 +612,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
             else fa[cur ^ 1][f - TN] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk] + (f - TN) * 16 * DBK64);
           }
           if (kk == KK - 1 && m % C::DSTEP == 0 && m / C::DSTEP < P) {
-            // slice it+2 into the stage just released; past the end every lane re-reads one valid address
+            // slice it+NS into the stage just released; past the end every lane re-reads one valid address
             const int q = m / C::DSTEP;
             const bf16_t* g = more ? gsrc[q] + goff : A;
             dma16(g, __builtin_amdgcn_readfirstlane(lds_addr_of(st + (wave * P + q) * C::RPI * DBK64)));
@@ -630,7 +632,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     constexpr int LDT = C::BM + 8;
     constexpr int ROWS = C::WGN * 32;
     constexpr int CPRW = C::BM / 8;
-    static_assert(ROWS * LDT <= 2 * C::STAGE, "staging buffer fits in the ring");
+    static_assert(ROWS * LDT <= C::NS * C::STAGE, "staging buffer fits in the ring");
     bf16_t* stg = lds;
     const int wc = wave % C::WGN;
 #pragma unroll
@@ -674,8 +676,8 @@ typedef Tile<128, 128> T128;
 typedef DmaCfg<256, 256, 2, 4> CfgL;  // large problems
 typedef DmaCfg<256, 128, 4, 2> CfgM;  // one tile per compute unit at ~256 tiles
 typedef DmaCfg<128, 128, 2, 2> CfgS;  // small outputs, two workgroups per compute unit
-typedef Dma64Cfg<256, 256, 2, 4> CfgL64;
-typedef Dma64Cfg<256, 128, 4, 2> CfgM64;
+typedef Dma64Cfg<256, 256, 2, 4, 2> CfgL64;  // 2 x 64 KB
+typedef Dma64Cfg<256, 128, 4, 2, 3> CfgM64;  // 3 x 48 KB: copies stay in flight for two slices
 
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
