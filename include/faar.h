@@ -170,8 +170,11 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K,
  * the first faar_layer_step of a layer:
  *
  *   Xt = Xq^T                as bf16 [K, Tp], Tp = faar_padded_tokens(T), columns T..Tp-1 zero
- *   C  = Y_fp - Xq W^T       as float [T, O]   (bf16 products are exact, float32 accumulation;
- *                                                a float32 W is split into three bf16 terms)
+ *   C  = Y_fp - Xq W^T       as float [ceil(T/4), O, 4]: element (t, o) at ((t / 4) * O + o) * 4 + t % 4,
+ *                            rows T..4*ceil(T/4)-1 zero.  (Four consecutive tokens of one output channel are
+ *                            what one lane of the step's GEMM epilogue holds: one 16-byte access.)  bf16
+ *                            products are exact, float32 accumulation; a float32 W is split into three
+ *                            bf16 terms.  The buffer holds 4 * ceil(T/4) * O floats.
  *
  * The residual of Eq. 5 is then  Xq W_q^T - Y_fp = Xq (W_q - W)^T - C,  which lets the step run its
  * GEMM on the small perturbation W_q - W without losing it to bf16 rounding of W_q.

@@ -174,14 +174,14 @@ def faar_softquant_fwd_bwd(W, s_global, scales, V, beta, dWt=None, lambda_round=
 
 
 def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None):
-    """-> (Xt bf16 [K, Tp], C f32 [T, O], icodes u8 [O, K/2])."""
+    """-> (Xt bf16 [K, Tp], C f32 [ceil(T/4), O, 4] (tokens interleaved in groups of four), icodes u8 [O, K/2])."""
     _dev(W, s_global, scales, Xq, Y_fp, ws)
     O, K = W.shape
     T = Xq.shape[0]
     if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or tuple(Y_fp.shape) != (T, O):
         raise ValueError("Xq must be bf16 [T,K]; Y_fp must be [T,O]")
     Xt = torch.empty((K, faar_padded_tokens(T)), dtype=torch.bfloat16, device=W.device)
-    C = torch.empty((T, O), dtype=torch.float32, device=W.device)
+    C = torch.empty(((T + 3) // 4, O, 4), dtype=torch.float32, device=W.device)   # row groups of 4 interleaved
     icodes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     ws = _workspace(OP_LAYER_PREPARE, O, K, T, device=W.device) if ws is None else ws
     _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(Y_fp),

@@ -161,18 +161,12 @@ struct EpiResidual {
   bf16_t* dY;
   double* partials;
   float sum;
-  // C[m..m+3][n] (zero outside the matrix); kept separate from value4 so that a whole slab's loads can be
+  // C of rows m..m+3 (m a multiple of 4) of column n: one 16-byte load from the row-group-interleaved layout
+  // [ceil(M/4)][N][4] (zero outside the matrix); kept separate from value4 so that a whole slab's loads can be
   // issued before the first dependent store
   __device__ __forceinline__ float4 load4(int64_t m, int64_t n, const GemmDims& d) const {
-    float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (n < d.N) {
-      const float* p = C + m * d.N + n;
-      if (m < d.M) c.x = p[0];
-      if (m + 1 < d.M) c.y = p[d.N];
-      if (m + 2 < d.M) c.z = p[2 * d.N];
-      if (m + 3 < d.M) c.w = p[3 * d.N];
-    }
-    return c;
+    if (n < d.N && m < d.M) return *reinterpret_cast<const float4*>(C + ((m >> 2) * d.N + n) * 4);
+    return make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   }
   // four consecutive rows m..m+3 of column n -> four bf16 dY values (zero outside the matrix)
   __device__ __forceinline__ uint2 value4(const float (&acc)[4], const float4& c4, int64_t m, int64_t n, const GemmDims& d) {
@@ -229,7 +223,10 @@ struct EpiF32 {
   __device__ __forceinline__ void finish(int) {}
 };
 
-// C_out[m][n] = (first ? Y[m][n] : C_out[m][n]) - acc
+// C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - acc, with C_out in the row-group-interleaved layout
+// [ceil(M/4)][N][4]: element (m, n) at ((m / 4) * N + n) * 4 + m % 4, so that the four consecutive rows a lane
+// holds of one column are one 16-byte access and the 16 or 32 lanes of a row group touch contiguous memory.
+// Rows M..4*ceil(M/4)-1 are written as zero.
 template <bool kYbf16>
 struct EpiSub {
   static constexpr bool kTransposedOut = false;
@@ -237,17 +234,24 @@ struct EpiSub {
   bool first;
   float* C_out;
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
-    if (n >= d.N) return;
+    if (n >= d.N || m >= d.M) return;  // m is a multiple of 4
+    float4* p = reinterpret_cast<float4*>(C_out + ((m >> 2) * d.N + n) * 4);
+    float y[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (!first) {
+      const float4 c = *p;
+      y[0] = c.x; y[1] = c.y; y[2] = c.z; y[3] = c.w;
+    } else {
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (m + q < d.M) {
-        const int64_t idx = (m + q) * d.N + n;
-        float y;
-        if (!first) y = C_out[idx];
-        else if (kYbf16) y = bf16_to_f32(static_cast<const bf16_t*>(Y)[idx]);
-        else y = static_cast<const float*>(Y)[idx];
-        C_out[idx] = y - acc[q];
-      }
+      for (int q = 0; q < 4; ++q)
+        if (m + q < d.M) {
+          const int64_t idx = (m + q) * d.N + n;
+          y[q] = kYbf16 ? bf16_to_f32(static_cast<const bf16_t*>(Y)[idx]) : static_cast<const float*>(Y)[idx];
+        }
+    }
+    float o[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q] = (m + q < d.M) ? y[q] - acc[q] : 0.0f;
+    *p = make_float4(o[0], o[1], o[2], o[3]);
   }
   __device__ __forceinline__ void finish(int) {}
 };

@@ -169,7 +169,11 @@ def test_layer_prepare(c):
     assert np.array_equal(xt[:, :c.T], c.Xq.T) and not xt[:, c.T:].any()
     C_want = c.Y_fp.astype(np.float64) - c.Xq.astype(np.float64) @ c.W.astype(np.float64).T
     scale = np.abs(c.Xq.astype(np.float64)) @ np.abs(c.W.astype(np.float64)).T      # size of the summed terms
-    assert np.all(np.abs(host(C) - C_want) <= 2e-6 * scale + 1e-30)
+    Cg = host(C)                                        # [ceil(T/4), O, 4]: rows interleaved in groups of four
+    assert Cg.shape == ((c.T + 3) // 4, c.O, 4)
+    Cg = Cg.transpose(0, 2, 1).reshape(-1, c.O)
+    assert not Cg[c.T:].any()
+    assert np.all(np.abs(Cg[:c.T] - C_want) <= 2e-6 * scale + 1e-30)
     # cached interval codes: sign bit and k_lo (7 for a zero weight)
     wt = fo.normalised_magnitude(c.W, q["scales"], q["s_global"])
     want_ic = (np.signbit(c.W).astype(np.uint8) << 3) | np.where(c.W == 0, 7, fo.find_interval(wt)).astype(np.uint8)
