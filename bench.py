@@ -261,6 +261,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep"])
+    ap.add_argument("--quantised-acts", action="store_true",
+                    help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=20)
@@ -293,6 +295,10 @@ def main() -> int:
     W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
     Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
     Y = Xq @ W.T                       # the frozen BF16 layer output: an input of the method (input generation only)
+    x_scale = None
+    if args.quantised_acts:            # X_q = NVFP4(X): node * block scale in bf16 (exact) and the tensor scale on the side
+        x_scale, _, _, Xq = faar.faar_quant_rtn(Xq, want_dq=True, dq_in_units=True)
+        X_h = (Xq.float() * x_scale).cpu().numpy()
     torch.cuda.synchronize()
     N = O * K
     alpha, lam, lr = 1.0 / (T * O), 0.01, 5e-4
@@ -307,14 +313,14 @@ def main() -> int:
     def layer_job(n_steps):
         sg, scales, codes, _ = faar.faar_quant_rtn(W, ws=ws_q)
         V, _ = faar.faar_init_v(W, sg, scales)
-        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y, ws=ws_p)
+        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y, ws=ws_p, x_scale=x_scale)
         m = torch.zeros_like(V)
         u = torch.zeros_like(V)
         for t in range(1, n_steps + 1):
             # every step but the last also prepares the next step's soft-quantised weights (beta_next)
             faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
                                  1e-8, t, losses, ws, beta_next=beta_at(t + 1, n_steps) if t < n_steps else 0.0,
-                                 forward_ready=t > 1)
+                                 forward_ready=t > 1, x_scale=x_scale)
         out, _, _, flips = faar.faar_harden_pack(W, sg, scales, V, want_flips=True)
         return sg, scales, V, m, u, Xt, C, ic, out, flips
 
@@ -350,11 +356,11 @@ def main() -> int:
 
     def first_step_call(i):      # a layer's first step: its own forward kernel, nothing prepared for the next
         faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
-                             args.steps + 1 + i, losses, ws)
+                             args.steps + 1 + i, losses, ws, x_scale=x_scale)
 
     def step_call(i):            # every later step: forward taken from / left in the workspace
         faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
-                             args.steps + 1 + i, losses, ws, beta_next=16.0, forward_ready=i > 0)
+                             args.steps + 1 + i, losses, ws, beta_next=16.0, forward_ready=i > 0, x_scale=x_scale)
 
     n_probe = max(5, args.probe_steps)
     probe["softquant_fwd"] = timed_kernel(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
@@ -405,7 +411,8 @@ def main() -> int:
         "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} bf16, NVFP4 block 16; "
+        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} "
+                               f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'}, NVFP4 block 16; "
                                "per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
                    "O": O, "K": K, "T": T},
         "weight_elems_per_sec": round(N * args.steps / elapsed, 1),

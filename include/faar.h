@@ -57,8 +57,11 @@ enum {
   FAAR_EMIT_DELTA = 1u << 1,    /* faar_softquant_fwd_bwd: Wt receives W_q - W instead of W_q */
   FAAR_WS_CHAINED = 1u << 2,    /* faar_workspace_bytes / faar_layer_step: size the workspace for a
                                    step that takes dY_ext and/or produces dX */
-  FAAR_WS_FORWARD_READY = 1u << 3 /* faar_layer_step: the workspace already holds this step's soft-quantised
+  FAAR_WS_FORWARD_READY = 1u << 3, /* faar_layer_step: the workspace already holds this step's soft-quantised
                                    weights, left there by the previous step (its beta_next) */
+  FAAR_DQ_IN_UNITS = 1u << 4    /* faar_quant_rtn: W_dq receives sign * node * E4M3 scale, i.e. the dequantised
+                                   value in units of s_global -- an exact product (at most 6 significant bits),
+                                   so exactly representable in bf16 */
 };
 
 /* operations, for faar_workspace_bytes */
@@ -125,7 +128,10 @@ int64_t faar_padded_tokens(int64_t T);
  *   scales   out uint8[O*K/16]
  *   codes    out uint8[O*K/2]
  *   W_dq     out, nullable: dequantised weights sign * N[code] * E4M3_value(byte) * s_global,
- *            dtype wdt (float32 product rounded once; then to bf16 if wdt is bf16)
+ *            dtype wdt (float32 product rounded once; then to bf16 if wdt is bf16).  With
+ *            FAAR_DQ_IN_UNITS the factor s_global is left out and the value is exact: quantising
+ *            ACTIVATIONS this way (tensor [T, K], blocks along K) gives the Xq / x_scale = s_global pair
+ *            that faar_layer_prepare and faar_layer_step take.
  *   ws       FAAR_OP_QUANT_RTN workspace
  */
 int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K,
@@ -185,13 +191,15 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K,
  *   icodes = uint8 [O*K/2], element 2j of a row in the low nibble: signbit(w) << 3 | (w == 0 ? 7 : k_lo)
  *
  *   s_global, scales  as written by faar_quant_rtn
- *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4)
+ *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4), in units of
+ *   x_scale in, nullable device float[1] (NULL = 1): X_q = x_scale * Xq.  NVFP4-quantised activations are
+ *        passed exactly as Xq = node * block scale (bf16-exact) and x_scale = their tensor scale.
  *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T
  *   ws   FAAR_OP_LAYER_PREPARE workspace
  */
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                        const float* s_global, const uint8_t* scales,
-                       const void* Xq, const void* Y_fp, faar_dtype ydt, int64_t T,
+                       const void* Xq, const float* x_scale, const void* Y_fp, faar_dtype ydt, int64_t T,
                        void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream);
 
 /* Adam hyper-parameters; t is the 1-based index of the step being taken. */
@@ -213,7 +221,7 @@ typedef struct {
  * accumulated in a fixed order (results are bit-reproducible run to run).
  *
  *   V, adam_m, adam_v   in/out float[O*K]
- *   Xq, Xt, C, icodes   as for / from faar_layer_prepare
+ *   Xq, x_scale, Xt, C, icodes   as for / from faar_layer_prepare
  *   dY_ext              in, nullable bf16[T*O]: upstream gradient replacing the locally derived dY
  *   dX                  out, nullable bf16[T*K]: dY W_q
  *   opt                 HOST pointer
@@ -233,8 +241,8 @@ typedef struct {
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* s_global, const uint8_t* scales,
                     float* V, float* adam_m, float* adam_v,
-                    const void* Xq, const void* Xt, const float* C, const uint8_t* icodes, int64_t T,
-                    const void* dY_ext, void* dX,
+                    const void* Xq, const float* x_scale, const void* Xt, const float* C, const uint8_t* icodes,
+                    int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfaar.so")
 
 FAAR_F32, FAAR_BF16 = 0, 1
-FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY = 1, 2, 4, 8
+FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
 OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK = range(6)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
@@ -62,10 +62,12 @@ def lib() -> ctypes.CDLL:
                                              c_size_t, c_void_p]
         L.faar_layer_prepare.restype = c_int
         L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                         c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+                                         c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
+                                         c_void_p]
         L.faar_layer_step.restype = c_int
         L.faar_layer_step.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
+                                      c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
         L.faar_harden_pack.restype = c_int
@@ -129,8 +131,9 @@ def _workspace(op, O, K, T=0, flags=0, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
-def faar_quant_rtn(W, s_global=None, want_dq=False, ws=None):
-    """-> (s_global[1] f32, scales [O,K/16] u8, codes [O,K/2] u8, W_dq or None)."""
+def faar_quant_rtn(W, s_global=None, want_dq=False, ws=None, dq_in_units=False):
+    """-> (s_global[1] f32, scales [O,K/16] u8, codes [O,K/2] u8, W_dq or None).
+    dq_in_units: W_dq = sign * node * block scale (exact), to be multiplied by s_global by its consumer."""
     _dev(W, s_global, ws)
     O, K = W.shape
     flags = 0
@@ -138,6 +141,8 @@ def faar_quant_rtn(W, s_global=None, want_dq=False, ws=None):
         s_global = torch.empty(1, dtype=torch.float32, device=W.device)
     else:
         flags |= FAAR_SGLOBAL_GIVEN
+    if dq_in_units:
+        flags |= FAAR_DQ_IN_UNITS
     scales = torch.empty((O, K // 16), dtype=torch.uint8, device=W.device)
     codes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     W_dq = torch.empty_like(W) if want_dq else None
@@ -173,9 +178,9 @@ def faar_softquant_fwd_bwd(W, s_global, scales, V, beta, dWt=None, lambda_round=
     return Wt, dV, rl
 
 
-def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None):
+def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None):
     """-> (Xt bf16 [K, Tp], C f32 [ceil(T/4), O, 4] (tokens interleaved in groups of four), icodes u8 [O, K/2])."""
-    _dev(W, s_global, scales, Xq, Y_fp, ws)
+    _dev(W, s_global, scales, Xq, Y_fp, ws, x_scale)
     O, K = W.shape
     T = Xq.shape[0]
     if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or tuple(Y_fp.shape) != (T, O):
@@ -184,22 +189,24 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None):
     C = torch.empty(((T + 3) // 4, O, 4), dtype=torch.float32, device=W.device)   # row groups of 4 interleaved
     icodes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     ws = _workspace(OP_LAYER_PREPARE, O, K, T, device=W.device) if ws is None else ws
-    _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(Y_fp),
-                                    _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(ws), ws.numel(), _stream()),
+    _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(x_scale),
+                                    _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(ws), ws.numel(), _stream()),
            "faar_layer_prepare")
     return Xt, C, icodes
 
 
 def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
-                    lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False):
+                    lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False,
+                    x_scale=None):
     """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L).
     beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them."""
-    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX)
+    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX, x_scale)
     O, K = W.shape
     T = Xq.shape[0]
     opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
     _check(lib().faar_layer_step(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m),
-                                 _ptr(adam_v), _ptr(Xq), _ptr(Xt), _ptr(C), _ptr(icodes), T, _ptr(dY_ext), _ptr(dX),
+                                 _ptr(adam_v), _ptr(Xq), _ptr(x_scale), _ptr(Xt), _ptr(C), _ptr(icodes), T, _ptr(dY_ext),
+                                 _ptr(dX),
                                  float(beta), float(beta_next), float(lambda_round), float(mse_scale),
                                  ctypes.byref(opt), _ptr(losses), FAAR_WS_FORWARD_READY if forward_ready else 0,
                                  _ptr(ws), ws.numel(), _stream()), "faar_layer_step")

@@ -128,7 +128,7 @@ int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K, float* s
   if (!W || !s_global || !scales || !codes) return FAAR_E_NULL;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_shape(O, K)) return e;
-  if (flags & ~(uint32_t)FAAR_SGLOBAL_GIVEN) return FAAR_E_ARG;
+  if (flags & ~(uint32_t)(FAAR_SGLOBAL_GIVEN | FAAR_DQ_IN_UNITS)) return FAAR_E_ARG;
   if (!aligned16(W) || !aligned16(codes) || !aligned16(W_dq) || (reinterpret_cast<uintptr_t>(s_global) & 3u))
     return FAAR_E_ARG;
   const bool given = (flags & FAAR_SGLOBAL_GIVEN) != 0;
@@ -138,7 +138,7 @@ int faar_quant_rtn(const void* W, faar_dtype wdt, int64_t O, int64_t K, float* s
   if (!given)
     if (int e = hip_status(launch_amax(W, bf, O * K, static_cast<float*>(ws), s_global, st))) return e;
   Bracket b(FAAR_K_QUANT_RTN, st);
-  return hip_status(launch_quant_rtn(W, bf, O * K, s_global, scales, codes, W_dq, st));
+  return hip_status(launch_quant_rtn(W, bf, O * K, s_global, scales, codes, W_dq, (flags & FAAR_DQ_IN_UNITS) != 0, st));
 }
 
 int faar_init_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
@@ -182,8 +182,8 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, 
 }
 
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
-                       const uint8_t* scales, const void* Xq, const void* Y_fp, faar_dtype ydt, int64_t T,
-                       void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream) {
+                       const uint8_t* scales, const void* Xq, const float* x_scale, const void* Y_fp, faar_dtype ydt,
+                       int64_t T, void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream) {
   if (!W || !s_global || !scales || !Xq || !Y_fp || !Xt || !C || !icodes) return FAAR_E_NULL;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_wdt(ydt)) return e;
@@ -198,18 +198,18 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   if (int e = hip_status(launch_interval_codes(W, bf, O * K, s_global, scales, icodes, st))) return e;
   if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), padded_tokens(T), st))) return e;
   const GemmDims d{T, O, K, K, K};
-  if (bf) return hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, st));
+  if (bf) return hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, x_scale, st));
   Carver cv(ws);
   bf16_t* term[3];
   for (auto& t : term) t = cv.take<bf16_t>((size_t)O * K);
   if (int e = hip_status(launch_split_f32(static_cast<const float*>(W), O * K, term[0], term[1], term[2], st))) return e;
   for (int i = 0; i < 3; ++i)
-    if (int e = hip_status(launch_gemm_sub(xq, term[i], d, Y_fp, ydt == FAAR_BF16, i == 0, C, st))) return e;
+    if (int e = hip_status(launch_gemm_sub(xq, term[i], d, Y_fp, ydt == FAAR_BF16, i == 0, C, x_scale, st))) return e;
   return FAAR_OK;
 }
 
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
-                    const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq,
+                    const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq, const float* x_scale,
                     const void* Xt, const float* C, const uint8_t* icodes, int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
@@ -262,7 +262,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   const bool need_local_dY = dX && !dY_ext;
   {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
-    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, 2.0f * mse_scale, dYt, L.Tp,
+    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, x_scale, 2.0f * mse_scale, dYt, L.Tp,
                                                 need_local_dY ? dY : nullptr, mse_p, &n_mse, st)))
       return e;
   }
@@ -290,7 +290,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.W = W; a.w_bf16 = bf; a.n = n;
   a.s_global = s_global; a.scales = scales; a.icodes = icodes;
   a.V = V; a.m = adam_m; a.u = adam_v;
-  a.beta = beta; a.G = G; a.n_split = L.n_split; a.split_stride = (int64_t)O * K;
+  a.beta = beta; a.G = G; a.n_split = L.n_split; a.split_stride = (int64_t)O * K; a.x_scale = x_scale;
   a.lambda_round = lambda_round;
   a.opt.lr = opt->lr; a.opt.beta1 = opt->beta1; a.opt.beta2 = opt->beta2; a.opt.eps = opt->eps;
   a.opt.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));

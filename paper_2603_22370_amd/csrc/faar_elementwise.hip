@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(kEltThreads) k_amax_final(const float* __restr
 template <typename WT, bool kDequant>
 __global__ void __launch_bounds__(kEltThreads)
 k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
-            uint8_t* __restrict__ scales, uint32_t* __restrict__ codes, WT* __restrict__ W_dq) {
+            uint8_t* __restrict__ scales, uint32_t* __restrict__ codes, WT* __restrict__ W_dq, bool dq_in_units) {
   const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
   if (i >= n8) return;  // n8 is even: both lanes of a pair leave together
   const float sg = *s_global_p;
@@ -104,7 +104,7 @@ k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_gl
       const int k_lo = interval_index(wt);
       const uint32_t nib = nibble(w[j], k_lo, wt >= interval_mid(k_lo));
       packed |= nib << (4 * j);
-      if (kDequant) dq[j] = dequant(nib, sgv, sg);
+      if (kDequant) dq[j] = dequant(nib, sgv, dq_in_units ? 1.0f : sg);  // in units of s_global: an exact product
     }
   };
   if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
@@ -445,7 +445,7 @@ __global__ void __launch_bounds__(kEltThreads)
 k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t* __restrict__ scales,
                 const uint32_t* __restrict__ icodes, float* __restrict__ V, float* __restrict__ M,
                 float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
-                float lam_over_n, AdamScalars o, LossSums fin, const WT* __restrict__ W, float beta_next,
+                const float* __restrict__ x_scale_p, float lam_over_n, AdamScalars o, LossSums fin, const WT* __restrict__ W, float beta_next,
                 bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_next) {
   const int workers = static_cast<int>(gridDim.x) - 1;
   if (static_cast<int>(blockIdx.x) == workers) {
@@ -454,6 +454,7 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
   }
   float rsum = 0.0f;
   const float sg = *s_global_p;
+  const float xs = x_scale_p ? *x_scale_p : 1.0f;  // G = x_scale * (dY^T X_q-in-units)
   for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)workers * kEltThreads) {
     const float s = effective_scale(scales[i >> 1], sg);
     const uint32_t codes = icodes[i];
@@ -472,7 +473,7 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
     for (int j = 0; j < 8; ++j) {
       const uint32_t nib = (codes >> (4 * j)) & 15u;
       const float h = h_beta_fast(v[j], beta);
-      const float d = g[j] * (signed_scale(nib, s) * node_width(nib & 7u) * beta * (h * (1.0f - h))) +
+      const float d = (xs * g[j]) * (signed_scale(nib, s) * node_width(nib & 7u) * beta * (h * (1.0f - h))) +
                       lam_over_n * (4.0f - 8.0f * v[j]);
       m[j] = o.beta1 * m[j] + (1.0f - o.beta1) * d;
       u[j] = o.beta2 * u[j] + (1.0f - o.beta2) * (d * d);
@@ -570,12 +571,12 @@ hipError_t launch_amax(const void* W, bool w_bf16, int64_t n, float* partials, f
 }
 
 hipError_t launch_quant_rtn(const void* W, bool w_bf16, int64_t n, const float* s_global,
-                            uint8_t* scales, uint8_t* codes, void* W_dq, hipStream_t st) {
+                            uint8_t* scales, uint8_t* codes, void* W_dq, bool dq_in_units, hipStream_t st) {
   const int64_t n8 = n / 8;
   const dim3 g(blocks_for(n8)), b(kEltThreads);
   uint32_t* c32 = reinterpret_cast<uint32_t*>(codes);
 #define FAAR_Q(WT, DQ) \
-  hipLaunchKernelGGL((k_quant_rtn<WT, DQ>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, static_cast<WT*>(W_dq))
+  hipLaunchKernelGGL((k_quant_rtn<WT, DQ>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, static_cast<WT*>(W_dq), dq_in_units)
   if (w_bf16) { if (W_dq) FAAR_Q(bf16_t, true); else FAAR_Q(bf16_t, false); }
   else        { if (W_dq) FAAR_Q(float, true);  else FAAR_Q(float, false); }
 #undef FAAR_Q
@@ -699,7 +700,7 @@ hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st) {
   const uint32_t* c32 = reinterpret_cast<const uint32_t*>(a.icodes);
 #define FAAR_SB(WT, E, F) \
   hipLaunchKernelGGL((k_step_bwd_adam<WT, E, F>), g, b, 0, st, n8, a.s_global, a.scales, c32, a.V, a.m, a.u, a.beta, a.G, \
-                     a.n_split, a.split_stride, lam_over_n, a.opt, fin, static_cast<const WT*>(a.W), a.beta_next, \
+                     a.n_split, a.split_stride, a.x_scale, lam_over_n, a.opt, fin, static_cast<const WT*>(a.W), a.beta_next, \
                      a.delta_next, a.wq_full_next, a.round_next)
   const bool emit = a.beta_next > 0.0f;
   if (!emit) { if (a.w_bf16) FAAR_SB(bf16_t, false, false); else FAAR_SB(float, false, false); }

@@ -133,6 +133,7 @@ k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d
   }
 
   // epilogue: hand every group of 4 consecutive rows (one column) to the functor
+  epi.begin();
   const int col = lane & 31, hi = lane >> 5;
 #pragma unroll
   for (int i = 0; i < T::TM; ++i)
@@ -151,10 +152,13 @@ k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d
 
 // ---- epilogues -----------------------------------------------------------------------------
 
-// R = acc - C; sum R^2; dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
+// R = x_scale * acc - C; sum R^2; dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
 struct EpiResidual {
   static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
   const float* C;
+  const float* x_scale;  // device scalar multiplying the A operand (activations stored in units of it); null = 1
+  float xs;
+  __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
   float two_alpha;
   bf16_t* dYt;
   int64_t ldt;
@@ -176,7 +180,7 @@ struct EpiResidual {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (m + q < d.M) {
-          const float r = acc[q] - c[q];
+          const float r = xs * acc[q] - c[q];
           sum += r * r;
           b[q] = f32_to_bf16(two_alpha * r);
           if (dY) dY[(m + q) * d.N + n] = static_cast<bf16_t>(b[q]);
@@ -213,6 +217,7 @@ struct EpiResidual {
 struct EpiF32 {
   static constexpr bool kTransposedOut = false;
   float* out;
+  __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int split, const GemmDims& d) {
     if (n >= d.N) return;
     float* o = out + (int64_t)split * d.M * d.N;
@@ -223,7 +228,7 @@ struct EpiF32 {
   __device__ __forceinline__ void finish(int) {}
 };
 
-// C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - acc, with C_out in the row-group-interleaved layout
+// C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc, with C_out in the row-group-interleaved layout
 // [ceil(M/4)][N][4]: element (m, n) at ((m / 4) * N + n) * 4 + m % 4, so that the four consecutive rows a lane
 // holds of one column are one 16-byte access and the 16 or 32 lanes of a row group touch contiguous memory.
 // Rows M..4*ceil(M/4)-1 are written as zero.
@@ -233,6 +238,9 @@ struct EpiSub {
   const void* Y;
   bool first;
   float* C_out;
+  const float* x_scale;  // as in EpiResidual
+  float xs;
+  __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N || m >= d.M) return;  // m is a multiple of 4
     float4* p = reinterpret_cast<float4*>(C_out + ((m >> 2) * d.N + n) * 4);
@@ -250,7 +258,7 @@ struct EpiSub {
     }
     float o[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) o[q] = (m + q < d.M) ? y[q] - acc[q] : 0.0f;
+    for (int q = 0; q < 4; ++q) o[q] = (m + q < d.M) ? y[q] - xs * acc[q] : 0.0f;
     *p = make_float4(o[0], o[1], o[2], o[3]);
   }
   __device__ __forceinline__ void finish(int) {}
@@ -260,6 +268,7 @@ struct EpiSub {
 struct EpiBf16 {
   static constexpr bool kTransposedOut = false;
   bf16_t* out;
+  __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N) return;
 #pragma unroll
@@ -429,6 +438,7 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
     FAAR_WAIT_VMCNT(0);  // no copy may still be in flight into this workgroup's LDS when it retires
   }
 
+  epi.begin();
   const int col = lane & 31, hi2 = lane >> 5;
   if constexpr (Epi::kTransposedOut) {
     // Output is wanted transposed ([n][m], m contiguous) while a lane holds 4 consecutive m of one n: stage
@@ -629,6 +639,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
   }
 
   // accumulator layout of the 16x16 tile: lane -> column lane % 16, rows 4 * (lane / 16) + 0..3
+  epi.begin();
   const int col = lane & 15, rq = lane >> 4;
   if constexpr (Epi::kTransposedOut) {
     // as in k_gemm_dma: stage a 32-column slab (two 16-column tiles) per wavefront column through LDS and
@@ -773,10 +784,10 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {
   return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, false, kEpiResidual).items();
 }
 
-hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
+hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, hipStream_t st) {
-  EpiResidual e{C, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
+  EpiResidual e{C, x_scale, 1.0f, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
   const Plan p = plan_gemm(d, false, kEpiResidual);
   *n_partials = p.items();
   return run(A, B, d, p, e, st);
@@ -793,13 +804,13 @@ hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* 
 }
 
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
-                           bool first, float* C_out, hipStream_t st) {
+                           bool first, float* C_out, const float* x_scale, hipStream_t st) {
   const Plan p = plan_gemm(d, false, kEpiSub);
   if (y_bf16) {
-    EpiSub<true> e{Y, first, C_out};
+    EpiSub<true> e{Y, first, C_out, x_scale, 1.0f};
     return run(A, B, d, p, e, st);
   }
-  EpiSub<false> e{Y, first, C_out};
+  EpiSub<false> e{Y, first, C_out, x_scale, 1.0f};
   return run(A, B, d, p, e, st);
 }
 

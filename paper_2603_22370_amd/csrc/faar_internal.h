@@ -19,8 +19,9 @@ inline int64_t padded_tokens(int64_t T) { return round_up(T, 64); }
 // ---- elementwise kernels (faar_elementwise.hip) -------------------------------------------
 hipError_t launch_amax(const void* W, bool w_bf16, int64_t n, float* partials, float* s_global,
                        hipStream_t st);
+// dq_in_units: W_dq receives sign * node * E4M3 scale (exact in bf16), without the factor s_global
 hipError_t launch_quant_rtn(const void* W, bool w_bf16, int64_t n, const float* s_global,
-                            uint8_t* scales, uint8_t* codes, void* W_dq, hipStream_t st);
+                            uint8_t* scales, uint8_t* codes, void* W_dq, bool dq_in_units, hipStream_t st);
 hipError_t launch_init_v(const void* W, bool w_bf16, int64_t n, const float* s_global,
                          const uint8_t* scales, float* V, uint8_t* floor_codes, hipStream_t st);
 hipError_t launch_harden_pack(const void* W, bool w_bf16, int64_t n, const float* s_global,
@@ -61,6 +62,7 @@ struct StepBwdArgs {
   const float* s_global; const uint8_t* scales; const uint8_t* icodes;
   float *V, *m, *u;
   float beta; const float* G; int n_split; int64_t split_stride;
+  const float* x_scale;  // device scalar multiplying G (activations stored in units of it); null = 1
   float lambda_round; AdamScalars opt;
   const double* mse_partials; int64_t n_mse; float mse_scale; const double* round_partials; float* losses;
   float beta_next; bf16_t* delta_next; bf16_t* wq_full_next; double* round_next;
@@ -84,10 +86,11 @@ hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid,
 // with the contraction index contiguous, lda/ldb/Kd multiples of 8.
 struct GemmDims { int64_t M, N, Kd, lda, ldb; };
 
-// Residual epilogue (Table 2 steps 9-10): R = acc - C[m][n]; partial sum of R^2 per tile (double);
+// Residual epilogue (Table 2 steps 9-10): R = x_scale * acc - C(m, n), C in the row-group-interleaved layout
+// [ceil(M/4)][N][4], x_scale a device scalar (null = 1); partial sum of R^2 per tile (double);
 // dYt[n][m] = bf16(two_alpha * R) with row stride ldt (rows n < N, columns m < ldt, zero for m >= M);
 // dY (nullable) [M, N] the same values un-transposed.
-hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C,
+hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, hipStream_t st);
 // number of per-work-item loss partials the residual GEMM writes for these sizes
@@ -96,9 +99,9 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st);
 int choose_split(int64_t M, int64_t N, int64_t Kd);
-// C_out[m][n] = (first ? Y[m][n] : C_out[m][n]) - acc   (Y bf16 or float32)
+// C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc   (Y bf16 or float32 row-major; C_out interleaved)
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
-                           bool first, float* C_out, hipStream_t st);
+                           bool first, float* C_out, const float* x_scale, hipStream_t st);
 // out[m][n] = bf16(acc)
 hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out,
                             hipStream_t st);

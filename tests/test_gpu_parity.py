@@ -404,6 +404,43 @@ def test_forward_left_by_the_previous_step_gives_identical_results():
         assert torch.equal(losses, oa[-1][0])
 
 
+def test_nvfp4_activations_in_units_of_their_tensor_scale():
+    """Activations quantised to NVFP4 by the same kernel (blocks along K, their own tensor scale): W_dq in units of
+    s_global is the exact product node * block scale, and a step fed (Xq, x_scale) agrees with the oracle fed the
+    dequantised activations x_scale * Xq."""
+    for c, seed in ((LCASES[1], 31), (LCASES[3], 32)):          # ragged 96x80 T=100 (generic GEMM), 320x256 T=300
+        X = synth.activations(c.T, c.K, seed)
+        qx = fo.quant_rtn(X, True)
+        sX, sc, cd, Xu = faar.faar_quant_rtn(dev(X, True), want_dq=True, dq_in_units=True)
+        assert np.array_equal(host(cd), qx["codes"]) and np.array_equal(host(sc), qx["scales"])
+        nib = fo.unpack_nibbles(qx["codes"])
+        units = np.where(nib & 8, -1.0, 1.0) * fo.e2m1_decode(nib & 7) * np.repeat(fo.e4m3_decode(qx["scales"]), 16, axis=1)
+        assert np.array_equal(host(Xu).astype(np.float64), units)                    # exact in bf16
+        Xq = (units.astype(np.float32) * np.float32(qx["s_global"])).astype(np.float32)   # what the step must see
+        Wd = dev(c.W, c.w_is_bf16)
+        sg, scales, _, _ = faar.faar_quant_rtn(Wd)
+        q = fo.quant_rtn(c.W, c.w_is_bf16)
+        Xt, C, ic = faar.faar_layer_prepare(Wd, sg, scales, Xu, dev(c.Y_fp, True), x_scale=sX)
+        Cg = host(C).transpose(0, 2, 1).reshape(-1, c.O)[:c.T]
+        C_want = c.Y_fp.astype(np.float64) - Xq.astype(np.float64) @ c.W.astype(np.float64).T
+        scale = np.abs(Xq.astype(np.float64)) @ np.abs(c.W.astype(np.float64)).T
+        assert np.all(np.abs(Cg - C_want) <= 4e-6 * scale + 1e-30)
+        V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+        V, m, u = dev(V0.copy()), dev(np.zeros_like(V0)), dev(np.zeros_like(V0))
+        losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+        ws = faar.layer_step_workspace(c.O, c.K, c.T)
+        alpha = 1.0 / (c.T * c.O)
+        faar.faar_layer_step(Wd, sg, scales, V, m, u, Xu, Xt, C, ic, 8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"],
+                             HYP["beta2"], HYP["eps"], 1, losses, ws, x_scale=sX)
+        ref = {mode: fo.layer_step(c.W, q["s_global"], q["scales"], V0, np.zeros_like(V0), np.zeros_like(V0), Xq, c.Y_fp,
+                                   8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 1,
+                                   declared_rounding=mode) for mode in (False, True)}
+        L = host(losses)
+        assert L[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
+        assert L[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
+        _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
+
+
 def test_full_size_q_proj_step_and_pack():
     """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
     X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
