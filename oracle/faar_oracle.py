@@ -13,6 +13,8 @@ computes, in the paper's order and notation:
   * Eq. 2-3 / Table 2 steps 6-7: soft-quantised weight through h_beta(v) = sigmoid(beta (v - 1/2)).
   * Eq. 5 / Table 2 steps 8-13: reconstruction loss + Round Loss, gradient, update, clip to [0, 1].
   * Eq. 7 / Table 2 steps 25-26: hardening and the final NVFP4 weights.
+  * Eq. 6 / Table 2 steps 18-22: the Stage-2 objective on given logits and last hidden states
+    (temperature softmax, KL(P_fp || P_q), Frobenius MSE, sum of the layers' Round Losses).
 
 Precision rules
   * "Decision arithmetic" -- everything that ends in an integer (scale byte, interval index,
@@ -27,7 +29,8 @@ Parity pins (tests/test_oracle_*.py): node-set enumeration, E4M3 against an inde
 cast, bf16 rounding against a library cast, harden(V_init) == RTN, interpolation identity,
 on-grid property, per-element brute-force nearest node, Round-Loss closed forms, beta -> inf limit,
 central finite differences for dL/dV and dL/dX, brute force over all 2^n roundings of a tiny layer,
-Adam first-step identity.  The scale derivation (tensor_scale / block_scale_bytes rounding mode) and
+Adam first-step identity; for the Stage-2 losses: a library relative-entropy / log-softmax routine, the
+two-class closed form, KL(P||P) = 0, shift and temperature invariances, central finite differences.  The scale derivation (tensor_scale / block_scale_bytes rounding mode) and
 the nibble packing order are conventions the paper does not fix: they are pinned to the published
 NVFP4 format description only through the structural invariants tested there.
 """
@@ -359,3 +362,41 @@ def hardened_loss(W, w_is_bf16, s_global, scale_bytes, V, Xq, Y_fp, alpha) -> fl
     hp = harden_pack(W, False, s_global, scale_bytes, V)
     R = np.asarray(Xq, dtype=np.float64) @ hp["W_final"].astype(np.float64).T - np.asarray(Y_fp, dtype=np.float64)
     return float(alpha) * float(np.sum(R * R))
+
+
+# ----------------------------------------------------------------------------------------------
+# Stage-2 objective on given model outputs (Sec. 3.5 "Stage 2", Eq. 6; Table 2 steps 18-22)
+# ----------------------------------------------------------------------------------------------
+
+def log_softmax_t(Z, tau) -> np.ndarray:
+    """log softmax(Z / tau) along the last axis (Table 2 step 18), float64, max-shifted."""
+    a = np.asarray(Z, dtype=np.float64) / float(tau)
+    a = a - a.max(axis=-1, keepdims=True)
+    return a - np.log(np.exp(a).sum(axis=-1, keepdims=True))
+
+
+def stage2_losses(Z_fp, Z_q, tau, kl_scale, H_fp, H_q, mse_scale, round_losses, lambda_kl, lambda_round) -> dict:
+    """Eq. 6 / Table 2 steps 18-22 on logits Z [T, vocab] and last hidden states H [T, D]:
+
+        P_fp = softmax(Z_fp / tau), P_q = softmax(Z_q / tau)
+        L_KL    = kl_scale  * sum_t sum_j P_fp[t,j] (log P_fp[t,j] - log P_q[t,j])
+        L_MSE   = mse_scale * ||H_fp - H_q||_F^2
+        L_round = sum_l round_losses[l]
+        L       = lambda_kl L_KL + L_MSE + lambda_round L_round
+
+    and the gradients of L with respect to the quantised model's outputs,
+
+        dZ_q = lambda_kl kl_scale / tau * (P_q - P_fp),     dH_q = 2 mse_scale (H_q - H_fp).
+
+    The paper does not say whether the KL is summed or averaged over tokens, nor whether the "MSE" (written
+    as a squared Frobenius norm) is a mean: both scales are arguments (1 = the formulas as printed)."""
+    la, lb = log_softmax_t(Z_fp, tau), log_softmax_t(Z_q, tau)
+    P_fp, P_q = np.exp(la), np.exp(lb)
+    kl = float(kl_scale) * float((P_fp * (la - lb)).sum())
+    dH = np.asarray(H_q, dtype=np.float64) - np.asarray(H_fp, dtype=np.float64)
+    mse = float(mse_scale) * float((dH * dH).sum())
+    rl = float(np.asarray(round_losses, dtype=np.float64).sum()) if round_losses is not None else 0.0
+    return {"L_kl": kl, "L_mse": mse, "L_round": rl,
+            "L": float(lambda_kl) * kl + mse + float(lambda_round) * rl,
+            "dZ_q": float(lambda_kl) * float(kl_scale) / float(tau) * (P_q - P_fp),
+            "dH_q": 2.0 * float(mse_scale) * dH}
