@@ -255,12 +255,86 @@ def run_pack_sweep(args) -> dict:
     }
 
 
+def run_stage2(args) -> dict:
+    """faar_stage2_losses on Llama3-1B-shaped model outputs: 4096 tokens, vocabulary 128256, hidden size 2048,
+    bf16 logits and hidden states, losses and both gradients.  One timed step = one call."""
+    import numpy as np
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+
+    T, V, D, tau = 4096, 128256, 2048, 1.0
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    Zf = (torch.randn((T, V), generator=gen, device="cuda") * 3.0).to(torch.bfloat16)
+    Zq = (Zf.float() + torch.randn((T, V), generator=gen, device="cuda") * 0.3).to(torch.bfloat16)
+    Hf = torch.randn((T, D), generator=gen, device="cuda").to(torch.bfloat16)
+    Hq = (Hf.float() + torch.randn((T, D), generator=gen, device="cuda") * 0.1).to(torch.bfloat16)
+    rl = torch.rand(112, generator=gen, device="cuda")
+    ws = torch.empty(faar.faar_workspace_bytes(fb.OP_STAGE2_LOSSES, V, D, T), dtype=torch.uint8, device="cuda")
+    kw = dict(kl_scale=1.0 / T, mse_scale=1.0 / (T * D), round_losses=rl, lambda_kl=1.0, lambda_round=0.01, ws=ws)
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    for _ in range(max(1, warmup)):
+        losses, dZ, dH = faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        losses, dZ, dH = faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ev = HipEvents()
+    e0, e1 = ev.create(), ev.create()
+    ts = []
+    fb.faar_time_kernel(fb.K_STAGE2_KL, e0.value, e1.value)
+    try:
+        for _ in range(8):
+            faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
+            ts.append(ev.elapsed_ms(e0, e1))
+    finally:
+        fb.faar_time_kernel(fb.K_NONE)
+    ms = sum(ts[2:]) / len(ts[2:])
+    algo = (T * V + T * D) * (2 + 2 + 2)            # read both tensors once, write the gradient (bf16)
+    gbs = algo / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "Stage-2 loss evaluations/sec (KL + MSE + gradients)", "value": round(steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"stage2_losses: logits {T}x{V} bf16 N(0, 3^2), quantised-model logits = those + N(0, 0.3^2); "
+                               f"hidden states {T}x{D} bf16; tau 1; losses and both gradients", "T": T, "vocab": V, "D": D},
+        "tokens_per_sec": round(T * steps / elapsed, 1),
+        "final_losses": losses.cpu().numpy().tolist(),
+        "roofline": {"kernel": "stage2 (KL rows + MSE + sums)", "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "launch_ms": round(ms, 5)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import faar_oracle as fo
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        rows = 64
+        zf, zq = Zf[:rows].float().cpu().numpy(), Zq[:rows].float().cpu().numpy()
+        hf, hq = Hf[:rows].float().cpu().numpy(), Hq[:rows].float().cpu().numpy()
+        n, t_cpu = 0, 0.0
+        while n < 1 or (t_cpu < args.cpu_seconds and n < 50):
+            c0 = time.perf_counter()
+            fo.stage2_losses(zf, zq, tau, 1.0 / T, hf, hq, 1.0 / (T * D), rl.cpu().numpy(), 1.0, 0.01)
+            t_cpu += time.perf_counter() - c0
+            n += 1
+        out["cpu_baseline"] = {"value": round(n * rows / T / t_cpu, 5), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{n} evaluations of {rows} of the {T} token rows (numpy float64, {t_cpu:.1f} s), "
+                                         "scaled to whole steps"}
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep"])
+    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep", "stage2_losses"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -288,6 +362,9 @@ def main() -> int:
         return 0
     if args.workload == "qwen_pack_sweep":
         print(json.dumps(run_pack_sweep(args)))
+        return 0
+    if args.workload == "stage2_losses":
+        print(json.dumps(run_stage2(args)))
         return 0
     O, K, T, gated = WORKLOADS[args.workload]
     W_h = synth.student_t_weight(O, K, seed=0)

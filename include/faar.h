@@ -71,7 +71,8 @@ enum {
   FAAR_OP_SOFTQUANT = 2,
   FAAR_OP_LAYER_PREPARE = 3,
   FAAR_OP_LAYER_STEP = 4,
-  FAAR_OP_HARDEN_PACK = 5
+  FAAR_OP_HARDEN_PACK = 5,
+  FAAR_OP_STAGE2_LOSSES = 6 /* faar_workspace_bytes(op, O = vocabulary, K = hidden size, T = tokens, 0) */
 };
 
 /* kernels of the path, for faar_time_kernel */
@@ -84,7 +85,8 @@ enum {
   FAAR_K_BWD_ADAM = 5,       /* dV, Round Loss, Adam, clip              (faar_layer_step) */
   FAAR_K_QUANT_RTN = 6,      /* the quantise kernel of faar_quant_rtn (not its amax pass) */
   FAAR_K_INIT_V = 7,
-  FAAR_K_HARDEN_PACK = 8
+  FAAR_K_HARDEN_PACK = 8,
+  FAAR_K_STAGE2_KL = 9       /* the three launches of faar_stage2_losses, bracketed together */
 };
 
 /* Library version, MAJOR*10000 + MINOR*100 + PATCH.  Pure host function. */
@@ -260,6 +262,35 @@ int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                      const float* s_global, const uint8_t* scales, const float* V,
                      uint8_t* codes, uint8_t* decisions, void* W_final,
                      unsigned long long* flip_count, void* stream);
+
+/*
+ * The Stage-2 objective evaluated on given outputs of the two models -- Sec. 3.5 "Stage 2", Eq. 6,
+ * Table 2 steps 18-22 (the models that produce the logits and hidden states are not part of this library):
+ *
+ *   P_fp = softmax(Z_fp / tau),  P_q = softmax(Z_q / tau)           row-wise over the vocabulary
+ *   L_KL    = kl_scale  * sum_t sum_j P_fp[t,j] (log P_fp[t,j] - log P_q[t,j])
+ *   L_MSE   = mse_scale * ||H_fp - H_q||_F^2
+ *   L_round = sum_l round_losses[l]
+ *   L       = lambda_kl L_KL + L_MSE + lambda_round L_round
+ *   dZ_q = lambda_kl kl_scale / tau (P_q - P_fp),   dH_q = 2 mse_scale (H_q - H_fp)    (gradients of L)
+ *
+ * The paper does not say whether the KL is summed or averaged over tokens, nor whether its "MSE" (printed as a
+ * squared Frobenius norm) is a mean: kl_scale and mse_scale are arguments (1 = as printed).  float32 arithmetic
+ * with hardware exp / log; row sums are accumulated online (one pass over the logits for the loss, a second
+ * one only when dZ_q is requested) and all sums are finished in a fixed order in double.
+ *
+ *   Z_fp, Z_q   in  [T * vocab] of dtype zdt; vocab a multiple of 8
+ *   H_fp, H_q   in  [T * D] of dtype hdt; D a multiple of 8
+ *   round_losses in, nullable device float[n_layers]
+ *   dZ_q        out, nullable [T * vocab] of dtype zdt (rounded to bf16 if zdt is bf16)
+ *   dH_q        out, nullable [T * D] of dtype hdt
+ *   losses      out float[4]: L_KL, L_MSE, L_round, L
+ *   ws          FAAR_OP_STAGE2_LOSSES workspace
+ */
+int faar_stage2_losses(const void* Z_fp, const void* Z_q, faar_dtype zdt, int64_t T, int64_t vocab, float tau,
+                       float kl_scale, const void* H_fp, const void* H_q, faar_dtype hdt, int64_t D, float mse_scale,
+                       const float* round_losses, int64_t n_layers, float lambda_kl, float lambda_round,
+                       void* dZ_q, void* dH_q, float* losses, void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

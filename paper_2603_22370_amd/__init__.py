@@ -3,4 +3,4 @@ plus a ctypes binding.  Importing the package does not load the library; the fir
 and raises if it has not been built."""
 from .binding import (FaarError, faar_adam, faar_harden_pack, faar_init_v, faar_layer_prepare,  # noqa: F401
                       faar_layer_step, faar_padded_tokens, faar_quant_rtn, faar_softquant_fwd_bwd,
-                      faar_workspace_bytes, layer_step_workspace, lib)
+                      faar_stage2_losses, faar_workspace_bytes, layer_step_workspace, lib)

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libfaar.so")
 
 FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
-OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK = range(6)
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES = range(7)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
 
@@ -70,6 +70,10 @@ def lib() -> ctypes.CDLL:
                                       c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_stage2_losses.restype = c_int
+        L.faar_stage2_losses.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_float, c_float, c_void_p, c_void_p,
+                                         c_int, c_int64, c_float, c_void_p, c_int64, c_float, c_float, c_void_p, c_void_p,
+                                         c_void_p, c_void_p, c_size_t, c_void_p]
         L.faar_harden_pack.restype = c_int
         L.faar_harden_pack.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                        c_void_p, c_void_p, c_void_p, c_void_p]
@@ -108,7 +112,7 @@ def faar_workspace_bytes(op: int, O: int, K: int, T: int = 0, flags: int = 0) ->
     return int(lib().faar_workspace_bytes(op, O, K, T, flags))
 
 
-K_NONE, K_SOFTQUANT_FWD, K_GEMM_RESIDUAL, K_GEMM_DW, K_GEMM_DX, K_BWD_ADAM, K_QUANT_RTN, K_INIT_V, K_HARDEN_PACK = range(9)
+K_NONE, K_SOFTQUANT_FWD, K_GEMM_RESIDUAL, K_GEMM_DW, K_GEMM_DX, K_BWD_ADAM, K_QUANT_RTN, K_INIT_V, K_HARDEN_PACK, K_STAGE2_KL = range(10)
 
 
 def faar_time_kernel(which: int, start_event=None, stop_event=None) -> None:
@@ -227,3 +231,23 @@ def faar_harden_pack(W, s_global, scales, V, want_decisions=False, want_final=Fa
     _check(lib().faar_harden_pack(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(codes),
                                   _ptr(dec), _ptr(Wf), _ptr(flips), _stream()), "faar_harden_pack")
     return codes, dec, Wf, flips
+
+
+def faar_stage2_losses(Z_fp, Z_q, tau, H_fp, H_q, kl_scale=1.0, mse_scale=1.0, round_losses=None, lambda_kl=1.0,
+                       lambda_round=0.0, want_grads=True, ws=None):
+    """-> (losses f32[4] = (L_KL, L_MSE, L_round, L), dZ_q or None, dH_q or None)."""
+    _dev(Z_fp, Z_q, H_fp, H_q, round_losses, ws)
+    T, vocab = Z_fp.shape
+    D = H_fp.shape[1]
+    if Z_q.shape != Z_fp.shape or Z_q.dtype != Z_fp.dtype or H_q.shape != H_fp.shape or H_q.dtype != H_fp.dtype:
+        raise ValueError("Z_fp / Z_q and H_fp / H_q must agree in shape and dtype")
+    losses = torch.empty(4, dtype=torch.float32, device=Z_fp.device)
+    dZ = torch.empty_like(Z_q) if want_grads else None
+    dH = torch.empty_like(H_q) if want_grads else None
+    ws = _workspace(OP_STAGE2_LOSSES, vocab, D, T, device=Z_fp.device) if ws is None else ws
+    n_layers = 0 if round_losses is None else int(round_losses.numel())
+    _check(lib().faar_stage2_losses(_ptr(Z_fp), _ptr(Z_q), _dt(Z_fp), T, vocab, float(tau), float(kl_scale), _ptr(H_fp),
+                                    _ptr(H_q), _dt(H_fp), D, float(mse_scale), _ptr(round_losses), n_layers,
+                                    float(lambda_kl), float(lambda_round), _ptr(dZ), _ptr(dH), _ptr(losses), _ptr(ws),
+                                    ws.numel(), _stream()), "faar_stage2_losses")
+    return losses, dZ, dH

@@ -88,7 +88,7 @@ int faar_version(void) { return 100; }
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
-  if (which < FAAR_K_NONE || which > FAAR_K_HARDEN_PACK) return FAAR_E_ARG;
+  if (which < FAAR_K_NONE || which > FAAR_K_STAGE2_KL) return FAAR_E_ARG;
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
   g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
   return FAAR_OK;
@@ -102,6 +102,10 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T) {
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
 size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags) {
+  if (op == FAAR_OP_STAGE2_LOSSES) {  // O = vocabulary size, K = hidden size, T = tokens
+    if (T <= 0 || O <= 0 || K <= 0 || T > kMaxElems / K) return 0;
+    return align256((size_t)T * sizeof(double)) + align256((size_t)stage2_mse_blocks(T * K) * sizeof(double));
+  }
   if (check_shape(O, K) != FAAR_OK) return 0;
   switch (op) {
     case FAAR_OP_QUANT_RTN:
@@ -299,6 +303,38 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.beta_next = beta_next; a.delta_next = delta; a.wq_full_next = wq_full; a.round_next = round_next;
   Bracket b(FAAR_K_BWD_ADAM, st);
   return hip_status(launch_step_bwd_adam(a, st));
+}
+
+int faar_stage2_losses(const void* Z_fp, const void* Z_q, faar_dtype zdt, int64_t T, int64_t vocab, float tau,
+                       float kl_scale, const void* H_fp, const void* H_q, faar_dtype hdt, int64_t D, float mse_scale,
+                       const float* round_losses, int64_t n_layers, float lambda_kl, float lambda_round, void* dZ_q,
+                       void* dH_q, float* losses, void* ws, size_t ws_bytes, void* stream) {
+  if (!Z_fp || !Z_q || !H_fp || !H_q || !losses) return FAAR_E_NULL;
+  if (int e = check_wdt(zdt)) return e;
+  if (int e = check_wdt(hdt)) return e;
+  if (T <= 0 || vocab <= 0 || D <= 0 || vocab % 8 != 0 || D % 8 != 0 || n_layers < 0) return FAAR_E_SHAPE;
+  if (T > kMaxElems / vocab || T > kMaxElems / D || T > 0x7FFFFFFF) return FAAR_E_SHAPE;
+  if (!(tau > 0.0f) || !std::isfinite(tau) || !std::isfinite(kl_scale) || !std::isfinite(mse_scale) ||
+      !std::isfinite(lambda_kl) || !std::isfinite(lambda_round))
+    return FAAR_E_ARG;
+  if (n_layers > 0 && !round_losses) return FAAR_E_NULL;
+  if (!aligned16(Z_fp) || !aligned16(Z_q) || !aligned16(H_fp) || !aligned16(H_q) || !aligned16(dZ_q) || !aligned16(dH_q) ||
+      !aligned16(ws))
+    return FAAR_E_ARG;
+  const size_t need = align256((size_t)T * sizeof(double)) + align256((size_t)stage2_mse_blocks(T * D) * sizeof(double));
+  if (!ws || ws_bytes < need) return FAAR_E_WORKSPACE;
+  Stage2Args a{};
+  a.Z_fp = Z_fp; a.Z_q = Z_q; a.z_bf16 = zdt == FAAR_BF16; a.T = T; a.vocab = vocab; a.tau = tau; a.kl_scale = kl_scale;
+  a.H_fp = H_fp; a.H_q = H_q; a.h_bf16 = hdt == FAAR_BF16; a.D = D; a.mse_scale = mse_scale;
+  a.round_losses = n_layers > 0 ? round_losses : nullptr; a.n_layers = n_layers;
+  a.lambda_kl = lambda_kl; a.lambda_round = lambda_round;
+  a.dZ_q = dZ_q; a.dH_q = dH_q;
+  a.kl_rows = static_cast<double*>(ws);
+  a.mse_partials = reinterpret_cast<double*>(static_cast<char*>(ws) + align256((size_t)T * sizeof(double)));
+  a.losses = losses;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Bracket b(FAAR_K_STAGE2_KL, st);
+  return hip_status(launch_stage2(a, st));
 }
 
 int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,

@@ -81,6 +81,18 @@ hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, b
 hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
                             hipStream_t st);
 
+// ---- Stage-2 objective on given logits / hidden states (faar_stage2.hip) -------------------
+struct Stage2Args {
+  const void *Z_fp, *Z_q; bool z_bf16; int64_t T, vocab; float tau, kl_scale;
+  const void *H_fp, *H_q; bool h_bf16; int64_t D; float mse_scale;
+  const float* round_losses; int64_t n_layers; float lambda_kl, lambda_round;
+  void *dZ_q, *dH_q;          // nullable outputs, dtypes of Z and H
+  double *kl_rows, *mse_partials;  // workspace: T and stage2_mse_blocks(T*D) doubles
+  float* losses;              // [4]: KL, MSE, Round-Loss sum, total
+};
+int64_t stage2_mse_blocks(int64_t n);
+hipError_t launch_stage2(const Stage2Args& a, hipStream_t st);
+
 // ---- bf16 MFMA GEMMs (faar_gemm.hip) ------------------------------------------------------
 // All GEMMs are "NT": acc[m][n] = sum_k A[m][k] * B[n][k], A [M, lda], B [N, ldb] bf16 row-major
 // with the contraction index contiguous, lda/ldb/Kd multiples of 8.

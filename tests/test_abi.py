@@ -82,6 +82,14 @@ def test_error_codes_without_a_gpu():
     assert st(*args(opt=fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 0))) == -6
     assert st(*args(ws=16)) == -4
     assert st(*args(O=12, dX=p)) == -2                                                     # chained needs O % 8 == 0
+    s2 = L.faar_stage2_losses
+    s2a = lambda **kw: [kw.get("Zf", p), p, 1, kw.get("T", 4), kw.get("V", 64), kw.get("tau", 1.0), 1.0, p, p, 1, kw.get("D", 16), 1.0,
+                        kw.get("rl", nul), kw.get("nl", 0), 1.0, 0.0, nul, nul, p, p, kw.get("ws", big), nul]
+    assert s2(*s2a(Zf=nul)) == -1
+    assert s2(*s2a(V=60)) == -2                                                            # vocabulary not a multiple of 8
+    assert s2(*s2a(tau=0.0)) == -6
+    assert s2(*s2a(nl=3)) == -1                                                            # layers announced, no array
+    assert s2(*s2a(ws=8)) == -4
     hp = L.faar_harden_pack
     assert hp(p, 1, 16, 16, p, p, p, nul, nul, nul, nul, nul) == -1
     assert hp(p, 2, 16, 16, p, p, p, p, nul, nul, nul, nul) == -3
