@@ -109,6 +109,106 @@ k_stage2_kl(const ZT* __restrict__ Zf, const ZT* __restrict__ Zq, int64_t v8, fl
   }
 }
 
+// bf16 rows of up to NC * 1024 chunks (8 logits each): the row of Z_fp stays in registers (packed bf16, NC x 4
+// VGPRs per lane) and the first kLdsChunks chunks per lane of Z_q's row stay in LDS between the loss pass and
+// the gradient pass, so that only the rest of Z_q is read a second time.
+constexpr int kLdsChunks = 9;  // 9 x 1024 lanes x 16 B = 144 KB of the 160 KB LDS
+
+__device__ __forceinline__ void unpack8(const uint4& q, float (&x)[8]) {
+  const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x[2 * i] = __uint_as_float(r[i] << 16);
+    x[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+  }
+}
+
+template <int NC>
+__global__ void __launch_bounds__(kRowThreads)
+k_stage2_kl_resident(const bf16_t* __restrict__ Zf, const bf16_t* __restrict__ Zq, int64_t v8, float inv_tau,
+                     float grad_coef, bf16_t* __restrict__ dZq, double* __restrict__ kl_rows) {
+  static_assert(NC >= kLdsChunks, "the LDS part is a prefix of the per-lane chunks");
+  __shared__ uint4 q_lds[kLdsChunks][kRowThreads];
+  const int64_t row = blockIdx.x;
+  const uint4* zf = reinterpret_cast<const uint4*>(Zf + row * v8 * 8);
+  const uint4* zq = reinterpret_cast<const uint4*>(Zq + row * v8 * 8);
+  const float ninf = -INFINITY;
+  RowStats st{ninf, 0.0f, 0.0f, ninf, 0.0f};
+  uint4 rf[NC];
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int64_t c = threadIdx.x + (int64_t)k * kRowThreads;
+    rf[k] = make_uint4(0u, 0u, 0u, 0u);
+    if (c < v8) {
+      rf[k] = zf[c];
+      const uint4 rq = zq[c];
+      if (k < kLdsChunks) q_lds[k][threadIdx.x] = rq;
+      float a[8], b[8];
+      unpack8(rf[k], a);
+      unpack8(rq, b);
+      float ca = ninf, cb = ninf;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        a[j] *= inv_tau;
+        b[j] *= inv_tau;
+        ca = fmaxf(ca, a[j]);
+        cb = fmaxf(cb, b[j]);
+      }
+      if (ca > st.ma) {
+        const float f = __expf(st.ma - ca);
+        st.sa *= f;
+        st.w *= f;
+        st.ma = ca;
+      }
+      if (cb > st.mb) {
+        st.sb *= __expf(st.mb - cb);
+        st.mb = cb;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float ea = __expf(a[j] - st.ma);
+        st.sa += ea;
+        st.w += ea * (a[j] - b[j]);
+        st.sb += __expf(b[j] - st.mb);
+      }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) st = merge(st, shuffle_xor(st, o));
+  __shared__ RowStats per_wave[kRowThreads / 64];
+  __shared__ RowStats row_stats;
+  if ((threadIdx.x & 63) == 0) per_wave[threadIdx.x >> 6] = st;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    RowStats t = per_wave[0];
+    for (int i = 1; i < kRowThreads / 64; ++i) t = merge(t, per_wave[i]);
+    row_stats = t;
+    kl_rows[row] = static_cast<double>(t.w) / static_cast<double>(t.sa) -
+                   (static_cast<double>(t.ma) - static_cast<double>(t.mb)) -
+                   log(static_cast<double>(t.sa) / static_cast<double>(t.sb));
+  }
+  if (!dZq) return;
+  __syncthreads();
+  const RowStats t = row_stats;
+  const float ia = 1.0f / t.sa, ib = 1.0f / t.sb;
+  uint4* g = reinterpret_cast<uint4*>(dZq + row * v8 * 8);
+#pragma unroll
+  for (int k = 0; k < NC; ++k) {
+    const int64_t c = threadIdx.x + (int64_t)k * kRowThreads;
+    if (c < v8) {
+      const uint4 rq = k < kLdsChunks ? q_lds[k][threadIdx.x] : zq[c];   // each lane reads back its own LDS slots
+      float a[8], b[8];
+      unpack8(rf[k], a);
+      unpack8(rq, b);
+      uint32_t o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        o[j] = f32_to_bf16(grad_coef * (__expf(b[j] * inv_tau - t.mb) * ib - __expf(a[j] * inv_tau - t.ma) * ia));
+      g[c] = make_uint4(o[0] | (o[1] << 16), o[2] | (o[3] << 16), o[4] | (o[5] << 16), o[6] | (o[7] << 16));
+    }
+  }
+}
+
 template <typename HT>
 __global__ void __launch_bounds__(kEltThreads)
 k_stage2_mse(const HT* __restrict__ Hf, const HT* __restrict__ Hq, int64_t n8, float two_scale, HT* __restrict__ dHq,
@@ -187,7 +287,16 @@ int64_t stage2_mse_blocks(int64_t n) {
 hipError_t launch_stage2(const Stage2Args& a, hipStream_t st) {
   const float inv_tau = 1.0f / a.tau;
   const float grad_coef = a.lambda_kl * a.kl_scale * inv_tau;
-  if (a.z_bf16)
+  const int64_t v8 = a.vocab / 8;
+  if (a.z_bf16 && v8 <= 16 * kRowThreads)
+    hipLaunchKernelGGL(k_stage2_kl_resident<16>, dim3(static_cast<unsigned>(a.T)), dim3(kRowThreads), 0, st,
+                       static_cast<const bf16_t*>(a.Z_fp), static_cast<const bf16_t*>(a.Z_q), v8, inv_tau, grad_coef,
+                       static_cast<bf16_t*>(a.dZ_q), a.kl_rows);
+  else if (a.z_bf16 && v8 <= 19 * kRowThreads)
+    hipLaunchKernelGGL(k_stage2_kl_resident<19>, dim3(static_cast<unsigned>(a.T)), dim3(kRowThreads), 0, st,
+                       static_cast<const bf16_t*>(a.Z_fp), static_cast<const bf16_t*>(a.Z_q), v8, inv_tau, grad_coef,
+                       static_cast<bf16_t*>(a.dZ_q), a.kl_rows);
+  else if (a.z_bf16)
     hipLaunchKernelGGL(k_stage2_kl<bf16_t>, dim3(static_cast<unsigned>(a.T)), dim3(kRowThreads), 0, st,
                        static_cast<const bf16_t*>(a.Z_fp), static_cast<const bf16_t*>(a.Z_q), a.vocab / 8, inv_tau, grad_coef,
                        static_cast<bf16_t*>(a.dZ_q), a.kl_rows);

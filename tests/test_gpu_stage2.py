@@ -34,6 +34,9 @@ CASES = [  # T, vocab, D, tau
     (7, 1000, 24, 0.7),             # ragged: fewer chunks than threads
     (3, 8 * 1024 * 3 + 40, 64, 2.0),  # several strides of the workgroup plus a tail
     (33, 32000, 256, 1.0),
+    (3, 128256, 16, 1.0),           # Llama3 vocabulary: the row of Z_fp held in registers (16 chunks per lane)
+    (2, 151936, 16, 0.9),           # Qwen3 vocabulary: 19 chunks per lane
+    (2, 163904, 16, 1.5),           # longer than a register-resident row: two passes over global memory
 ]
 
 
