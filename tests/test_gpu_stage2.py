@@ -2,9 +2,11 @@
 
 Tolerances: the kernel works in float32 with the hardware exp (about 2 ulp).  A row's KL is w/sa - log(sa/sb) - ...
 with sa, sb float32 sums over the vocabulary, each good to about 1e-6 relative, so the row's KL carries an ABSOLUTE
-error of about 1e-6 whatever its size: losses are compared with 1e-5 relative plus 2e-6 per row; gradients per
-element against 2e-6 of the largest gradient of the tensor.  bf16 outputs are the float32 values rounded once
-more: one bf16 ulp."""
+error of about 1e-6 whatever its size: losses are compared with 1e-5 relative plus 2e-6 per row.  The hardware
+exp of an argument of size 10-15 is good to about 1e-6 relative (the argument is scaled by log2 e in float32
+first), so each probability carries that relative error and a logit gradient coef * (P_q - P_fp) is compared per
+element against 3e-6 * coef * (largest probability of the tensor).  bf16 outputs are the float32 values rounded
+once more: one bf16 ulp."""
 import numpy as np
 import pytest
 import torch
@@ -59,7 +61,9 @@ def test_stage2_losses_and_gradients(T, V, D, tau, dtype):
     assert L[3] == pytest.approx(ref["L"], rel=1e-5, abs=2e-6 * kw["kl_scale"] * T * kw["lambda_kl"])
     gz, gh = dZ.float().cpu().numpy().astype(np.float64), dH.float().cpu().numpy().astype(np.float64)
     ulp = 2.0 ** -8 if dtype == "bf16" else 0.0
-    assert np.all(np.abs(gz - ref["dZ_q"]) <= 2e-6 * np.abs(ref["dZ_q"]).max() + ulp * np.abs(ref["dZ_q"]))
+    pmax = max(np.exp(fo.log_softmax_t(Zf, tau)).max(), np.exp(fo.log_softmax_t(Zq, tau)).max())
+    coef = kw["lambda_kl"] * kw["kl_scale"] / tau
+    assert np.all(np.abs(gz - ref["dZ_q"]) <= 3e-6 * coef * pmax + ulp * np.abs(ref["dZ_q"]))
     assert np.all(np.abs(gh - ref["dH_q"]) <= 2e-6 * np.abs(ref["dH_q"]).max() + ulp * np.abs(ref["dH_q"]))
     # loss only: same numbers, no gradient buffers
     l2, z2, h2 = faar.faar_stage2_losses(dev(Zf), dev(Zq), tau, dev(Hf), dev(Hq), round_losses=torch.from_numpy(rl).cuda(),
