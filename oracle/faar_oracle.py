@@ -400,3 +400,42 @@ def stage2_losses(Z_fp, Z_q, tau, kl_scale, H_fp, H_q, mse_scale, round_losses, 
             "L": float(lambda_kl) * kl + mse + float(lambda_round) * rl,
             "dZ_q": float(lambda_kl) * float(kl_scale) / float(tau) * (P_q - P_fp),
             "dH_q": 2.0 * float(mse_scale) * dH}
+
+
+# ----------------------------------------------------------------------------------------------
+# Stochastic rounding candidates (Sec. 3.2, Table 1: "among only 100 stochastic rounding trials ...")
+# ----------------------------------------------------------------------------------------------
+
+def philox4x32_10(counter, key) -> np.ndarray:
+    """Philox-4x32 with 10 rounds (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3", SC'11):
+    counter [..., 4] uint32, key [..., 2] uint32 -> [..., 4] uint32.  A counter-based generator, so that
+    any other implementation can draw exactly the same numbers."""
+    M0, M1 = np.uint64(0xD2511F53), np.uint64(0xCD9E8D57)
+    W0, W1 = np.uint32(0x9E3779B9), np.uint32(0xBB67AE85)
+    c = np.array(counter, dtype=np.uint32).copy()
+    k = np.broadcast_to(np.array(key, dtype=np.uint32), c.shape[:-1] + (2,)).copy()
+    with np.errstate(over="ignore"):
+        for _ in range(10):
+            p0 = M0 * c[..., 0].astype(np.uint64)
+            p1 = M1 * c[..., 2].astype(np.uint64)
+            hi0, lo0 = (p0 >> np.uint64(32)).astype(np.uint32), p0.astype(np.uint32)
+            hi1, lo1 = (p1 >> np.uint64(32)).astype(np.uint32), p1.astype(np.uint32)
+            c = np.stack([hi1 ^ c[..., 1] ^ k[..., 0], lo1, hi0 ^ c[..., 3] ^ k[..., 1], lo0], axis=-1)
+            k = np.stack([k[..., 0] + W0, k[..., 1] + W1], axis=-1)
+    return c
+
+
+def stochastic_v(V_init, seed: int, sample: int) -> np.ndarray:
+    """One stochastic-rounding candidate: v = 1 with probability v_init (the weight's relative position in its
+    interval, Eq. 4), else 0.  The paper reports such trials (Table 1) without defining them; this is the
+    standard unbiased rule.  Element i (row-major) draws word i % 4 of Philox(counter = (i / 4 low, i / 4 high,
+    sample, 0), key = (seed low, seed high)); u = (word >> 8) * 2^-24; up iff u < v_init."""
+    v = np.asarray(V_init, dtype=np.float32)
+    n = v.size
+    blocks = np.arange((n + 3) // 4, dtype=np.uint64)
+    ctr = np.stack([(blocks & np.uint64(0xFFFFFFFF)).astype(np.uint32), (blocks >> np.uint64(32)).astype(np.uint32),
+                    np.full(blocks.shape, np.uint32(sample & 0xFFFFFFFF)), np.zeros(blocks.shape, dtype=np.uint32)], axis=-1)
+    key = np.array([seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF], dtype=np.uint32)
+    words = philox4x32_10(ctr, key).reshape(-1)[:n]
+    u = (words >> np.uint32(8)).astype(np.float32) * np.float32(2.0 ** -24)
+    return (u < v.reshape(-1)).astype(np.float32).reshape(v.shape)

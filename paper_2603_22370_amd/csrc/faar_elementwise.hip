@@ -249,46 +249,6 @@ k_softquant_bwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ 
   if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
 }
 
-// ---- backward + Adam + clip in one pass (Table 2 steps 11-13) ------------------------------
-template <typename WT>
-__global__ void __launch_bounds__(kEltThreads)
-k_bwd_adam(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
-           const uint8_t* __restrict__ scales, float* __restrict__ V, float* __restrict__ M,
-           float* __restrict__ U, float beta, const float* __restrict__ G, int n_split,
-           int64_t split_stride, float lam_over_n, AdamScalars o, double* __restrict__ round_partials) {
-  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
-  float rsum = 0.0f;
-  if (i < n8) {
-    const float s = effective_scale(scales[i >> 1], *s_global_p);
-    float w[8], v[8], g[8], m[8], u[8];
-    W8<WT>::load(W + i * 8, w);
-    load8(V + i * 8, v);
-    load8(M + i * 8, m);
-    load8(U + i * 8, u);
-    load8(G + i * 8, g);
-    for (int sp = 1; sp < n_split; ++sp) {
-      float g2[8];
-      load8(G + sp * split_stride + i * 8, g2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) g[j] += g2[j];
-    }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float rt;
-      const float d = grad_v(g[j], w[j], s, v[j], beta, lam_over_n, rt);
-      rsum += rt;
-      m[j] = o.beta1 * m[j] + (1.0f - o.beta1) * d;
-      u[j] = o.beta2 * u[j] + (1.0f - o.beta2) * (d * d);
-      const float step = o.lr * (m[j] * o.inv_bc1) / (sqrtf(u[j] * o.inv_bc2) + o.eps);
-      v[j] = fminf(fmaxf(v[j] - step, 0.0f), 1.0f);  // V clipped to [0, 1] after every update
-    }
-    store8(V + i * 8, v);
-    store8(M + i * 8, m);
-    store8(U + i * 8, u);
-  }
-  const double bs = block_sum(static_cast<double>(rsum));
-  if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
-}
 
 
 // ---- layer-step kernels on cached interval codes -------------------------------------------
@@ -646,23 +606,6 @@ hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const flo
                        beta, G, n_split, split_stride, lam_over_n, dV, round_partials);
   return hipGetLastError();
 }
-
-hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s_global,
-                           const uint8_t* scales, float* V, float* m, float* u, float beta,
-                           const float* G, int n_split, int64_t split_stride, float lambda_round,
-                           AdamScalars opt, double* round_partials, hipStream_t st) {
-  const int64_t n8 = n / 8;
-  const dim3 g(blocks_for(n8)), b(kEltThreads);
-  const float lam_over_n = static_cast<float>(static_cast<double>(lambda_round) / static_cast<double>(n));
-  if (w_bf16)
-    hipLaunchKernelGGL(k_bwd_adam<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, m, u,
-                       beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
-  else
-    hipLaunchKernelGGL(k_bwd_adam<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, m, u,
-                       beta, G, n_split, split_stride, lam_over_n, opt, round_partials);
-  return hipGetLastError();
-}
-
 
 hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const float* s_global,
                                  const uint8_t* scales, uint8_t* icodes, hipStream_t st) {

@@ -7,15 +7,18 @@
 // (X_q^T, dY^T, W_q^T) are produced in that layout by the kernel that writes them, so one tuned
 // main loop serves all of them.
 //
-// Two main loops:
-//  * k_gemm_dma (the fast path, contraction length a multiple of 32): 256x256 or 256x128 output tile
-//    per 512-thread workgroup (8 wavefronts, 2 per SIMD), BK = 32 slices copied global -> LDS by
-//    global_load_lds_dwordx4 (no VGPR staging) into a 4-stage ring; LDS rows are 64 B, un-padded, with
-//    the 16-byte chunk index XOR-swizzled by (row / 4) % 4 so that the fragment reads of 16 consecutive
-//    rows hit 16 distinct bank groups (measured: zero LDS bank conflicts); fragments are prefetched one
-//    MFMA phase ahead, also across the slice boundary, and the ds_reads / DMA issues are interleaved
-//    one by one between the v_mfma_f32_32x32x16_bf16 instructions; workgroups are dealt to the 8 XCDs
-//    in contiguous chunks of a grouped tile order so that each XCD's L2 sees a compact sub-grid.
+// Three main loops:
+//  * k_gemm_dma64 (contraction length a multiple of 64 -- every GEMM of an LLM-shaped layer): 256x256 or
+//    256x128 output tile per 512-thread workgroup (8 wavefronts, 2 per SIMD), BK = 64 slices copied
+//    global -> LDS by global_load_lds_dwordx4 (no VGPR staging) into two or three stages, 128-byte LDS rows,
+//    v_mfma_f32_16x16x32_bf16, one workgroup barrier per slice.  Described at the kernel.
+//  * k_gemm_dma (contraction length a multiple of 32, and all 128x128 tiles): BK = 32 slices in a 4-stage
+//    ring; LDS rows are 64 B, un-padded, with the 16-byte chunk index XOR-swizzled by (row / 4) % 4 so that the
+//    fragment reads of 16 consecutive rows hit 16 distinct bank groups (measured: zero LDS bank conflicts);
+//    fragments are prefetched one MFMA phase ahead, also across the slice boundary, and the ds_reads / DMA
+//    issues are interleaved one by one between the v_mfma_f32_32x32x16_bf16 instructions.
+//    In both, workgroups are dealt to the 8 XCDs in contiguous chunks of a grouped tile order so that each
+//    XCD's L2 sees a compact sub-grid.
 //  * k_gemm_nt (generic fallback for ragged contraction lengths): 128x128 tile, register-staged,
 //    padded LDS, bounds-checked loads.
 #include "faar_internal.h"

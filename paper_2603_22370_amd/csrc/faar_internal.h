@@ -39,12 +39,7 @@ hipError_t launch_softquant_bwd(const void* W, bool w_bf16, int64_t n, const flo
                                 double* round_partials, hipStream_t st);
 int64_t softquant_bwd_blocks(int64_t n);
 int64_t step_bwd_blocks(int64_t n);
-// Backward + Adam + clip in one pass; same partial layout as launch_softquant_bwd.
 struct AdamScalars { float lr, beta1, beta2, eps, inv_bc1, inv_bc2; };
-hipError_t launch_bwd_adam(const void* W, bool w_bf16, int64_t n, const float* s_global,
-                           const uint8_t* scales, float* V, float* m, float* u, float beta,
-                           const float* G, int n_split, int64_t split_stride, float lambda_round,
-                           AdamScalars opt, double* round_partials, hipStream_t st);
 // Interval codes signbit(w) << 3 | (w == 0 ? 7 : k_lo), two per byte, for the per-step kernels below.
 hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const float* s_global,
                                  const uint8_t* scales, uint8_t* icodes, hipStream_t st);

@@ -196,3 +196,22 @@ def test_flip_count_counts_changed_nibbles():
     changed = np.count_nonzero(fo.unpack_nibbles(hp["codes"]) != fo.unpack_nibbles(q["codes"]))
     assert hp["flip_count"] == changed
     assert 1 <= changed <= 10
+
+
+def test_philox_known_answers_and_stochastic_rounding_statistics():
+    """The generator against the known-answer vectors published with it (Random123 kat_vectors, philox4x32 10
+    rounds), and the candidate sampler against what its definition implies."""
+    kat = [((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+           ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+           ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+            (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1))]
+    for ctr, key, want in kat:
+        got = fo.philox4x32_10(np.array(ctr, dtype=np.uint32), np.array(key, dtype=np.uint32))
+        assert tuple(int(x) for x in got) == want
+    v = np.linspace(0.0, 1.0, 11, dtype=np.float32)[None, :].repeat(20000, axis=0)
+    s = fo.stochastic_v(v, seed=5, sample=3)
+    assert set(np.unique(s)) <= {0.0, 1.0}
+    assert not s[:, 0].any() and s[:, -1].all()                       # v = 0 never goes up, v = 1 always
+    assert np.abs(s.mean(axis=0) - v[0]).max() < 0.015                # unbiased: P(up) = v  (sigma <= 0.0036)
+    assert not np.array_equal(s, fo.stochastic_v(v, seed=5, sample=4))
+    assert np.array_equal(s, fo.stochastic_v(v, seed=5, sample=3))
