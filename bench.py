@@ -337,6 +337,8 @@ def main() -> int:
     ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep", "stage2_losses"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
+    ap.add_argument("--stochastic-trials", type=int, default=0,
+                    help="after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=20)
@@ -413,6 +415,20 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     final_losses = losses.cpu().numpy().tolist()
     n_flips = int(flips.item())
+    # what the optimisation bought, on the hardened (deployable) weights: reconstruction loss of round-to-nearest
+    # against that of the hardened V (outside the timed region)
+    V_rtn, _ = faar.faar_init_v(W, sg, scales)
+    loss_rtn = float(faar.faar_hardened_loss(W, sg, scales, V_rtn, Xq, C, alpha, ws, x_scale=x_scale).item())
+    loss_faar = float(faar.faar_hardened_loss(W, sg, scales, V, Xq, C, alpha, ws, x_scale=x_scale).item())
+    stochastic = None
+    if args.stochastic_trials > 0:
+        trial = torch.empty(args.stochastic_trials, dtype=torch.float32, device="cuda")
+        for k in range(args.stochastic_trials):
+            Vs = faar.faar_stochastic_v(W, sg, scales, 2603, k)
+            faar.faar_hardened_loss(W, sg, scales, Vs, Xq, C, alpha, ws, x_scale=x_scale, loss=trial[k:k + 1])
+        tl = trial.cpu().numpy()
+        stochastic = {"trials": int(tl.size), "better_than_rtn": int((tl < loss_rtn).sum()), "best": float(tl.min()),
+                      "mean": float(tl.mean()), "std": float(tl.std())}
 
     # per-kernel durations: HIP events recorded by the library around each launch of one kernel
     ev = HipEvents()
@@ -495,6 +511,7 @@ def main() -> int:
         "weight_elems_per_sec": round(N * args.steps / elapsed, 1),
         "step_gemm_tflops": round(2 * gemm_flops / (ms_per_step * 1e-3) / 1e12, 1),
         "dw_split": dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
+        "hardened_loss": {"rtn": loss_rtn, "faar": loss_faar, "stochastic": stochastic},
         "roofline": roofline, "kernels": kernels,
     }
 

@@ -264,6 +264,35 @@ int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                      unsigned long long* flip_count, void* stream);
 
 /*
+ * One stochastic-rounding candidate (the trials of Sec. 3.2 / Table 1, which the paper reports without defining
+ * them; this is the standard unbiased rule): V[i] = 1 with probability v_init[i] (Eq. 4), else 0.  Element i
+ * (row-major) draws word i % 4 of Philox-4x32-10(counter = (i / 4 low, i / 4 high, sample, 0), key = (seed low,
+ * seed high)); u = (word >> 8) * 2^-24; V[i] = (u < v_init[i]).  The result is a valid V for
+ * faar_harden_pack and faar_hardened_loss.
+ *
+ *   V  out float[O*K]
+ */
+int faar_stochastic_v(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                      const float* s_global, const uint8_t* scales,
+                      unsigned long long seed, uint32_t sample, float* V, void* stream);
+
+/*
+ * Reconstruction loss of the HARDENED weights of a rounding candidate -- Eq. 5's first term at the weights of
+ * Eq. 7:  loss = mse_scale * || Xq W_final(V)^T - Y_fp ||_F^2  with W_final = sign * node * block scale * tensor
+ * scale in float32 -- what an NVFP4 decoder produces from the bytes faar_harden_pack writes (not rounded to bf16).
+ * Computed like a step's forward half: the bf16 matrix cores see W_final - W and the per-layer constant C.
+ * V = V_init gives the loss of round-to-nearest.
+ *
+ *   Xq, x_scale, C  as for / from faar_layer_prepare
+ *   loss            out device float[1]
+ *   ws              FAAR_OP_LAYER_STEP workspace (contents destroyed: a prepared forward is lost)
+ */
+int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                       const float* s_global, const uint8_t* scales, const float* V,
+                       const void* Xq, const float* x_scale, const float* C, int64_t T,
+                       float mse_scale, float* loss, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * The Stage-2 objective evaluated on given outputs of the two models -- Sec. 3.5 "Stage 2", Eq. 6,
  * Table 2 steps 18-22 (the models that produce the logits and hidden states are not part of this library):
  *

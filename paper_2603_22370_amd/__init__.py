@@ -1,6 +1,7 @@
 """MI355X-native FAAR layer-step library: hand-written HIP kernels behind a C ABI (libfaar.so)
 plus a ctypes binding.  Importing the package does not load the library; the first call does,
 and raises if it has not been built."""
-from .binding import (FaarError, faar_adam, faar_harden_pack, faar_init_v, faar_layer_prepare,  # noqa: F401
+from .binding import (FaarError, faar_adam, faar_harden_pack, faar_hardened_loss, faar_init_v,  # noqa: F401
+                      faar_layer_prepare, faar_stochastic_v,
                       faar_layer_step, faar_padded_tokens, faar_quant_rtn, faar_softquant_fwd_bwd,
                       faar_stage2_losses, faar_workspace_bytes, layer_step_workspace, lib)

@@ -70,6 +70,12 @@ def lib() -> ctypes.CDLL:
                                       c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_stochastic_v.restype = c_int
+        L.faar_stochastic_v.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, ctypes.c_ulonglong, c_uint32,
+                                        c_void_p, c_void_p]
+        L.faar_hardened_loss.restype = c_int
+        L.faar_hardened_loss.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_void_p, c_int64, c_float, c_void_p, c_void_p, c_size_t, c_void_p]
         L.faar_stage2_losses.restype = c_int
         L.faar_stage2_losses.argtypes = [c_void_p, c_void_p, c_int, c_int64, c_int64, c_float, c_float, c_void_p, c_void_p,
                                          c_int, c_int64, c_float, c_void_p, c_int64, c_float, c_float, c_void_p, c_void_p,
@@ -251,3 +257,25 @@ def faar_stage2_losses(Z_fp, Z_q, tau, H_fp, H_q, kl_scale=1.0, mse_scale=1.0, r
                                     float(lambda_kl), float(lambda_round), _ptr(dZ), _ptr(dH), _ptr(losses), _ptr(ws),
                                     ws.numel(), _stream()), "faar_stage2_losses")
     return losses, dZ, dH
+
+
+def faar_stochastic_v(W, s_global, scales, seed, sample):
+    """-> V f32 [O,K] in {0,1}: up with probability v_init, drawn from Philox keyed by (seed, sample)."""
+    _dev(W, s_global, scales)
+    O, K = W.shape
+    V = torch.empty((O, K), dtype=torch.float32, device=W.device)
+    _check(lib().faar_stochastic_v(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), int(seed), int(sample), _ptr(V),
+                                   _stream()), "faar_stochastic_v")
+    return V
+
+
+def faar_hardened_loss(W, s_global, scales, V, Xq, C, mse_scale, ws, x_scale=None, loss=None):
+    """-> loss f32[1]: mse_scale * ||Xq W_final(V)^T - Y_fp||^2 for the hardened V (ws: a layer-step workspace)."""
+    _dev(W, s_global, scales, V, Xq, C, ws, x_scale, loss)
+    O, K = W.shape
+    T = Xq.shape[0]
+    loss = torch.empty(1, dtype=torch.float32, device=W.device) if loss is None else loss
+    _check(lib().faar_hardened_loss(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(Xq), _ptr(x_scale),
+                                    _ptr(C), T, float(mse_scale), _ptr(loss), _ptr(ws), ws.numel(), _stream()),
+           "faar_hardened_loss")
+    return loss

@@ -305,6 +305,41 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   return hip_status(launch_step_bwd_adam(a, st));
 }
 
+int faar_stochastic_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                      const uint8_t* scales, unsigned long long seed, uint32_t sample, float* V, void* stream) {
+  if (!W || !s_global || !scales || !V) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (!aligned16(W) || !aligned16(V)) return FAAR_E_ARG;
+  return hip_status(launch_stochastic_v(W, wdt == FAAR_BF16, O * K, s_global, scales, seed, sample, V,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                       const uint8_t* scales, const float* V, const void* Xq, const float* x_scale, const float* C,
+                       int64_t T, float mse_scale, float* loss, void* ws, size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !V || !Xq || !C || !loss) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
+  if (!std::isfinite(mse_scale)) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(Xq) || !aligned16(C) || !aligned16(ws)) return FAAR_E_ARG;
+  const StepLayout L = step_layout(O, K, T, false);
+  if (!ws || ws_bytes < L.total) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(ws);
+  bf16_t* delta = reinterpret_cast<bf16_t*>(base + L.delta);
+  bf16_t* dYt = reinterpret_cast<bf16_t*>(base + L.dYt);
+  double* mse_p = reinterpret_cast<double*>(base + L.mse_partials);
+  if (int e = hip_status(launch_hardened_delta(W, wdt == FAAR_BF16, O * K, s_global, scales, V, delta, st))) return e;
+  int64_t n_mse = 0;
+  const GemmDims d1{T, O, K, K, K};
+  if (int e = hip_status(launch_gemm_residual(static_cast<const bf16_t*>(Xq), delta, d1, C, x_scale, 2.0f * mse_scale, dYt,
+                                              L.Tp, nullptr, mse_p, &n_mse, st)))
+    return e;
+  return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, nullptr, 0, 0.0, 0.0f, loss, nullptr, nullptr, st));
+}
+
 int faar_stage2_losses(const void* Z_fp, const void* Z_q, faar_dtype zdt, int64_t T, int64_t vocab, float tau,
                        float kl_scale, const void* H_fp, const void* H_q, faar_dtype hdt, int64_t D, float mse_scale,
                        const float* round_losses, int64_t n_layers, float lambda_kl, float lambda_round, void* dZ_q,

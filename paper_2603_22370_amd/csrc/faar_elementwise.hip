@@ -451,6 +451,71 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
   }
 }
 
+// ---- stochastic-rounding candidates and the loss of a hardened candidate (Sec. 3.2, Table 1) ----
+// Philox-4x32 with 10 rounds (Salmon et al., SC'11): counter-based, so any implementation draws the same words.
+__device__ __forceinline__ uint4 philox4x32_10(uint4 c, uint2 k) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c.x), lo0 = 0xD2511F53u * c.x;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c.z), lo1 = 0xCD9E8D57u * c.z;
+    c = make_uint4(hi1 ^ c.y ^ k.x, lo1, hi0 ^ c.w ^ k.y, lo0);
+    k.x += 0x9E3779B9u;
+    k.y += 0xBB67AE85u;
+  }
+  return c;
+}
+
+// v = 1 with probability v_init (Eq. 4), else 0: element i draws word i % 4 of
+// Philox(counter = (i / 4 low, i / 4 high, sample, 0), key = seed); u = (word >> 8) * 2^-24; up iff u < v_init
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_stochastic_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+               const uint8_t* __restrict__ scales, uint32_t seed_lo, uint32_t seed_hi, uint32_t sample,
+               float* __restrict__ V) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float s = effective_scale(scales[i >> 1], *s_global_p);
+  float w[8], v[8];
+  W8<WT>::load(W + i * 8, w);
+  uint32_t word[8];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint64_t blk = static_cast<uint64_t>(i) * 2 + h;
+    const uint4 r = philox4x32_10(make_uint4(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), sample, 0u),
+                                  make_uint2(seed_lo, seed_hi));
+    word[4 * h] = r.x; word[4 * h + 1] = r.y; word[4 * h + 2] = r.z; word[4 * h + 3] = r.w;
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float u = static_cast<float>(word[j] >> 8) * 0x1p-24f;
+    v[j] = u < find_interval(w[j], s).v_init ? 1.0f : 0.0f;
+  }
+  store8(V + i * 8, v);
+}
+
+// delta = bf16(W_final - W) with W_final = sign * node * block scale * tensor scale in float32 (the value an
+// NVFP4 decoder produces, not rounded to W's storage type): the perturbation whose reconstruction loss ranks a
+// rounding candidate
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_hardened_delta(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+                 const uint8_t* __restrict__ scales, const float* __restrict__ V, bf16_t* __restrict__ delta) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  const float sg = *s_global_p;
+  const float sgv = e4m3_value(scales[i >> 1]);
+  const float s = sgv * sg;
+  float w[8], v[8], out[8];
+  W8<WT>::load(W + i * 8, w);
+  load8(V + i * 8, v);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int k_lo = interval_index(normalised(w[j], s));
+    out[j] = dequant(nibble(w[j], k_lo, v[j] >= 0.5f), sgv, sg) - w[j];
+  }
+  store_bf16x8(delta + i * 8, out);
+}
+
 // ---- bf16 transpose with zero padding (X_q^T for the dW GEMM) -------------------------------
 // 64 x 64 tiles through LDS; 16-byte global accesses on both sides (rows of the tile are 128 contiguous bytes).
 // The LDS row pitch of 33 words makes the transposed 2-byte reads of a wavefront hit 32 distinct banks.
@@ -660,6 +725,29 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
   const LossSums f{mse_partials, n_mse, mse_scale, round_partials, n_round, inv_n, lambda_round,
                    loss_mse, loss_round, loss_total};
   hipLaunchKernelGGL(k_finalize_losses, dim3(1), dim3(kEltThreads), 0, st, f);
+  return hipGetLastError();
+}
+
+hipError_t launch_stochastic_v(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                               uint64_t seed, uint32_t sample, float* V, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  const uint32_t lo = static_cast<uint32_t>(seed), hi = static_cast<uint32_t>(seed >> 32);
+  if (w_bf16)
+    hipLaunchKernelGGL(k_stochastic_v<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, lo, hi, sample, V);
+  else
+    hipLaunchKernelGGL(k_stochastic_v<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, lo, hi, sample, V);
+  return hipGetLastError();
+}
+
+hipError_t launch_hardened_delta(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                                 const float* V, bf16_t* delta, hipStream_t st) {
+  const int64_t n8 = n / 8;
+  const dim3 g(blocks_for(n8)), b(kEltThreads);
+  if (w_bf16)
+    hipLaunchKernelGGL(k_hardened_delta<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, delta);
+  else
+    hipLaunchKernelGGL(k_hardened_delta<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, delta);
   return hipGetLastError();
 }
 

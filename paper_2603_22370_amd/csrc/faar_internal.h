@@ -76,6 +76,13 @@ hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, b
 hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
                             hipStream_t st);
 
+// V = 1 with probability v_init else 0, from Philox-4x32-10 keyed by (seed, sample)
+hipError_t launch_stochastic_v(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                               uint64_t seed, uint32_t sample, float* V, hipStream_t st);
+// delta = bf16(W_final(V) - W) for the hardened V
+hipError_t launch_hardened_delta(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
+                                 const float* V, bf16_t* delta, hipStream_t st);
+
 // ---- Stage-2 objective on given logits / hidden states (faar_stage2.hip) -------------------
 struct Stage2Args {
   const void *Z_fp, *Z_q; bool z_bf16; int64_t T, vocab; float tau, kl_scale;

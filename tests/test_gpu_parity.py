@@ -441,6 +441,31 @@ def test_nvfp4_activations_in_units_of_their_tensor_scale():
         _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
 
 
+def test_stochastic_candidates_and_hardened_loss():
+    """Candidate sampler bit-exact against the oracle's Philox draw; hardened reconstruction loss of arbitrary,
+    round-to-nearest and sampled V against the oracle's float64 evaluation of the packed weights."""
+    for name, W, isbf in WCASES[:3]:
+        q = fo.quant_rtn(W, isbf)
+        Wd = dev(W, isbf)
+        sg, scales, _, _ = faar.faar_quant_rtn(Wd)
+        V0 = fo.init_v(W, q["s_global"], q["scales"])["V"]
+        for seed, sample in ((0, 0), (2 ** 40 + 17, 99)):
+            Vs = faar.faar_stochastic_v(Wd, sg, scales, seed, sample)
+            assert np.array_equal(host(Vs), fo.stochastic_v(V0, seed, sample)), name
+    for c in (LCASES[0], LCASES[1], LCASES[3]):
+        Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
+        alpha = 1.0 / (c.T * c.O)
+        ws = faar.layer_step_workspace(c.O, c.K, c.T)
+        V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+        cands = {"rtn": V0, "planted": synth.rounding_variables(c.O, c.K, 3), "sampled": fo.stochastic_v(V0, 7, 1)}
+        got = {}
+        for k, V in cands.items():
+            got[k] = float(faar.faar_hardened_loss(Wd, sg, scales, dev(V), Xq, C, alpha, ws).item())
+            want = fo.hardened_loss(c.W, c.w_is_bf16, q["s_global"], q["scales"], V, c.Xq, c.Y_fp, alpha)
+            assert got[k] == pytest.approx(want, rel=TOL_EXACT), (c.name, k)
+        assert got["rtn"] < got["planted"]          # arbitrary decisions are worse than round-to-nearest
+
+
 def test_full_size_q_proj_step_and_pack():
     """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
     X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
