@@ -466,6 +466,48 @@ def test_stochastic_candidates_and_hardened_loss():
         assert got["rtn"] < got["planted"]          # arbitrary decisions are worse than round-to-nearest
 
 
+def test_steps_captured_in_a_hip_graph_replay_identically():
+    """Every entry point only enqueues kernels on the caller's stream (no allocation, host copy, memset or
+    synchronisation), so a run of steps can be captured once and replayed.  Each replay starts from the same
+    state and must reproduce the eager results bit for bit; eager work and synchronisations sit between replays."""
+    c = synth.config1(0)
+    Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
+    alpha = 1.0 / (c.T * c.O)
+    ws = faar.layer_step_workspace(c.O, c.K, c.T)
+    V0, _ = faar.faar_init_v(Wd, sg, scales)
+    betas = [4.0, 8.0, 12.0, 16.0]
+
+    def run_steps(V, m, u, losses):
+        for i, beta in enumerate(betas):
+            faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, C, ic, beta, 0.01, alpha, 1e-2, 0.9, 0.999, 1e-8, i + 1,
+                                 losses[i], ws, beta_next=betas[i + 1] if i + 1 < len(betas) else 0.0, forward_ready=i > 0)
+
+    V, m, u = V0.clone(), torch.zeros_like(V0), torch.zeros_like(V0)
+    losses = torch.zeros((len(betas), 3), dtype=torch.float32, device="cuda")
+    run_steps(V, m, u, losses)
+    torch.cuda.synchronize()
+    want = [x.clone() for x in (V, m, u, losses)]
+
+    gV, gm, gu = V0.clone(), torch.zeros_like(V0), torch.zeros_like(V0)
+    glosses = torch.zeros_like(losses)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_steps(gV, gm, gu, glosses)            # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        run_steps(gV, gm, gu, glosses)
+    for _ in range(3):
+        gV.copy_(V0); gm.zero_(); gu.zero_(); glosses.zero_()      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip((gV, gm, gu, glosses), want):
+            assert torch.equal(a, b)
+
+
 def test_full_size_q_proj_step_and_pack():
     """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
     X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
