@@ -15,7 +15,8 @@
  *    as void*; NULL is the default stream).  Scalar results are written to device memory.
  *  - Device buffers must be 16-byte aligned.  Buffers must not overlap unless stated.
  *  - Scratch memory comes from a caller-provided workspace `ws` of at least
- *    faar_workspace_bytes(op, ...) bytes; its contents are undefined after the call.
+ *    faar_workspace_bytes(op, ...) bytes; its contents are undefined after the call (one exception:
+ *    faar_layer_step can leave the next step's forward outputs there, see beta_next).
  *  - Return value: FAAR_OK, or a negative error code, in which case NOTHING was launched.
  *    FAAR_E_HIP means a HIP call failed; the raw hipError_t is kept per host thread and read
  *    with faar_last_hip_error().  No other global mutable state exists.
