@@ -508,6 +508,34 @@ def test_steps_captured_in_a_hip_graph_replay_identically():
             assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("O,K,T", [(1, 16, 1), (8, 16, 3), (3, 32, 65), (130, 48, 1)])
+def test_smallest_layers_run_the_whole_path(O, K, T):
+    """Degenerate sizes: a single scale block, a single token, fewer rows than a lane group; every GEMM is one
+    partly filled tile of the generic kernel.  Quantise, prepare, two steps (the second with a prepared forward),
+    harden and pack, all against the oracle."""
+    c = synth.llm_linear(f"tiny_{O}x{K}_T{T}", O, K, T, 50 + O)
+    Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
+    V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+    V, _ = faar.faar_init_v(Wd, sg, scales)
+    assert np.array_equal(host(V), V0)
+    m, u = torch.zeros_like(V), torch.zeros_like(V)
+    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+    ws = faar.layer_step_workspace(O, K, T)
+    alpha = 1.0 / (T * O)
+    Vo, mo, uo = V0, np.zeros_like(V0), np.zeros_like(V0)
+    for t, beta in ((1, 6.0), (2, 9.0)):
+        faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, C, ic, beta, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"],
+                             HYP["beta2"], HYP["eps"], t, losses, ws, beta_next=9.0 if t == 1 else 0.0, forward_ready=t == 2)
+        r = fo.layer_step(c.W, q["s_global"], q["scales"], Vo, mo, uo, c.Xq, c.Y_fp, beta, HYP["lambda_round"], alpha,
+                          HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], t)
+        L = host(losses)
+        assert L[0] == pytest.approx(r["L_mse"], rel=2 * TOL_EXACT, abs=1e-12)   # a handful of terms: no averaging
+        assert L[1] == pytest.approx(r["L_round"], rel=1e-5, abs=1e-7)
+        Vo, mo, uo = host(V).copy(), host(m).copy(), host(u).copy()               # re-synchronise
+    codes, _, _, _ = faar.faar_harden_pack(Wd, sg, scales, V)
+    assert np.array_equal(host(codes), fo.harden_pack(c.W, True, q["s_global"], q["scales"], host(V))["codes"])
+
+
 def test_full_size_q_proj_step_and_pack():
     """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
     X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
