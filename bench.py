@@ -347,7 +347,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path has no collectives or sharding "
-              "(see DESIGN.md, 'More than one GPU'). Use --gpus 1.", file=sys.stderr)
+              "(layers and output rows are independent jobs: shard those across processes). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -1,6 +1,6 @@
 """GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
-Integer / byte / index results bit-exact; float results within the tolerances derived in
-the design doc (bf16 tensor-core path vs float64 oracle)."""
+Integer / byte / index results bit-exact; float results within the tolerances stated at TOL_EXACT below
+(bf16 matrix-core path vs float64 oracle)."""
 import numpy as np
 import pytest
 import torch
