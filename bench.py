@@ -51,6 +51,8 @@ def bytes_per_weight(dw_split: int) -> dict:
         "quant_rtn": 2 + 0.5 + 1 / 16,                         # read W; write codes, scales
         "init_v": 2 + 1 / 16 + 4,                              # read W, scales; write V
         "harden_pack": 2 + 4 + 1 / 16 + 0.5,                   # read W, V, scales; write codes
+        # stand-alone call: forward reads W, V, scale and writes W_q - W; backward reads dW_q, W, V, scale and writes dV
+        "softquant_fwd_bwd_call": (2 + 4 + 1 / 16 + 2) + (4 + 2 + 4 + 1 / 16 + 4),
     }
 
 
@@ -459,6 +461,18 @@ def main() -> int:
     probe["softquant_fwd"] = timed_kernel(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
     for name, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
         probe[name] = timed_kernel(kid, step_call, n_probe)
+    # the stand-alone soft-quantisation entry point (forward + backward from a given dL/dW_q; it re-derives the
+    # intervals from W and the scales on every call): torch events around the whole call, output allocation included
+    dWt = torch.randn((O, K), device="cuda") * 1e-3
+    te0, te1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(n_probe + 3):
+        if i == 3:
+            te0.record()
+        faar.faar_softquant_fwd_bwd(W, sg, scales, V, 16.0, dWt=dWt, lambda_round=lam, emit_delta=True)
+    te1.record()
+    torch.cuda.synchronize()
+    probe["softquant_fwd_bwd_call"] = te0.elapsed_time(te1) / n_probe
+    del dWt
     probe["quant_rtn"] = timed_kernel(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(W, ws=ws_q), n_probe)
     probe["init_v"] = timed_kernel(fb.K_INIT_V, lambda i: faar.faar_init_v(W, sg, scales), n_probe)
     probe["harden_pack"] = timed_kernel(fb.K_HARDEN_PACK, lambda i: faar.faar_harden_pack(W, sg, scales, V), n_probe)
