@@ -542,7 +542,7 @@ def main() -> int:
         m0 = np.zeros_like(V0)
         u0 = np.zeros_like(V0)
         n_cpu, t_cpu = 0, 0.0
-        while n_cpu < 1 or (t_cpu < args.cpu_seconds and n_cpu < 20):
+        while n_cpu < 1 or (t_cpu < args.cpu_seconds and n_cpu < 500):
             c0 = time.perf_counter()
             r = fo.layer_step(W_h, q["s_global"], q["scales"], V0, m0, u0, X_h, Y_h,
                               beta_at(n_cpu + 1, args.steps), lam, alpha, lr, 0.9, 0.999, 1e-8, n_cpu + 1)
