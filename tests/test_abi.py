@@ -101,3 +101,19 @@ def test_missing_library_is_a_loud_error(monkeypatch):
     monkeypatch.setattr(fb, "LIB_PATH", "/nonexistent/libfaar.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         fb.lib()
+
+
+def test_token_split_of_the_dw_gemm_is_sane():
+    """faar_dw_split is pure host logic (the GEMM planner): 1..8 splits, at least 512 tokens per split, no
+    empty split, and the workspace grows with it."""
+    for O, K, T in [(2048, 2048, 4096), (512, 2048, 4096), (8192, 2048, 4096), (2048, 8192, 4096), (6144, 2048, 16384),
+                    (1024, 2048, 16384), (256, 256, 64), (96, 80, 100), (16, 16, 1), (12288, 64, 2048)]:
+        s = fb.faar_dw_split(O, K, T)
+        Tp = fb.faar_padded_tokens(T)
+        assert 1 <= s <= 16, (O, K, T, s)
+        assert s == 1 or Tp // s >= 512, (O, K, T, s)
+        assert fb.faar_workspace_bytes(fb.OP_LAYER_STEP, O, K, T) >= s * O * K * 4
+    assert fb.faar_dw_split(0, 16, 8) == 0 and fb.faar_dw_split(16, 8, 8) == 0      # invalid shapes
+    # small outputs with a long token axis split; large outputs do not
+    assert fb.faar_dw_split(512, 2048, 4096) > 1
+    assert fb.faar_dw_split(8192, 2048, 4096) == 1
