@@ -32,12 +32,16 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 
-# name -> (O, K, T, gated_input): linears of the Llama3-1B-shaped (T = 4096) and Qwen3-1.7B-shaped (T = 8192) blocks
+# name -> (O, K, T, gated_input): linears of the Llama3-1B-shaped (T = 4096), Qwen3-1.7B-shaped (T = 8192) and
+# Llama3-8B-shaped (T = 4096) blocks
 WORKLOADS = {
     "q_proj": (2048, 2048, 4096, False), "k_proj": (512, 2048, 4096, False),
     "gate_proj": (8192, 2048, 4096, False), "down_proj": (2048, 8192, 4096, True),
     "qwen_k_proj": (1024, 2048, 8192, False), "qwen_q_proj": (2048, 2048, 8192, False),
     "qwen_gate_proj": (6144, 2048, 8192, False), "qwen_down_proj": (2048, 6144, 8192, True),
+    # Llama3-8B-shaped linears (the paper's larger model), T = 4096
+    "llama8b_q_proj": (4096, 4096, 4096, False), "llama8b_k_proj": (1024, 4096, 4096, False),
+    "llama8b_gate_proj": (14336, 4096, 4096, False), "llama8b_down_proj": (4096, 14336, 4096, True),
 }
 
 
