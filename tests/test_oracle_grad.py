@@ -248,3 +248,23 @@ def test_optimisation_reduces_the_hardened_loss_on_config1():
         first = r["L_mse"] if first is None else first
     L_end = fo.hardened_loss(c.W, False, sg, sb, V, c.Xq, c.Y_fp, alpha)
     assert L_end < L_rtn
+
+
+def test_adam_matches_a_library_optimiser_over_several_steps():
+    """Moments, bias correction and step size against torch.optim.Adam (float64, no weight decay), with the
+    clip to [0, 1] applied to both after every update."""
+    import torch
+    rng = np.random.default_rng(12)
+    V = rng.uniform(0.05, 0.95, size=(6, 16))
+    p = torch.tensor(V.copy(), dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([p], lr=3e-2, betas=(0.9, 0.999), eps=1e-8)
+    m = np.zeros_like(V)
+    u = np.zeros_like(V)
+    for t in range(1, 8):
+        g = rng.standard_normal(V.shape) * (1.0 if t % 2 else 1e-3)
+        V, m, u = fo.adam_update(V, m, u, g, 3e-2, 0.9, 0.999, 1e-8, t)
+        p.grad = torch.tensor(g)
+        opt.step()
+        with torch.no_grad():
+            p.clamp_(0.0, 1.0)
+        assert np.allclose(np.asarray(V, dtype=np.float64), p.detach().numpy(), rtol=1e-6, atol=1e-7), t
