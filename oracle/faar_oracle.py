@@ -392,7 +392,11 @@ def stage2_losses(Z_fp, Z_q, tau, kl_scale, H_fp, H_q, mse_scale, round_losses, 
     as a squared Frobenius norm) is a mean: both scales are arguments (1 = the formulas as printed)."""
     la, lb = log_softmax_t(Z_fp, tau), log_softmax_t(Z_q, tau)
     P_fp, P_q = np.exp(la), np.exp(lb)
-    kl = float(kl_scale) * float((P_fp * (la - lb)).sum())
+    # a logit of -inf (a masked vocabulary entry) has probability 0; the KL divergence takes 0 log 0 = 0, so an
+    # entry with P_fp = 0 contributes nothing whatever P_q is, and P_q = 0 under P_fp > 0 makes the sum +inf
+    with np.errstate(invalid="ignore"):
+        terms = np.where(P_fp > 0.0, P_fp * (la - lb), 0.0)
+    kl = float(kl_scale) * float(terms.sum())
     dH = np.asarray(H_q, dtype=np.float64) - np.asarray(H_fp, dtype=np.float64)
     mse = float(mse_scale) * float((dH * dH).sum())
     rl = float(np.asarray(round_losses, dtype=np.float64).sum()) if round_losses is not None else 0.0

@@ -78,3 +78,25 @@ def test_gradients_by_central_finite_differences():
         e = np.zeros_like(Hq); e[i, j] = eps
         fd = (L(Zq, Hq + e) - L(Zq, Hq - e)) / (2 * eps)
         assert r["dH_q"][i, j] == pytest.approx(fd, rel=1e-6, abs=1e-10)
+
+
+def test_masked_logits_follow_the_zero_log_zero_convention():
+    """Logits of -inf (masked vocabulary entries) have probability 0.  An entry with P_fp = 0 contributes nothing to
+    KL(P_fp || P_q) whatever P_q is; P_q = 0 where P_fp > 0 makes it +inf: the library relative entropy
+    (rel_entr(0, y) = 0, rel_entr(x, 0) = inf) on library softmaxes, and the restriction to the unmasked entries."""
+    Zf, Zq, Hf, Hq = _rand(4, 24, 3, 5)
+    Zf[:, 3] = -np.inf                      # masked in both models
+    Zq[:, 3] = -np.inf
+    Zf[1, 7] = -np.inf                      # masked in the full-precision model only
+    Zf[2, :5] = -np.inf                     # a masked prefix (the running maximum starts at -inf)
+    r = fo.stage2_losses(Zf, Zq, 1.4, 1.0, Hf, Hq, 1.0, None, 1.0, 0.0)
+    Pf, Pq = np.exp(log_softmax(Zf / 1.4, axis=-1)), np.exp(log_softmax(Zq / 1.4, axis=-1))
+    assert np.isfinite(r["L_kl"]) and r["L_kl"] == pytest.approx(rel_entr(Pf, Pq).sum(), rel=1e-12)
+    assert np.isfinite(r["dZ_q"]).all() and not r["dZ_q"][:, 3].any()
+    # masking an entry in both models is the same as deleting it
+    keep = [j for j in range(24) if j != 3]
+    r_del = fo.stage2_losses(Zf[:, keep], Zq[:, keep], 1.4, 1.0, Hf, Hq, 1.0, None, 1.0, 0.0)
+    assert r["L_kl"] == pytest.approx(r_del["L_kl"], rel=1e-12)
+    Zq2 = Zq.copy()
+    Zq2[0, 9] = -np.inf                     # P_q = 0 where P_fp > 0
+    assert fo.stage2_losses(Zf, Zq2, 1.4, 1.0, Hf, Hq, 1.0, None, 1.0, 0.0)["L_kl"] == np.inf
