@@ -1,4 +1,3 @@
-#!/usr/bin/env python3
 """Benchmark of the FAAR per-layer rounding-optimisation path on one MI355X.
 
 Default workload (N=1): the Llama3-1B-shaped attention projection of the second configuration --

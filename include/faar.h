@@ -16,7 +16,8 @@
  *  - Device buffers must be 16-byte aligned.  Buffers must not overlap unless stated.
  *  - Scratch memory comes from a caller-provided workspace `ws` of at least
  *    faar_workspace_bytes(op, ...) bytes; its contents are undefined after the call (one exception:
- *    faar_layer_step can leave the next step's forward outputs there, see beta_next).
+ *    faar_layer_step can leave the next step's forward outputs there, see beta_next).  A FAAR_OP_LAYER_STEP
+ *    workspace must be 16-byte aligned.
  *  - Return value: FAAR_OK, or a negative error code, in which case NOTHING was launched.
  *    FAAR_E_HIP means a HIP call failed; the raw hipError_t is kept per host thread and read
  *    with faar_last_hip_error().  No other global mutable state exists.
@@ -87,7 +88,18 @@ enum {
   FAAR_K_QUANT_RTN = 6,      /* the quantise kernel of faar_quant_rtn (not its amax pass) */
   FAAR_K_INIT_V = 7,
   FAAR_K_HARDEN_PACK = 8,
-  FAAR_K_STAGE2_KL = 9       /* the three launches of faar_stage2_losses, bracketed together */
+  FAAR_K_STAGE2_KL = 9,      /* the three launches of faar_stage2_losses, bracketed together */
+  FAAR_K_GEMM_C = 10         /* Y_fp - X_q W^T of faar_layer_prepare (faar_gemm_plan only: it has no time bracket) */
+};
+
+/* GEMM kernel variants, as reported by faar_gemm_plan */
+enum {
+  FAAR_GEMM_GENERIC = 0,  /* register-staged 128x128 tile, any contraction length */
+  FAAR_GEMM_L = 1,        /* contraction % 32 == 0: direct-to-LDS ring of 32-wide slices, 256x256 tile */
+  FAAR_GEMM_M = 2,        /*   256x128 tile */
+  FAAR_GEMM_S = 3,        /*   128x128 tile */
+  FAAR_GEMM_L64 = 4,      /* contraction % 64 == 0: 64-wide slices, 256x256 tile */
+  FAAR_GEMM_M64 = 5       /*   256x128 tile */
 };
 
 /* Library version, MAJOR*10000 + MINOR*100 + PATCH.  Pure host function. */
@@ -110,6 +122,13 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
 /* Number of ways faar_layer_step splits the token contraction of the dW GEMM for these sizes (the
  * float32 partial products are summed by the kernel that consumes them).  Pure host function. */
 int faar_dw_split(int64_t O, int64_t K, int64_t T);
+
+/* Which kernel variant, output tile and contraction split the library uses for one of the GEMMs of a layer of
+ * these sizes: which = FAAR_K_GEMM_RESIDUAL (T x O x K), FAAR_K_GEMM_DW (O x K x padded T; the only one that may
+ * split its contraction), FAAR_K_GEMM_DX (T x K x O) or FAAR_K_GEMM_C (T x O x K, in faar_layer_prepare).
+ * out[0..3] = variant (FAAR_GEMM_*), tile rows, tile columns, contraction splits.  Pure host function; lets tests
+ * prove that their cases reach every variant. */
+int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out);
 
 /* Padded leading dimension (in elements) of the transposed activations Xt written by
  * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
@@ -236,10 +255,18 @@ typedef struct {
  *                       is requested) with that V's Round-Loss partial sums in ws, saving the next step
  *                       its forward kernel.  Same arithmetic, same results bit for bit.
  *   flags               FAAR_WS_CHAINED is accepted and has no effect on the computation.
- *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  The caller
- *                       vouches that the previous call on this ws was step opt->t - 1 of the same layer
- *                       (same W, scales, shapes, dX requested or not) with beta_next equal to this call's
- *                       beta, and that V and ws have not been written since.  Not checked.
+ *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  That is valid
+ *                       when the previous call on this ws was step opt->t - 1 of the same layer (same W, scales,
+ *                       V, shapes, dX requested or not) with beta_next equal to this call's beta, and neither V
+ *                       nor ws has been written since.  Checked ON THE DEVICE as far as it can be: the step that
+ *                       leaves a forward in ws tags it with (step index, beta, addresses of V, W and scales, O*K,
+ *                       dX requested), every call that overwrites that forward (a step without the flag,
+ *                       faar_hardened_loss) clears the tag, and a step consumes the tag it checks.  On a mismatch
+ *                       -- a stale or foreign workspace, a repeated or skipped step, another beta -- the step
+ *                       writes NaN to losses[0..2], leaves V, adam_m and adam_v untouched (dX is undefined) and
+ *                       leaves no forward behind, so every later FAAR_WS_FORWARD_READY step fails the same way
+ *                       until one runs without the flag.  The return code is still FAAR_OK (the check runs on the
+ *                       stream).  A write to V's memory between the two steps is the one violation it cannot see.
  */
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* s_global, const uint8_t* scales,
@@ -308,6 +335,10 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K,
  * squared Frobenius norm) is a mean: kl_scale and mse_scale are arguments (1 = as printed).  float32 arithmetic
  * with hardware exp / log; row sums are accumulated online (one pass over the logits for the loss, a second
  * one only when dZ_q is requested) and all sums are finished in a fixed order in double.
+ *
+ * A logit of -inf (a masked vocabulary entry) has probability 0 and, by the convention 0 log 0 = 0, adds nothing to
+ * the KL term where P_fp = 0; where P_fp > 0 and Z_q = -inf the KL is +inf.  A row whose logits are all -inf has no
+ * softmax: its results are NaN.  +inf and NaN logits are not supported.
  *
  *   Z_fp, Z_q   in  [T * vocab] of dtype zdt; vocab a multiple of 8
  *   H_fp, H_q   in  [T * D] of dtype hdt; D a multiple of 8

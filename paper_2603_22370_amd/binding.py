@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.faar_time_kernel.argtypes = [c_int, c_void_p, c_void_p]
         L.faar_dw_split.restype = c_int
         L.faar_dw_split.argtypes = [c_int64, c_int64, c_int64]
+        L.faar_gemm_plan.restype = c_int
+        L.faar_gemm_plan.argtypes = [c_int, c_int64, c_int64, c_int64, ctypes.POINTER(c_int32)]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -128,6 +130,17 @@ def faar_time_kernel(which: int, start_event=None, stop_event=None) -> None:
 
 def faar_dw_split(O: int, K: int, T: int) -> int:
     return int(lib().faar_dw_split(O, K, T))
+
+
+K_GEMM_C = 10
+GEMM_KINDS = ("generic", "L", "M", "S", "L64", "M64")
+
+
+def faar_gemm_plan(which: int, O: int, K: int, T: int):
+    """-> (variant name, tile rows, tile columns, contraction splits) of one GEMM of a layer of these sizes."""
+    out = (c_int32 * 4)()
+    _check(lib().faar_gemm_plan(which, O, K, T, out), "faar_gemm_plan")
+    return GEMM_KINDS[out[0]], int(out[1]), int(out[2]), int(out[3])
 
 
 def faar_padded_tokens(T: int) -> int:

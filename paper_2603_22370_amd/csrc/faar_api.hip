@@ -53,7 +53,7 @@ struct Carver {
 };
 
 struct StepLayout {
-  size_t delta, dYt, G, mse_partials, round_partials, wq_full, wqt, dY, total;
+  size_t guard, delta, dYt, G, mse_partials, round_partials, wq_full, wqt, dY, total;
   int n_split;
   int64_t Tp, Op;
 };
@@ -65,6 +65,7 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   L.n_split = choose_split(O, K, L.Tp);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t r = off; off += align256(bytes); return r; };
+  L.guard = take((size_t)(kTagWords + 1) * 4);  // first, so that every user of a step workspace finds it
   L.delta = take((size_t)O * K * 2);
   L.dYt = take((size_t)O * L.Tp * 2);
   L.G = take((size_t)L.n_split * O * K * 4);
@@ -79,6 +80,58 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   return L;
 }
 
+// Tag of the forward pass "W_q - W (and W_q when dX is wanted) of step t of this layer at this beta".
+ForwardTag forward_tag(int32_t t, float beta, const void* V, const void* W, const void* scales, int64_t n, bool with_wq) {
+  ForwardTag g{};
+  uint32_t bits;
+  static_assert(sizeof(bits) == sizeof(beta), "float is 32 bits");
+  __builtin_memcpy(&bits, &beta, sizeof(bits));
+  auto lo = [](uint64_t x) { return static_cast<uint32_t>(x); };
+  auto hi = [](uint64_t x) { return static_cast<uint32_t>(x >> 32); };
+  const uint64_t v = reinterpret_cast<uintptr_t>(V), w = reinterpret_cast<uintptr_t>(W), s = reinterpret_cast<uintptr_t>(scales);
+  g.w[0] = 0xFAA2F0D1u;
+  g.w[1] = static_cast<uint32_t>(t);
+  g.w[2] = bits;
+  g.w[3] = lo(v); g.w[4] = hi(v);
+  g.w[5] = lo(w); g.w[6] = hi(w);
+  g.w[7] = lo(s); g.w[8] = hi(s);
+  g.w[9] = lo(static_cast<uint64_t>(n)); g.w[10] = hi(static_cast<uint64_t>(n));
+  g.w[11] = with_wq ? 1u : 0u;
+  return g;
+}
+
+// ---- soft quantisation forward / backward, shared by the two entry points that differ in where the per-block
+// Round-Loss partial sums live ----
+int softquant_check(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global, const uint8_t* scales,
+                    const float* V, float beta, void* Wt, const float* dWt, float lambda_round, float* dV, uint32_t flags) {
+  if (!W || !s_global || !scales || !V || !Wt) return FAAR_E_NULL;
+  if (dWt && !dV) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (flags & ~(uint32_t)FAAR_EMIT_DELTA) return FAAR_E_ARG;
+  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round)) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(Wt) || !aligned16(dWt) || !aligned16(dV)) return FAAR_E_ARG;
+  return FAAR_OK;
+}
+
+int softquant_run(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global, const uint8_t* scales,
+                  const float* V, float beta, void* Wt, const float* dWt, float lambda_round, float* dV, float* round_loss,
+                  uint32_t flags, double* partials, hipStream_t st) {
+  const bool bf = wdt == FAAR_BF16;
+  const int64_t n = O * K;
+  if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, (flags & FAAR_EMIT_DELTA) != 0,
+                                              static_cast<bf16_t*>(Wt), nullptr, st)))
+    return e;
+  if (!dWt) return FAAR_OK;
+  if (int e = hip_status(launch_softquant_bwd(W, bf, n, s_global, scales, V, beta, dWt, 1, 0, lambda_round, dV,
+                                              partials, st)))
+    return e;
+  if (round_loss)
+    return hip_status(launch_finalize_losses(nullptr, 0, 0.0f, partials, softquant_bwd_blocks(n), 1.0 / (double)n,
+                                             lambda_round, nullptr, round_loss, nullptr, st));
+  return FAAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -88,7 +141,7 @@ int faar_version(void) { return 100; }
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
-  if (which < FAAR_K_NONE || which > FAAR_K_STAGE2_KL) return FAAR_E_ARG;
+  if (which < FAAR_K_NONE || which > FAAR_K_STAGE2_KL) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
   g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
   return FAAR_OK;
@@ -100,6 +153,22 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T) {
 }
 
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
+
+int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out) {
+  if (!out) return FAAR_E_NULL;
+  if (int e = check_shape(O, K)) return e;
+  if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
+  GemmPlanInfo p{};
+  switch (which) {
+    case FAAR_K_GEMM_RESIDUAL: p = gemm_plan_info(kGemmEpiResidual, T, O, K); break;
+    case FAAR_K_GEMM_DW: p = gemm_plan_info(kGemmEpiF32, O, K, padded_tokens(T)); break;
+    case FAAR_K_GEMM_DX: p = gemm_plan_info(kGemmEpiBf16, T, K, O); break;
+    case FAAR_K_GEMM_C: p = gemm_plan_info(kGemmEpiSub, T, O, K); break;
+    default: return FAAR_E_ARG;
+  }
+  out[0] = p.kind; out[1] = p.bm; out[2] = p.bn; out[3] = p.n_split;
+  return FAAR_OK;
+}
 
 size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t flags) {
   if (op == FAAR_OP_STAGE2_LOSSES) {  // O = vocabulary size, K = hidden size, T = tokens
@@ -160,29 +229,10 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, 
                            const uint8_t* scales, const float* V, float beta, void* Wt,
                            const float* dWt, float lambda_round, float* dV, float* round_loss,
                            uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
-  if (!W || !s_global || !scales || !V || !Wt) return FAAR_E_NULL;
-  if (dWt && !dV) return FAAR_E_NULL;
-  if (int e = check_wdt(wdt)) return e;
-  if (int e = check_shape(O, K)) return e;
-  if (flags & ~(uint32_t)FAAR_EMIT_DELTA) return FAAR_E_ARG;
-  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round)) return FAAR_E_ARG;
-  if (!aligned16(W) || !aligned16(V) || !aligned16(Wt) || !aligned16(dWt) || !aligned16(dV)) return FAAR_E_ARG;
+  if (int e = softquant_check(W, wdt, O, K, s_global, scales, V, beta, Wt, dWt, lambda_round, dV, flags)) return e;
   if (dWt && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_SOFTQUANT, O, K, 0, flags))) return FAAR_E_WORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool bf = wdt == FAAR_BF16;
-  const int64_t n = O * K;
-  if (int e = hip_status(launch_softquant_fwd(W, bf, n, s_global, scales, V, beta, (flags & FAAR_EMIT_DELTA) != 0,
-                                              static_cast<bf16_t*>(Wt), nullptr, st)))
-    return e;
-  if (!dWt) return FAAR_OK;
-  double* partials = static_cast<double*>(ws);
-  if (int e = hip_status(launch_softquant_bwd(W, bf, n, s_global, scales, V, beta, dWt, 1, 0, lambda_round, dV,
-                                              partials, st)))
-    return e;
-  if (round_loss)
-    return hip_status(launch_finalize_losses(nullptr, 0, 0.0f, partials, softquant_bwd_blocks(n), 1.0 / (double)n,
-                                             lambda_round, nullptr, round_loss, nullptr, st));
-  return FAAR_OK;
+  return softquant_run(W, wdt, O, K, s_global, scales, V, beta, Wt, dWt, lambda_round, dV, round_loss, flags,
+                       static_cast<double*>(ws), static_cast<hipStream_t>(stream));
 }
 
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
@@ -254,11 +304,17 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   bf16_t* dY = chained ? reinterpret_cast<bf16_t*>(base + L.dY) : nullptr;
   const bf16_t* xq = static_cast<const bf16_t*>(Xq);
 
-  // s1: W_q - W (bf16), W_q itself when dX is wanted, Round-Loss partials -- unless the previous step left them
+  // s1: W_q - W (bf16), W_q itself when dX is wanted, Round-Loss partials -- unless the previous step left them,
+  // in which case the residual GEMM first checks that what the workspace holds is this step's forward
+  uint32_t* guard_slot = reinterpret_cast<uint32_t*>(base + L.guard);
+  ForwardGuard guard{nullptr, {}};
   if (!(flags & FAAR_WS_FORWARD_READY)) {
     Bracket b(FAAR_K_SOFTQUANT_FWD, st);
-    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, round_p, st)))
+    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, round_p, guard_slot, st)))
       return e;
+  } else {
+    guard.slot = guard_slot;
+    guard.expect = forward_tag(opt->t, beta, V, W, scales, n, wq_full != nullptr);
   }
   // s2: residual GEMM + loss + dY
   int64_t n_mse = 0;
@@ -267,7 +323,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
     if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, x_scale, 2.0f * mse_scale, dYt, L.Tp,
-                                                need_local_dY ? dY : nullptr, mse_p, &n_mse, st)))
+                                                need_local_dY ? dY : nullptr, mse_p, &n_mse, guard, st)))
       return e;
   }
   const bf16_t* dY_used = dY;
@@ -301,6 +357,8 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.opt.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
   a.mse_partials = mse_p; a.n_mse = n_mse; a.mse_scale = mse_scale; a.round_partials = round_p; a.losses = losses;
   a.beta_next = beta_next; a.delta_next = delta; a.wq_full_next = wq_full; a.round_next = round_next;
+  a.guard_slot = guard_slot;
+  a.next_tag = forward_tag(opt->t + 1, beta_next, V, W, scales, n, wq_full != nullptr);
   Bracket b(FAAR_K_BWD_ADAM, st);
   return hip_status(launch_step_bwd_adam(a, st));
 }
@@ -331,11 +389,13 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   bf16_t* delta = reinterpret_cast<bf16_t*>(base + L.delta);
   bf16_t* dYt = reinterpret_cast<bf16_t*>(base + L.dYt);
   double* mse_p = reinterpret_cast<double*>(base + L.mse_partials);
-  if (int e = hip_status(launch_hardened_delta(W, wdt == FAAR_BF16, O * K, s_global, scales, V, delta, st))) return e;
+  if (int e = hip_status(launch_hardened_delta(W, wdt == FAAR_BF16, O * K, s_global, scales, V, delta,
+                                               reinterpret_cast<uint32_t*>(base + L.guard), st)))
+    return e;
   int64_t n_mse = 0;
   const GemmDims d1{T, O, K, K, K};
   if (int e = hip_status(launch_gemm_residual(static_cast<const bf16_t*>(Xq), delta, d1, C, x_scale, 2.0f * mse_scale, dYt,
-                                              L.Tp, nullptr, mse_p, &n_mse, st)))
+                                              L.Tp, nullptr, mse_p, &n_mse, ForwardGuard{nullptr, {}}, st)))
     return e;
   return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, nullptr, 0, 0.0, 0.0f, loss, nullptr, nullptr, st));
 }

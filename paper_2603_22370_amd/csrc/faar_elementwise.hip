@@ -341,7 +341,12 @@ template <typename WT, bool kFull>
 __global__ void __launch_bounds__(kEltThreads)
 k_step_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
            const uint8_t* __restrict__ scales, const uint32_t* __restrict__ icodes, const float* __restrict__ V,
-           float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_partials) {
+           float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_partials,
+           uint32_t* __restrict__ guard_slot) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) {  // a fresh forward: whatever tag the workspace held is void, verdict 1
+    for (int i = 0; i < kTagWords; ++i) guard_slot[i] = 0u;
+    guard_slot[kTagWords] = 1u;
+  }
   float rsum = 0.0f;
   const float sg = *s_global_p;
   for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kEltThreads) {
@@ -365,7 +370,16 @@ struct LossSums {
   float *loss_mse, *loss_round, *loss_total;
 };
 
-__device__ __forceinline__ void finalize_block(const LossSums& f) {
+__device__ __forceinline__ void finalize_block(const LossSums& f, bool valid = true) {
+  if (!valid) {  // the step ran on a forward pass that is not the one its caller described: no result
+    if (threadIdx.x == 0) {
+      const float nan = __uint_as_float(0x7FC00000u);
+      if (f.loss_mse) *f.loss_mse = nan;
+      if (f.loss_round) *f.loss_round = nan;
+      if (f.loss_total) *f.loss_total = nan;
+    }
+    return;
+  }
   double a = 0.0, b = 0.0;
   // per-thread partial sums in a fixed order; loads of one batch are independent
 #pragma unroll 4
@@ -406,12 +420,18 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
                 const uint32_t* __restrict__ icodes, float* __restrict__ V, float* __restrict__ M,
                 float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
                 const float* __restrict__ x_scale_p, float lam_over_n, AdamScalars o, LossSums fin, const WT* __restrict__ W, float beta_next,
-                bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_next) {
+                bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_next,
+                uint32_t* __restrict__ guard_slot, ForwardTag next_tag) {
   const int workers = static_cast<int>(gridDim.x) - 1;
+  const bool valid = guard_slot[kTagWords] != 0u;  // written by an earlier kernel of this step
   if (static_cast<int>(blockIdx.x) == workers) {
-    finalize_block(fin);
+    finalize_block(fin, valid);
+    if (kEmit && valid && threadIdx.x == 0) {      // nobody in this launch reads the tag words
+      for (int i = 0; i < kTagWords; ++i) guard_slot[i] = next_tag.w[i];
+    }
     return;
   }
+  if (!valid) return;
   float rsum = 0.0f;
   const float sg = *s_global_p;
   const float xs = x_scale_p ? *x_scale_p : 1.0f;  // G = x_scale * (dY^T X_q-in-units)
@@ -499,8 +519,12 @@ k_stochastic_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s
 template <typename WT>
 __global__ void __launch_bounds__(kEltThreads)
 k_hardened_delta(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
-                 const uint8_t* __restrict__ scales, const float* __restrict__ V, bf16_t* __restrict__ delta) {
+                 const uint8_t* __restrict__ scales, const float* __restrict__ V, bf16_t* __restrict__ delta,
+                 uint32_t* __restrict__ guard_slot) {
   const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i == 0) {
+    for (int k = 0; k < kTagWords; ++k) guard_slot[k] = 0u;   // delta replaces whatever forward the workspace held
+  }
   if (i >= n8) return;
   const float sg = *s_global_p;
   const float sgv = e4m3_value(scales[i >> 1]);
@@ -521,9 +545,9 @@ k_hardened_delta(const WT* __restrict__ W, int64_t n8, const float* __restrict__
 // The LDS row pitch of 33 words makes the transposed 2-byte reads of a wavefront hit 32 distinct banks.
 __global__ void __launch_bounds__(256)
 k_transpose_bf16(const bf16_t* __restrict__ in, int64_t rows, int64_t cols, bf16_t* __restrict__ out,
-                 int64_t ld_out) {
+                 int64_t ld_out, unsigned tiles_c) {
   __shared__ uint32_t tile[64][33];
-  const int64_t r0 = blockIdx.y * 64LL, c0 = blockIdx.x * 64LL;
+  const int64_t r0 = (blockIdx.x / tiles_c) * 64LL, c0 = (blockIdx.x % tiles_c) * 64LL;
   const int sub = threadIdx.x >> 3, ch = threadIdx.x & 7;
   const bool vec_in = (cols % 8) == 0;
 #pragma unroll
@@ -686,12 +710,12 @@ hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const fl
 
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           double* round_partials, hipStream_t st) {
+                           double* round_partials, uint32_t* guard_slot, hipStream_t st) {
   const int64_t n8 = n / 8;
   const dim3 g(static_cast<unsigned>(step_bwd_blocks(n))), b(kEltThreads);
   const uint32_t* c32 = reinterpret_cast<const uint32_t*>(icodes);
 #define FAAR_SF(WT, F) \
-  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full, round_partials)
+  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full, round_partials, guard_slot)
   if (w_bf16) { if (Wq_full) FAAR_SF(bf16_t, true); else FAAR_SF(bf16_t, false); }
   else        { if (Wq_full) FAAR_SF(float, true);  else FAAR_SF(float, false); }
 #undef FAAR_SF
@@ -709,7 +733,7 @@ hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st) {
 #define FAAR_SB(WT, E, F) \
   hipLaunchKernelGGL((k_step_bwd_adam<WT, E, F>), g, b, 0, st, n8, a.s_global, a.scales, c32, a.V, a.m, a.u, a.beta, a.G, \
                      a.n_split, a.split_stride, a.x_scale, lam_over_n, a.opt, fin, static_cast<const WT*>(a.W), a.beta_next, \
-                     a.delta_next, a.wq_full_next, a.round_next)
+                     a.delta_next, a.wq_full_next, a.round_next, a.guard_slot, a.next_tag)
   const bool emit = a.beta_next > 0.0f;
   if (!emit) { if (a.w_bf16) FAAR_SB(bf16_t, false, false); else FAAR_SB(float, false, false); }
   else if (a.wq_full_next) { if (a.w_bf16) FAAR_SB(bf16_t, true, true); else FAAR_SB(float, true, true); }
@@ -741,22 +765,25 @@ hipError_t launch_stochastic_v(const void* W, bool w_bf16, int64_t n, const floa
 }
 
 hipError_t launch_hardened_delta(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
-                                 const float* V, bf16_t* delta, hipStream_t st) {
+                                 const float* V, bf16_t* delta, uint32_t* guard_slot, hipStream_t st) {
   const int64_t n8 = n / 8;
   const dim3 g(blocks_for(n8)), b(kEltThreads);
   if (w_bf16)
-    hipLaunchKernelGGL(k_hardened_delta<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, delta);
+    hipLaunchKernelGGL(k_hardened_delta<bf16_t>, g, b, 0, st, static_cast<const bf16_t*>(W), n8, s_global, scales, V, delta, guard_slot);
   else
-    hipLaunchKernelGGL(k_hardened_delta<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, delta);
+    hipLaunchKernelGGL(k_hardened_delta<float>, g, b, 0, st, static_cast<const float*>(W), n8, s_global, scales, V, delta, guard_slot);
   return hipGetLastError();
 }
 
 hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
                                  int64_t ld_out, hipStream_t st) {
   if (ld_out % 64 != 0) return hipErrorInvalidValue;  // the kernel stores whole 8-element chunks
-  // the grid covers rows up to ld_out so that the zero padding is written too
-  const dim3 g(static_cast<unsigned>((cols + 63) / 64), static_cast<unsigned>((ld_out + 63) / 64));
-  hipLaunchKernelGGL(k_transpose_bf16, g, dim3(256), 0, st, in, rows, cols, out, ld_out);
+  // the grid covers rows up to ld_out so that the zero padding is written too; one flat grid dimension (limit
+  // 2^31 - 1 workgroups) so that neither extent is bounded by the 65535 of the other dimensions
+  const int64_t tiles_c = (cols + 63) / 64, tiles_r = (ld_out + 63) / 64;
+  if (tiles_c * tiles_r > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_transpose_bf16, dim3(static_cast<unsigned>(tiles_c * tiles_r)), dim3(256), 0, st, in, rows, cols, out,
+                     ld_out, static_cast<unsigned>(tiles_c));
   return hipGetLastError();
 }
 

@@ -55,6 +55,7 @@ __global__ void __launch_bounds__(GEMM_THREADS)
 k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n,
           int64_t k_per_split, Epi epi) {
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * T::STAGE];
+  epi.once();
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * T::WM, wn = (wave & 1) * T::WN;
 
@@ -162,6 +163,16 @@ struct EpiResidual {
   const float* x_scale;  // device scalar multiplying the A operand (activations stored in units of it); null = 1
   float xs;
   __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
+  // first thing workgroup 0 does: is the forward in the workspace the one this step's caller says it is?
+  ForwardGuard guard;
+  __device__ __forceinline__ void once() {
+    if (guard.slot && blockIdx.x == 0 && threadIdx.x == 0) {
+      bool ok = true;
+      for (int i = 0; i < kTagWords; ++i) ok = ok && guard.slot[i] == guard.expect.w[i];
+      for (int i = 0; i < kTagWords; ++i) guard.slot[i] = 0u;   // consumed: a replay of this step must not match
+      guard.slot[kTagWords] = ok ? 1u : 0u;
+    }
+  }
   float two_alpha;
   bf16_t* dYt;
   int64_t ldt;
@@ -220,6 +231,7 @@ struct EpiResidual {
 struct EpiF32 {
   static constexpr bool kTransposedOut = false;
   float* out;
+  __device__ __forceinline__ void once() {}
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int split, const GemmDims& d) {
     if (n >= d.N) return;
@@ -243,6 +255,7 @@ struct EpiSub {
   float* C_out;
   const float* x_scale;  // as in EpiResidual
   float xs;
+  __device__ __forceinline__ void once() {}
   __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N || m >= d.M) return;  // m is a multiple of 4
@@ -271,6 +284,7 @@ struct EpiSub {
 struct EpiBf16 {
   static constexpr bool kTransposedOut = false;
   bf16_t* out;
+  __device__ __forceinline__ void once() {}
   __device__ __forceinline__ void begin() {}
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N) return;
@@ -341,6 +355,7 @@ __global__ void __launch_bounds__(C::THREADS)
 k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
            int ksteps_per_split, Epi epi) {
   __shared__ __attribute__((aligned(1024))) bf16_t lds[DNS * C::STAGE];
+  epi.once();
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
   int tm, tn, split, item;
@@ -529,6 +544,7 @@ __global__ void __launch_bounds__(C::THREADS)
 k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
              int ksteps_per_split, Epi epi) {
   __shared__ __attribute__((aligned(1024))) bf16_t lds[C::NS * C::STAGE];
+  epi.once();
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
   int tm, tn, split, item;
@@ -789,14 +805,25 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {
 
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
-                                double* mse_partials, int64_t* n_partials, hipStream_t st) {
-  EpiResidual e{C, x_scale, 1.0f, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
+                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, hipStream_t st) {
+  EpiResidual e{C, x_scale, 1.0f, guard, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
   const Plan p = plan_gemm(d, false, kEpiResidual);
   *n_partials = p.items();
   return run(A, B, d, p, e, st);
 }
 
 int choose_split(int64_t M, int64_t N, int64_t Kd) { return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, true, kEpiF32).n_split; }
+
+GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd) {
+  const GemmDims d{M, N, Kd, Kd, Kd};
+  const Plan p = epilogue == kGemmEpiResidual ? plan_gemm(d, false, kEpiResidual)
+               : epilogue == kGemmEpiF32    ? plan_gemm(d, true, kEpiF32)
+               : epilogue == kGemmEpiSub    ? plan_gemm(d, false, kEpiSub)
+                                            : plan_gemm(d, false, kEpiBf16);
+  const int bm = p.kind == KIND_S || p.kind == KIND_GENERIC ? 128 : 256;
+  const int bn = p.kind == KIND_L || p.kind == KIND_L64 ? 256 : 128;
+  return GemmPlanInfo{p.kind, bm, bn, p.n_split};
+}
 
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st) {

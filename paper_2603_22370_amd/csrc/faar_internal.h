@@ -16,6 +16,15 @@ constexpr int kStepBwdMaxBlocks = 2048;  // grid cap of the fused backward + Ada
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline int64_t padded_tokens(int64_t T) { return round_up(T, 64); }
 
+// Identity of the forward pass (W_q - W at some beta, for some V) that a step leaves in its workspace for the step
+// that follows.  The guard slot in the workspace holds kTagWords tag words followed by one verdict word: the first
+// kernel of a step either produces a fresh forward (verdict 1) or compares the stored tag with the one its caller
+// implies (verdict = equal), and in both cases clears the tag; the kernel that updates V reads the verdict, and
+// writes the tag of the next step's forward when it produces one.
+constexpr int kTagWords = 12;
+struct ForwardTag { uint32_t w[kTagWords]; };
+struct ForwardGuard { uint32_t* slot; ForwardTag expect; };  // slot == nullptr: nothing to check
+
 // ---- elementwise kernels (faar_elementwise.hip) -------------------------------------------
 hipError_t launch_amax(const void* W, bool w_bf16, int64_t n, float* partials, float* s_global,
                        hipStream_t st);
@@ -47,7 +56,7 @@ hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const fl
 // partial sums of V, one per block (step_bwd_blocks(n) of them).
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           double* round_partials, hipStream_t st);
+                           double* round_partials, uint32_t* guard_slot, hipStream_t st);
 // Step backward + Adam + clip on cached codes.  One more block sums this step's losses (mse_partials from the
 // residual GEMM, round_partials of the V the step started from) into losses[0..2].  beta_next > 0 also emits
 // the next step's forward outputs from the updated V: delta_next (and wq_full_next when not null) and that
@@ -61,6 +70,8 @@ struct StepBwdArgs {
   float lambda_round; AdamScalars opt;
   const double* mse_partials; int64_t n_mse; float mse_scale; const double* round_partials; float* losses;
   float beta_next; bf16_t* delta_next; bf16_t* wq_full_next; double* round_next;
+  uint32_t* guard_slot;   // verdict of the step's first kernel; a failed check leaves V, m, u alone and gives NaN losses
+  ForwardTag next_tag;    // written to the slot when beta_next > 0
 };
 hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st);
 // losses[0] = mse_scale * sum(mse_partials), losses[1] = sum(round_partials) / n,
@@ -79,9 +90,9 @@ hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid,
 // V = 1 with probability v_init else 0, from Philox-4x32-10 keyed by (seed, sample)
 hipError_t launch_stochastic_v(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                                uint64_t seed, uint32_t sample, float* V, hipStream_t st);
-// delta = bf16(W_final(V) - W) for the hardened V
+// delta = bf16(W_final(V) - W) for the hardened V; clears the forward tag in guard_slot (delta replaces that forward)
 hipError_t launch_hardened_delta(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
-                                 const float* V, bf16_t* delta, hipStream_t st);
+                                 const float* V, bf16_t* delta, uint32_t* guard_slot, hipStream_t st);
 
 // ---- Stage-2 objective on given logits / hidden states (faar_stage2.hip) -------------------
 struct Stage2Args {
@@ -104,15 +115,22 @@ struct GemmDims { int64_t M, N, Kd, lda, ldb; };
 // [ceil(M/4)][N][4], x_scale a device scalar (null = 1); partial sum of R^2 per tile (double);
 // dYt[n][m] = bf16(two_alpha * R) with row stride ldt (rows n < N, columns m < ldt, zero for m >= M);
 // dY (nullable) [M, N] the same values un-transposed.
+// guard: when its slot is set, workgroup 0 first compares the stored forward tag with guard.expect (see ForwardTag)
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
-                                double* mse_partials, int64_t* n_partials, hipStream_t st);
+                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, hipStream_t st);
 // number of per-work-item loss partials the residual GEMM writes for these sizes
 int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 // Plain float32 output with the contraction split n_split ways: out[s][m][n] (split stride M*N).
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st);
 int choose_split(int64_t M, int64_t N, int64_t Kd);
+// The kernel variant, tile shape and contraction split the launchers above pick for an M x N x Kd product
+// (kind: 0 generic, 1 / 2 / 3 the BK = 32 kernels with 256x256 / 256x128 / 128x128 tiles, 4 / 5 the BK = 64
+// kernels with 256x256 / 256x128 tiles).  Pure host function.
+enum { kGemmEpiResidual = 0, kGemmEpiF32 = 1, kGemmEpiSub = 2, kGemmEpiBf16 = 3 };
+struct GemmPlanInfo { int kind, bm, bn, n_split; };
+GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd);
 // C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc   (Y bf16 or float32 row-major; C_out interleaved)
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
                            bool first, float* C_out, const float* x_scale, hipStream_t st);

@@ -37,6 +37,17 @@ __device__ __forceinline__ RowStats shuffle_xor(const RowStats& x, int o) {
   return r;
 }
 
+// One vocabulary entry added to the running sums (st.ma / st.mb already cover it).  A logit of -inf (a masked
+// entry) has probability 0: it adds nothing to either sum, and by the convention 0 log 0 = 0 nothing to the KL
+// term either -- also where only z_fp is -inf.  Where P_fp > 0 and z_q = -inf the term, and the row's KL, is +inf.
+// A row whose logits are all -inf has no softmax; its results are NaN.
+__device__ __forceinline__ void accumulate(RowStats& st, float a, float b) {
+  const float ea = a == -INFINITY ? 0.0f : __expf(a - st.ma);
+  st.sa += ea;
+  if (ea != 0.0f) st.w += ea * (a - b);
+  st.sb += b == -INFINITY ? 0.0f : __expf(b - st.mb);
+}
+
 template <typename ZT>
 __global__ void __launch_bounds__(kRowThreads)
 k_stage2_kl(const ZT* __restrict__ Zf, const ZT* __restrict__ Zq, int64_t v8, float inv_tau, float grad_coef,
@@ -69,12 +80,7 @@ k_stage2_kl(const ZT* __restrict__ Zf, const ZT* __restrict__ Zq, int64_t v8, fl
       st.mb = cb;
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const float ea = __expf(a[j] - st.ma);
-      st.sa += ea;
-      st.w += ea * (a[j] - b[j]);
-      st.sb += __expf(b[j] - st.mb);
-    }
+    for (int j = 0; j < 8; ++j) accumulate(st, a[j], b[j]);
   }
   // fixed-order reduction: butterfly inside each wavefront, then the wavefronts in index order
 #pragma unroll
@@ -165,12 +171,7 @@ k_stage2_kl_resident(const bf16_t* __restrict__ Zf, const bf16_t* __restrict__ Z
         st.mb = cb;
       }
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float ea = __expf(a[j] - st.ma);
-        st.sa += ea;
-        st.w += ea * (a[j] - b[j]);
-        st.sb += __expf(b[j] - st.mb);
-      }
+      for (int j = 0; j < 8; ++j) accumulate(st, a[j], b[j]);
     }
   }
 #pragma unroll

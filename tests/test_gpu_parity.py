@@ -1,12 +1,16 @@
 """GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
-Integer / byte / index results bit-exact; float results within the tolerances stated at TOL_EXACT below
+Integer / byte / index results bit-exact; float results within the tolerances stated in the block above HYP below
 (bf16 matrix-core path vs float64 oracle)."""
+import functools
+
 import numpy as np
 import pytest
 import torch
 
 from oracle import faar_oracle as fo
 from workloads import synth
+
+from parity_cases import BY_NAME, STEP_CASES
 
 pytestmark = pytest.mark.gpu
 
@@ -134,20 +138,19 @@ def test_softquant_forward_and_backward(name, W, isbf, beta):
     assert host(rl)[0] == pytest.approx(fo.round_loss(V), rel=1e-6)
 
 
-def linear_cases():
-    yield synth.config1(0)
-    c = synth.llm_linear("ragged", 96, 80, 100, 21, quantised_acts=True)          # nothing a multiple of the tile
-    yield c
-    yield synth.llm_linear("kproj_slice", 512, 2048, 640, 22)
-    yield synth.llm_linear("three_tiles", 320, 256, 300, 23, quantised_acts=True)
-    # tile-shape coverage of the GEMM planner: 384 tiles of 256x256 with only two contraction slices,
-    # and 192 tiles of 256x128; the dW GEMM of both splits its contraction over the tokens
-    yield synth.llm_linear("wide_256x256_tiles", 12288, 64, 2048, 24)
-    yield synth.llm_linear("mid_256x128_tiles", 3072, 96, 2048, 25, quantised_acts=True)
+@functools.lru_cache(maxsize=2)
+def build_case(name):
+    """The seeded tensors of one parity case (see tests/parity_cases.py); the two most recent are kept."""
+    p = BY_NAME[name]
+    if p.fp32_small:
+        return synth.config1(p.seed)
+    return synth.llm_linear(p.name, p.O, p.K, p.T, p.seed, gated_input=p.gated_input, quantised_acts=p.quantised_acts)
 
 
-LCASES = list(linear_cases())
-LIDS = [c.name for c in LCASES]
+SMALL = [c.name for c in STEP_CASES if not c.full_size]
+FULL = [c.name for c in STEP_CASES if c.full_size]
+# the cases other tests below reuse
+RAGGED, THREE_TILES = "ragged", "three_tiles"
 
 
 def _setup(c):
@@ -160,8 +163,9 @@ def _setup(c):
     return Wd, sg, scales, q, Xq, Y, Xt, (C, ic)
 
 
-@pytest.mark.parametrize("c", LCASES, ids=LIDS)
-def test_layer_prepare(c):
+@pytest.mark.parametrize("name", SMALL + FULL)
+def test_layer_prepare(name):
+    c = build_case(name)
     Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
     Tp = faar.faar_padded_tokens(c.T)
     xt = host(Xt)
@@ -174,6 +178,7 @@ def test_layer_prepare(c):
     Cg = Cg.transpose(0, 2, 1).reshape(-1, c.O)
     assert not Cg[c.T:].any()
     assert np.all(np.abs(Cg[:c.T] - C_want) <= 2e-6 * scale + 1e-30)
+    del Cg, C_want, scale
     # cached interval codes: sign bit and k_lo (7 for a zero weight)
     wt = fo.normalised_magnitude(c.W, q["scales"], q["s_global"])
     want_ic = (np.signbit(c.W).astype(np.uint8) << 3) | np.where(c.W == 0, 7, fo.find_interval(wt)).astype(np.uint8)
@@ -183,13 +188,56 @@ def test_layer_prepare(c):
     assert torch.equal(C2, C) and torch.equal(Xt2, Xt) and torch.equal(ic2, ic)
 
 
-# Two bf16 roundings (unit roundoff u = 2^-9) sit between the inputs and the loss / gradient: the
-# weight perturbation W_q - W and dY.  A loss or gradient dominated by a few outlier terms can move
-# by up to 2u; sums over many terms average far below that.  Against the oracle evaluated with the
-# same declared roundings only float32 accumulation noise remains.
-TOL_EXACT = 2 * 2.0 ** -9
+# ---- tolerances of the float results -------------------------------------------------------------------------
+# Two bf16 roundings (unit roundoff u = 2^-9) sit between the inputs and the loss / gradient: the weight
+# perturbation W_q - W and dY (a third, dX, on the input-gradient path).
+#  * Against the oracle evaluated WITH those declared roundings only float32 accumulation noise and rounding-boundary
+#    flips remain (a value that sits on a bf16 rounding boundary may round the other way in float32 than in float64).
+#    Measured over all cases below: loss <= 6.2e-6, ||dV|| <= 3.4e-4, ||dX|| <= 4.8e-5.
+#  * Against the EXACT float64 oracle the loss moves by 2 sum(d * err(d)) / sum(d^2) over the weights d = W_q - W that
+#    carry it: at most 2u, and far less once many weights share the loss.  The full-size LLM-shaped layers measure
+#    5.9e-5 ... 4.4e-4 and are held to 1e-3.  Small slices with outlier channels are dominated by a few dozen
+#    heavy-tailed weights in the outlier columns (measured up to 2.05e-3 = 1.05u on 512x2048 with 640 tokens at
+#    beta = 4) and are held to the bound 2u.
+#  * The gradient against the exact oracle carries two independent roundings of rms u / sqrt(3) each (W_q - W, dY):
+#    sqrt(2/3) u = 1.6e-3 expected, 1.4e-3 ... 2.2e-3 measured, held to 1.5u.  With an upstream gradient given, dY is
+#    not rounded and G does not depend on W_q: measured 5e-7.
+#  * dX (bf16) against the exact oracle is the final rounding, u / sqrt(3) * ~2: measured 2.3e-3 ... 2.4e-3.
+U = 2.0 ** -9
+TOL_LOSS_EXACT_FULL = 1e-3       # full-size LLM-shaped layers
+TOL_LOSS_EXACT_OUTLIER = 2 * U   # few-term or outlier-dominated sums: the worst-case bound
+TOL_LOSS_DECLARED = 2e-5
+TOL_GRAD_EXACT = 1.5 * U
+TOL_GRAD_DECLARED = 5e-4
+# per element, vs the oracle with the declared roundings: excess = (|g - g*| - GRAD_ELEM_A |g*|) / rms(g*).  A boundary
+# flip of one W_q - W moves that weight's own gradient by up to 2^-8 of its own term 2 alpha ||X_k||^2 d, which is
+# the size of g* itself unless the cross terms cancel it; a flip of one dY moves a whole row of G a little.
+# Measured distribution over all cases (16.8 M elements in the largest): the fraction of elements with excess >
+# 1e-3 is <= 8e-5 and with excess > 3e-3 is <= 2.7e-5; the largest excess is <= 1.4e-3 on the small cases, 1.2e-2 on
+# the 16.8 M-weight gate projection (one element in ten million) -- and 5.8e-2 on the one case with 33 tokens, where
+# the own terms of the outlier columns are ten times rms(g*) and largely cancelled by the other outlier columns
+# (33 tokens cannot decorrelate 123 columns).  Held to: fraction above 1e-3 <= 2e-4; largest <= 2e-2 (9e-2 there).
+GRAD_ELEM_A, GRAD_ELEM_FRAC_AT, GRAD_ELEM_FRAC, GRAD_ELEM_MAX = 2.0 ** -7, 1e-3, 2e-4, 2e-2
+GRAD_ELEM_MAX_BY_CASE = {"dw_one_slice": 9e-2}
+# dX per element: one ulp of the final bf16 rounding (a boundary flip).  With the upstream gradient given, measured
+# excess <= 1.4e-6 rms and norm-wise <= 4.8e-5 against the declared oracle; with the locally derived dY its own
+# boundary flips come on top (single terms of the sum over O): 1.9e-3 rms and 2.7e-4 measured.
+DX_ELEM_A = 2.0 ** -7
+DX_ELEM_B = {"upstream": 1e-4, "local": 5e-3}
+TOL_DX_EXACT = 1.5 * U
+TOL_DX_DECLARED = {"upstream": 2e-4, "local": 6e-4}
 
 HYP = dict(lambda_round=0.01, lr=5e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+
+
+def loss_tol(name):
+    return TOL_LOSS_EXACT_FULL if BY_NAME[name].full_size else TOL_LOSS_EXACT_OUTLIER
+
+
+def upstream_gradient(c, seed):
+    """Synthetic upstream gradient of a chained step: bf16 N(0, 1) * 1e-3."""
+    rng = np.random.default_rng([seed, 41])
+    return synth.round_to_bf16((rng.standard_normal((c.T, c.O)) * 1e-3).astype(np.float32))
 
 
 def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False):
@@ -206,24 +254,55 @@ def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False):
                          HYP["beta1"], HYP["beta2"], HYP["eps"], t, losses, ws,
                          dY_ext=None if dY_ext is None else dev(dY_ext, True), dX=dX)
     torch.cuda.synchronize()
+    out = host(V), host(m), host(u), host(losses), (None if dX is None else host(dX))
+    del Wd, Xq, Y, Xt, C, V, m, u, ws, dX
+    torch.cuda.empty_cache()
     ref = {}
     for mode in (False, True):
         ref[mode] = fo.layer_step(c.W, q["s_global"], q["scales"], V0, np.zeros_like(V0) if m0 is None else m0,
                                   np.zeros_like(V0) if u0 is None else u0, c.Xq, c.Y_fp, beta, HYP["lambda_round"],
                                   alpha, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], t, want_dX=want_dX,
                                   dY_ext=dY_ext, declared_rounding=mode)
-    return host(V), host(m), host(u), host(losses), (None if dX is None else host(dX)), ref
+        for k in ("R", "dY", "Wq"):        # not compared; large
+            ref[mode].pop(k, None)
+    return out + (ref,)
 
 
-def _check_grad(g, ref):
+def grad_errors(g, ref):
+    """Error figures of a gradient against the two oracles (see the tolerance block above)."""
     exact, decl = ref[False]["dV"], ref[True]["dV"]
     n = np.linalg.norm
-    assert n(g - exact) <= TOL_EXACT * n(exact)                  # vs float64 oracle, no rounding anywhere
-    assert n(g - decl) <= 5e-4 * n(decl)                         # vs oracle with the three declared bf16 roundings
     rms = np.sqrt(np.mean(decl ** 2))
-    # a value on a bf16 rounding boundary may round the other way in float32 than in float64: one such
-    # flip of W_q - W moves that weight's own gradient by up to 2^-8 relative (coherent over all tokens)
-    assert np.all(np.abs(g - decl) <= 2.0 ** -7 * np.abs(decl) + 2e-2 * rms)
+    excess = (np.abs(g - decl) - GRAD_ELEM_A * np.abs(decl)) / rms
+    return {"norm_exact": n(g - exact) / n(exact), "norm_declared": n(g - decl) / n(decl),
+            "elem_excess_over_rms": float(excess.max()),
+            "frac_above": {thr: float(np.mean(excess > thr)) for thr in (3e-4, 1e-3, 3e-3)}}
+
+
+def dx_errors(dX, ref):
+    exact, decl = ref[False]["dX"], ref[True]["dX"]
+    n = np.linalg.norm
+    rms = np.sqrt(np.mean(decl ** 2))
+    excess = np.abs(dX - decl) - DX_ELEM_A * np.abs(decl)  # in absolute units; divided by rms below
+    return {"norm_exact": n(dX - exact) / n(exact), "norm_declared": n(dX - decl) / n(decl),
+            "elem_excess_over_rms": float(excess.max() / rms)}
+
+
+def _check_grad(g, ref, elem_max=GRAD_ELEM_MAX):
+    e = grad_errors(g, ref)
+    assert e["norm_exact"] <= TOL_GRAD_EXACT, e          # vs float64 oracle, no rounding anywhere
+    assert e["norm_declared"] <= TOL_GRAD_DECLARED, e    # vs oracle with the declared bf16 roundings
+    assert e["elem_excess_over_rms"] <= elem_max, e      # element by element: the largest ...
+    assert e["frac_above"][GRAD_ELEM_FRAC_AT] <= GRAD_ELEM_FRAC, e   # ... and how many come anywhere near it
+
+
+def _check_dx(dX, ref, dy="upstream"):
+    """dX = dY W_q element by element against the oracle with the declared roundings (dY, W_q and dX itself in
+    bf16), and norm-wise against the exact one (three roundings on this path).  dy: where dY came from."""
+    e = dx_errors(dX, ref)
+    assert e["norm_exact"] <= TOL_DX_EXACT, e
+    assert e["norm_declared"] <= TOL_DX_DECLARED[dy], e
+    assert e["elem_excess_over_rms"] <= DX_ELEM_B[dy], e
 
 
 def _check_update(V, m, u, V0, m0, u0, t):
@@ -239,24 +318,59 @@ def _check_update(V, m, u, V0, m0, u0, t):
     assert V.min() >= 0.0 and V.max() <= 1.0
 
 
-@pytest.mark.parametrize("c", LCASES, ids=LIDS)
-@pytest.mark.parametrize("beta", [4.0, 20.0])
-def test_layer_step_first_step(c, beta):
+def step_case_errors(name, beta, chained):
+    """One first step of a parity case through the C ABI against both oracles -- chained: with an upstream gradient
+    and dX; otherwise with the locally derived dY.  Asserts what is exact and returns the error figures of everything
+    that has a tolerance."""
+    p = BY_NAME[name]
+    c = build_case(name)
     q = fo.quant_rtn(c.W, c.w_is_bf16)
     V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
-    V, m, u, losses, _, ref = _one_step(c, beta, V0)
-    ex = ref[False]
-    assert losses[0] == pytest.approx(ex["L_mse"], rel=TOL_EXACT)
-    assert losses[1] == pytest.approx(ex["L_round"], rel=1e-5)
-    assert losses[2] == pytest.approx(ex["L"], rel=TOL_EXACT)
-    assert losses[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
+    dY_ext = upstream_gradient(c, p.seed) if chained else None
+    V, m, u, losses, dX, ref = _one_step(c, beta, V0, dY_ext=dY_ext, want_dX=chained)
+    ex, de = ref[False], ref[True]
+    errs = {"loss_exact": abs(losses[0] - ex["L_mse"]) / ex["L_mse"], "loss_declared": abs(losses[0] - de["L_mse"]) / de["L_mse"],
+            "round": abs(losses[1] - ex["L_round"]) / ex["L_round"],
+            "total": abs(losses[2] - ex["L"]) / ex["L"]}
     # with zero initial state, m = (1 - beta1) g: the gradient is observable through m
-    _check_grad(m.astype(np.float64) / (1 - HYP["beta1"]), ref)
+    errs["grad"] = grad_errors(m.astype(np.float64) / (1 - HYP["beta1"]), ref)
+    if chained:
+        errs["dx"] = dx_errors(dX, ref)
     _check_update(V, m, u, V0, np.zeros_like(V0), np.zeros_like(V0), 1)
+    return errs, (m, dX, ref)
+
+
+def _assert_step_case(name, beta):
+    """A chained case runs twice: with the upstream gradient and dX (three GEMMs), and plainly (the residual GEMM's own
+    dY^T feeds the dW GEMM), so that every output of every kernel variant it reaches is compared."""
+    for chained in ((True, False) if BY_NAME[name].chained else (False,)):
+        errs, (m, dX, ref) = step_case_errors(name, beta, chained)
+        assert errs["loss_exact"] <= loss_tol(name), errs
+        assert errs["loss_declared"] <= TOL_LOSS_DECLARED, errs
+        assert errs["round"] <= 1e-5, errs
+        assert errs["total"] <= loss_tol(name), errs
+        _check_grad(m.astype(np.float64) / (1 - HYP["beta1"]), ref, GRAD_ELEM_MAX_BY_CASE.get(name, GRAD_ELEM_MAX))
+        if dX is not None:
+            _check_dx(dX, ref)
+        del m, dX, ref
+
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("beta", [4.0, 20.0])
+def test_layer_step_first_step(name, beta):
+    _assert_step_case(name, beta)
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_layer_step_full_size(name):
+    """The benchmark's own shapes and launch configurations (all tiles, every contraction slice, the ring wrapping
+    around): one whole step -- with an upstream gradient and dX where the case is chained -- element by element
+    against the oracle.  The float64 products of the largest case take a few seconds on the host."""
+    _assert_step_case(name, 8.0)
 
 
 def test_layer_step_with_state_and_random_v():
-    c = LCASES[3]
+    c = build_case(THREE_TILES)
     rng = np.random.default_rng(11)
     V0 = synth.rounding_variables(c.O, c.K, 12)
     m0 = (rng.standard_normal(V0.shape) * 1e-7).astype(np.float32)
@@ -267,13 +381,13 @@ def test_layer_step_with_state_and_random_v():
     n = np.linalg.norm
     assert n(g - decl["dV"]) <= 1e-3 * n(decl["dV"])
     _check_update(V, m, u, V0, m0, u0, 7)
-    assert losses[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
+    assert losses[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER)
     assert losses[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
     assert losses[1] == pytest.approx(ref[False]["L_round"], rel=1e-5)
 
 
 def test_layer_step_chained_dY_ext_and_dX():
-    c = LCASES[3]
+    c = build_case(THREE_TILES)
     rng = np.random.default_rng(13)
     q = fo.quant_rtn(c.W, c.w_is_bf16)
     V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
@@ -281,10 +395,8 @@ def test_layer_step_chained_dY_ext_and_dX():
     for ext in (dY, None):
         V, m, u, losses, dX, ref = _one_step(c, 6.0, V0, dY_ext=ext, want_dX=True)
         _check_grad(m.astype(np.float64) / (1 - HYP["beta1"]), ref)
-        n = np.linalg.norm
-        assert n(dX - ref[False]["dX"]) <= 5e-3 * n(ref[False]["dX"])   # three roundings on this path: dY, W_q, dX
-        assert n(dX - ref[True]["dX"]) <= 1e-3 * n(ref[True]["dX"])     # final bf16 rounding of dX included on both sides
-        assert losses[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
+        _check_dx(dX, ref, "upstream" if ext is not None else "local")
+        assert losses[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER)
 
 
 def test_config1_trajectory_100_adam_steps():
@@ -309,7 +421,7 @@ def test_config1_trajectory_100_adam_steps():
                           0.999, 1e-8, t)
         Vo, mo, uo = r["V"], r["m"], r["u"]
         L = host(losses)
-        assert L[0] == pytest.approx(r["L_mse"], rel=TOL_EXACT), t
+        assert L[0] == pytest.approx(r["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER), t
         assert L[1] == pytest.approx(r["L_round"], rel=1e-3), t
         first = L[0] if first is None else first
         last = L[0]
@@ -331,7 +443,7 @@ def test_config1_trajectory_100_adam_steps():
 
 
 def test_resume_is_bit_exact_and_runs_are_deterministic():
-    c = LCASES[3]
+    c = build_case(THREE_TILES)
     Wd, sg, scales, q, Xq, Y, Xt, C = _setup(c)
     alpha = 1.0 / (c.T * c.O)
     ws = faar.layer_step_workspace(c.O, c.K, c.T)
@@ -364,7 +476,7 @@ def test_forward_left_by_the_previous_step_gives_identical_results():
     step may consume them (forward_ready): same arithmetic, so losses and state must match the plain
     sequence bit for bit -- float32 and bf16 weights, with and without dX, odd and even step indices."""
     rng = np.random.default_rng(17)
-    for c, want_dX in ((synth.config1(0), False), (LCASES[3], False), (LCASES[3], True), (LCASES[1], True)):
+    for c, want_dX in ((synth.config1(0), False), (build_case(THREE_TILES), False), (build_case(THREE_TILES), True), (build_case(RAGGED), True)):
         Wd, sg, scales, q, Xq, Y, Xt, C = _setup(c)
         alpha = 1.0 / (c.T * c.O)
         ws = faar.layer_step_workspace(c.O, c.K, c.T, chained=want_dX)
@@ -404,11 +516,88 @@ def test_forward_left_by_the_previous_step_gives_identical_results():
         assert torch.equal(losses, oa[-1][0])
 
 
+def test_forward_ready_is_checked_on_the_device():
+    """A step told that its forward pass is already in the workspace verifies that claim against the tag the
+    producing step left (step index, beta, the layer's buffers, dX or not).  Every violation must give NaN losses and
+    leave V and the Adam state untouched; a following step without the flag recovers."""
+    c = build_case(THREE_TILES)
+    Wd, sg, scales, q, Xq, Y, Xt, C = _setup(c)
+    alpha = 1.0 / (c.T * c.O)
+    nan3 = lambda L: bool(torch.isnan(L).all())
+
+    def fresh(chained=False):
+        V, _ = faar.faar_init_v(Wd, sg, scales)
+        return dict(V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), losses=torch.zeros(3, dtype=torch.float32, device="cuda"),
+                    ws=faar.layer_step_workspace(c.O, c.K, c.T, chained=chained))
+
+    def step(s, t, beta, beta_next=0.0, ready=False, V=None, dX=None, ws=None):
+        faar.faar_layer_step(Wd, sg, scales, s["V"] if V is None else V, s["m"], s["u"], Xq, Xt, *C, beta, 0.01, alpha, 5e-3,
+                             0.9, 0.999, 1e-8, t, s["losses"], s["ws"] if ws is None else ws, dX=dX, beta_next=beta_next,
+                             forward_ready=ready)
+        torch.cuda.synchronize()
+
+    def snapshot(s):
+        return [s[k].clone() for k in ("V", "m", "u")]
+
+    def unchanged(s, snap):
+        return all(torch.equal(s[k], x) for k, x in zip(("V", "m", "u"), snap))
+
+    # the valid sequence works, and each violation below starts from it
+    def prepared():
+        s = fresh()
+        step(s, 1, 4.0, beta_next=6.0)
+        assert not nan3(s["losses"])
+        return s, snapshot(s)
+
+    s, snap = prepared()
+    step(s, 2, 6.0, ready=True)
+    assert not nan3(s["losses"]) and not unchanged(s, snap)
+    # a workspace nobody prepared (zeroed, and one full of stale bytes)
+    for fill in (0, 0xA5):
+        s = fresh()
+        s["ws"].fill_(fill)
+        snap = snapshot(s)
+        step(s, 2, 6.0, ready=True)
+        assert nan3(s["losses"]) and unchanged(s, snap)
+        step(s, 2, 6.0)                                   # without the flag the step is fine again
+        assert not nan3(s["losses"]) and not unchanged(s, snap)
+    # another beta than the one the forward was computed at; a skipped step; a repeated step
+    s, snap = prepared()
+    step(s, 2, 7.0, ready=True)
+    assert nan3(s["losses"]) and unchanged(s, snap)
+    s, snap = prepared()
+    step(s, 3, 6.0, ready=True)
+    assert nan3(s["losses"]) and unchanged(s, snap)
+    s, snap = prepared()
+    step(s, 2, 6.0, beta_next=8.0, ready=True)
+    snap = snapshot(s)
+    step(s, 2, 6.0, ready=True)                           # step 2 again: its forward was consumed
+    assert nan3(s["losses"]) and unchanged(s, snap)
+    step(s, 3, 8.0, ready=True)                           # and the failed step left nothing behind
+    assert nan3(s["losses"]) and unchanged(s, snap)
+    # another V buffer (another layer's state on the same workspace)
+    s, snap = prepared()
+    V2 = s["V"].clone()
+    step(s, 2, 6.0, ready=True, V=V2)
+    assert nan3(s["losses"]) and unchanged(s, snap) and torch.equal(V2, snap[0])
+    # a forward prepared without W_q cannot serve a step that wants dX
+    s = fresh(chained=True)
+    step(s, 1, 4.0, beta_next=6.0)
+    snap = snapshot(s)
+    step(s, 2, 6.0, ready=True, dX=torch.empty((c.T, c.K), dtype=torch.bfloat16, device="cuda"))
+    assert nan3(s["losses"]) and unchanged(s, snap)
+    # a call that reuses the workspace in between destroys the forward and clears the tag
+    s, snap = prepared()
+    faar.faar_hardened_loss(Wd, sg, scales, s["V"], Xq, C[0], alpha, s["ws"])
+    step(s, 2, 6.0, ready=True)
+    assert nan3(s["losses"]) and unchanged(s, snap)
+
+
 def test_nvfp4_activations_in_units_of_their_tensor_scale():
     """Activations quantised to NVFP4 by the same kernel (blocks along K, their own tensor scale): W_dq in units of
     s_global is the exact product node * block scale, and a step fed (Xq, x_scale) agrees with the oracle fed the
     dequantised activations x_scale * Xq."""
-    for c, seed in ((LCASES[1], 31), (LCASES[3], 32)):          # ragged 96x80 T=100 (generic GEMM), 320x256 T=300
+    for c, seed in ((build_case(RAGGED), 31), (build_case(THREE_TILES), 32)):          # ragged 96x80 T=100 (generic GEMM), 320x256 T=300
         X = synth.activations(c.T, c.K, seed)
         qx = fo.quant_rtn(X, True)
         sX, sc, cd, Xu = faar.faar_quant_rtn(dev(X, True), want_dq=True, dq_in_units=True)
@@ -436,7 +625,7 @@ def test_nvfp4_activations_in_units_of_their_tensor_scale():
                                    8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 1,
                                    declared_rounding=mode) for mode in (False, True)}
         L = host(losses)
-        assert L[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
+        assert L[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER)
         assert L[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
         _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
 
@@ -452,7 +641,7 @@ def test_stochastic_candidates_and_hardened_loss():
         for seed, sample in ((0, 0), (2 ** 40 + 17, 99)):
             Vs = faar.faar_stochastic_v(Wd, sg, scales, seed, sample)
             assert np.array_equal(host(Vs), fo.stochastic_v(V0, seed, sample)), name
-    for c in (LCASES[0], LCASES[1], LCASES[3]):
+    for c in (build_case("config1"), build_case(RAGGED), build_case(THREE_TILES)):
         Wd, sg, scales, q, Xq, Y, Xt, (C, ic) = _setup(c)
         alpha = 1.0 / (c.T * c.O)
         ws = faar.layer_step_workspace(c.O, c.K, c.T)
@@ -462,7 +651,7 @@ def test_stochastic_candidates_and_hardened_loss():
         for k, V in cands.items():
             got[k] = float(faar.faar_hardened_loss(Wd, sg, scales, dev(V), Xq, C, alpha, ws).item())
             want = fo.hardened_loss(c.W, c.w_is_bf16, q["s_global"], q["scales"], V, c.Xq, c.Y_fp, alpha)
-            assert got[k] == pytest.approx(want, rel=TOL_EXACT), (c.name, k)
+            assert got[k] == pytest.approx(want, rel=TOL_LOSS_EXACT_OUTLIER), (c.name, k)
         assert got["rtn"] < got["planted"]          # arbitrary decisions are worse than round-to-nearest
 
 
@@ -529,44 +718,31 @@ def test_smallest_layers_run_the_whole_path(O, K, T):
         r = fo.layer_step(c.W, q["s_global"], q["scales"], Vo, mo, uo, c.Xq, c.Y_fp, beta, HYP["lambda_round"], alpha,
                           HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], t)
         L = host(losses)
-        assert L[0] == pytest.approx(r["L_mse"], rel=2 * TOL_EXACT, abs=1e-12)   # a handful of terms: no averaging
+        assert L[0] == pytest.approx(r["L_mse"], rel=2 * TOL_LOSS_EXACT_OUTLIER, abs=1e-12)   # a handful of terms: no averaging
         assert L[1] == pytest.approx(r["L_round"], rel=1e-5, abs=1e-7)
         Vo, mo, uo = host(V).copy(), host(m).copy(), host(u).copy()               # re-synchronise
     codes, _, _, _ = faar.faar_harden_pack(Wd, sg, scales, V)
     assert np.array_equal(host(codes), fo.harden_pack(c.W, True, q["s_global"], q["scales"], host(V))["codes"])
 
 
-def test_full_size_q_proj_step_and_pack():
-    """The benchmark's own workload and launch configuration (Llama3-1B-shaped q_proj, W 2048x2048 bf16,
-    X 4096x2048): one whole step against the oracle -- the float64 matmuls of this size take a few seconds --
-    and bit-exact quantisation / packing of all 4.2 M weights."""
-    c = synth.llm_linear("q_proj", 2048, 2048, 4096, 0)
+@pytest.mark.parametrize("name", ["llama_q_proj", "llama_gate_proj"])
+def test_full_size_codec_bit_exact(name):
+    """Quantisation, V initialisation and hardening + packing of whole benchmark-sized tensors (4.2 M and 16.8 M
+    weights, the launch configurations the benchmark times), bit for bit against the oracle."""
+    c = build_case(name)
     q = fo.quant_rtn(c.W, True)
-    Wd, sg, scales, _, Xq, Y, Xt, C = _setup(c)
-    _, scales_g, codes_g, _ = faar.faar_quant_rtn(Wd)
-    assert np.array_equal(host(scales_g), q["scales"]) and np.array_equal(host(codes_g), q["codes"])
-    V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
-    Vg, _ = faar.faar_init_v(Wd, sg, scales)
-    assert np.array_equal(host(Vg).view(np.uint32), V0.view(np.uint32))
-    alpha = 1.0 / (c.T * c.O)
-    m = torch.zeros_like(Vg)
-    u = torch.zeros_like(Vg)
-    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
-    ws = faar.layer_step_workspace(c.O, c.K, c.T)
-    faar.faar_layer_step(Wd, sg, scales, Vg, m, u, Xq, Xt, *C, 8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"],
-                         HYP["beta2"], HYP["eps"], 1, losses, ws)
-    torch.cuda.synchronize()
-    ref = {mode: fo.layer_step(c.W, q["s_global"], q["scales"], V0, np.zeros_like(V0), np.zeros_like(V0), c.Xq, c.Y_fp,
-                               8.0, HYP["lambda_round"], alpha, HYP["lr"], HYP["beta1"], HYP["beta2"], HYP["eps"], 1,
-                               declared_rounding=mode) for mode in (False, True)}
-    L = host(losses)
-    assert L[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_EXACT)
-    assert L[0] == pytest.approx(ref[True]["L_mse"], rel=2e-5)
-    assert L[1] == pytest.approx(ref[False]["L_round"], rel=1e-5)
-    _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
-    _check_update(host(Vg), host(m), host(u), V0, np.zeros_like(V0), np.zeros_like(V0), 1)
-    hp = fo.harden_pack(c.W, True, q["s_global"], q["scales"], host(Vg))
-    codes2, dec, Wf, flips = faar.faar_harden_pack(Wd, sg, scales, Vg, want_decisions=True, want_final=True, want_flips=True)
+    Wd = dev(c.W, True)
+    sg, scales, codes_g, Wdq = faar.faar_quant_rtn(Wd, want_dq=True)
+    assert host(sg)[0].view(np.uint32) == np.float32(q["s_global"]).view(np.uint32)
+    assert np.array_equal(host(scales), q["scales"]) and np.array_equal(host(codes_g), q["codes"])
+    assert np.array_equal(host(Wdq).view(np.uint32), q["W_dq"].view(np.uint32))
+    iv = fo.init_v(c.W, q["s_global"], q["scales"])
+    Vg, fc = faar.faar_init_v(Wd, sg, scales, want_floor_codes=True)
+    assert np.array_equal(host(Vg).view(np.uint32), iv["V"].view(np.uint32))
+    assert np.array_equal(host(fc), iv["floor_codes"])
+    Vs = synth.rounding_variables(c.O, c.K, 77)
+    hp = fo.harden_pack(c.W, True, q["s_global"], q["scales"], Vs)
+    codes2, dec, Wf, flips = faar.faar_harden_pack(Wd, sg, scales, dev(Vs), want_decisions=True, want_final=True, want_flips=True)
     assert np.array_equal(host(codes2), hp["codes"]) and np.array_equal(host(dec), hp["decisions"])
     assert np.array_equal(host(Wf).view(np.uint32), hp["W_final"].view(np.uint32))
     assert int(flips.item()) == hp["flip_count"]

@@ -90,3 +90,33 @@ def test_stage2_degenerate_and_extreme_inputs():
     a = faar.faar_stage2_losses(dev(Zf), dev(Zq), 1.3, dev(Hf), dev(Hq))
     b = faar.faar_stage2_losses(dev(Zf), dev(Zq), 1.3, dev(Hf), dev(Hq))
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+@pytest.mark.parametrize("V", [4096, 128256])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stage2_masked_logits(V, dtype):
+    """Logits of -inf (masked vocabulary entries): probability 0, no contribution to the KL where P_fp = 0 (also when
+    only the full-precision model masks the entry), finite losses and gradients; +inf where only the quantised model
+    masks an entry the full-precision model gives weight to.  Both the plain and the register-resident row kernel."""
+    T, D = 4, 16
+    Zf, Zq, Hf, Hq = _inputs(T, V, D, 13)
+    if dtype == "bf16":
+        Zf, Zq, Hf, Hq = _bf16(Zf), _bf16(Zq), _bf16(Hf), _bf16(Hq)
+    Zf[:, 100:164] = -np.inf
+    Zq[:, 100:164] = -np.inf
+    Zf[1, 7] = -np.inf
+    Zf[2, :2048] = -np.inf          # the first chunks of every lane are all masked: the running maximum stays -inf
+    Zq[2, :1024] = -np.inf
+    td = torch.bfloat16 if dtype == "bf16" else torch.float32
+    dev = lambda a: torch.from_numpy(a).cuda().to(td)
+    ref = fo.stage2_losses(Zf, Zq, 1.0, 1.0 / T, Hf, Hq, 1.0, None, 1.0, 0.0)
+    losses, dZ, _ = faar.faar_stage2_losses(dev(Zf), dev(Zq), 1.0, dev(Hf), dev(Hq), kl_scale=1.0 / T)
+    L = losses.cpu().numpy().astype(np.float64)
+    assert np.isfinite(L).all() and L[0] == pytest.approx(ref["L_kl"], rel=1e-5, abs=2e-6)
+    gz = dZ.float().cpu().numpy().astype(np.float64)
+    ulp = 2.0 ** -8 if dtype == "bf16" else 0.0
+    assert np.isfinite(gz).all()
+    assert np.all(np.abs(gz - ref["dZ_q"]) <= 3e-6 / T + ulp * np.abs(ref["dZ_q"]))
+    Zq[0, 9] = -np.inf
+    losses, _, _ = faar.faar_stage2_losses(dev(Zf), dev(Zq), 1.0, dev(Hf), dev(Hq), kl_scale=1.0 / T)
+    assert losses[0].item() == np.inf

@@ -1,0 +1,56 @@
+"""CPU-only: the layer-step parity cases together reach every GEMM kernel variant the library can pick.
+
+faar_gemm_plan is a pure host function that reports the variant (tile shape, slice width, contraction split)
+the library uses for each GEMM of a layer.  The set of (GEMM, variant, split or not) combinations that ANY layer
+shape can produce is found by scanning a wide grid of shapes; the parity cases must cover all of it, so that no
+kernel instantiation runs in the benchmark without having been compared with the oracle."""
+import itertools
+
+from paper_2603_22370_amd import binding as fb
+
+from parity_cases import STEP_CASES
+
+GEMMS = {"residual": fb.K_GEMM_RESIDUAL, "dw": fb.K_GEMM_DW, "dx": fb.K_GEMM_DX, "c": fb.K_GEMM_C}
+DIMS = [16, 32, 48, 64, 80, 96, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512, 640, 768, 1024, 1280, 1536, 2048,
+        2560, 3072, 4096, 6144, 8192, 12288, 14336, 16384]
+TOKENS = [1, 3, 33, 64, 65, 100, 128, 256, 300, 512, 640, 1024, 1536, 2048, 3072, 4096, 8192, 16384, 65536]
+
+
+def _combos(O, K, T, chained):
+    for g, which in GEMMS.items():
+        if g == "dx" and not chained:
+            continue
+        kind, bm, bn, split = fb.faar_gemm_plan(which, O, K, T)
+        yield (g, kind, (bm, bn), "split" if split > 1 else "whole")
+
+
+def test_parity_cases_reach_every_gemm_variant():
+    reachable = {}
+    for O, K, T in itertools.product(DIMS, DIMS, TOKENS):
+        if O * K * T > 2 ** 40:
+            continue
+        for combo in _combos(O, K, T, chained=(O % 8 == 0)):
+            reachable.setdefault(combo, (O, K, T))
+    covered = set()
+    for c in STEP_CASES:
+        covered.update(_combos(c.O, c.K, c.T, c.chained))
+    missing = {k: v for k, v in reachable.items() if k not in covered}
+    assert not missing, f"variants no parity case reaches (with an example shape): {missing}"
+    # every variant name the library knows is reachable by some GEMM, so none is dead code
+    assert {k[1] for k in reachable} == set(fb.GEMM_KINDS)
+
+
+def test_benchmark_shapes_are_parity_cases_at_full_size():
+    """Every (variant, split) the Llama3-1B- and Qwen3-1.7B-shaped linears take at the benchmark's token counts is
+    also taken by a full-size parity case (several contraction slices, ring wrap-around, all tiles)."""
+    llama = [(2048, 2048), (512, 2048), (8192, 2048), (2048, 8192)]
+    qwen = [(2048, 2048), (1024, 2048), (6144, 2048), (2048, 6144)]
+    full = set()
+    for c in STEP_CASES:
+        if c.full_size:
+            full.update(_combos(c.O, c.K, c.T, c.chained))
+    for shapes, T, chained in ((llama, 4096, False), (qwen, 8192, False), (qwen, 16384, True)):
+        for O, K in shapes:
+            for combo in _combos(O, K, T, chained):
+                if combo[1] in ("L64", "M64"):          # the two fast kernels; the 128x128 one is covered by small cases
+                    assert combo in full, (O, K, T, combo)
