@@ -194,6 +194,23 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                            uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * faar_softquant_fwd_bwd for callers that cannot hand over a workspace because they cannot allocate one: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without ws /
+ * ws_bytes, same kernels, same results bit for bit.  The per-block Round-Loss partial sums live in a 512 KB array
+ * that is part of the library's code object (each GPU the library runs on holds its copy until the process ends),
+ * which bounds the tensor: O * K <= 2^27 weights, else FAAR_E_SHAPE.  The call allocates and frees nothing and does
+ * not synchronise.  The first call with dWt != NULL on each device looks up that device's copy of the array (not an
+ * allocation; make that call outside stream capture).  Every partial sum a call reads was written earlier in the same
+ * call, so nothing needs clearing between calls; but all calls on one GPU share the one array: calls that overlap on
+ * a GPU (two streams, two host threads) race on it and must be serialised by the caller.
+ */
+int faar_softquant_fwd_bwd_static(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                                  const float* s_global, const uint8_t* scales,
+                                  const float* V, float beta, void* Wt,
+                                  const float* dWt, float lambda_round, float* dV, float* round_loss,
+                                  uint32_t flags, void* stream);
+
+/*
  * Per-layer constants of the Stage-1 objective (Eq. 5, Table 2 steps 8-9), computed once before
  * the first faar_layer_step of a layer:
  *

@@ -62,6 +62,9 @@ def lib() -> ctypes.CDLL:
         L.faar_softquant_fwd_bwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float,
                                              c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p,
                                              c_size_t, c_void_p]
+        L.faar_softquant_fwd_bwd_static.restype = c_int
+        L.faar_softquant_fwd_bwd_static.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float,
+                                                    c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p]
         L.faar_layer_prepare.restype = c_int
         L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
                                          c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
@@ -199,6 +202,18 @@ def faar_softquant_fwd_bwd(W, s_global, scales, V, beta, dWt=None, lambda_round=
                                         _ptr(Wt), _ptr(dWt), float(lambda_round), _ptr(dV), _ptr(rl), flags,
                                         _ptr(ws), ws.numel(), _stream()), "faar_softquant_fwd_bwd")
     return Wt, dV, rl
+
+
+def faar_softquant_fwd_bwd_static(W, s_global, scales, V, beta, Wt, dWt=None, lambda_round=0.0, dV=None, round_loss=None,
+                                  emit_delta=False):
+    """The same operation through the entry point that allocates nothing: outputs (Wt bf16 [O,K], and with dWt also
+    dV f32 [O,K], round_loss f32[1]) are the caller's; no workspace."""
+    _dev(W, s_global, scales, V, Wt, dWt, dV, round_loss)
+    O, K = W.shape
+    flags = FAAR_EMIT_DELTA if emit_delta else 0
+    _check(lib().faar_softquant_fwd_bwd_static(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), float(beta),
+                                               _ptr(Wt), _ptr(dWt), float(lambda_round), _ptr(dV), _ptr(round_loss), flags,
+                                               _stream()), "faar_softquant_fwd_bwd_static")
 
 
 def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None):

@@ -1,11 +1,21 @@
 // extern "C" entry points of libfaar (declared and documented in include/faar.h): argument
 // validation, workspace carving and kernel sequencing.  Nothing here allocates or synchronises.
 #include <cmath>
+#include <mutex>
 
 #include "../../include/faar.h"
 #include "faar_internal.h"
 
 using namespace faar;
+
+// ---- scratch memory that lives in the code object, for faar_softquant_fwd_bwd_static ----
+// One double per block of the backward kernel (kEltThreads lanes x 8 weights each), for tensors of up to
+// kStaticMaxWeights weights.  Every GPU the library runs on holds its own copy of the array at its own address
+// until the process ends; the address is looked up once per device, with that device current, and kept
+// (static_scratch below).  Kernels receive that address as an argument like any other buffer.
+constexpr int64_t kStaticMaxWeights = (int64_t)1 << 27;
+constexpr int64_t kStaticPartials = kStaticMaxWeights / (8 * kEltThreads);   // 65536 doubles = 512 KB
+static __device__ __align__(256) double scratch[kStaticPartials];
 
 namespace {
 
@@ -132,6 +142,27 @@ int softquant_run(const void* W, faar_dtype wdt, int64_t O, int64_t K, const flo
   return FAAR_OK;
 }
 
+// The address of `scratch` (declared at file scope above) on the current device.  In host code the array's name is
+// only a handle for this lookup, never a device address.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(double** out) {
+  int dev = -1;
+  if (int e = hip_status(hipGetDevice(&dev))) return e;
+  if (dev < 0 || dev >= kMaxDevices) return FAAR_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (int e = hip_status(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)))) return e;
+    if (!p) return FAAR_E_HIP;
+    g_scratch_ptr[dev] = static_cast<double*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return FAAR_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -233,6 +264,19 @@ int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, 
   if (dWt && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_SOFTQUANT, O, K, 0, flags))) return FAAR_E_WORKSPACE;
   return softquant_run(W, wdt, O, K, s_global, scales, V, beta, Wt, dWt, lambda_round, dV, round_loss, flags,
                        static_cast<double*>(ws), static_cast<hipStream_t>(stream));
+}
+
+int faar_softquant_fwd_bwd_static(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
+                                  const uint8_t* scales, const float* V, float beta, void* Wt,
+                                  const float* dWt, float lambda_round, float* dV, float* round_loss,
+                                  uint32_t flags, void* stream) {
+  if (int e = softquant_check(W, wdt, O, K, s_global, scales, V, beta, Wt, dWt, lambda_round, dV, flags)) return e;
+  if (O * K > kStaticMaxWeights) return FAAR_E_SHAPE;  // the resident partial-sum array holds no more blocks
+  double* partials = nullptr;
+  if (dWt)
+    if (int e = static_scratch(&partials)) return e;
+  return softquant_run(W, wdt, O, K, s_global, scales, V, beta, Wt, dWt, lambda_round, dV, round_loss, flags, partials,
+                       static_cast<hipStream_t>(stream));
 }
 
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
