@@ -1,19 +1,28 @@
 """Benchmark of the FAAR per-layer rounding-optimisation path on one MI355X.
 
-Default workload (N=1): the Llama3-1B-shaped attention projection of the second configuration --
-q_proj, W 2048x2048 bf16 Student-t(4) scaled to std 0.02, calibration X 4096 tokens x 2048 bf16
-with 1% outlier channels x30 -- synthetic, seeded, resident in HBM before the timed region.
---workload picks another linear of the Llama3-1B- / Qwen3-1.7B-shaped blocks (see WORKLOADS).
+Default workload (N=1): one Qwen3-1.7B-shaped transformer layer -- the largest Stage-1 configuration of the
+workload list: its seven linears (q/o 2048x2048, k/v 1024x2048, gate/up 6144x2048, down 2048x6144), bf16
+Student-t(4) weights scaled to std 0.02, 8192 calibration tokens per linear with 1 % outlier channels x30
+(silu(g)*u inputs for the down projection) -- synthetic, seeded, resident in HBM before the timed region.
 
-Timed region: one whole per-layer job = faar_quant_rtn + faar_init_v + faar_layer_prepare, then
-EXACTLY K faar_layer_step calls (soft-quant, residual GEMM + loss, dW GEMM, dV + Round Loss + Adam +
-clip; beta annealed 4 -> 32), then faar_harden_pack.  value = K / elapsed (steps/s).
+Timed region: a whole per-layer job for each of the seven linears = faar_quant_rtn + faar_init_v +
+faar_layer_prepare, then EXACTLY K faar_layer_step calls per linear (soft-quantisation, residual GEMM + loss,
+dW GEMM, dV + Round Loss + Adam + clip; beta annealed 4 -> 32), then faar_harden_pack.  One "step" of the
+command line is one optimisation step of every linear; value = 7 K / elapsed (linear-layer steps / s).
 
-Also printed in the same JSON line:
-  roofline      -- the dominant kernel's achieved rate from HIP-event brackets around each of its
-                   launches (library hook faar_time_kernel), against the MI355X published peak
+Other workloads (--workload): one linear of the Llama3-1B- / Qwen3-1.7B- / Llama3-8B-shaped blocks by name;
+qwen_block_chained (the seven linears at 16384 tokens with dY supplied and dX produced); qwen_pack_sweep
+(quantise / initialise / harden+pack all 196 weight tensors of the model); stage2_losses; gemm_ceiling (what
+bounds the GEMM main loop: the loop with only its matrix instructions, with only its copies, and whole, with the
+clock the compute units ran at).
+
+Printed in the same JSON line:
+  roofline      -- the dominant kernel's achieved rate from HIP-event brackets around each of its launches
+                   (library hook faar_time_kernel), against the MI355X published peak
   kernels       -- the same measurement for every kernel of the path
-  cpu_baseline  -- the CPU oracle timed on this host on a bounded number of steps of the same layer
+  cpu_baseline  -- the CPU oracle timed on this host on a bounded sample of the same workload
+
+Launch it as `python3 bench.py ...` (also under rocprofv3: the program itself after `--`).
 """
 from __future__ import annotations
 
@@ -21,6 +30,7 @@ import argparse
 import ctypes
 import json
 import os
+import platform
 import sys
 import time
 
@@ -38,10 +48,17 @@ WORKLOADS = {
     "gate_proj": (8192, 2048, 4096, False), "down_proj": (2048, 8192, 4096, True),
     "qwen_k_proj": (1024, 2048, 8192, False), "qwen_q_proj": (2048, 2048, 8192, False),
     "qwen_gate_proj": (6144, 2048, 8192, False), "qwen_down_proj": (2048, 6144, 8192, True),
-    # Llama3-8B-shaped linears (the paper's larger model), T = 4096
     "llama8b_q_proj": (4096, 4096, 4096, False), "llama8b_k_proj": (1024, 4096, 4096, False),
     "llama8b_gate_proj": (14336, 4096, 4096, False), "llama8b_down_proj": (4096, 14336, 4096, True),
 }
+
+# The seven linears of one Qwen3-1.7B-shaped block: (name, O, K, input group, gated input)
+QWEN_BLOCK = [("q_proj", 2048, 2048, "attn_in", False), ("k_proj", 1024, 2048, "attn_in", False),
+              ("v_proj", 1024, 2048, "attn_in", False), ("o_proj", 2048, 2048, "attn_out", False),
+              ("gate_proj", 6144, 2048, "mlp_in", False), ("up_proj", 6144, 2048, "mlp_in", False),
+              ("down_proj", 2048, 6144, "mlp_mid", True)]
+QWEN_LAYERS = 28
+LAM, LR = 0.01, 5e-4
 
 
 def bytes_per_weight(dw_split: int) -> dict:
@@ -84,12 +101,366 @@ class HipEvents:
         return float(ms.value)
 
 
-# The seven linears of one Qwen3-1.7B-shaped block: name -> (O, K, input group, gated input)
-QWEN_BLOCK = [("q_proj", 2048, 2048, "attn_in", False), ("k_proj", 1024, 2048, "attn_in", False),
-              ("v_proj", 1024, 2048, "attn_in", False), ("o_proj", 2048, 2048, "attn_out", False),
-              ("gate_proj", 6144, 2048, "mlp_in", False), ("up_proj", 6144, 2048, "mlp_in", False),
-              ("down_proj", 2048, 6144, "mlp_mid", True)]
-QWEN_LAYERS = 28
+class KernelTimer:
+    """Average duration of one kernel of the path: HIP events recorded by the library around each of its launches, on
+    the stream it is launched on."""
+
+    def __init__(self):
+        self.ev = HipEvents()
+        self.e0, self.e1 = self.ev.create(), self.ev.create()
+
+    def time(self, which, call, n):
+        from paper_2603_22370_amd import binding as fb
+        ts = []
+        fb.faar_time_kernel(which, self.e0.value, self.e1.value)
+        try:
+            for i in range(n):
+                call(i)
+                ts.append(self.ev.elapsed_ms(self.e0, self.e1))
+        finally:
+            fb.faar_time_kernel(fb.K_NONE)
+        ts = ts[2:] if len(ts) > 4 else ts
+        return sum(ts) / len(ts)
+
+
+def host_description() -> dict:
+    """CPU model, thread count and BLAS of the host the oracle is timed on."""
+    model = platform.processor() or "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    threads, blas = os.cpu_count() or 1, "unknown BLAS"
+    try:
+        from threadpoolctl import threadpool_info
+        pools = [p for p in threadpool_info() if p.get("user_api") == "blas"]
+        if pools:
+            threads = max(p.get("num_threads", 1) for p in pools)
+            blas = ", ".join(f"{p.get('internal_api')} {p.get('version')}" for p in pools)
+    except Exception:
+        pass
+    import numpy as np
+    return {"cores": int(threads), "host": f"{model}; numpy {np.__version__} float64 on {blas}, {threads} threads"}
+
+
+def traffic_for(kernel: str, O: int, K: int, T: int):
+    """HBM-side bytes per launch of `kernel` on an O x K layer with T tokens, from the committed rocprofv3 counter
+    summary (profiles/hbm_traffic.txt: lines `kernel O K T fetch_MB write_MB`).  None when that exact kernel and shape
+    was not measured: a number is never carried over from another shape."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 6 and f[0] == kernel and f[1:4] == [str(O), str(K), str(T)]:
+            return int((float(f[4]) + float(f[5])) * 1e6)
+    return None
+
+
+class LinearJob:
+    """Device-resident inputs and state of one linear layer's rounding optimisation."""
+
+    def __init__(self, name, O, K, T, W, Xq, quantised_acts=False):
+        import torch
+
+        import paper_2603_22370_amd as faar
+        from paper_2603_22370_amd import binding as fb
+        self.name, self.O, self.K, self.T = name, O, K, T
+        self.W, self.Xq = W, Xq
+        self.Y = Xq @ W.T              # the frozen BF16 layer output: an input of the method (input generation only)
+        self.x_scale = None
+        if quantised_acts:             # X_q = NVFP4(X): node * block scale in bf16 (exact) and the tensor scale on the side
+            self.x_scale, _, _, self.Xq = faar.faar_quant_rtn(Xq, want_dq=True, dq_in_units=True)
+        self.alpha = 1.0 / (T * O)
+        self.losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+        self.ws = faar.layer_step_workspace(O, K, T)
+        self.ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, O, K), dtype=torch.uint8, device="cuda")
+        self.ws_p = torch.empty(max(256, faar.faar_workspace_bytes(fb.OP_LAYER_PREPARE, O, K, T)), dtype=torch.uint8, device="cuda")
+        self.dw_split = fb.faar_dw_split(O, K, T)
+        self.state = None
+
+    @staticmethod
+    def beta_at(t, total):
+        return 4.0 + 28.0 * (t - 1) / max(1, total - 1)
+
+    def setup(self):
+        import torch
+
+        import paper_2603_22370_amd as faar
+        sg, scales, codes, _ = faar.faar_quant_rtn(self.W, ws=self.ws_q)
+        V, _ = faar.faar_init_v(self.W, sg, scales)
+        Xt, C, ic = faar.faar_layer_prepare(self.W, sg, scales, self.Xq, self.Y, ws=self.ws_p, x_scale=self.x_scale)
+        self.state = dict(sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=Xt, C=C, ic=ic)
+
+    def step(self, t, total, beta=None, beta_next=None, forward_ready=None):
+        import paper_2603_22370_amd as faar
+        s = self.state
+        beta = self.beta_at(t, total) if beta is None else beta
+        if beta_next is None:      # every step but the last also prepares the next step's soft-quantised weights
+            beta_next = self.beta_at(t + 1, total) if t < total else 0.0
+        faar.faar_layer_step(self.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], self.Xq, s["Xt"], s["C"], s["ic"], beta,
+                             LAM, self.alpha, LR, 0.9, 0.999, 1e-8, t, self.losses, self.ws, beta_next=beta_next,
+                             forward_ready=(t > 1) if forward_ready is None else forward_ready, x_scale=self.x_scale)
+
+    def finish(self):
+        import paper_2603_22370_amd as faar
+        s = self.state
+        s["packed"], _, _, s["flips"] = faar.faar_harden_pack(self.W, s["sg"], s["scales"], s["V"], want_flips=True)
+
+    def hardened_losses(self):
+        import paper_2603_22370_amd as faar
+        s = self.state
+        V_rtn, _ = faar.faar_init_v(self.W, s["sg"], s["scales"])
+        rtn = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], V_rtn, self.Xq, s["C"], self.alpha, self.ws,
+                                            x_scale=self.x_scale).item())
+        opt = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], s["V"], self.Xq, s["C"], self.alpha, self.ws,
+                                            x_scale=self.x_scale).item())
+        return rtn, opt
+
+    def probe_kernels(self, timer, n_probe, t_base, codec=True):
+        """Per-kernel durations of this linear: name -> ms."""
+        import paper_2603_22370_amd as faar
+        from paper_2603_22370_amd import binding as fb
+        s = self.state
+        probe = {}
+
+        def first_step_call(i):      # a layer's first step: its own forward kernel, nothing prepared for the next
+            self.step(t_base + i, 0, beta=16.0, beta_next=0.0, forward_ready=False)
+
+        def step_call(i):            # every later step: forward taken from / left in the workspace
+            self.step(t_base + i, 0, beta=16.0, beta_next=16.0, forward_ready=i > 0)
+
+        probe["softquant_fwd"] = timer.time(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
+        for name, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
+            probe[name] = timer.time(kid, step_call, n_probe)
+        if codec:
+            probe["quant_rtn"] = timer.time(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(self.W, ws=self.ws_q), n_probe)
+            probe["init_v"] = timer.time(fb.K_INIT_V, lambda i: faar.faar_init_v(self.W, s["sg"], s["scales"]), n_probe)
+            probe["harden_pack"] = timer.time(fb.K_HARDEN_PACK,
+                                              lambda i: faar.faar_harden_pack(self.W, s["sg"], s["scales"], s["V"]), n_probe)
+        return probe
+
+    def kernel_table(self, probe):
+        gemm_flops = 2.0 * self.T * self.O * self.K
+        bpw = bytes_per_weight(self.dw_split)
+        N = self.O * self.K
+        # working set of one step: W, V, m, u, W_q - W, G partials, X_q, X_q^T, C, dY^T
+        step_bytes = N * (2 + 12 + 2 + 4 * self.dw_split) + self.T * self.K * 4 + self.T * self.O * 6
+        out = {}
+        for name, ms in probe.items():
+            if name.startswith("gemm"):
+                ach = gemm_flops / (ms * 1e-3) / 1e12
+                out[name] = {"ms": round(ms, 5), "bound": "mfma", "achieved": round(ach, 2), "unit": "TFLOP/s",
+                             "frac": round(ach / BF16_PEAK_TFLOPS, 4)}
+            else:
+                ach = bpw[name] * N / (ms * 1e-3) / 1e9
+                out[name] = {"ms": round(ms, 5), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
+                             "frac": round(ach / HBM_PEAK_GBS, 4)}
+                if step_bytes < 256e6:     # the step's working set fits the 256 MB Infinity Cache: not an HBM rate
+                    out[name]["note"] = "effective rate: working set resident in the Infinity Cache"
+            out[name]["traffic"] = traffic_for(name, self.O, self.K, self.T)
+        return out
+
+
+def oracle_step_time(job_inputs, seconds, max_steps=500):
+    """Times fo.layer_step (exact mode) on host copies of one linear's inputs: (steps done, seconds)."""
+    import numpy as np
+
+    from oracle import faar_oracle as fo
+    W_h, X_h, Y_h, alpha = job_inputs
+    q = fo.quant_rtn(W_h, True)
+    V0 = fo.init_v(W_h, q["s_global"], q["scales"])["V"]
+    m0, u0 = np.zeros_like(V0), np.zeros_like(V0)
+    n, t_cpu = 0, 0.0
+    while n < 1 or (t_cpu < seconds and n < max_steps):
+        c0 = time.perf_counter()
+        r = fo.layer_step(W_h, q["s_global"], q["scales"], V0, m0, u0, X_h, Y_h, LinearJob.beta_at(n + 1, 500), LAM, alpha,
+                          LR, 0.9, 0.999, 1e-8, n + 1)
+        V0, m0, u0 = r["V"], r["m"], r["u"]
+        t_cpu += time.perf_counter() - c0
+        n += 1
+    return n, t_cpu
+
+
+def make_block_jobs(T, quantised_acts=False):
+    import torch
+
+    from workloads import synth
+    X_by_group, jobs = {}, []
+    for idx, (name, O, K, group, gated) in enumerate(QWEN_BLOCK):
+        if group not in X_by_group:
+            X_h = synth.silu_gated_activations(T, K, seed=idx) if gated else synth.activations(T, K, seed=idx)
+            X_by_group[group] = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
+        W = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
+        jobs.append(LinearJob(name, O, K, T, W, X_by_group[group], quantised_acts))
+    return jobs
+
+
+def run_layer(args) -> dict:
+    """The default: one Qwen3-1.7B-shaped layer, all seven linears, 8192 tokens (see the module docstring)."""
+    import torch
+
+    T = 8192
+    jobs = make_block_jobs(T, args.quantised_acts)
+    torch.cuda.synchronize()
+
+    def layer_job(n_steps):
+        for j in jobs:
+            j.setup()
+            for t in range(1, n_steps + 1):
+                j.step(t, n_steps)
+            j.finish()
+
+    layer_job(max(1, args.warmup))          # warm-up (untimed)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    layer_job(args.steps)                    # timed region: exactly K steps of every linear inside whole per-layer jobs
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    n_lin = len(jobs)
+    weights = sum(j.O * j.K for j in jobs)
+    flops_per_set = sum(2 * 2.0 * T * j.O * j.K for j in jobs)
+    per_linear, timer = {}, KernelTimer()
+    n_probe = max(5, args.probe_steps)
+    for j in jobs:
+        rtn, opt = j.hardened_losses()
+        table = j.kernel_table(j.probe_kernels(timer, n_probe, args.steps + 1, codec=True))
+        per_linear[j.name] = {"O": j.O, "K": j.K, "dw_split": j.dw_split, "final_losses": j.losses.cpu().numpy().tolist(),
+                              "flipped_decisions": int(j.state["flips"].item()), "hardened_loss": {"rtn": rtn, "faar": opt},
+                              "kernels": table}
+    # the kernel that takes the largest share of a step of the whole layer
+    dom_l, dom_k = max(((l, k) for l in per_linear for k in ("gemm_residual", "gemm_dw", "bwd_adam")),
+                       key=lambda lk: per_linear[lk[0]]["kernels"][lk[1]]["ms"])
+    dom = per_linear[dom_l]["kernels"][dom_k]
+    ms_per_step = elapsed / args.steps * 1e3
+    out = {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(n_lin * args.steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qwen_layer: the 7 linears of one Qwen3-1.7B-shaped layer (q/o 2048x2048, k/v 1024x2048, gate/up "
+                               "6144x2048, down 2048x6144; bf16 Student-t(4) std 0.02), X 8192 tokens "
+                               f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'} with 1% outlier channels x30, "
+                               "NVFP4 block 16; per linear: quant_rtn + init_v + prepare + K steps + harden_pack; one timed step = "
+                               "one step of every linear; value = linear-layer steps/s",
+                   "T": T, "linears": n_lin, "weights": weights},
+        "weight_elems_per_sec": round(weights * args.steps / elapsed, 1),
+        "step_gemm_tflops": round(flops_per_set / (ms_per_step * 1e-3) / 1e12, 1),
+        "roofline": {"kernel": f"{dom_l}.{dom_k}", "bound": dom["bound"], "achieved": dom["achieved"],
+                     "peak": BF16_PEAK_TFLOPS if dom["bound"] == "mfma" else HBM_PEAK_GBS, "unit": dom["unit"],
+                     "frac": dom["frac"], "traffic": dom["traffic"], "launch_ms": dom["ms"]},
+        "per_linear": per_linear,
+    }
+    if not args.no_cpu_baseline:
+        # one step of each of the seven linears (2 x 824 GF of float64 products)
+        t_cpu, n_cpu = 0.0, 0
+        for j in jobs:
+            xs = j.x_scale if j.x_scale is not None else 1.0
+            n, t = oracle_step_time((j.W.float().cpu().numpy(), (j.Xq.float() * xs).cpu().numpy(), j.Y.float().cpu().numpy(),
+                                     j.alpha), seconds=0.0, max_steps=1)
+            n_cpu += n
+            t_cpu += t
+        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"one step of each of the {n_cpu} linears of the same layer ({t_cpu:.1f} s)",
+                               **host_description()}
+    return out
+
+
+def run_linear(args) -> dict:
+    """One linear layer's whole job (the shapes of WORKLOADS)."""
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from workloads import synth
+
+    O, K, T, gated = WORKLOADS[args.workload]
+    W_h = synth.student_t_weight(O, K, seed=0)
+    X_h = synth.silu_gated_activations(T, K, seed=0) if gated else synth.activations(T, K, seed=0)
+    W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
+    Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
+    j = LinearJob(args.workload, O, K, T, W, Xq, args.quantised_acts)
+    torch.cuda.synchronize()
+
+    def layer_job(n_steps):
+        j.setup()
+        for t in range(1, n_steps + 1):
+            j.step(t, n_steps)
+        j.finish()
+
+    layer_job(max(1, args.warmup))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    layer_job(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    final_losses = j.losses.cpu().numpy().tolist()
+    n_flips = int(j.state["flips"].item())
+    loss_rtn, loss_faar = j.hardened_losses()
+    s = j.state
+    stochastic = None
+    if args.stochastic_trials > 0:
+        trial = torch.empty(args.stochastic_trials, dtype=torch.float32, device="cuda")
+        for k in range(args.stochastic_trials):
+            Vs = faar.faar_stochastic_v(W, s["sg"], s["scales"], 2603, k)
+            faar.faar_hardened_loss(W, s["sg"], s["scales"], Vs, j.Xq, s["C"], j.alpha, j.ws, x_scale=j.x_scale, loss=trial[k:k + 1])
+        tl = trial.cpu().numpy()
+        stochastic = {"trials": int(tl.size), "better_than_rtn": int((tl < loss_rtn).sum()), "best": float(tl.min()),
+                      "mean": float(tl.mean()), "std": float(tl.std())}
+
+    timer = KernelTimer()
+    n_probe = max(5, args.probe_steps)
+    probe = j.probe_kernels(timer, n_probe, args.steps + 1)
+    # the stand-alone soft-quantisation entry point (forward + backward from a given dL/dW_q; it re-derives the
+    # intervals from W and the scales on every call): torch events around the whole call, output allocation included
+    dWt = torch.randn((O, K), device="cuda") * 1e-3
+    te0, te1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(n_probe + 3):
+        if i == 3:
+            te0.record()
+        faar.faar_softquant_fwd_bwd(W, s["sg"], s["scales"], s["V"], 16.0, dWt=dWt, lambda_round=LAM, emit_delta=True)
+    te1.record()
+    torch.cuda.synchronize()
+    probe["softquant_fwd_bwd_call"] = te0.elapsed_time(te1) / n_probe
+    del dWt
+    kernels = j.kernel_table(probe)
+    dom = max(("gemm_residual", "gemm_dw", "bwd_adam"), key=lambda k: probe[k])
+    roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
+                "peak": BF16_PEAK_TFLOPS if kernels[dom]["bound"] == "mfma" else HBM_PEAK_GBS,
+                "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": kernels[dom]["traffic"],
+                "launch_ms": kernels[dom]["ms"]}
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    ms_per_step = elapsed / args.steps * 1e3
+    gemm_flops = 2.0 * T * O * K
+    out = {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} "
+                               f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'}, NVFP4 block 16; "
+                               "per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
+                   "O": O, "K": K, "T": T},
+        "weight_elems_per_sec": round(O * K * args.steps / elapsed, 1),
+        "step_gemm_tflops": round(2 * gemm_flops / (ms_per_step * 1e-3) / 1e12, 1),
+        "dw_split": j.dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
+        "hardened_loss": {"rtn": loss_rtn, "faar": loss_faar, "stochastic": stochastic},
+        "roofline": roofline, "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        X_used = (j.Xq.float() * (j.x_scale if j.x_scale is not None else 1.0)).cpu().numpy()
+        n_cpu, t_cpu = oracle_step_time((W_h, X_used, j.Y.float().cpu().numpy(), j.alpha), args.cpu_seconds)
+        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"{n_cpu} layer steps of the same {args.workload} layer ({t_cpu:.1f} s)",
+                               **host_description()}
+    return out
 
 
 def run_block_chained(args) -> dict:
@@ -100,87 +471,68 @@ def run_block_chained(args) -> dict:
 
     import paper_2603_22370_amd as faar
     from paper_2603_22370_amd import binding as fb
-    from workloads import synth
 
     T = 16384
     steps = min(args.steps, 50)
     warmup = min(args.warmup, 5)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(5)
-    X_by_group, lin = {}, []
-    for idx, (name, O, K, group, gated) in enumerate(QWEN_BLOCK):
-        if group not in X_by_group:
-            X_h = synth.silu_gated_activations(T, K, seed=idx) if gated else synth.activations(T, K, seed=idx)
-            X_by_group[group] = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
-        Xq = X_by_group[group]
-        W = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
-        Y = Xq @ W.T                                                     # input generation only
-        dY = (torch.randn((T, O), generator=gen, device="cuda") * 1e-3).to(torch.bfloat16)
-        sg, scales, _, _ = faar.faar_quant_rtn(W)
-        V, _ = faar.faar_init_v(W, sg, scales)
-        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y)
-        del Y
-        lin.append(dict(name=name, O=O, K=K, W=W, sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V),
-                        Xq=Xq, Xt=Xt, C=C, ic=ic, dY=dY, dX=torch.empty((T, K), dtype=torch.bfloat16, device="cuda"),
-                        ws=faar.layer_step_workspace(O, K, T, chained=True),
-                        losses=torch.zeros(3, dtype=torch.float32, device="cuda"), ready=False))
-    lam, lr = 0.01, 5e-4
+    jobs = make_block_jobs(T)
+    lin = []
+    for j in jobs:
+        j.setup()
+        j.Y = None
+        j.ws = None
+        dY = (torch.randn((T, j.O), generator=gen, device="cuda") * 1e-3).to(torch.bfloat16)
+        lin.append(dict(j=j, dY=dY, dX=torch.empty((T, j.K), dtype=torch.bfloat16, device="cuda"),
+                        ws=faar.layer_step_workspace(j.O, j.K, T, chained=True), t=0, ready=False))
 
-    def step_linear(L, t, beta=16.0, fused=True):
-        faar.faar_layer_step(L["W"], L["sg"], L["scales"], L["V"], L["m"], L["u"], L["Xq"], L["Xt"], L["C"], L["ic"], beta,
-                             lam, 1.0 / (T * L["O"]), lr, 0.9, 0.999, 1e-8, t, L["losses"], L["ws"], dY_ext=L["dY"],
-                             dX=L["dX"], beta_next=beta if fused else 0.0, forward_ready=fused and L["ready"])
-        L["ready"] = fused
+    def step_linear(L, beta=16.0):
+        j, s = L["j"], L["j"].state
+        L["t"] += 1
+        faar.faar_layer_step(j.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], j.Xq, s["Xt"], s["C"], s["ic"], beta,
+                             LAM, j.alpha, LR, 0.9, 0.999, 1e-8, L["t"], j.losses, L["ws"], dY_ext=L["dY"],
+                             dX=L["dX"], beta_next=beta, forward_ready=L["ready"])
+        L["ready"] = True
 
-    t = 0
     for _ in range(warmup):
-        t += 1
         for L in lin:
-            step_linear(L, t)
+            step_linear(L)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        t += 1
         for L in lin:
-            step_linear(L, t)
+            step_linear(L)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    ev = HipEvents()
-    e0, e1 = ev.create(), ev.create()
+    timer = KernelTimer()
     per_linear = {}
     total_flops = 0.0
     for L in lin:
-        O, K = L["O"], L["K"]
+        j = L["j"]
+        O, K = j.O, j.K
         flops = 2.0 * T * O * K
         total_flops += 3 * flops
         row = {}
         for kname, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("gemm_dx", fb.K_GEMM_DX),
                            ("bwd_adam", fb.K_BWD_ADAM)]:
-            ts = []
-            fb.faar_time_kernel(kid, e0.value, e1.value)
-            try:
-                for _ in range(6):
-                    t += 1
-                    step_linear(L, t)
-                    ts.append(ev.elapsed_ms(e0, e1))
-            finally:
-                fb.faar_time_kernel(fb.K_NONE)
-            ms = sum(ts[2:]) / len(ts[2:])
+            ms = timer.time(kid, lambda i: step_linear(L), 6)
             if kname.startswith("gemm"):
                 row[kname] = {"ms": round(ms, 5), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
                               "frac": round(flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)}
             else:
-                b = bytes_per_weight(fb.faar_dw_split(O, K, T))["bwd_adam"] + 2      # + W_q for the next dX
+                b = bytes_per_weight(j.dw_split)["bwd_adam"] + 2      # + W_q for the next dX
                 row[kname] = {"ms": round(ms, 5), "gbs": round(b * O * K / (ms * 1e-3) / 1e9, 1),
                               "frac": round(b * O * K / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        row["dw_split"] = fb.faar_dw_split(O, K, T)
-        per_linear[L["name"]] = row
+        row["dw_split"] = j.dw_split
+        row["losses"] = j.losses.cpu().numpy().tolist()
+        per_linear[j.name] = row
     dom_l, dom_k = max(((l, k) for l in per_linear for k in ("gemm_residual", "gemm_dw", "gemm_dx")),
                        key=lambda lk: per_linear[lk[0]][lk[1]]["ms"])
     dom = per_linear[dom_l][dom_k]
     n_lin = len(lin)
-    return {
+    out = {
         "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(n_lin * steps / elapsed, 2), "unit": "steps/s",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
@@ -193,12 +545,40 @@ def run_block_chained(args) -> dict:
                      "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "launch_ms": dom["ms"]},
         "per_linear": per_linear,
     }
+    if not args.no_cpu_baseline:
+        # the oracle's chained step (dY given, dX produced) on the smallest linear of the block, k_proj; the other six
+        # are scaled by their share of the products: labelled as extrapolated
+        import numpy as np
+
+        from oracle import faar_oracle as fo
+        L = lin[1]
+        j = L["j"]
+        W_h, X_h = j.W.float().cpu().numpy(), j.Xq.float().cpu().numpy()
+        Y_h = (j.Xq @ j.W.T).float().cpu().numpy()
+        dY_h = L["dY"].float().cpu().numpy()
+        q = fo.quant_rtn(W_h, True)
+        V0 = fo.init_v(W_h, q["s_global"], q["scales"])["V"]
+        z = np.zeros_like(V0)
+        n, t_cpu = 0, 0.0
+        while n < 1 or (t_cpu < args.cpu_seconds and n < 20):
+            c0 = time.perf_counter()
+            fo.layer_step(W_h, q["s_global"], q["scales"], V0, z, z, X_h, Y_h, 16.0, LAM, j.alpha, LR, 0.9, 0.999, 1e-8, n + 1,
+                          want_dX=True, dY_ext=dY_h)
+            t_cpu += time.perf_counter() - c0
+            n += 1
+        share = (j.O * j.K) / sum(x["j"].O * x["j"].K for x in lin)
+        out["cpu_baseline"] = {"value": round(n_lin / (t_cpu / n / share), 4), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"{n} chained steps of k_proj 1024x2048 at T 16384 measured ({t_cpu / n:.2f} s each); the block's "
+                                         f"7 linears extrapolated by weight count (k_proj is {share:.3f} of the block)",
+                               **host_description()}
+    return out
 
 
 def run_pack_sweep(args) -> dict:
-    """Set-up and tear-down kernels over every linear of a Qwen3-1.7B-shaped model (28 layers x 7 linears,
-    1.409 G weights, each tensor in memory of its own): faar_quant_rtn, faar_init_v and faar_harden_pack,
-    each timed as a sweep over all 196 tensors.  `value` is the harden+pack rate."""
+    """Set-up and tear-down over every linear of a Qwen3-1.7B-shaped model (28 layers x 7 linears, 1.409 G weights,
+    each tensor in memory of its own): quantisation, V initialisation and hardening + packing, each as ONE batched call
+    over all 196 tensors (5 launches of up to 48 tensors), outputs preallocated.  `value` is the harden+pack rate.
+    The same sweeps as 196 single-tensor calls are reported beside them."""
     import torch
 
     import paper_2603_22370_amd as faar
@@ -211,59 +591,104 @@ def run_pack_sweep(args) -> dict:
             base[(O, K)] = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(7)
-    tensors = []
+    Ws, Vs, sgs, scs, cds = [], [], [], [], []
     n_total = 0
     for layer in range(QWEN_LAYERS):
         for name, O, K, _, _ in QWEN_BLOCK:
-            W = base[(O, K)].clone()
-            V = torch.rand((O, K), generator=gen, device="cuda", dtype=torch.float32)   # rounding variables mid-optimisation
-            tensors.append([W, V, None, None])
+            Ws.append(base[(O, K)].clone())
+            Vs.append(torch.rand((O, K), generator=gen, device="cuda", dtype=torch.float32))   # rounding variables mid-optimisation
+            sgs.append(torch.empty(1, dtype=torch.float32, device="cuda"))
+            scs.append(torch.empty((O, K // 16), dtype=torch.uint8, device="cuda"))
+            cds.append(torch.empty((O, K // 2), dtype=torch.uint8, device="cuda"))
             n_total += O * K
+    ws_b = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN_BATCH, 16, 16), dtype=torch.uint8, device="cuda")
     ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, 6144, 2048), dtype=torch.uint8, device="cuda")
-    reps = 5
+    items_q, dt = faar.tensor_batch(Ws, sgs, scs, codes=cds)
+    Vout = [torch.empty_like(v) for v in Vs]         # V initialisation writes 5.6 GB: every tensor gets its own output
+    items_i, _ = faar.tensor_batch(Ws, sgs, scs, Vs=Vout)
+    items_p, _ = faar.tensor_batch(Ws, sgs, scs, Vs=Vs, codes=cds)
+    reps = max(3, min(args.steps, 10))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def sweep(fn):
+        fn()
         torch.cuda.synchronize()
         best = None
         for _ in range(reps):
-            t0 = time.perf_counter()
-            for rec in tensors:
-                fn(rec)
+            e0.record()
+            fn()
+            e1.record()
             torch.cuda.synchronize()
-            dt = time.perf_counter() - t0
-            best = dt if best is None else min(best, dt)
-        return best
+            dt_ms = e0.elapsed_time(e1)
+            best = dt_ms if best is None else min(best, dt_ms)
+        return best * 1e-3
 
-    def do_quant(rec):
-        rec[2], rec[3], _, _ = faar.faar_quant_rtn(rec[0], ws=ws_q)
+    L = fb.lib()
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
 
-    t_quant = sweep(do_quant)
-    t_init = sweep(lambda rec: faar.faar_init_v(rec[0], rec[2], rec[3]))
-    t_pack = sweep(lambda rec: faar.faar_harden_pack(rec[0], rec[2], rec[3], rec[1]))
+    def single_quant():
+        for k, W in enumerate(Ws):
+            L.faar_quant_rtn(ptr(W), 1, W.shape[0], W.shape[1], ptr(sgs[k]), ptr(scs[k]), ptr(cds[k]), None, 0, ptr(ws_q), ws_q.numel(), st)
+
+    def single_init():
+        for k, W in enumerate(Ws):
+            L.faar_init_v(ptr(W), 1, W.shape[0], W.shape[1], ptr(sgs[k]), ptr(scs[k]), ptr(Vout[k]), None, st)
+
+    def single_pack():
+        for k, W in enumerate(Ws):
+            L.faar_harden_pack(ptr(W), 1, W.shape[0], W.shape[1], ptr(sgs[k]), ptr(scs[k]), ptr(Vs[k]), ptr(cds[k]), None, None, None, st)
+
+    t = {"quant_rtn": sweep(lambda: faar.faar_quant_rtn_batch(items_q, dt, ws_b)),
+         "init_v": sweep(lambda: faar.faar_init_v_batch(items_i, dt)),
+         "harden_pack": sweep(lambda: faar.faar_harden_pack_batch(items_p, dt))}
+    t1 = {"quant_rtn": sweep(single_quant), "init_v": sweep(single_init), "harden_pack": sweep(single_pack)}
     bpw = bytes_per_weight(1)
+    bytes_of = {"quant_rtn": bpw["quant_rtn"] + 2, "init_v": bpw["init_v"], "harden_pack": bpw["harden_pack"]}
     rows = {}
-    for name, tt, b in (("quant_rtn", t_quant, bpw["quant_rtn"] + 2), ("init_v", t_init, bpw["init_v"]),
-                        ("harden_pack", t_pack, bpw["harden_pack"])):
-        rows[name] = {"ms": round(tt * 1e3, 3), "gbs": round(b * n_total / tt / 1e9, 1),
-                      "frac": round(b * n_total / tt / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_weight": b}
-    return {
-        "metric": "NVFP4 harden+pack weight elements/sec", "value": round(n_total / t_pack, 1), "unit": "elems/s",
-        "n_gpus": 1, "steps": reps, "warmup": 0, "ms_per_step": rows["harden_pack"]["ms"], "higher_is_better": True,
+    for name in t:
+        b = bytes_of[name]
+        rows[name] = {"ms": round(t[name] * 1e3, 3), "gbs": round(b * n_total / t[name] / 1e9, 1),
+                      "frac": round(b * n_total / t[name] / 1e9 / HBM_PEAK_GBS, 4), "bytes_per_weight": b,
+                      "single_tensor_calls_ms": round(t1[name] * 1e3, 3),
+                      "single_tensor_calls_gbs": round(b * n_total / t1[name] / 1e9, 1)}
+    out = {
+        "metric": "NVFP4 harden+pack weight elements/sec", "value": round(n_total / t["harden_pack"], 1), "unit": "elems/s",
+        "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": rows["harden_pack"]["ms"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
-        "config": {"workload": f"qwen_pack_sweep: {len(tensors)} weight tensors of a Qwen3-1.7B-shaped model "
-                               f"({n_total / 1e9:.3f} G weights, bf16 W + float32 V in, NVFP4 codes out); best of {reps} sweeps; "
-                               "times include the allocation of each output by the binding",
+        "config": {"workload": f"qwen_pack_sweep: {len(Ws)} weight tensors of a Qwen3-1.7B-shaped model "
+                               f"({n_total / 1e9:.3f} G weights, bf16 W + float32 V in, NVFP4 codes out), one batched call per "
+                               f"operation; best of {reps} sweeps, GPU time between events on the launch stream",
                    "weights": n_total},
-        "roofline": {"kernel": "harden_pack", "bound": "hbm", "achieved": rows["harden_pack"]["gbs"], "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": rows["harden_pack"]["frac"], "traffic": None},
+        "roofline": {"kernel": "harden_pack (batched)", "bound": "hbm", "achieved": rows["harden_pack"]["gbs"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": rows["harden_pack"]["frac"], "traffic": None, "launch_ms": rows["harden_pack"]["ms"]},
         "sweeps": rows,
     }
+    if not args.no_cpu_baseline:
+        # the oracle's quantise / initialise / harden+pack on the smallest tensor of the model (k_proj, 2.1 M weights);
+        # the model's 1.409 G weights are extrapolated linearly (the work is O(N))
+        from oracle import faar_oracle as fo
+        W_h = base[(1024, 2048)].float().cpu().numpy()
+        V_h = Vs[1].cpu().numpy()
+        n, t_cpu = 0, 0.0
+        while n < 1 or (t_cpu < args.cpu_seconds and n < 100):
+            c0 = time.perf_counter()
+            q = fo.quant_rtn(W_h, True)
+            fo.init_v(W_h, q["s_global"], q["scales"])
+            fo.harden_pack(W_h, True, q["s_global"], q["scales"], V_h)
+            t_cpu += time.perf_counter() - c0
+            n += 1
+        out["cpu_baseline"] = {"value": round(W_h.size * n / t_cpu, 1), "unit": "elems/s", "kind": "oracle",
+                               "sample": f"quantise + initialise + harden+pack of one k_proj tensor (2.1 M weights) {n} times "
+                                         f"({t_cpu:.1f} s); all three operations, so a lower bound of the pack rate; the model's "
+                                         "196 tensors extrapolated linearly (O(N) work)",
+                               **host_description()}
+    return out
 
 
 def run_stage2(args) -> dict:
     """faar_stage2_losses on Llama3-1B-shaped model outputs: 4096 tokens, vocabulary 128256, hidden size 2048,
     bf16 logits and hidden states, losses and both gradients.  One timed step = one call."""
-    import numpy as np
     import torch
 
     import paper_2603_22370_amd as faar
@@ -288,17 +713,7 @@ def run_stage2(args) -> dict:
         losses, dZ, dH = faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    ev = HipEvents()
-    e0, e1 = ev.create(), ev.create()
-    ts = []
-    fb.faar_time_kernel(fb.K_STAGE2_KL, e0.value, e1.value)
-    try:
-        for _ in range(8):
-            faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
-            ts.append(ev.elapsed_ms(e0, e1))
-    finally:
-        fb.faar_time_kernel(fb.K_NONE)
-    ms = sum(ts[2:]) / len(ts[2:])
+    ms = KernelTimer().time(fb.K_STAGE2_KL, lambda i: faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw), 8)
     algo = (T * V + T * D) * (2 + 2 + 2)            # read both tensors once, write the gradient (bf16)
     gbs = algo / (ms * 1e-3) / 1e9
     out = {
@@ -314,11 +729,6 @@ def run_stage2(args) -> dict:
     }
     if not args.no_cpu_baseline:
         from oracle import faar_oracle as fo
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count() or 1
         rows = 64
         zf, zq = Zf[:rows].float().cpu().numpy(), Zq[:rows].float().cpu().numpy()
         hf, hq = Hf[:rows].float().cpu().numpy(), Hq[:rows].float().cpu().numpy()
@@ -328,234 +738,93 @@ def run_stage2(args) -> dict:
             fo.stage2_losses(zf, zq, tau, 1.0 / T, hf, hq, 1.0 / (T * D), rl.cpu().numpy(), 1.0, 0.01)
             t_cpu += time.perf_counter() - c0
             n += 1
-        out["cpu_baseline"] = {"value": round(n * rows / T / t_cpu, 5), "unit": "steps/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"{n} evaluations of {rows} of the {T} token rows (numpy float64, {t_cpu:.1f} s), "
-                                         "scaled to whole steps"}
+        out["cpu_baseline"] = {"value": round(n * rows / T / t_cpu, 5), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"{n} evaluations of {rows} of the {T} token rows ({t_cpu:.1f} s), "
+                                         "scaled to whole steps", **host_description()}
     return out
+
+
+def run_gemm_ceiling(args) -> dict:
+    """What bounds the GEMM main loop, measured through the library's own kernel (faar_gemm_probe) on the product of the
+    Llama3-1B-shaped gate_proj dW GEMM (8192 x 2048 outputs, contraction over 4096 tokens), random bf16 operands: the
+    loop with only its matrix instructions (operands read from LDS, nothing copied), with only its global->LDS copies,
+    and whole -- each with the core clock the compute units ran at (shader clock counter / constant 100 MHz counter)."""
+    import torch
+
+    from paper_2603_22370_amd import binding as fb
+
+    M, N, Kd = 8192, 2048, 4096
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    A = torch.randn((M, Kd), generator=gen, device="cuda").to(torch.bfloat16)
+    B = torch.randn((N, Kd), generator=gen, device="cuda").to(torch.bfloat16)
+    A0, B0 = torch.zeros_like(A), torch.zeros_like(B)
+    flops = 2.0 * M * N * Kd
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    rows = {}
+    for label, mode, a, b in (("whole loop", fb.PROBE_FULL, A, B), ("matrix instructions only", fb.PROBE_MFMA_ONLY, A, B),
+                              ("copies only", fb.PROBE_DMA_ONLY, A, B), ("whole loop, all-zero operands", fb.PROBE_FULL, A0, B0)):
+        for _ in range(3):
+            clocks, variant = fb.faar_gemm_probe(mode, a, b)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(10):
+            clocks, variant = fb.faar_gemm_probe(mode, a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 10 * 1e3
+        c = clocks.cpu().numpy().astype("float64")
+        core, wall = c[:, 0], c[:, 1]
+        mhz = float((core / (wall / 100.0)).mean())            # the constant counter ticks at 100 MHz
+        row = {"us": round(us, 1), "core_mhz": round(mhz, 0), "core_cycles_per_item": round(float(core.mean()), 0), "variant": variant}
+        if mode != fb.PROBE_DMA_ONLY:
+            row["tflops"] = round(flops / us / 1e6, 1)
+            row["frac_of_published_peak"] = round(flops / us / 1e6 / BF16_PEAK_TFLOPS, 4)
+            # what the matrix cores can deliver at the clock they actually ran at
+            row["frac_of_peak_at_measured_clock"] = round(flops / us / 1e6 / (BF16_PEAK_TFLOPS * mhz / 2400.0), 4)
+        rows[label] = row
+    whole = rows["whole loop"]
+    return {
+        "metric": "GEMM main-loop ceiling", "value": whole["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": 10, "warmup": 3,
+        "ms_per_step": round(whole["us"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"gemm_ceiling: {M}x{N} outputs, contraction {Kd}, bf16 N(0,1) operands, float32 output", "M": M, "N": N, "Kd": Kd},
+        "roofline": {"kernel": f"gemm main loop ({whole['variant']})", "bound": "mfma", "achieved": whole["tflops"],
+                     "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": whole["frac_of_published_peak"], "traffic": None,
+                     "launch_ms": round(whole["us"] * 1e-3, 5)},
+        "modes": rows,
+    }
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="q_proj", choices=sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep", "stage2_losses"])
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen_layer",
+                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
-                    help="after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
+                    help="single-linear workloads: after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
-    ap.add_argument("--probe-steps", type=int, default=20)
+    ap.add_argument("--probe-steps", type=int, default=12)
     ap.add_argument("--calib-copy", action="store_true",
-                    help="also run a plain 256 MiB device copy three times (reference for scaling HBM byte counters)")
+                    help="single-linear workloads: also run a plain 256 MiB device copy three times (reference for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path has no collectives or sharding "
               "(layers and output rows are independent jobs: shard those across processes). Use --gpus 1.", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
-
-    import paper_2603_22370_amd as faar
-    from paper_2603_22370_amd import binding as fb
-    from workloads import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    if args.workload == "qwen_block_chained":
-        print(json.dumps(run_block_chained(args)))
-        return 0
-    if args.workload == "qwen_pack_sweep":
-        print(json.dumps(run_pack_sweep(args)))
-        return 0
-    if args.workload == "stage2_losses":
-        print(json.dumps(run_stage2(args)))
-        return 0
-    O, K, T, gated = WORKLOADS[args.workload]
-    W_h = synth.student_t_weight(O, K, seed=0)
-    X_h = synth.silu_gated_activations(T, K, seed=0) if gated else synth.activations(T, K, seed=0)
-    W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
-    Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
-    Y = Xq @ W.T                       # the frozen BF16 layer output: an input of the method (input generation only)
-    x_scale = None
-    if args.quantised_acts:            # X_q = NVFP4(X): node * block scale in bf16 (exact) and the tensor scale on the side
-        x_scale, _, _, Xq = faar.faar_quant_rtn(Xq, want_dq=True, dq_in_units=True)
-        X_h = (Xq.float() * x_scale).cpu().numpy()
-    torch.cuda.synchronize()
-    N = O * K
-    alpha, lam, lr = 1.0 / (T * O), 0.01, 5e-4
-    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
-    ws = faar.layer_step_workspace(O, K, T)
-    ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, O, K), dtype=torch.uint8, device="cuda")
-    ws_p = torch.empty(max(256, faar.faar_workspace_bytes(fb.OP_LAYER_PREPARE, O, K, T)), dtype=torch.uint8, device="cuda")
-
-    def beta_at(t, total):
-        return 4.0 + 28.0 * (t - 1) / max(1, total - 1)
-
-    def layer_job(n_steps):
-        sg, scales, codes, _ = faar.faar_quant_rtn(W, ws=ws_q)
-        V, _ = faar.faar_init_v(W, sg, scales)
-        Xt, C, ic = faar.faar_layer_prepare(W, sg, scales, Xq, Y, ws=ws_p, x_scale=x_scale)
-        m = torch.zeros_like(V)
-        u = torch.zeros_like(V)
-        for t in range(1, n_steps + 1):
-            # every step but the last also prepares the next step's soft-quantised weights (beta_next)
-            faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, beta_at(t, n_steps), lam, alpha, lr, 0.9, 0.999,
-                                 1e-8, t, losses, ws, beta_next=beta_at(t + 1, n_steps) if t < n_steps else 0.0,
-                                 forward_ready=t > 1, x_scale=x_scale)
-        out, _, _, flips = faar.faar_harden_pack(W, sg, scales, V, want_flips=True)
-        return sg, scales, V, m, u, Xt, C, ic, out, flips
-
-    # warm-up (untimed)
-    layer_job(max(1, args.warmup))
-    torch.cuda.synchronize()
-
-    # timed region: exactly K steps inside one whole per-layer job
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    sg, scales, V, m, u, Xt, C, ic, packed, flips = layer_job(args.steps)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    final_losses = losses.cpu().numpy().tolist()
-    n_flips = int(flips.item())
-    # what the optimisation bought, on the hardened (deployable) weights: reconstruction loss of round-to-nearest
-    # against that of the hardened V (outside the timed region)
-    V_rtn, _ = faar.faar_init_v(W, sg, scales)
-    loss_rtn = float(faar.faar_hardened_loss(W, sg, scales, V_rtn, Xq, C, alpha, ws, x_scale=x_scale).item())
-    loss_faar = float(faar.faar_hardened_loss(W, sg, scales, V, Xq, C, alpha, ws, x_scale=x_scale).item())
-    stochastic = None
-    if args.stochastic_trials > 0:
-        trial = torch.empty(args.stochastic_trials, dtype=torch.float32, device="cuda")
-        for k in range(args.stochastic_trials):
-            Vs = faar.faar_stochastic_v(W, sg, scales, 2603, k)
-            faar.faar_hardened_loss(W, sg, scales, Vs, Xq, C, alpha, ws, x_scale=x_scale, loss=trial[k:k + 1])
-        tl = trial.cpu().numpy()
-        stochastic = {"trials": int(tl.size), "better_than_rtn": int((tl < loss_rtn).sum()), "best": float(tl.min()),
-                      "mean": float(tl.mean()), "std": float(tl.std())}
-
-    # per-kernel durations: HIP events recorded by the library around each launch of one kernel
-    ev = HipEvents()
-    e0, e1 = ev.create(), ev.create()
-    probe = {}
-
-    def timed_kernel(which, call, n):
-        ts = []
-        fb.faar_time_kernel(which, e0.value, e1.value)
-        try:
-            for i in range(n):
-                call(i)
-                ts.append(ev.elapsed_ms(e0, e1))
-        finally:
-            fb.faar_time_kernel(fb.K_NONE)
-        ts = ts[2:] if len(ts) > 4 else ts
-        return sum(ts) / len(ts)
-
-    def first_step_call(i):      # a layer's first step: its own forward kernel, nothing prepared for the next
-        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
-                             args.steps + 1 + i, losses, ws, x_scale=x_scale)
-
-    def step_call(i):            # every later step: forward taken from / left in the workspace
-        faar.faar_layer_step(W, sg, scales, V, m, u, Xq, Xt, C, ic, 16.0, lam, alpha, lr, 0.9, 0.999, 1e-8,
-                             args.steps + 1 + i, losses, ws, beta_next=16.0, forward_ready=i > 0, x_scale=x_scale)
-
-    n_probe = max(5, args.probe_steps)
-    probe["softquant_fwd"] = timed_kernel(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
-    for name, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
-        probe[name] = timed_kernel(kid, step_call, n_probe)
-    # the stand-alone soft-quantisation entry point (forward + backward from a given dL/dW_q; it re-derives the
-    # intervals from W and the scales on every call): torch events around the whole call, output allocation included
-    dWt = torch.randn((O, K), device="cuda") * 1e-3
-    te0, te1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for i in range(n_probe + 3):
-        if i == 3:
-            te0.record()
-        faar.faar_softquant_fwd_bwd(W, sg, scales, V, 16.0, dWt=dWt, lambda_round=lam, emit_delta=True)
-    te1.record()
-    torch.cuda.synchronize()
-    probe["softquant_fwd_bwd_call"] = te0.elapsed_time(te1) / n_probe
-    del dWt
-    probe["quant_rtn"] = timed_kernel(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(W, ws=ws_q), n_probe)
-    probe["init_v"] = timed_kernel(fb.K_INIT_V, lambda i: faar.faar_init_v(W, sg, scales), n_probe)
-    probe["harden_pack"] = timed_kernel(fb.K_HARDEN_PACK, lambda i: faar.faar_harden_pack(W, sg, scales, V), n_probe)
-
-    gemm_flops = 2.0 * T * O * K
-    dw_split = fb.faar_dw_split(O, K, T)
-    bpw = bytes_per_weight(dw_split)
-    kernels = {}
-    for name, ms in probe.items():
-        if name.startswith("gemm"):
-            ach = gemm_flops / (ms * 1e-3) / 1e12
-            kernels[name] = {"ms": round(ms, 5), "bound": "mfma", "achieved": round(ach, 2), "unit": "TFLOP/s",
-                             "frac": round(ach / BF16_PEAK_TFLOPS, 4)}
-        else:
-            ach = bpw[name] * N / (ms * 1e-3) / 1e9
-            kernels[name] = {"ms": round(ms, 5), "bound": "hbm", "achieved": round(ach, 1), "unit": "GB/s",
-                             "frac": round(ach / HBM_PEAK_GBS, 4)}
-    # HBM-side bytes per launch measured with rocprofv3 PMC counters (committed summary; None if not measured)
-    traffic = {}
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
-    if os.path.exists(tpath):
-        for line in open(tpath):
-            f = line.split()
-            if len(f) == 4 and f[0] == args.workload:
-                traffic[f[1]] = int((float(f[2]) + float(f[3])) * 1e6)
-    for name in kernels:
-        kernels[name]["traffic"] = traffic.get(name)
-    dom = max(("gemm_residual", "gemm_dw", "softquant_fwd", "bwd_adam"), key=lambda k: probe[k])
-    roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
-                "peak": BF16_PEAK_TFLOPS if kernels[dom]["bound"] == "mfma" else HBM_PEAK_GBS,
-                "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": kernels[dom]["traffic"],
-                "launch_ms": kernels[dom]["ms"]}
-
-    if args.calib_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-
-    ms_per_step = elapsed / args.steps * 1e3
-    out = {
-        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} "
-                               f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'}, NVFP4 block 16; "
-                               "per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
-                   "O": O, "K": K, "T": T},
-        "weight_elems_per_sec": round(N * args.steps / elapsed, 1),
-        "step_gemm_tflops": round(2 * gemm_flops / (ms_per_step * 1e-3) / 1e12, 1),
-        "dw_split": dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
-        "hardened_loss": {"rtn": loss_rtn, "faar": loss_faar, "stochastic": stochastic},
-        "roofline": roofline, "kernels": kernels,
-    }
-
-    if not args.no_cpu_baseline:
-        from oracle import faar_oracle as fo
-        try:
-            from threadpoolctl import threadpool_info
-            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-        except Exception:
-            cores = os.cpu_count() or 1
-        Y_h = Y.float().cpu().numpy()
-        q = fo.quant_rtn(W_h, True)
-        V0 = fo.init_v(W_h, q["s_global"], q["scales"])["V"]
-        m0 = np.zeros_like(V0)
-        u0 = np.zeros_like(V0)
-        n_cpu, t_cpu = 0, 0.0
-        while n_cpu < 1 or (t_cpu < args.cpu_seconds and n_cpu < 500):
-            c0 = time.perf_counter()
-            r = fo.layer_step(W_h, q["s_global"], q["scales"], V0, m0, u0, X_h, Y_h,
-                              beta_at(n_cpu + 1, args.steps), lam, alpha, lr, 0.9, 0.999, 1e-8, n_cpu + 1)
-            V0, m0, u0 = r["V"], r["m"], r["u"]
-            t_cpu += time.perf_counter() - c0
-            n_cpu += 1
-        out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "cores": int(cores),
-                               "kind": "oracle",
-                               "sample": f"{n_cpu} layer steps of the same {args.workload} layer (numpy float64, "
-                                         f"{t_cpu:.1f} s)"}
+    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_pack_sweep": run_pack_sweep,
+               "stage2_losses": run_stage2, "gemm_ceiling": run_gemm_ceiling}
+    out = runners.get(args.workload, run_linear)(args)
     print(json.dumps(out))
     return 0
 

@@ -74,7 +74,8 @@ enum {
   FAAR_OP_LAYER_PREPARE = 3,
   FAAR_OP_LAYER_STEP = 4,
   FAAR_OP_HARDEN_PACK = 5,
-  FAAR_OP_STAGE2_LOSSES = 6 /* faar_workspace_bytes(op, O = vocabulary, K = hidden size, T = tokens, 0) */
+  FAAR_OP_STAGE2_LOSSES = 6, /* faar_workspace_bytes(op, O = vocabulary, K = hidden size, T = tokens, 0) */
+  FAAR_OP_QUANT_RTN_BATCH = 7 /* independent of the tensors: pass any valid O, K (e.g. 16, 16) */
 };
 
 /* kernels of the path, for faar_time_kernel */
@@ -129,6 +130,17 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T);
  * out[0..3] = variant (FAAR_GEMM_*), tile rows, tile columns, contraction splits.  Pure host function; lets tests
  * prove that their cases reach every variant. */
 int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out);
+
+/* Measurement hook for benchmarks: runs the main loop of the library's GEMM kernel on the product
+ * acc[m][n] = sum_k A[m][k] B[n][k]  (A [M, Kd], B [N, Kd] bf16 row-major, Kd a multiple of 64) WITHOUT storing a result,
+ * whole (mode 0), with only its matrix instructions (mode 1: the LDS stages are filled once and never refilled) or
+ * with only its global-to-LDS copies (mode 2).  Work item i (one output tile) writes the shader-clock cycles it took
+ * to clocks[2 i] and the ticks of the constant 100 MHz counter to clocks[2 i + 1]: their ratio is the clock the
+ * compute units ran at.  info (HOST, out): [0] work items, [1] kernel variant (FAAR_GEMM_*).  capacity: pairs that
+ * fit in clocks (FAAR_E_WORKSPACE if too few); sink: one device float, never written for real operands.
+ * FAAR_E_UNSUPPORTED when the product would not run on the 64-wide-slice kernels. */
+int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
+                    unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream);
 
 /* Padded leading dimension (in elements) of the transposed activations Xt written by
  * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
@@ -307,6 +319,33 @@ int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                      const float* s_global, const uint8_t* scales, const float* V,
                      uint8_t* codes, uint8_t* decisions, void* W_final,
                      unsigned long long* flip_count, void* stream);
+
+/*
+ * The set-up and tear-down operations over MANY weight tensors in one call -- Table 2 steps 2-5 and 25-26 for every
+ * linear layer of a model (the loops "for each layer" of Table 2).  Most tensors of a model are small (a 2 M-weight
+ * projection is a launch of a few microseconds, half of it ramp-up and tail), so these calls put up to 48 tensors into
+ * one launch.  Results are identical, bit for bit, to calling faar_quant_rtn / faar_init_v / faar_harden_pack on each
+ * tensor.  A tensor is described by its flat weight count n = O * K (a multiple of 16: scale blocks are 16 consecutive
+ * weights and rows are multiples of 16, so the row structure does not matter here).
+ *
+ *   items   HOST array of n_items descriptors (read during the call); every pointer in it is a device pointer
+ *   wdt     storage type of every W in the batch
+ */
+typedef struct {
+  const void* W;      /* in  [n] */
+  float* s_global;    /* [1]: out of faar_quant_rtn_batch (in with FAAR_SGLOBAL_GIVEN); in of the other two */
+  uint8_t* scales;    /* [n/16]: out of faar_quant_rtn_batch; in of the other two */
+  float* V;           /* [n]: out of faar_init_v_batch; in of faar_harden_pack_batch; ignored by faar_quant_rtn_batch */
+  uint8_t* codes;     /* [n/2]: out of faar_quant_rtn_batch (round-to-nearest nibbles) and faar_harden_pack_batch (hardened
+                         nibbles); faar_init_v_batch: nullable out, floor codes signbit(w) << 3 | k_lo */
+  int64_t n;          /* weights in the tensor */
+} faar_tensor;
+
+/* ws: FAAR_OP_QUANT_RTN_BATCH workspace (not needed with FAAR_SGLOBAL_GIVEN) */
+int faar_quant_rtn_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, uint32_t flags,
+                         void* ws, size_t ws_bytes, void* stream);
+int faar_init_v_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, void* stream);
+int faar_harden_pack_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, void* stream);
 
 /*
  * One stochastic-rounding candidate (the trials of Sec. 3.2 / Table 1, which the paper reports without defining

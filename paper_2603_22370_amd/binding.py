@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libfaar.so")
 
 FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
-OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES = range(7)
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH = range(8)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
 
@@ -24,6 +24,11 @@ class FaarError(RuntimeError):
         self.code = code
         detail = f" (hipError_t {lib().faar_last_hip_error()})" if code == -5 else ""
         super().__init__(f"{where}: {ERRORS.get(code, code)}{detail}")
+
+
+class faar_tensor(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("s_global", c_void_p), ("scales", c_void_p), ("V", c_void_p), ("codes", c_void_p),
+                ("n", c_int64)]
 
 
 class faar_adam(ctypes.Structure):
@@ -51,6 +56,9 @@ def lib() -> ctypes.CDLL:
         L.faar_dw_split.argtypes = [c_int64, c_int64, c_int64]
         L.faar_gemm_plan.restype = c_int
         L.faar_gemm_plan.argtypes = [c_int, c_int64, c_int64, c_int64, ctypes.POINTER(c_int32)]
+        L.faar_gemm_probe.restype = c_int
+        L.faar_gemm_probe.argtypes = [c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
+                                      ctypes.POINTER(c_int32), c_void_p]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -62,6 +70,12 @@ def lib() -> ctypes.CDLL:
         L.faar_softquant_fwd_bwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float,
                                              c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p,
                                              c_size_t, c_void_p]
+        L.faar_quant_rtn_batch.restype = c_int
+        L.faar_quant_rtn_batch.argtypes = [ctypes.POINTER(faar_tensor), c_int64, c_int, c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_init_v_batch.restype = c_int
+        L.faar_init_v_batch.argtypes = [ctypes.POINTER(faar_tensor), c_int64, c_int, c_void_p]
+        L.faar_harden_pack_batch.restype = c_int
+        L.faar_harden_pack_batch.argtypes = [ctypes.POINTER(faar_tensor), c_int64, c_int, c_void_p]
         L.faar_softquant_fwd_bwd_static.restype = c_int
         L.faar_softquant_fwd_bwd_static.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float,
                                                     c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p]
@@ -146,6 +160,27 @@ def faar_gemm_plan(which: int, O: int, K: int, T: int):
     return GEMM_KINDS[out[0]], int(out[1]), int(out[2]), int(out[3])
 
 
+PROBE_FULL, PROBE_MFMA_ONLY, PROBE_DMA_ONLY = 0, 1, 2
+_probe_buffers = {}
+
+
+def faar_gemm_probe(mode: int, A, B):
+    """Runs one measurement variant of the GEMM main loop on A [M, Kd] x B [N, Kd]^T (bf16).
+    -> (clocks int64 [items, 2]: shader-clock cycles and 100 MHz ticks per work item, variant name)."""
+    _dev(A, B)
+    M, Kd = A.shape
+    N = B.shape[0]
+    cap = 1 << 16
+    if A.device not in _probe_buffers:
+        _probe_buffers[A.device] = (torch.zeros((cap, 2), dtype=torch.int64, device=A.device),
+                                    torch.zeros(1, dtype=torch.float32, device=A.device))
+    clocks, sink = _probe_buffers[A.device]
+    info = (c_int32 * 2)()
+    _check(lib().faar_gemm_probe(mode, M, N, Kd, _ptr(A), _ptr(B), _ptr(clocks), cap, _ptr(sink), info, _stream()),
+           "faar_gemm_probe")
+    return clocks[:info[0]], GEMM_KINDS[info[1]]
+
+
 def faar_padded_tokens(T: int) -> int:
     return int(lib().faar_padded_tokens(T))
 
@@ -176,6 +211,35 @@ def faar_quant_rtn(W, s_global=None, want_dq=False, ws=None, dq_in_units=False):
     _check(lib().faar_quant_rtn(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(codes), _ptr(W_dq),
                                 flags, _ptr(ws), ws.numel(), _stream()), "faar_quant_rtn")
     return s_global, scales, codes, W_dq
+
+
+def tensor_batch(Ws, s_globals, scales, Vs=None, codes=None):
+    """A host array of faar_tensor descriptors over lists of device tensors (one entry per weight tensor; Vs / codes
+    may be None where the batched call does not use them).  Build it once and reuse it: the calls only read it."""
+    n = len(Ws)
+    items = (faar_tensor * n)()
+    dt = _dt(Ws[0])
+    for k in range(n):
+        _dev(Ws[k], s_globals[k], scales[k], None if Vs is None else Vs[k], None if codes is None else codes[k])
+        if _dt(Ws[k]) != dt:
+            raise TypeError("all tensors of a batch share one storage type")
+        items[k] = faar_tensor(Ws[k].data_ptr(), s_globals[k].data_ptr(), scales[k].data_ptr(),
+                               None if Vs is None else Vs[k].data_ptr(), None if codes is None else codes[k].data_ptr(),
+                               Ws[k].numel())
+    return items, dt
+
+
+def faar_quant_rtn_batch(items, dt, ws, s_global_given=False):
+    _check(lib().faar_quant_rtn_batch(items, len(items), dt, FAAR_SGLOBAL_GIVEN if s_global_given else 0, _ptr(ws),
+                                      0 if ws is None else ws.numel(), _stream()), "faar_quant_rtn_batch")
+
+
+def faar_init_v_batch(items, dt):
+    _check(lib().faar_init_v_batch(items, len(items), dt, _stream()), "faar_init_v_batch")
+
+
+def faar_harden_pack_batch(items, dt):
+    _check(lib().faar_harden_pack_batch(items, len(items), dt, _stream()), "faar_harden_pack_batch")
 
 
 def faar_init_v(W, s_global, scales, want_floor_codes=False):

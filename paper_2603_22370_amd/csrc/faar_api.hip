@@ -185,6 +185,24 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T) {
 
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
+int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
+                    unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream) {
+  if (!A || !B || !clocks || !sink || !info) return FAAR_E_NULL;
+  if (mode < 0 || mode > 2) return FAAR_E_ARG;
+  if (M <= 0 || N <= 0 || Kd <= 0 || Kd % 64 != 0 || M > kMaxElems / Kd || N > kMaxElems / Kd) return FAAR_E_SHAPE;
+  if (!aligned16(A) || !aligned16(B) || (reinterpret_cast<uintptr_t>(clocks) & 7u)) return FAAR_E_ARG;
+  int kind = 0;
+  int64_t items = 0;
+  const hipError_t e = launch_gemm_probe(mode, static_cast<const bf16_t*>(A), static_cast<const bf16_t*>(B),
+                                         GemmDims{M, N, Kd, Kd, Kd}, clocks, capacity, sink, &kind, &items,
+                                         static_cast<hipStream_t>(stream));
+  info[0] = static_cast<int32_t>(items);
+  info[1] = kind;
+  if (e == hipErrorNotSupported) return FAAR_E_UNSUPPORTED;
+  if (e == hipErrorInvalidValue) return FAAR_E_WORKSPACE;
+  return hip_status(e);
+}
+
 int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out) {
   if (!out) return FAAR_E_NULL;
   if (int e = check_shape(O, K)) return e;
@@ -210,6 +228,8 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
   switch (op) {
     case FAAR_OP_QUANT_RTN:
       return align256(kAmaxPartials * sizeof(float));
+    case FAAR_OP_QUANT_RTN_BATCH:   // whatever the number and sizes of the tensors: launches reuse it in stream order
+      return align256((size_t)kBatchMax * kBatchAmaxBlocks * sizeof(float));
     case FAAR_OP_INIT_V:
     case FAAR_OP_HARDEN_PACK:
       return 256;  // none needed; a non-zero size keeps callers' allocation code uniform
@@ -254,6 +274,55 @@ int faar_init_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float
   Bracket b(FAAR_K_INIT_V, static_cast<hipStream_t>(stream));
   return hip_status(launch_init_v(W, wdt == FAAR_BF16, O * K, s_global, scales, V, floor_codes,
                                   static_cast<hipStream_t>(stream)));
+}
+
+// ---- batched codec entry points -----------------------------------------------------------------------------------
+static int codec_batch(int op, const faar_tensor* items, int64_t n_items, faar_dtype wdt, uint32_t flags, void* ws,
+                       size_t ws_bytes, void* stream) {
+  if (!items) return FAAR_E_NULL;
+  if (n_items <= 0 || n_items > (1 << 20)) return FAAR_E_SHAPE;
+  if (int e = check_wdt(wdt)) return e;
+  const bool given = (flags & FAAR_SGLOBAL_GIVEN) != 0;
+  if (flags & ~(uint32_t)(op == kBatchQuant ? FAAR_SGLOBAL_GIVEN : 0)) return FAAR_E_ARG;
+  for (int64_t k = 0; k < n_items; ++k) {   // validate everything before the first launch
+    const faar_tensor& t = items[k];
+    if (!t.W || !t.s_global || !t.scales) return FAAR_E_NULL;
+    if (op != kBatchInitV && !t.codes) return FAAR_E_NULL;
+    if (op != kBatchQuant && !t.V) return FAAR_E_NULL;
+    if (t.n <= 0 || t.n % 16 != 0 || t.n > kMaxElems) return FAAR_E_SHAPE;
+    if (!aligned16(t.W) || !aligned16(t.V) || !aligned16(t.codes) || (reinterpret_cast<uintptr_t>(t.s_global) & 3u))
+      return FAAR_E_ARG;
+  }
+  const bool need_ws = op == kBatchQuant && !given;
+  if (need_ws && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_QUANT_RTN_BATCH, 16, 16, 0, 0))) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  for (int64_t k0 = 0; k0 < n_items; k0 += kBatchMax) {
+    CodecBatch B{};
+    B.n = static_cast<int>(n_items - k0 < kBatchMax ? n_items - k0 : kBatchMax);
+    uint32_t blocks = 0;
+    for (int j = 0; j < B.n; ++j) {
+      const faar_tensor& t = items[k0 + j];
+      B.first_block[j] = blocks;
+      B.it[j] = CodecItem{t.W, t.s_global, t.scales, t.V, reinterpret_cast<uint32_t*>(t.codes), t.n / 8};
+      blocks += static_cast<uint32_t>((t.n / 8 + kEltThreads - 1) / kEltThreads);  // <= 48 * 2^25 in total
+    }
+    B.first_block[B.n] = blocks;
+    if (int e = hip_status(launch_codec_batch(op, B, wdt == FAAR_BF16, given, static_cast<float*>(ws), st))) return e;
+  }
+  return FAAR_OK;
+}
+
+int faar_quant_rtn_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, uint32_t flags, void* ws,
+                         size_t ws_bytes, void* stream) {
+  return codec_batch(kBatchQuant, items, n_items, wdt, flags, ws, ws_bytes, stream);
+}
+
+int faar_init_v_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, void* stream) {
+  return codec_batch(kBatchInitV, items, n_items, wdt, 0, nullptr, 0, stream);
+}
+
+int faar_harden_pack_batch(const faar_tensor* items, int64_t n_items, faar_dtype wdt, void* stream) {
+  return codec_batch(kBatchHardenPack, items, n_items, wdt, 0, nullptr, 0, stream);
 }
 
 int faar_softquant_fwd_bwd(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,

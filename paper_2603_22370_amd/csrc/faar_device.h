@@ -19,11 +19,28 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float x) {
   return u >> 16;
 }
 
+// 16 bytes that are read once and not again by this kernel: a load with the nontemporal hint, which lets the
+// caches drop the line early (measured on a plain copy of 1 GiB: 6.5 instead of 6.3 TB/s)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // Eight consecutive weights as float, from bf16 or float storage (16-byte aligned).
 template <typename WT> struct W8;
 template <> struct W8<bf16_t> {
   static __device__ __forceinline__ void load(const bf16_t* p, float (&w)[8]) {
     const uint4 q = *reinterpret_cast<const uint4*>(p);
+    const uint32_t r[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      w[2 * i] = __uint_as_float(r[i] << 16);
+      w[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  }
+  static __device__ __forceinline__ void load_stream(const bf16_t* p, float (&w)[8]) {
+    const uint4 q = load16_stream(p);
     const uint32_t r[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -45,6 +62,11 @@ template <> struct W8<float> {
     const float4 b = *reinterpret_cast<const float4*>(p + 4);
     w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w;
     w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
+  }
+  static __device__ __forceinline__ void load_stream(const float* p, float (&w)[8]) {
+    const uint4 a = load16_stream(p), b = load16_stream(p + 4);
+    w[0] = __uint_as_float(a.x); w[1] = __uint_as_float(a.y); w[2] = __uint_as_float(a.z); w[3] = __uint_as_float(a.w);
+    w[4] = __uint_as_float(b.x); w[5] = __uint_as_float(b.y); w[6] = __uint_as_float(b.z); w[7] = __uint_as_float(b.w);
   }
   static __device__ __forceinline__ void store(float* p, const float (&w)[8]) {
     *reinterpret_cast<float4*>(p) = make_float4(w[0], w[1], w[2], w[3]);
@@ -99,6 +121,16 @@ __device__ __forceinline__ int interval_index(float wt) {
 __device__ __forceinline__ float interval_lo(int k) {
   return k < 2 ? 0.5f * static_cast<float>(k)
                : __uint_as_float(((126u + (static_cast<uint32_t>(k) >> 1)) << 23) | ((static_cast<uint32_t>(k) & 1u) << 22));
+}
+
+// Magnitude code 0..7 of the node nearest to wt (finite, >= 0), exact midpoints going up: the same decision as
+// "k_lo + (wt >= midpoint of interval k_lo)", taken in one step.  From 1 upwards an E2M1 code is the float's exponent
+// and leading significand bit, so adding half an E2M1 ulp to the bit pattern (bit 21) and truncating rounds the
+// magnitude half-up; below 1 the nodes are 0, 0.5 and 1 with midpoints 0.25 and 0.75.  A zero weight gives code 0.
+__device__ __forceinline__ uint32_t nearest_magnitude_code(float wt) {
+  const int hi = static_cast<int>((__float_as_uint(wt) + 0x200000u) >> 22) - 252;
+  const int lo = static_cast<int>(wt >= 0.25f) + static_cast<int>(wt >= 0.75f);
+  return static_cast<uint32_t>(wt < 1.0f ? lo : min(hi, 7));
 }
 
 // Midpoint of interval k: round-to-nearest goes up exactly when w~ >= midpoint (w~ - lo is exact and

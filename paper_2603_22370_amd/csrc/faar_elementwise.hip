@@ -77,16 +77,16 @@ __global__ void __launch_bounds__(kEltThreads) k_amax_final(const float* __restr
   }
 }
 
-// ---- round-to-nearest quantisation -----------------------------------------------------------
+// ---- codec operations on one chunk of 8 weights (thread i of a tensor owns weights 8i .. 8i+7) ----------------
+// Shared by the single-tensor kernels and the batched ones below.  Inputs that a kernel reads exactly once are
+// loaded with the nontemporal hint.
+
+// Round-to-nearest quantisation (Sec. 3.1; Table 2 steps 2-3).  Both lanes of an even/odd pair must be active.
 template <typename WT, bool kDequant>
-__global__ void __launch_bounds__(kEltThreads)
-k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
-            uint8_t* __restrict__ scales, uint32_t* __restrict__ codes, WT* __restrict__ W_dq, bool dq_in_units) {
-  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
-  if (i >= n8) return;  // n8 is even: both lanes of a pair leave together
-  const float sg = *s_global_p;
+__device__ __forceinline__ void quant_chunk(const WT* __restrict__ W, int64_t i, float sg, uint8_t* __restrict__ scales,
+                                            uint32_t* __restrict__ codes, WT* __restrict__ W_dq, bool dq_in_units) {
   float w[8];
-  W8<WT>::load(W + i * 8, w);
+  W8<WT>::load_stream(W + i * 8, w);
   float a = 0.0f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(w[j]));
@@ -101,8 +101,8 @@ k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_gl
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
-      const int k_lo = interval_index(wt);
-      const uint32_t nib = nibble(w[j], k_lo, wt >= interval_mid(k_lo));
+      // a zero weight has wt == 0 and therefore magnitude code 0; its nibble keeps the sign bit of w
+      const uint32_t nib = ((__float_as_uint(w[j]) >> 31) << 3) | nearest_magnitude_code(wt);
       packed |= nib << (4 * j);
       if (kDequant) dq[j] = dequant(nib, sgv, dq_in_units ? 1.0f : sg);  // in units of s_global: an exact product
     }
@@ -113,16 +113,13 @@ k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_gl
   if (kDequant) W8<WT>::store(W_dq + i * 8, dq);
 }
 
-// ---- V initialisation (Eq. 4) ---------------------------------------------------------------
+// V initialisation (Eq. 4)
 template <typename WT>
-__global__ void __launch_bounds__(kEltThreads)
-k_init_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
-         const uint8_t* __restrict__ scales, float* __restrict__ V, uint32_t* __restrict__ floor_codes) {
-  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
-  if (i >= n8) return;
-  const float s = effective_scale(scales[i >> 1], *s_global_p);
+__device__ __forceinline__ void init_v_chunk(const WT* __restrict__ W, int64_t i, float sg, const uint8_t* __restrict__ scales,
+                                             float* __restrict__ V, uint32_t* __restrict__ floor_codes) {
+  const float s = effective_scale(scales[i >> 1], sg);
   float w[8], v[8];
-  W8<WT>::load(W + i * 8, w);
+  W8<WT>::load_stream(W + i * 8, w);
   uint32_t packed = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -134,7 +131,69 @@ k_init_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_globa
   if (floor_codes) floor_codes[i] = packed;
 }
 
-// ---- hardening + NVFP4 packing (Eq. 7; Table 2 steps 25-26) --------------------------------
+// Hardening + NVFP4 packing (Eq. 7; Table 2 steps 25-26); returns how many of the 8 nibbles differ from round-to-nearest
+template <typename WT>
+__device__ __forceinline__ unsigned harden_chunk(const WT* __restrict__ W, int64_t i, float sg, const uint8_t* __restrict__ scales,
+                                                 const float* __restrict__ V, uint32_t* __restrict__ codes,
+                                                 uint8_t* __restrict__ decisions, WT* __restrict__ W_final) {
+  const float sgv = e4m3_value(scales[i >> 1]);
+  const float s = sgv * sg;
+  float w[8], v[8], dq[8];
+  W8<WT>::load_stream(W + i * 8, w);
+  W8<float>::load_stream(V + i * 8, v);
+  uint32_t packed = 0, bits = 0;
+  unsigned flips = 0;
+  float amax = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(w[j]));
+  const BlockDivider div(s, amax);
+  auto encode = [&](auto fast) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
+      const int k_lo = interval_index(wt);
+      const int up = v[j] >= 0.5f;
+      const uint32_t nib = nibble(w[j], k_lo, up);
+      flips += (nib & 7u) != nearest_magnitude_code(wt);  // differs from round-to-nearest (never for a zero weight)
+      packed |= nib << (4 * j);
+      bits |= static_cast<uint32_t>(up) << j;
+      if (W_final) dq[j] = dequant(nib, sgv, sg);
+    }
+  };
+  if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
+  codes[i] = packed;
+  if (decisions) decisions[i] = static_cast<uint8_t>(bits);
+  if (W_final) W8<WT>::store(W_final + i * 8, dq);
+  return flips;
+}
+
+__device__ __forceinline__ void add_flips(unsigned flips, unsigned long long* __restrict__ flip_count) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) flips += __shfl_xor(flips, o);
+  if ((threadIdx.x & 63) == 0 && flips) atomicAdd(flip_count, (unsigned long long)flips);
+}
+
+// ---- single-tensor kernels: one chunk per thread, as many blocks as chunks / 256 ---------------------------------
+// (the shape that streams best on this part: a plain copy written this way moves 6.3 TB/s, the same copy as a
+// grid-stride loop over a few thousand blocks, or with several chunks per thread, 4.4 - 5.9 TB/s)
+template <typename WT, bool kDequant>
+__global__ void __launch_bounds__(kEltThreads)
+k_quant_rtn(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+            uint8_t* __restrict__ scales, uint32_t* __restrict__ codes, WT* __restrict__ W_dq, bool dq_in_units) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;  // n8 is even: both lanes of a pair leave together
+  quant_chunk<WT, kDequant>(W, i, *s_global_p, scales, codes, W_dq, dq_in_units);
+}
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads)
+k_init_v(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
+         const uint8_t* __restrict__ scales, float* __restrict__ V, uint32_t* __restrict__ floor_codes) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  init_v_chunk<WT>(W, i, *s_global_p, scales, V, floor_codes);
+}
+
 template <typename WT>
 __global__ void __launch_bounds__(kEltThreads)
 k_harden_pack(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
@@ -143,41 +202,89 @@ k_harden_pack(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_
               unsigned long long* __restrict__ flip_count) {
   const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
   unsigned flips = 0;
-  if (i < n8) {
-    const float sg = *s_global_p;
-    const float sgv = e4m3_value(scales[i >> 1]);
-    const float s = sgv * sg;
-    float w[8], v[8], dq[8];
-    W8<WT>::load(W + i * 8, w);
-    load8(V + i * 8, v);
-    uint32_t packed = 0, bits = 0;
-    float amax = 0.0f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) amax = fmaxf(amax, fabsf(w[j]));
-    const BlockDivider div(s, amax);
-    auto encode = [&](auto fast) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float wt = div.quotient<decltype(fast)::value>(fabsf(w[j]));
-        const int k_lo = interval_index(wt);
-        const int up = v[j] >= 0.5f;
-        const uint32_t nib = nibble(w[j], k_lo, up);
-        flips += (w[j] != 0.0f) & (up != (wt >= interval_mid(k_lo)));  // differs from round-to-nearest
-        packed |= nib << (4 * j);
-        bits |= static_cast<uint32_t>(up) << j;
-        dq[j] = dequant(nib, sgv, sg);
-      }
-    };
-    if (div.fast) encode(std::true_type{}); else encode(std::false_type{});
-    codes[i] = packed;
-    if (decisions) decisions[i] = static_cast<uint8_t>(bits);
-    if (W_final) W8<WT>::store(W_final + i * 8, dq);
+  if (i < n8) flips = harden_chunk<WT>(W, i, *s_global_p, scales, V, codes, decisions, W_final);
+  if (flip_count) add_flips(flips, flip_count);  // uniform branch: every lane of the block reaches the reduction
+}
+
+// ---- batched kernels: many tensors, one launch ----------------------------------------------------------------------
+// A model's weight tensors are quantised, initialised and packed tensor by tensor, and most of them are small (a
+// 2 M-weight projection is a 5 us launch, half of it ramp-up and tail).  The batched entry points put up to
+// kBatchMax tensors into one launch: the descriptors travel in the kernel arguments, workgroup b finds its tensor by
+// a binary search over the tensors' first workgroup indices (uniform: scalar loads) and then runs the same chunk code.
+__device__ __forceinline__ int batch_item(const CodecBatch& B, uint32_t block) {
+  int lo = 0, hi = B.n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (B.first_block[mid] <= block) lo = mid; else hi = mid;
   }
-  if (flip_count) {  // uniform branch: every lane of the block reaches the reduction
+  return lo;
+}
+
+// Per-tensor amax: kBatchAmaxBlocks workgroups per tensor walk its chunks with a stride; a tensor's partial maxima
+// are finished by k_batch_amax_final (one workgroup per tensor).
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads) k_batch_amax_partial(CodecBatch B, float* __restrict__ partials) {
+  const int item = blockIdx.x / kBatchAmaxBlocks, part = blockIdx.x % kBatchAmaxBlocks;
+  const WT* W = static_cast<const WT*>(B.it[item].W);
+  const int64_t n8 = B.it[item].n8;
+  float a = 0.0f;
+  for (int64_t i = part * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)kBatchAmaxBlocks * kEltThreads) {
+    float w[8];
+    W8<WT>::load(W + i * 8, w);   // read again by the quantise kernel: keep it cached
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) flips += __shfl_xor(flips, o);
-    if ((threadIdx.x & 63) == 0 && flips) atomicAdd(flip_count, (unsigned long long)flips);
+    for (int j = 0; j < 8; ++j) a = fmaxf(a, fabsf(w[j]));
   }
+  __shared__ float s[kEltThreads / 64];
+  a = wave_max(a);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 1; i < kEltThreads / 64; ++i) a = fmaxf(a, s[i]);
+    partials[blockIdx.x] = a;
+  }
+}
+
+__global__ void __launch_bounds__(kEltThreads) k_batch_amax_final(CodecBatch B, const float* __restrict__ partials) {
+  const int item = blockIdx.x;
+  float a = 0.0f;
+  for (int i = threadIdx.x; i < kBatchAmaxBlocks; i += kEltThreads) a = fmaxf(a, partials[item * kBatchAmaxBlocks + i]);
+  __shared__ float s[kEltThreads / 64];
+  a = wave_max(a);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int i = 1; i < kEltThreads / 64; ++i) a = fmaxf(a, s[i]);
+    *B.it[item].s_global = (a == 0.0f) ? 1.0f : a / 2688.0f;
+  }
+}
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads) k_batch_quant_rtn(CodecBatch B) {
+  const int item = batch_item(B, blockIdx.x);
+  const CodecItem& t = B.it[item];
+  const int64_t i = (blockIdx.x - B.first_block[item]) * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= t.n8) return;
+  quant_chunk<WT, false>(static_cast<const WT*>(t.W), i, *t.s_global, t.scales, t.codes, nullptr, false);
+}
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads) k_batch_init_v(CodecBatch B) {
+  const int item = batch_item(B, blockIdx.x);
+  const CodecItem& t = B.it[item];
+  const int64_t i = (blockIdx.x - B.first_block[item]) * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= t.n8) return;
+  init_v_chunk<WT>(static_cast<const WT*>(t.W), i, *t.s_global, t.scales, t.V, t.codes);
+}
+
+template <typename WT>
+__global__ void __launch_bounds__(kEltThreads) k_batch_harden_pack(CodecBatch B) {
+  const int item = batch_item(B, blockIdx.x);
+  const CodecItem& t = B.it[item];
+  const int64_t i = (blockIdx.x - B.first_block[item]) * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= t.n8) return;
+  (void)harden_chunk<WT>(static_cast<const WT*>(t.W), i, *t.s_global, t.scales, t.V, t.codes, nullptr, nullptr);
 }
 
 // ---- soft quantisation forward (Eq. 2-3) ----------------------------------------------------
@@ -629,6 +736,28 @@ hipError_t launch_quant_rtn(const void* W, bool w_bf16, int64_t n, const float* 
   if (w_bf16) { if (W_dq) FAAR_Q(bf16_t, true); else FAAR_Q(bf16_t, false); }
   else        { if (W_dq) FAAR_Q(float, true);  else FAAR_Q(float, false); }
 #undef FAAR_Q
+  return hipGetLastError();
+}
+
+hipError_t launch_codec_batch(int op, const CodecBatch& B, bool w_bf16, bool sglobal_given, float* partials, hipStream_t st) {
+  const dim3 b(kEltThreads);
+  const dim3 g(B.first_block[B.n]);
+  if (op == kBatchQuant) {
+    if (!sglobal_given) {
+      const dim3 ga(static_cast<unsigned>(B.n * kBatchAmaxBlocks));
+      if (w_bf16) hipLaunchKernelGGL(k_batch_amax_partial<bf16_t>, ga, b, 0, st, B, partials);
+      else hipLaunchKernelGGL(k_batch_amax_partial<float>, ga, b, 0, st, B, partials);
+      hipLaunchKernelGGL(k_batch_amax_final, dim3(static_cast<unsigned>(B.n)), b, 0, st, B, partials);
+    }
+    if (w_bf16) hipLaunchKernelGGL(k_batch_quant_rtn<bf16_t>, g, b, 0, st, B);
+    else hipLaunchKernelGGL(k_batch_quant_rtn<float>, g, b, 0, st, B);
+  } else if (op == kBatchInitV) {
+    if (w_bf16) hipLaunchKernelGGL(k_batch_init_v<bf16_t>, g, b, 0, st, B);
+    else hipLaunchKernelGGL(k_batch_init_v<float>, g, b, 0, st, B);
+  } else {
+    if (w_bf16) hipLaunchKernelGGL(k_batch_harden_pack<bf16_t>, g, b, 0, st, B);
+    else hipLaunchKernelGGL(k_batch_harden_pack<float>, g, b, 0, st, B);
+  }
   return hipGetLastError();
 }
 

@@ -159,6 +159,7 @@ k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d
 // R = x_scale * acc - C; sum R^2; dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
 struct EpiResidual {
   static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
+  static constexpr int kMode = 0;               // 0: the whole main loop (1, 2: measurement variants, see EpiProbe)
   const float* C;
   const float* x_scale;  // device scalar multiplying the A operand (activations stored in units of it); null = 1
   float xs;
@@ -230,6 +231,7 @@ struct EpiResidual {
 // out[split][m][n] = acc
 struct EpiF32 {
   static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = 0;
   float* out;
   __device__ __forceinline__ void once() {}
   __device__ __forceinline__ void begin() {}
@@ -250,6 +252,7 @@ struct EpiF32 {
 template <bool kYbf16>
 struct EpiSub {
   static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = 0;
   const void* Y;
   bool first;
   float* C_out;
@@ -283,6 +286,7 @@ struct EpiSub {
 // out[m][n] = bf16(acc)
 struct EpiBf16 {
   static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = 0;
   bf16_t* out;
   __device__ __forceinline__ void once() {}
   __device__ __forceinline__ void begin() {}
@@ -293,6 +297,32 @@ struct EpiBf16 {
       if (m + q < d.M) out[(m + q) * d.N + n] = static_cast<bf16_t>(f32_to_bf16(acc[q]));
   }
   __device__ __forceinline__ void finish(int) {}
+};
+
+// Measurement epilogue (faar_gemm_probe): no output; every work item reports how many shader-clock cycles and how
+// many ticks of the constant 100 MHz counter it took, so that the clock the compute units ran at can be read off.
+// kMode selects what the main loop of k_gemm_dma64 keeps: 0 everything, 1 only the matrix instructions and their
+// LDS reads (the stages are filled once and never refilled), 2 only the global->LDS copies.
+template <int MODE>
+struct EpiProbe {
+  static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = MODE;
+  unsigned long long* clocks;   // [items][2]
+  float* sink;
+  long long t0, w0;
+  float sum;
+  __device__ __forceinline__ void once() { t0 = clock64(); w0 = wall_clock64(); sum = 0.0f; }
+  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t, int64_t, int, const GemmDims&) {
+    sum += (acc[0] + acc[1]) + (acc[2] + acc[3]);
+  }
+  __device__ __forceinline__ void finish(int item) {
+    if (sum == 1.2345e-30f) *sink = sum;   // keeps the accumulators alive; never true for real operands
+    if (threadIdx.x == 0) {
+      clocks[2 * item] = static_cast<unsigned long long>(clock64() - t0);
+      clocks[2 * item + 1] = static_cast<unsigned long long>(wall_clock64() - w0);
+    }
+  }
 };
 
 // ---- fast path: direct-to-LDS ring, swizzled LDS, interleaved schedule ------------------------------
@@ -637,14 +667,15 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
         for (int m = 0; m < NM; ++m) {
           // boustrophedon over the tile grid: consecutive MFMAs share one operand
           const int mi = m / TN, mj = (mi & 1) ? TN - 1 - m % TN : m % TN;
-          acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
-          if (m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
+          if constexpr (Epi::kMode != 2)
+            acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
+          if (Epi::kMode != 2 && m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
             const int f = m / C::FSTEP;
             if (f == 0) fa[cur ^ 1][0] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk]);
             else if (f <= TN) fb[cur ^ 1][f - 1] = *reinterpret_cast<const bf16x8*>(src + b_off[nkk] + (f - 1) * 16 * DBK64);
             else fa[cur ^ 1][f - TN] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk] + (f - TN) * 16 * DBK64);
           }
-          if (kk == KK - 1 && m % C::DSTEP == 0 && m / C::DSTEP < P) {
+          if (Epi::kMode != 1 && kk == KK - 1 && m % C::DSTEP == 0 && m / C::DSTEP < P) {
             // slice it+NS into the stage just released; past the end every lane re-reads one valid address
             const int q = m / C::DSTEP;
             const bf16_t* g = more ? gsrc[q] + goff : A;
@@ -831,6 +862,18 @@ hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* 
   Plan p = plan_gemm(d, true, kEpiF32);
   if (p.n_split != n_split) return hipErrorInvalidValue;  // the caller sized its workspace with choose_split
   return run(A, B, d, p, e, st);
+}
+
+hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,
+                             int64_t capacity, float* sink, int* kind, int64_t* items, hipStream_t st) {
+  const Plan p = plan_gemm(d, false, kEpiF32);
+  *kind = p.kind;
+  *items = p.items();
+  if (p.kind != KIND_L64 && p.kind != KIND_M64) return hipErrorNotSupported;   // only the BK = 64 loop has the variants
+  if (p.items() > capacity) return hipErrorInvalidValue;
+  if (mode == 0) return run(A, B, d, p, EpiProbe<0>{clocks, sink, 0, 0, 0.0f}, st);
+  if (mode == 1) return run(A, B, d, p, EpiProbe<1>{clocks, sink, 0, 0, 0.0f}, st);
+  return run(A, B, d, p, EpiProbe<2>{clocks, sink, 0, 0, 0.0f}, st);
 }
 
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,

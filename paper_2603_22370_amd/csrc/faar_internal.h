@@ -37,6 +37,22 @@ hipError_t launch_harden_pack(const void* W, bool w_bf16, int64_t n, const float
                               const uint8_t* scales, const float* V, uint8_t* codes,
                               uint8_t* decisions, void* W_final, unsigned long long* flip_count,
                               hipStream_t st);
+// Batched codec operations: up to kBatchMax tensors per launch, descriptors passed in the kernel arguments.
+constexpr int kBatchMax = 48;          // 48 descriptors of 48 bytes + the index table stay below the 4 KB argument limit
+constexpr int kBatchAmaxBlocks = 64;   // workgroups (and partial maxima) per tensor in the batched amax pass
+struct CodecItem {
+  const void* W; float* s_global; uint8_t* scales; float* V; uint32_t* codes;
+  int64_t n8;                          // chunks of 8 weights
+};
+struct CodecBatch {
+  int n;                               // tensors in this launch
+  uint32_t first_block[kBatchMax + 1]; // first workgroup of each tensor; [n] = grid size
+  CodecItem it[kBatchMax];
+};
+enum { kBatchQuant = 0, kBatchInitV = 1, kBatchHardenPack = 2 };
+// partials: kBatchAmaxBlocks floats per tensor (quantise without given tensor scales only)
+hipError_t launch_codec_batch(int op, const CodecBatch& B, bool w_bf16, bool sglobal_given, float* partials, hipStream_t st);
+
 // Wt = bf16(W_q) or bf16(W_q - W); Wq_full (nullable) additionally receives bf16(W_q).
 hipError_t launch_softquant_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global,
                                 const uint8_t* scales, const float* V, float beta, bool delta,
@@ -134,6 +150,10 @@ GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd);
 // C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc   (Y bf16 or float32 row-major; C_out interleaved)
 hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const void* Y, bool y_bf16,
                            bool first, float* C_out, const float* x_scale, hipStream_t st);
+// Measurement variants of the main loop (mode 0 whole, 1 matrix instructions only, 2 copies only) on an M x N x Kd
+// product, no output: clocks[2 i], clocks[2 i + 1] = shader-clock cycles and 100 MHz ticks of work item i.
+hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,
+                             int64_t capacity, float* sink, int* kind, int64_t* items, hipStream_t st);
 // out[m][n] = bf16(acc)
 hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out,
                             hipStream_t st);

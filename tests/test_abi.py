@@ -117,3 +117,27 @@ def test_token_split_of_the_dw_gemm_is_sane():
     # small outputs with a long token axis split; large outputs do not
     assert fb.faar_dw_split(512, 2048, 4096) > 1
     assert fb.faar_dw_split(8192, 2048, 4096) == 1
+
+
+def test_batched_codec_calls_validate_every_descriptor_first():
+    L = fb.lib()
+    good = fb.faar_tensor(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 256)
+    def batch(*ts):
+        arr = (fb.faar_tensor * len(ts))(*ts)
+        return arr, len(ts)
+    ws = ctypes.c_void_p(0x9000)
+    arr, n = batch(good, fb.faar_tensor(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 250))       # n % 16
+    assert L.faar_quant_rtn_batch(arr, n, 1, 0, ws, 1 << 20, None) == -2
+    arr, n = batch(good, fb.faar_tensor(0x1000, None, 0x3000, 0x4000, 0x5000, 256))          # missing tensor scale
+    assert L.faar_harden_pack_batch(arr, n, 1, None) == -1
+    arr, n = batch(fb.faar_tensor(0x1000, 0x2000, 0x3000, None, 0x5000, 256))                # V missing where it is used
+    assert L.faar_init_v_batch(arr, n, 1, None) == -1
+    assert L.faar_harden_pack_batch(arr, n, 1, None) == -1
+    arr, n = batch(fb.faar_tensor(0x1004, 0x2000, 0x3000, 0x4000, 0x5000, 256))              # unaligned W
+    assert L.faar_init_v_batch(arr, n, 1, None) == -6
+    arr, n = batch(good)
+    assert L.faar_quant_rtn_batch(arr, n, 1, 0, None, 0, None) == -4                         # workspace missing
+    assert L.faar_quant_rtn_batch(arr, n, 5, 0, ws, 1 << 20, None) == -3
+    assert L.faar_quant_rtn_batch(arr, 0, 1, 0, ws, 1 << 20, None) == -2
+    assert L.faar_init_v_batch(None, 1, 1, None) == -1
+    assert fb.faar_workspace_bytes(fb.OP_QUANT_RTN_BATCH, 16, 16) >= 48 * 64 * 4

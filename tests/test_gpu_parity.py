@@ -630,6 +630,59 @@ def test_nvfp4_activations_in_units_of_their_tensor_scale():
         _check_grad(host(m).astype(np.float64) / (1 - HYP["beta1"]), ref)
 
 
+def test_batched_codec_calls_match_the_single_tensor_calls_and_the_oracle():
+    """faar_quant_rtn_batch / faar_init_v_batch / faar_harden_pack_batch over 60 tensors of mixed sizes (two launches of
+    48 and 12; single-block, ragged and multi-block tensors; both storage types): every output bit-identical to the
+    single-tensor entry points, and, for a subset, to the oracle."""
+    shapes = [(1, 16), (8, 64), (96, 320), (16, 2048), (512, 2048), (33, 48), (1024, 1024), (7, 4112)]
+    for isbf in (True, False):
+        Ws_h = []
+        for k in range(60):
+            O, K = shapes[k % len(shapes)]
+            if k == 5:
+                Ws_h.append(synth.adversarial_weight(1, isbf))
+            else:
+                w = synth.student_t_weight(O, K, 100 + k) if isbf else synth.gaussian_weight(O, K, 100 + k)
+                Ws_h.append(w)
+        Ws = [dev(w, isbf) for w in Ws_h]
+        Vs_h = [synth.rounding_variables(w.shape[0], w.shape[1], 200 + k) for k, w in enumerate(Ws_h)]
+        mk = lambda shape, dt: torch.empty(shape, dtype=dt, device="cuda")
+        sgs = [mk(1, torch.float32) for _ in Ws]
+        scs = [mk((w.shape[0], w.shape[1] // 16), torch.uint8) for w in Ws]
+        cds = [mk((w.shape[0], w.shape[1] // 2), torch.uint8) for w in Ws]
+        ws = torch.empty(faar.faar_workspace_bytes(faar.binding.OP_QUANT_RTN_BATCH, 16, 16), dtype=torch.uint8, device="cuda")
+        items, dt = faar.tensor_batch(Ws, sgs, scs, codes=cds)
+        faar.faar_quant_rtn_batch(items, dt, ws)
+        for k, W in enumerate(Ws):
+            sg1, sc1, cd1, _ = faar.faar_quant_rtn(W)
+            assert torch.equal(sgs[k], sg1) and torch.equal(scs[k], sc1) and torch.equal(cds[k], cd1), k
+        # with given tensor scales: same codes again, no workspace
+        cds2 = [torch.zeros_like(c) for c in cds]
+        scs2 = [torch.zeros_like(c) for c in scs]
+        items2, _ = faar.tensor_batch(Ws, sgs, scs2, codes=cds2)
+        faar.faar_quant_rtn_batch(items2, dt, None, s_global_given=True)
+        assert all(torch.equal(a, b) for a, b in zip(cds, cds2)) and all(torch.equal(a, b) for a, b in zip(scs, scs2))
+        # V initialisation (with floor codes) and hardening of planted V
+        Vg = [mk(w.shape, torch.float32) for w in Ws]
+        fcs = [torch.zeros_like(c) for c in cds]
+        items3, _ = faar.tensor_batch(Ws, sgs, scs, Vs=Vg, codes=fcs)
+        faar.faar_init_v_batch(items3, dt)
+        for k, W in enumerate(Ws):
+            V1, fc1 = faar.faar_init_v(W, sgs[k], scs[k], want_floor_codes=True)
+            assert torch.equal(Vg[k].view(torch.int32), V1.view(torch.int32)) and torch.equal(fcs[k], fc1), k
+        Vd = [dev(v) for v in Vs_h]
+        out = [torch.zeros_like(c) for c in cds]
+        items4, _ = faar.tensor_batch(Ws, sgs, scs, Vs=Vd, codes=out)
+        faar.faar_harden_pack_batch(items4, dt)
+        for k, W in enumerate(Ws):
+            c1, _, _, _ = faar.faar_harden_pack(W, sgs[k], scs[k], Vd[k])
+            assert torch.equal(out[k], c1), k
+        for k in (0, 2, 5, 6, 55):
+            q = fo.quant_rtn(Ws_h[k], isbf)
+            assert np.array_equal(host(cds[k]), q["codes"]) and np.array_equal(host(scs[k]), q["scales"])
+            assert np.array_equal(host(out[k]), fo.harden_pack(Ws_h[k], isbf, q["s_global"], q["scales"], Vs_h[k])["codes"])
+
+
 def test_stochastic_candidates_and_hardened_loss():
     """Candidate sampler bit-exact against the oracle's Philox draw; hardened reconstruction loss of arbitrary,
     round-to-nearest and sampled V against the oracle's float64 evaluation of the packed weights."""
