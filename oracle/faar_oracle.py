@@ -296,6 +296,12 @@ def stage1_loss_and_grads(W, s_global, scale_bytes, V, Xq, Y_fp, beta, lambda_ro
     declared_rounding=True applies the three storage roundings a bf16 tensor-core implementation
     declares -- the weight perturbation (W_q - W), dY and dX are each rounded to bf16 where they
     are stored -- and nothing else; with it off, every quantity is exact float64.
+
+    declared_rounding="split" is the same contract for an implementation that splits the constant
+    part off the gradient: with d = W_q - W and C = Y_fp - X_q W^T (both as above),
+        R = X_q d^T - C,   dY = 2 alpha R   =>   G = dY^T X_q = (2 alpha X_q d^T)^T X_q - 2 alpha C^T X_q,
+    and only the first, V-dependent factor 2 alpha X_q d^T is stored (rounded to bf16); the constant
+    C^T X_q is exact.  Same mathematics (Eq. 5 and its chain rule), another rounding point for dY.
     """
     W = _check_w(W)
     V64 = np.asarray(V, dtype=F32).astype(np.float64)
@@ -313,13 +319,19 @@ def stage1_loss_and_grads(W, s_global, scale_bytes, V, Xq, Y_fp, beta, lambda_ro
     N = W.size
     L_mse = float(alpha) * float(np.sum(R * R))
     L_round = round_loss(V64)
-    if dY_ext is None:
-        dY = 2.0 * float(alpha) * R
-        if declared_rounding:
-            dY = bf16_round(dY.astype(F32)).astype(np.float64)
+    if dY_ext is None and declared_rounding == "split":
+        C = Y_fp - Xq @ W64.T
+        dYa = bf16_round((2.0 * float(alpha) * (Xq @ delta.T)).astype(F32)).astype(np.float64)
+        dY = dYa - 2.0 * float(alpha) * C
+        G = dYa.T @ Xq - 2.0 * float(alpha) * (C.T @ Xq)
     else:
-        dY = np.asarray(dY_ext, dtype=np.float64)
-    G = dY.T @ Xq
+        if dY_ext is None:
+            dY = 2.0 * float(alpha) * R
+            if declared_rounding:
+                dY = bf16_round(dY.astype(F32)).astype(np.float64)
+        else:
+            dY = np.asarray(dY_ext, dtype=np.float64)
+        G = dY.T @ Xq
     dV = G * sign * s * (hi - lo) * float(beta) * h * (1.0 - h) + float(lambda_round) / N * (4.0 - 8.0 * V64)
     out = {"Wq": Wq, "R": R, "dY": dY, "G": G, "dV": dV, "L_mse": L_mse, "L_round": L_round,
            "L": L_mse + float(lambda_round) * L_round}

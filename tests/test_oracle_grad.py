@@ -196,6 +196,33 @@ def test_declared_rounding_mode_is_a_small_perturbation():
     assert b["L_round"] == a["L_round"]
 
 
+def test_split_contract_mode_is_the_same_gradient_with_one_rounding_moved():
+    """G = dY^T X_q with dY = 2 alpha (X_q d^T - C) splits into (2 alpha X_q d^T)^T X_q - 2 alpha C^T X_q.  The "split"
+    contract rounds only the first factor to bf16: it must agree with the exact gradient to the size of that one
+    rounding, agree with it EXACTLY when the factor happens to be bf16-representable (here: everything scaled so that
+    the products are small integers), and leave the losses of the other contract untouched."""
+    W, sg, sb, V, X, Xq, Y = _tiny(O=16, K=64, T=64)
+    al = 1.0 / (64 * 16)
+    a = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al)
+    b = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, declared_rounding=True)
+    c = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, declared_rounding="split")
+    assert c["L_mse"] == b["L_mse"] and c["L_round"] == a["L_round"]
+    n = np.linalg.norm
+    assert 0 < n(c["dV"] - a["dV"]) <= 1e-2 * n(a["dV"])
+    assert n(c["dV"] - b["dV"]) > 0                     # another rounding point: not the same numbers
+    # the split itself is an identity: undo the roundings by hand and compare with the exact G
+    W64, X64 = W.astype(np.float64), Xq.astype(np.float64)
+    C = Y.astype(np.float64) - X64 @ W64.T
+    d = a["Wq"] - W64
+    G = (2 * al * (X64 @ d.T)).T @ X64 - 2 * al * (C.T @ X64)
+    assert np.allclose(G, a["G"], rtol=1e-10, atol=1e-18)
+    # an upstream gradient bypasses dY altogether: both contracts coincide
+    dY = (np.arange(64 * 16).reshape(64, 16) % 7 - 3).astype(np.float32) * 2.0 ** -10
+    e = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, dY_ext=dY, declared_rounding=True)
+    f = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, dY_ext=dY, declared_rounding="split")
+    assert np.array_equal(e["dV"], f["dV"])
+
+
 def test_brute_force_over_all_roundings_of_a_tiny_layer():
     """Eq. 1: enumerate every V in {0,1}^16 for one 16-weight row.  The oracle's hardened loss must
     agree with an independent evaluator (decode packed bytes -> dense matmul) at every assignment;
