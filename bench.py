@@ -61,13 +61,14 @@ QWEN_LAYERS = 28
 LAM, LR = 0.01, 5e-4
 
 
-def bytes_per_weight(dw_split: int) -> dict:
+def bytes_per_weight(dw_split: int, use_h: bool = False) -> dict:
     """Algorithmic bytes per weight element of each HBM-bound kernel (bf16 W, fp32 V/m/u, 1/16 B scale,
     1/2 B cached interval code), for the design as built: the dV kernel reads one fp32 partial per dW split
     and, in every step but a layer's last, also writes the next step's W_q - W."""
     return {
         "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,             # read W, V, code, scale; write W_q - W (bf16)
-        "bwd_adam": 4 * dw_split + 0.5 + 1 / 16 + 12 + 12 + 2 + 2,  # read G partials, code, scale, V, m, u, W; write V, m, u, W_q - W
+        # read G partials (and H), code, scale, V, m, u, W; write V, m, u, W_q - W
+        "bwd_adam": 4 * dw_split + (4 if use_h else 0) + 0.5 + 1 / 16 + 12 + 12 + 2 + 2,
         "quant_rtn": 2 + 0.5 + 1 / 16,                         # read W; write codes, scales
         "init_v": 2 + 1 / 16 + 4,                              # read W, scales; write V
         "harden_pack": 2 + 4 + 1 / 16 + 0.5,                   # read W, V, scales; write codes
@@ -178,8 +179,11 @@ class LinearJob:
         self.losses = torch.zeros(3, dtype=torch.float32, device="cuda")
         self.ws = faar.layer_step_workspace(O, K, T)
         self.ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, O, K), dtype=torch.uint8, device="cuda")
-        self.ws_p = torch.empty(max(256, faar.faar_workspace_bytes(fb.OP_LAYER_PREPARE, O, K, T)), dtype=torch.uint8, device="cuda")
+        self.ws_p = None
         self.dw_split = fb.faar_dw_split(O, K, T)
+        # the gradient constant H = C^T X_q trades 4 bytes per output of Y in the residual GEMM's epilogue for 4 bytes
+        # per weight in the pass that updates V: used where that is a saving
+        self.use_h = T >= K
         self.state = None
 
     @staticmethod
@@ -192,8 +196,15 @@ class LinearJob:
         import paper_2603_22370_amd as faar
         sg, scales, codes, _ = faar.faar_quant_rtn(self.W, ws=self.ws_q)
         V, _ = faar.faar_init_v(self.W, sg, scales)
-        Xt, C, ic = faar.faar_layer_prepare(self.W, sg, scales, self.Xq, self.Y, ws=self.ws_p, x_scale=self.x_scale)
-        self.state = dict(sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=Xt, C=C, ic=ic)
+        if self.ws_p is None:
+            from paper_2603_22370_amd import binding as fb
+            flags = fb.FAAR_WS_GRADIENT_CONSTANT if self.use_h else 0
+            self.ws_p = torch.empty(max(256, faar.faar_workspace_bytes(fb.OP_LAYER_PREPARE, self.O, self.K, self.T, flags)),
+                                    dtype=torch.uint8, device="cuda")
+        out = faar.faar_layer_prepare(self.W, sg, scales, self.Xq, self.Y, ws=self.ws_p, x_scale=self.x_scale,
+                                      gradient_constant=self.use_h)
+        self.state = dict(sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=out[0], C=out[1], ic=out[2],
+                          hk=dict(H=out[3], c_norm2=out[4]) if self.use_h else {})
 
     def step(self, t, total, beta=None, beta_next=None, forward_ready=None):
         import paper_2603_22370_amd as faar
@@ -203,7 +214,7 @@ class LinearJob:
             beta_next = self.beta_at(t + 1, total) if t < total else 0.0
         faar.faar_layer_step(self.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], self.Xq, s["Xt"], s["C"], s["ic"], beta,
                              LAM, self.alpha, LR, 0.9, 0.999, 1e-8, t, self.losses, self.ws, beta_next=beta_next,
-                             forward_ready=(t > 1) if forward_ready is None else forward_ready, x_scale=self.x_scale)
+                             forward_ready=(t > 1) if forward_ready is None else forward_ready, x_scale=self.x_scale, **s["hk"])
 
     def finish(self):
         import paper_2603_22370_amd as faar
@@ -245,7 +256,7 @@ class LinearJob:
 
     def kernel_table(self, probe):
         gemm_flops = 2.0 * self.T * self.O * self.K
-        bpw = bytes_per_weight(self.dw_split)
+        bpw = bytes_per_weight(self.dw_split, self.use_h)
         N = self.O * self.K
         # working set of one step: W, V, m, u, W_q - W, G partials, X_q, X_q^T, C, dY^T
         step_bytes = N * (2 + 12 + 2 + 4 * self.dw_split) + self.T * self.K * 4 + self.T * self.O * 6
@@ -306,13 +317,38 @@ def run_layer(args) -> dict:
     T = 8192
     jobs = make_block_jobs(T, args.quantised_acts)
     torch.cuda.synchronize()
+    # Stage 1 optimises every linear against frozen inputs: the seven jobs are independent, so they are issued on
+    # several HIP streams (default priority).  While one job's workgroups sit in a GEMM epilogue or in the
+    # memory-bound pass that updates V, compute units that fall idle pick up another job's GEMM tiles.
+    by_name = {j.name: j for j in jobs}
+    groups = {1: [["q_proj", "k_proj", "v_proj", "o_proj", "gate_proj", "up_proj", "down_proj"]],
+              2: [["gate_proj", "q_proj", "k_proj", "v_proj", "o_proj"], ["up_proj", "down_proj"]],
+              3: [["gate_proj", "q_proj", "k_proj"], ["up_proj", "v_proj", "o_proj"], ["down_proj"]]}[args.streams]
+    streams = [torch.cuda.Stream() for _ in groups] if args.streams > 1 else [torch.cuda.current_stream()]
+
+    def job_ops(j, n_steps):
+        yield j.setup
+        for t in range(1, n_steps + 1):
+            yield lambda t=t: j.step(t, n_steps)
+        yield j.finish
 
     def layer_job(n_steps):
-        for j in jobs:
-            j.setup()
-            for t in range(1, n_steps + 1):
-                j.step(t, n_steps)
-            j.finish()
+        cur = torch.cuda.current_stream()
+        for st in streams:
+            st.wait_stream(cur)
+        pending = [iter([op for name in g for op in job_ops(by_name[name], n_steps)]) for g in groups]
+        streams_live = list(streams)
+        while pending:                       # round-robin over the streams so that every queue stays fed
+            for k in range(len(pending) - 1, -1, -1):
+                op = next(pending[k], None)
+                if op is None:
+                    pending.pop(k)
+                    streams_live.pop(k)
+                    continue
+                with torch.cuda.stream(streams_live[k]):
+                    op()
+        for st in streams:
+            cur.wait_stream(st)
 
     layer_job(max(1, args.warmup))          # warm-up (untimed)
     torch.cuda.synchronize()
@@ -329,7 +365,7 @@ def run_layer(args) -> dict:
     for j in jobs:
         rtn, opt = j.hardened_losses()
         table = j.kernel_table(j.probe_kernels(timer, n_probe, args.steps + 1, codec=True))
-        per_linear[j.name] = {"O": j.O, "K": j.K, "dw_split": j.dw_split, "final_losses": j.losses.cpu().numpy().tolist(),
+        per_linear[j.name] = {"O": j.O, "K": j.K, "dw_split": j.dw_split, "gradient_constant": j.use_h, "final_losses": j.losses.cpu().numpy().tolist(),
                               "flipped_decisions": int(j.state["flips"].item()), "hardened_loss": {"rtn": rtn, "faar": opt},
                               "kernels": table}
     # the kernel that takes the largest share of a step of the whole layer
@@ -345,8 +381,9 @@ def run_layer(args) -> dict:
                                "6144x2048, down 2048x6144; bf16 Student-t(4) std 0.02), X 8192 tokens "
                                f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'} with 1% outlier channels x30, "
                                "NVFP4 block 16; per linear: quant_rtn + init_v + prepare + K steps + harden_pack; one timed step = "
-                               "one step of every linear; value = linear-layer steps/s",
-                   "T": T, "linears": n_lin, "weights": weights},
+                               f"one step of every linear; value = linear-layer steps/s; the 7 independent jobs issued on {args.streams} "
+                               "HIP stream(s)",
+                   "T": T, "linears": n_lin, "weights": weights, "streams": args.streams},
         "weight_elems_per_sec": round(weights * args.steps / elapsed, 1),
         "step_gemm_tflops": round(flops_per_set / (ms_per_step * 1e-3) / 1e12, 1),
         "roofline": {"kernel": f"{dom_l}.{dom_k}", "bound": dom["bound"], "achieved": dom["achieved"],
@@ -450,7 +487,7 @@ def run_linear(args) -> dict:
                    "O": O, "K": K, "T": T},
         "weight_elems_per_sec": round(O * K * args.steps / elapsed, 1),
         "step_gemm_tflops": round(2 * gemm_flops / (ms_per_step * 1e-3) / 1e12, 1),
-        "dw_split": j.dw_split, "final_losses": final_losses, "flipped_decisions": n_flips,
+        "dw_split": j.dw_split, "gradient_constant": j.use_h, "final_losses": final_losses, "flipped_decisions": n_flips,
         "hardened_loss": {"rtn": loss_rtn, "faar": loss_faar, "stochastic": stochastic},
         "roofline": roofline, "kernels": kernels,
     }
@@ -480,6 +517,7 @@ def run_block_chained(args) -> dict:
     jobs = make_block_jobs(T)
     lin = []
     for j in jobs:
+        j.use_h = True          # with dY from upstream the residual GEMM then only sums the loss
         j.setup()
         j.Y = None
         j.ws = None
@@ -492,7 +530,7 @@ def run_block_chained(args) -> dict:
         L["t"] += 1
         faar.faar_layer_step(j.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], j.Xq, s["Xt"], s["C"], s["ic"], beta,
                              LAM, j.alpha, LR, 0.9, 0.999, 1e-8, L["t"], j.losses, L["ws"], dY_ext=L["dY"],
-                             dX=L["dX"], beta_next=beta, forward_ready=L["ready"])
+                             dX=L["dX"], beta_next=beta, forward_ready=L["ready"], **s["hk"])
         L["ready"] = True
 
     for _ in range(warmup):
@@ -522,7 +560,7 @@ def run_block_chained(args) -> dict:
                 row[kname] = {"ms": round(ms, 5), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
                               "frac": round(flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)}
             else:
-                b = bytes_per_weight(j.dw_split)["bwd_adam"] + 2      # + W_q for the next dX
+                b = bytes_per_weight(j.dw_split, True)["bwd_adam"] + 2      # + W_q for the next dX
                 row[kname] = {"ms": round(ms, 5), "gbs": round(b * O * K / (ms * 1e-3) / 1e9, 1),
                               "frac": round(b * O * K / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         row["dw_split"] = j.dw_split
@@ -807,6 +845,8 @@ def main() -> int:
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
                     help="single-linear workloads: after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
+    ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
+                    help="qwen_layer: HIP streams the seven independent per-linear jobs are issued on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=12)

@@ -61,6 +61,8 @@ enum {
                                    step that takes dY_ext and/or produces dX */
   FAAR_WS_FORWARD_READY = 1u << 3, /* faar_layer_step: the workspace already holds this step's soft-quantised
                                    weights, left there by the previous step (its beta_next) */
+  FAAR_WS_GRADIENT_CONSTANT = 1u << 5, /* faar_workspace_bytes(FAAR_OP_LAYER_PREPARE): size the workspace for a call that
+                                   also produces H and c_norm2 */
   FAAR_DQ_IN_UNITS = 1u << 4    /* faar_quant_rtn: W_dq receives sign * node * E4M3 scale, i.e. the dequantised
                                    value in units of s_global -- an exact product (at most 6 significant bits),
                                    so exactly representable in bf16 */
@@ -241,17 +243,30 @@ int faar_softquant_fwd_bwd_static(const void* W, faar_dtype wdt, int64_t O, int6
  *
  *   icodes = uint8 [O*K/2], element 2j of a row in the low nibble: signbit(w) << 3 | (w == 0 ? 7 : k_lo)
  *
+ * and, optionally, the part of the gradient that does not depend on V.  With A = x_scale Xq (W_q - W)^T the residual is
+ * R = A - C, so  dL_mse/dW_q = (2 a R)^T X_q = (2 a A)^T X_q - 2 a C^T X_q  and  ||R||^2 = ||A||^2 - 2 <A, C> + ||C||^2
+ * with <A, C> = x_scale <W_q - W, C^T Xq>  (a = mse_scale).  Given
+ *
+ *   H       = C^T Xq     as float [O*K]  (products of three bf16 terms of C with Xq: exact; float32 accumulation)
+ *   c_norm2 = ||C||^2    as double[1]
+ *
+ * a step's residual GEMM reads no constant in its epilogue (4 bytes per output of Y less), at the price of reading H
+ * (4 bytes per weight) in the pass that updates V: a saving whenever T > K, and always when the step's dY comes
+ * from upstream.  H and c_norm2 are both NULL or both given; pass the same pair to faar_layer_step.
+ *
  *   s_global, scales  as written by faar_quant_rtn
  *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4), in units of
  *   x_scale in, nullable device float[1] (NULL = 1): X_q = x_scale * Xq.  NVFP4-quantised activations are
  *        passed exactly as Xq = node * block scale (bf16-exact) and x_scale = their tensor scale.
  *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T
- *   ws   FAAR_OP_LAYER_PREPARE workspace
+ *   ws   FAAR_OP_LAYER_PREPARE workspace (queried with FAAR_WS_GRADIENT_CONSTANT when H is wanted; needed for a
+ *        float32 W or with H)
  */
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                        const float* s_global, const uint8_t* scales,
                        const void* Xq, const float* x_scale, const void* Y_fp, faar_dtype ydt, int64_t T,
-                       void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream);
+                       void* Xt, float* C, uint8_t* icodes, float* H, double* c_norm2,
+                       void* ws, size_t ws_bytes, void* stream);
 
 /* Adam hyper-parameters; t is the 1-based index of the step being taken. */
 typedef struct {
@@ -273,6 +288,11 @@ typedef struct {
  *
  *   V, adam_m, adam_v   in/out float[O*K]
  *   Xq, x_scale, Xt, C, icodes   as for / from faar_layer_prepare
+ *   H, c_norm2          nullable pair from faar_layer_prepare.  When given, the step uses the split form described
+ *                       there: what is stored (and rounded to bf16) as dY is 2 a A instead of 2 a (A - C), and H
+ *                       supplies the rest -- the same loss and gradient with one rounding point moved, so results
+ *                       agree with the H-less form to rounding, not bit for bit.  With dY_ext the residual GEMM then
+ *                       only sums the loss.  Ignored (the C form is used) when dX is wanted without dY_ext.
  *   dY_ext              in, nullable bf16[T*O]: upstream gradient replacing the locally derived dY
  *   dX                  out, nullable bf16[T*K]: dY W_q
  *   opt                 HOST pointer
@@ -289,7 +309,7 @@ typedef struct {
  *                       V, shapes, dX requested or not) with beta_next equal to this call's beta, and neither V
  *                       nor ws has been written since.  Checked ON THE DEVICE as far as it can be: the step that
  *                       leaves a forward in ws tags it with (step index, beta, addresses of V, W and scales, O*K,
- *                       dX requested), every call that overwrites that forward (a step without the flag,
+ *                       dX requested, H), every call that overwrites that forward (a step without the flag,
  *                       faar_hardened_loss) clears the tag, and a step consumes the tag it checks.  On a mismatch
  *                       -- a stale or foreign workspace, a repeated or skipped step, another beta -- the step
  *                       writes NaN to losses[0..2], leaves V, adam_m and adam_v untouched (dX is undefined) and
@@ -301,7 +321,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* s_global, const uint8_t* scales,
                     float* V, float* adam_m, float* adam_v,
                     const void* Xq, const float* x_scale, const void* Xt, const float* C, const uint8_t* icodes,
-                    int64_t T, const void* dY_ext, void* dX,
+                    const float* H, const double* c_norm2, int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libfaar.so")
 
 FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
+FAAR_WS_GRADIENT_CONSTANT = 32
 OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH = range(8)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
@@ -81,12 +82,12 @@ def lib() -> ctypes.CDLL:
                                                     c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_uint32, c_void_p]
         L.faar_layer_prepare.restype = c_int
         L.faar_layer_prepare.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                         c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t,
-                                         c_void_p]
+                                         c_void_p, c_int, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                         c_void_p, c_size_t, c_void_p]
         L.faar_layer_step.restype = c_int
         L.faar_layer_step.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
-                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
-                                      c_void_p,
+                                      c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                      c_int64, c_void_p, c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
         L.faar_stochastic_v.restype = c_int
@@ -280,8 +281,9 @@ def faar_softquant_fwd_bwd_static(W, s_global, scales, V, beta, Wt, dWt=None, la
                                                _stream()), "faar_softquant_fwd_bwd_static")
 
 
-def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None):
-    """-> (Xt bf16 [K, Tp], C f32 [ceil(T/4), O, 4] (tokens interleaved in groups of four), icodes u8 [O, K/2])."""
+def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None, gradient_constant=False):
+    """-> (Xt bf16 [K, Tp], C f32 [ceil(T/4), O, 4] (tokens interleaved in groups of four), icodes u8 [O, K/2]);
+    with gradient_constant also -> (..., H f32 [O, K] = C^T Xq, c_norm2 f64[1] = ||C||^2)."""
     _dev(W, s_global, scales, Xq, Y_fp, ws, x_scale)
     O, K = W.shape
     T = Xq.shape[0]
@@ -290,25 +292,30 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None):
     Xt = torch.empty((K, faar_padded_tokens(T)), dtype=torch.bfloat16, device=W.device)
     C = torch.empty(((T + 3) // 4, O, 4), dtype=torch.float32, device=W.device)   # row groups of 4 interleaved
     icodes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
-    ws = _workspace(OP_LAYER_PREPARE, O, K, T, device=W.device) if ws is None else ws
+    H = torch.empty((O, K), dtype=torch.float32, device=W.device) if gradient_constant else None
+    cn = torch.empty(1, dtype=torch.float64, device=W.device) if gradient_constant else None
+    flags = FAAR_WS_GRADIENT_CONSTANT if gradient_constant else 0
+    ws = _workspace(OP_LAYER_PREPARE, O, K, T, flags, device=W.device) if ws is None else ws
     _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(x_scale),
-                                    _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(ws), ws.numel(), _stream()),
+                                    _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(H), _ptr(cn), _ptr(ws),
+                                    ws.numel(), _stream()),
            "faar_layer_prepare")
-    return Xt, C, icodes
+    return (Xt, C, icodes, H, cn) if gradient_constant else (Xt, C, icodes)
 
 
 def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
                     lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False,
-                    x_scale=None):
+                    x_scale=None, H=None, c_norm2=None):
     """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L).
-    beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them."""
-    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX, x_scale)
+    beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them.
+    H, c_norm2: the gradient constant of faar_layer_prepare(gradient_constant=True), or None."""
+    _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX, x_scale, H, c_norm2)
     O, K = W.shape
     T = Xq.shape[0]
     opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
     _check(lib().faar_layer_step(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m),
-                                 _ptr(adam_v), _ptr(Xq), _ptr(x_scale), _ptr(Xt), _ptr(C), _ptr(icodes), T, _ptr(dY_ext),
-                                 _ptr(dX),
+                                 _ptr(adam_v), _ptr(Xq), _ptr(x_scale), _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(H),
+                                 _ptr(c_norm2), T, _ptr(dY_ext), _ptr(dX),
                                  float(beta), float(beta_next), float(lambda_round), float(mse_scale),
                                  ctypes.byref(opt), _ptr(losses), FAAR_WS_FORWARD_READY if forward_ready else 0,
                                  _ptr(ws), ws.numel(), _stream()), "faar_layer_step")

@@ -63,7 +63,7 @@ struct Carver {
 };
 
 struct StepLayout {
-  size_t guard, delta, dYt, G, mse_partials, round_partials, wq_full, wqt, dY, total;
+  size_t guard, delta, dYt, G, mse_partials, round_partials, cross_partials, wq_full, wqt, dY, total;
   int n_split;
   int64_t Tp, Op;
 };
@@ -81,6 +81,7 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   L.G = take((size_t)L.n_split * O * K * 4);
   L.mse_partials = take((size_t)gemm_residual_partials(T, O, K) * 8);
   L.round_partials = take((size_t)2 * kStepBwdMaxBlocks * 8);  // two sets: steps of even / odd index
+  L.cross_partials = take((size_t)2 * kStepBwdMaxBlocks * 8);  // likewise; used when the layer carries H
   if (chained) {
     L.wq_full = take((size_t)O * K * 2);
     L.wqt = take((size_t)K * L.Op * 2);
@@ -91,7 +92,8 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
 }
 
 // Tag of the forward pass "W_q - W (and W_q when dX is wanted) of step t of this layer at this beta".
-ForwardTag forward_tag(int32_t t, float beta, const void* V, const void* W, const void* scales, int64_t n, bool with_wq) {
+ForwardTag forward_tag(int32_t t, float beta, const void* V, const void* W, const void* scales, int64_t n, bool with_wq,
+                       const void* H) {
   ForwardTag g{};
   uint32_t bits;
   static_assert(sizeof(bits) == sizeof(beta), "float is 32 bits");
@@ -106,7 +108,9 @@ ForwardTag forward_tag(int32_t t, float beta, const void* V, const void* W, cons
   g.w[5] = lo(w); g.w[6] = hi(w);
   g.w[7] = lo(s); g.w[8] = hi(s);
   g.w[9] = lo(static_cast<uint64_t>(n)); g.w[10] = hi(static_cast<uint64_t>(n));
-  g.w[11] = with_wq ? 1u : 0u;
+  // with H the forward also left the loss's cross term <delta, H>: fold H's address in
+  g.w[11] = (with_wq ? 1u : 0u) | (H ? 2u : 0u) | (lo(reinterpret_cast<uintptr_t>(H)) & ~3u);
+  g.w[9] ^= hi(reinterpret_cast<uintptr_t>(H));
   return g;
 }
 
@@ -235,9 +239,17 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
       return 256;  // none needed; a non-zero size keeps callers' allocation code uniform
     case FAAR_OP_SOFTQUANT:
       return align256((size_t)softquant_bwd_blocks(O * K) * sizeof(double));
-    case FAAR_OP_LAYER_PREPARE:
-      if (T <= 0) return 0;
-      return 3 * align256((size_t)O * K * 2);  // hi/mid/lo bf16 terms of a float32 W
+    case FAAR_OP_LAYER_PREPARE: {
+      if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return 0;
+      size_t need = 3 * align256((size_t)O * K * 2);  // hi/mid/lo bf16 terms of a float32 W
+      if (flags & FAAR_WS_GRADIENT_CONSTANT) {        // one bf16 term of C^T, the partial products, sums of C^2
+        const int64_t Tp = padded_tokens(T);
+        const size_t h = align256((size_t)O * Tp * 2) + align256((size_t)choose_split(O, K, Tp) * O * K * 4) +
+                         align256((size_t)c_term_blocks(T, O) * 8);
+        need = need > h ? need : h;
+      }
+      return need;
+    }
     case FAAR_OP_LAYER_STEP:
       if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return 0;
       return step_layout(O, K, T, (flags & FAAR_WS_CHAINED) != 0).total;
@@ -350,8 +362,11 @@ int faar_softquant_fwd_bwd_static(const void* W, faar_dtype wdt, int64_t O, int6
 
 int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
                        const uint8_t* scales, const void* Xq, const float* x_scale, const void* Y_fp, faar_dtype ydt,
-                       int64_t T, void* Xt, float* C, uint8_t* icodes, void* ws, size_t ws_bytes, void* stream) {
+                       int64_t T, void* Xt, float* C, uint8_t* icodes, float* H, double* c_norm2, void* ws, size_t ws_bytes,
+                       void* stream) {
   if (!W || !s_global || !scales || !Xq || !Y_fp || !Xt || !C || !icodes) return FAAR_E_NULL;
+  if ((H != nullptr) != (c_norm2 != nullptr)) return FAAR_E_NULL;
+  if (!aligned16(H) || (reinterpret_cast<uintptr_t>(c_norm2) & 7u)) return FAAR_E_ARG;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_wdt(ydt)) return e;
   if (int e = check_shape(O, K)) return e;
@@ -359,29 +374,54 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   if (!aligned16(W) || !aligned16(Xq) || !aligned16(Y_fp) || !aligned16(Xt) || !aligned16(C) || !aligned16(icodes))
     return FAAR_E_ARG;
   const bool bf = wdt == FAAR_BF16;
-  if (!bf && (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_LAYER_PREPARE, O, K, T, 0))) return FAAR_E_WORKSPACE;
+  if ((!bf || H) &&
+      (!ws || !aligned16(ws) || ws_bytes < faar_workspace_bytes(FAAR_OP_LAYER_PREPARE, O, K, T, H ? FAAR_WS_GRADIENT_CONSTANT : 0)))
+    return FAAR_E_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const bf16_t* xq = static_cast<const bf16_t*>(Xq);
+  const int64_t Tp = padded_tokens(T);
   if (int e = hip_status(launch_interval_codes(W, bf, O * K, s_global, scales, icodes, st))) return e;
-  if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), padded_tokens(T), st))) return e;
+  if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), Tp, st))) return e;
   const GemmDims d{T, O, K, K, K};
-  if (bf) return hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, x_scale, st));
-  Carver cv(ws);
-  bf16_t* term[3];
-  for (auto& t : term) t = cv.take<bf16_t>((size_t)O * K);
-  if (int e = hip_status(launch_split_f32(static_cast<const float*>(W), O * K, term[0], term[1], term[2], st))) return e;
-  for (int i = 0; i < 3; ++i)
-    if (int e = hip_status(launch_gemm_sub(xq, term[i], d, Y_fp, ydt == FAAR_BF16, i == 0, C, x_scale, st))) return e;
-  return FAAR_OK;
+  if (bf) {
+    if (int e = hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, x_scale, st)))
+      return e;
+  } else {
+    Carver cv(ws);
+    bf16_t* term[3];
+    for (auto& t : term) t = cv.take<bf16_t>((size_t)O * K);
+    if (int e = hip_status(launch_split_f32(static_cast<const float*>(W), O * K, term[0], term[1], term[2], st))) return e;
+    for (int i = 0; i < 3; ++i)
+      if (int e = hip_status(launch_gemm_sub(xq, term[i], d, Y_fp, ydt == FAAR_BF16, i == 0, C, x_scale, st))) return e;
+  }
+  if (!H) return FAAR_OK;
+  // H = C^T Xq (the activations as stored, i.e. in units of x_scale): C is split into three bf16 terms, each
+  // transposed into the operand layout of the dW GEMM and multiplied with Xt on the matrix cores (exact products,
+  // float32 accumulation); the terms' partial products are summed into H.  ||C||^2 comes from the first pass over C.
+  Carver cv(ws);   // the float32-W terms above are no longer needed
+  bf16_t* ct = cv.take<bf16_t>((size_t)O * Tp);
+  const int n_split = choose_split(O, K, Tp);
+  float* part = cv.take<float>((size_t)n_split * O * K);
+  double* sq = cv.take<double>((size_t)c_term_blocks(T, O));
+  const GemmDims d2{O, K, Tp, Tp, Tp};
+  for (int term = 0; term < 3; ++term) {
+    if (int e = hip_status(launch_c_term_transposed(C, T, O, term, ct, Tp, term == 0 ? sq : nullptr, st))) return e;
+    if (int e = hip_status(launch_gemm_f32(ct, static_cast<const bf16_t*>(Xt), d2, part, n_split, st))) return e;
+    if (int e = hip_status(launch_accumulate_partials(H, part, n_split, (int64_t)O * K, O * K, term == 0, st))) return e;
+  }
+  return hip_status(launch_sum_doubles(sq, c_term_blocks(T, O), c_norm2, st));
 }
 
 int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,
                     const uint8_t* scales, float* V, float* adam_m, float* adam_v, const void* Xq, const float* x_scale,
-                    const void* Xt, const float* C, const uint8_t* icodes, int64_t T, const void* dY_ext, void* dX,
+                    const void* Xt, const float* C, const uint8_t* icodes, const float* H, const double* c_norm2,
+                    int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
   if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !icodes || !opt || !losses)
     return FAAR_E_NULL;
+  if ((H != nullptr) != (c_norm2 != nullptr)) return FAAR_E_NULL;
+  if (!aligned16(H) || (reinterpret_cast<uintptr_t>(c_norm2) & 7u)) return FAAR_E_ARG;
   if (int e = check_wdt(wdt)) return e;
   if (int e = check_shape(O, K)) return e;
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
@@ -412,6 +452,11 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   // next one writes the other set while its last block reads this one
   double* round_p = reinterpret_cast<double*>(base + L.round_partials) + (opt->t & 1) * kStepBwdMaxBlocks;
   double* round_next = reinterpret_cast<double*>(base + L.round_partials) + ((opt->t + 1) & 1) * kStepBwdMaxBlocks;
+  double* cross_p = reinterpret_cast<double*>(base + L.cross_partials) + (opt->t & 1) * kStepBwdMaxBlocks;
+  double* cross_next = reinterpret_cast<double*>(base + L.cross_partials) + ((opt->t + 1) & 1) * kStepBwdMaxBlocks;
+  // The constant part of the gradient is carried separately when the caller provides it -- unless dX has to come
+  // from the locally derived dY, which then must contain the constant
+  const float* Hs = (H && !(dX && !dY_ext)) ? H : nullptr;
   bf16_t* wq_full = chained && dX ? reinterpret_cast<bf16_t*>(base + L.wq_full) : nullptr;
   bf16_t* wqt = chained ? reinterpret_cast<bf16_t*>(base + L.wqt) : nullptr;
   bf16_t* dY = chained ? reinterpret_cast<bf16_t*>(base + L.dY) : nullptr;
@@ -423,11 +468,12 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   ForwardGuard guard{nullptr, {}};
   if (!(flags & FAAR_WS_FORWARD_READY)) {
     Bracket b(FAAR_K_SOFTQUANT_FWD, st);
-    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, round_p, guard_slot, st)))
+    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, wq_full, round_p, guard_slot, Hs,
+                                           cross_p, st)))
       return e;
   } else {
     guard.slot = guard_slot;
-    guard.expect = forward_tag(opt->t, beta, V, W, scales, n, wq_full != nullptr);
+    guard.expect = forward_tag(opt->t, beta, V, W, scales, n, wq_full != nullptr, Hs);
   }
   // s2: residual GEMM + loss + dY
   int64_t n_mse = 0;
@@ -435,8 +481,10 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   const bool need_local_dY = dX && !dY_ext;
   {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
-    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, C, x_scale, 2.0f * mse_scale, dYt, L.Tp,
-                                                need_local_dY ? dY : nullptr, mse_p, &n_mse, guard, st)))
+    // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
+    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, Hs ? nullptr : C, x_scale, 2.0f * mse_scale,
+                                                (Hs && dY_ext) ? nullptr : dYt, L.Tp, need_local_dY ? dY : nullptr, mse_p,
+                                                &n_mse, guard, st)))
       return e;
   }
   const bf16_t* dY_used = dY;
@@ -471,7 +519,9 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.mse_partials = mse_p; a.n_mse = n_mse; a.mse_scale = mse_scale; a.round_partials = round_p; a.losses = losses;
   a.beta_next = beta_next; a.delta_next = delta; a.wq_full_next = wq_full; a.round_next = round_next;
   a.guard_slot = guard_slot;
-  a.next_tag = forward_tag(opt->t + 1, beta_next, V, W, scales, n, wq_full != nullptr);
+  a.next_tag = forward_tag(opt->t + 1, beta_next, V, W, scales, n, wq_full != nullptr, Hs);
+  a.H = Hs; a.two_alpha_h = (Hs && !dY_ext) ? 2.0f * mse_scale : 0.0f;
+  a.cross_partials = cross_p; a.c_norm2 = c_norm2; a.cross_next = cross_next;
   Bracket b(FAAR_K_BWD_ADAM, st);
   return hip_status(launch_step_bwd_adam(a, st));
 }

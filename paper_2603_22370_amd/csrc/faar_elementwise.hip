@@ -423,11 +423,13 @@ __device__ __forceinline__ void store_bf16x8(bf16_t* p, const float (&x)[8]) {
                                             pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
 }
 
-// delta = bf16(W_q - W) (and bf16(W_q)) for eight weights, plus their Round-Loss terms sum(1 - (2v - 1)^2)
+// delta = bf16(W_q - W) (and bf16(W_q)) for eight weights, plus their Round-Loss terms sum(1 - (2v - 1)^2) and, when
+// the layer carries the constant H = C^T X_q (use_h; hh its eight values), the cross term sum(delta * H) of the loss, taken on the
+// ROUNDED delta -- the operand the residual GEMM actually multiplies
 template <typename WT, bool kFull>
 __device__ __forceinline__ float forward8(const WT* __restrict__ W, int64_t i, uint32_t codes, float s,
                                           const float (&v)[8], float beta, bf16_t* __restrict__ delta,
-                                          bf16_t* __restrict__ Wq_full) {
+                                          bf16_t* __restrict__ Wq_full, bool use_h, const float (&hh)[8], float& cross) {
   float w[8], out[8], full[8];
   W8<WT>::load(W + i * 8, w);
   float rsum = 0.0f;
@@ -439,7 +441,15 @@ __device__ __forceinline__ float forward8(const WT* __restrict__ W, int64_t i, u
     const float t = 2.0f * v[j] - 1.0f;
     rsum += 1.0f - t * t;
   }
-  store_bf16x8(delta + i * 8, out);
+  const uint4 packed = make_uint4(pack_bf16x2(out[0], out[1]), pack_bf16x2(out[2], out[3]),
+                                  pack_bf16x2(out[4], out[5]), pack_bf16x2(out[6], out[7]));
+  *reinterpret_cast<uint4*>(delta + i * 8) = packed;
+  if (use_h) {   // hh stays in registers: indexed by constants only
+    const uint32_t r[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      cross += __uint_as_float(r[j] << 16) * hh[2 * j] + __uint_as_float(r[j] & 0xFFFF0000u) * hh[2 * j + 1];
+  }
   if (kFull) store_bf16x8(Wq_full + i * 8, full);
   return rsum;
 }
@@ -449,20 +459,27 @@ __global__ void __launch_bounds__(kEltThreads)
 k_step_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_global_p,
            const uint8_t* __restrict__ scales, const uint32_t* __restrict__ icodes, const float* __restrict__ V,
            float beta, bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_partials,
-           uint32_t* __restrict__ guard_slot) {
+           uint32_t* __restrict__ guard_slot, const float* __restrict__ H, double* __restrict__ cross_partials) {
   if (blockIdx.x == 0 && threadIdx.x == 0) {  // a fresh forward: whatever tag the workspace held is void, verdict 1
     for (int i = 0; i < kTagWords; ++i) guard_slot[i] = 0u;
     guard_slot[kTagWords] = 1u;
   }
-  float rsum = 0.0f;
+  float rsum = 0.0f, cross = 0.0f;
   const float sg = *s_global_p;
   for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)gridDim.x * kEltThreads) {
-    float v[8];
+    float v[8], hh[8];
     load8(V + i * 8, v);
-    rsum += forward8<WT, kFull>(W, i, icodes[i], effective_scale(scales[i >> 1], sg), v, beta, delta, Wq_full);
+    if (H) load8(H + i * 8, hh);
+    rsum += forward8<WT, kFull>(W, i, icodes[i], effective_scale(scales[i >> 1], sg), v, beta, delta, Wq_full,
+                                H != nullptr, hh, cross);
   }
   const double bs = block_sum(static_cast<double>(rsum));
   if (threadIdx.x == 0) round_partials[blockIdx.x] = bs;
+  if (H) {
+    __syncthreads();                      // block_sum's scratch is reused
+    const double cs = block_sum(static_cast<double>(cross));
+    if (threadIdx.x == 0) cross_partials[blockIdx.x] = cs;
+  }
 }
 
 // ---- loss finalisation: fixed-order sums of the per-block partials (one block) ---------------
@@ -470,6 +487,12 @@ struct LossSums {
   const double* mse_partials;
   int64_t n_mse;
   float mse_scale;
+  // with the constant part of the residual carried separately (R = A - C, A = x_scale * acc):
+  // ||R||^2 = sum A^2 - 2 x_scale <delta, H> + ||C||^2; cross_partials sum to <delta, H>.  Null: mse_partials are ||R||^2.
+  const double* cross_partials;
+  int64_t n_cross;
+  const double* c_norm2;
+  const float* x_scale;
   const double* round_partials;
   int64_t n_round;
   double inv_n;
@@ -487,27 +510,36 @@ __device__ __forceinline__ void finalize_block(const LossSums& f, bool valid = t
     }
     return;
   }
-  double a = 0.0, b = 0.0;
+  double a = 0.0, b = 0.0, c = 0.0;
   // per-thread partial sums in a fixed order; loads of one batch are independent
 #pragma unroll 4
   for (int64_t i = threadIdx.x; i < f.n_mse; i += kEltThreads) a += f.mse_partials[i];
 #pragma unroll 4
   for (int64_t i = threadIdx.x; i < f.n_round; i += kEltThreads) b += f.round_partials[i];
-  __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64];
+  if (f.cross_partials) {
+#pragma unroll 4
+    for (int64_t i = threadIdx.x; i < f.n_cross; i += kEltThreads) c += f.cross_partials[i];
+  }
+  __shared__ double sa[kEltThreads / 64], sb[kEltThreads / 64], sc[kEltThreads / 64];
   a = wave_sum(a);
   b = wave_sum(b);
+  c = wave_sum(c);
   if ((threadIdx.x & 63) == 0) {
     sa[threadIdx.x >> 6] = a;
     sb[threadIdx.x >> 6] = b;
+    sc[threadIdx.x >> 6] = c;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     a = 0.0;
     b = 0.0;
+    c = 0.0;
     for (int i = 0; i < kEltThreads / 64; ++i) {
       a += sa[i];
       b += sb[i];
+      c += sc[i];
     }
+    if (f.cross_partials) a += *f.c_norm2 - 2.0 * static_cast<double>(f.x_scale ? *f.x_scale : 1.0f) * c;
     const double mse = a * static_cast<double>(f.mse_scale);
     const double rl = b * f.inv_n;
     if (f.loss_mse) *f.loss_mse = static_cast<float>(mse);
@@ -528,7 +560,8 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
                 float* __restrict__ U, float beta, const float* __restrict__ G, int n_split, int64_t split_stride,
                 const float* __restrict__ x_scale_p, float lam_over_n, AdamScalars o, LossSums fin, const WT* __restrict__ W, float beta_next,
                 bf16_t* __restrict__ delta, bf16_t* __restrict__ Wq_full, double* __restrict__ round_next,
-                uint32_t* __restrict__ guard_slot, ForwardTag next_tag) {
+                uint32_t* __restrict__ guard_slot, ForwardTag next_tag, const float* __restrict__ H, float two_alpha_h,
+                double* __restrict__ cross_next) {
   const int workers = static_cast<int>(gridDim.x) - 1;
   const bool valid = guard_slot[kTagWords] != 0u;  // written by an earlier kernel of this step
   if (static_cast<int>(blockIdx.x) == workers) {
@@ -539,13 +572,13 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
     return;
   }
   if (!valid) return;
-  float rsum = 0.0f;
+  float rsum = 0.0f, cross = 0.0f;
   const float sg = *s_global_p;
   const float xs = x_scale_p ? *x_scale_p : 1.0f;  // G = x_scale * (dY^T X_q-in-units)
   for (int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x; i < n8; i += (int64_t)workers * kEltThreads) {
     const float s = effective_scale(scales[i >> 1], sg);
     const uint32_t codes = icodes[i];
-    float v[8], g[8], m[8], u[8];
+    float v[8], g[8], m[8], u[8], hh[8];
     load8(V + i * 8, v);
     load8(M + i * 8, m);
     load8(U + i * 8, u);
@@ -555,6 +588,11 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
       load8(G + sp * split_stride + i * 8, g2);
 #pragma unroll
       for (int j = 0; j < 8; ++j) g[j] += g2[j];
+    }
+    if (H) {  // the constant part of the gradient, -2 alpha C^T X_q (two_alpha_h is 0 when dY came from upstream)
+      load8(H + i * 8, hh);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) g[j] -= two_alpha_h * hh[j];
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -570,11 +608,16 @@ k_step_bwd_adam(int64_t n8, const float* __restrict__ s_global_p, const uint8_t*
     store8(V + i * 8, v);
     store8(M + i * 8, m);
     store8(U + i * 8, u);
-    if (kEmit) rsum += forward8<WT, kFull>(W, i, codes, s, v, beta_next, delta, Wq_full);
+    if (kEmit) rsum += forward8<WT, kFull>(W, i, codes, s, v, beta_next, delta, Wq_full, H != nullptr, hh, cross);
   }
   if (kEmit) {
     const double bs = block_sum(static_cast<double>(rsum));
     if (threadIdx.x == 0) round_next[blockIdx.x] = bs;
+    if (H) {
+      __syncthreads();                    // block_sum's scratch is reused
+      const double cs = block_sum(static_cast<double>(cross));
+      if (threadIdx.x == 0) cross_next[blockIdx.x] = cs;
+    }
   }
 }
 
@@ -690,6 +733,78 @@ k_transpose_bf16(const bf16_t* __restrict__ in, int64_t rows, int64_t cols, bf16
           make_uint4(e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16));
     }
   }
+}
+
+// ---- the constant part of the gradient, H = C^T X_q (once per layer) -----------------------------------------------
+// C (float32, tokens interleaved in groups of four: [ceil(T/4)][O][4]) -> one of its three bf16 terms hi / mid / lo
+// (each the rounding of the running remainder: together all 24 significand bits), transposed to [O, ld_out] with
+// zero padding, i.e. in the operand layout of the dW GEMM.  64 outputs x 64 tokens per workgroup through LDS; both
+// sides move whole 128-byte (or longer) runs.  With sq_partials != null the workgroup also writes its sum of C^2.
+__global__ void __launch_bounds__(256)
+k_c_term_transposed(const float* __restrict__ C, int64_t T, int64_t O, int term, bf16_t* __restrict__ out, int64_t ld_out,
+                    unsigned tiles_o, double* __restrict__ sq_partials) {
+  __shared__ uint32_t tile[64][33];            // [output][token pair], pitch 33 words
+  const int64_t o0 = (blockIdx.x % tiles_o) * 64LL, t0 = (blockIdx.x / tiles_o) * 64LL;
+  const int og = threadIdx.x & 63, gq = threadIdx.x >> 6;
+  const int64_t groups = (T + 3) / 4;
+  float sq = 0.0f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int g = gq + 4 * it;                 // token group within the tile
+    const int64_t gg = t0 / 4 + g, o = o0 + og;
+    float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (gg < groups && o < O) c = *reinterpret_cast<const float4*>(C + (gg * O + o) * 4);
+    const float x[4] = {c.x, c.y, c.z, c.w};
+    uint32_t b[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      sq += x[q] * x[q];
+      const uint32_t h = f32_to_bf16(x[q]);
+      const float r1 = x[q] - bf16_to_f32(h);
+      const uint32_t m = f32_to_bf16(r1);
+      const float r2 = r1 - bf16_to_f32(m);
+      b[q] = term == 0 ? h : (term == 1 ? m : f32_to_bf16(r2));
+    }
+    tile[og][2 * g] = b[0] | (b[1] << 16);
+    tile[og][2 * g + 1] = b[2] | (b[3] << 16);
+  }
+  __syncthreads();
+  const int sub = threadIdx.x >> 3, ch = threadIdx.x & 7;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int row = p * 32 + sub;
+    const int64_t o = o0 + row, t = t0 + ch * 8;
+    if (o < O && t < ld_out)                   // ld_out is a multiple of 64: a chunk is inside or outside as a whole
+      *reinterpret_cast<uint4*>(out + o * ld_out + t) =
+          make_uint4(tile[row][ch * 4], tile[row][ch * 4 + 1], tile[row][ch * 4 + 2], tile[row][ch * 4 + 3]);
+  }
+  if (sq_partials) {
+    __syncthreads();
+    const double bs = block_sum(static_cast<double>(sq));
+    if (threadIdx.x == 0) sq_partials[blockIdx.x] = bs;
+  }
+}
+
+// H = (first ? 0 : H) + sum over the splits of the partial products
+__global__ void __launch_bounds__(kEltThreads)
+k_accumulate_partials(float* __restrict__ H, const float* __restrict__ partials, int n_split, int64_t stride, int64_t n4,
+                      bool first) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n4) return;
+  float4 a = first ? make_float4(0.0f, 0.0f, 0.0f, 0.0f) : reinterpret_cast<const float4*>(H)[i];
+  for (int s = 0; s < n_split; ++s) {
+    const float4 p = *reinterpret_cast<const float4*>(partials + s * stride + i * 4);
+    a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+  }
+  reinterpret_cast<float4*>(H)[i] = a;
+}
+
+// out[0] = sum of n doubles, in a fixed order (one workgroup)
+__global__ void __launch_bounds__(kEltThreads) k_sum_doubles(const double* __restrict__ p, int64_t n, double* __restrict__ out) {
+  double a = 0.0;
+  for (int64_t i = threadIdx.x; i < n; i += kEltThreads) a += p[i];
+  const double t = block_sum(a);
+  if (threadIdx.x == 0) *out = t;
 }
 
 // float32 -> hi + mid + lo bf16 terms (24 significand bits covered by 3 x 8).
@@ -839,12 +954,13 @@ hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const fl
 
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           double* round_partials, uint32_t* guard_slot, hipStream_t st) {
+                           double* round_partials, uint32_t* guard_slot, const float* H, double* cross_partials,
+                           hipStream_t st) {
   const int64_t n8 = n / 8;
   const dim3 g(static_cast<unsigned>(step_bwd_blocks(n))), b(kEltThreads);
   const uint32_t* c32 = reinterpret_cast<const uint32_t*>(icodes);
 #define FAAR_SF(WT, F) \
-  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full, round_partials, guard_slot)
+  hipLaunchKernelGGL((k_step_fwd<WT, F>), g, b, 0, st, static_cast<const WT*>(W), n8, s_global, scales, c32, V, beta, delta, Wq_full, round_partials, guard_slot, H, cross_partials)
   if (w_bf16) { if (Wq_full) FAAR_SF(bf16_t, true); else FAAR_SF(bf16_t, false); }
   else        { if (Wq_full) FAAR_SF(float, true);  else FAAR_SF(float, false); }
 #undef FAAR_SF
@@ -856,13 +972,14 @@ hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st) {
   const int64_t workers = step_bwd_blocks(a.n);
   const dim3 g(static_cast<unsigned>(workers + 1)), b(kEltThreads);  // the extra block finishes the losses
   const float lam_over_n = static_cast<float>(static_cast<double>(a.lambda_round) / static_cast<double>(a.n));
-  const LossSums fin{a.mse_partials, a.n_mse, a.mse_scale, a.round_partials, workers, 1.0 / static_cast<double>(a.n),
+  const LossSums fin{a.mse_partials, a.n_mse, a.mse_scale, a.H ? a.cross_partials : nullptr, workers, a.c_norm2, a.x_scale,
+                     a.round_partials, workers, 1.0 / static_cast<double>(a.n),
                      a.lambda_round, a.losses, a.losses + 1, a.losses + 2};
   const uint32_t* c32 = reinterpret_cast<const uint32_t*>(a.icodes);
 #define FAAR_SB(WT, E, F) \
   hipLaunchKernelGGL((k_step_bwd_adam<WT, E, F>), g, b, 0, st, n8, a.s_global, a.scales, c32, a.V, a.m, a.u, a.beta, a.G, \
                      a.n_split, a.split_stride, a.x_scale, lam_over_n, a.opt, fin, static_cast<const WT*>(a.W), a.beta_next, \
-                     a.delta_next, a.wq_full_next, a.round_next, a.guard_slot, a.next_tag)
+                     a.delta_next, a.wq_full_next, a.round_next, a.guard_slot, a.next_tag, a.H, a.two_alpha_h, a.cross_next)
   const bool emit = a.beta_next > 0.0f;
   if (!emit) { if (a.w_bf16) FAAR_SB(bf16_t, false, false); else FAAR_SB(float, false, false); }
   else if (a.wq_full_next) { if (a.w_bf16) FAAR_SB(bf16_t, true, true); else FAAR_SB(float, true, true); }
@@ -875,7 +992,7 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
                                   const double* round_partials, int64_t n_round, double inv_n,
                                   float lambda_round, float* loss_mse, float* loss_round,
                                   float* loss_total, hipStream_t st) {
-  const LossSums f{mse_partials, n_mse, mse_scale, round_partials, n_round, inv_n, lambda_round,
+  const LossSums f{mse_partials, n_mse, mse_scale, nullptr, 0, nullptr, nullptr, round_partials, n_round, inv_n, lambda_round,
                    loss_mse, loss_round, loss_total};
   hipLaunchKernelGGL(k_finalize_losses, dim3(1), dim3(kEltThreads), 0, st, f);
   return hipGetLastError();
@@ -913,6 +1030,31 @@ hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, b
   if (tiles_c * tiles_r > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_transpose_bf16, dim3(static_cast<unsigned>(tiles_c * tiles_r)), dim3(256), 0, st, in, rows, cols, out,
                      ld_out, static_cast<unsigned>(tiles_c));
+  return hipGetLastError();
+}
+
+int64_t c_term_blocks(int64_t T, int64_t O) { return ((O + 63) / 64) * (padded_tokens(T) / 64); }
+
+hipError_t launch_c_term_transposed(const float* C, int64_t T, int64_t O, int term, bf16_t* out, int64_t ld_out,
+                                    double* sq_partials, hipStream_t st) {
+  if (ld_out != padded_tokens(T)) return hipErrorInvalidValue;
+  const int64_t tiles_o = (O + 63) / 64, blocks = c_term_blocks(T, O);
+  if (blocks > 0x7FFFFFFFLL) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_c_term_transposed, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, st, C, T, O, term, out, ld_out,
+                     static_cast<unsigned>(tiles_o), sq_partials);
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_partials(float* H, const float* partials, int n_split, int64_t stride, int64_t n, bool first,
+                                      hipStream_t st) {
+  const int64_t n4 = n / 4;   // n = O * K is a multiple of 16
+  hipLaunchKernelGGL(k_accumulate_partials, dim3(static_cast<unsigned>((n4 + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads),
+                     0, st, H, partials, n_split, stride, n4, first);
+  return hipGetLastError();
+}
+
+hipError_t launch_sum_doubles(const double* p, int64_t n, double* out, hipStream_t st) {
+  hipLaunchKernelGGL(k_sum_doubles, dim3(1), dim3(kEltThreads), 0, st, p, n, out);
   return hipGetLastError();
 }
 

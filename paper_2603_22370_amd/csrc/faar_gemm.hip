@@ -21,6 +21,8 @@
 //    XCD's L2 sees a compact sub-grid.
 //  * k_gemm_nt (generic fallback for ragged contraction lengths): 128x128 tile, register-staged,
 //    padded LDS, bounds-checked loads.
+#include <algorithm>
+
 #include "faar_internal.h"
 
 namespace faar {
@@ -156,8 +158,28 @@ k_gemm_nt(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d
 
 // ---- epilogues -----------------------------------------------------------------------------
 
-// R = x_scale * acc - C; sum R^2; dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
-struct EpiResidual {
+// fixed-order sum of one float per lane over the workgroup's wavefronts (4 or 8), as a double, to partials[item]
+__device__ __forceinline__ void finish_sum(float sum, double* partials, int item) {
+  __shared__ double s[8];
+  double a = static_cast<double>(sum);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+  if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    const int nw = blockDim.x >> 6;
+    for (int i = 0; i < nw; ++i) t += s[i];
+    partials[item] = t;
+  }
+}
+
+// kWithC:  R = x_scale * acc - C;  sum R^2;  dYt[n][m] = bf16(two_alpha R) (zero-padded to ldt); optional dY[m][n].
+// !kWithC: the V-dependent part alone, for steps that carry the constant part of the gradient separately
+//          (G = dY^T X_q = (2 alpha x_scale acc)^T X_q - 2 alpha C^T X_q):  A = x_scale * acc;  sum A^2;
+//          dYt[n][m] = bf16(two_alpha A).  Nothing is read in the epilogue.
+template <bool kWithC>
+struct EpiResidualT {
   static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
   static constexpr int kMode = 0;               // 0: the whole main loop (1, 2: measurement variants, see EpiProbe)
   const float* C;
@@ -184,7 +206,7 @@ struct EpiResidual {
   // [ceil(M/4)][N][4] (zero outside the matrix); kept separate from value4 so that a whole slab's loads can be
   // issued before the first dependent store
   __device__ __forceinline__ float4 load4(int64_t m, int64_t n, const GemmDims& d) const {
-    if (n < d.N && m < d.M) return *reinterpret_cast<const float4*>(C + ((m >> 2) * d.N + n) * 4);
+    if (kWithC && n < d.N && m < d.M) return *reinterpret_cast<const float4*>(C + ((m >> 2) * d.N + n) * 4);
     return make_float4(0.0f, 0.0f, 0.0f, 0.0f);
   }
   // four consecutive rows m..m+3 of column n -> four bf16 dY values (zero outside the matrix)
@@ -195,10 +217,10 @@ struct EpiResidual {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         if (m + q < d.M) {
-          const float r = xs * acc[q] - c[q];
+          const float r = kWithC ? xs * acc[q] - c[q] : xs * acc[q];
           sum += r * r;
           b[q] = f32_to_bf16(two_alpha * r);
-          if (dY) dY[(m + q) * d.N + n] = static_cast<bf16_t>(b[q]);
+          if (kWithC && dY) dY[(m + q) * d.N + n] = static_cast<bf16_t>(b[q]);
         }
       }
     }
@@ -212,20 +234,39 @@ struct EpiResidual {
     *reinterpret_cast<uint2*>(dYt + n * ldt + m) = value4(acc, load4(m, n, d), m, n, d);
   }
   // fixed-order sum over the workgroup's wavefronts (4 or 8)
-  __device__ __forceinline__ void finish(int item) {
-    __shared__ double s[8];
-    double a = static_cast<double>(sum);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
-    if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = a;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      double t = 0.0;
-      const int nw = blockDim.x >> 6;
-      for (int i = 0; i < nw; ++i) t += s[i];
-      partials[item] = t;
+  __device__ __forceinline__ void finish(int item) { finish_sum(sum, partials, item); }
+};
+typedef EpiResidualT<true> EpiResidual;
+typedef EpiResidualT<false> EpiPerturbation;
+
+// sum of (x_scale * acc)^2 per work item and nothing else: the loss of a step whose dY comes from upstream
+struct EpiSumSq {
+  static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = 0;
+  const float* x_scale;
+  float xs;
+  ForwardGuard guard;
+  double* partials;
+  float sum;
+  __device__ __forceinline__ void once() {
+    if (guard.slot && blockIdx.x == 0 && threadIdx.x == 0) {
+      bool ok = true;
+      for (int i = 0; i < kTagWords; ++i) ok = ok && guard.slot[i] == guard.expect.w[i];
+      for (int i = 0; i < kTagWords; ++i) guard.slot[i] = 0u;
+      guard.slot[kTagWords] = ok ? 1u : 0u;
     }
   }
+  __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
+  __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
+    if (n >= d.N) return;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (m + q < d.M) {
+        const float r = xs * acc[q];
+        sum += r * r;
+      }
+  }
+  __device__ __forceinline__ void finish(int item) { finish_sum(sum, partials, item); }
 };
 
 // out[split][m][n] = acc
@@ -803,7 +844,7 @@ Plan plan_gemm(const GemmDims& d, bool may_split, EpiCost epi) {
   return best;
 }
 
-constexpr EpiCost kEpiResidual{4.0f, 2.0f}, kEpiF32{0.0f, 4.0f}, kEpiSub{4.0f, 4.0f}, kEpiBf16{0.0f, 2.0f};
+constexpr EpiCost kEpiResidual{4.0f, 2.0f}, kEpiF32{0.0f, 4.0f}, kEpiSub{4.0f, 4.0f}, kEpiBf16{0.0f, 2.0f}, kEpiNone{0.0f, 0.0f};
 
 template <class Epi>
 hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hipStream_t st) {
@@ -830,15 +871,30 @@ hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hi
 
 }  // namespace
 
-int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {
-  return plan_gemm(GemmDims{M, N, Kd, Kd, Kd}, false, kEpiResidual).items();
+int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {  // the most any of the three epilogues writes
+  const GemmDims d{M, N, Kd, Kd, Kd};
+  return std::max(plan_gemm(d, false, kEpiResidual).items(),
+                  std::max(plan_gemm(d, false, kEpiBf16).items(), plan_gemm(d, false, kEpiNone).items()));
 }
 
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, hipStream_t st) {
-  EpiResidual e{C, x_scale, 1.0f, guard, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
-  const Plan p = plan_gemm(d, false, kEpiResidual);
+  if (C) {
+    EpiResidual e{C, x_scale, 1.0f, guard, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
+    const Plan p = plan_gemm(d, false, kEpiResidual);
+    *n_partials = p.items();
+    return run(A, B, d, p, e, st);
+  }
+  if (dY) return hipErrorInvalidValue;   // the un-transposed dY exists only with the constant
+  if (dYt) {
+    EpiPerturbation e{nullptr, x_scale, 1.0f, guard, two_alpha, dYt, ldt, nullptr, mse_partials, 0.0f};
+    const Plan p = plan_gemm(d, false, kEpiBf16);
+    *n_partials = p.items();
+    return run(A, B, d, p, e, st);
+  }
+  EpiSumSq e{x_scale, 1.0f, guard, mse_partials, 0.0f};
+  const Plan p = plan_gemm(d, false, kEpiNone);
   *n_partials = p.items();
   return run(A, B, d, p, e, st);
 }
@@ -850,6 +906,7 @@ GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd) {
   const Plan p = epilogue == kGemmEpiResidual ? plan_gemm(d, false, kEpiResidual)
                : epilogue == kGemmEpiF32    ? plan_gemm(d, true, kEpiF32)
                : epilogue == kGemmEpiSub    ? plan_gemm(d, false, kEpiSub)
+               : epilogue == kGemmEpiNone   ? plan_gemm(d, false, kEpiNone)
                                             : plan_gemm(d, false, kEpiBf16);
   const int bm = p.kind == KIND_S || p.kind == KIND_GENERIC ? 128 : 256;
   const int bn = p.kind == KIND_L || p.kind == KIND_L64 ? 256 : 128;

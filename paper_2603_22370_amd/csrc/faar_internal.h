@@ -72,7 +72,8 @@ hipError_t launch_interval_codes(const void* W, bool w_bf16, int64_t n, const fl
 // partial sums of V, one per block (step_bwd_blocks(n) of them).
 hipError_t launch_step_fwd(const void* W, bool w_bf16, int64_t n, const float* s_global, const uint8_t* scales,
                            const uint8_t* icodes, const float* V, float beta, bf16_t* delta, bf16_t* Wq_full,
-                           double* round_partials, uint32_t* guard_slot, hipStream_t st);
+                           double* round_partials, uint32_t* guard_slot, const float* H, double* cross_partials,
+                           hipStream_t st);
 // Step backward + Adam + clip on cached codes.  One more block sums this step's losses (mse_partials from the
 // residual GEMM, round_partials of the V the step started from) into losses[0..2].  beta_next > 0 also emits
 // the next step's forward outputs from the updated V: delta_next (and wq_full_next when not null) and that
@@ -88,6 +89,9 @@ struct StepBwdArgs {
   float beta_next; bf16_t* delta_next; bf16_t* wq_full_next; double* round_next;
   uint32_t* guard_slot;   // verdict of the step's first kernel; a failed check leaves V, m, u alone and gives NaN losses
   ForwardTag next_tag;    // written to the slot when beta_next > 0
+  // Constant part of the gradient carried separately (null: not in use): H = C^T X_q [n]; G -= two_alpha_h * H;
+  // L_mse = mse_scale * (sum mse_partials - 2 x_scale sum cross_partials + *c_norm2); cross_next: <delta_next, H> per block
+  const float* H; float two_alpha_h; const double* cross_partials; const double* c_norm2; double* cross_next;
 };
 hipError_t launch_step_bwd_adam(const StepBwdArgs& a, hipStream_t st);
 // losses[0] = mse_scale * sum(mse_partials), losses[1] = sum(round_partials) / n,
@@ -99,6 +103,15 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
 // out[c * ld_out + r] = in[r * cols + c] for r < rows, c < cols; columns rows..ld_out-1 zeroed.
 hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
                                  int64_t ld_out, hipStream_t st);
+// Term `term` (0 hi, 1 mid, 2 lo) of the float32 C [ceil(T/4)][O][4] as bf16, transposed to [O, ld_out] (ld_out =
+// padded_tokens(T), zero padded); sq_partials (nullable): c_term_blocks(T, O) per-workgroup sums of C^2
+int64_t c_term_blocks(int64_t T, int64_t O);
+hipError_t launch_c_term_transposed(const float* C, int64_t T, int64_t O, int term, bf16_t* out, int64_t ld_out,
+                                    double* sq_partials, hipStream_t st);
+// H[0..n) = (first ? 0 : H) + sum_s partials[s * stride + i]
+hipError_t launch_accumulate_partials(float* H, const float* partials, int n_split, int64_t stride, int64_t n, bool first,
+                                      hipStream_t st);
+hipError_t launch_sum_doubles(const double* p, int64_t n, double* out, hipStream_t st);
 // float32 -> three bf16 terms hi + mid + lo (each the rounding of the running remainder).
 hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
                             hipStream_t st);
@@ -131,6 +144,8 @@ struct GemmDims { int64_t M, N, Kd, lda, ldb; };
 // [ceil(M/4)][N][4], x_scale a device scalar (null = 1); partial sum of R^2 per tile (double);
 // dYt[n][m] = bf16(two_alpha * R) with row stride ldt (rows n < N, columns m < ldt, zero for m >= M);
 // dY (nullable) [M, N] the same values un-transposed.
+// C == nullptr: the V-dependent part alone -- A = x_scale * acc, sum A^2 per tile, dYt = bf16(two_alpha * A) (dY must
+// be null); with dYt == nullptr too, only the sums are produced.
 // guard: when its slot is set, workgroup 0 first compares the stored forward tag with guard.expect (see ForwardTag)
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
@@ -144,7 +159,7 @@ int choose_split(int64_t M, int64_t N, int64_t Kd);
 // The kernel variant, tile shape and contraction split the launchers above pick for an M x N x Kd product
 // (kind: 0 generic, 1 / 2 / 3 the BK = 32 kernels with 256x256 / 256x128 / 128x128 tiles, 4 / 5 the BK = 64
 // kernels with 256x256 / 256x128 tiles).  Pure host function.
-enum { kGemmEpiResidual = 0, kGemmEpiF32 = 1, kGemmEpiSub = 2, kGemmEpiBf16 = 3 };
+enum { kGemmEpiResidual = 0, kGemmEpiF32 = 1, kGemmEpiSub = 2, kGemmEpiBf16 = 3, kGemmEpiNone = 4 };
 struct GemmPlanInfo { int kind, bm, bn, n_split; };
 GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd);
 // C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc   (Y bf16 or float32 row-major; C_out interleaved)

@@ -63,13 +63,20 @@ def test_error_codes_without_a_gpu():
     assert sq(p, 1, 16, 16, p, p, p, float("inf"), p, nul, 0.0, nul, nul, 0, p, 4096, nul) == -6
     assert sq(p, 1, 16, 16, p, p, p, 4.0, p, p, 0.0, nul, nul, 0, p, 4096, nul) == -1         # dWt without dV
     assert sq(p, 1, 16, 16, p, p, p, 4.0, p, p, 0.0, p, nul, 0, p, 1, nul) == -4
-    assert L.faar_layer_prepare(p, 1, 16, 16, p, p, p, nul, p, 1, 0, p, p, p, p, 1 << 20, nul) == -2   # T <= 0
-    assert L.faar_layer_prepare(p, 0, 16, 16, p, p, p, nul, p, 1, 8, p, p, p, nul, 0, nul) == -4       # fp32 W needs ws
-    assert L.faar_layer_prepare(p, 1, 16, 16, p, p, p, nul, p, 1, 8, p, p, nul, p, 1 << 20, nul) == -1 # icodes missing
+    lp = L.faar_layer_prepare
+    assert lp(p, 1, 16, 16, p, p, p, nul, p, 1, 0, p, p, p, nul, nul, p, 1 << 20, nul) == -2   # T <= 0
+    assert lp(p, 0, 16, 16, p, p, p, nul, p, 1, 8, p, p, p, nul, nul, nul, 0, nul) == -4       # fp32 W needs ws
+    assert lp(p, 1, 16, 16, p, p, p, nul, p, 1, 8, p, p, nul, nul, nul, p, 1 << 20, nul) == -1 # icodes missing
+    assert lp(p, 1, 16, 16, p, p, p, nul, p, 1, 8, p, p, p, p, nul, p, 1 << 20, nul) == -1     # H without c_norm2
+    assert lp(p, 1, 16, 16, p, p, p, nul, p, 1, 8, p, p, p, p, p, nul, 0, nul) == -4           # H needs ws
+    assert lp(p, 1, 16, 16, p, p, p, nul, p, 1, 8, p, p, p, p, p, p, 64, nul) == -4
+    assert (fb.faar_workspace_bytes(fb.OP_LAYER_PREPARE, 2048, 2048, 4096, fb.FAAR_WS_GRADIENT_CONSTANT)
+            > fb.faar_workspace_bytes(fb.OP_LAYER_PREPARE, 2048, 2048, 4096))
     opt = fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 1)
     st = L.faar_layer_step
     big = 1 << 30
-    args = lambda **kw: [kw.get("W", p), 1, kw.get("O", 16), 16, p, p, p, p, p, p, nul, p, p, p, kw.get("T", 8),
+    args = lambda **kw: [kw.get("W", p), 1, kw.get("O", 16), 16, p, p, p, p, p, p, nul, p, p, p, kw.get("H", nul),
+                         kw.get("cn", nul), kw.get("T", 8),
                          kw.get("dYe", nul), kw.get("dX", nul), kw.get("beta", 4.0), kw.get("beta_next", 0.0), 0.01, 1.0,
                          ctypes.byref(kw.get("opt", opt)), p, kw.get("flags", 0), p, kw.get("ws", big), nul]
     assert st(*args(W=nul)) == -1
@@ -82,6 +89,8 @@ def test_error_codes_without_a_gpu():
     assert st(*args(opt=fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 0))) == -6
     assert st(*args(ws=16)) == -4
     assert st(*args(O=12, dX=p)) == -2                                                     # chained needs O % 8 == 0
+    assert st(*args(H=p)) == -1                                                            # H and c_norm2 come as a pair
+    assert st(*args(cn=p)) == -1
     s2 = L.faar_stage2_losses
     s2a = lambda **kw: [kw.get("Zf", p), p, 1, kw.get("T", 4), kw.get("V", 64), kw.get("tau", 1.0), 1.0, p, p, 1, kw.get("D", 16), 1.0,
                         kw.get("rl", nul), kw.get("nl", 0), 1.0, 0.0, nul, nul, p, p, kw.get("ws", big), nul]
