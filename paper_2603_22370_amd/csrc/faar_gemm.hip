@@ -532,7 +532,9 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
   if constexpr (Epi::kTransposedOut) {
     // Output is wanted transposed ([n][m], m contiguous) while a lane holds 4 consecutive m of one n: stage
     // one 32-column slab per wavefront column through LDS and write whole 2*BM-byte rows with 16 B per lane.
-    constexpr int LDT = C::BM + 8;          // padded staging row, elements
+    // staging row: BM elements + 4, i.e. a pitch of 2 words more than a multiple of 32: the 16 lanes that write one
+    // 8-byte group of four rows each then fall into 32 distinct LDS banks (a pitch of BM + 8 made rows r and r + 8 collide)
+    constexpr int LDT = C::BM + 4;
     constexpr int ROWS = C::WGN * 32;       // staged n-rows per pass
     constexpr int CPRW = C::BM / 8;         // 16-byte chunks per staged row
     static_assert(ROWS * LDT <= DNS * C::STAGE, "staging buffer fits in the ring");
@@ -558,8 +560,9 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
       __syncthreads();
       for (int idx = tid; idx < ROWS * CPRW; idx += C::THREADS) {
         const int row = idx / CPRW, ch = idx % CPRW;
-        const uint4 v = *reinterpret_cast<const uint4*>(stg + row * LDT + ch * 8);
-        epi.store_chunk(v, m0 + ch * 8, n0 + (row / 32) * C::WN + j * 32 + (row % 32), d);
+        const uint2* src = reinterpret_cast<const uint2*>(stg + row * LDT + ch * 8);   // 8-byte aligned
+        const uint2 lo = src[0], hi = src[1];
+        epi.store_chunk(make_uint4(lo.x, lo.y, hi.x, hi.y), m0 + ch * 8, n0 + (row / 32) * C::WN + j * 32 + (row % 32), d);
       }
     }
   } else {
@@ -735,7 +738,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
   if constexpr (Epi::kTransposedOut) {
     // as in k_gemm_dma: stage a 32-column slab (two 16-column tiles) per wavefront column through LDS and
     // write whole rows of the transposed output with 16 B per lane
-    constexpr int LDT = C::BM + 8;
+    constexpr int LDT = C::BM + 4;          // pitch of 2 words beyond a multiple of 32: conflict-free 8-byte writes
     constexpr int ROWS = C::WGN * 32;
     constexpr int CPRW = C::BM / 8;
     static_assert(ROWS * LDT <= C::NS * C::STAGE, "staging buffer fits in the ring");
@@ -762,8 +765,9 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       __syncthreads();
       for (int idx = tid; idx < ROWS * CPRW; idx += C::THREADS) {
         const int row = idx / CPRW, ch = idx % CPRW;
-        const uint4 v = *reinterpret_cast<const uint4*>(stg + row * LDT + ch * 8);
-        epi.store_chunk(v, m0 + ch * 8, n0 + (row / 32) * C::WN + jj * 32 + (row % 32), d);
+        const uint2* src = reinterpret_cast<const uint2*>(stg + row * LDT + ch * 8);   // 8-byte aligned
+        const uint2 lo = src[0], hi = src[1];
+        epi.store_chunk(make_uint4(lo.x, lo.y, hi.x, hi.y), m0 + ch * 8, n0 + (row / 32) * C::WN + jj * 32 + (row % 32), d);
       }
     }
   } else {
