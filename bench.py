@@ -11,7 +11,8 @@ dW GEMM, dV + Round Loss + Adam + clip; beta annealed 4 -> 32), then faar_harden
 command line is one optimisation step of every linear; value = 7 K / elapsed (linear-layer steps / s).
 
 Other workloads (--workload): one linear of the Llama3-1B- / Qwen3-1.7B- / Llama3-8B-shaped blocks by name;
-qwen_block_chained (the seven linears at 16384 tokens with dY supplied and dX produced); qwen_pack_sweep
+qwen_block_chained (the seven linears at 16384 tokens with dY supplied and dX produced); qwen_mlp_joint (one joint
+step of the MLP half of the block: norm, three linears, gate, residual, block-output loss, and back); qwen_pack_sweep
 (quantise / initialise / harden+pack all 196 weight tensors of the model); stage2_losses; gemm_ceiling (what
 bounds the GEMM main loop: the loop with only its matrix instructions, with only its copies, and whole, with the
 clock the compute units ran at).
@@ -612,6 +613,134 @@ def run_block_chained(args) -> dict:
     return out
 
 
+def run_mlp_joint(args) -> dict:
+    """One joint step of the MLP half of a Qwen3-1.7B-shaped block at T = 16384: RMSNorm, gate / up projections,
+    SiLU * up, down projection, residual and block-output MSE forward; then the gradient back through all of it into
+    the rounding variables of the three linears (one Adam update each) and into the block's input.  Nine GEMMs per
+    step.  `value` counts linear-layer steps (three per block step)."""
+    import numpy as np
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+    from workloads import synth
+
+    T, D, F = 16384, 2048, 6144
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    beta, eps, ms_scale = 16.0, 1e-6, 1.0 / (T * D)
+    shapes = (("gate", F, D), ("up", F, D), ("down", D, F))
+    x_h = synth.activations(T, D, 31)
+    x = torch.from_numpy(x_h).cuda().to(torch.bfloat16)
+    g = torch.ones(D, dtype=torch.float32, device="cuda")
+    lin = {}
+    for i, (n, O, K) in enumerate(shapes):
+        W = torch.from_numpy(synth.weights(O, K, 40 + i)).cuda().to(torch.bfloat16)
+        sg, sc, _, _ = faar.faar_quant_rtn(W)
+        V = faar.faar_init_v(W, sg, sc)
+        X0 = torch.zeros((T, K), dtype=torch.bfloat16, device="cuda")
+        Xt, _, ic = faar.faar_layer_prepare(W, sg, sc, X0, None)          # only the node codes depend on W alone
+        lin[n] = dict(W=W, sg=sg, sc=sc, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=Xt, ic=ic, O=O, K=K, t=0,
+                      losses=torch.zeros(3, dtype=torch.float32, device="cuda"),
+                      ws=faar.layer_step_workspace(O, K, T, chained=True), fws=fb._workspace(fb.OP_LINEAR_FORWARD, O, K, T, device="cuda"),
+                      Y=torch.empty((T, O), dtype=torch.bfloat16, device="cuda"),
+                      dX=torch.empty((T, K), dtype=torch.bfloat16, device="cuda"))
+        del X0
+    # the full-precision block's output: the same MLP with the unquantised weights, computed once with library GEMMs
+    with torch.no_grad():
+        xf = x.float()
+        hf = (xf * torch.rsqrt((xf * xf).mean(-1, keepdim=True) + eps)).to(torch.bfloat16)
+        pf, qf = hf @ lin["gate"]["W"].T, hf @ lin["up"]["W"].T
+        y_fp = (xf + ((torch.nn.functional.silu(pf.float()) * qf.float()).to(torch.bfloat16) @ lin["down"]["W"].T).float()).to(torch.bfloat16)
+        del xf, hf, pf, qf
+    state = {"loss": None}
+
+    def fwd(n, X):
+        L = lin[n]
+        return faar.faar_linear_forward(L["W"], L["sg"], L["sc"], L["V"], beta, X, ws=L["fws"], out=L["Y"])
+
+    def back(n, X, dY):
+        L = lin[n]
+        L["t"] += 1
+        faar.faar_layer_step(L["W"], L["sg"], L["sc"], L["V"], L["m"], L["u"], X, L["Xt"], None, L["ic"], beta, LAM, 0.0, LR,
+                             0.9, 0.999, 1e-8, L["t"], L["losses"], L["ws"], dY_ext=dY, dX=L["dX"], joint=True)
+        return L["dX"]
+
+    def block_step():
+        h, rstd = faar.faar_rmsnorm_fwd(x, g, eps)
+        p, q = fwd("gate", h), fwd("up", h)
+        a = faar.faar_silu_mul_fwd(p, q)
+        d = fwd("down", a)
+        state["loss"], dy, _ = faar.faar_block_output_loss(x, d, y_fp, ms_scale)
+        da = back("down", a, dy)
+        dp, dq = faar.faar_silu_mul_bwd(da, p, q)
+        dh1, dh2 = back("gate", h, dp), back("up", h, dq)
+        return faar.faar_rmsnorm_bwd(dh1, x, g, rstd, dh2=dh2, d_res=dy)
+
+    for _ in range(warmup):
+        block_step()
+    torch.cuda.synchronize()
+    first_loss = float(state["loss"].item())
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        block_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    timer = KernelTimer()
+    kernels = {}
+    flops = 2.0 * T * F * D
+    for kname, kid in [("gemm_fwd", fb.K_GEMM_FWD), ("gemm_dw", fb.K_GEMM_DW), ("gemm_dx", fb.K_GEMM_DX), ("bwd_adam", fb.K_BWD_ADAM)]:
+        # three launches of each per block step, of equal size; the events keep the last one (down_proj's forward GEMM,
+        # up_proj's backward kernels)
+        ms = timer.time(kid, lambda i: block_step(), 4)
+        if kname.startswith("gemm"):
+            kernels[kname] = {"ms": round(ms, 5), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                              "frac": round(flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)}
+        else:
+            kernels[kname] = {"ms": round(ms, 5)}
+    dom_k = max((k for k in kernels if k.startswith("gemm")), key=lambda k: kernels[k]["ms"])
+    dom = kernels[dom_k]
+    gemm_ms = 3 * sum(kernels[k]["ms"] for k in kernels if k.startswith("gemm"))
+    out = {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(3 * steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qwen_mlp_joint: the MLP half of one Qwen3-1.7B-shaped block (RMSNorm, gate/up 6144x2048, SiLU*, "
+                               "down 2048x6144, residual, block-output MSE), T 16384, one joint step = forward + backward + Adam "
+                               "on the rounding variables of all three linears (9 GEMMs); value = linear-layer steps/s",
+                   "T": T, "D": D, "F": F, "linears": 3},
+        "block_step_gemm_tflops": round(9 * flops / (elapsed / steps) / 1e12, 1),
+        "gemm_share_of_step": round(gemm_ms / (elapsed / steps * 1e3), 3),
+        "block_loss": {"after_warmup": first_loss, "at_end": float(state["loss"].item())},
+        "roofline": {"kernel": dom_k, "bound": "mfma", "achieved": dom["tflops"], "peak": BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "launch_ms": dom["ms"]},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        # the oracle's joint step at two small token counts; its cost is linear in T (a part per weight plus a part per
+        # token), extrapolated to T = 16384 and labelled so
+        from oracle import block_oracle as bo
+        from oracle import faar_oracle as fo
+        layers = {}
+        for n in lin:
+            W_h = lin[n]["W"].float().cpu().numpy()
+            qh = fo.quant_rtn(W_h, True)
+            layers[n] = (W_h, qh["s_global"], qh["scales"], fo.init_v(W_h, qh["s_global"], qh["scales"])["V"])
+        times = {}
+        for Ts in (256, 512):
+            xs, ys = x_h[:Ts].astype(np.float64), y_fp[:Ts].float().cpu().numpy()
+            c0 = time.perf_counter()
+            bo.mlp_block_step(xs, np.ones(D), eps, layers, ys, 1.0 / (Ts * D), beta, LAM, bf16_storage=True)
+            times[Ts] = time.perf_counter() - c0
+        per_tok = max(times[512] - times[256], 0.0) / 256
+        t_full = times[256] + per_tok * (T - 256)
+        out["cpu_baseline"] = {"value": round(3 / t_full, 5), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"joint MLP step of the oracle (gradients only, no Adam) at T 256 ({times[256]:.1f} s) and T 512 "
+                                         f"({times[512]:.1f} s), extrapolated linearly in T to 16384 ({t_full:.0f} s per block step)",
+                               **host_description()}
+    return out
+
+
 def run_pack_sweep(args) -> dict:
     """Set-up and tear-down over every linear of a Qwen3-1.7B-shaped model (28 layers x 7 linears, 1.409 G weights,
     each tensor in memory of its own): quantisation, V initialisation and hardening + packing, each as ONE batched call
@@ -840,7 +969,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_layer",
-                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
+                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_mlp_joint", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
@@ -862,7 +991,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_pack_sweep": run_pack_sweep,
+    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_mlp_joint": run_mlp_joint,
+               "qwen_pack_sweep": run_pack_sweep,
                "stage2_losses": run_stage2, "gemm_ceiling": run_gemm_ceiling}
     out = runners.get(args.workload, run_linear)(args)
     print(json.dumps(out))

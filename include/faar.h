@@ -61,6 +61,7 @@ enum {
                                    step that takes dY_ext and/or produces dX */
   FAAR_WS_FORWARD_READY = 1u << 3, /* faar_layer_step: the workspace already holds this step's soft-quantised
                                    weights, left there by the previous step (its beta_next) */
+  FAAR_STEP_JOINT = 1u << 6,    /* faar_layer_step: the layer is one link of a jointly optimised chain (see there) */
   FAAR_WS_GRADIENT_CONSTANT = 1u << 5, /* faar_workspace_bytes(FAAR_OP_LAYER_PREPARE): size the workspace for a call that
                                    also produces H and c_norm2 */
   FAAR_DQ_IN_UNITS = 1u << 4    /* faar_quant_rtn: W_dq receives sign * node * E4M3 scale, i.e. the dequantised
@@ -77,7 +78,9 @@ enum {
   FAAR_OP_LAYER_STEP = 4,
   FAAR_OP_HARDEN_PACK = 5,
   FAAR_OP_STAGE2_LOSSES = 6, /* faar_workspace_bytes(op, O = vocabulary, K = hidden size, T = tokens, 0) */
-  FAAR_OP_QUANT_RTN_BATCH = 7 /* independent of the tensors: pass any valid O, K (e.g. 16, 16) */
+  FAAR_OP_QUANT_RTN_BATCH = 7, /* independent of the tensors: pass any valid O, K (e.g. 16, 16) */
+  FAAR_OP_LINEAR_FORWARD = 8,
+  FAAR_OP_BLOCK_OUTPUT_LOSS = 9 /* faar_workspace_bytes(op, O = D (row length), K = 16, T = rows, 0) */
 };
 
 /* kernels of the path, for faar_time_kernel */
@@ -92,7 +95,8 @@ enum {
   FAAR_K_INIT_V = 7,
   FAAR_K_HARDEN_PACK = 8,
   FAAR_K_STAGE2_KL = 9,      /* the three launches of faar_stage2_losses, bracketed together */
-  FAAR_K_GEMM_C = 10         /* Y_fp - X_q W^T of faar_layer_prepare (faar_gemm_plan only: it has no time bracket) */
+  FAAR_K_GEMM_C = 10,        /* Y_fp - X_q W^T of faar_layer_prepare (faar_gemm_plan only: it has no time bracket) */
+  FAAR_K_GEMM_FWD = 11       /* X_q W_q^T of faar_linear_forward */
 };
 
 /* GEMM kernel variants, as reported by faar_gemm_plan */
@@ -128,7 +132,8 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T);
 
 /* Which kernel variant, output tile and contraction split the library uses for one of the GEMMs of a layer of
  * these sizes: which = FAAR_K_GEMM_RESIDUAL (T x O x K), FAAR_K_GEMM_DW (O x K x padded T; the only one that may
- * split its contraction), FAAR_K_GEMM_DX (T x K x O) or FAAR_K_GEMM_C (T x O x K, in faar_layer_prepare).
+ * split its contraction), FAAR_K_GEMM_DX (T x K x O), FAAR_K_GEMM_C (T x O x K, in faar_layer_prepare) or FAAR_K_GEMM_FWD (T x O x K, in
+ * faar_linear_forward).
  * out[0..3] = variant (FAAR_GEMM_*), tile rows, tile columns, contraction splits.  Pure host function; lets tests
  * prove that their cases reach every variant. */
 int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out);
@@ -258,7 +263,8 @@ int faar_softquant_fwd_bwd_static(const void* W, faar_dtype wdt, int64_t O, int6
  *   Xq   in bf16[T*K]   -- the activations fed to the quantised path (X_q of Sec. 3.4), in units of
  *   x_scale in, nullable device float[1] (NULL = 1): X_q = x_scale * Xq.  NVFP4-quantised activations are
  *        passed exactly as Xq = node * block scale (bf16-exact) and x_scale = their tensor scale.
- *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T
+ *   Y_fp in [T*O] of dtype ydt -- the frozen full-precision layer output X W^T.  Y_fp and C may both be NULL (a layer
+ *        that is only stepped jointly, FAAR_STEP_JOINT): then only Xt and icodes are produced
  *   ws   FAAR_OP_LAYER_PREPARE workspace (queried with FAAR_WS_GRADIENT_CONSTANT when H is wanted; needed for a
  *        float32 W or with H)
  */
@@ -303,7 +309,13 @@ typedef struct {
  *                       evaluates Eq. 2-3 on the updated V at beta_next and leaves W_q - W (and W_q when dX
  *                       is requested) with that V's Round-Loss partial sums in ws, saving the next step
  *                       its forward kernel.  Same arithmetic, same results bit for bit.
- *   flags               FAAR_WS_CHAINED is accepted and has no effect on the computation.
+ *   flags               FAAR_STEP_JOINT: a joint (Stage-2-style) step -- Table 2 steps 15-17 and 23: the loss is computed
+ *                       downstream of the layer (faar_block_output_loss, faar_stage2_losses) and arrives as dY_ext, which
+ *                       is required; the layer's own reconstruction loss is not evaluated (losses[0] = 0, no residual GEMM;
+ *                       C may be NULL, H must be).  The activations Xq are the quantised model's own and change with
+ *                       every step: the call writes their transpose into Xt itself (Xt is then scratch of
+ *                       K * faar_padded_tokens(T) bf16, not an input).  dX is normally requested.
+ *                       FAAR_WS_CHAINED is accepted and has no effect on the computation.
  *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  That is valid
  *                       when the previous call on this ws was step opt->t - 1 of the same layer (same W, scales,
  *                       V, shapes, dX requested or not) with beta_next equal to this call's beta, and neither V
@@ -395,6 +407,52 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                        const float* s_global, const uint8_t* scales, const float* V,
                        const void* Xq, const float* x_scale, const float* C, int64_t T,
                        float mse_scale, float* loss, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The operations between the quantised linears of a transformer block, for joint steps -- Sec. 3.5 "Stage 2", Table 2
+ * steps 15-17 and 23: the assembled quantised model runs forward and ONE loss is back-propagated into every layer's V.
+ * The paper evaluates Llama3 / Qwen3 models; these are the parts of their blocks around the MLP's three linears
+ * (pre-norm RMSNorm, gated SiLU, residual connection) and the squared error of the block output, the block-level
+ * form of Eq. 6's hidden-state term.  Activations and gradients between kernels are bf16 [rows * row length],
+ * row-major; arithmetic is float32.  A joint step of the MLP half of a block is then
+ *
+ *   h = faar_rmsnorm_fwd(x1);  p = faar_linear_forward(gate, h);  q = faar_linear_forward(up, h);
+ *   a = faar_silu_mul_fwd(p, q);  d = faar_linear_forward(down, a);  (L, dy) = faar_block_output_loss(x1, d, y_fp)
+ *   da = dX of faar_layer_step(down, Xq = a, dY_ext = dy, FAAR_STEP_JOINT);  (dp, dq) = faar_silu_mul_bwd(da, p, q)
+ *   dh1 = dX of faar_layer_step(gate, Xq = h, dY_ext = dp, ...);  dh2 = dX of faar_layer_step(up, Xq = h, dY_ext = dq, ...)
+ *   dx1 = faar_rmsnorm_bwd(dh1, dh2, x1, d_res = dy)
+ *
+ * (the attention half -- rotary embedding and the attention core -- is not part of this library yet).
+ */
+
+/* Y = x_scale * Xq W_q(V)^T in bf16 [T*O]: the soft-quantised linear of Eq. 2-3 applied to activations [T*K] (bf16).
+ * W_q is rounded to bf16 for the matrix cores, as a bf16 model's fake-quantised forward does.  ws: FAAR_OP_LINEAR_FORWARD. */
+int faar_linear_forward(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global, const uint8_t* scales,
+                        const float* V, float beta, const void* Xq, const float* x_scale, int64_t T, void* Y,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* h[t, i] = x[t, i] g[i] rstd[t],  rstd[t] = 1 / sqrt(mean_i x[t, i]^2 + eps).
+ *   x in [T*D] of dtype xdt; g in float[D]; h out bf16 [T*D]; rstd out float[T] (kept for the backward).  D % 8 == 0. */
+int faar_rmsnorm_fwd(const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g, float eps, void* h, float* rstd,
+                     void* stream);
+
+/* dx = rstd g dh - x rstd^3 / D * sum_i (x g dh) + d_res  with dh = dh1 + dh2 (g is frozen: no gradient for it).
+ *   dh1 in bf16 [T*D]; dh2 in, nullable (a second consumer of h, e.g. the up projection next to the gate projection);
+ *   d_res in, nullable bf16 [T*D]: the gradient arriving over the residual connection; dx out bf16 [T*D]. */
+int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g,
+                     const float* rstd, const void* d_res, void* dx, void* stream);
+
+/* a = SiLU(p) q = p sigmoid(p) q, all bf16 [n], n % 8 == 0 */
+int faar_silu_mul_fwd(const void* p, const void* q, int64_t n, void* a, void* stream);
+
+/* dp = da q s (1 + p (1 - s)),  dq = da p s,  s = sigmoid(p); all bf16 [n] */
+int faar_silu_mul_bwd(const void* da, const void* p, const void* q, int64_t n, void* dp, void* dq, void* stream);
+
+/* y = x + d (residual connection);  loss = mse_scale * ||y - y_fp||_F^2;  dy = 2 mse_scale (y - y_fp)  (bf16).
+ *   x in [T*D] of dtype xdt (the block's input stream); d in bf16 [T*D] (the MLP's output); y_fp in [T*D] of dtype ydt
+ *   (the full-precision block output); y out, nullable bf16; dy out bf16; loss out float[1]; ws: FAAR_OP_BLOCK_OUTPUT_LOSS */
+int faar_block_output_loss(const void* x, faar_dtype xdt, const void* d, const void* y_fp, faar_dtype ydt, int64_t T, int64_t D,
+                           float mse_scale, void* y, void* dy, float* loss, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * The Stage-2 objective evaluated on given outputs of the two models -- Sec. 3.5 "Stage 2", Eq. 6,

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libfaar.so")
 FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
 FAAR_WS_GRADIENT_CONSTANT = 32
-OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH = range(8)
+FAAR_STEP_JOINT = 64
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS = range(10)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
 
@@ -90,6 +91,21 @@ def lib() -> ctypes.CDLL:
                                       c_int64, c_void_p, c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_linear_forward.restype = c_int
+        L.faar_linear_forward.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float, c_void_p,
+                                          c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_rmsnorm_fwd.restype = c_int
+        L.faar_rmsnorm_fwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_float, c_void_p, c_void_p, c_void_p]
+        L.faar_rmsnorm_bwd.restype = c_int
+        L.faar_rmsnorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
+                                       c_void_p, c_void_p]
+        L.faar_silu_mul_fwd.restype = c_int
+        L.faar_silu_mul_fwd.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
+        L.faar_silu_mul_bwd.restype = c_int
+        L.faar_silu_mul_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p]
+        L.faar_block_output_loss.restype = c_int
+        L.faar_block_output_loss.argtypes = [c_void_p, c_int, c_void_p, c_void_p, c_int, c_int64, c_int64, c_float, c_void_p,
+                                             c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
         L.faar_stochastic_v.restype = c_int
         L.faar_stochastic_v.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, ctypes.c_ulonglong, c_uint32,
                                         c_void_p, c_void_p]
@@ -150,7 +166,7 @@ def faar_dw_split(O: int, K: int, T: int) -> int:
     return int(lib().faar_dw_split(O, K, T))
 
 
-K_GEMM_C = 10
+K_GEMM_C, K_GEMM_FWD = 10, 11
 GEMM_KINDS = ("generic", "L", "M", "S", "L64", "M64")
 
 
@@ -287,17 +303,19 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None, gra
     _dev(W, s_global, scales, Xq, Y_fp, ws, x_scale)
     O, K = W.shape
     T = Xq.shape[0]
-    if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or tuple(Y_fp.shape) != (T, O):
+    if Xq.dtype != torch.bfloat16 or Xq.shape[1] != K or (Y_fp is not None and tuple(Y_fp.shape) != (T, O)):
         raise ValueError("Xq must be bf16 [T,K]; Y_fp must be [T,O]")
     Xt = torch.empty((K, faar_padded_tokens(T)), dtype=torch.bfloat16, device=W.device)
-    C = torch.empty(((T + 3) // 4, O, 4), dtype=torch.float32, device=W.device)   # row groups of 4 interleaved
+    # row groups of 4 interleaved; none without a reference output (a layer that is only stepped jointly)
+    C = torch.empty(((T + 3) // 4, O, 4), dtype=torch.float32, device=W.device) if Y_fp is not None else None
     icodes = torch.empty((O, K // 2), dtype=torch.uint8, device=W.device)
     H = torch.empty((O, K), dtype=torch.float32, device=W.device) if gradient_constant else None
     cn = torch.empty(1, dtype=torch.float64, device=W.device) if gradient_constant else None
     flags = FAAR_WS_GRADIENT_CONSTANT if gradient_constant else 0
     ws = _workspace(OP_LAYER_PREPARE, O, K, T, flags, device=W.device) if ws is None else ws
     _check(lib().faar_layer_prepare(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(Xq), _ptr(x_scale),
-                                    _ptr(Y_fp), _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(H), _ptr(cn), _ptr(ws),
+                                    _ptr(Y_fp), FAAR_BF16 if Y_fp is None else _dt(Y_fp), T, _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(H),
+                                    _ptr(cn), _ptr(ws),
                                     ws.numel(), _stream()),
            "faar_layer_prepare")
     return (Xt, C, icodes, H, cn) if gradient_constant else (Xt, C, icodes)
@@ -305,10 +323,11 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None, gra
 
 def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
                     lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False,
-                    x_scale=None, H=None, c_norm2=None):
+                    x_scale=None, H=None, c_norm2=None, joint=False):
     """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L).
     beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them.
-    H, c_norm2: the gradient constant of faar_layer_prepare(gradient_constant=True), or None."""
+    H, c_norm2: the gradient constant of faar_layer_prepare(gradient_constant=True), or None.
+    joint: a Stage-2-style step (dY_ext required; no local loss; Xt is rewritten from Xq; C may be None)."""
     _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX, x_scale, H, c_norm2)
     O, K = W.shape
     T = Xq.shape[0]
@@ -317,7 +336,8 @@ def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, b
                                  _ptr(adam_v), _ptr(Xq), _ptr(x_scale), _ptr(Xt), _ptr(C), _ptr(icodes), _ptr(H),
                                  _ptr(c_norm2), T, _ptr(dY_ext), _ptr(dX),
                                  float(beta), float(beta_next), float(lambda_round), float(mse_scale),
-                                 ctypes.byref(opt), _ptr(losses), FAAR_WS_FORWARD_READY if forward_ready else 0,
+                                 ctypes.byref(opt), _ptr(losses),
+                                 (FAAR_WS_FORWARD_READY if forward_ready else 0) | (FAAR_STEP_JOINT if joint else 0),
                                  _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
 
 
@@ -356,6 +376,65 @@ def faar_stage2_losses(Z_fp, Z_q, tau, H_fp, H_q, kl_scale=1.0, mse_scale=1.0, r
                                     float(lambda_kl), float(lambda_round), _ptr(dZ), _ptr(dH), _ptr(losses), _ptr(ws),
                                     ws.numel(), _stream()), "faar_stage2_losses")
     return losses, dZ, dH
+
+
+def faar_linear_forward(W, s_global, scales, V, beta, Xq, x_scale=None, ws=None, out=None):
+    """-> Y bf16 [T, O] = x_scale * Xq W_q(V)^T."""
+    _dev(W, s_global, scales, V, Xq, x_scale, ws, out)
+    O, K = W.shape
+    T = Xq.shape[0]
+    Y = torch.empty((T, O), dtype=torch.bfloat16, device=W.device) if out is None else out
+    ws = _workspace(OP_LINEAR_FORWARD, O, K, T, device=W.device) if ws is None else ws
+    _check(lib().faar_linear_forward(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), float(beta), _ptr(Xq),
+                                     _ptr(x_scale), T, _ptr(Y), _ptr(ws), ws.numel(), _stream()), "faar_linear_forward")
+    return Y
+
+
+def faar_rmsnorm_fwd(x, g, eps):
+    """-> (h bf16 [T, D], rstd f32 [T])."""
+    _dev(x, g)
+    T, D = x.shape
+    h = torch.empty((T, D), dtype=torch.bfloat16, device=x.device)
+    rstd = torch.empty(T, dtype=torch.float32, device=x.device)
+    _check(lib().faar_rmsnorm_fwd(_ptr(x), _dt(x), T, D, _ptr(g), float(eps), _ptr(h), _ptr(rstd), _stream()), "faar_rmsnorm_fwd")
+    return h, rstd
+
+
+def faar_rmsnorm_bwd(dh1, x, g, rstd, dh2=None, d_res=None):
+    """-> dx bf16 [T, D]."""
+    _dev(dh1, dh2, x, g, rstd, d_res)
+    T, D = x.shape
+    dx = torch.empty((T, D), dtype=torch.bfloat16, device=x.device)
+    _check(lib().faar_rmsnorm_bwd(_ptr(dh1), _ptr(dh2), _ptr(x), _dt(x), T, D, _ptr(g), _ptr(rstd), _ptr(d_res), _ptr(dx),
+                                  _stream()), "faar_rmsnorm_bwd")
+    return dx
+
+
+def faar_silu_mul_fwd(p, q):
+    _dev(p, q)
+    a = torch.empty_like(p)
+    _check(lib().faar_silu_mul_fwd(_ptr(p), _ptr(q), p.numel(), _ptr(a), _stream()), "faar_silu_mul_fwd")
+    return a
+
+
+def faar_silu_mul_bwd(da, p, q):
+    _dev(da, p, q)
+    dp, dq = torch.empty_like(p), torch.empty_like(q)
+    _check(lib().faar_silu_mul_bwd(_ptr(da), _ptr(p), _ptr(q), p.numel(), _ptr(dp), _ptr(dq), _stream()), "faar_silu_mul_bwd")
+    return dp, dq
+
+
+def faar_block_output_loss(x, d, y_fp, mse_scale, want_y=False, ws=None):
+    """-> (loss f32[1], dy bf16 [T, D], y bf16 or None)."""
+    _dev(x, d, y_fp, ws)
+    T, D = x.shape
+    dy = torch.empty((T, D), dtype=torch.bfloat16, device=x.device)
+    y = torch.empty((T, D), dtype=torch.bfloat16, device=x.device) if want_y else None
+    loss = torch.empty(1, dtype=torch.float32, device=x.device)
+    ws = _workspace(OP_BLOCK_OUTPUT_LOSS, D, 16, T, device=x.device) if ws is None else ws
+    _check(lib().faar_block_output_loss(_ptr(x), _dt(x), _ptr(d), _ptr(y_fp), _dt(y_fp), T, D, float(mse_scale), _ptr(y), _ptr(dy),
+                                        _ptr(loss), _ptr(ws), ws.numel(), _stream()), "faar_block_output_loss")
+    return loss, dy, y
 
 
 def faar_stochastic_v(W, s_global, scales, seed, sample):

@@ -176,7 +176,7 @@ int faar_version(void) { return 100; }
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
-  if (which < FAAR_K_NONE || which > FAAR_K_STAGE2_KL) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
+  if (which < FAAR_K_NONE || which > FAAR_K_GEMM_FWD || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
   g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
   return FAAR_OK;
@@ -217,6 +217,7 @@ int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out) {
     case FAAR_K_GEMM_DW: p = gemm_plan_info(kGemmEpiF32, O, K, padded_tokens(T)); break;
     case FAAR_K_GEMM_DX: p = gemm_plan_info(kGemmEpiBf16, T, K, O); break;
     case FAAR_K_GEMM_C: p = gemm_plan_info(kGemmEpiSub, T, O, K); break;
+    case FAAR_K_GEMM_FWD: p = gemm_plan_info(kGemmEpiBf16, T, O, K); break;
     default: return FAAR_E_ARG;
   }
   out[0] = p.kind; out[1] = p.bm; out[2] = p.bn; out[3] = p.n_split;
@@ -232,6 +233,11 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
   switch (op) {
     case FAAR_OP_QUANT_RTN:
       return align256(kAmaxPartials * sizeof(float));
+    case FAAR_OP_LINEAR_FORWARD:
+      return align256((size_t)O * K * 2);   // W_q in bf16
+    case FAAR_OP_BLOCK_OUTPUT_LOSS:         // O = D (row length), T rows
+      if (T <= 0 || O % 8 != 0) return 0;
+      return align256((size_t)block_loss_blocks(T * O) * sizeof(double));
     case FAAR_OP_QUANT_RTN_BATCH:   // whatever the number and sizes of the tensors: launches reuse it in stream order
       return align256((size_t)kBatchMax * kBatchAmaxBlocks * sizeof(float));
     case FAAR_OP_INIT_V:
@@ -364,7 +370,9 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
                        const uint8_t* scales, const void* Xq, const float* x_scale, const void* Y_fp, faar_dtype ydt,
                        int64_t T, void* Xt, float* C, uint8_t* icodes, float* H, double* c_norm2, void* ws, size_t ws_bytes,
                        void* stream) {
-  if (!W || !s_global || !scales || !Xq || !Y_fp || !Xt || !C || !icodes) return FAAR_E_NULL;
+  if (!W || !s_global || !scales || !Xq || !Xt || !icodes) return FAAR_E_NULL;
+  if ((Y_fp != nullptr) != (C != nullptr)) return FAAR_E_NULL;   // no reference output: only Xt and the interval codes
+  if (!Y_fp && H) return FAAR_E_NULL;
   if ((H != nullptr) != (c_norm2 != nullptr)) return FAAR_E_NULL;
   if (!aligned16(H) || (reinterpret_cast<uintptr_t>(c_norm2) & 7u)) return FAAR_E_ARG;
   if (int e = check_wdt(wdt)) return e;
@@ -374,7 +382,7 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   if (!aligned16(W) || !aligned16(Xq) || !aligned16(Y_fp) || !aligned16(Xt) || !aligned16(C) || !aligned16(icodes))
     return FAAR_E_ARG;
   const bool bf = wdt == FAAR_BF16;
-  if ((!bf || H) &&
+  if (((!bf && Y_fp) || H) &&
       (!ws || !aligned16(ws) || ws_bytes < faar_workspace_bytes(FAAR_OP_LAYER_PREPARE, O, K, T, H ? FAAR_WS_GRADIENT_CONSTANT : 0)))
     return FAAR_E_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -382,6 +390,7 @@ int faar_layer_prepare(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   const int64_t Tp = padded_tokens(T);
   if (int e = hip_status(launch_interval_codes(W, bf, O * K, s_global, scales, icodes, st))) return e;
   if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(Xt), Tp, st))) return e;
+  if (!Y_fp) return FAAR_OK;
   const GemmDims d{T, O, K, K, K};
   if (bf) {
     if (int e = hip_status(launch_gemm_sub(xq, static_cast<const bf16_t*>(W), d, Y_fp, ydt == FAAR_BF16, true, C, x_scale, st)))
@@ -418,8 +427,10 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
                     int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream) {
-  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || !C || !icodes || !opt || !losses)
+  const bool joint = (flags & FAAR_STEP_JOINT) != 0;
+  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !Xq || !Xt || (!C && !joint) || !icodes || !opt || !losses)
     return FAAR_E_NULL;
+  if (joint && (!dY_ext || H)) return FAAR_E_ARG;   // the loss lives outside the layer: its gradient must be given
   if ((H != nullptr) != (c_norm2 != nullptr)) return FAAR_E_NULL;
   if (!aligned16(H) || (reinterpret_cast<uintptr_t>(c_norm2) & 7u)) return FAAR_E_ARG;
   if (int e = check_wdt(wdt)) return e;
@@ -427,7 +438,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
   const bool chained = dY_ext || dX;
   if (chained && O % 8 != 0) return FAAR_E_SHAPE;
-  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY)) return FAAR_E_ARG;
+  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY | FAAR_STEP_JOINT)) return FAAR_E_ARG;
   if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
     return FAAR_E_ARG;
   if (!(beta_next >= 0.0f) || !std::isfinite(beta_next)) return FAAR_E_ARG;
@@ -475,11 +486,17 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     guard.slot = guard_slot;
     guard.expect = forward_tag(opt->t, beta, V, W, scales, n, wq_full != nullptr, Hs);
   }
-  // s2: residual GEMM + loss + dY
+  // s2: residual GEMM + loss + dY -- not in a joint step, whose loss is computed downstream of the layer; there the
+  // activations change from step to step, so their transpose for the dW GEMM is refreshed here
   int64_t n_mse = 0;
   const GemmDims d1{T, O, K, K, K};
   const bool need_local_dY = dX && !dY_ext;
-  {
+  if (joint) {
+    if (flags & FAAR_WS_FORWARD_READY) {   // nobody else consumes the tag: check it in a kernel of its own
+      if (int e = hip_status(launch_check_forward_tag(guard, st))) return e;
+    }
+    if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(const_cast<void*>(Xt)), L.Tp, st))) return e;
+  } else {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
     // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
     if (int e = hip_status(launch_gemm_residual(xq, delta, d1, Hs ? nullptr : C, x_scale, 2.0f * mse_scale,
@@ -503,7 +520,7 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     if (int e = hip_status(launch_transpose_bf16(wq_full, O, K, wqt, L.Op, st))) return e;
     const GemmDims d3{T, K, O, O, L.Op};
     Bracket b(FAAR_K_GEMM_DX, st);
-    if (int e = hip_status(launch_gemm_bf16(dY_used, wqt, d3, static_cast<bf16_t*>(dX), st))) return e;
+    if (int e = hip_status(launch_gemm_bf16(dY_used, wqt, d3, static_cast<bf16_t*>(dX), nullptr, st))) return e;
   }
   // s5 + s6: dV, Adam, clip; the same launch sums the losses (both kinds of partials are complete by now:
   // they come from earlier kernels) and, when asked, runs s1 of the next step on the updated V
@@ -524,6 +541,87 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.cross_partials = cross_p; a.c_norm2 = c_norm2; a.cross_next = cross_next;
   Bracket b(FAAR_K_BWD_ADAM, st);
   return hip_status(launch_step_bwd_adam(a, st));
+}
+
+// ---- glue of a block for joint (Stage-2-style) steps ---------------------------------------------------------------
+static int check_rows(int64_t T, int64_t D) {
+  if (T <= 0 || D <= 0 || D % 8 != 0 || T > 0x7FFFFFFF || T > kMaxElems / D) return FAAR_E_SHAPE;
+  return FAAR_OK;
+}
+
+int faar_linear_forward(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global, const uint8_t* scales,
+                        const float* V, float beta, const void* Xq, const float* x_scale, int64_t T, void* Y, void* ws,
+                        size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !V || !Xq || !Y) return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
+  if (!(beta > 0.0f) || !std::isfinite(beta)) return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(Xq) || !aligned16(Y) || !aligned16(ws)) return FAAR_E_ARG;
+  if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_LINEAR_FORWARD, O, K, T, 0)) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  bf16_t* wq = static_cast<bf16_t*>(ws);
+  if (int e = hip_status(launch_softquant_fwd(W, wdt == FAAR_BF16, O * K, s_global, scales, V, beta, false, wq, nullptr, st)))
+    return e;
+  Bracket b(FAAR_K_GEMM_FWD, st);
+  return hip_status(launch_gemm_bf16(static_cast<const bf16_t*>(Xq), wq, GemmDims{T, O, K, K, K}, static_cast<bf16_t*>(Y),
+                                     x_scale, st));
+}
+
+int faar_rmsnorm_fwd(const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g, float eps, void* h, float* rstd,
+                     void* stream) {
+  if (!x || !g || !h || !rstd) return FAAR_E_NULL;
+  if (int e = check_wdt(xdt)) return e;
+  if (int e = check_rows(T, D)) return e;
+  if (!(eps >= 0.0f) || !std::isfinite(eps)) return FAAR_E_ARG;
+  if (!aligned16(x) || !aligned16(g) || !aligned16(h)) return FAAR_E_ARG;
+  return hip_status(launch_rmsnorm_fwd(x, xdt == FAAR_BF16, T, D, g, eps, static_cast<bf16_t*>(h), rstd,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g,
+                     const float* rstd, const void* d_res, void* dx, void* stream) {
+  if (!dh1 || !x || !g || !rstd || !dx) return FAAR_E_NULL;
+  if (int e = check_wdt(xdt)) return e;
+  if (int e = check_rows(T, D)) return e;
+  if (!aligned16(dh1) || !aligned16(dh2) || !aligned16(x) || !aligned16(g) || !aligned16(d_res) || !aligned16(dx)) return FAAR_E_ARG;
+  return hip_status(launch_rmsnorm_bwd(static_cast<const bf16_t*>(dh1), static_cast<const bf16_t*>(dh2), x, xdt == FAAR_BF16, T, D,
+                                       g, rstd, static_cast<const bf16_t*>(d_res), static_cast<bf16_t*>(dx),
+                                       static_cast<hipStream_t>(stream)));
+}
+
+int faar_silu_mul_fwd(const void* p, const void* q, int64_t n, void* a, void* stream) {
+  if (!p || !q || !a) return FAAR_E_NULL;
+  if (n <= 0 || n % 8 != 0 || n > kMaxElems) return FAAR_E_SHAPE;
+  if (!aligned16(p) || !aligned16(q) || !aligned16(a)) return FAAR_E_ARG;
+  return hip_status(launch_silu_mul_fwd(static_cast<const bf16_t*>(p), static_cast<const bf16_t*>(q), n, static_cast<bf16_t*>(a),
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int faar_silu_mul_bwd(const void* da, const void* p, const void* q, int64_t n, void* dp, void* dq, void* stream) {
+  if (!da || !p || !q || !dp || !dq) return FAAR_E_NULL;
+  if (n <= 0 || n % 8 != 0 || n > kMaxElems) return FAAR_E_SHAPE;
+  if (!aligned16(da) || !aligned16(p) || !aligned16(q) || !aligned16(dp) || !aligned16(dq)) return FAAR_E_ARG;
+  return hip_status(launch_silu_mul_bwd(static_cast<const bf16_t*>(da), static_cast<const bf16_t*>(p), static_cast<const bf16_t*>(q),
+                                        n, static_cast<bf16_t*>(dp), static_cast<bf16_t*>(dq), static_cast<hipStream_t>(stream)));
+}
+
+int faar_block_output_loss(const void* x, faar_dtype xdt, const void* d, const void* y_fp, faar_dtype ydt, int64_t T, int64_t D,
+                           float mse_scale, void* y, void* dy, float* loss, void* ws, size_t ws_bytes, void* stream) {
+  if (!x || !d || !y_fp || !dy || !loss) return FAAR_E_NULL;
+  if (int e = check_wdt(xdt)) return e;
+  if (int e = check_wdt(ydt)) return e;
+  if (int e = check_rows(T, D)) return e;
+  if (!std::isfinite(mse_scale)) return FAAR_E_ARG;
+  if (!aligned16(x) || !aligned16(d) || !aligned16(y_fp) || !aligned16(y) || !aligned16(dy) || !aligned16(ws)) return FAAR_E_ARG;
+  if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_BLOCK_OUTPUT_LOSS, D, 16, T, 0)) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  double* partials = static_cast<double*>(ws);
+  if (int e = hip_status(launch_block_output_loss(x, xdt == FAAR_BF16, static_cast<const bf16_t*>(d), y_fp, ydt == FAAR_BF16, T * D,
+                                                  2.0f * mse_scale, static_cast<bf16_t*>(y), static_cast<bf16_t*>(dy), partials, st)))
+    return e;
+  return hip_status(launch_finalize_losses(partials, block_loss_blocks(T * D), mse_scale, nullptr, 0, 0.0, 0.0f, loss, nullptr,
+                                           nullptr, st));
 }
 
 int faar_stochastic_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,

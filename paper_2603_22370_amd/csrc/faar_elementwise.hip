@@ -482,6 +482,17 @@ k_step_fwd(const WT* __restrict__ W, int64_t n8, const float* __restrict__ s_glo
   }
 }
 
+// The forward-tag check of a step that consumes a prepared forward, for steps whose first kernel is not the residual
+// GEMM (which otherwise does it): compare, clear, write the verdict.
+__global__ void k_check_forward_tag(ForwardGuard guard) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    bool ok = true;
+    for (int i = 0; i < kTagWords; ++i) ok = ok && guard.slot[i] == guard.expect.w[i];
+    for (int i = 0; i < kTagWords; ++i) guard.slot[i] = 0u;
+    guard.slot[kTagWords] = ok ? 1u : 0u;
+  }
+}
+
 // ---- loss finalisation: fixed-order sums of the per-block partials (one block) ---------------
 struct LossSums {
   const double* mse_partials;
@@ -1030,6 +1041,11 @@ hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, b
   if (tiles_c * tiles_r > 0x7FFFFFFFLL) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_transpose_bf16, dim3(static_cast<unsigned>(tiles_c * tiles_r)), dim3(256), 0, st, in, rows, cols, out,
                      ld_out, static_cast<unsigned>(tiles_c));
+  return hipGetLastError();
+}
+
+hipError_t launch_check_forward_tag(const ForwardGuard& guard, hipStream_t st) {
+  hipLaunchKernelGGL(k_check_forward_tag, dim3(1), dim3(64), 0, st, guard);
   return hipGetLastError();
 }
 

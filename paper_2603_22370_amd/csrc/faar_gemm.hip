@@ -324,18 +324,20 @@ struct EpiSub {
   __device__ __forceinline__ void finish(int) {}
 };
 
-// out[m][n] = bf16(acc)
+// out[m][n] = bf16(scale * acc)
 struct EpiBf16 {
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   bf16_t* out;
+  const float* scale;   // device scalar multiplying the product (activations stored in units of it); null = 1
+  float sc;
   __device__ __forceinline__ void once() {}
-  __device__ __forceinline__ void begin() {}
+  __device__ __forceinline__ void begin() { sc = scale ? *scale : 1.0f; }
   __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
     if (n >= d.N) return;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
-      if (m + q < d.M) out[(m + q) * d.N + n] = static_cast<bf16_t>(f32_to_bf16(acc[q]));
+      if (m + q < d.M) out[(m + q) * d.N + n] = static_cast<bf16_t>(f32_to_bf16(sc * acc[q]));
   }
   __device__ __forceinline__ void finish(int) {}
 };
@@ -948,8 +950,8 @@ hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const v
   return run(A, B, d, p, e, st);
 }
 
-hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, hipStream_t st) {
-  EpiBf16 e{out};
+hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, const float* scale, hipStream_t st) {
+  EpiBf16 e{out, scale, 1.0f};
   return run(A, B, d, plan_gemm(d, false, kEpiBf16), e, st);
 }
 

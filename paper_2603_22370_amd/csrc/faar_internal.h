@@ -103,6 +103,7 @@ hipError_t launch_finalize_losses(const double* mse_partials, int64_t n_mse, flo
 // out[c * ld_out + r] = in[r * cols + c] for r < rows, c < cols; columns rows..ld_out-1 zeroed.
 hipError_t launch_transpose_bf16(const bf16_t* in, int64_t rows, int64_t cols, bf16_t* out,
                                  int64_t ld_out, hipStream_t st);
+hipError_t launch_check_forward_tag(const ForwardGuard& guard, hipStream_t st);
 // Term `term` (0 hi, 1 mid, 2 lo) of the float32 C [ceil(T/4)][O][4] as bf16, transposed to [O, ld_out] (ld_out =
 // padded_tokens(T), zero padded); sq_partials (nullable): c_term_blocks(T, O) per-workgroup sums of C^2
 int64_t c_term_blocks(int64_t T, int64_t O);
@@ -134,6 +135,18 @@ struct Stage2Args {
 };
 int64_t stage2_mse_blocks(int64_t n);
 hipError_t launch_stage2(const Stage2Args& a, hipStream_t st);
+
+// ---- glue between the linears of a block (faar_block.hip); activations and gradients bf16, D and n multiples of 8 ----
+hipError_t launch_rmsnorm_fwd(const void* X, bool x_bf16, int64_t T, int64_t D, const float* g, float eps, bf16_t* H,
+                              float* rstd, hipStream_t st);
+hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const void* X, bool x_bf16, int64_t T, int64_t D,
+                              const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st);
+hipError_t launch_silu_mul_fwd(const bf16_t* P, const bf16_t* Q, int64_t n, bf16_t* A, hipStream_t st);
+hipError_t launch_silu_mul_bwd(const bf16_t* dA, const bf16_t* P, const bf16_t* Q, int64_t n, bf16_t* dP, bf16_t* dQ,
+                               hipStream_t st);
+int64_t block_loss_blocks(int64_t n);
+hipError_t launch_block_output_loss(const void* X, bool x_bf16, const bf16_t* Dm, const void* Yfp, bool y_bf16, int64_t n,
+                                    float two_scale, bf16_t* Y, bf16_t* dY, double* partials, hipStream_t st);
 
 // ---- bf16 MFMA GEMMs (faar_gemm.hip) ------------------------------------------------------
 // All GEMMs are "NT": acc[m][n] = sum_k A[m][k] * B[n][k], A [M, lda], B [N, ldb] bf16 row-major
@@ -169,8 +182,8 @@ hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const v
 // product, no output: clocks[2 i], clocks[2 i + 1] = shader-clock cycles and 100 MHz ticks of work item i.
 hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,
                              int64_t capacity, float* sink, int* kind, int64_t* items, hipStream_t st);
-// out[m][n] = bf16(acc)
-hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out,
+// out[m][n] = bf16(scale * acc), scale a device scalar (null = 1)
+hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, const float* scale,
                             hipStream_t st);
 
 }  // namespace faar

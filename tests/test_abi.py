@@ -150,3 +150,52 @@ def test_batched_codec_calls_validate_every_descriptor_first():
     assert L.faar_quant_rtn_batch(arr, 0, 1, 0, ws, 1 << 20, None) == -2
     assert L.faar_init_v_batch(None, 1, 1, None) == -1
     assert fb.faar_workspace_bytes(fb.OP_QUANT_RTN_BATCH, 16, 16) >= 48 * 64 * 4
+
+
+def test_block_glue_calls_reject_bad_arguments_without_a_gpu():
+    L = fb.lib()
+    p, odd, nul = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), None
+    f = L.faar_linear_forward
+    ws = fb.faar_workspace_bytes(fb.OP_LINEAR_FORWARD, 32, 32, 64)
+    assert ws >= 32 * 32 * 2
+    assert f(p, 1, 32, 32, p, p, nul, 1.0, p, nul, 64, p, p, ws, nul) == -1
+    assert f(p, 5, 32, 32, p, p, p, 1.0, p, nul, 64, p, p, ws, nul) == -3
+    assert f(p, 1, 32, 24, p, p, p, 1.0, p, nul, 64, p, p, ws, nul) == -2
+    assert f(p, 1, 32, 32, p, p, p, 1.0, p, nul, 0, p, p, ws, nul) == -2
+    assert f(p, 1, 32, 32, p, p, p, 0.0, p, nul, 64, p, p, ws, nul) == -6
+    assert f(p, 1, 32, 32, p, p, p, 1.0, odd, nul, 64, p, p, ws, nul) == -6
+    assert f(p, 1, 32, 32, p, p, p, 1.0, p, nul, 64, p, p, ws - 1, nul) == -4
+    assert f(p, 1, 32, 32, p, p, p, 1.0, p, nul, 64, p, nul, 0, nul) == -4
+    n = L.faar_rmsnorm_fwd
+    assert n(p, 1, 4, 64, nul, 1e-6, p, p, nul) == -1
+    assert n(p, 1, 4, 60, p, 1e-6, p, p, nul) == -2
+    assert n(p, 1, 0, 64, p, 1e-6, p, p, nul) == -2
+    assert n(p, 9, 4, 64, p, 1e-6, p, p, nul) == -3
+    assert n(p, 1, 4, 64, p, -1.0, p, p, nul) == -6
+    assert n(p, 1, 4, 64, p, float("nan"), p, p, nul) == -6
+    assert n(odd, 1, 4, 64, p, 1e-6, p, p, nul) == -6
+    b = L.faar_rmsnorm_bwd
+    assert b(nul, nul, p, 1, 4, 64, p, p, nul, p, nul) == -1
+    assert b(p, nul, p, 1, 4, 64, p, p, nul, nul, nul) == -1
+    assert b(p, nul, p, 1, 4, 12, p, p, nul, p, nul) == -2
+    assert b(p, odd, p, 1, 4, 64, p, p, nul, p, nul) == -6
+    assert b(p, nul, p, 1, 4, 64, p, p, odd, p, nul) == -6
+    s = L.faar_silu_mul_fwd
+    assert s(p, nul, 64, p, nul) == -1
+    assert s(p, p, 60, p, nul) == -2
+    assert s(p, p, 0, p, nul) == -2
+    assert s(p, odd, 64, p, nul) == -6
+    sb = L.faar_silu_mul_bwd
+    assert sb(p, p, p, 64, p, nul, nul) == -1
+    assert sb(p, p, p, 12, p, p, nul) == -2
+    assert sb(p, p, p, 64, odd, p, nul) == -6
+    o = L.faar_block_output_loss
+    wsl = fb.faar_workspace_bytes(fb.OP_BLOCK_OUTPUT_LOSS, 64, 16, 4)
+    assert wsl >= 8
+    assert o(p, 1, p, p, 1, 4, 64, 1.0, nul, p, nul, p, wsl, nul) == -1
+    assert o(p, 1, p, p, 4, 4, 64, 1.0, nul, p, p, p, wsl, nul) == -3
+    assert o(p, 1, p, p, 1, 4, 20, 1.0, nul, p, p, p, wsl, nul) == -2
+    assert o(p, 1, p, p, 1, 4, 64, float("inf"), nul, p, p, p, wsl, nul) == -6
+    assert o(p, 1, p, p, 1, 4, 64, 1.0, odd, p, p, p, wsl, nul) == -6
+    assert o(p, 1, p, p, 1, 4, 64, 1.0, nul, p, p, p, wsl - 1, nul) == -4
+    assert o(p, 1, p, p, 1, 4, 64, 1.0, nul, p, p, nul, 0, nul) == -4

@@ -16,6 +16,10 @@ DIMS = [16, 32, 48, 64, 80, 96, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512
 TOKENS = [1, 3, 33, 64, 65, 100, 128, 256, 300, 512, 640, 1024, 1536, 2048, 3072, 4096, 8192, 16384, 65536]
 
 
+# shapes (O, K, T) on which tests/test_gpu_block.py compares faar_linear_forward with the oracle
+FORWARD_CASES = [(96, 80, 100), (640, 256, 300), (2048, 512, 1024), (6144, 2048, 2048), (640, 256, 300), (256, 640, 300)]
+
+
 def _combos(O, K, T, chained):
     for g, which in GEMMS.items():
         if g == "dx" and not chained:
@@ -54,3 +58,19 @@ def test_benchmark_shapes_are_parity_cases_at_full_size():
             for combo in _combos(O, K, T, chained):
                 if combo[1] in ("L64", "M64"):          # the two fast kernels; the 128x128 one is covered by small cases
                     assert combo in full, (O, K, T, combo)
+
+
+def test_forward_gemm_of_the_joint_step_runs_kernels_that_parity_cases_cover():
+    """faar_linear_forward uses the bf16-output GEMM (the dX GEMM's epilogue) on T x O x K: every variant it takes on the
+    joint benchmark's shapes is a variant some parity case reaches with that epilogue (as dX GEMM or as forward GEMM)."""
+    covered = set()
+    for c in STEP_CASES:
+        if c.chained:
+            kind, bm, bn, _ = fb.faar_gemm_plan(fb.K_GEMM_DX, c.O, c.K, c.T)
+            covered.add((kind, bm, bn))
+    for O, K, T in FORWARD_CASES:
+        kind, bm, bn, _ = fb.faar_gemm_plan(fb.K_GEMM_FWD, O, K, T)
+        covered.add((kind, bm, bn))
+    for O, K in ((6144, 2048), (2048, 6144)):
+        kind, bm, bn, _ = fb.faar_gemm_plan(fb.K_GEMM_FWD, O, K, 16384)
+        assert (kind, bm, bn) in covered, (O, K, kind)
