@@ -634,9 +634,9 @@ def run_mlp_joint(args) -> dict:
     g = torch.ones(D, dtype=torch.float32, device="cuda")
     lin = {}
     for i, (n, O, K) in enumerate(shapes):
-        W = torch.from_numpy(synth.weights(O, K, 40 + i)).cuda().to(torch.bfloat16)
+        W = torch.from_numpy(synth.student_t_weight(O, K, 40 + i)).cuda().to(torch.bfloat16)
         sg, sc, _, _ = faar.faar_quant_rtn(W)
-        V = faar.faar_init_v(W, sg, sc)
+        V, _ = faar.faar_init_v(W, sg, sc)
         X0 = torch.zeros((T, K), dtype=torch.bfloat16, device="cuda")
         Xt, _, ic = faar.faar_layer_prepare(W, sg, sc, X0, None)          # only the node codes depend on W alone
         lin[n] = dict(W=W, sg=sg, sc=sc, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=Xt, ic=ic, O=O, K=K, t=0,
@@ -912,15 +912,15 @@ def run_stage2(args) -> dict:
 
 
 def run_gemm_ceiling(args) -> dict:
-    """What bounds the GEMM main loop, measured through the library's own kernel (faar_gemm_probe) on the product of the
-    Llama3-1B-shaped gate_proj dW GEMM (8192 x 2048 outputs, contraction over 4096 tokens), random bf16 operands: the
+    """What bounds the GEMM main loop, measured through the library's own kernel (faar_gemm_probe) on one product
+    (default: the Llama3-1B-shaped gate_proj dW GEMM, 8192 x 2048 outputs, contraction over 4096 tokens), random bf16 operands: the
     loop with only its matrix instructions (operands read from LDS, nothing copied), with only its global->LDS copies,
     and whole -- each with the core clock the compute units ran at (shader clock counter / constant 100 MHz counter)."""
     import torch
 
     from paper_2603_22370_amd import binding as fb
 
-    M, N, Kd = 8192, 2048, 4096
+    M, N, Kd = (int(v) for v in args.gemm_shape.split(","))
     gen = torch.Generator(device="cuda")
     gen.manual_seed(3)
     A = torch.randn((M, Kd), generator=gen, device="cuda").to(torch.bfloat16)
@@ -974,6 +974,8 @@ def main() -> int:
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
                     help="single-linear workloads: after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
+    ap.add_argument("--gemm-shape", default="8192,2048,4096",
+                    help="gemm_ceiling: outputs M x N and contraction, default the Llama3-1B-shaped gate_proj dW GEMM")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
                     help="qwen_layer: HIP streams the seven independent per-linear jobs are issued on")
     ap.add_argument("--no-cpu-baseline", action="store_true")

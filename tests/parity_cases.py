@@ -45,6 +45,8 @@ STEP_CASES = [
     StepCase("llama_gate_proj", 8192, 2048, 4096, 1, chained=True, full_size=True),
     StepCase("llama_down_proj", 2048, 8192, 4096, 2, gated_input=True, chained=True, full_size=True),
     StepCase("qwen_k_proj", 1024, 2048, 8192, 3, quantised_acts=True, chained=True, full_size=True),
+    StepCase("qwen_q_proj", 2048, 2048, 8192, 5, full_size=True),                       # the default benchmark's q / o projection
+    StepCase("qwen_down_proj", 2048, 6144, 8192, 6, gated_input=True, full_size=True),  # ... and its down projection
     StepCase("qwen_gate_proj_T16384", 6144, 2048, 16384, 4, chained=True, full_size=True),
 ]
 
