@@ -80,7 +80,9 @@ enum {
   FAAR_OP_STAGE2_LOSSES = 6, /* faar_workspace_bytes(op, O = vocabulary, K = hidden size, T = tokens, 0) */
   FAAR_OP_QUANT_RTN_BATCH = 7, /* independent of the tensors: pass any valid O, K (e.g. 16, 16) */
   FAAR_OP_LINEAR_FORWARD = 8,
-  FAAR_OP_BLOCK_OUTPUT_LOSS = 9 /* faar_workspace_bytes(op, O = D (row length), K = 16, T = rows, 0) */
+  FAAR_OP_BLOCK_OUTPUT_LOSS = 9, /* faar_workspace_bytes(op, O = D (row length), K = 16, T = rows, 0) */
+  FAAR_OP_ATTENTION_FWD = 10, /* faar_workspace_bytes(op, O = n_q * dh, K = n_kv * dh, T = tokens, 0) */
+  FAAR_OP_ATTENTION_BWD = 11  /* likewise */
 };
 
 /* kernels of the path, for faar_time_kernel */
@@ -420,9 +422,18 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K,
  *   a = faar_silu_mul_fwd(p, q);  d = faar_linear_forward(down, a);  (L, dy) = faar_block_output_loss(x1, d, y_fp)
  *   da = dX of faar_layer_step(down, Xq = a, dY_ext = dy, FAAR_STEP_JOINT);  (dp, dq) = faar_silu_mul_bwd(da, p, q)
  *   dh1 = dX of faar_layer_step(gate, Xq = h, dY_ext = dp, ...);  dh2 = dX of faar_layer_step(up, Xq = h, dY_ext = dq, ...)
- *   dx1 = faar_rmsnorm_bwd(dh1, dh2, x1, d_res = dy)
+ *   dx1 = faar_rmsnorm_bwd(dh1, dh2, NULL, x1, d_res = dy)
  *
- * (the attention half -- rotary embedding and the attention core -- is not part of this library yet).
+ * and of the attention half before it (x1 = x + o_proj(attention); its output gradient is dx1)
+ *
+ *   h = faar_rmsnorm_fwd(x);  q, k, v = faar_linear_forward(q_proj / k_proj / v_proj, h)
+ *   [Qwen3: q, k = faar_rmsnorm_fwd over each head's dh entries: rows = T * heads, row length dh]
+ *   q, k = faar_rope(q), faar_rope(k);  (o, lse) = faar_attention_fwd(q, k, v);  d = faar_linear_forward(o_proj, o)
+ *   x1 = faar_residual_add(x, d)                                   ... the MLP half above, which returns dx1 ...
+ *   do = dX of faar_layer_step(o_proj, Xq = o, dY_ext = dx1, FAAR_STEP_JOINT)
+ *   (dq, dk, dv) = faar_attention_bwd(do, q, k, v, o, lse);  dq, dk = faar_rope(dq / dk, inverse)  [, faar_rmsnorm_bwd per head]
+ *   dh1, dh2, dh3 = dX of faar_layer_step(q_proj / k_proj / v_proj, Xq = h, dY_ext = dq / dk / dv, ...)
+ *   dx = faar_rmsnorm_bwd(dh1, dh2, dh3, x, d_res = dx1)
  */
 
 /* Y = x_scale * Xq W_q(V)^T in bf16 [T*O]: the soft-quantised linear of Eq. 2-3 applied to activations [T*K] (bf16).
@@ -436,11 +447,38 @@ int faar_linear_forward(const void* W, faar_dtype wdt, int64_t O, int64_t K, con
 int faar_rmsnorm_fwd(const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g, float eps, void* h, float* rstd,
                      void* stream);
 
-/* dx = rstd g dh - x rstd^3 / D * sum_i (x g dh) + d_res  with dh = dh1 + dh2 (g is frozen: no gradient for it).
- *   dh1 in bf16 [T*D]; dh2 in, nullable (a second consumer of h, e.g. the up projection next to the gate projection);
+/* dx = rstd g dh - x rstd^3 / D * sum_i (x g dh) + d_res  with dh = dh1 + dh2 + dh3 (g is frozen: no gradient for it).
+ *   dh1 in bf16 [T*D]; dh2, dh3 in, nullable (further consumers of h: the up projection next to the gate projection; the
+ *   k and v projections next to the q projection), added in float32 in that order;
  *   d_res in, nullable bf16 [T*D]: the gradient arriving over the residual connection; dx out bf16 [T*D]. */
-int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g,
-                     const float* rstd, const void* d_res, void* dx, void* stream);
+int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* dh3, const void* x, faar_dtype xdt, int64_t T, int64_t D,
+                     const float* g, const float* rstd, const void* d_res, void* dx, void* stream);
+
+/* Rotary position embedding of those models ("rotate-half" form): for every head of x [T * H * dh] (bf16) and i < dh / 2,
+ *   y[i] = x[i] c - x[i + dh/2] s,  y[i + dh/2] = x[i + dh/2] c + x[i] s,  c = cos_t[(t % S) * dh/2 + i], s likewise from sin_t.
+ * The tables (float [S * dh/2], device) are the caller's: position p of a sequence, frequency i.  inverse != 0 rotates by the
+ * opposite angle, which is the backward pass (the rotation is orthogonal).  y out bf16, may be x.  dh % 16 == 0. */
+int faar_rope(const void* x, int64_t T, int64_t H, int64_t dh, const float* cos_t, const float* sin_t, int64_t S,
+              int32_t inverse, void* y, void* stream);
+
+/* Causal softmax attention with grouped key / value heads, per sequence:
+ *   o[t, j] = sum_{t' <= t, same sequence} softmax_t'(scale q[t, j] . k[t', j / (n_q / n_kv)]) v[t', j / (n_q / n_kv)]
+ *   q in bf16 [T * n_q * dh], k, v in bf16 [T * n_kv * dh], T = n_seq * S tokens, sequence b = rows b*S .. (b+1)*S - 1;
+ *   o out bf16 [T * n_q * dh]; lse out float [n_q * T]: log of the softmax denominator per head and query (for the backward).
+ *   S % 32 == 0, dh 64 or 128, n_q % n_kv == 0, scale > 0.  float32 arithmetic, probabilities rounded to bf16 as matrix-core
+ *   operands.  ws: FAAR_OP_ATTENTION_FWD (a transposed copy of v). */
+int faar_attention_fwd(const void* q, const void* k, const void* v, int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv,
+                       int64_t dh, float scale, void* o, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/* (dq, dk, dv) of the above for the output gradient d_o (bf16 [T * n_q * dh]); o and lse from the forward call.
+ *   dq out bf16 [T * n_q * dh]; dk, dv out bf16 [T * n_kv * dh] (summed over the query heads of a group in a fixed order).
+ *   ws: FAAR_OP_ATTENTION_BWD (transposed copies of q, k, d_o and one float per head and query). */
+int faar_attention_bwd(const void* d_o, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                       int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, float scale, void* dq, void* dk,
+                       void* dv, void* ws, size_t ws_bytes, void* stream);
+
+/* y = x + d: the residual connection after the attention half (x of dtype xdt, d and y bf16, [n], n % 8 == 0; y may be d) */
+int faar_residual_add(const void* x, faar_dtype xdt, const void* d, int64_t n, void* y, void* stream);
 
 /* a = SiLU(p) q = p sigmoid(p) q, all bf16 [n], n % 8 == 0 */
 int faar_silu_mul_fwd(const void* p, const void* q, int64_t n, void* a, void* stream);

@@ -16,7 +16,7 @@ FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
 FAAR_WS_GRADIENT_CONSTANT = 32
 FAAR_STEP_JOINT = 64
-OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS = range(10)
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS, OP_ATTENTION_FWD, OP_ATTENTION_BWD = range(12)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
 
@@ -97,7 +97,17 @@ def lib() -> ctypes.CDLL:
         L.faar_rmsnorm_fwd.restype = c_int
         L.faar_rmsnorm_fwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_float, c_void_p, c_void_p, c_void_p]
         L.faar_rmsnorm_bwd.restype = c_int
-        L.faar_rmsnorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
+        L.faar_residual_add.restype = c_int
+        L.faar_residual_add.argtypes = [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p]
+        L.faar_rope.restype = c_int
+        L.faar_rope.argtypes = [c_void_p, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_int64, ctypes.c_int32, c_void_p, c_void_p]
+        L.faar_attention_fwd.restype = c_int
+        L.faar_attention_fwd.argtypes = [c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64, c_int64, c_int64, c_float, c_void_p,
+                                         c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_attention_bwd.restype = c_int
+        L.faar_attention_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_int64, c_int64,
+                                         c_int64, c_int64, c_float, c_void_p, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_rmsnorm_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p,
                                        c_void_p, c_void_p]
         L.faar_silu_mul_fwd.restype = c_int
         L.faar_silu_mul_fwd.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_void_p]
@@ -400,14 +410,70 @@ def faar_rmsnorm_fwd(x, g, eps):
     return h, rstd
 
 
-def faar_rmsnorm_bwd(dh1, x, g, rstd, dh2=None, d_res=None):
+def faar_rmsnorm_bwd(dh1, x, g, rstd, dh2=None, d_res=None, dh3=None):
     """-> dx bf16 [T, D]."""
-    _dev(dh1, dh2, x, g, rstd, d_res)
+    _dev(dh1, dh2, dh3, x, g, rstd, d_res)
     T, D = x.shape
     dx = torch.empty((T, D), dtype=torch.bfloat16, device=x.device)
-    _check(lib().faar_rmsnorm_bwd(_ptr(dh1), _ptr(dh2), _ptr(x), _dt(x), T, D, _ptr(g), _ptr(rstd), _ptr(d_res), _ptr(dx),
-                                  _stream()), "faar_rmsnorm_bwd")
+    _check(lib().faar_rmsnorm_bwd(_ptr(dh1), _ptr(dh2), _ptr(dh3), _ptr(x), _dt(x), T, D, _ptr(g), _ptr(rstd), _ptr(d_res),
+                                  _ptr(dx), _stream()), "faar_rmsnorm_bwd")
     return dx
+
+
+def faar_residual_add(x, d, out=None):
+    """-> y = x + d, bf16 like d."""
+    _dev(x, d, out)
+    y = torch.empty_like(d) if out is None else out
+    _check(lib().faar_residual_add(_ptr(x), _dt(x), _ptr(d), d.numel(), _ptr(y), _stream()), "faar_residual_add")
+    return y
+
+
+def faar_rope(x, n_heads, cos_t, sin_t, inverse=False, out=None):
+    """x bf16 [T, n_heads * dh]; cos_t, sin_t float32 [S, dh / 2] (row = position in the sequence, T a multiple of S).
+    -> y bf16 like x (out may be x)."""
+    _dev(x, cos_t, sin_t, out)
+    T, HD = x.shape
+    S, half = cos_t.shape
+    if HD != n_heads * 2 * half or T % S != 0 or sin_t.shape != cos_t.shape:
+        raise ValueError("faar_rope: x [T, n_heads * dh], tables [S, dh / 2], T a multiple of S")
+    y = torch.empty_like(x) if out is None else out
+    _check(lib().faar_rope(_ptr(x), T, n_heads, 2 * half, _ptr(cos_t), _ptr(sin_t), S, int(bool(inverse)), _ptr(y), _stream()),
+           "faar_rope")
+    return y
+
+
+def faar_attention_fwd(q, k, v, n_seq, n_q, n_kv, scale=None, ws=None):
+    """Causal grouped-query attention.  q bf16 [T, n_q * dh]; k, v bf16 [T, n_kv * dh]; T = n_seq * S.
+    -> (o bf16 [T, n_q * dh], lse float32 [n_q, T])."""
+    _dev(q, k, v, ws)
+    T, QD = q.shape
+    dh = QD // n_q
+    S = T // n_seq
+    if k.shape != (T, n_kv * dh) or v.shape != k.shape or S * n_seq != T:
+        raise ValueError("faar_attention_fwd: shapes")
+    scale = dh ** -0.5 if scale is None else scale
+    o = torch.empty_like(q)
+    lse = torch.empty((n_q, T), dtype=torch.float32, device=q.device)
+    ws = _workspace(OP_ATTENTION_FWD, n_q * dh, n_kv * dh, T, device=q.device) if ws is None else ws
+    _check(lib().faar_attention_fwd(_ptr(q), _ptr(k), _ptr(v), n_seq, S, n_q, n_kv, dh, float(scale), _ptr(o), _ptr(lse), _ptr(ws),
+                                    ws.numel(), _stream()), "faar_attention_fwd")
+    return o, lse
+
+
+def faar_attention_bwd(d_o, q, k, v, o, lse, n_seq, n_q, n_kv, scale=None, ws=None):
+    """-> (dq, dk, dv) bf16, shaped like q, k, v."""
+    _dev(d_o, q, k, v, o, lse, ws)
+    T, QD = q.shape
+    dh = QD // n_q
+    S = T // n_seq
+    if d_o.shape != q.shape or o.shape != q.shape or k.shape != (T, n_kv * dh) or v.shape != k.shape or lse.shape != (n_q, T):
+        raise ValueError("faar_attention_bwd: shapes")
+    scale = dh ** -0.5 if scale is None else scale
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = _workspace(OP_ATTENTION_BWD, n_q * dh, n_kv * dh, T, device=q.device) if ws is None else ws
+    _check(lib().faar_attention_bwd(_ptr(d_o), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), n_seq, S, n_q, n_kv, dh, float(scale),
+                                    _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()), "faar_attention_bwd")
+    return dq, dk, dv
 
 
 def faar_silu_mul_fwd(p, q):

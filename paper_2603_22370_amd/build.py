@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libfaar.so")
-SOURCES = ["faar_api.hip", "faar_elementwise.hip", "faar_gemm.hip", "faar_stage2.hip", "faar_block.hip"]
+SOURCES = ["faar_api.hip", "faar_elementwise.hip", "faar_gemm.hip", "faar_stage2.hip", "faar_block.hip", "faar_attention.hip"]
 
 # -ffp-contract=off: the decision arithmetic must round once per operation (bit-exact parity).
 # packed-fp32 ops are disabled for the test machines.

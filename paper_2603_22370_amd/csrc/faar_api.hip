@@ -235,6 +235,13 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
       return align256(kAmaxPartials * sizeof(float));
     case FAAR_OP_LINEAR_FORWARD:
       return align256((size_t)O * K * 2);   // W_q in bf16
+    case FAAR_OP_ATTENTION_FWD:             // O = n_q * dh, K = n_kv * dh: V transposed
+      if (T <= 0) return 0;
+      return align256((size_t)K * padded_tokens(T) * 2);
+    case FAAR_OP_ATTENTION_BWD:             // Q, dO, K transposed; one float per head and query (at most O / 64 heads)
+      if (T <= 0) return 0;
+      return align256((size_t)O * padded_tokens(T) * 2) * 2 + align256((size_t)K * padded_tokens(T) * 2) +
+             align256((size_t)(O / 64) * T * sizeof(float));
     case FAAR_OP_BLOCK_OUTPUT_LOSS:         // O = D (row length), T rows
       if (T <= 0 || O % 8 != 0) return 0;
       return align256((size_t)block_loss_blocks(T * O) * sizeof(double));
@@ -579,15 +586,73 @@ int faar_rmsnorm_fwd(const void* x, faar_dtype xdt, int64_t T, int64_t D, const 
                                        static_cast<hipStream_t>(stream)));
 }
 
-int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* x, faar_dtype xdt, int64_t T, int64_t D, const float* g,
-                     const float* rstd, const void* d_res, void* dx, void* stream) {
+int faar_rmsnorm_bwd(const void* dh1, const void* dh2, const void* dh3, const void* x, faar_dtype xdt, int64_t T, int64_t D,
+                     const float* g, const float* rstd, const void* d_res, void* dx, void* stream) {
   if (!dh1 || !x || !g || !rstd || !dx) return FAAR_E_NULL;
   if (int e = check_wdt(xdt)) return e;
   if (int e = check_rows(T, D)) return e;
-  if (!aligned16(dh1) || !aligned16(dh2) || !aligned16(x) || !aligned16(g) || !aligned16(d_res) || !aligned16(dx)) return FAAR_E_ARG;
-  return hip_status(launch_rmsnorm_bwd(static_cast<const bf16_t*>(dh1), static_cast<const bf16_t*>(dh2), x, xdt == FAAR_BF16, T, D,
-                                       g, rstd, static_cast<const bf16_t*>(d_res), static_cast<bf16_t*>(dx),
+  if (!aligned16(dh1) || !aligned16(dh2) || !aligned16(dh3) || !aligned16(x) || !aligned16(g) || !aligned16(d_res) || !aligned16(dx))
+    return FAAR_E_ARG;
+  return hip_status(launch_rmsnorm_bwd(static_cast<const bf16_t*>(dh1), static_cast<const bf16_t*>(dh2),
+                                       static_cast<const bf16_t*>(dh3), x, xdt == FAAR_BF16, T, D, g, rstd,
+                                       static_cast<const bf16_t*>(d_res), static_cast<bf16_t*>(dx),
                                        static_cast<hipStream_t>(stream)));
+}
+
+int faar_rope(const void* x, int64_t T, int64_t H, int64_t dh, const float* cos_t, const float* sin_t, int64_t S, int32_t inverse,
+              void* y, void* stream) {
+  if (!x || !cos_t || !sin_t || !y) return FAAR_E_NULL;
+  if (T <= 0 || H <= 0 || dh <= 0 || S <= 0 || dh % 16 != 0 || dh > 4096 || H > 65536 || T > kMaxElems / (H * dh)) return FAAR_E_SHAPE;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(cos_t) || !aligned16(sin_t)) return FAAR_E_ARG;
+  return hip_status(launch_rope(static_cast<const bf16_t*>(x), T, H, dh, cos_t, sin_t, S, inverse != 0, static_cast<bf16_t*>(y),
+                                static_cast<hipStream_t>(stream)));
+}
+
+static int check_attention(int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, float scale) {
+  if (n_seq <= 0 || S <= 0 || S % 32 != 0 || S > (1 << 20) || n_q <= 0 || n_kv <= 0 || n_q % n_kv != 0 || n_q > 4096) return FAAR_E_SHAPE;
+  if (dh != 64 && dh != 128) return FAAR_E_SHAPE;
+  if (n_seq > kMaxElems / (S * n_q * dh) || n_seq * n_q * (S / 32) > 0x7FFFFFFFLL) return FAAR_E_SHAPE;
+  if (!(scale > 0.0f) || !std::isfinite(scale)) return FAAR_E_ARG;
+  return FAAR_OK;
+}
+
+int faar_attention_fwd(const void* q, const void* k, const void* v, int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv,
+                       int64_t dh, float scale, void* o, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  if (!q || !k || !v || !o || !lse) return FAAR_E_NULL;
+  if (int e = check_attention(n_seq, S, n_q, n_kv, dh, scale)) return e;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(ws)) return FAAR_E_ARG;
+  const int64_t T = n_seq * S, Tp = padded_tokens(T);
+  if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_ATTENTION_FWD, n_q * dh, n_kv * dh, T, 0)) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  bf16_t* vt = static_cast<bf16_t*>(ws);
+  if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(v), T, n_kv * dh, vt, Tp, st))) return e;
+  return hip_status(launch_attention_fwd(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k), vt, n_seq, S, n_q, n_kv, dh,
+                                         Tp, scale, static_cast<bf16_t*>(o), lse, st));
+}
+
+int faar_attention_bwd(const void* d_o, const void* q, const void* k, const void* v, const void* o, const float* lse,
+                       int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, float scale, void* dq, void* dk,
+                       void* dv, void* ws, size_t ws_bytes, void* stream) {
+  if (!d_o || !q || !k || !v || !o || !lse || !dq || !dk || !dv) return FAAR_E_NULL;
+  if (int e = check_attention(n_seq, S, n_q, n_kv, dh, scale)) return e;
+  if (!aligned16(d_o) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv) || !aligned16(ws))
+    return FAAR_E_ARG;
+  const int64_t T = n_seq * S, Tp = padded_tokens(T);
+  if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_ATTENTION_BWD, n_q * dh, n_kv * dh, T, 0)) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  Carver c(ws);
+  bf16_t* qt = c.take<bf16_t>((size_t)n_q * dh * Tp);
+  bf16_t* dot = c.take<bf16_t>((size_t)n_q * dh * Tp);
+  bf16_t* kt = c.take<bf16_t>((size_t)n_kv * dh * Tp);
+  float* delta = c.take<float>((size_t)n_q * T);
+  if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(q), T, n_q * dh, qt, Tp, st))) return e;
+  if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(d_o), T, n_q * dh, dot, Tp, st))) return e;
+  if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(k), T, n_kv * dh, kt, Tp, st))) return e;
+  return hip_status(launch_attention_bwd(static_cast<const bf16_t*>(d_o), static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                                         static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(o), lse, qt, kt, dot, delta, n_seq,
+                                         S, n_q, n_kv, dh, Tp, scale, static_cast<bf16_t*>(dq), static_cast<bf16_t*>(dk),
+                                         static_cast<bf16_t*>(dv), st));
 }
 
 int faar_silu_mul_fwd(const void* p, const void* q, int64_t n, void* a, void* stream) {
@@ -604,6 +669,15 @@ int faar_silu_mul_bwd(const void* da, const void* p, const void* q, int64_t n, v
   if (!aligned16(da) || !aligned16(p) || !aligned16(q) || !aligned16(dp) || !aligned16(dq)) return FAAR_E_ARG;
   return hip_status(launch_silu_mul_bwd(static_cast<const bf16_t*>(da), static_cast<const bf16_t*>(p), static_cast<const bf16_t*>(q),
                                         n, static_cast<bf16_t*>(dp), static_cast<bf16_t*>(dq), static_cast<hipStream_t>(stream)));
+}
+
+int faar_residual_add(const void* x, faar_dtype xdt, const void* d, int64_t n, void* y, void* stream) {
+  if (!x || !d || !y) return FAAR_E_NULL;
+  if (int e = check_wdt(xdt)) return e;
+  if (n <= 0 || n % 8 != 0 || n > kMaxElems) return FAAR_E_SHAPE;
+  if (!aligned16(x) || !aligned16(d) || !aligned16(y)) return FAAR_E_ARG;
+  return hip_status(launch_residual_add(x, xdt == FAAR_BF16, static_cast<const bf16_t*>(d), n, static_cast<bf16_t*>(y),
+                                        static_cast<hipStream_t>(stream)));
 }
 
 int faar_block_output_loss(const void* x, faar_dtype xdt, const void* d, const void* y_fp, faar_dtype ydt, int64_t T, int64_t D,

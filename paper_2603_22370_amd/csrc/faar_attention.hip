@@ -1,0 +1,438 @@
+// The attention core between the q / k / v and the output projections of a block, for a Stage-2-style joint step (paper
+// Sec. 3.5 "Stage 2"; Table 2 steps 15-17 and 23: the quantised model runs forward and one loss is back-propagated into
+// every layer's rounding variables).  The operations are those of the Llama3 / Qwen3 blocks the paper evaluates: rotary
+// position embedding ("rotate-half" form) and causal softmax attention with grouped key / value heads, forward and
+// backward.  Activations and gradients are bf16 between kernels, arithmetic is float32, products run on the matrix
+// cores (v_mfma_f32_16x16x32_bf16) with the probabilities and their gradients rounded to bf16 as operands.
+//
+// Layouts.  q, o, dO, dq: [T, n_q * dh]; k, v, dk, dv: [T, n_kv * dh]; T = n_seq * S tokens, sequence b = rows b*S ..
+// (b+1)*S-1, S a multiple of 32; query head j reads key / value head j / (n_q / n_kv).  Every product is arranged so that
+// its matrix-core operands are read straight from global memory with 8- or 16-byte loads and no shared-memory transpose:
+//   * a product whose contraction runs over dh reads rows of q, k, v, dO ([token][dh], dh contiguous);
+//   * a product whose contraction runs over tokens (P V, dS K, P^T dO, dS^T Q) reads rows of a transposed copy
+//     ([head * dh + d][token], tokens contiguous) that the entry point makes once with the library's transpose kernel;
+//   * the probabilities enter those products in the accumulator layout they were computed in: an accumulator tile holds,
+//     per lane, 4 consecutive rows of one column, and two such tiles side by side are exactly the 8 contraction values a
+//     lane must supply as the second operand -- with the contraction index permuted, which the first operand's loads follow.
+// Each wavefront works alone (no shared memory, no barriers): 32 queries (forward, dq) or 32 keys (dk, dv), walking the
+// causal range in blocks of 32.  This part is under 5 % of a block step's flops; the design favours simplicity.
+#include "faar_internal.h"
+
+namespace faar {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f, kLn2 = 0.6931471805599453f;
+
+union Frag {
+  bf16x8 v;
+  uint4 q;
+  uint2 h[2];
+  uint32_t w[4];
+};
+
+__device__ __forceinline__ bf16x8 load_frag16(const bf16_t* p) {   // 8 consecutive bf16
+  Frag f;
+  f.q = *reinterpret_cast<const uint4*>(p);
+  return f.v;
+}
+// 4 consecutive bf16 at p and 4 at p + 16: the contraction slots (g, 0..3) and (g, 4..7) of a 32-token step, for the
+// lane group g whose accumulator rows are tokens 4g .. 4g+3 of the first and of the second 16-token tile
+__device__ __forceinline__ bf16x8 load_frag_split(const bf16_t* p) {
+  Frag f;
+  f.h[0] = *reinterpret_cast<const uint2*>(p);
+  f.h[1] = *reinterpret_cast<const uint2*>(p + 16);
+  return f.v;
+}
+__device__ __forceinline__ bf16x8 pack_tiles(const f32x4& a, const f32x4& b) {   // two accumulator tiles -> one operand
+  Frag f;
+  f.w[0] = pack_bf16x2(a[0], a[1]);
+  f.w[1] = pack_bf16x2(a[2], a[3]);
+  f.w[2] = pack_bf16x2(b[0], b[1]);
+  f.w[3] = pack_bf16x2(b[2], b[3]);
+  return f.v;
+}
+__device__ __forceinline__ f32x4 mfma(const bf16x8& a, const bf16x8& b, const f32x4& c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float group_max(float x) {   // over the 4 lanes that share lane % 16
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float group_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+__device__ __forceinline__ void store4_bf16(bf16_t* p, const f32x4& a, float s) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack_bf16x2(a[0] * s, a[1] * s), pack_bf16x2(a[2] * s, a[3] * s));
+}
+
+struct AttnDims {
+  int S, n_q, n_kv;
+  int64_t T, Tp;      // tokens, and the row pitch of the transposed copies
+  float scale;        // of the scores (1 / sqrt(dh) for the models here)
+};
+
+// wave -> (sequence, head, block of 32 positions)
+__device__ __forceinline__ bool wave_coords(int64_t total, int blocks, int heads, int64_t& b, int& head, int& blk) {
+  const int64_t w = blockIdx.x * 4LL + (threadIdx.x >> 6);
+  if (w >= total) return false;
+  blk = static_cast<int>(w % blocks);
+  head = static_cast<int>((w / blocks) % heads);
+  b = w / blocks / heads;
+  return true;
+}
+
+// o = softmax(q k^T scale, causal) v and lse = log sum exp of the scaled scores per query ([n_q][T])
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
+           int64_t total, bf16_t* __restrict__ O, float* __restrict__ lse) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  int64_t b;
+  int head, qb;
+  if (!wave_coords(total, d.S / 32, d.n_q, b, head, qb)) return;
+  const int kvh = head / (d.n_q / d.n_kv);
+  const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int p0 = qb * 32;
+  const float c = d.scale * kLog2e;     // scores in units of log 2
+
+  bf16x8 qf[2][KS];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[qt][ks] = load_frag16(Q + (t0 + p0 + qt * 16 + n) * ldq + head * DH + ks * 32 + 8 * g);
+  f32x4 oacc[2][DT];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};
+
+  for (int kb = 0; kb <= qb; ++kb) {
+    const int k0 = kb * 32;
+    f32x4 s[2][2];   // [query tile][key tile]: rows = keys 4g .. 4g+3 of the tile, column = query n
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      bf16x8 kf[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) kf[ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) a = mfma(kf[ks], qf[qt][ks], a);
+        s[qt][kt] = a;
+      }
+    }
+    bf16x8 pf[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      float mx = m[qt];
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float x = s[qt][kt][r] * c;
+          if (kb == qb && kt * 16 + 4 * g + r > qt * 16 + n) x = -INFINITY;   // a key after the query
+          s[qt][kt][r] = x;
+          mx = fmaxf(mx, x);
+        }
+      mx = group_max(mx);   // finite: a query's own position is never masked
+      const float alpha = exp2f(m[qt] - mx);
+      m[qt] = mx;
+      float ps = 0.0f;
+#pragma unroll
+      for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = exp2f(s[qt][kt][r] - mx);
+          s[qt][kt][r] = p;
+          ps += p;
+        }
+      l[qt] = l[qt] * alpha + ps;     // this lane's keys only; the four lanes of a query add up at the end
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] *= alpha;
+      pf[qt] = pack_tiles(s[qt][0], s[qt][1]);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 vf = load_frag_split(Vt + ((int64_t)kvh * DH + dt * 16 + n) * d.Tp + t0 + k0 + 4 * g);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) oacc[qt][dt] = mfma(vf, pf[qt], oacc[qt][dt]);
+    }
+  }
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float lt = group_sum(l[qt]);
+    const float inv = 1.0f / lt;
+    const int64_t t = t0 + p0 + qt * 16 + n;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) store4_bf16(O + t * ldq + head * DH + dt * 16 + 4 * g, oacc[qt][dt], inv);
+    if (g == 0) lse[(int64_t)head * d.T + t] = m[qt] * kLn2 + logf(lt);
+  }
+}
+
+// delta[head][t] = sum_d dO[t][head, d] * O[t][head, d]  (= sum_k P dP of that query: the softmax Jacobian's second term)
+template <int DH>
+__global__ void __launch_bounds__(kEltThreads)
+k_attn_rowdot(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O, int64_t T, int n_q, float* __restrict__ delta) {
+  constexpr int LPR = DH / 8;   // lanes per (token, head): 8 or 16, a divisor of the wavefront
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  const int64_t row = i / LPR;      // = t * n_q + head
+  float a[8], bb[8], acc = 0.0f;
+  if (row < T * n_q) {
+    W8<bf16_t>::load(dO + i * 8, a);
+    W8<bf16_t>::load(O + i * 8, bb);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc += a[j] * bb[j];
+  }
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o);
+  if (row < T * n_q && (threadIdx.x % LPR) == 0) delta[(row % n_q) * T + row / n_q] = acc;
+}
+
+// dq = scale * dS k with dS = P * (dP - delta), P = exp(scores - lse), dP = dO v^T
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+              const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
+              const float* __restrict__ delta, AttnDims d, int64_t total, bf16_t* __restrict__ dQ) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  int64_t b;
+  int head, qb;
+  if (!wave_coords(total, d.S / 32, d.n_q, b, head, qb)) return;
+  const int kvh = head / (d.n_q / d.n_kv);
+  const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int p0 = qb * 32;
+  const float c = d.scale * kLog2e;
+
+  bf16x8 qf[2][KS], dof[2][KS];
+  float lse2[2], dl[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const int64_t t = t0 + p0 + qt * 16 + n;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qf[qt][ks] = load_frag16(Q + t * ldq + head * DH + ks * 32 + 8 * g);
+      dof[qt][ks] = load_frag16(dO + t * ldq + head * DH + ks * 32 + 8 * g);
+    }
+    lse2[qt] = lse[(int64_t)head * d.T + t] * kLog2e;
+    dl[qt] = delta[(int64_t)head * d.T + t];
+  }
+  f32x4 acc[2][DT];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) acc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+
+  for (int kb = 0; kb <= qb; ++kb) {
+    const int k0 = kb * 32;
+    f32x4 ds[2][2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      bf16x8 kf[KS], vf[KS];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        kf[ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
+        vf[ks] = load_frag16(V + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
+      }
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          s = mfma(kf[ks], qf[qt][ks], s);
+          dp = mfma(vf[ks], dof[qt][ks], dp);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const bool masked = kb == qb && kt * 16 + 4 * g + r > qt * 16 + n;
+          const float p = masked ? 0.0f : exp2f(s[r] * c - lse2[qt]);
+          ds[qt][kt][r] = p * (dp[r] - dl[qt]);
+        }
+      }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const bf16x8 ktf = load_frag_split(Kt + ((int64_t)kvh * DH + dt * 16 + n) * d.Tp + t0 + k0 + 4 * g);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) acc[qt][dt] = mfma(ktf, pack_tiles(ds[qt][0], ds[qt][1]), acc[qt][dt]);
+    }
+  }
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const int64_t t = t0 + p0 + qt * 16 + n;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) store4_bf16(dQ + t * ldq + head * DH + dt * 16 + 4 * g, acc[qt][dt], d.scale);
+  }
+}
+
+// dv = P^T dO and dk = scale * dS^T q, summed over the query heads that share the key / value head
+template <int DH>
+__global__ void __launch_bounds__(256)
+k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+               const bf16_t* __restrict__ Qt, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dOt,
+               const float* __restrict__ lse, const float* __restrict__ delta, AttnDims d, int64_t total,
+               bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
+  int64_t b;
+  int kvh, kb;
+  if (!wave_coords(total, d.S / 32, d.n_kv, b, kvh, kb)) return;
+  const int rep = d.n_q / d.n_kv, blocks = d.S / 32;
+  const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int k0 = kb * 32;
+  const float c = d.scale * kLog2e;
+
+  bf16x8 kf[2][KS], vf[2][KS];    // second operands: column = key n of the tile, contraction = dh
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[kt][ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
+      vf[kt][ks] = load_frag16(V + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
+    }
+  f32x4 dk[2][DT], dv[2][DT];     // rows = dh 4g .. 4g+3 of the tile, column = key n
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      dk[kt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+      dv[kt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+
+  for (int hj = 0; hj < rep; ++hj) {
+    const int head = kvh * rep + hj;
+    for (int qb = kb; qb < blocks; ++qb) {
+      const int q0 = qb * 32;
+      f32x4 p[2][2], ds[2][2];    // [query tile][key tile]: rows = queries 4g .. 4g+3 of the tile, column = key n
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const int64_t t = t0 + q0 + qt * 16;
+        bf16x8 qa[KS], da[KS];    // first operands: row = query n of the tile, contraction = dh
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          qa[ks] = load_frag16(Q + (t + n) * ldq + head * DH + ks * 32 + 8 * g);
+          da[ks] = load_frag16(dO + (t + n) * ldq + head * DH + ks * 32 + 8 * g);
+        }
+        const float4 l4 = *reinterpret_cast<const float4*>(lse + (int64_t)head * d.T + t + 4 * g);
+        const float4 d4 = *reinterpret_cast<const float4*>(delta + (int64_t)head * d.T + t + 4 * g);
+        const float lr[4] = {l4.x, l4.y, l4.z, l4.w}, dr[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+          f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            s = mfma(qa[ks], kf[kt][ks], s);
+            dp = mfma(da[ks], vf[kt][ks], dp);
+          }
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const bool masked = qb == kb && kt * 16 + n > qt * 16 + 4 * g + r;   // the key comes after the query
+            const float pr = masked ? 0.0f : exp2f(s[r] * c - lr[r] * kLog2e);
+            p[qt][kt][r] = pr;
+            ds[qt][kt][r] = pr * (dp[r] - dr[r]);
+          }
+        }
+      }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        const bf16x8 dotf = load_frag_split(dOt + ((int64_t)head * DH + dt * 16 + n) * d.Tp + t0 + q0 + 4 * g);
+        const bf16x8 qtf = load_frag_split(Qt + ((int64_t)head * DH + dt * 16 + n) * d.Tp + t0 + q0 + 4 * g);
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+          dv[kt][dt] = mfma(dotf, pack_tiles(p[0][kt], p[1][kt]), dv[kt][dt]);
+          dk[kt][dt] = mfma(qtf, pack_tiles(ds[0][kt], ds[1][kt]), dk[kt][dt]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    const int64_t t = t0 + k0 + kt * 16 + n;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      store4_bf16(dK + t * ldk + kvh * DH + dt * 16 + 4 * g, dk[kt][dt], d.scale);
+      store4_bf16(dV + t * ldk + kvh * DH + dt * 16 + 4 * g, dv[kt][dt], 1.0f);
+    }
+  }
+}
+
+// rotate-half rotary embedding of every head: pair (i, i + dh/2) by the angle whose cosine / sine are in the tables' row
+// t % S; sign = -1 rotates back (the backward pass)
+__global__ void __launch_bounds__(kEltThreads)
+k_rope(const bf16_t* X, int64_t n_chunks, int H, int dh, const float* __restrict__ cos_t,
+       const float* __restrict__ sin_t, int S, float sign, bf16_t* Y) {   // Y may be X: a thread reads what it overwrites first
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;   // one 8-element chunk of a head's first half
+  if (i >= n_chunks) return;
+  const int cph = dh / 16;                       // chunks per half head
+  const int ch = static_cast<int>(i % cph);
+  const int64_t th = i / cph;                    // = t * H + head
+  const int64_t t = th / H;
+  const int64_t base = th * dh + ch * 8;
+  const int64_t tab = (t % S) * (dh / 2) + ch * 8;
+  float a[8], b[8], c[8], s[8], ya[8], yb[8];
+  W8<bf16_t>::load(X + base, a);
+  W8<bf16_t>::load(X + base + dh / 2, b);
+  load8(cos_t + tab, c);
+  load8(sin_t + tab, s);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float sj = sign * s[j];
+    ya[j] = a[j] * c[j] - b[j] * sj;
+    yb[j] = b[j] * c[j] + a[j] * sj;
+  }
+  W8<bf16_t>::store(Y + base, ya);
+  W8<bf16_t>::store(Y + base + dh / 2, yb);
+}
+
+inline unsigned wave_blocks(int64_t waves) { return static_cast<unsigned>((waves + 3) / 4); }
+
+}  // namespace
+
+hipError_t launch_rope(const bf16_t* X, int64_t T, int64_t H, int64_t dh, const float* cos_t, const float* sin_t, int64_t S,
+                       bool inverse, bf16_t* Y, hipStream_t st) {
+  const int64_t n_chunks = T * H * (dh / 16);
+  hipLaunchKernelGGL(k_rope, dim3(static_cast<unsigned>((n_chunks + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0, st, X,
+                     n_chunks, static_cast<int>(H), static_cast<int>(dh), cos_t, sin_t, static_cast<int>(S), inverse ? -1.0f : 1.0f, Y);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_fwd(const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, int64_t n_seq, int64_t S, int64_t n_q,
+                                int64_t n_kv, int64_t dh, int64_t Tp, float scale, bf16_t* O, float* lse, hipStream_t st) {
+  const AttnDims d{static_cast<int>(S), static_cast<int>(n_q), static_cast<int>(n_kv), n_seq * S, Tp, scale};
+  const int64_t total = n_seq * n_q * (S / 32);
+  if (dh == 128)
+    hipLaunchKernelGGL(k_attn_fwd<128>, dim3(wave_blocks(total)), dim3(256), 0, st, Q, K, Vt, d, total, O, lse);
+  else
+    hipLaunchKernelGGL(k_attn_fwd<64>, dim3(wave_blocks(total)), dim3(256), 0, st, Q, K, Vt, d, total, O, lse);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd(const bf16_t* dO, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
+                                const float* lse, const bf16_t* Qt, const bf16_t* Kt, const bf16_t* dOt, float* delta,
+                                int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, int64_t Tp, float scale,
+                                bf16_t* dQ, bf16_t* dK, bf16_t* dV, hipStream_t st) {
+  const int64_t T = n_seq * S;
+  const AttnDims d{static_cast<int>(S), static_cast<int>(n_q), static_cast<int>(n_kv), T, Tp, scale};
+  const int64_t lanes = T * n_q * (dh / 8);
+  const dim3 rgrid(static_cast<unsigned>((lanes + kEltThreads - 1) / kEltThreads));
+  const int64_t tq = n_seq * n_q * (S / 32), tk = n_seq * n_kv * (S / 32);
+  if (dh == 128) {
+    hipLaunchKernelGGL(k_attn_rowdot<128>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
+    hipLaunchKernelGGL(k_attn_bwd_dq<128>, dim3(wave_blocks(tq)), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, tq, dQ);
+    hipLaunchKernelGGL(k_attn_bwd_dkv<128>, dim3(wave_blocks(tk)), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, tk, dK, dV);
+  } else {
+    hipLaunchKernelGGL(k_attn_rowdot<64>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
+    hipLaunchKernelGGL(k_attn_bwd_dq<64>, dim3(wave_blocks(tq)), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, tq, dQ);
+    hipLaunchKernelGGL(k_attn_bwd_dkv<64>, dim3(wave_blocks(tk)), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, tk, dK, dV);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace faar

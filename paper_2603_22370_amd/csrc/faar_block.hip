@@ -51,25 +51,36 @@ k_rmsnorm_fwd(const XT* __restrict__ X, int64_t D8, const float* __restrict__ g,
   }
 }
 
-// dx = r g dh - x r^3 / D * sum(x g dh) + d_res,  dh = dh1 + dh2
+// the gradient entering the norm's output: dh1 (+ dh2) (+ dh3), each stored in bf16, added in float32 in that order
+__device__ __forceinline__ void load_dh(const bf16_t* dH1, const bf16_t* dH2, const bf16_t* dH3, int64_t at, float (&d1)[8]) {
+  float d2[8];
+  W8<bf16_t>::load(dH1 + at, d1);
+  if (dH2) {
+    W8<bf16_t>::load(dH2 + at, d2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) d1[j] += d2[j];
+  }
+  if (dH3) {
+    W8<bf16_t>::load(dH3 + at, d2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) d1[j] += d2[j];
+  }
+}
+
+// dx = r g dh - x r^3 / D * sum(x g dh) + d_res,  dh = dh1 + dh2 + dh3
 template <typename XT>
 __global__ void __launch_bounds__(kRowThreads)
-k_rmsnorm_bwd(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, const XT* __restrict__ X, int64_t D8,
-              const float* __restrict__ g, const float* __restrict__ rstd, const bf16_t* __restrict__ d_res,
-              bf16_t* __restrict__ dX) {
+k_rmsnorm_bwd(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, const bf16_t* __restrict__ dH3,
+              const XT* __restrict__ X, int64_t D8, const float* __restrict__ g, const float* __restrict__ rstd,
+              const bf16_t* __restrict__ d_res, bf16_t* __restrict__ dX) {
   const int64_t row = blockIdx.x, base = row * D8;
   const float r = rstd[row];
   float dot = 0.0f;
   for (int64_t c = threadIdx.x; c < D8; c += kRowThreads) {
-    float v[8], gg[8], d1[8], d2[8];
+    float v[8], gg[8], d1[8];
     W8<XT>::load(X + (base + c) * 8, v);
     load8(g + c * 8, gg);
-    W8<bf16_t>::load(dH1 + (base + c) * 8, d1);
-    if (dH2) {
-      W8<bf16_t>::load(dH2 + (base + c) * 8, d2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) d1[j] += d2[j];
-    }
+    load_dh(dH1, dH2, dH3, (base + c) * 8, d1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) dot += v[j] * (gg[j] * d1[j]);
   }
@@ -79,12 +90,7 @@ k_rmsnorm_bwd(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, co
     float v[8], gg[8], d1[8], d2[8], o[8];
     W8<XT>::load(X + (base + c) * 8, v);
     load8(g + c * 8, gg);
-    W8<bf16_t>::load(dH1 + (base + c) * 8, d1);
-    if (dH2) {
-      W8<bf16_t>::load(dH2 + (base + c) * 8, d2);
-#pragma unroll
-      for (int j = 0; j < 8; ++j) d1[j] += d2[j];
-    }
+    load_dh(dH1, dH2, dH3, (base + c) * 8, d1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) o[j] = r * (gg[j] * d1[j]) - v[j] * k;
     if (d_res) {
@@ -94,6 +100,68 @@ k_rmsnorm_bwd(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, co
     }
     W8<bf16_t>::store(dX + (base + c) * 8, o);
   }
+}
+
+// Rows of at most 512 entries (the per-head norm of q and k: dh = 128): one wavefront per row, one chunk per lane
+__device__ __forceinline__ float wave_sum_f(float a) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+  return a;
+}
+
+template <typename XT>
+__global__ void __launch_bounds__(kRowThreads)
+k_rmsnorm_fwd_short(const XT* __restrict__ X, int64_t rows, int D8, const float* __restrict__ g, float eps,
+                    bf16_t* __restrict__ H, float* __restrict__ rstd) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)(kRowThreads / 64) + (threadIdx.x >> 6);
+  const bool on = row < rows && lane < D8;
+  float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f}, gg[8], o[8];
+  if (on) W8<XT>::load(X + (row * D8 + lane) * 8, v);
+  float ss = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+  ss = wave_sum_f(ss);
+  const float r = 1.0f / sqrtf(ss / static_cast<float>(D8 * 8) + eps);
+  if (row < rows && lane == 0) rstd[row] = r;
+  if (!on) return;
+  load8(g + lane * 8, gg);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = (v[j] * r) * gg[j];
+  W8<bf16_t>::store(H + (row * D8 + lane) * 8, o);
+}
+
+template <typename XT>
+__global__ void __launch_bounds__(kRowThreads)
+k_rmsnorm_bwd_short(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, const bf16_t* __restrict__ dH3,
+                    const XT* __restrict__ X, int64_t rows, int D8, const float* __restrict__ g,
+                    const float* __restrict__ rstd, const bf16_t* __restrict__ d_res, bf16_t* __restrict__ dX) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)(kRowThreads / 64) + (threadIdx.x >> 6);
+  const bool on = row < rows && lane < D8;
+  const int64_t at = (row * D8 + lane) * 8;
+  float v[8], gg[8], d1[8], o[8];
+  float dot = 0.0f;
+  if (on) {
+    W8<XT>::load(X + at, v);
+    load8(g + lane * 8, gg);
+    load_dh(dH1, dH2, dH3, at, d1);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) dot += v[j] * (gg[j] * d1[j]);
+  }
+  dot = wave_sum_f(dot);
+  if (!on) return;
+  const float r = rstd[row];
+  const float k = (r * r * r) * (dot / static_cast<float>(D8 * 8));
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = r * (gg[j] * d1[j]) - v[j] * k;
+  if (d_res) {
+    float d2[8];
+    W8<bf16_t>::load(d_res + at, d2);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] += d2[j];
+  }
+  W8<bf16_t>::store(dX + at, o);
 }
 
 __device__ __forceinline__ float sigmoidf_(float p) { return 1.0f / (1.0f + __expf(-p)); }
@@ -162,13 +230,36 @@ k_block_output_loss(const XT* __restrict__ X, const bf16_t* __restrict__ Dm, con
   if (threadIdx.x == 0) partials[blockIdx.x] = (s[0] + s[1]) + (s[2] + s[3]);
 }
 
+// y = x + d (the residual connection between the two halves of a block)
+template <typename XT>
+__global__ void __launch_bounds__(kEltThreads)
+k_residual_add(const XT* __restrict__ X, const bf16_t* __restrict__ Dm, int64_t n8, bf16_t* __restrict__ Y) {
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n8) return;
+  float x[8], d[8];
+  W8<XT>::load(X + i * 8, x);
+  W8<bf16_t>::load(Dm + i * 8, d);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] += d[j];
+  W8<bf16_t>::store(Y + i * 8, x);
+}
+
 inline unsigned blocks_for(int64_t n8) { return static_cast<unsigned>((n8 + kEltThreads - 1) / kEltThreads); }
 
 }  // namespace
 
 hipError_t launch_rmsnorm_fwd(const void* X, bool x_bf16, int64_t T, int64_t D, const float* g, float eps, bf16_t* H,
                               float* rstd, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(T)), block(kRowThreads);
+  const dim3 block(kRowThreads);
+  if (D <= 512) {
+    const dim3 grid(static_cast<unsigned>((T + kRowThreads / 64 - 1) / (kRowThreads / 64)));
+    if (x_bf16)
+      hipLaunchKernelGGL(k_rmsnorm_fwd_short<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(X), T, static_cast<int>(D / 8), g, eps, H, rstd);
+    else
+      hipLaunchKernelGGL(k_rmsnorm_fwd_short<float>, grid, block, 0, st, static_cast<const float*>(X), T, static_cast<int>(D / 8), g, eps, H, rstd);
+    return hipGetLastError();
+  }
+  const dim3 grid(static_cast<unsigned>(T));
   if (x_bf16)
     hipLaunchKernelGGL(k_rmsnorm_fwd<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(X), D / 8, g, eps, H, rstd);
   else
@@ -176,13 +267,22 @@ hipError_t launch_rmsnorm_fwd(const void* X, bool x_bf16, int64_t T, int64_t D, 
   return hipGetLastError();
 }
 
-hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const void* X, bool x_bf16, int64_t T, int64_t D,
-                              const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st) {
-  const dim3 grid(static_cast<unsigned>(T)), block(kRowThreads);
+hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const bf16_t* dH3, const void* X, bool x_bf16, int64_t T,
+                              int64_t D, const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st) {
+  const dim3 block(kRowThreads);
+  if (D <= 512) {
+    const dim3 grid(static_cast<unsigned>((T + kRowThreads / 64 - 1) / (kRowThreads / 64)));
+    if (x_bf16)
+      hipLaunchKernelGGL(k_rmsnorm_bwd_short<bf16_t>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const bf16_t*>(X), T, static_cast<int>(D / 8), g, rstd, d_res, dX);
+    else
+      hipLaunchKernelGGL(k_rmsnorm_bwd_short<float>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const float*>(X), T, static_cast<int>(D / 8), g, rstd, d_res, dX);
+    return hipGetLastError();
+  }
+  const dim3 grid(static_cast<unsigned>(T));
   if (x_bf16)
-    hipLaunchKernelGGL(k_rmsnorm_bwd<bf16_t>, grid, block, 0, st, dH1, dH2, static_cast<const bf16_t*>(X), D / 8, g, rstd, d_res, dX);
+    hipLaunchKernelGGL(k_rmsnorm_bwd<bf16_t>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const bf16_t*>(X), D / 8, g, rstd, d_res, dX);
   else
-    hipLaunchKernelGGL(k_rmsnorm_bwd<float>, grid, block, 0, st, dH1, dH2, static_cast<const float*>(X), D / 8, g, rstd, d_res, dX);
+    hipLaunchKernelGGL(k_rmsnorm_bwd<float>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const float*>(X), D / 8, g, rstd, d_res, dX);
   return hipGetLastError();
 }
 
@@ -194,6 +294,15 @@ hipError_t launch_silu_mul_fwd(const bf16_t* P, const bf16_t* Q, int64_t n, bf16
 hipError_t launch_silu_mul_bwd(const bf16_t* dA, const bf16_t* P, const bf16_t* Q, int64_t n, bf16_t* dP, bf16_t* dQ,
                                hipStream_t st) {
   hipLaunchKernelGGL(k_silu_mul_bwd, dim3(blocks_for(n / 8)), dim3(kEltThreads), 0, st, dA, P, Q, n / 8, dP, dQ);
+  return hipGetLastError();
+}
+
+hipError_t launch_residual_add(const void* X, bool x_bf16, const bf16_t* Dm, int64_t n, bf16_t* Y, hipStream_t st) {
+  const dim3 grid(blocks_for(n / 8)), block(kEltThreads);
+  if (x_bf16)
+    hipLaunchKernelGGL(k_residual_add<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(X), Dm, n / 8, Y);
+  else
+    hipLaunchKernelGGL(k_residual_add<float>, grid, block, 0, st, static_cast<const float*>(X), Dm, n / 8, Y);
   return hipGetLastError();
 }
 

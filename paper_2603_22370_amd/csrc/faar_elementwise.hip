@@ -404,14 +404,6 @@ __device__ __forceinline__ float signed_scale(uint32_t nib, float s) {
   return (nib & 7u) == 7u ? 0.0f : ((nib & 8u) ? -s : s);
 }
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {  // round-to-nearest-even pair conversion
-  f32x2_t f = {a, b};
-  bf16x2_t h = __builtin_convertvector(f, bf16x2_t);
-  return *reinterpret_cast<uint32_t*>(&h);
-}
-
 // soft-quantised weight of one coded element
 __device__ __forceinline__ float soft_weight(uint32_t nib, float s, float v, float beta) {
   const uint32_t k = nib & 7u;

@@ -139,14 +139,28 @@ hipError_t launch_stage2(const Stage2Args& a, hipStream_t st);
 // ---- glue between the linears of a block (faar_block.hip); activations and gradients bf16, D and n multiples of 8 ----
 hipError_t launch_rmsnorm_fwd(const void* X, bool x_bf16, int64_t T, int64_t D, const float* g, float eps, bf16_t* H,
                               float* rstd, hipStream_t st);
-hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const void* X, bool x_bf16, int64_t T, int64_t D,
-                              const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st);
+hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const bf16_t* dH3, const void* X, bool x_bf16, int64_t T,
+                              int64_t D, const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st);
 hipError_t launch_silu_mul_fwd(const bf16_t* P, const bf16_t* Q, int64_t n, bf16_t* A, hipStream_t st);
 hipError_t launch_silu_mul_bwd(const bf16_t* dA, const bf16_t* P, const bf16_t* Q, int64_t n, bf16_t* dP, bf16_t* dQ,
                                hipStream_t st);
+hipError_t launch_residual_add(const void* X, bool x_bf16, const bf16_t* Dm, int64_t n, bf16_t* Y, hipStream_t st);
 int64_t block_loss_blocks(int64_t n);
 hipError_t launch_block_output_loss(const void* X, bool x_bf16, const bf16_t* Dm, const void* Yfp, bool y_bf16, int64_t n,
                                     float two_scale, bf16_t* Y, bf16_t* dY, double* partials, hipStream_t st);
+
+// ---- rotary embedding and the attention core (faar_attention.hip); T = n_seq * S, S % 32 == 0, dh 64 or 128 ----
+// Y (may be X) = every head of X [T, H * dh] rotated by the angles of the tables' row t % S (cos_t, sin_t [S, dh / 2])
+hipError_t launch_rope(const bf16_t* X, int64_t T, int64_t H, int64_t dh, const float* cos_t, const float* sin_t, int64_t S,
+                       bool inverse, bf16_t* Y, hipStream_t st);
+// Vt = V transposed, [n_kv * dh, Tp]; lse [n_q, T]
+hipError_t launch_attention_fwd(const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, int64_t n_seq, int64_t S, int64_t n_q,
+                                int64_t n_kv, int64_t dh, int64_t Tp, float scale, bf16_t* O, float* lse, hipStream_t st);
+// Qt, dOt [n_q * dh, Tp], Kt [n_kv * dh, Tp]: transposed copies; delta [n_q, T] scratch
+hipError_t launch_attention_bwd(const bf16_t* dO, const bf16_t* Q, const bf16_t* K, const bf16_t* V, const bf16_t* O,
+                                const float* lse, const bf16_t* Qt, const bf16_t* Kt, const bf16_t* dOt, float* delta,
+                                int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, int64_t Tp, float scale,
+                                bf16_t* dQ, bf16_t* dK, bf16_t* dV, hipStream_t st);
 
 // ---- bf16 MFMA GEMMs (faar_gemm.hip) ------------------------------------------------------
 // All GEMMs are "NT": acc[m][n] = sum_k A[m][k] * B[n][k], A [M, lda], B [N, ldb] bf16 row-major

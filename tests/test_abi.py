@@ -175,11 +175,12 @@ def test_block_glue_calls_reject_bad_arguments_without_a_gpu():
     assert n(p, 1, 4, 64, p, float("nan"), p, p, nul) == -6
     assert n(odd, 1, 4, 64, p, 1e-6, p, p, nul) == -6
     b = L.faar_rmsnorm_bwd
-    assert b(nul, nul, p, 1, 4, 64, p, p, nul, p, nul) == -1
-    assert b(p, nul, p, 1, 4, 64, p, p, nul, nul, nul) == -1
-    assert b(p, nul, p, 1, 4, 12, p, p, nul, p, nul) == -2
-    assert b(p, odd, p, 1, 4, 64, p, p, nul, p, nul) == -6
-    assert b(p, nul, p, 1, 4, 64, p, p, odd, p, nul) == -6
+    assert b(nul, nul, nul, p, 1, 4, 64, p, p, nul, p, nul) == -1
+    assert b(p, nul, nul, p, 1, 4, 64, p, p, nul, nul, nul) == -1
+    assert b(p, nul, nul, p, 1, 4, 12, p, p, nul, p, nul) == -2
+    assert b(p, odd, nul, p, 1, 4, 64, p, p, nul, p, nul) == -6
+    assert b(p, nul, odd, p, 1, 4, 64, p, p, nul, p, nul) == -6
+    assert b(p, nul, nul, p, 1, 4, 64, p, p, odd, p, nul) == -6
     s = L.faar_silu_mul_fwd
     assert s(p, nul, 64, p, nul) == -1
     assert s(p, p, 60, p, nul) == -2
@@ -199,3 +200,41 @@ def test_block_glue_calls_reject_bad_arguments_without_a_gpu():
     assert o(p, 1, p, p, 1, 4, 64, 1.0, odd, p, p, p, wsl, nul) == -6
     assert o(p, 1, p, p, 1, 4, 64, 1.0, nul, p, p, p, wsl - 1, nul) == -4
     assert o(p, 1, p, p, 1, 4, 64, 1.0, nul, p, p, nul, 0, nul) == -4
+
+
+def test_attention_calls_reject_bad_arguments_without_a_gpu():
+    L = fb.lib()
+    p, odd, nul = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1004), None
+    r = L.faar_rope
+    assert r(p, 64, 2, 64, p, nul, 32, 0, p, nul) == -1
+    assert r(p, 64, 2, 24, p, p, 32, 0, p, nul) == -2          # dh % 16
+    assert r(p, 0, 2, 64, p, p, 32, 0, p, nul) == -2
+    assert r(p, 64, 2, 64, p, p, 0, 0, p, nul) == -2
+    assert r(odd, 64, 2, 64, p, p, 32, 0, p, nul) == -6
+    n_q, n_kv, dh, S, n_seq = 4, 2, 128, 64, 2
+    wf = fb.faar_workspace_bytes(fb.OP_ATTENTION_FWD, n_q * dh, n_kv * dh, n_seq * S)
+    wb = fb.faar_workspace_bytes(fb.OP_ATTENTION_BWD, n_q * dh, n_kv * dh, n_seq * S)
+    assert wf >= n_kv * dh * 128 * 2 and wb >= (2 * n_q + n_kv) * dh * 128 * 2 + n_q * 128 * 4
+    assert fb.faar_workspace_bytes(fb.OP_ATTENTION_FWD, n_q * dh, n_kv * dh, 0) == 0
+    f = L.faar_attention_fwd
+    assert f(p, p, nul, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, wf, nul) == -1
+    assert f(p, p, p, n_seq, 48, n_q, n_kv, dh, 0.1, p, p, p, wf, nul) == -2        # S % 32
+    assert f(p, p, p, n_seq, S, n_q, 3, dh, 0.1, p, p, p, wf, nul) == -2            # n_q % n_kv
+    assert f(p, p, p, n_seq, S, n_q, n_kv, 96, 0.1, p, p, p, wf, nul) == -2         # dh
+    assert f(p, p, p, 0, S, n_q, n_kv, dh, 0.1, p, p, p, wf, nul) == -2
+    assert f(p, p, p, n_seq, S, n_q, n_kv, dh, 0.0, p, p, p, wf, nul) == -6
+    assert f(p, odd, p, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, wf, nul) == -6
+    assert f(p, p, p, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, wf - 1, nul) == -4
+    assert f(p, p, p, n_seq, S, n_q, n_kv, dh, 0.1, p, p, nul, 0, nul) == -4
+    b = L.faar_attention_bwd
+    assert b(p, p, p, p, p, nul, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, p, wb, nul) == -1
+    assert b(p, p, p, p, p, p, n_seq, S, n_q, n_kv, dh, 0.1, p, p, nul, p, wb, nul) == -1
+    assert b(p, p, p, p, p, p, n_seq, 33, n_q, n_kv, dh, 0.1, p, p, p, p, wb, nul) == -2
+    assert b(p, p, p, p, p, p, n_seq, S, n_q, n_kv, dh, float("nan"), p, p, p, p, wb, nul) == -6
+    assert b(p, p, p, p, p, p, n_seq, S, n_q, n_kv, dh, 0.1, p, odd, p, p, wb, nul) == -6
+    assert b(p, p, p, p, p, p, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, p, wb - 1, nul) == -4
+    a = L.faar_residual_add
+    assert a(p, 1, nul, 64, p, nul) == -1
+    assert a(p, 3, p, 64, p, nul) == -3
+    assert a(p, 1, p, 60, p, nul) == -2
+    assert a(p, 1, odd, 64, p, nul) == -6
