@@ -62,6 +62,8 @@ enum {
   FAAR_WS_FORWARD_READY = 1u << 3, /* faar_layer_step: the workspace already holds this step's soft-quantised
                                    weights, left there by the previous step (its beta_next) */
   FAAR_STEP_JOINT = 1u << 6,    /* faar_layer_step: the layer is one link of a jointly optimised chain (see there) */
+  FAAR_STEP_XT_READY = 1u << 7, /* faar_layer_step with FAAR_STEP_JOINT: Xt already holds the transpose of Xq (written by the
+                                   joint step of another linear that reads the same activations): do not transpose again */
   FAAR_WS_GRADIENT_CONSTANT = 1u << 5, /* faar_workspace_bytes(FAAR_OP_LAYER_PREPARE): size the workspace for a call that
                                    also produces H and c_norm2 */
   FAAR_DQ_IN_UNITS = 1u << 4    /* faar_quant_rtn: W_dq receives sign * node * E4M3 scale, i.e. the dequantised
@@ -316,7 +318,8 @@ typedef struct {
  *                       is required; the layer's own reconstruction loss is not evaluated (losses[0] = 0, no residual GEMM;
  *                       C may be NULL, H must be).  The activations Xq are the quantised model's own and change with
  *                       every step: the call writes their transpose into Xt itself (Xt is then scratch of
- *                       K * faar_padded_tokens(T) bf16, not an input).  dX is normally requested.
+ *                       K * faar_padded_tokens(T) bf16, not an input; with FAAR_STEP_XT_READY it is an input again: the
+ *                       transpose of this very Xq, left by the joint step of a sibling linear).  dX is normally requested.
  *                       FAAR_WS_CHAINED is accepted and has no effect on the computation.
  *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  That is valid
  *                       when the previous call on this ws was step opt->t - 1 of the same layer (same W, scales,
@@ -479,6 +482,58 @@ int faar_attention_bwd(const void* d_o, const void* q, const void* k, const void
 
 /* y = x + d: the residual connection after the attention half (x of dtype xdt, d and y bf16, [n], n % 8 == 0; y may be d) */
 int faar_residual_add(const void* x, faar_dtype xdt, const void* d, int64_t n, void* y, void* stream);
+
+/*
+ * One joint step of a whole block: the sequence of calls listed above -- attention half, residual, MLP half, squared error
+ * of the block output against the full-precision block's, and the gradient back through all of it into the rounding
+ * variables of the seven linears (one Adam update each, Sec. 3.5 "Stage 2"; Table 2 steps 15-17, 23) and into the block's
+ * input -- enqueued by one call, on one stream, with every intermediate tensor in the caller's workspace.
+ */
+typedef struct {
+  const void* W;           /* in  [O*K], dtype faar_block.wdt */
+  const float* s_global;   /* in  device scalar */
+  const uint8_t* scales;   /* in  [O*K/16] */
+  const uint8_t* icodes;   /* in  [O*K/2]: interval codes from faar_layer_prepare */
+  float* V;                /* inout [O*K] */
+  float* adam_m;           /* inout [O*K] */
+  float* adam_u;           /* inout [O*K] */
+  float* losses;           /* out device [3]: 0, Round Loss of the V the step started from, lambda_round times it */
+} faar_block_linear;
+
+enum faar_block_slot { FAAR_LIN_Q = 0, FAAR_LIN_K, FAAR_LIN_V, FAAR_LIN_O, FAAR_LIN_GATE, FAAR_LIN_UP, FAAR_LIN_DOWN, FAAR_LIN_COUNT };
+
+typedef struct {
+  int64_t n_seq, S;        /* T = n_seq * S tokens; S % 32 == 0 */
+  int64_t D;               /* model width; q_proj is [n_q*dh, D], k/v_proj [n_kv*dh, D], o_proj [D, n_q*dh] */
+  int64_t n_q, n_kv, dh;   /* heads; dh 64 or 128 */
+  int64_t F;               /* MLP width: gate/up_proj [F, D], down_proj [D, F] */
+  float eps;               /* of every RMSNorm */
+  float attn_scale;        /* of the attention scores; 0: 1 / sqrt(dh) */
+  faar_dtype wdt;          /* dtype of all seven W */
+  const float* g_attn;     /* in  float[D]: weights of the norm before the attention half */
+  const float* g_mlp;      /* in  float[D]: ... before the MLP half */
+  const float* g_q;        /* in  float[dh], nullable: per-head norm of q (Qwen3); g_q and g_k both or neither */
+  const float* g_k;
+  const float* cos_t;      /* in  float[S * dh/2]: rotary tables, see faar_rope */
+  const float* sin_t;
+  faar_block_linear lin[FAAR_LIN_COUNT];
+} faar_block;
+
+/* Bytes of workspace faar_block_joint_step needs for this block (0 if the description is invalid).  Pure host function. */
+size_t faar_block_workspace_bytes(const faar_block* blk);
+
+/*   blk         HOST pointer; read during the call only
+ *   x           in  bf16 [T*D]: the block's input;  y_fp in bf16 [T*D]: the full-precision block's output
+ *   mse_scale   the block loss is mse_scale * ||y - y_fp||_F^2
+ *   beta, lambda_round, opt   as in faar_layer_step, for all seven linears (opt->t is the step index)
+ *   block_loss  out device float[1]
+ *   dx          out, nullable bf16 [T*D]: dL/dx (the first block of a model does not need it; the dX GEMMs of q, k, v
+ *               are then skipped)
+ *   ws          faar_block_workspace_bytes(blk) bytes, 256-byte aligned; contents are scratch
+ * Errors as everywhere: a negative code and nothing is launched for argument errors found up front. */
+int faar_block_joint_step(const faar_block* blk, const void* x, const void* y_fp, float mse_scale, float beta,
+                          float lambda_round, const faar_adam* opt, float* block_loss, void* dx, void* ws, size_t ws_bytes,
+                          void* stream);
 
 /* a = SiLU(p) q = p sigmoid(p) q, all bf16 [n], n % 8 == 0 */
 int faar_silu_mul_fwd(const void* p, const void* q, int64_t n, void* a, void* stream);

@@ -37,6 +37,21 @@ class faar_adam(ctypes.Structure):
     _fields_ = [("lr", c_float), ("beta1", c_float), ("beta2", c_float), ("eps", c_float), ("t", c_int32)]
 
 
+class faar_block_linear(ctypes.Structure):
+    _fields_ = [("W", c_void_p), ("s_global", c_void_p), ("scales", c_void_p), ("icodes", c_void_p), ("V", c_void_p),
+                ("adam_m", c_void_p), ("adam_u", c_void_p), ("losses", c_void_p)]
+
+
+BLOCK_SLOTS = ("q", "k", "v", "o", "gate", "up", "down")
+
+
+class faar_block(ctypes.Structure):
+    _fields_ = [("n_seq", c_int64), ("S", c_int64), ("D", c_int64), ("n_q", c_int64), ("n_kv", c_int64), ("dh", c_int64),
+                ("F", c_int64), ("eps", c_float), ("attn_scale", c_float), ("wdt", c_int), ("g_attn", c_void_p),
+                ("g_mlp", c_void_p), ("g_q", c_void_p), ("g_k", c_void_p), ("cos_t", c_void_p), ("sin_t", c_void_p),
+                ("lin", faar_block_linear * 7)]
+
+
 _lib = None
 
 
@@ -97,6 +112,11 @@ def lib() -> ctypes.CDLL:
         L.faar_rmsnorm_fwd.restype = c_int
         L.faar_rmsnorm_fwd.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_float, c_void_p, c_void_p, c_void_p]
         L.faar_rmsnorm_bwd.restype = c_int
+        L.faar_block_workspace_bytes.restype = c_size_t
+        L.faar_block_workspace_bytes.argtypes = [ctypes.POINTER(faar_block)]
+        L.faar_block_joint_step.restype = c_int
+        L.faar_block_joint_step.argtypes = [ctypes.POINTER(faar_block), c_void_p, c_void_p, c_float, c_float, c_float,
+                                            ctypes.POINTER(faar_adam), c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
         L.faar_residual_add.restype = c_int
         L.faar_residual_add.argtypes = [c_void_p, c_int, c_void_p, c_int64, c_void_p, c_void_p]
         L.faar_rope.restype = c_int
@@ -523,3 +543,45 @@ def faar_hardened_loss(W, s_global, scales, V, Xq, C, mse_scale, ws, x_scale=Non
                                     _ptr(C), T, float(mse_scale), _ptr(loss), _ptr(ws), ws.numel(), _stream()),
            "faar_hardened_loss")
     return loss
+
+
+def block_description(n_seq, S, D, n_q, n_kv, dh, F, eps, g_attn, g_mlp, cos_t, sin_t, linears, g_q=None, g_k=None, attn_scale=0.0):
+    """A faar_block for faar_block_joint_step.  linears: dict slot name (BLOCK_SLOTS) -> dict with the device tensors
+    W, s_global, scales, icodes, V, m, u, losses.  Keeps references to every tensor it points to."""
+    _dev(g_attn, g_mlp, cos_t, sin_t, g_q, g_k)
+    b = faar_block()
+    b.n_seq, b.S, b.D, b.n_q, b.n_kv, b.dh, b.F = n_seq, S, D, n_q, n_kv, dh, F
+    b.eps, b.attn_scale = float(eps), float(attn_scale)
+    b.wdt = _dt(linears["q"]["W"])
+    b.g_attn, b.g_mlp, b.g_q, b.g_k, b.cos_t, b.sin_t = (_ptr(t) for t in (g_attn, g_mlp, g_q, g_k, cos_t, sin_t))
+    keep = [g_attn, g_mlp, g_q, g_k, cos_t, sin_t]
+    for i, name in enumerate(BLOCK_SLOTS):
+        lay = linears[name]
+        ts = [lay[k] for k in ("W", "s_global", "scales", "icodes", "V", "m", "u", "losses")]
+        _dev(*ts)
+        if _dt(lay["W"]) != b.wdt:
+            raise ValueError("block_description: all seven W must have one dtype")
+        (b.lin[i].W, b.lin[i].s_global, b.lin[i].scales, b.lin[i].icodes, b.lin[i].V, b.lin[i].adam_m, b.lin[i].adam_u,
+         b.lin[i].losses) = (_ptr(t) for t in ts)
+        keep += ts
+    b._keep = keep
+    return b
+
+
+def faar_block_workspace(block, device="cuda"):
+    n = int(lib().faar_block_workspace_bytes(ctypes.byref(block)))
+    if n == 0:
+        raise FaarError(-2, "faar_block_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def faar_block_joint_step(block, x, y_fp, mse_scale, beta, lambda_round, lr, beta1, beta2, eps, t, ws, want_dx=True, block_loss=None):
+    """One joint step of a whole block.  -> (block_loss float32[1], dx bf16 [T, D] or None)."""
+    _dev(x, y_fp, ws, block_loss)
+    loss = torch.empty(1, dtype=torch.float32, device=x.device) if block_loss is None else block_loss
+    dx = torch.empty_like(x) if want_dx else None
+    opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
+    _check(lib().faar_block_joint_step(ctypes.byref(block), _ptr(x), _ptr(y_fp), float(mse_scale), float(beta), float(lambda_round),
+                                       ctypes.byref(opt), _ptr(loss), _ptr(dx), _ptr(ws), ws.numel(), _stream()),
+           "faar_block_joint_step")
+    return loss, dx

@@ -445,7 +445,8 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
   const bool chained = dY_ext || dX;
   if (chained && O % 8 != 0) return FAAR_E_SHAPE;
-  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY | FAAR_STEP_JOINT)) return FAAR_E_ARG;
+  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY | FAAR_STEP_JOINT | FAAR_STEP_XT_READY)) return FAAR_E_ARG;
+  if ((flags & FAAR_STEP_XT_READY) && !joint) return FAAR_E_ARG;
   if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
     return FAAR_E_ARG;
   if (!(beta_next >= 0.0f) || !std::isfinite(beta_next)) return FAAR_E_ARG;
@@ -502,7 +503,9 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     if (flags & FAAR_WS_FORWARD_READY) {   // nobody else consumes the tag: check it in a kernel of its own
       if (int e = hip_status(launch_check_forward_tag(guard, st))) return e;
     }
-    if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(const_cast<void*>(Xt)), L.Tp, st))) return e;
+    if (!(flags & FAAR_STEP_XT_READY)) {
+      if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(const_cast<void*>(Xt)), L.Tp, st))) return e;
+    }
   } else {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
     // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
@@ -696,6 +699,188 @@ int faar_block_output_loss(const void* x, faar_dtype xdt, const void* d, const v
     return e;
   return hip_status(launch_finalize_losses(partials, block_loss_blocks(T * D), mse_scale, nullptr, 0, 0.0, 0.0f, loss, nullptr,
                                            nullptr, st));
+}
+
+// ---- a whole block's joint step: the calls above in sequence, every intermediate in the caller's workspace ------------
+namespace {
+
+struct BlockDims {
+  int64_t T, Tp, D, Qd, Kd, F;
+  bool qk_norm;
+  float scale;
+};
+
+struct BlockLayout {
+  // offsets into the workspace (bytes)
+  size_t h, q0, k0, v, q1, k1, rq, rk, o, lse, d1, x1, rstd1, rstd2, h2, p, u, a, d2, dy, da, dp, du, dh_a, dh_b, dh_c, dx1,
+      d_o, dq, dk, dv, dq0, dk0, xt, fwd_ws, step_ws, attn_ws, loss_ws, total;
+  size_t fwd_bytes, step_bytes, attn_bytes, loss_bytes;
+};
+
+int block_dims(const faar_block* b, BlockDims& d) {
+  if (!b) return FAAR_E_NULL;
+  if (b->n_seq <= 0 || b->S <= 0 || b->D <= 0 || b->F <= 0 || b->n_q <= 0 || b->n_kv <= 0) return FAAR_E_SHAPE;
+  if (b->D % 16 != 0 || b->F % 16 != 0) return FAAR_E_SHAPE;
+  const float scale = b->attn_scale == 0.0f ? 1.0f / std::sqrt(static_cast<float>(b->dh)) : b->attn_scale;
+  if (int e = check_attention(b->n_seq, b->S, b->n_q, b->n_kv, b->dh, scale)) return e;
+  if (int e = check_wdt(b->wdt)) return e;
+  d.T = b->n_seq * b->S;
+  d.Tp = padded_tokens(d.T);
+  d.D = b->D; d.Qd = b->n_q * b->dh; d.Kd = b->n_kv * b->dh; d.F = b->F;
+  const int64_t widest = std::max(std::max(d.D, d.F), d.Qd);
+  if (d.T > kMaxElems / widest || d.D > kMaxElems / d.F) return FAAR_E_SHAPE;
+  if ((b->g_q != nullptr) != (b->g_k != nullptr)) return FAAR_E_NULL;
+  d.qk_norm = b->g_q != nullptr;
+  d.scale = scale;
+  if (!(b->eps >= 0.0f) || !std::isfinite(b->eps)) return FAAR_E_ARG;
+  return FAAR_OK;
+}
+
+void lin_shape(const BlockDims& d, int slot, int64_t& O, int64_t& K) {
+  switch (slot) {
+    case FAAR_LIN_Q: O = d.Qd; K = d.D; break;
+    case FAAR_LIN_K: case FAAR_LIN_V: O = d.Kd; K = d.D; break;
+    case FAAR_LIN_O: O = d.D; K = d.Qd; break;
+    case FAAR_LIN_GATE: case FAAR_LIN_UP: O = d.F; K = d.D; break;
+    default: O = d.D; K = d.F; break;
+  }
+}
+
+BlockLayout block_layout(const BlockDims& d, int64_t n_q, int64_t n_kv) {
+  BlockLayout L{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) { const size_t at = off; off += align256(bytes); return at; };
+  const size_t T = d.T, td = T * d.D * 2, tq = T * d.Qd * 2, tk = T * d.Kd * 2, tf = T * d.F * 2;
+  L.h = take(td); L.q0 = take(tq); L.k0 = take(tk); L.v = take(tk);
+  L.q1 = take(tq); L.k1 = take(tk);                       // after the per-head norm (if any) and the rotary embedding
+  L.rq = take(T * n_q * 4); L.rk = take(T * n_kv * 4);
+  L.o = take(tq); L.lse = take(T * n_q * 4); L.d1 = take(td); L.x1 = take(td);
+  L.rstd1 = take(T * 4); L.rstd2 = take(T * 4);
+  L.h2 = take(td); L.p = take(tf); L.u = take(tf); L.a = take(tf); L.d2 = take(td); L.dy = take(td);
+  L.da = take(tf); L.dp = take(tf); L.du = take(tf);
+  L.dh_a = take(td); L.dh_b = take(td); L.dh_c = take(td); L.dx1 = take(td);
+  L.d_o = take(tq); L.dq = take(tq); L.dk = take(tk); L.dv = take(tk); L.dq0 = take(tq); L.dk0 = take(tk);
+  L.xt = take(static_cast<size_t>(std::max(std::max(d.D, d.F), d.Qd)) * d.Tp * 2);
+  for (int s = 0; s < FAAR_LIN_COUNT; ++s) {
+    int64_t O, K;
+    lin_shape(d, s, O, K);
+    L.fwd_bytes = std::max(L.fwd_bytes, faar_workspace_bytes(FAAR_OP_LINEAR_FORWARD, O, K, d.T, 0));
+    L.step_bytes = std::max(L.step_bytes, faar_workspace_bytes(FAAR_OP_LAYER_STEP, O, K, d.T, FAAR_WS_CHAINED));
+  }
+  L.attn_bytes = std::max(faar_workspace_bytes(FAAR_OP_ATTENTION_FWD, d.Qd, d.Kd, d.T, 0),
+                          faar_workspace_bytes(FAAR_OP_ATTENTION_BWD, d.Qd, d.Kd, d.T, 0));
+  L.loss_bytes = faar_workspace_bytes(FAAR_OP_BLOCK_OUTPUT_LOSS, d.D, 16, d.T, 0);
+  L.fwd_ws = take(L.fwd_bytes); L.step_ws = take(L.step_bytes); L.attn_ws = take(L.attn_bytes); L.loss_ws = take(L.loss_bytes);
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+size_t faar_block_workspace_bytes(const faar_block* blk) {
+  BlockDims d;
+  if (block_dims(blk, d) != FAAR_OK) return 0;
+  return block_layout(d, blk->n_q, blk->n_kv).total;
+}
+
+int faar_block_joint_step(const faar_block* blk, const void* x, const void* y_fp, float mse_scale, float beta,
+                          float lambda_round, const faar_adam* opt, float* block_loss, void* dx, void* ws, size_t ws_bytes,
+                          void* stream) {
+  BlockDims d;
+  if (int e = block_dims(blk, d)) return e;
+  if (!x || !y_fp || !opt || !block_loss || !blk->g_attn || !blk->g_mlp || !blk->cos_t || !blk->sin_t) return FAAR_E_NULL;
+  for (int s = 0; s < FAAR_LIN_COUNT; ++s) {
+    const faar_block_linear& l = blk->lin[s];
+    if (!l.W || !l.s_global || !l.scales || !l.icodes || !l.V || !l.adam_m || !l.adam_u || !l.losses) return FAAR_E_NULL;
+    if (!aligned16(l.W) || !aligned16(l.scales) || !aligned16(l.icodes) || !aligned16(l.V) || !aligned16(l.adam_m) ||
+        !aligned16(l.adam_u))
+      return FAAR_E_ARG;
+  }
+  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale)) return FAAR_E_ARG;
+  if (!(opt->lr >= 0.0f) || !std::isfinite(opt->lr) || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) ||
+      !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) || !std::isfinite(opt->eps) || opt->t < 1)
+    return FAAR_E_ARG;
+  if (!aligned16(x) || !aligned16(y_fp) || !aligned16(dx) || (reinterpret_cast<uintptr_t>(ws) & 255u)) return FAAR_E_ARG;
+  const BlockLayout L = block_layout(d, blk->n_q, blk->n_kv);
+  if (!ws || ws_bytes < L.total) return FAAR_E_WORKSPACE;
+
+  char* base = static_cast<char*>(ws);
+  auto at = [&](size_t off) { return static_cast<void*>(base + off); };
+  auto fl = [&](size_t off) { return reinterpret_cast<float*>(base + off); };
+  const int64_t T = d.T, Hq = blk->n_q, Hk = blk->n_kv, dh = blk->dh;
+  const faar_dtype bf = FAAR_BF16;
+
+  auto forward = [&](int slot, const void* X, void* Y) {
+    int64_t O, K;
+    lin_shape(d, slot, O, K);
+    const faar_block_linear& l = blk->lin[slot];
+    return faar_linear_forward(l.W, blk->wdt, O, K, l.s_global, l.scales, l.V, beta, X, nullptr, T, Y, at(L.fwd_ws), L.fwd_bytes,
+                               stream);
+  };
+  auto backward = [&](int slot, const void* X, const void* dY, void* dX, bool xt_ready) {
+    int64_t O, K;
+    lin_shape(d, slot, O, K);
+    const faar_block_linear& l = blk->lin[slot];
+    const uint32_t flags = FAAR_WS_CHAINED | FAAR_STEP_JOINT | (xt_ready ? FAAR_STEP_XT_READY : 0u);
+    return faar_layer_step(l.W, blk->wdt, O, K, l.s_global, l.scales, l.V, l.adam_m, l.adam_u, X, nullptr, at(L.xt), nullptr,
+                           l.icodes, nullptr, nullptr, T, dY, dX, beta, 0.0f, lambda_round, 0.0f, opt, l.losses, flags,
+                           at(L.step_ws), L.step_bytes, stream);
+  };
+#define FAAR_TRY(call) do { if (int e_ = (call)) return e_; } while (0)
+
+  // ---- forward: attention half
+  FAAR_TRY(faar_rmsnorm_fwd(x, bf, T, d.D, blk->g_attn, blk->eps, at(L.h), fl(L.rstd1), stream));
+  FAAR_TRY(forward(FAAR_LIN_Q, at(L.h), at(L.q0)));
+  FAAR_TRY(forward(FAAR_LIN_K, at(L.h), at(L.k0)));
+  FAAR_TRY(forward(FAAR_LIN_V, at(L.h), at(L.v)));
+  const void *qn = at(L.q0), *kn = at(L.k0);
+  if (d.qk_norm) {
+    FAAR_TRY(faar_rmsnorm_fwd(at(L.q0), bf, T * Hq, dh, blk->g_q, blk->eps, at(L.q1), fl(L.rq), stream));
+    FAAR_TRY(faar_rmsnorm_fwd(at(L.k0), bf, T * Hk, dh, blk->g_k, blk->eps, at(L.k1), fl(L.rk), stream));
+    qn = at(L.q1);
+    kn = at(L.k1);
+  }
+  FAAR_TRY(faar_rope(qn, T, Hq, dh, blk->cos_t, blk->sin_t, blk->S, 0, at(L.q1), stream));   // in place after the norm
+  FAAR_TRY(faar_rope(kn, T, Hk, dh, blk->cos_t, blk->sin_t, blk->S, 0, at(L.k1), stream));
+  FAAR_TRY(faar_attention_fwd(at(L.q1), at(L.k1), at(L.v), blk->n_seq, blk->S, Hq, Hk, dh, d.scale, at(L.o), fl(L.lse),
+                              at(L.attn_ws), L.attn_bytes, stream));
+  FAAR_TRY(forward(FAAR_LIN_O, at(L.o), at(L.d1)));
+  FAAR_TRY(faar_residual_add(x, bf, at(L.d1), T * d.D, at(L.x1), stream));
+  // ---- forward: MLP half and the loss
+  FAAR_TRY(faar_rmsnorm_fwd(at(L.x1), bf, T, d.D, blk->g_mlp, blk->eps, at(L.h2), fl(L.rstd2), stream));
+  FAAR_TRY(forward(FAAR_LIN_GATE, at(L.h2), at(L.p)));
+  FAAR_TRY(forward(FAAR_LIN_UP, at(L.h2), at(L.u)));
+  FAAR_TRY(faar_silu_mul_fwd(at(L.p), at(L.u), T * d.F, at(L.a), stream));
+  FAAR_TRY(forward(FAAR_LIN_DOWN, at(L.a), at(L.d2)));
+  FAAR_TRY(faar_block_output_loss(at(L.x1), bf, at(L.d2), y_fp, bf, T, d.D, mse_scale, nullptr, at(L.dy), block_loss,
+                                  at(L.loss_ws), L.loss_bytes, stream));
+  // ---- backward: MLP half
+  FAAR_TRY(backward(FAAR_LIN_DOWN, at(L.a), at(L.dy), at(L.da), false));
+  FAAR_TRY(faar_silu_mul_bwd(at(L.da), at(L.p), at(L.u), T * d.F, at(L.dp), at(L.du), stream));
+  FAAR_TRY(backward(FAAR_LIN_GATE, at(L.h2), at(L.dp), at(L.dh_a), false));
+  FAAR_TRY(backward(FAAR_LIN_UP, at(L.h2), at(L.du), at(L.dh_b), true));      // h2^T is still in the scratch
+  FAAR_TRY(faar_rmsnorm_bwd(at(L.dh_a), at(L.dh_b), nullptr, at(L.x1), bf, T, d.D, blk->g_mlp, fl(L.rstd2), at(L.dy), at(L.dx1),
+                            stream));
+  // ---- backward: attention half
+  FAAR_TRY(backward(FAAR_LIN_O, at(L.o), at(L.dx1), at(L.d_o), false));
+  FAAR_TRY(faar_attention_bwd(at(L.d_o), at(L.q1), at(L.k1), at(L.v), at(L.o), fl(L.lse), blk->n_seq, blk->S, Hq, Hk, dh,
+                              d.scale, at(L.dq), at(L.dk), at(L.dv), at(L.attn_ws), L.attn_bytes, stream));
+  FAAR_TRY(faar_rope(at(L.dq), T, Hq, dh, blk->cos_t, blk->sin_t, blk->S, 1, at(L.dq), stream));
+  FAAR_TRY(faar_rope(at(L.dk), T, Hk, dh, blk->cos_t, blk->sin_t, blk->S, 1, at(L.dk), stream));
+  const void *dq0 = at(L.dq), *dk0 = at(L.dk);
+  if (d.qk_norm) {
+    FAAR_TRY(faar_rmsnorm_bwd(at(L.dq), nullptr, nullptr, at(L.q0), bf, T * Hq, dh, blk->g_q, fl(L.rq), nullptr, at(L.dq0), stream));
+    FAAR_TRY(faar_rmsnorm_bwd(at(L.dk), nullptr, nullptr, at(L.k0), bf, T * Hk, dh, blk->g_k, fl(L.rk), nullptr, at(L.dk0), stream));
+    dq0 = at(L.dq0);
+    dk0 = at(L.dk0);
+  }
+  FAAR_TRY(backward(FAAR_LIN_Q, at(L.h), dq0, dx ? at(L.dh_a) : nullptr, false));
+  FAAR_TRY(backward(FAAR_LIN_K, at(L.h), dk0, dx ? at(L.dh_b) : nullptr, true));
+  FAAR_TRY(backward(FAAR_LIN_V, at(L.h), at(L.dv), dx ? at(L.dh_c) : nullptr, true));
+  if (dx)
+    FAAR_TRY(faar_rmsnorm_bwd(at(L.dh_a), at(L.dh_b), at(L.dh_c), x, bf, T, d.D, blk->g_attn, fl(L.rstd1), at(L.dx1), dx, stream));
+#undef FAAR_TRY
+  return FAAR_OK;
 }
 
 int faar_stochastic_v(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global,

@@ -372,3 +372,80 @@ def test_joint_step_of_a_whole_block():
         e, ee = nrm(grads[n] - want) / nrm(want), nrm(grads[n] - want_ex) / nrm(want_ex)
         print(f"dV[{n}]: {e:.2e} (vs exact {ee:.2e})", flush=True)
         assert e <= 8e-3 and ee <= 3e-2, n
+
+
+@pytest.mark.parametrize("qk_norm,want_dx", [(True, True), (False, False)])
+def test_block_joint_step_entry_point_matches_the_call_sequence_and_the_oracle(qk_norm, want_dx):
+    """faar_block_joint_step enqueues the documented sequence of calls itself: its updated V, Adam state, losses and dx are
+    compared with the oracle (as the hand-sequenced step above) over two steps, and the run is bit-reproducible."""
+    n_seq, S, D, n_q, n_kv, dh, F = 2, 32, 128, 4, 2, 64, 384
+    T = n_seq * S
+    rng = np.random.default_rng(321)
+    shapes = dict(q=(n_q * dh, D), k=(n_kv * dh, D), v=(n_kv * dh, D), o=(D, n_q * dh), gate=(F, D), up=(F, D), down=(D, F))
+    layers = {n: _layer(O, K, 900 + i) for i, (n, (O, K)) in enumerate(shapes.items())}
+    x = bf(synth.activations(T, D, 39))
+    g1, g2 = (rng.uniform(0.5, 1.5, D).astype(np.float32) for _ in range(2))
+    gq, gk = (rng.uniform(0.5, 1.5, dh).astype(np.float32) for _ in range(2))
+    y_fp = bf(x + rng.standard_normal((T, D)) * 0.3)
+    cos, sin = rope_tables(S, dh)
+    beta, lam, ms, eps = 6.0, 0.01, 1.0 / (T * D), 1e-6
+    hyp = dict(lr=5e-3, b1=0.9, b2=0.999, eps=1e-8)
+    qkn = (gq, gk) if qk_norm else None
+
+    def run():
+        lin = {}
+        for n, (W, sg, sb, V) in layers.items():
+            Wd = dev(W)
+            sgd, scd, _, _ = faar.faar_quant_rtn(Wd)
+            Vd = dev(V, False)
+            O, K = shapes[n]
+            _, _, ic = faar.faar_layer_prepare(Wd, sgd, scd, torch.zeros((T, K), dtype=torch.bfloat16, device="cuda"), None)
+            lin[n] = dict(W=Wd, s_global=sgd, scales=scd, icodes=ic, V=Vd, m=torch.zeros_like(Vd), u=torch.zeros_like(Vd),
+                          losses=torch.zeros(3, dtype=torch.float32, device="cuda"))
+        tc = lambda a: torch.from_numpy(a).cuda()
+        blk = faar.block_description(n_seq, S, D, n_q, n_kv, dh, F, eps, tc(g1), tc(g2), tc(cos), tc(sin), lin,
+                                     g_q=tc(gq) if qk_norm else None, g_k=tc(gk) if qk_norm else None)
+        ws = faar.faar_block_workspace(blk)
+        ws.fill_(0xA5)                                    # whatever the workspace held must not matter
+        out = []
+        for t in (1, 2):
+            loss, dx = faar.faar_block_joint_step(blk, dev(x), dev(y_fp), ms, beta, lam, hyp["lr"], hyp["b1"], hyp["b2"], hyp["eps"],
+                                                  t, ws, want_dx=want_dx)
+            torch.cuda.synchronize()
+            out.append((loss.clone(), None if dx is None else dx.clone(), {n: lin[n]["V"].clone() for n in lin},
+                        {n: lin[n]["m"].clone() for n in lin}, {n: lin[n]["losses"].clone() for n in lin}))
+        return out
+
+    first, again = run(), run()
+    for a, b in zip(first, again):                        # bit-reproducible
+        assert torch.equal(a[0], b[0]) and (a[1] is None or torch.equal(a[1], b[1]))
+        assert all(torch.equal(a[2][n], b[2][n]) and torch.equal(a[3][n], b[3][n]) for n in layers)
+
+    # the oracle, step by step (its V updated by its own Adam, re-synchronised to the GPU's V after each step)
+    attn = lambda Ls: {n: Ls[n] for n in ("q", "k", "v", "o")}
+    mlp = lambda Ls: {n: Ls[n] for n in ("gate", "up", "down")}
+    cur = dict(layers)
+    nrm = np.linalg.norm
+    for step, (loss, dx, Vs, ms_, losses) in enumerate(first, start=1):
+        a0 = bo.attn_block_step(x, g1, eps, attn(cur), n_seq, n_q, n_kv, dh, cos, sin, beta, lam, d_out=np.zeros((T, D)), qk_norm=qkn,
+                                bf16_storage=True)
+        m = bo.mlp_block_step(bf(a0["y"]), g2, eps, mlp(cur), y_fp, ms, beta, lam, bf16_storage=True)
+        a = bo.attn_block_step(x, g1, eps, attn(cur), n_seq, n_q, n_kv, dh, cos, sin, beta, lam, d_out=m["dx"], qk_norm=qkn,
+                               bf16_storage=True)
+        assert loss.item() == pytest.approx(m["L_block"], rel=5e-3), step
+        if dx is not None:
+            near(dx, a["dx"], f"dx step {step}", norm=8e-3, elem=0.2)
+        for n in layers:
+            ref = (m if n in ("gate", "up", "down") else a)
+            assert host(losses[n])[1] == pytest.approx(ref["L_round"][n], rel=1e-5), (step, n)
+            if step == 1:                                 # zero initial Adam state: m = (1 - beta1) g
+                grad = host(ms_[n]) / (1 - hyp["b1"])
+                e = nrm(grad - ref["dV"][n]) / nrm(ref["dV"][n])
+                print(f"step 1 dV[{n}]: {e:.2e}", flush=True)
+                assert e <= 8e-3, n
+        cur = {n: (layers[n][0], layers[n][1], layers[n][2], host(Vs[n]).astype(np.float32)) for n in layers}
+    # the second step really moved on: V changed between the steps, by at most lr per step
+    for n in layers:
+        dv1 = host(first[0][2][n]) - layers[n][3]
+        dv2 = host(first[1][2][n]) - host(first[0][2][n])
+        assert 0 < np.abs(dv1).max() <= hyp["lr"] * 1.001 and 0 < np.abs(dv2).max() <= hyp["lr"] * 1.001
