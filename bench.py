@@ -12,7 +12,8 @@ command line is one optimisation step of every linear; value = 7 K / elapsed (li
 
 Other workloads (--workload): one linear of the Llama3-1B- / Qwen3-1.7B- / Llama3-8B-shaped blocks by name;
 qwen_block_chained (the seven linears at 16384 tokens with dY supplied and dX produced); qwen_mlp_joint (one joint
-step of the MLP half of the block: norm, three linears, gate, residual, block-output loss, and back); qwen_pack_sweep
+step of the MLP half of the block: norm, three linears, gate, residual, block-output loss, and back); qwen_block_joint
+(one joint step of the whole block, attention half included, by one faar_block_joint_step call); qwen_pack_sweep
 (quantise / initialise / harden+pack all 196 weight tensors of the model); stage2_losses; gemm_ceiling (what
 bounds the GEMM main loop: the loop with only its matrix instructions, with only its copies, and whole, with the
 clock the compute units ran at).
@@ -741,6 +742,149 @@ def run_mlp_joint(args) -> dict:
     return out
 
 
+def run_block_joint(args) -> dict:
+    """One joint step of a whole Qwen3-1.7B-shaped block at T = 16384 (32 sequences of 512 tokens): RMSNorm, q / k / v
+    projections, per-head norm, rotary embedding, causal grouped-query attention (16 query heads on 8 key / value heads of
+    128), output projection, residual, RMSNorm, gated-SiLU MLP, residual, squared error against the full-precision block's
+    output; then the gradient back through all of it into the rounding variables of the seven linears (one Adam update
+    each) and into the block's input.  One call of faar_block_joint_step per step; 21 GEMMs.  `value` counts linear-layer
+    steps (seven per block step)."""
+    import numpy as np
+    import torch
+
+    import paper_2603_22370_amd as faar
+    from paper_2603_22370_amd import binding as fb
+    from workloads import synth
+
+    n_seq, S, D, n_q, n_kv, dh, F = 32, 512, 2048, 16, 8, 128, 6144
+    T = n_seq * S
+    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    beta, eps, ms_scale = 16.0, 1e-6, 1.0 / (T * D)
+    shapes = dict(q=(n_q * dh, D), k=(n_kv * dh, D), v=(n_kv * dh, D), o=(D, n_q * dh), gate=(F, D), up=(F, D), down=(D, F))
+    x_h = synth.activations(T, D, 51)
+    x = torch.from_numpy(x_h).cuda().to(torch.bfloat16)
+    ones_d, ones_h = torch.ones(D, dtype=torch.float32, device="cuda"), torch.ones(dh, dtype=torch.float32, device="cuda")
+    inv = 1.0e6 ** (-np.arange(dh // 2) * 2.0 / dh)                    # rotary base of the Qwen3 models
+    ang = np.arange(S)[:, None] * inv[None, :]
+    cos_h, sin_h = np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+    cos_t, sin_t = torch.from_numpy(cos_h).cuda(), torch.from_numpy(sin_h).cuda()
+    lin, W_h = {}, {}
+    for i, (n, (O, K)) in enumerate(shapes.items()):
+        W_h[n] = synth.student_t_weight(O, K, 60 + i)
+        W = torch.from_numpy(W_h[n]).cuda().to(torch.bfloat16)
+        sg, sc, _, _ = faar.faar_quant_rtn(W)
+        V, _ = faar.faar_init_v(W, sg, sc)
+        _, _, ic = faar.faar_layer_prepare(W, sg, sc, torch.zeros((T, K), dtype=torch.bfloat16, device="cuda"), None)
+        lin[n] = dict(W=W, s_global=sg, scales=sc, icodes=ic, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V),
+                      losses=torch.zeros(3, dtype=torch.float32, device="cuda"))
+    # the full-precision block's output, from library ops on the unquantised weights (input synthesis, outside the path)
+    with torch.no_grad():
+        def norm(t, width):
+            tf = t.float()
+            return (tf * torch.rsqrt((tf * tf).mean(-1, keepdim=True) + eps)).to(torch.bfloat16)
+
+        def rot(t, H):
+            th = t.float().view(T, H, dh)
+            c = cos_t.repeat(n_seq, 2)[:, None, :]
+            s_ = sin_t.repeat(n_seq, 2)[:, None, :]
+            half = torch.cat([-th[..., dh // 2:], th[..., :dh // 2]], dim=-1)
+            return (th * c + half * s_).to(torch.bfloat16).view(T, H * dh)
+
+        h = norm(x, D)
+        q, k, v = (h @ lin[n]["W"].T for n in ("q", "k", "v"))
+        q, k = rot(norm(q.view(T * n_q, dh), dh).view(T, -1), n_q), rot(norm(k.view(T * n_kv, dh), dh).view(T, -1), n_kv)
+        sp = lambda t, H: t.view(n_seq, S, H, dh).permute(0, 2, 1, 3)
+        o = torch.nn.functional.scaled_dot_product_attention(sp(q, n_q), sp(k, n_kv).repeat_interleave(n_q // n_kv, dim=1),
+                                                             sp(v, n_kv).repeat_interleave(n_q // n_kv, dim=1), is_causal=True)
+        x1 = (x.float() + (o.permute(0, 2, 1, 3).reshape(T, n_q * dh) @ lin["o"]["W"].T).float()).to(torch.bfloat16)
+        h2 = norm(x1, D)
+        a = (torch.nn.functional.silu((h2 @ lin["gate"]["W"].T).float()) * (h2 @ lin["up"]["W"].T).float()).to(torch.bfloat16)
+        y_fp = (x1.float() + (a @ lin["down"]["W"].T).float()).to(torch.bfloat16)
+        del h, q, k, v, o, x1, h2, a
+    blk = faar.block_description(n_seq, S, D, n_q, n_kv, dh, F, eps, ones_d, ones_d.clone(), cos_t, sin_t, lin, g_q=ones_h, g_k=ones_h.clone())
+    ws = faar.faar_block_workspace(blk)
+    loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+    dx_keep = {}
+    state = {"t": 0}
+
+    def block_step():
+        state["t"] += 1
+        _, dx_keep["dx"] = faar.faar_block_joint_step(blk, x, y_fp, ms_scale, beta, LAM, LR, 0.9, 0.999, 1e-8, state["t"], ws,
+                                                      block_loss=loss)
+
+    for _ in range(warmup):
+        block_step()
+    torch.cuda.synchronize()
+    first_loss = float(loss.item())
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        block_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    timer = KernelTimer()
+    kernels = {}
+    flops_mlp = 2.0 * T * F * D
+    for kname, kid, fl, what in [("gemm_fwd", fb.K_GEMM_FWD, flops_mlp, "down_proj forward"), ("gemm_dw", fb.K_GEMM_DW, 2.0 * T * n_kv * dh * D, "v_proj dW"),
+                                 ("gemm_dx", fb.K_GEMM_DX, 2.0 * T * n_kv * dh * D, "v_proj dX"), ("bwd_adam", fb.K_BWD_ADAM, 0.0, "v_proj"),
+                                 ("attention_fwd", fb.K_ATTENTION_FWD, 2.0 * n_seq * n_q * S * S * dh, "causal: half the S x S scores count"),
+                                 ("attention_bwd", fb.K_ATTENTION_BWD, 5.0 * n_seq * n_q * S * S * dh, "three kernels; causal half of five S x S x dh products")]:
+        ms = timer.time(kid, lambda i: block_step(), 4)     # the events keep the last bracketed launch of a block step
+        row = {"ms": round(ms, 5), "launch": what}
+        if fl:
+            row["tflops"] = round(fl / (ms * 1e-3) / 1e12, 1)
+            row["frac"] = round(fl / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)
+        kernels[kname] = row
+    gemm_flops = 3 * 2.0 * T * (2 * n_q * dh * D + 2 * n_kv * dh * D + 3 * F * D)
+    attn_flops = 7.0 * n_seq * n_q * S * S * dh
+    dom = kernels["gemm_fwd"]
+    out = {
+        "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(7 * steps / elapsed, 2), "unit": "steps/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "qwen_block_joint: one joint step of a whole Qwen3-1.7B-shaped block (attention half with per-head norm, "
+                               "rotary embedding and causal grouped-query attention 16/8 heads of 128; gated-SiLU MLP 6144; residuals; "
+                               "block-output MSE), 32 sequences of 512 tokens, forward + backward + Adam on the rounding variables of "
+                               "all seven linears (21 GEMMs) by one faar_block_joint_step call; value = linear-layer steps/s",
+                   "T": T, "n_seq": n_seq, "S": S, "D": D, "F": F, "n_q": n_q, "n_kv": n_kv, "dh": dh, "linears": 7},
+        "block_step_tflops": round((gemm_flops + attn_flops) / (elapsed / steps) / 1e12, 1),
+        "block_loss": {"after_warmup": first_loss, "at_end": float(loss.item())},
+        "roofline": {"kernel": "gemm_fwd (down_proj forward, 16384 x 2048 x 6144)", "bound": "mfma", "achieved": dom["tflops"],
+                     "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom["frac"], "traffic": None, "launch_ms": dom["ms"]},
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        # the oracle's joint block step on one and on two sequences of 512 tokens; its cost is a part per weight plus a part per
+        # sequence, extrapolated linearly to 32 sequences and labelled so
+        from oracle import block_oracle as bo
+        from oracle import faar_oracle as fo
+        layers = {}
+        for n in lin:
+            qh = fo.quant_rtn(W_h[n], True)
+            layers[n] = (W_h[n], qh["s_global"], qh["scales"], fo.init_v(W_h[n], qh["s_global"], qh["scales"])["V"])
+        attn_l, mlp_l = {n: layers[n] for n in ("q", "k", "v", "o")}, {n: layers[n] for n in ("gate", "up", "down")}
+        one = np.ones(D)
+        times = {}
+        for ns in (1, 2):
+            Ts = ns * S
+            xs, ys = x_h[:Ts].astype(np.float64), y_fp[:Ts].float().cpu().numpy()
+            c0 = time.perf_counter()
+            a0 = bo.attn_block_step(xs, one, eps, attn_l, ns, n_q, n_kv, dh, cos_h, sin_h, beta, LAM, d_out=np.zeros((Ts, D)),
+                                    qk_norm=(np.ones(dh), np.ones(dh)), bf16_storage=True)
+            m = bo.mlp_block_step(a0["y"], one, eps, mlp_l, ys, 1.0 / (Ts * D), beta, LAM, bf16_storage=True)
+            bo.attn_block_step(xs, one, eps, attn_l, ns, n_q, n_kv, dh, cos_h, sin_h, beta, LAM, d_out=m["dx"],
+                               qk_norm=(np.ones(dh), np.ones(dh)), bf16_storage=True)
+            times[ns] = time.perf_counter() - c0
+        per_seq = max(times[2] - times[1], 0.0)
+        t_full = times[1] + per_seq * (n_seq - 1)
+        out["cpu_baseline"] = {"value": round(7 / t_full, 5), "unit": "steps/s", "kind": "oracle",
+                               "sample": f"joint block step of the oracle (gradients only, no Adam; its attention half evaluated twice) on 1 "
+                                         f"sequence ({times[1]:.1f} s) and 2 sequences ({times[2]:.1f} s) of 512 tokens, extrapolated linearly "
+                                         f"to 32 sequences ({t_full:.0f} s per block step)",
+                               **host_description()}
+    return out
+
+
 def run_pack_sweep(args) -> dict:
     """Set-up and tear-down over every linear of a Qwen3-1.7B-shaped model (28 layers x 7 linears, 1.409 G weights,
     each tensor in memory of its own): quantisation, V initialisation and hardening + packing, each as ONE batched call
@@ -969,7 +1113,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_layer",
-                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_mlp_joint", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
+                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_mlp_joint", "qwen_block_joint", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
@@ -993,7 +1137,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_mlp_joint": run_mlp_joint,
+    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_mlp_joint": run_mlp_joint, "qwen_block_joint": run_block_joint,
                "qwen_pack_sweep": run_pack_sweep,
                "stage2_losses": run_stage2, "gemm_ceiling": run_gemm_ceiling}
     out = runners.get(args.workload, run_linear)(args)

@@ -100,7 +100,9 @@ enum {
   FAAR_K_HARDEN_PACK = 8,
   FAAR_K_STAGE2_KL = 9,      /* the three launches of faar_stage2_losses, bracketed together */
   FAAR_K_GEMM_C = 10,        /* Y_fp - X_q W^T of faar_layer_prepare (faar_gemm_plan only: it has no time bracket) */
-  FAAR_K_GEMM_FWD = 11       /* X_q W_q^T of faar_linear_forward */
+  FAAR_K_GEMM_FWD = 11,      /* X_q W_q^T of faar_linear_forward */
+  FAAR_K_ATTENTION_FWD = 12, /* the attention kernel of faar_attention_fwd (not the transpose before it) */
+  FAAR_K_ATTENTION_BWD = 13  /* the three kernels of faar_attention_bwd (not the transposes before them) */
 };
 
 /* GEMM kernel variants, as reported by faar_gemm_plan */

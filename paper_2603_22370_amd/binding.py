@@ -196,7 +196,7 @@ def faar_dw_split(O: int, K: int, T: int) -> int:
     return int(lib().faar_dw_split(O, K, T))
 
 
-K_GEMM_C, K_GEMM_FWD = 10, 11
+K_GEMM_C, K_GEMM_FWD, K_ATTENTION_FWD, K_ATTENTION_BWD = 10, 11, 12, 13
 GEMM_KINDS = ("generic", "L", "M", "S", "L64", "M64")
 
 

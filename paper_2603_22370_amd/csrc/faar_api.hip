@@ -176,7 +176,7 @@ int faar_version(void) { return 100; }
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
-  if (which < FAAR_K_NONE || which > FAAR_K_GEMM_FWD || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
+  if (which < FAAR_K_NONE || which > FAAR_K_ATTENTION_BWD || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
   g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
   return FAAR_OK;
@@ -237,10 +237,10 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
       return align256((size_t)O * K * 2);   // W_q in bf16
     case FAAR_OP_ATTENTION_FWD:             // O = n_q * dh, K = n_kv * dh: V transposed
       if (T <= 0) return 0;
-      return align256((size_t)K * padded_tokens(T) * 2);
+      return align256((size_t)K * (padded_tokens(T) + 64) * 2);
     case FAAR_OP_ATTENTION_BWD:             // Q, dO, K transposed; one float per head and query (at most O / 64 heads)
       if (T <= 0) return 0;
-      return align256((size_t)O * padded_tokens(T) * 2) * 2 + align256((size_t)K * padded_tokens(T) * 2) +
+      return align256((size_t)O * (padded_tokens(T) + 64) * 2) * 2 + align256((size_t)K * (padded_tokens(T) + 64) * 2) +
              align256((size_t)(O / 64) * T * sizeof(float));
     case FAAR_OP_BLOCK_OUTPUT_LOSS:         // O = D (row length), T rows
       if (T <= 0 || O % 8 != 0) return 0;
@@ -611,6 +611,11 @@ int faar_rope(const void* x, int64_t T, int64_t H, int64_t dh, const float* cos_
                                 static_cast<hipStream_t>(stream)));
 }
 
+// Row pitch of the transposed copies the attention kernels read column blocks of: the padded token count plus 64 entries,
+// so that consecutive rows (one per head-dimension index, all read by one load instruction) do not sit a power of two apart
+// and collide in the same cache sets and memory channels
+static int64_t attention_pitch(int64_t T) { return padded_tokens(T) + 64; }
+
 static int check_attention(int64_t n_seq, int64_t S, int64_t n_q, int64_t n_kv, int64_t dh, float scale) {
   if (n_seq <= 0 || S <= 0 || S % 32 != 0 || S > (1 << 20) || n_q <= 0 || n_kv <= 0 || n_q % n_kv != 0 || n_q > 4096) return FAAR_E_SHAPE;
   if (dh != 64 && dh != 128) return FAAR_E_SHAPE;
@@ -624,11 +629,12 @@ int faar_attention_fwd(const void* q, const void* k, const void* v, int64_t n_se
   if (!q || !k || !v || !o || !lse) return FAAR_E_NULL;
   if (int e = check_attention(n_seq, S, n_q, n_kv, dh, scale)) return e;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(ws)) return FAAR_E_ARG;
-  const int64_t T = n_seq * S, Tp = padded_tokens(T);
+  const int64_t T = n_seq * S, Tp = attention_pitch(T);
   if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_ATTENTION_FWD, n_q * dh, n_kv * dh, T, 0)) return FAAR_E_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   bf16_t* vt = static_cast<bf16_t*>(ws);
   if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(v), T, n_kv * dh, vt, Tp, st))) return e;
+  Bracket b(FAAR_K_ATTENTION_FWD, st);
   return hip_status(launch_attention_fwd(static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k), vt, n_seq, S, n_q, n_kv, dh,
                                          Tp, scale, static_cast<bf16_t*>(o), lse, st));
 }
@@ -641,7 +647,7 @@ int faar_attention_bwd(const void* d_o, const void* q, const void* k, const void
   if (!aligned16(d_o) || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dq) ||
       !aligned16(dk) || !aligned16(dv) || !aligned16(ws))
     return FAAR_E_ARG;
-  const int64_t T = n_seq * S, Tp = padded_tokens(T);
+  const int64_t T = n_seq * S, Tp = attention_pitch(T);
   if (!ws || ws_bytes < faar_workspace_bytes(FAAR_OP_ATTENTION_BWD, n_q * dh, n_kv * dh, T, 0)) return FAAR_E_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(stream);
   Carver c(ws);
@@ -652,6 +658,7 @@ int faar_attention_bwd(const void* d_o, const void* q, const void* k, const void
   if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(q), T, n_q * dh, qt, Tp, st))) return e;
   if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(d_o), T, n_q * dh, dot, Tp, st))) return e;
   if (int e = hip_status(launch_transpose_bf16(static_cast<const bf16_t*>(k), T, n_kv * dh, kt, Tp, st))) return e;
+  Bracket b(FAAR_K_ATTENTION_BWD, st);
   return hip_status(launch_attention_bwd(static_cast<const bf16_t*>(d_o), static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                                          static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(o), lse, qt, kt, dot, delta, n_seq,
                                          S, n_q, n_kv, dh, Tp, scale, static_cast<bf16_t*>(dq), static_cast<bf16_t*>(dk),

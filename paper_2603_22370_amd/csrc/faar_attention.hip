@@ -85,94 +85,198 @@ __device__ __forceinline__ bool wave_coords(int64_t total, int blocks, int heads
   return true;
 }
 
-// o = softmax(q k^T scale, causal) v and lse = log sum exp of the scaled scores per query ([n_q][T])
+// 2^x by the hardware instruction alone: the arguments here are at most a few units above zero and results far below one
+// may flush to zero
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// o = softmax(q k^T scale, causal) v and lse = log sum exp of the scaled scores per query ([n_q][T]).
+// The running maximum of a query's scores is only raised when a block exceeds it by more than 2^kLazy (the probabilities are
+// then at most 2^kLazy instead of 1, harmless in float32 and bf16): the accumulators are rescaled in a branch that is
+// rarely taken after the first blocks, and otherwise only matrix instructions touch them.
+constexpr float kLazy = 8.0f;
+
+// A workgroup of four wavefronts shares the keys and values of a block through LDS: its 256 threads copy the block's
+// [32 keys][dh] tile of k and [dh][32 keys] tile of the transposed v with row-contiguous 16-byte loads (one block ahead, held
+// in registers while the current block is worked on), so the cache sees whole rows once per workgroup instead of 16 partial
+// lines per matrix-operand load of every wavefront.  The 16-byte chunks of a row are stored XOR-swizzled by the row so that
+// the operand reads (16 rows at the same chunk index) spread over the banks.
+template <int DH>
+struct KvTile {
+  static constexpr int CPRK = DH / 8;                 // 16-byte chunks per row of the k tile
+  static constexpr int KCH = 32 * CPRK / 256;         // chunks of the k tile per thread
+  static constexpr int VCH = DH * 4 / 256;            // chunks of the v^T tile per thread (rows of 32 keys = 4 chunks)
+  static constexpr int ELEMS = 32 * DH;               // per tile
+
+  static __device__ __forceinline__ void load(uint4 (&kreg)[KCH], uint4 (&vreg)[VCH], const bf16_t* __restrict__ K,
+                                              const bf16_t* __restrict__ Vt, int64_t krow0, int64_t ldk, int64_t kcol0,
+                                              int64_t vrow0, int64_t Tp, int64_t vcol0, int tid) {
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+      const int i = tid + 256 * j, row = i / CPRK, ch = i % CPRK;
+      kreg[j] = *reinterpret_cast<const uint4*>(K + (krow0 + row) * ldk + kcol0 + ch * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < VCH; ++j) {
+      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
+      vreg[j] = *reinterpret_cast<const uint4*>(Vt + (vrow0 + row) * Tp + vcol0 + ch * 8);
+    }
+  }
+  static __device__ __forceinline__ void store(const uint4 (&kreg)[KCH], const uint4 (&vreg)[VCH], bf16_t* kt, bf16_t* vt, int tid) {
+#pragma unroll
+    for (int j = 0; j < KCH; ++j) {
+      const int i = tid + 256 * j, row = i / CPRK, ch = i % CPRK;
+      *reinterpret_cast<uint4*>(kt + row * DH + ((ch ^ (row % CPRK)) * 8)) = kreg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < VCH; ++j) {
+      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
+      *reinterpret_cast<uint4*>(vt + row * 32 + ((ch ^ ((row / 4) % 4)) * 8)) = vreg[j];
+    }
+  }
+  // matrix operands out of the tiles: k rows (tile kt, dh chunk group ks) and v^T rows (tile dt; keys 4g.. and 16+4g..)
+  static __device__ __forceinline__ bf16x8 k_frag(const bf16_t* kt, int tile, int ks, int n, int g) {
+    const int row = tile * 16 + n, ch = ks * 4 + g;
+    return *reinterpret_cast<const bf16x8*>(kt + row * DH + ((ch ^ (row % CPRK)) * 8));
+  }
+  static __device__ __forceinline__ bf16x8 v_frag(const bf16_t* vt, int tile, int n, int g) {
+    const int row = tile * 16 + n, sw = (row / 4) % 4;
+    Frag f;
+    f.h[0] = *reinterpret_cast<const uint2*>(vt + row * 32 + (((g / 2) ^ sw) * 8) + (g % 2) * 4);
+    f.h[1] = *reinterpret_cast<const uint2*>(vt + row * 32 + (((2 + g / 2) ^ sw) * 8) + (g % 2) * 4);
+    return f.v;
+  }
+};
+
+template <int DH>
+struct FwdState {
+  static constexpr int KS = DH / 32, DT = DH / 16;
+  bf16x8 qf[2][KS];
+  f32x4 oacc[2][DT];
+  float m[2], l[2];     // reference maximum (raw score units) and this lane's share of the denominator, per query tile
+};
+
+template <int DH, bool kDiagonal>
+__device__ __forceinline__ void fwd_block(FwdState<DH>& st, const bf16_t* kt_lds, const bf16_t* vt_lds, float c, int n, int g) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  f32x4 s[2][2];   // [query tile][key tile]: rows = keys 4g .. 4g+3 of the tile, column = query n
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    bf16x8 kf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kf[ks] = KvTile<DH>::k_frag(kt_lds, kt, ks, n, g);
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) a = mfma(kf[ks], st.qf[qt][ks], a);
+      s[qt][kt] = a;
+    }
+  }
+  float mx[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    float v = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (kDiagonal && kt * 16 + 4 * g + r > qt * 16 + n) s[qt][kt][r] = -INFINITY;   // a key after the query
+        v = fmaxf(v, s[qt][kt][r]);
+      }
+    mx[qt] = group_max(v);   // finite: a query's own position is never masked
+  }
+  if (__any(mx[0] * c > st.m[0] * c + kLazy || mx[1] * c > st.m[1] * c + kLazy)) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      const float nm = fmaxf(st.m[qt], mx[qt]);
+      const float alpha = fast_exp2((st.m[qt] - nm) * c);
+      st.m[qt] = nm;
+      st.l[qt] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) st.oacc[qt][dt] *= alpha;
+    }
+  }
+  bf16x8 pf[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float off = -st.m[qt] * c;
+    float ps = 0.0f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float p = fast_exp2(fmaf(s[qt][kt][r], c, off));
+        s[qt][kt][r] = p;
+        ps += p;
+      }
+    st.l[qt] += ps;       // this lane's keys only; the four lanes of a query add up at the end
+    pf[qt] = pack_tiles(s[qt][0], s[qt][1]);
+  }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const bf16x8 vf = KvTile<DH>::v_frag(vt_lds, dt, n, g);
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) st.oacc[qt][dt] = mfma(vf, pf[qt], st.oacc[qt][dt]);
+  }
+}
+
+// workgroup -> (sequence, head, group of 128 query positions); wavefront w of it owns positions 32w .. 32w+31 of the group
 template <int DH>
 __global__ void __launch_bounds__(256)
 k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
-           int64_t total, bf16_t* __restrict__ O, float* __restrict__ lse) {
+           bf16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
-  int64_t b;
-  int head, qb;
-  if (!wave_coords(total, d.S / 32, d.n_q, b, head, qb)) return;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][KvTile<DH>::ELEMS];   // [stage][k, v^T]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
+  const int blocks = d.S / 32, groups = (blocks + 3) / 4;
+  const int grp = blockIdx.x % groups;
+  const int head = (blockIdx.x / groups) % d.n_q;
+  const int64_t b = blockIdx.x / groups / d.n_q;
   const int kvh = head / (d.n_q / d.n_kv);
   const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int qb = grp * 4 + wave;                   // this wavefront's block of 32 positions
+  const bool active = qb < blocks;                 // the last group of a sequence may be short
+  const int last = min(grp * 4 + 3, blocks - 1);   // last key block any wavefront of the group needs
   const int p0 = qb * 32;
   const float c = d.scale * kLog2e;     // scores in units of log 2
 
-  bf16x8 qf[2][KS];
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qf[qt][ks] = load_frag16(Q + (t0 + p0 + qt * 16 + n) * ldq + head * DH + ks * 32 + 8 * g);
-  f32x4 oacc[2][DT];
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-  float m[2] = {-INFINITY, -INFINITY}, l[2] = {0.0f, 0.0f};
-
-  for (int kb = 0; kb <= qb; ++kb) {
-    const int k0 = kb * 32;
-    f32x4 s[2][2];   // [query tile][key tile]: rows = keys 4g .. 4g+3 of the tile, column = query n
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      bf16x8 kf[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) kf[ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) a = mfma(kf[ks], qf[qt][ks], a);
-        s[qt][kt] = a;
-      }
-    }
-    bf16x8 pf[2];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      float mx = m[qt];
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float x = s[qt][kt][r] * c;
-          if (kb == qb && kt * 16 + 4 * g + r > qt * 16 + n) x = -INFINITY;   // a key after the query
-          s[qt][kt][r] = x;
-          mx = fmaxf(mx, x);
-        }
-      mx = group_max(mx);   // finite: a query's own position is never masked
-      const float alpha = exp2f(m[qt] - mx);
-      m[qt] = mx;
-      float ps = 0.0f;
-#pragma unroll
-      for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float p = exp2f(s[qt][kt][r] - mx);
-          s[qt][kt][r] = p;
-          ps += p;
-        }
-      l[qt] = l[qt] * alpha + ps;     // this lane's keys only; the four lanes of a query add up at the end
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) oacc[qt][dt] *= alpha;
-      pf[qt] = pack_tiles(s[qt][0], s[qt][1]);
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const bf16x8 vf = load_frag_split(Vt + ((int64_t)kvh * DH + dt * 16 + n) * d.Tp + t0 + k0 + 4 * g);
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) oacc[qt][dt] = mfma(vf, pf[qt], oacc[qt][dt]);
-    }
-  }
+  FwdState<DH> st;
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
-    const float lt = group_sum(l[qt]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      st.qf[qt][ks] = active ? load_frag16(Q + (t0 + p0 + qt * 16 + n) * ldq + head * DH + ks * 32 + 8 * g) : bf16x8{};
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) st.oacc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    st.m[qt] = -INFINITY;
+    st.l[qt] = 0.0f;
+  }
+  typedef KvTile<DH> Tile;
+  uint4 kreg[Tile::KCH], vreg[Tile::VCH];
+  Tile::load(kreg, vreg, K, Vt, t0, ldk, (int64_t)kvh * DH, (int64_t)kvh * DH, d.Tp, t0, tid);
+  Tile::store(kreg, vreg, lds[0][0], lds[0][1], tid);
+  __syncthreads();
+  for (int kb = 0; kb <= last; ++kb) {
+    const int cur = kb & 1;
+    // past the last block the loads repeat it (unused): the loop body stays free of divergent control around them
+    const int64_t nxt = t0 + (kb < last ? kb + 1 : kb) * 32;
+    Tile::load(kreg, vreg, K, Vt, nxt, ldk, (int64_t)kvh * DH, (int64_t)kvh * DH, d.Tp, nxt, tid);
+    if (active) {
+      if (kb < qb) fwd_block<DH, false>(st, lds[cur][0], lds[cur][1], c, n, g);
+      else if (kb == qb) fwd_block<DH, true>(st, lds[cur][0], lds[cur][1], c, n, g);   // the queries' own positions
+    }
+    Tile::store(kreg, vreg, lds[cur ^ 1][0], lds[cur ^ 1][1], tid);   // that stage was last read one block ago
+    __syncthreads();
+  }
+  if (!active) return;
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float lt = group_sum(st.l[qt]);
     const float inv = 1.0f / lt;
     const int64_t t = t0 + p0 + qt * 16 + n;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) store4_bf16(O + t * ldq + head * DH + dt * 16 + 4 * g, oacc[qt][dt], inv);
-    if (g == 0) lse[(int64_t)head * d.T + t] = m[qt] * kLn2 + logf(lt);
+    for (int dt = 0; dt < DT; ++dt) store4_bf16(O + t * ldq + head * DH + dt * 16 + 4 * g, st.oacc[qt][dt], inv);
+    if (g == 0) lse[(int64_t)head * d.T + t] = st.m[qt] * c * kLn2 + logf(lt);
   }
 }
 
@@ -406,11 +510,11 @@ hipError_t launch_rope(const bf16_t* X, int64_t T, int64_t H, int64_t dh, const 
 hipError_t launch_attention_fwd(const bf16_t* Q, const bf16_t* K, const bf16_t* Vt, int64_t n_seq, int64_t S, int64_t n_q,
                                 int64_t n_kv, int64_t dh, int64_t Tp, float scale, bf16_t* O, float* lse, hipStream_t st) {
   const AttnDims d{static_cast<int>(S), static_cast<int>(n_q), static_cast<int>(n_kv), n_seq * S, Tp, scale};
-  const int64_t total = n_seq * n_q * (S / 32);
+  const int64_t groups = n_seq * n_q * ((S / 32 + 3) / 4);    // one workgroup per 128 query positions of a head and sequence
   if (dh == 128)
-    hipLaunchKernelGGL(k_attn_fwd<128>, dim3(wave_blocks(total)), dim3(256), 0, st, Q, K, Vt, d, total, O, lse);
+    hipLaunchKernelGGL(k_attn_fwd<128>, dim3(static_cast<unsigned>(groups)), dim3(256), 0, st, Q, K, Vt, d, O, lse);
   else
-    hipLaunchKernelGGL(k_attn_fwd<64>, dim3(wave_blocks(total)), dim3(256), 0, st, Q, K, Vt, d, total, O, lse);
+    hipLaunchKernelGGL(k_attn_fwd<64>, dim3(static_cast<unsigned>(groups)), dim3(256), 0, st, Q, K, Vt, d, O, lse);
   return hipGetLastError();
 }
 

@@ -214,7 +214,7 @@ def test_attention_calls_reject_bad_arguments_without_a_gpu():
     n_q, n_kv, dh, S, n_seq = 4, 2, 128, 64, 2
     wf = fb.faar_workspace_bytes(fb.OP_ATTENTION_FWD, n_q * dh, n_kv * dh, n_seq * S)
     wb = fb.faar_workspace_bytes(fb.OP_ATTENTION_BWD, n_q * dh, n_kv * dh, n_seq * S)
-    assert wf >= n_kv * dh * 128 * 2 and wb >= (2 * n_q + n_kv) * dh * 128 * 2 + n_q * 128 * 4
+    assert wf >= n_kv * dh * 192 * 2 and wb >= (2 * n_q + n_kv) * dh * 192 * 2 + n_q * 128 * 4
     assert fb.faar_workspace_bytes(fb.OP_ATTENTION_FWD, n_q * dh, n_kv * dh, 0) == 0
     f = L.faar_attention_fwd
     assert f(p, p, nul, n_seq, S, n_q, n_kv, dh, 0.1, p, p, p, wf, nul) == -1
@@ -238,3 +238,48 @@ def test_attention_calls_reject_bad_arguments_without_a_gpu():
     assert a(p, 3, p, 64, p, nul) == -3
     assert a(p, 1, p, 60, p, nul) == -2
     assert a(p, 1, odd, 64, p, nul) == -6
+
+
+def test_block_joint_step_validates_its_description_without_a_gpu():
+    L = fb.lib()
+    p, nul = 0x1000, None
+
+    def block(**kw):
+        b = fb.faar_block()
+        b.n_seq, b.S, b.D, b.n_q, b.n_kv, b.dh, b.F = 2, 64, 256, 4, 2, 64, 512
+        b.eps, b.attn_scale, b.wdt = 1e-6, 0.0, 1
+        b.g_attn = b.g_mlp = b.cos_t = b.sin_t = p
+        for i in range(7):
+            for f, _ in fb.faar_block_linear._fields_:
+                setattr(b.lin[i], f, p)
+        for k, v in kw.items():
+            setattr(b, k, v)
+        return b
+
+    good = block()
+    n = L.faar_block_workspace_bytes(ctypes.byref(good))
+    T = 128
+    assert n > T * (6 * 512 + 12 * 256) * 2                     # at least the activations it keeps
+    assert L.faar_block_workspace_bytes(ctypes.byref(block(S=48))) == 0
+    assert L.faar_block_workspace_bytes(ctypes.byref(block(dh=96))) == 0
+    assert L.faar_block_workspace_bytes(ctypes.byref(block(n_kv=3))) == 0
+    assert L.faar_block_workspace_bytes(ctypes.byref(block(D=100))) == 0
+    assert L.faar_block_workspace_bytes(ctypes.byref(block(g_q=p))) == 0      # g_q without g_k
+    opt = fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 1)
+    ws = ctypes.c_void_p(0x10000)
+    f = L.faar_block_joint_step
+    P = ctypes.c_void_p(p)
+    assert f(nul, P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -1
+    assert f(ctypes.byref(good), nul, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -1
+    assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, nul, P, P, ws, n, nul) == -1
+    assert f(ctypes.byref(block(g_mlp=nul)), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -1
+    bad_lin = block()
+    bad_lin.lin[3].icodes = nul
+    assert f(ctypes.byref(bad_lin), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -1
+    assert f(ctypes.byref(block(S=40)), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -2
+    assert f(ctypes.byref(block(wdt=7)), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -3
+    assert f(ctypes.byref(good), P, P, 1.0, 0.0, 0.01, ctypes.byref(opt), P, P, ws, n, nul) == -6
+    assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 0)), P, P, ws, n, nul) == -6
+    assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ctypes.c_void_p(0x10010), n, nul) == -6
+    assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n - 1, nul) == -4
+    assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, nul, 0, nul) == -4
