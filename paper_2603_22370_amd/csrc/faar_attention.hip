@@ -75,16 +75,6 @@ struct AttnDims {
   float scale;        // of the scores (1 / sqrt(dh) for the models here)
 };
 
-// wave -> (sequence, head, block of 32 positions)
-__device__ __forceinline__ bool wave_coords(int64_t total, int blocks, int heads, int64_t& b, int& head, int& blk) {
-  const int64_t w = blockIdx.x * 4LL + (threadIdx.x >> 6);
-  if (w >= total) return false;
-  blk = static_cast<int>(w % blocks);
-  head = static_cast<int>((w / blocks) % heads);
-  b = w / blocks / heads;
-  return true;
-}
-
 // 2^x by the hardware instruction alone: the arguments here are at most a few units above zero and results far below one
 // may flush to zero
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -101,48 +91,55 @@ constexpr float kLazy = 8.0f;
 // lines per matrix-operand load of every wavefront.  The 16-byte chunks of a row are stored XOR-swizzled by the row so that
 // the operand reads (16 rows at the same chunk index) spread over the banks.
 template <int DH>
-struct KvTile {
-  static constexpr int CPRK = DH / 8;                 // 16-byte chunks per row of the k tile
-  static constexpr int KCH = 32 * CPRK / 256;         // chunks of the k tile per thread
-  static constexpr int VCH = DH * 4 / 256;            // chunks of the v^T tile per thread (rows of 32 keys = 4 chunks)
-  static constexpr int ELEMS = 32 * DH;               // per tile
+struct Tile {
+  static constexpr int CPR = DH / 8;                  // 16-byte chunks per row of a [32 tokens][dh] tile
+  static constexpr int RCH = 32 * CPR / 256;          // chunks of such a tile per thread
+  static constexpr int CCH = DH * 4 / 256;            // chunks of a [dh][32 tokens] tile per thread (rows of 4 chunks)
+  static constexpr int ELEMS = 32 * DH;               // per tile, either kind
 
-  static __device__ __forceinline__ void load(uint4 (&kreg)[KCH], uint4 (&vreg)[VCH], const bf16_t* __restrict__ K,
-                                              const bf16_t* __restrict__ Vt, int64_t krow0, int64_t ldk, int64_t kcol0,
-                                              int64_t vrow0, int64_t Tp, int64_t vcol0, int tid) {
+  // [32 tokens][dh] out of a token-major tensor: rows row0 .. row0+31, columns col0 .. col0+dh-1
+  static __device__ __forceinline__ void load_rows(uint4 (&reg)[RCH], const bf16_t* __restrict__ src, int64_t row0, int64_t ld,
+                                                   int64_t col0, int tid) {
 #pragma unroll
-    for (int j = 0; j < KCH; ++j) {
-      const int i = tid + 256 * j, row = i / CPRK, ch = i % CPRK;
-      kreg[j] = *reinterpret_cast<const uint4*>(K + (krow0 + row) * ldk + kcol0 + ch * 8);
-    }
-#pragma unroll
-    for (int j = 0; j < VCH; ++j) {
-      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
-      vreg[j] = *reinterpret_cast<const uint4*>(Vt + (vrow0 + row) * Tp + vcol0 + ch * 8);
+    for (int j = 0; j < RCH; ++j) {
+      const int i = tid + 256 * j, row = i / CPR, ch = i % CPR;
+      reg[j] = *reinterpret_cast<const uint4*>(src + (row0 + row) * ld + col0 + ch * 8);
     }
   }
-  static __device__ __forceinline__ void store(const uint4 (&kreg)[KCH], const uint4 (&vreg)[VCH], bf16_t* kt, bf16_t* vt, int tid) {
+  // [dh][32 tokens] out of a transposed copy: rows row0 .. row0+dh-1, columns col0 .. col0+31
+  static __device__ __forceinline__ void load_cols(uint4 (&reg)[CCH], const bf16_t* __restrict__ src, int64_t row0, int64_t ld,
+                                                   int64_t col0, int tid) {
 #pragma unroll
-    for (int j = 0; j < KCH; ++j) {
-      const int i = tid + 256 * j, row = i / CPRK, ch = i % CPRK;
-      *reinterpret_cast<uint4*>(kt + row * DH + ((ch ^ (row % CPRK)) * 8)) = kreg[j];
-    }
-#pragma unroll
-    for (int j = 0; j < VCH; ++j) {
+    for (int j = 0; j < CCH; ++j) {
       const int i = tid + 256 * j, row = i / 4, ch = i % 4;
-      *reinterpret_cast<uint4*>(vt + row * 32 + ((ch ^ ((row / 4) % 4)) * 8)) = vreg[j];
+      reg[j] = *reinterpret_cast<const uint4*>(src + (row0 + row) * ld + col0 + ch * 8);
     }
   }
-  // matrix operands out of the tiles: k rows (tile kt, dh chunk group ks) and v^T rows (tile dt; keys 4g.. and 16+4g..)
-  static __device__ __forceinline__ bf16x8 k_frag(const bf16_t* kt, int tile, int ks, int n, int g) {
+  static __device__ __forceinline__ void store_rows(const uint4 (&reg)[RCH], bf16_t* t, int tid) {
+#pragma unroll
+    for (int j = 0; j < RCH; ++j) {
+      const int i = tid + 256 * j, row = i / CPR, ch = i % CPR;
+      *reinterpret_cast<uint4*>(t + row * DH + ((ch ^ (row % CPR)) * 8)) = reg[j];
+    }
+  }
+  static __device__ __forceinline__ void store_cols(const uint4 (&reg)[CCH], bf16_t* t, int tid) {
+#pragma unroll
+    for (int j = 0; j < CCH; ++j) {
+      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
+      *reinterpret_cast<uint4*>(t + row * 32 + ((ch ^ ((row / 4) % 4)) * 8)) = reg[j];
+    }
+  }
+  // matrix operands out of the tiles: 16 token rows x 32 of dh (tile, dh chunk group ks) of a row tile; 16 dh rows x 32 tokens
+  // of a column tile, the tokens in the slot order 4g .. 4g+3, 16+4g .. 16+4g+3
+  static __device__ __forceinline__ bf16x8 row_frag(const bf16_t* t, int tile, int ks, int n, int g) {
     const int row = tile * 16 + n, ch = ks * 4 + g;
-    return *reinterpret_cast<const bf16x8*>(kt + row * DH + ((ch ^ (row % CPRK)) * 8));
+    return *reinterpret_cast<const bf16x8*>(t + row * DH + ((ch ^ (row % CPR)) * 8));
   }
-  static __device__ __forceinline__ bf16x8 v_frag(const bf16_t* vt, int tile, int n, int g) {
+  static __device__ __forceinline__ bf16x8 col_frag(const bf16_t* t, int tile, int n, int g) {
     const int row = tile * 16 + n, sw = (row / 4) % 4;
     Frag f;
-    f.h[0] = *reinterpret_cast<const uint2*>(vt + row * 32 + (((g / 2) ^ sw) * 8) + (g % 2) * 4);
-    f.h[1] = *reinterpret_cast<const uint2*>(vt + row * 32 + (((2 + g / 2) ^ sw) * 8) + (g % 2) * 4);
+    f.h[0] = *reinterpret_cast<const uint2*>(t + row * 32 + (((g / 2) ^ sw) * 8) + (g % 2) * 4);
+    f.h[1] = *reinterpret_cast<const uint2*>(t + row * 32 + (((2 + g / 2) ^ sw) * 8) + (g % 2) * 4);
     return f.v;
   }
 };
@@ -163,7 +160,7 @@ __device__ __forceinline__ void fwd_block(FwdState<DH>& st, const bf16_t* kt_lds
   for (int kt = 0; kt < 2; ++kt) {
     bf16x8 kf[KS];
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) kf[ks] = KvTile<DH>::k_frag(kt_lds, kt, ks, n, g);
+    for (int ks = 0; ks < KS; ++ks) kf[ks] = Tile<DH>::row_frag(kt_lds, kt, ks, n, g);
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
       f32x4 a = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -214,7 +211,7 @@ __device__ __forceinline__ void fwd_block(FwdState<DH>& st, const bf16_t* kt_lds
   }
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) {
-    const bf16x8 vf = KvTile<DH>::v_frag(vt_lds, dt, n, g);
+    const bf16x8 vf = Tile<DH>::col_frag(vt_lds, dt, n, g);
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) st.oacc[qt][dt] = mfma(vf, pf[qt], st.oacc[qt][dt]);
   }
@@ -226,7 +223,7 @@ __global__ void __launch_bounds__(256)
 k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
            bf16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][KvTile<DH>::ELEMS];   // [stage][k, v^T]
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][Tile<DH>::ELEMS];   // [stage][k, v^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
   const int blocks = d.S / 32, groups = (blocks + 3) / 4;
   const int grp = blockIdx.x % groups;
@@ -251,21 +248,26 @@ k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf1
     st.m[qt] = -INFINITY;
     st.l[qt] = 0.0f;
   }
-  typedef KvTile<DH> Tile;
-  uint4 kreg[Tile::KCH], vreg[Tile::VCH];
-  Tile::load(kreg, vreg, K, Vt, t0, ldk, (int64_t)kvh * DH, (int64_t)kvh * DH, d.Tp, t0, tid);
-  Tile::store(kreg, vreg, lds[0][0], lds[0][1], tid);
+  typedef Tile<DH> Tl;
+  uint4 kreg[Tl::RCH], vreg[Tl::CCH];
+  const int64_t kvcol = (int64_t)kvh * DH;
+  Tl::load_rows(kreg, K, t0, ldk, kvcol, tid);
+  Tl::load_cols(vreg, Vt, kvcol, d.Tp, t0, tid);
+  Tl::store_rows(kreg, lds[0][0], tid);
+  Tl::store_cols(vreg, lds[0][1], tid);
   __syncthreads();
   for (int kb = 0; kb <= last; ++kb) {
     const int cur = kb & 1;
     // past the last block the loads repeat it (unused): the loop body stays free of divergent control around them
     const int64_t nxt = t0 + (kb < last ? kb + 1 : kb) * 32;
-    Tile::load(kreg, vreg, K, Vt, nxt, ldk, (int64_t)kvh * DH, (int64_t)kvh * DH, d.Tp, nxt, tid);
+    Tl::load_rows(kreg, K, nxt, ldk, kvcol, tid);
+    Tl::load_cols(vreg, Vt, kvcol, d.Tp, nxt, tid);
     if (active) {
       if (kb < qb) fwd_block<DH, false>(st, lds[cur][0], lds[cur][1], c, n, g);
       else if (kb == qb) fwd_block<DH, true>(st, lds[cur][0], lds[cur][1], c, n, g);   // the queries' own positions
     }
-    Tile::store(kreg, vreg, lds[cur ^ 1][0], lds[cur ^ 1][1], tid);   // that stage was last read one block ago
+    Tl::store_rows(kreg, lds[cur ^ 1][0], tid);   // that stage was last read one block ago
+    Tl::store_cols(vreg, lds[cur ^ 1][1], tid);
     __syncthreads();
   }
   if (!active) return;
@@ -299,75 +301,110 @@ k_attn_rowdot(const bf16_t* __restrict__ dO, const bf16_t* __restrict__ O, int64
   if (row < T * n_q && (threadIdx.x % LPR) == 0) delta[(row % n_q) * T + row / n_q] = acc;
 }
 
-// dq = scale * dS k with dS = P * (dP - delta), P = exp(scores - lse), dP = dO v^T
+// dq = scale * dS k with dS = P * (dP - delta), P = exp(scores - lse), dP = dO v^T.  Workgroups and wavefronts as in the
+// forward kernel; per key block the tiles of k, v ([32 keys][dh]) and of the transposed k ([dh][32 keys]) go through LDS.
+template <int DH, bool kDiagonal>
+__device__ __forceinline__ void dq_block(f32x4 (&acc)[2][DH / 16], const bf16x8 (&qf)[2][DH / 32], const bf16x8 (&dof)[2][DH / 32],
+                                         const float (&lse2)[2], const float (&dl)[2], const bf16_t* k_lds, const bf16_t* v_lds,
+                                         const bf16_t* kt_lds, float c, int n, int g) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  f32x4 ds[2][2];
+#pragma unroll
+  for (int kt = 0; kt < 2; ++kt) {
+    bf16x8 kf[KS], vf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[ks] = Tile<DH>::row_frag(k_lds, kt, ks, n, g);
+      vf[ks] = Tile<DH>::row_frag(v_lds, kt, ks, n, g);
+    }
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s = mfma(kf[ks], qf[qt][ks], s);
+        dp = mfma(vf[ks], dof[qt][ks], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float p = fast_exp2(fmaf(s[r], c, -lse2[qt]));
+        if (kDiagonal && kt * 16 + 4 * g + r > qt * 16 + n) p = 0.0f;   // a key after the query
+        ds[qt][kt][r] = p * (dp[r] - dl[qt]);
+      }
+    }
+  }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const bf16x8 ktf = Tile<DH>::col_frag(kt_lds, dt, n, g);
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) acc[qt][dt] = mfma(ktf, pack_tiles(ds[qt][0], ds[qt][1]), acc[qt][dt]);
+  }
+}
+
 template <int DH>
 __global__ void __launch_bounds__(256)
 k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
               const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
-              const float* __restrict__ delta, AttnDims d, int64_t total, bf16_t* __restrict__ dQ) {
+              const float* __restrict__ delta, AttnDims d, bf16_t* __restrict__ dQ) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
-  int64_t b;
-  int head, qb;
-  if (!wave_coords(total, d.S / 32, d.n_q, b, head, qb)) return;
+  typedef Tile<DH> Tl;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][3][Tl::ELEMS];   // [stage][k, v, k^T]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
+  const int blocks = d.S / 32, groups = (blocks + 3) / 4;
+  const int grp = blockIdx.x % groups;
+  const int head = (blockIdx.x / groups) % d.n_q;
+  const int64_t b = blockIdx.x / groups / d.n_q;
   const int kvh = head / (d.n_q / d.n_kv);
   const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int qb = grp * 4 + wave;
+  const bool active = qb < blocks;
+  const int last = min(grp * 4 + 3, blocks - 1);
   const int p0 = qb * 32;
   const float c = d.scale * kLog2e;
 
   bf16x8 qf[2][KS], dof[2][KS];
-  float lse2[2], dl[2];
+  float lse2[2] = {0.0f, 0.0f}, dl[2] = {0.0f, 0.0f};
+  f32x4 acc[2][DT];
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const int64_t t = t0 + p0 + qt * 16 + n;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      qf[qt][ks] = load_frag16(Q + t * ldq + head * DH + ks * 32 + 8 * g);
-      dof[qt][ks] = load_frag16(dO + t * ldq + head * DH + ks * 32 + 8 * g);
+      qf[qt][ks] = active ? load_frag16(Q + t * ldq + head * DH + ks * 32 + 8 * g) : bf16x8{};
+      dof[qt][ks] = active ? load_frag16(dO + t * ldq + head * DH + ks * 32 + 8 * g) : bf16x8{};
     }
-    lse2[qt] = lse[(int64_t)head * d.T + t] * kLog2e;
-    dl[qt] = delta[(int64_t)head * d.T + t];
-  }
-  f32x4 acc[2][DT];
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
+    if (active) {
+      lse2[qt] = lse[(int64_t)head * d.T + t] * kLog2e;
+      dl[qt] = delta[(int64_t)head * d.T + t];
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-
-  for (int kb = 0; kb <= qb; ++kb) {
-    const int k0 = kb * 32;
-    f32x4 ds[2][2];
-#pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
-      bf16x8 kf[KS], vf[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        kf[ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
-        vf[ks] = load_frag16(V + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
-      }
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          s = mfma(kf[ks], qf[qt][ks], s);
-          dp = mfma(vf[ks], dof[qt][ks], dp);
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const bool masked = kb == qb && kt * 16 + 4 * g + r > qt * 16 + n;
-          const float p = masked ? 0.0f : exp2f(s[r] * c - lse2[qt]);
-          ds[qt][kt][r] = p * (dp[r] - dl[qt]);
-        }
-      }
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      const bf16x8 ktf = load_frag_split(Kt + ((int64_t)kvh * DH + dt * 16 + n) * d.Tp + t0 + k0 + 4 * g);
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) acc[qt][dt] = mfma(ktf, pack_tiles(ds[qt][0], ds[qt][1]), acc[qt][dt]);
-    }
   }
+  uint4 kreg[Tl::RCH], vreg[Tl::RCH], ktreg[Tl::CCH];
+  const int64_t kvcol = (int64_t)kvh * DH;
+  Tl::load_rows(kreg, K, t0, ldk, kvcol, tid);
+  Tl::load_rows(vreg, V, t0, ldk, kvcol, tid);
+  Tl::load_cols(ktreg, Kt, kvcol, d.Tp, t0, tid);
+  Tl::store_rows(kreg, lds[0][0], tid);
+  Tl::store_rows(vreg, lds[0][1], tid);
+  Tl::store_cols(ktreg, lds[0][2], tid);
+  __syncthreads();
+  for (int kb = 0; kb <= last; ++kb) {
+    const int cur = kb & 1;
+    const int64_t nxt = t0 + (kb < last ? kb + 1 : kb) * 32;   // past the end: the last block again, unused
+    Tl::load_rows(kreg, K, nxt, ldk, kvcol, tid);
+    Tl::load_rows(vreg, V, nxt, ldk, kvcol, tid);
+    Tl::load_cols(ktreg, Kt, kvcol, d.Tp, nxt, tid);
+    if (active) {
+      if (kb < qb) dq_block<DH, false>(acc, qf, dof, lse2, dl, lds[cur][0], lds[cur][1], lds[cur][2], c, n, g);
+      else if (kb == qb) dq_block<DH, true>(acc, qf, dof, lse2, dl, lds[cur][0], lds[cur][1], lds[cur][2], c, n, g);
+    }
+    Tl::store_rows(kreg, lds[cur ^ 1][0], tid);
+    Tl::store_rows(vreg, lds[cur ^ 1][1], tid);
+    Tl::store_cols(ktreg, lds[cur ^ 1][2], tid);
+    __syncthreads();
+  }
+  if (!active) return;
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     const int64_t t = t0 + p0 + qt * 16 + n;
@@ -376,86 +413,133 @@ k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const 
   }
 }
 
-// dv = P^T dO and dk = scale * dS^T q, summed over the query heads that share the key / value head
+// dv = P^T dO and dk = scale * dS^T q, summed over the query heads that share the key / value head.  A workgroup owns 128
+// key positions of a key / value head and sequence (wavefront w: 32 of them) and walks the query blocks at or after them,
+// for each query head of the group in turn; per step the tiles of q, dO ([32 queries][dh]) and of their transposed copies
+// ([dh][32 queries]) go through LDS.
+template <int DH, bool kDiagonal>
+__device__ __forceinline__ void dkv_block(f32x4 (&dk)[2][DH / 16], f32x4 (&dv)[2][DH / 16], const bf16x8 (&kf)[2][DH / 32],
+                                          const bf16x8 (&vf)[2][DH / 32], const float* __restrict__ lse_q,
+                                          const float* __restrict__ delta_q, const bf16_t* q_lds, const bf16_t* do_lds,
+                                          const bf16_t* qt_lds, const bf16_t* dot_lds, float c, int n, int g) {
+  constexpr int KS = DH / 32, DT = DH / 16;
+  f32x4 p[2][2], ds[2][2];    // [query tile][key tile]: rows = queries 4g .. 4g+3 of the tile, column = key n
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    bf16x8 qa[KS], da[KS];    // first operands: row = query n of the tile, contraction = dh
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qa[ks] = Tile<DH>::row_frag(q_lds, qt, ks, n, g);
+      da[ks] = Tile<DH>::row_frag(do_lds, qt, ks, n, g);
+    }
+    const float4 l4 = *reinterpret_cast<const float4*>(lse_q + qt * 16 + 4 * g);
+    const float4 d4 = *reinterpret_cast<const float4*>(delta_q + qt * 16 + 4 * g);
+    const float lr[4] = {l4.x, l4.y, l4.z, l4.w}, dr[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        s = mfma(qa[ks], kf[kt][ks], s);
+        dp = mfma(da[ks], vf[kt][ks], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float pr = fast_exp2(fmaf(s[r], c, -lr[r] * kLog2e));
+        if (kDiagonal && kt * 16 + n > qt * 16 + 4 * g + r) pr = 0.0f;   // the key comes after the query
+        p[qt][kt][r] = pr;
+        ds[qt][kt][r] = pr * (dp[r] - dr[r]);
+      }
+    }
+  }
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const bf16x8 dotf = Tile<DH>::col_frag(dot_lds, dt, n, g);
+    const bf16x8 qtf = Tile<DH>::col_frag(qt_lds, dt, n, g);
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      dv[kt][dt] = mfma(dotf, pack_tiles(p[0][kt], p[1][kt]), dv[kt][dt]);
+      dk[kt][dt] = mfma(qtf, pack_tiles(ds[0][kt], ds[1][kt]), dk[kt][dt]);
+    }
+  }
+}
+
 template <int DH>
 __global__ void __launch_bounds__(256)
 k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                const bf16_t* __restrict__ Qt, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dOt,
-               const float* __restrict__ lse, const float* __restrict__ delta, AttnDims d, int64_t total,
-               bf16_t* __restrict__ dK, bf16_t* __restrict__ dV) {
+               const float* __restrict__ lse, const float* __restrict__ delta, AttnDims d, bf16_t* __restrict__ dK,
+               bf16_t* __restrict__ dV) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
-  int64_t b;
-  int kvh, kb;
-  if (!wave_coords(total, d.S / 32, d.n_kv, b, kvh, kb)) return;
-  const int rep = d.n_q / d.n_kv, blocks = d.S / 32;
+  typedef Tile<DH> Tl;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][4][Tl::ELEMS];   // [stage][q, dO, q^T, dO^T]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
+  const int blocks = d.S / 32, groups = (blocks + 3) / 4;
+  const int grp = blockIdx.x % groups;
+  const int kvh = (blockIdx.x / groups) % d.n_kv;
+  const int64_t b = blockIdx.x / groups / d.n_kv;
+  const int rep = d.n_q / d.n_kv;
   const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
+  const int kb = grp * 4 + wave;                 // this wavefront's block of 32 key positions
+  const bool active = kb < blocks;
+  const int first = grp * 4;                     // first query block any wavefront of the group needs
   const int k0 = kb * 32;
   const float c = d.scale * kLog2e;
 
   bf16x8 kf[2][KS], vf[2][KS];    // second operands: column = key n of the tile, contraction = dh
-#pragma unroll
-  for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      kf[kt][ks] = load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
-      vf[kt][ks] = load_frag16(V + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g);
-    }
   f32x4 dk[2][DT], dv[2][DT];     // rows = dh 4g .. 4g+3 of the tile, column = key n
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt)
+  for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      kf[kt][ks] = active ? load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g) : bf16x8{};
+      vf[kt][ks] = active ? load_frag16(V + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g) : bf16x8{};
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
       dk[kt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
       dv[kt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-
-  for (int hj = 0; hj < rep; ++hj) {
-    const int head = kvh * rep + hj;
-    for (int qb = kb; qb < blocks; ++qb) {
-      const int q0 = qb * 32;
-      f32x4 p[2][2], ds[2][2];    // [query tile][key tile]: rows = queries 4g .. 4g+3 of the tile, column = key n
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        const int64_t t = t0 + q0 + qt * 16;
-        bf16x8 qa[KS], da[KS];    // first operands: row = query n of the tile, contraction = dh
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          qa[ks] = load_frag16(Q + (t + n) * ldq + head * DH + ks * 32 + 8 * g);
-          da[ks] = load_frag16(dO + (t + n) * ldq + head * DH + ks * 32 + 8 * g);
-        }
-        const float4 l4 = *reinterpret_cast<const float4*>(lse + (int64_t)head * d.T + t + 4 * g);
-        const float4 d4 = *reinterpret_cast<const float4*>(delta + (int64_t)head * d.T + t + 4 * g);
-        const float lr[4] = {l4.x, l4.y, l4.z, l4.w}, dr[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-          f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-          for (int ks = 0; ks < KS; ++ks) {
-            s = mfma(qa[ks], kf[kt][ks], s);
-            dp = mfma(da[ks], vf[kt][ks], dp);
-          }
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const bool masked = qb == kb && kt * 16 + n > qt * 16 + 4 * g + r;   // the key comes after the query
-            const float pr = masked ? 0.0f : exp2f(s[r] * c - lr[r] * kLog2e);
-            p[qt][kt][r] = pr;
-            ds[qt][kt][r] = pr * (dp[r] - dr[r]);
-          }
-        }
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const bf16x8 dotf = load_frag_split(dOt + ((int64_t)head * DH + dt * 16 + n) * d.Tp + t0 + q0 + 4 * g);
-        const bf16x8 qtf = load_frag_split(Qt + ((int64_t)head * DH + dt * 16 + n) * d.Tp + t0 + q0 + 4 * g);
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-          dv[kt][dt] = mfma(dotf, pack_tiles(p[0][kt], p[1][kt]), dv[kt][dt]);
-          dk[kt][dt] = mfma(qtf, pack_tiles(ds[0][kt], ds[1][kt]), dk[kt][dt]);
-        }
-      }
-    }
   }
+  // steps: query head hj of the group (outer) x query block first .. blocks-1 (inner)
+  const int per_head = blocks - first, steps = rep * per_head;
+  uint4 qreg[Tl::RCH], doreg[Tl::RCH], qtreg[Tl::CCH], dotreg[Tl::CCH];
+#define FAAR_LOAD_STEP(IT)                                                  \
+  do {                                                                      \
+    const int64_t hcol_ = (int64_t)(kvh * rep + (IT) / per_head) * DH;      \
+    const int64_t q0_ = t0 + (first + (IT) % per_head) * 32;                \
+    Tl::load_rows(qreg, Q, q0_, ldq, hcol_, tid);                           \
+    Tl::load_rows(doreg, dO, q0_, ldq, hcol_, tid);                         \
+    Tl::load_cols(qtreg, Qt, hcol_, d.Tp, q0_, tid);                        \
+    Tl::load_cols(dotreg, dOt, hcol_, d.Tp, q0_, tid);                      \
+  } while (0)
+#define FAAR_STORE_STEP(STAGE)                      \
+  do {                                              \
+    Tl::store_rows(qreg, lds[STAGE][0], tid);       \
+    Tl::store_rows(doreg, lds[STAGE][1], tid);      \
+    Tl::store_cols(qtreg, lds[STAGE][2], tid);      \
+    Tl::store_cols(dotreg, lds[STAGE][3], tid);     \
+  } while (0)
+  FAAR_LOAD_STEP(0);
+  FAAR_STORE_STEP(0);
+  __syncthreads();
+  for (int it = 0; it < steps; ++it) {
+    const int cur = it & 1;
+    const int nx = it + 1 < steps ? it + 1 : it;     // past the end: the last step again, unused
+    FAAR_LOAD_STEP(nx);
+    const int head = kvh * rep + it / per_head, qb = first + it % per_head;
+    if (active && qb >= kb) {
+      const float* lse_q = lse + (int64_t)head * d.T + t0 + qb * 32;
+      const float* delta_q = delta + (int64_t)head * d.T + t0 + qb * 32;
+      if (qb > kb) dkv_block<DH, false>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, n, g);
+      else dkv_block<DH, true>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, n, g);
+    }
+    FAAR_STORE_STEP(cur ^ 1);
+    __syncthreads();
+  }
+#undef FAAR_LOAD_STEP
+#undef FAAR_STORE_STEP
+  if (!active) return;
 #pragma unroll
   for (int kt = 0; kt < 2; ++kt) {
     const int64_t t = t0 + k0 + kt * 16 + n;
@@ -495,8 +579,6 @@ k_rope(const bf16_t* X, int64_t n_chunks, int H, int dh, const float* __restrict
   W8<bf16_t>::store(Y + base + dh / 2, yb);
 }
 
-inline unsigned wave_blocks(int64_t waves) { return static_cast<unsigned>((waves + 3) / 4); }
-
 }  // namespace
 
 hipError_t launch_rope(const bf16_t* X, int64_t T, int64_t H, int64_t dh, const float* cos_t, const float* sin_t, int64_t S,
@@ -526,15 +608,15 @@ hipError_t launch_attention_bwd(const bf16_t* dO, const bf16_t* Q, const bf16_t*
   const AttnDims d{static_cast<int>(S), static_cast<int>(n_q), static_cast<int>(n_kv), T, Tp, scale};
   const int64_t lanes = T * n_q * (dh / 8);
   const dim3 rgrid(static_cast<unsigned>((lanes + kEltThreads - 1) / kEltThreads));
-  const int64_t tq = n_seq * n_q * (S / 32), tk = n_seq * n_kv * (S / 32);
+  const unsigned gq = static_cast<unsigned>(n_seq * n_q * ((S / 32 + 3) / 4)), gk = static_cast<unsigned>(n_seq * n_kv * ((S / 32 + 3) / 4));
   if (dh == 128) {
     hipLaunchKernelGGL(k_attn_rowdot<128>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
-    hipLaunchKernelGGL(k_attn_bwd_dq<128>, dim3(wave_blocks(tq)), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, tq, dQ);
-    hipLaunchKernelGGL(k_attn_bwd_dkv<128>, dim3(wave_blocks(tk)), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, tk, dK, dV);
+    hipLaunchKernelGGL(k_attn_bwd_dq<128>, dim3(gq), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, dQ);
+    hipLaunchKernelGGL(k_attn_bwd_dkv<128>, dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
   } else {
     hipLaunchKernelGGL(k_attn_rowdot<64>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
-    hipLaunchKernelGGL(k_attn_bwd_dq<64>, dim3(wave_blocks(tq)), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, tq, dQ);
-    hipLaunchKernelGGL(k_attn_bwd_dkv<64>, dim3(wave_blocks(tk)), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, tk, dK, dV);
+    hipLaunchKernelGGL(k_attn_bwd_dq<64>, dim3(gq), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, dQ);
+    hipLaunchKernelGGL(k_attn_bwd_dkv<64>, dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
   }
   return hipGetLastError();
 }
