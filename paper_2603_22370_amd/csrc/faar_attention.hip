@@ -219,7 +219,7 @@ __device__ __forceinline__ void fwd_block(FwdState<DH>& st, const bf16_t* kt_lds
 
 // workgroup -> (sequence, head, group of 128 query positions); wavefront w of it owns positions 32w .. 32w+31 of the group
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
            bf16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KS = DH / 32, DT = DH / 16;
@@ -342,7 +342,7 @@ __device__ __forceinline__ void dq_block(f32x4 (&acc)[2][DH / 16], const bf16x8 
 }
 
 template <int DH>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
               const bf16_t* __restrict__ Kt, const bf16_t* __restrict__ dO, const float* __restrict__ lse,
               const float* __restrict__ delta, AttnDims d, bf16_t* __restrict__ dQ) {
@@ -413,17 +413,19 @@ k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const 
   }
 }
 
-// dv = P^T dO and dk = scale * dS^T q, summed over the query heads that share the key / value head.  A workgroup owns 128
-// key positions of a key / value head and sequence (wavefront w: 32 of them) and walks the query blocks at or after them,
-// for each query head of the group in turn; per step the tiles of q, dO ([32 queries][dh]) and of their transposed copies
-// ([dh][32 queries]) go through LDS.
-template <int DH, bool kDiagonal>
-__device__ __forceinline__ void dkv_block(f32x4 (&dk)[2][DH / 16], f32x4 (&dv)[2][DH / 16], const bf16x8 (&kf)[2][DH / 32],
-                                          const bf16x8 (&vf)[2][DH / 32], const float* __restrict__ lse_q,
+// dv = P^T dO and dk = scale * dS^T q, summed over the query heads that share the key / value head.  A workgroup owns
+// 64 * KT key positions of a key / value head and sequence (wavefront w: 16 * KT of them) and walks the blocks of 32 queries
+// at or after them, for each query head of the group in turn; per step the tiles of q, dO ([32 queries][dh]) and of their
+// transposed copies ([dh][32 queries]) go through LDS.  KT = 2 everywhere: with KT = 1 at dh = 128 two workgroups fit a compute
+// unit, but every tile operand read from LDS then feeds half as many matrix instructions, and the kernel is slower (418 vs
+// 360 us on 32 x 512 tokens, 16 / 8 heads).
+template <int DH, int KT, bool kDiagonal>
+__device__ __forceinline__ void dkv_block(f32x4 (&dk)[KT][DH / 16], f32x4 (&dv)[KT][DH / 16], const bf16x8 (&kf)[KT][DH / 32],
+                                          const bf16x8 (&vf)[KT][DH / 32], const float* __restrict__ lse_q,
                                           const float* __restrict__ delta_q, const bf16_t* q_lds, const bf16_t* do_lds,
-                                          const bf16_t* qt_lds, const bf16_t* dot_lds, float c, int n, int g) {
+                                          const bf16_t* qt_lds, const bf16_t* dot_lds, float c, int key_minus_q0, int n, int g) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  f32x4 p[2][2], ds[2][2];    // [query tile][key tile]: rows = queries 4g .. 4g+3 of the tile, column = key n
+  f32x4 p[2][KT], ds[2][KT];    // [query tile][key tile]: rows = queries 4g .. 4g+3 of the tile, column = key n
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
     bf16x8 qa[KS], da[KS];    // first operands: row = query n of the tile, contraction = dh
@@ -436,7 +438,7 @@ __device__ __forceinline__ void dkv_block(f32x4 (&dk)[2][DH / 16], f32x4 (&dv)[2
     const float4 d4 = *reinterpret_cast<const float4*>(delta_q + qt * 16 + 4 * g);
     const float lr[4] = {l4.x, l4.y, l4.z, l4.w}, dr[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < KT; ++kt) {
       f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f}, dp = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
@@ -446,7 +448,8 @@ __device__ __forceinline__ void dkv_block(f32x4 (&dk)[2][DH / 16], f32x4 (&dv)[2
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         float pr = fast_exp2(fmaf(s[r], c, -lr[r] * kLog2e));
-        if (kDiagonal && kt * 16 + n > qt * 16 + 4 * g + r) pr = 0.0f;   // the key comes after the query
+        // key_minus_q0 = position of this wavefront's first key relative to the block's first query
+        if (kDiagonal && key_minus_q0 + kt * 16 + n > qt * 16 + 4 * g + r) pr = 0.0f;   // the key comes after the query
         p[qt][kt][r] = pr;
         ds[qt][kt][r] = pr * (dp[r] - dr[r]);
       }
@@ -457,39 +460,39 @@ __device__ __forceinline__ void dkv_block(f32x4 (&dk)[2][DH / 16], f32x4 (&dv)[2
     const bf16x8 dotf = Tile<DH>::col_frag(dot_lds, dt, n, g);
     const bf16x8 qtf = Tile<DH>::col_frag(qt_lds, dt, n, g);
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int kt = 0; kt < KT; ++kt) {
       dv[kt][dt] = mfma(dotf, pack_tiles(p[0][kt], p[1][kt]), dv[kt][dt]);
       dk[kt][dt] = mfma(qtf, pack_tiles(ds[0][kt], ds[1][kt]), dk[kt][dt]);
     }
   }
 }
 
-template <int DH>
-__global__ void __launch_bounds__(256)
+template <int DH, int KT>
+__global__ void __launch_bounds__(256, (DH * KT <= 128 ? 2 : 1))
 k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
                const bf16_t* __restrict__ Qt, const bf16_t* __restrict__ dO, const bf16_t* __restrict__ dOt,
                const float* __restrict__ lse, const float* __restrict__ delta, AttnDims d, bf16_t* __restrict__ dK,
                bf16_t* __restrict__ dV) {
-  constexpr int KS = DH / 32, DT = DH / 16;
+  constexpr int KS = DH / 32, DT = DH / 16, WK = 16 * KT;    // WK keys per wavefront
   typedef Tile<DH> Tl;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2][4][Tl::ELEMS];   // [stage][q, dO, q^T, dO^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
-  const int blocks = d.S / 32, groups = (blocks + 3) / 4;
+  const int blocks = d.S / 32, groups = (d.S + 4 * WK - 1) / (4 * WK);
   const int grp = blockIdx.x % groups;
   const int kvh = (blockIdx.x / groups) % d.n_kv;
   const int64_t b = blockIdx.x / groups / d.n_kv;
   const int rep = d.n_q / d.n_kv;
   const int64_t t0 = b * d.S, ldq = (int64_t)d.n_q * DH, ldk = (int64_t)d.n_kv * DH;
-  const int kb = grp * 4 + wave;                 // this wavefront's block of 32 key positions
-  const bool active = kb < blocks;
-  const int first = grp * 4;                     // first query block any wavefront of the group needs
-  const int k0 = kb * 32;
+  const int k0 = (grp * 4 + wave) * WK;          // this wavefront's first key position
+  const bool active = k0 < d.S;                  // S is a multiple of 32 and WK divides 32: a wavefront is in or out as a whole
+  const int first = grp * 4 * WK / 32;           // first query block any wavefront of the group needs
+  const int my_first = k0 / 32;                  // ... and this wavefront
   const float c = d.scale * kLog2e;
 
-  bf16x8 kf[2][KS], vf[2][KS];    // second operands: column = key n of the tile, contraction = dh
-  f32x4 dk[2][DT], dv[2][DT];     // rows = dh 4g .. 4g+3 of the tile, column = key n
+  bf16x8 kf[KT][KS], vf[KT][KS];  // second operands: column = key n of the tile, contraction = dh
+  f32x4 dk[KT][DT], dv[KT][DT];   // rows = dh 4g .. 4g+3 of the tile, column = key n
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
+  for (int kt = 0; kt < KT; ++kt) {
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       kf[kt][ks] = active ? load_frag16(K + (t0 + k0 + kt * 16 + n) * ldk + kvh * DH + ks * 32 + 8 * g) : bf16x8{};
@@ -528,11 +531,14 @@ k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const
     const int nx = it + 1 < steps ? it + 1 : it;     // past the end: the last step again, unused
     FAAR_LOAD_STEP(nx);
     const int head = kvh * rep + it / per_head, qb = first + it % per_head;
-    if (active && qb >= kb) {
+    if (active && qb >= my_first) {
       const float* lse_q = lse + (int64_t)head * d.T + t0 + qb * 32;
       const float* delta_q = delta + (int64_t)head * d.T + t0 + qb * 32;
-      if (qb > kb) dkv_block<DH, false>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, n, g);
-      else dkv_block<DH, true>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, n, g);
+      if (qb > my_first)
+        dkv_block<DH, KT, false>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, 0, n, g);
+      else
+        dkv_block<DH, KT, true>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, k0 - qb * 32,
+                                n, g);
     }
     FAAR_STORE_STEP(cur ^ 1);
     __syncthreads();
@@ -541,7 +547,7 @@ k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const
 #undef FAAR_STORE_STEP
   if (!active) return;
 #pragma unroll
-  for (int kt = 0; kt < 2; ++kt) {
+  for (int kt = 0; kt < KT; ++kt) {
     const int64_t t = t0 + k0 + kt * 16 + n;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
@@ -608,15 +614,16 @@ hipError_t launch_attention_bwd(const bf16_t* dO, const bf16_t* Q, const bf16_t*
   const AttnDims d{static_cast<int>(S), static_cast<int>(n_q), static_cast<int>(n_kv), T, Tp, scale};
   const int64_t lanes = T * n_q * (dh / 8);
   const dim3 rgrid(static_cast<unsigned>((lanes + kEltThreads - 1) / kEltThreads));
-  const unsigned gq = static_cast<unsigned>(n_seq * n_q * ((S / 32 + 3) / 4)), gk = static_cast<unsigned>(n_seq * n_kv * ((S / 32 + 3) / 4));
+  const unsigned gq = static_cast<unsigned>(n_seq * n_q * ((S / 32 + 3) / 4));
+  const unsigned gk = static_cast<unsigned>(n_seq * n_kv * ((S + 127) / 128));
   if (dh == 128) {
     hipLaunchKernelGGL(k_attn_rowdot<128>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
     hipLaunchKernelGGL(k_attn_bwd_dq<128>, dim3(gq), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, dQ);
-    hipLaunchKernelGGL(k_attn_bwd_dkv<128>, dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
+    hipLaunchKernelGGL((k_attn_bwd_dkv<128, 2>), dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
   } else {
     hipLaunchKernelGGL(k_attn_rowdot<64>, rgrid, dim3(kEltThreads), 0, st, dO, O, T, static_cast<int>(n_q), delta);
     hipLaunchKernelGGL(k_attn_bwd_dq<64>, dim3(gq), dim3(256), 0, st, Q, K, V, Kt, dO, lse, delta, d, dQ);
-    hipLaunchKernelGGL(k_attn_bwd_dkv<64>, dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
+    hipLaunchKernelGGL((k_attn_bwd_dkv<64, 2>), dim3(gk), dim3(256), 0, st, Q, K, V, Qt, dO, dOt, lse, delta, d, dK, dV);
   }
   return hipGetLastError();
 }
