@@ -102,54 +102,58 @@ k_rmsnorm_bwd(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, co
   }
 }
 
-// Rows of at most 512 entries (the per-head norm of q and k: dh = 128): one wavefront per row, one chunk per lane
-__device__ __forceinline__ float wave_sum_f(float a) {
+// Rows of at most 512 entries (the per-head norm of q and k: dh = 128): LPR lanes per row (the power of two that holds the
+// row's 16-byte chunks, one per lane), 64 / LPR rows per wavefront, sums within a row's lanes by shuffles
+template <int LPR>
+__device__ __forceinline__ float row_group_sum(float a) {
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+  for (int o = LPR / 2; o > 0; o >>= 1) a += __shfl_xor(a, o);
   return a;
 }
 
-template <typename XT>
+template <typename XT, int LPR>
 __global__ void __launch_bounds__(kRowThreads)
 k_rmsnorm_fwd_short(const XT* __restrict__ X, int64_t rows, int D8, const float* __restrict__ g, float eps,
                     bf16_t* __restrict__ H, float* __restrict__ rstd) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = blockIdx.x * (int64_t)(kRowThreads / 64) + (threadIdx.x >> 6);
-  const bool on = row < rows && lane < D8;
+  constexpr int RPB = kRowThreads / LPR;           // rows per workgroup
+  const int sub = threadIdx.x % LPR;
+  const int64_t row = blockIdx.x * (int64_t)RPB + threadIdx.x / LPR;
+  const bool on = row < rows && sub < D8;
   float v[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f}, gg[8], o[8];
-  if (on) W8<XT>::load(X + (row * D8 + lane) * 8, v);
+  if (on) W8<XT>::load(X + (row * D8 + sub) * 8, v);
   float ss = 0.0f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
-  ss = wave_sum_f(ss);
+  ss = row_group_sum<LPR>(ss);
   const float r = 1.0f / sqrtf(ss / static_cast<float>(D8 * 8) + eps);
-  if (row < rows && lane == 0) rstd[row] = r;
+  if (row < rows && sub == 0) rstd[row] = r;
   if (!on) return;
-  load8(g + lane * 8, gg);
+  load8(g + sub * 8, gg);
 #pragma unroll
   for (int j = 0; j < 8; ++j) o[j] = (v[j] * r) * gg[j];
-  W8<bf16_t>::store(H + (row * D8 + lane) * 8, o);
+  W8<bf16_t>::store(H + (row * D8 + sub) * 8, o);
 }
 
-template <typename XT>
+template <typename XT, int LPR>
 __global__ void __launch_bounds__(kRowThreads)
 k_rmsnorm_bwd_short(const bf16_t* __restrict__ dH1, const bf16_t* __restrict__ dH2, const bf16_t* __restrict__ dH3,
                     const XT* __restrict__ X, int64_t rows, int D8, const float* __restrict__ g,
                     const float* __restrict__ rstd, const bf16_t* __restrict__ d_res, bf16_t* __restrict__ dX) {
-  const int lane = threadIdx.x & 63;
-  const int64_t row = blockIdx.x * (int64_t)(kRowThreads / 64) + (threadIdx.x >> 6);
-  const bool on = row < rows && lane < D8;
-  const int64_t at = (row * D8 + lane) * 8;
+  constexpr int RPB = kRowThreads / LPR;
+  const int sub = threadIdx.x % LPR;
+  const int64_t row = blockIdx.x * (int64_t)RPB + threadIdx.x / LPR;
+  const bool on = row < rows && sub < D8;
+  const int64_t at = (row * D8 + sub) * 8;
   float v[8], gg[8], d1[8], o[8];
   float dot = 0.0f;
   if (on) {
     W8<XT>::load(X + at, v);
-    load8(g + lane * 8, gg);
+    load8(g + sub * 8, gg);
     load_dh(dH1, dH2, dH3, at, d1);
 #pragma unroll
     for (int j = 0; j < 8; ++j) dot += v[j] * (gg[j] * d1[j]);
   }
-  dot = wave_sum_f(dot);
+  dot = row_group_sum<LPR>(dot);
   if (!on) return;
   const float r = rstd[row];
   const float k = (r * r * r) * (dot / static_cast<float>(D8 * 8));
@@ -248,15 +252,21 @@ inline unsigned blocks_for(int64_t n8) { return static_cast<unsigned>((n8 + kElt
 
 }  // namespace
 
+inline int lanes_per_row(int64_t D) { return D <= 64 ? 8 : D <= 128 ? 16 : D <= 256 ? 32 : 64; }
+
 hipError_t launch_rmsnorm_fwd(const void* X, bool x_bf16, int64_t T, int64_t D, const float* g, float eps, bf16_t* H,
                               float* rstd, hipStream_t st) {
   const dim3 block(kRowThreads);
   if (D <= 512) {
-    const dim3 grid(static_cast<unsigned>((T + kRowThreads / 64 - 1) / (kRowThreads / 64)));
-    if (x_bf16)
-      hipLaunchKernelGGL(k_rmsnorm_fwd_short<bf16_t>, grid, block, 0, st, static_cast<const bf16_t*>(X), T, static_cast<int>(D / 8), g, eps, H, rstd);
-    else
-      hipLaunchKernelGGL(k_rmsnorm_fwd_short<float>, grid, block, 0, st, static_cast<const float*>(X), T, static_cast<int>(D / 8), g, eps, H, rstd);
+    const int lpr = lanes_per_row(D), rpb = kRowThreads / lpr, d8 = static_cast<int>(D / 8);
+    const dim3 grid(static_cast<unsigned>((T + rpb - 1) / rpb));
+#define FAAR_RF(XT, LPR) \
+  hipLaunchKernelGGL((k_rmsnorm_fwd_short<XT, LPR>), grid, block, 0, st, static_cast<const XT*>(X), T, d8, g, eps, H, rstd)
+#define FAAR_RF_T(XT) \
+  do { if (lpr == 8) FAAR_RF(XT, 8); else if (lpr == 16) FAAR_RF(XT, 16); else if (lpr == 32) FAAR_RF(XT, 32); else FAAR_RF(XT, 64); } while (0)
+    if (x_bf16) FAAR_RF_T(bf16_t); else FAAR_RF_T(float);
+#undef FAAR_RF_T
+#undef FAAR_RF
     return hipGetLastError();
   }
   const dim3 grid(static_cast<unsigned>(T));
@@ -271,11 +281,15 @@ hipError_t launch_rmsnorm_bwd(const bf16_t* dH1, const bf16_t* dH2, const bf16_t
                               int64_t D, const float* g, const float* rstd, const bf16_t* d_res, bf16_t* dX, hipStream_t st) {
   const dim3 block(kRowThreads);
   if (D <= 512) {
-    const dim3 grid(static_cast<unsigned>((T + kRowThreads / 64 - 1) / (kRowThreads / 64)));
-    if (x_bf16)
-      hipLaunchKernelGGL(k_rmsnorm_bwd_short<bf16_t>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const bf16_t*>(X), T, static_cast<int>(D / 8), g, rstd, d_res, dX);
-    else
-      hipLaunchKernelGGL(k_rmsnorm_bwd_short<float>, grid, block, 0, st, dH1, dH2, dH3, static_cast<const float*>(X), T, static_cast<int>(D / 8), g, rstd, d_res, dX);
+    const int lpr = lanes_per_row(D), rpb = kRowThreads / lpr, d8 = static_cast<int>(D / 8);
+    const dim3 grid(static_cast<unsigned>((T + rpb - 1) / rpb));
+#define FAAR_RB(XT, LPR) \
+  hipLaunchKernelGGL((k_rmsnorm_bwd_short<XT, LPR>), grid, block, 0, st, dH1, dH2, dH3, static_cast<const XT*>(X), T, d8, g, rstd, d_res, dX)
+#define FAAR_RB_T(XT) \
+  do { if (lpr == 8) FAAR_RB(XT, 8); else if (lpr == 16) FAAR_RB(XT, 16); else if (lpr == 32) FAAR_RB(XT, 32); else FAAR_RB(XT, 64); } while (0)
+    if (x_bf16) FAAR_RB_T(bf16_t); else FAAR_RB_T(float);
+#undef FAAR_RB_T
+#undef FAAR_RB
     return hipGetLastError();
   }
   const dim3 grid(static_cast<unsigned>(T));
