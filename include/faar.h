@@ -418,9 +418,10 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K,
 /*
  * The operations between the quantised linears of a transformer block, for joint steps -- Sec. 3.5 "Stage 2", Table 2
  * steps 15-17 and 23: the assembled quantised model runs forward and ONE loss is back-propagated into every layer's V.
- * The paper evaluates Llama3 / Qwen3 models; these are the parts of their blocks around the MLP's three linears
- * (pre-norm RMSNorm, gated SiLU, residual connection) and the squared error of the block output, the block-level
- * form of Eq. 6's hidden-state term.  Activations and gradients between kernels are bf16 [rows * row length],
+ * The paper evaluates Llama3 / Qwen3 models; these are the parts of their blocks around the seven linears (pre-norm
+ * RMSNorm, also over each head of q and k; rotary position embedding; causal attention with grouped key / value heads;
+ * gated SiLU; residual connections) and the squared error of the block output, the block-level form of Eq. 6's
+ * hidden-state term.  faar_block_joint_step at the end of this section enqueues all of it in one call.  Activations and gradients between kernels are bf16 [rows * row length],
  * row-major; arithmetic is float32.  A joint step of the MLP half of a block is then
  *
  *   h = faar_rmsnorm_fwd(x1);  p = faar_linear_forward(gate, h);  q = faar_linear_forward(up, h);
