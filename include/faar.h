@@ -362,7 +362,7 @@ int faar_harden_pack(const void* W, faar_dtype wdt, int64_t O, int64_t K,
 /*
  * The set-up and tear-down operations over MANY weight tensors in one call -- Table 2 steps 2-5 and 25-26 for every
  * linear layer of a model (the loops "for each layer" of Table 2).  Most tensors of a model are small (a 2 M-weight
- * projection is a launch of a few microseconds, half of it ramp-up and tail), so these calls put up to 48 tensors into
+ * projection is a launch of a few microseconds, half of it ramp-up and tail), so these calls put up to 72 tensors into
  * one launch.  Results are identical, bit for bit, to calling faar_quant_rtn / faar_init_v / faar_harden_pack on each
  * tensor.  A tensor is described by its flat weight count n = O * K (a multiple of 16: scale blocks are 16 consecutive
  * weights and rows are multiples of 16, so the row structure does not matter here).

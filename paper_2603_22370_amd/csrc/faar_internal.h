@@ -38,7 +38,7 @@ hipError_t launch_harden_pack(const void* W, bool w_bf16, int64_t n, const float
                               uint8_t* decisions, void* W_final, unsigned long long* flip_count,
                               hipStream_t st);
 // Batched codec operations: up to kBatchMax tensors per launch, descriptors passed in the kernel arguments.
-constexpr int kBatchMax = 48;          // 48 descriptors of 48 bytes + the index table stay below the 4 KB argument limit
+constexpr int kBatchMax = 72;          // 72 descriptors of 48 bytes + the index table stay below the 4 KB argument limit
 constexpr int kBatchAmaxBlocks = 64;   // workgroups (and partial maxima) per tensor in the batched amax pass
 struct CodecItem {
   const void* W; float* s_global; uint8_t* scales; float* V; uint32_t* codes;
@@ -49,6 +49,7 @@ struct CodecBatch {
   uint32_t first_block[kBatchMax + 1]; // first workgroup of each tensor; [n] = grid size
   CodecItem it[kBatchMax];
 };
+static_assert(sizeof(CodecBatch) <= 4096, "kernel arguments are limited to 4 KB");
 enum { kBatchQuant = 0, kBatchInitV = 1, kBatchHardenPack = 2 };
 // partials: kBatchAmaxBlocks floats per tensor (quantise without given tensor scales only)
 hipError_t launch_codec_batch(int op, const CodecBatch& B, bool w_bf16, bool sglobal_given, float* partials, hipStream_t st);

@@ -670,13 +670,13 @@ def test_nvfp4_activations_in_units_of_their_tensor_scale():
 
 
 def test_batched_codec_calls_match_the_single_tensor_calls_and_the_oracle():
-    """faar_quant_rtn_batch / faar_init_v_batch / faar_harden_pack_batch over 60 tensors of mixed sizes (two launches of
-    48 and 12; single-block, ragged and multi-block tensors; both storage types): every output bit-identical to the
+    """faar_quant_rtn_batch / faar_init_v_batch / faar_harden_pack_batch over 90 tensors of mixed sizes (two launches of
+    72 and 18; single-block, ragged and multi-block tensors; both storage types): every output bit-identical to the
     single-tensor entry points, and, for a subset, to the oracle."""
     shapes = [(1, 16), (8, 64), (96, 320), (16, 2048), (512, 2048), (33, 48), (1024, 1024), (7, 4112)]
     for isbf in (True, False):
         Ws_h = []
-        for k in range(60):
+        for k in range(90):
             O, K = shapes[k % len(shapes)]
             if k == 5:
                 Ws_h.append(synth.adversarial_weight(1, isbf))
