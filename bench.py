@@ -394,16 +394,18 @@ def run_layer(args) -> dict:
         "per_linear": per_linear,
     }
     if not args.no_cpu_baseline:
-        # one step of each of the seven linears (2 x 824 GF of float64 products)
+        # the same number of steps of each of the seven linears (the layer's mix of shapes): 3 by default, about 10 s of
+        # float64 products (2 x 824 GF per step of all seven)
+        each = max(1, int(round(args.cpu_seconds / 5.0)))
         t_cpu, n_cpu = 0.0, 0
         for j in jobs:
             xs = j.x_scale if j.x_scale is not None else 1.0
             n, t = oracle_step_time((j.W.float().cpu().numpy(), (j.Xq.float() * xs).cpu().numpy(), j.Y.float().cpu().numpy(),
-                                     j.alpha), seconds=0.0, max_steps=1)
+                                     j.alpha), seconds=1e9, max_steps=each)
             n_cpu += n
             t_cpu += t
         out["cpu_baseline"] = {"value": round(n_cpu / t_cpu, 4), "unit": "steps/s", "kind": "oracle",
-                               "sample": f"one step of each of the {n_cpu} linears of the same layer ({t_cpu:.1f} s)",
+                               "sample": f"{each} step(s) of each of the {len(jobs)} linears of the same layer ({t_cpu:.1f} s)",
                                **host_description()}
     return out
 
