@@ -380,8 +380,8 @@ def test_joint_step_of_a_whole_block():
         assert e <= 8e-3 and ee <= 3e-2, n
 
 
-@pytest.mark.parametrize("qk_norm,want_dx", [(True, True), (False, False)])
-def test_block_joint_step_entry_point_matches_the_call_sequence_and_the_oracle(qk_norm, want_dx):
+@pytest.mark.parametrize("qk_norm,want_dx,w_bf16", [(True, True, True), (False, False, True), (True, True, False)])
+def test_block_joint_step_entry_point_matches_the_call_sequence_and_the_oracle(qk_norm, want_dx, w_bf16):
     """faar_block_joint_step enqueues the documented sequence of calls itself: its updated V, Adam state, losses and dx are
     compared with the oracle (as the hand-sequenced step above) over two steps, and the run is bit-reproducible."""
     n_seq, S, D, n_q, n_kv, dh, F = 2, 32, 128, 4, 2, 64, 384
@@ -389,6 +389,14 @@ def test_block_joint_step_entry_point_matches_the_call_sequence_and_the_oracle(q
     rng = np.random.default_rng(321)
     shapes = dict(q=(n_q * dh, D), k=(n_kv * dh, D), v=(n_kv * dh, D), o=(D, n_q * dh), gate=(F, D), up=(F, D), down=(D, F))
     layers = {n: _layer(O, K, 900 + i) for i, (n, (O, K)) in enumerate(shapes.items())}
+    if not w_bf16:      # float32 weights that are not bf16 values
+        prng = np.random.default_rng(77)
+        layers = {}
+        for i, (n, (O, K)) in enumerate(shapes.items()):
+            W = synth.gaussian_weight(O, K, 900 + i)
+            qz = fo.quant_rtn(W, False)
+            V = np.clip(fo.init_v(W, qz["s_global"], qz["scales"])["V"] + prng.uniform(-0.3, 0.3, W.shape), 0.0, 1.0).astype(np.float32)
+            layers[n] = (W, qz["s_global"], qz["scales"], V)
     x = bf(synth.activations(T, D, 39))
     g1, g2 = (rng.uniform(0.5, 1.5, D).astype(np.float32) for _ in range(2))
     gq, gk = (rng.uniform(0.5, 1.5, dh).astype(np.float32) for _ in range(2))
@@ -401,7 +409,7 @@ def test_block_joint_step_entry_point_matches_the_call_sequence_and_the_oracle(q
     def run():
         lin = {}
         for n, (W, sg, sb, V) in layers.items():
-            Wd = dev(W)
+            Wd = dev(W, w_bf16)
             sgd, scd, _, _ = faar.faar_quant_rtn(Wd)
             Vd = dev(V, False)
             O, K = shapes[n]
