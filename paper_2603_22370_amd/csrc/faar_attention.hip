@@ -7,15 +7,17 @@
 //
 // Layouts.  q, o, dO, dq: [T, n_q * dh]; k, v, dk, dv: [T, n_kv * dh]; T = n_seq * S tokens, sequence b = rows b*S ..
 // (b+1)*S-1, S a multiple of 32; query head j reads key / value head j / (n_q / n_kv).  Every product is arranged so that
-// its matrix-core operands are read straight from global memory with 8- or 16-byte loads and no shared-memory transpose:
+// its matrix-core operands are plain row reads, with no transpose inside the kernel:
 //   * a product whose contraction runs over dh reads rows of q, k, v, dO ([token][dh], dh contiguous);
 //   * a product whose contraction runs over tokens (P V, dS K, P^T dO, dS^T Q) reads rows of a transposed copy
 //     ([head * dh + d][token], tokens contiguous) that the entry point makes once with the library's transpose kernel;
 //   * the probabilities enter those products in the accumulator layout they were computed in: an accumulator tile holds,
 //     per lane, 4 consecutive rows of one column, and two such tiles side by side are exactly the 8 contraction values a
-//     lane must supply as the second operand -- with the contraction index permuted, which the first operand's loads follow.
-// Each wavefront works alone (no shared memory, no barriers): 32 queries (forward, dq) or 32 keys (dk, dv), walking the
-// causal range in blocks of 32.  This part is under 5 % of a block step's flops; the design favours simplicity.
+//     lane must supply as the second operand -- with the contraction index permuted, which the first operand's reads follow.
+// A workgroup of four wavefronts owns 128 query positions (forward, dq) or 128 key positions (dk, dv) of one head and
+// sequence, 32 per wavefront, and walks the causal range in blocks of 32 tokens whose tiles it shares through LDS (Tile
+// below): letting every wavefront fetch its own operand fragments from global memory costs 16 partial cache lines per
+// load instruction and was 2.5 times slower.  This part is under 5 % of a block step's flops.
 #include "faar_internal.h"
 
 namespace faar {
