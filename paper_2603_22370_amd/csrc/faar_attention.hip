@@ -88,10 +88,21 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 constexpr float kLazy = 8.0f;
 
 // A workgroup of four wavefronts shares the keys and values of a block through LDS: its 256 threads copy the block's
-// [32 keys][dh] tile of k and [dh][32 keys] tile of the transposed v with row-contiguous 16-byte loads (one block ahead, held
-// in registers while the current block is worked on), so the cache sees whole rows once per workgroup instead of 16 partial
-// lines per matrix-operand load of every wavefront.  The 16-byte chunks of a row are stored XOR-swizzled by the row so that
-// the operand reads (16 rows at the same chunk index) spread over the banks.
+// [32 keys][dh] tile of k and [dh][32 keys] tile of the transposed v global -> LDS, row-contiguous 16-byte chunks, two blocks
+// ahead of their use, so the cache sees whole rows once per workgroup instead of 16 partial lines per matrix-operand load
+// of every wavefront.  The 16-byte chunks of a row are stored XOR-swizzled by the row so that the operand reads (16 rows at
+// the same chunk index) spread over the banks.
+// 16 bytes per lane from global memory straight into LDS at lds_addr + 16 * lane (lds_addr wave-uniform).  Inline assembly:
+// the compiler does not see the LDS write, so completion is tracked by hand (wait_vmcnt, then the workgroup barrier); its own
+// wait counts for ordinary loads stay sufficient, since memory operations return in order.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(gptr) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
+}
+#define FAAR_WAIT_VMCNT(N) __builtin_amdgcn_s_waitcnt(0x0F70 | ((N)&0xF) | (((N) >> 4) << 14))
+
 template <int DH>
 struct Tile {
   static constexpr int CPR = DH / 8;                  // 16-byte chunks per row of a [32 tokens][dh] tile
@@ -99,36 +110,26 @@ struct Tile {
   static constexpr int CCH = DH * 4 / 256;            // chunks of a [dh][32 tokens] tile per thread (rows of 4 chunks)
   static constexpr int ELEMS = 32 * DH;               // per tile, either kind
 
-  // [32 tokens][dh] out of a token-major tensor: rows row0 .. row0+31, columns col0 .. col0+dh-1
-  static __device__ __forceinline__ void load_rows(uint4 (&reg)[RCH], const bf16_t* __restrict__ src, int64_t row0, int64_t ld,
-                                                   int64_t col0, int tid) {
+  // [32 tokens][dh] out of a token-major tensor (rows row0 .. row0+31, columns col0 .. col0+dh-1), copied global -> LDS
+  // without passing through registers: chunk i = tid + 256 j of the tile lands at byte 16 i, and holds the row's chunk
+  // (i % CPR) ^ (row % CPR)
+  static __device__ __forceinline__ void dma_rows(const bf16_t* __restrict__ src, int64_t row0, int64_t ld, int64_t col0,
+                                                  const bf16_t* tile, int tid) {
+    const uint32_t base = lds_addr_of(tile) + 16u * (static_cast<uint32_t>(tid) & ~63u);
 #pragma unroll
     for (int j = 0; j < RCH; ++j) {
-      const int i = tid + 256 * j, row = i / CPR, ch = i % CPR;
-      reg[j] = *reinterpret_cast<const uint4*>(src + (row0 + row) * ld + col0 + ch * 8);
+      const int i = tid + 256 * j, row = i / CPR, ch = (i % CPR) ^ (row % CPR);
+      dma16(src + (row0 + row) * ld + col0 + ch * 8, __builtin_amdgcn_readfirstlane(base + 4096u * j));
     }
   }
   // [dh][32 tokens] out of a transposed copy: rows row0 .. row0+dh-1, columns col0 .. col0+31
-  static __device__ __forceinline__ void load_cols(uint4 (&reg)[CCH], const bf16_t* __restrict__ src, int64_t row0, int64_t ld,
-                                                   int64_t col0, int tid) {
+  static __device__ __forceinline__ void dma_cols(const bf16_t* __restrict__ src, int64_t row0, int64_t ld, int64_t col0,
+                                                  const bf16_t* tile, int tid) {
+    const uint32_t base = lds_addr_of(tile) + 16u * (static_cast<uint32_t>(tid) & ~63u);
 #pragma unroll
     for (int j = 0; j < CCH; ++j) {
-      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
-      reg[j] = *reinterpret_cast<const uint4*>(src + (row0 + row) * ld + col0 + ch * 8);
-    }
-  }
-  static __device__ __forceinline__ void store_rows(const uint4 (&reg)[RCH], bf16_t* t, int tid) {
-#pragma unroll
-    for (int j = 0; j < RCH; ++j) {
-      const int i = tid + 256 * j, row = i / CPR, ch = i % CPR;
-      *reinterpret_cast<uint4*>(t + row * DH + ((ch ^ (row % CPR)) * 8)) = reg[j];
-    }
-  }
-  static __device__ __forceinline__ void store_cols(const uint4 (&reg)[CCH], bf16_t* t, int tid) {
-#pragma unroll
-    for (int j = 0; j < CCH; ++j) {
-      const int i = tid + 256 * j, row = i / 4, ch = i % 4;
-      *reinterpret_cast<uint4*>(t + row * 32 + ((ch ^ ((row / 4) % 4)) * 8)) = reg[j];
+      const int i = tid + 256 * j, row = i / 4, ch = (i % 4) ^ ((row / 4) % 4);
+      dma16(src + (row0 + row) * ld + col0 + ch * 8, __builtin_amdgcn_readfirstlane(base + 4096u * j));
     }
   }
   // matrix operands out of the tiles: 16 token rows x 32 of dh (tile, dh chunk group ks) of a row tile; 16 dh rows x 32 tokens
@@ -225,7 +226,8 @@ __global__ void __launch_bounds__(256, 2)
 k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
            bf16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KS = DH / 32, DT = DH / 16;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][Tile<DH>::ELEMS];   // [stage][k, v^T]
+  typedef Tile<DH> Tl;
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[3][2][Tl::ELEMS];   // [stage][k, v^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
   const int blocks = d.S / 32, groups = (blocks + 3) / 4;
   const int grp = blockIdx.x % groups;
@@ -250,28 +252,32 @@ k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf1
     st.m[qt] = -INFINITY;
     st.l[qt] = 0.0f;
   }
-  typedef Tile<DH> Tl;
-  uint4 kreg[Tl::RCH], vreg[Tl::CCH];
+  // Three LDS stages: a block's tiles are requested two blocks ahead (one was not enough: half of a wavefront's time went
+  // into waiting), by copies that bypass the registers.  Past the last block the copies repeat it (unused).
   const int64_t kvcol = (int64_t)kvh * DH;
-  Tl::load_rows(kreg, K, t0, ldk, kvcol, tid);
-  Tl::load_cols(vreg, Vt, kvcol, d.Tp, t0, tid);
-  Tl::store_rows(kreg, lds[0][0], tid);
-  Tl::store_cols(vreg, lds[0][1], tid);
+  constexpr int kCopies = Tl::RCH + Tl::CCH;      // per wavefront and block
+#define FAAR_FWD_COPY(KB)                                            \
+  do {                                                               \
+    const int64_t at_ = t0 + ((KB) < last ? (KB) : last) * 32;       \
+    Tl::dma_rows(K, at_, ldk, kvcol, lds[(KB) % 3][0], tid);         \
+    Tl::dma_cols(Vt, kvcol, d.Tp, at_, lds[(KB) % 3][1], tid);       \
+  } while (0)
+  FAAR_FWD_COPY(0);
+  FAAR_FWD_COPY(1);
+  FAAR_WAIT_VMCNT(kCopies);                        // block 0 has landed (mine); the barrier: everybody's
   __syncthreads();
   for (int kb = 0; kb <= last; ++kb) {
-    const int cur = kb & 1;
-    // past the last block the loads repeat it (unused): the loop body stays free of divergent control around them
-    const int64_t nxt = t0 + (kb < last ? kb + 1 : kb) * 32;
-    Tl::load_rows(kreg, K, nxt, ldk, kvcol, tid);
-    Tl::load_cols(vreg, Vt, kvcol, d.Tp, nxt, tid);
+    const int cur = kb % 3;
+    FAAR_FWD_COPY(kb + 2);                         // into the stage read one block ago: everybody is past that barrier
     if (active) {
       if (kb < qb) fwd_block<DH, false>(st, lds[cur][0], lds[cur][1], c, n, g);
       else if (kb == qb) fwd_block<DH, true>(st, lds[cur][0], lds[cur][1], c, n, g);   // the queries' own positions
     }
-    Tl::store_rows(kreg, lds[cur ^ 1][0], tid);   // that stage was last read one block ago
-    Tl::store_cols(vreg, lds[cur ^ 1][1], tid);
+    FAAR_WAIT_VMCNT(kCopies);                      // all but the copies just issued: block kb + 1 has landed
     __syncthreads();
   }
+  FAAR_WAIT_VMCNT(0);                              // no copy may still be in flight into this workgroup's LDS when it retires
+#undef FAAR_FWD_COPY
   if (!active) return;
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
@@ -350,7 +356,7 @@ k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const 
               const float* __restrict__ delta, AttnDims d, bf16_t* __restrict__ dQ) {
   constexpr int KS = DH / 32, DT = DH / 16;
   typedef Tile<DH> Tl;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][3][Tl::ELEMS];   // [stage][k, v, k^T]
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[3][3][Tl::ELEMS];   // [stage][k, v, k^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
   const int blocks = d.S / 32, groups = (blocks + 3) / 4;
   const int grp = blockIdx.x % groups;
@@ -382,30 +388,31 @@ k_attn_bwd_dq(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const 
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) acc[qt][dt] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
   }
-  uint4 kreg[Tl::RCH], vreg[Tl::RCH], ktreg[Tl::CCH];
   const int64_t kvcol = (int64_t)kvh * DH;
-  Tl::load_rows(kreg, K, t0, ldk, kvcol, tid);
-  Tl::load_rows(vreg, V, t0, ldk, kvcol, tid);
-  Tl::load_cols(ktreg, Kt, kvcol, d.Tp, t0, tid);
-  Tl::store_rows(kreg, lds[0][0], tid);
-  Tl::store_rows(vreg, lds[0][1], tid);
-  Tl::store_cols(ktreg, lds[0][2], tid);
+  constexpr int kCopies = 2 * Tl::RCH + Tl::CCH;    // per wavefront and block
+#define FAAR_DQ_COPY(KB)                                             \
+  do {                                                               \
+    const int64_t at_ = t0 + ((KB) < last ? (KB) : last) * 32;       \
+    Tl::dma_rows(K, at_, ldk, kvcol, lds[(KB) % 3][0], tid);         \
+    Tl::dma_rows(V, at_, ldk, kvcol, lds[(KB) % 3][1], tid);         \
+    Tl::dma_cols(Kt, kvcol, d.Tp, at_, lds[(KB) % 3][2], tid);       \
+  } while (0)
+  FAAR_DQ_COPY(0);
+  FAAR_DQ_COPY(1);
+  FAAR_WAIT_VMCNT(kCopies);
   __syncthreads();
   for (int kb = 0; kb <= last; ++kb) {
-    const int cur = kb & 1;
-    const int64_t nxt = t0 + (kb < last ? kb + 1 : kb) * 32;   // past the end: the last block again, unused
-    Tl::load_rows(kreg, K, nxt, ldk, kvcol, tid);
-    Tl::load_rows(vreg, V, nxt, ldk, kvcol, tid);
-    Tl::load_cols(ktreg, Kt, kvcol, d.Tp, nxt, tid);
+    const int cur = kb % 3;
+    FAAR_DQ_COPY(kb + 2);
     if (active) {
       if (kb < qb) dq_block<DH, false>(acc, qf, dof, lse2, dl, lds[cur][0], lds[cur][1], lds[cur][2], c, n, g);
       else if (kb == qb) dq_block<DH, true>(acc, qf, dof, lse2, dl, lds[cur][0], lds[cur][1], lds[cur][2], c, n, g);
     }
-    Tl::store_rows(kreg, lds[cur ^ 1][0], tid);
-    Tl::store_rows(vreg, lds[cur ^ 1][1], tid);
-    Tl::store_cols(ktreg, lds[cur ^ 1][2], tid);
+    FAAR_WAIT_VMCNT(kCopies);
     __syncthreads();
   }
+  FAAR_WAIT_VMCNT(0);
+#undef FAAR_DQ_COPY
   if (!active) return;
 #pragma unroll
   for (int qt = 0; qt < 2; ++qt) {
@@ -477,7 +484,7 @@ k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const
                bf16_t* __restrict__ dV) {
   constexpr int KS = DH / 32, DT = DH / 16, WK = 16 * KT;    // WK keys per wavefront
   typedef Tile<DH> Tl;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][4][Tl::ELEMS];   // [stage][q, dO, q^T, dO^T]
+  __shared__ __attribute__((aligned(1024))) bf16_t lds[3][4][Tl::ELEMS];   // [stage][q, dO, q^T, dO^T]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, g = lane >> 4;
   const int blocks = d.S / 32, groups = (d.S + 4 * WK - 1) / (4 * WK);
   const int grp = blockIdx.x % groups;
@@ -508,30 +515,24 @@ k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const
   }
   // steps: query head hj of the group (outer) x query block first .. blocks-1 (inner)
   const int per_head = blocks - first, steps = rep * per_head;
-  uint4 qreg[Tl::RCH], doreg[Tl::RCH], qtreg[Tl::CCH], dotreg[Tl::CCH];
-#define FAAR_LOAD_STEP(IT)                                                  \
+  constexpr int kCopies = 2 * Tl::RCH + 2 * Tl::CCH;    // per wavefront and step
+#define FAAR_DKV_COPY(IT)                                                   \
   do {                                                                      \
-    const int64_t hcol_ = (int64_t)(kvh * rep + (IT) / per_head) * DH;      \
-    const int64_t q0_ = t0 + (first + (IT) % per_head) * 32;                \
-    Tl::load_rows(qreg, Q, q0_, ldq, hcol_, tid);                           \
-    Tl::load_rows(doreg, dO, q0_, ldq, hcol_, tid);                         \
-    Tl::load_cols(qtreg, Qt, hcol_, d.Tp, q0_, tid);                        \
-    Tl::load_cols(dotreg, dOt, hcol_, d.Tp, q0_, tid);                      \
+    const int it_ = (IT) < steps ? (IT) : steps - 1;                        \
+    const int64_t hcol_ = (int64_t)(kvh * rep + it_ / per_head) * DH;       \
+    const int64_t q0_ = t0 + (first + it_ % per_head) * 32;                 \
+    Tl::dma_rows(Q, q0_, ldq, hcol_, lds[(IT) % 3][0], tid);                \
+    Tl::dma_rows(dO, q0_, ldq, hcol_, lds[(IT) % 3][1], tid);               \
+    Tl::dma_cols(Qt, hcol_, d.Tp, q0_, lds[(IT) % 3][2], tid);              \
+    Tl::dma_cols(dOt, hcol_, d.Tp, q0_, lds[(IT) % 3][3], tid);             \
   } while (0)
-#define FAAR_STORE_STEP(STAGE)                      \
-  do {                                              \
-    Tl::store_rows(qreg, lds[STAGE][0], tid);       \
-    Tl::store_rows(doreg, lds[STAGE][1], tid);      \
-    Tl::store_cols(qtreg, lds[STAGE][2], tid);      \
-    Tl::store_cols(dotreg, lds[STAGE][3], tid);     \
-  } while (0)
-  FAAR_LOAD_STEP(0);
-  FAAR_STORE_STEP(0);
+  FAAR_DKV_COPY(0);
+  FAAR_DKV_COPY(1);
+  FAAR_WAIT_VMCNT(kCopies);
   __syncthreads();
   for (int it = 0; it < steps; ++it) {
-    const int cur = it & 1;
-    const int nx = it + 1 < steps ? it + 1 : it;     // past the end: the last step again, unused
-    FAAR_LOAD_STEP(nx);
+    const int cur = it % 3;
+    FAAR_DKV_COPY(it + 2);                          // past the end: the last step again, unused
     const int head = kvh * rep + it / per_head, qb = first + it % per_head;
     if (active && qb >= my_first) {
       const float* lse_q = lse + (int64_t)head * d.T + t0 + qb * 32;
@@ -542,11 +543,11 @@ k_attn_bwd_dkv(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const
         dkv_block<DH, KT, true>(dk, dv, kf, vf, lse_q, delta_q, lds[cur][0], lds[cur][1], lds[cur][2], lds[cur][3], c, k0 - qb * 32,
                                 n, g);
     }
-    FAAR_STORE_STEP(cur ^ 1);
+    FAAR_WAIT_VMCNT(kCopies);
     __syncthreads();
   }
-#undef FAAR_LOAD_STEP
-#undef FAAR_STORE_STEP
+  FAAR_WAIT_VMCNT(0);
+#undef FAAR_DKV_COPY
   if (!active) return;
 #pragma unroll
   for (int kt = 0; kt < KT; ++kt) {
