@@ -68,7 +68,8 @@ def bytes_per_weight(dw_split: int, use_h: bool = False) -> dict:
     1/2 B cached interval code), for the design as built: the dV kernel reads one fp32 partial per dW split
     and, in every step but a layer's last, also writes the next step's W_q - W."""
     return {
-        "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2,             # read W, V, code, scale; write W_q - W (bf16)
+        # read W, V, code, scale (and H, for the loss's cross term); write W_q - W (bf16)
+        "softquant_fwd": 2 + 4 + 0.5 + 1 / 16 + 2 + (4 if use_h else 0),
         # read G partials (and H), code, scale, V, m, u, W; write V, m, u, W_q - W
         "bwd_adam": 4 * dw_split + (4 if use_h else 0) + 0.5 + 1 / 16 + 12 + 12 + 2 + 2,
         "quant_rtn": 2 + 0.5 + 1 / 16,                         # read W; write codes, scales
