@@ -222,7 +222,7 @@ __device__ __forceinline__ void fwd_block(FwdState<DH>& st, const bf16_t* kt_lds
 
 // workgroup -> (sequence, head, group of 128 query positions); wavefront w of it owns positions 32w .. 32w+31 of the group
 template <int DH>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, 3)
 k_attn_fwd(const bf16_t* __restrict__ Q, const bf16_t* __restrict__ K, const bf16_t* __restrict__ Vt, AttnDims d,
            bf16_t* __restrict__ O, float* __restrict__ lse) {
   constexpr int KS = DH / 32, DT = DH / 16;
