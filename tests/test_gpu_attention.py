@@ -521,3 +521,73 @@ def test_block_joint_step_at_the_benchmark_size_on_sampled_sequences():
         # the first Adam step moves a variable by lr g / (|g| + eps): most of a layer's variables moved (the rest sit clipped
         # at 0 or 1, or belong to zero weights)
         assert (np.abs(dV) > 0.0).mean() > 0.5, n
+
+
+def test_block_joint_step_captured_in_a_hip_graph_replays_identically():
+    """faar_block_joint_step only enqueues kernels on the caller's stream (no allocation, memset, host copy or
+    synchronisation): two steps are captured once and replayed three times from the same state, with eager work and
+    synchronisations between the replays; every replay reproduces the eager run bit for bit."""
+    n_seq, S, D, n_q, n_kv, dh, F = 2, 32, 128, 4, 2, 64, 256
+    T = n_seq * S
+    rng = np.random.default_rng(5)
+    shapes = dict(q=(n_q * dh, D), k=(n_kv * dh, D), v=(n_kv * dh, D), o=(D, n_q * dh), gate=(F, D), up=(F, D), down=(D, F))
+    x = dev(bf(synth.activations(T, D, 71)))
+    y_fp = dev(bf(host(x) + rng.standard_normal((T, D)) * 0.3))
+    cos, sin = rope_tables(S, dh)
+    tc = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    lin, V0 = {}, {}
+    for i, (n, (O, K)) in enumerate(shapes.items()):
+        Wd = dev(synth.student_t_weight(O, K, 990 + i))
+        sgd, scd, _, _ = faar.faar_quant_rtn(Wd)
+        Vd, _ = faar.faar_init_v(Wd, sgd, scd)
+        _, _, ic = faar.faar_layer_prepare(Wd, sgd, scd, torch.zeros((T, K), dtype=torch.bfloat16, device="cuda"), None)
+        lin[n] = dict(W=Wd, s_global=sgd, scales=scd, icodes=ic, V=Vd, m=torch.zeros_like(Vd), u=torch.zeros_like(Vd),
+                      losses=torch.zeros(3, dtype=torch.float32, device="cuda"))
+        V0[n] = Vd.clone()
+    blk = faar.block_description(n_seq, S, D, n_q, n_kv, dh, F, 1e-6, tc(rng.uniform(0.5, 1.5, D)), tc(rng.uniform(0.5, 1.5, D)),
+                                 tc(cos), tc(sin), lin, g_q=tc(rng.uniform(0.5, 1.5, dh)), g_k=tc(rng.uniform(0.5, 1.5, dh)))
+    ws = faar.faar_block_workspace(blk)
+    loss = torch.zeros(2, dtype=torch.float32, device="cuda")
+    dx = torch.zeros((2, T, D), dtype=torch.bfloat16, device="cuda")
+
+    def reset():
+        for n in lin:
+            lin[n]["V"].copy_(V0[n]); lin[n]["m"].zero_(); lin[n]["u"].zero_(); lin[n]["losses"].zero_()
+        loss.zero_(); dx.zero_()
+
+    def two_steps():
+        for t in (1, 2):
+            opt = faar.binding.faar_adam(5e-3, 0.9, 0.999, 1e-8, t)
+            import ctypes
+            rc = faar.binding.lib().faar_block_joint_step(ctypes.byref(blk), x.data_ptr(), y_fp.data_ptr(), 1.0 / (T * D), 6.0, 0.01,
+                                                          ctypes.byref(opt), loss[t - 1:].data_ptr(), dx[t - 1].data_ptr(), ws.data_ptr(),
+                                                          ws.numel(), torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+
+    state = lambda: [t.clone() for n in lin for t in (lin[n]["V"], lin[n]["m"], lin[n]["u"], lin[n]["losses"])] + [loss.clone(), dx.clone()]
+    reset()
+    two_steps()
+    torch.cuda.synchronize()
+    want = state()
+    assert float(loss[1]) < float(loss[0])                # the second step starts from a better V
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        reset()
+        two_steps()                                        # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    reset()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        two_steps()
+    for _ in range(3):
+        reset()                                            # eager work between replays
+        ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(state(), want):
+            assert torch.equal(a, b)
