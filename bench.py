@@ -10,7 +10,9 @@ faar_layer_prepare, then EXACTLY K faar_layer_step calls per linear (soft-quanti
 dW GEMM, dV + Round Loss + Adam + clip; beta annealed 4 -> 32), then faar_harden_pack.  One "step" of the
 command line is one optimisation step of every linear; value = 7 K / elapsed (linear-layer steps / s).
 
-Other workloads (--workload): one linear of the Llama3-1B- / Qwen3-1.7B- / Llama3-8B-shaped blocks by name;
+Other workloads (--workload): qwen_layer_gram (the same layer jobs with every step in its optional Gram-matrix form,
+faar_layer_step_gram: one O x K x K product per step instead of two T x O x K ones -- valid because a layer's calibration
+activations do not change between steps; NOT the default, which forms the layer output in every step); one linear of the Llama3-1B- / Qwen3-1.7B- / Llama3-8B-shaped blocks by name;
 qwen_block_chained (the seven linears at 16384 tokens with dY supplied and dX produced); qwen_mlp_joint (one joint
 step of the MLP half of the block: norm, three linears, gate, residual, block-output loss, and back); qwen_block_joint
 (one joint step of the whole block, attention half included, by one faar_block_joint_step call); qwen_pack_sweep
@@ -167,7 +169,7 @@ def traffic_for(kernel: str, O: int, K: int, T: int):
 class LinearJob:
     """Device-resident inputs and state of one linear layer's rounding optimisation."""
 
-    def __init__(self, name, O, K, T, W, Xq, quantised_acts=False):
+    def __init__(self, name, O, K, T, W, Xq, quantised_acts=False, form="token"):
         import torch
 
         import paper_2603_22370_amd as faar
@@ -180,13 +182,17 @@ class LinearJob:
             self.x_scale, _, _, self.Xq = faar.faar_quant_rtn(Xq, want_dq=True, dq_in_units=True)
         self.alpha = 1.0 / (T * O)
         self.losses = torch.zeros(3, dtype=torch.float32, device="cuda")
-        self.ws = faar.layer_step_workspace(O, K, T)
+        self.form = form               # "token": faar_layer_step; "gram": faar_layer_step_gram
+        self.ws = faar.layer_step_workspace(O, K, T) if form == "token" else fb.layer_step_gram_workspace(O, K)
+        self.ws_g = (torch.empty(faar.faar_workspace_bytes(fb.OP_GRAM_PREPARE, K, K, T), dtype=torch.uint8, device="cuda")
+                     if form == "gram" else None)
         self.ws_q = torch.empty(faar.faar_workspace_bytes(fb.OP_QUANT_RTN, O, K), dtype=torch.uint8, device="cuda")
         self.ws_p = None
         self.dw_split = fb.faar_dw_split(O, K, T)
         # the gradient constant H = C^T X_q trades 4 bytes per output of Y in the residual GEMM's epilogue for 4 bytes
         # per weight in the pass that updates V: used where that is a saving
-        self.use_h = T >= K
+        self.use_h = T >= K or form == "gram"
+        self.gram_split = fb.faar_gemm_plan(fb.K_GEMM_GRAM, O, K, 1)[3] if form == "gram" else 0
         self.state = None
 
     @staticmethod
@@ -197,6 +203,7 @@ class LinearJob:
         import torch
 
         import paper_2603_22370_amd as faar
+        self.state = None              # a previous job's buffers go back to torch's caching allocator first: no hipMalloc here
         sg, scales, codes, _ = faar.faar_quant_rtn(self.W, ws=self.ws_q)
         V, _ = faar.faar_init_v(self.W, sg, scales)
         if self.ws_p is None:
@@ -208,6 +215,9 @@ class LinearJob:
                                       gradient_constant=self.use_h)
         self.state = dict(sg=sg, scales=scales, V=V, m=torch.zeros_like(V), u=torch.zeros_like(V), Xt=out[0], C=out[1], ic=out[2],
                           hk=dict(H=out[3], c_norm2=out[4]) if self.use_h else {})
+        if self.form == "gram":
+            from paper_2603_22370_amd import binding as fb
+            self.state["gram"], self.state["gram_lo"] = fb.faar_gram_prepare(out[0], self.T, ws=self.ws_g)
 
     def step(self, t, total, beta=None, beta_next=None, forward_ready=None):
         import paper_2603_22370_amd as faar
@@ -215,9 +225,16 @@ class LinearJob:
         beta = self.beta_at(t, total) if beta is None else beta
         if beta_next is None:      # every step but the last also prepares the next step's soft-quantised weights
             beta_next = self.beta_at(t + 1, total) if t < total else 0.0
+        ready = (t > 1) if forward_ready is None else forward_ready
+        if self.form == "gram":
+            from paper_2603_22370_amd import binding as fb
+            fb.faar_layer_step_gram(self.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], s["ic"], s["hk"]["H"], s["hk"]["c_norm2"],
+                                    s["gram"], s["gram_lo"], beta, LAM, self.alpha, LR, 0.9, 0.999, 1e-8, t, self.losses, self.ws,
+                                    beta_next=beta_next, forward_ready=ready, x_scale=self.x_scale)
+            return
         faar.faar_layer_step(self.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], self.Xq, s["Xt"], s["C"], s["ic"], beta,
                              LAM, self.alpha, LR, 0.9, 0.999, 1e-8, t, self.losses, self.ws, beta_next=beta_next,
-                             forward_ready=(t > 1) if forward_ready is None else forward_ready, x_scale=self.x_scale, **s["hk"])
+                             forward_ready=ready, x_scale=self.x_scale, **s["hk"])
 
     def finish(self):
         import paper_2603_22370_amd as faar
@@ -227,10 +244,11 @@ class LinearJob:
     def hardened_losses(self):
         import paper_2603_22370_amd as faar
         s = self.state
+        ws = self.ws if self.form == "token" else faar.layer_step_workspace(self.O, self.K, self.T)
         V_rtn, _ = faar.faar_init_v(self.W, s["sg"], s["scales"])
-        rtn = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], V_rtn, self.Xq, s["C"], self.alpha, self.ws,
+        rtn = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], V_rtn, self.Xq, s["C"], self.alpha, ws,
                                             x_scale=self.x_scale).item())
-        opt = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], s["V"], self.Xq, s["C"], self.alpha, self.ws,
+        opt = float(faar.faar_hardened_loss(self.W, s["sg"], s["scales"], s["V"], self.Xq, s["C"], self.alpha, ws,
                                             x_scale=self.x_scale).item())
         return rtn, opt
 
@@ -248,7 +266,9 @@ class LinearJob:
             self.step(t_base + i, 0, beta=16.0, beta_next=16.0, forward_ready=i > 0)
 
         probe["softquant_fwd"] = timer.time(fb.K_SOFTQUANT_FWD, first_step_call, n_probe)
-        for name, kid in [("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW), ("bwd_adam", fb.K_BWD_ADAM)]:
+        gemms = ([("gemm_residual", fb.K_GEMM_RESIDUAL), ("gemm_dw", fb.K_GEMM_DW)] if self.form == "token"
+                 else [("gemm_gram", fb.K_GEMM_GRAM)])
+        for name, kid in gemms + [("bwd_adam", fb.K_BWD_ADAM)]:
             probe[name] = timer.time(kid, step_call, n_probe)
         if codec:
             probe["quant_rtn"] = timer.time(fb.K_QUANT_RTN, lambda i: faar.faar_quant_rtn(self.W, ws=self.ws_q), n_probe)
@@ -258,8 +278,8 @@ class LinearJob:
         return probe
 
     def kernel_table(self, probe):
-        gemm_flops = 2.0 * self.T * self.O * self.K
-        bpw = bytes_per_weight(self.dw_split, self.use_h)
+        gemm_flops = 2.0 * self.T * self.O * self.K if self.form == "token" else 2.0 * self.O * self.K * self.K
+        bpw = bytes_per_weight(self.dw_split if self.form == "token" else self.gram_split, self.use_h)
         N = self.O * self.K
         # working set of one step: W, V, m, u, W_q - W, G partials, X_q, X_q^T, C, dY^T
         step_bytes = N * (2 + 12 + 2 + 4 * self.dw_split) + self.T * self.K * 4 + self.T * self.O * 6
@@ -299,7 +319,7 @@ def oracle_step_time(job_inputs, seconds, max_steps=500):
     return n, t_cpu
 
 
-def make_block_jobs(T, quantised_acts=False):
+def make_block_jobs(T, quantised_acts=False, form="token"):
     import torch
 
     from workloads import synth
@@ -309,7 +329,7 @@ def make_block_jobs(T, quantised_acts=False):
             X_h = synth.silu_gated_activations(T, K, seed=idx) if gated else synth.activations(T, K, seed=idx)
             X_by_group[group] = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
         W = torch.from_numpy(synth.student_t_weight(O, K, seed=idx)).cuda().to(torch.bfloat16)
-        jobs.append(LinearJob(name, O, K, T, W, X_by_group[group], quantised_acts))
+        jobs.append(LinearJob(name, O, K, T, W, X_by_group[group], quantised_acts, form))
     return jobs
 
 
@@ -318,7 +338,8 @@ def run_layer(args) -> dict:
     import torch
 
     T = 8192
-    jobs = make_block_jobs(T, args.quantised_acts)
+    gram = args.workload == "qwen_layer_gram"
+    jobs = make_block_jobs(T, args.quantised_acts, "gram" if gram else "token")
     torch.cuda.synchronize()
     # Stage 1 optimises every linear against frozen inputs: the seven jobs are independent, so they are issued on
     # several HIP streams (default priority).  While one job's workgroups sit in a GEMM epilogue or in the
@@ -362,7 +383,7 @@ def run_layer(args) -> dict:
 
     n_lin = len(jobs)
     weights = sum(j.O * j.K for j in jobs)
-    flops_per_set = sum(2 * 2.0 * T * j.O * j.K for j in jobs)
+    flops_per_set = sum(2.0 * j.O * j.K * j.K if gram else 2 * 2.0 * T * j.O * j.K for j in jobs)
     per_linear, timer = {}, KernelTimer()
     n_probe = max(5, args.probe_steps)
     for j in jobs:
@@ -372,7 +393,7 @@ def run_layer(args) -> dict:
                               "flipped_decisions": int(j.state["flips"].item()), "hardened_loss": {"rtn": rtn, "faar": opt},
                               "kernels": table}
     # the kernel that takes the largest share of a step of the whole layer
-    dom_l, dom_k = max(((l, k) for l in per_linear for k in ("gemm_residual", "gemm_dw", "bwd_adam")),
+    dom_l, dom_k = max(((l, k) for l in per_linear for k in (("gemm_gram", "bwd_adam") if gram else ("gemm_residual", "gemm_dw", "bwd_adam"))),
                        key=lambda lk: per_linear[lk[0]]["kernels"][lk[1]]["ms"])
     dom = per_linear[dom_l]["kernels"][dom_k]
     ms_per_step = elapsed / args.steps * 1e3
@@ -380,10 +401,13 @@ def run_layer(args) -> dict:
         "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(n_lin * args.steps / elapsed, 2), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "qwen_layer: the 7 linears of one Qwen3-1.7B-shaped layer (q/o 2048x2048, k/v 1024x2048, gate/up "
+        "config": {"workload": ("qwen_layer_gram (every step in its Gram-matrix form, faar_layer_step_gram: no layer output is formed; "
+                                "NOT the default workload): " if gram else "qwen_layer: ") +
+                               "the 7 linears of one Qwen3-1.7B-shaped layer (q/o 2048x2048, k/v 1024x2048, gate/up "
                                "6144x2048, down 2048x6144; bf16 Student-t(4) std 0.02), X 8192 tokens "
                                f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'} with 1% outlier channels x30, "
-                               "NVFP4 block 16; per linear: quant_rtn + init_v + prepare + K steps + harden_pack; one timed step = "
+                               "NVFP4 block 16; per linear: quant_rtn + init_v + prepare" + (" + gram_prepare" if gram else "") +
+                               " + K steps + harden_pack; one timed step = "
                                f"one step of every linear; value = linear-layer steps/s; the 7 independent jobs issued on {args.streams} "
                                "HIP stream(s)",
                    "T": T, "linears": n_lin, "weights": weights, "streams": args.streams},
@@ -516,7 +540,7 @@ def run_block_chained(args) -> dict:
 
     T = 16384
     steps = min(args.steps, 50)
-    warmup = min(args.warmup, 5)
+    warmup = min(args.warmup, 30)           # ~0.2 s under load before the timed region: the chip's clocks have settled
     gen = torch.Generator(device="cuda")
     gen.manual_seed(5)
     jobs = make_block_jobs(T)
@@ -630,7 +654,7 @@ def run_mlp_joint(args) -> dict:
     from workloads import synth
 
     T, D, F = 16384, 2048, 6144
-    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    steps, warmup = min(args.steps, 100), min(args.warmup, 30)
     beta, eps, ms_scale = 16.0, 1e-6, 1.0 / (T * D)
     shapes = (("gate", F, D), ("up", F, D), ("down", D, F))
     x_h = synth.activations(T, D, 31)
@@ -761,7 +785,7 @@ def run_block_joint(args) -> dict:
 
     n_seq, S, D, n_q, n_kv, dh, F = 32, 512, 2048, 16, 8, 128, 6144
     T = n_seq * S
-    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    steps, warmup = min(args.steps, 100), min(args.warmup, 30)
     beta, eps, ms_scale = 16.0, 1e-6, 1.0 / (T * D)
     shapes = dict(q=(n_q * dh, D), k=(n_kv * dh, D), v=(n_kv * dh, D), o=(D, n_q * dh), gate=(F, D), up=(F, D), down=(D, F))
     x_h = synth.activations(T, D, 51)
@@ -1018,7 +1042,7 @@ def run_stage2(args) -> dict:
     rl = torch.rand(112, generator=gen, device="cuda")
     ws = torch.empty(faar.faar_workspace_bytes(fb.OP_STAGE2_LOSSES, V, D, T), dtype=torch.uint8, device="cuda")
     kw = dict(kl_scale=1.0 / T, mse_scale=1.0 / (T * D), round_losses=rl, lambda_kl=1.0, lambda_round=0.01, ws=ws)
-    steps, warmup = min(args.steps, 50), min(args.warmup, 5)
+    steps, warmup = min(args.steps, 100), min(args.warmup, 30)
     for _ in range(max(1, warmup)):
         losses, dZ, dH = faar.faar_stage2_losses(Zf, Zq, tau, Hf, Hq, **kw)
     torch.cuda.synchronize()
@@ -1113,10 +1137,12 @@ def run_gemm_ceiling(args) -> dict:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=5)
+    # 500 steps per layer is the job length of the workload list; the untimed warm-up is a 100-step job of the same kind:
+    # the chip needs about 0.2 s under load before its clocks settle (the first 100 steps after idling run ~20 % slower)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="qwen_layer",
-                    choices=["qwen_layer"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_mlp_joint", "qwen_block_joint", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
+                    choices=["qwen_layer", "qwen_layer_gram"] + sorted(WORKLOADS) + ["qwen_block_chained", "qwen_mlp_joint", "qwen_block_joint", "qwen_pack_sweep", "stage2_losses", "gemm_ceiling"])
     ap.add_argument("--quantised-acts", action="store_true",
                     help="W4A4: quantise the activations to NVFP4 with the same kernel and feed them as (units, tensor scale)")
     ap.add_argument("--stochastic-trials", type=int, default=0,
@@ -1140,7 +1166,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    runners = {"qwen_layer": run_layer, "qwen_block_chained": run_block_chained, "qwen_mlp_joint": run_mlp_joint, "qwen_block_joint": run_block_joint,
+    runners = {"qwen_layer": run_layer, "qwen_layer_gram": run_layer, "qwen_block_chained": run_block_chained, "qwen_mlp_joint": run_mlp_joint, "qwen_block_joint": run_block_joint,
                "qwen_pack_sweep": run_pack_sweep,
                "stage2_losses": run_stage2, "gemm_ceiling": run_gemm_ceiling}
     out = runners.get(args.workload, run_linear)(args)

@@ -84,7 +84,9 @@ enum {
   FAAR_OP_LINEAR_FORWARD = 8,
   FAAR_OP_BLOCK_OUTPUT_LOSS = 9, /* faar_workspace_bytes(op, O = D (row length), K = 16, T = rows, 0) */
   FAAR_OP_ATTENTION_FWD = 10, /* faar_workspace_bytes(op, O = n_q * dh, K = n_kv * dh, T = tokens, 0) */
-  FAAR_OP_ATTENTION_BWD = 11  /* likewise */
+  FAAR_OP_ATTENTION_BWD = 11, /* likewise */
+  FAAR_OP_GRAM_PREPARE = 12,  /* faar_workspace_bytes(op, O = K, K, T, 0) */
+  FAAR_OP_LAYER_STEP_GRAM = 13 /* faar_workspace_bytes(op, O, K, T = 1, 0) */
 };
 
 /* kernels of the path, for faar_time_kernel */
@@ -102,7 +104,8 @@ enum {
   FAAR_K_GEMM_C = 10,        /* Y_fp - X_q W^T of faar_layer_prepare (faar_gemm_plan only: it has no time bracket) */
   FAAR_K_GEMM_FWD = 11,      /* X_q W_q^T of faar_linear_forward */
   FAAR_K_ATTENTION_FWD = 12, /* the attention kernel of faar_attention_fwd (not the transpose before it) */
-  FAAR_K_ATTENTION_BWD = 13  /* the three kernels of faar_attention_bwd (not the transposes before them) */
+  FAAR_K_ATTENTION_BWD = 13, /* the three kernels of faar_attention_bwd (not the transposes before them) */
+  FAAR_K_GEMM_GRAM = 14      /* (W_q - W) (X_q^T X_q), loss, gradient   (faar_layer_step_gram) */
 };
 
 /* GEMM kernel variants, as reported by faar_gemm_plan */
@@ -343,6 +346,36 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K,
                     const float* H, const double* c_norm2, int64_t T, const void* dY_ext, void* dX,
                     float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
                     float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The same step (Table 2 steps 6-13, Eq. 5) for a layer whose calibration activations stay the same from step to step,
+ * as in the layer-wise first stage (Sec. 3.5): an OPTIONAL algebraic rearrangement, not what faar_layer_step does.
+ * With D = W_q - W, A = x_scale Xq D^T, R = A - C and the token Gram matrix  Gm = Xq^T Xq  (K x K, constant per layer),
+ *
+ *   ||R||_F^2   = x_scale^2 <D Gm, D> - 2 x_scale <D, H> + ||C||^2
+ *   dL_mse/dW_q = 2 a (x_scale^2 D Gm - x_scale H)                       (a = mse_scale, H and ||C||^2 as above)
+ *
+ * i.e. the loss and gradient of faar_layer_step without forming the layer output: one O x K x K product per step instead
+ * of two T x O x K ones (a gain when 2 T > K).  The layer output, dY and dX do not exist in this form.
+ *
+ * faar_gram_prepare, once per layer, from the Xt that faar_layer_prepare wrote:
+ *   gram     out bf16 [K*K]:  Gm rounded to bf16 (float32 accumulation of exact bf16 products over the tokens)
+ *   gram_lo  out float [K]:   what the rounding took from the diagonal, Gm[k][k] - bf16(Gm[k][k]) -- the one place where
+ *                             the rounding errors of a row would add up coherently; the step adds it back in float32
+ *   ws       FAAR_OP_GRAM_PREPARE workspace
+ *
+ * faar_layer_step_gram: arguments as for faar_layer_step; H and c_norm2 are required.  Rounded to bf16: W_q - W and Gm.
+ * Results agree with faar_layer_step to the rounding of those, not bit for bit.  flags: 0 or FAAR_WS_FORWARD_READY (same
+ * contract; a workspace is good for one of the two step functions only).  ws: FAAR_OP_LAYER_STEP_GRAM workspace.
+ */
+int faar_gram_prepare(const void* Xt, int64_t K, int64_t T, void* gram, float* gram_lo, void* ws, size_t ws_bytes,
+                      void* stream);
+int faar_layer_step_gram(const void* W, faar_dtype wdt, int64_t O, int64_t K,
+                         const float* s_global, const uint8_t* scales,
+                         float* V, float* adam_m, float* adam_v, const float* x_scale, const uint8_t* icodes,
+                         const float* H, const double* c_norm2, const void* gram, const float* gram_lo,
+                         float beta, float beta_next, float lambda_round, float mse_scale, const faar_adam* opt,
+                         float* losses, uint32_t flags, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Hardening and NVFP4 packing -- Eq. 7 and Table 2 steps 25-26:

@@ -302,6 +302,12 @@ def stage1_loss_and_grads(W, s_global, scale_bytes, V, Xq, Y_fp, beta, lambda_ro
         R = X_q d^T - C,   dY = 2 alpha R   =>   G = dY^T X_q = (2 alpha X_q d^T)^T X_q - 2 alpha C^T X_q,
     and only the first, V-dependent factor 2 alpha X_q d^T is stored (rounded to bf16); the constant
     C^T X_q is exact.  Same mathematics (Eq. 5 and its chain rule), another rounding point for dY.
+
+    declared_rounding="gram" is the contract of an implementation that, for activations that stay the same
+    from step to step, never forms the layer output: with Gm = X_q^T X_q,
+        ||R||^2 = <d Gm, d> - 2 <d, C^T X_q> + ||C||^2,   G = 2 alpha (d Gm - C^T X_q)
+    (Eq. 5 expanded, and its chain rule), where d is stored rounded to bf16 as above and Gm is stored rounded
+    to bf16 off its diagonal (the diagonal is kept exact); dY does not exist.  No dY_ext, no dX.
     """
     W = _check_w(W)
     V64 = np.asarray(V, dtype=F32).astype(np.float64)
@@ -319,7 +325,19 @@ def stage1_loss_and_grads(W, s_global, scale_bytes, V, Xq, Y_fp, beta, lambda_ro
     N = W.size
     L_mse = float(alpha) * float(np.sum(R * R))
     L_round = round_loss(V64)
-    if dY_ext is None and declared_rounding == "split":
+    if declared_rounding == "gram":
+        if dY_ext is not None or want_dX:
+            raise ValueError("the Gram-matrix form has neither dY nor dX")
+        C = Y_fp - Xq @ W64.T
+        Gm = Xq.T @ Xq
+        Gm_stored = bf16_round(Gm.astype(F32)).astype(np.float64)
+        np.fill_diagonal(Gm_stored, np.diag(Gm))
+        Hc = C.T @ Xq
+        dG = delta @ Gm_stored
+        L_mse = float(alpha) * (float(np.sum(dG * delta)) - 2.0 * float(np.sum(delta * Hc)) + float(np.sum(C * C)))
+        G = 2.0 * float(alpha) * (dG - Hc)
+        dY = None
+    elif dY_ext is None and declared_rounding == "split":
         C = Y_fp - Xq @ W64.T
         dYa = bf16_round((2.0 * float(alpha) * (Xq @ delta.T)).astype(F32)).astype(np.float64)
         dY = dYa - 2.0 * float(alpha) * C

@@ -16,7 +16,7 @@ FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
 FAAR_WS_GRADIENT_CONSTANT = 32
 FAAR_STEP_JOINT = 64
-OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS, OP_ATTENTION_FWD, OP_ATTENTION_BWD = range(12)
+OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS, OP_ATTENTION_FWD, OP_ATTENTION_BWD, OP_GRAM_PREPARE, OP_LAYER_STEP_GRAM = range(14)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
 
@@ -106,6 +106,13 @@ def lib() -> ctypes.CDLL:
                                       c_int64, c_void_p, c_void_p,
                                       c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
                                       c_uint32, c_void_p, c_size_t, c_void_p]
+        L.faar_gram_prepare.restype = c_int
+        L.faar_gram_prepare.argtypes = [c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+        L.faar_layer_step_gram.restype = c_int
+        L.faar_layer_step_gram.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                           c_float, c_float, c_float, c_float, ctypes.POINTER(faar_adam), c_void_p,
+                                           c_uint32, c_void_p, c_size_t, c_void_p]
         L.faar_linear_forward.restype = c_int
         L.faar_linear_forward.argtypes = [c_void_p, c_int, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_float, c_void_p,
                                           c_void_p, c_int64, c_void_p, c_void_p, c_size_t, c_void_p]
@@ -196,7 +203,7 @@ def faar_dw_split(O: int, K: int, T: int) -> int:
     return int(lib().faar_dw_split(O, K, T))
 
 
-K_GEMM_C, K_GEMM_FWD, K_ATTENTION_FWD, K_ATTENTION_BWD = 10, 11, 12, 13
+K_GEMM_C, K_GEMM_FWD, K_ATTENTION_FWD, K_ATTENTION_BWD, K_GEMM_GRAM = 10, 11, 12, 13, 14
 GEMM_KINDS = ("generic", "L", "M", "S", "L64", "M64")
 
 
@@ -369,6 +376,37 @@ def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, b
                                  ctypes.byref(opt), _ptr(losses),
                                  (FAAR_WS_FORWARD_READY if forward_ready else 0) | (FAAR_STEP_JOINT if joint else 0),
                                  _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
+
+
+def faar_gram_prepare(Xt, T, ws=None):
+    """Xt bf16 [K, Tp] as written by faar_layer_prepare -> (gram bf16 [K, K] = bf16(Xq^T Xq), gram_lo f32 [K])."""
+    _dev(Xt, ws)
+    K = Xt.shape[0]
+    if Xt.dtype != torch.bfloat16 or Xt.shape[1] != faar_padded_tokens(T):
+        raise ValueError("Xt must be the bf16 [K, padded T] transpose written by faar_layer_prepare")
+    gram = torch.empty((K, K), dtype=torch.bfloat16, device=Xt.device)
+    gram_lo = torch.empty(K, dtype=torch.float32, device=Xt.device)
+    ws = _workspace(OP_GRAM_PREPARE, K, K, T, device=Xt.device) if ws is None else ws
+    _check(lib().faar_gram_prepare(_ptr(Xt), K, T, _ptr(gram), _ptr(gram_lo), _ptr(ws), ws.numel(), _stream()),
+           "faar_gram_prepare")
+    return gram, gram_lo
+
+
+def faar_layer_step_gram(W, s_global, scales, V, adam_m, adam_v, icodes, H, c_norm2, gram, gram_lo, beta, lambda_round,
+                         mse_scale, lr, beta1, beta2, eps, t, losses, ws, beta_next=0.0, forward_ready=False, x_scale=None):
+    """faar_layer_step in its Gram-matrix form (constant activations): in place on (V, adam_m, adam_v); losses f32[3]."""
+    _dev(W, s_global, scales, V, adam_m, adam_v, icodes, H, c_norm2, gram, gram_lo, losses, ws, x_scale)
+    O, K = W.shape
+    opt = faar_adam(float(lr), float(beta1), float(beta2), float(eps), int(t))
+    _check(lib().faar_layer_step_gram(_ptr(W), _dt(W), O, K, _ptr(s_global), _ptr(scales), _ptr(V), _ptr(adam_m), _ptr(adam_v),
+                                      _ptr(x_scale), _ptr(icodes), _ptr(H), _ptr(c_norm2), _ptr(gram), _ptr(gram_lo),
+                                      float(beta), float(beta_next), float(lambda_round), float(mse_scale), ctypes.byref(opt),
+                                      _ptr(losses), FAAR_WS_FORWARD_READY if forward_ready else 0, _ptr(ws), ws.numel(),
+                                      _stream()), "faar_layer_step_gram")
+
+
+def layer_step_gram_workspace(O, K, device="cuda"):
+    return _workspace(OP_LAYER_STEP_GRAM, O, K, 1, device=device)
 
 
 def layer_step_workspace(O, K, T, chained=False, device="cuda"):

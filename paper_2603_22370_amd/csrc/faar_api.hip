@@ -91,6 +91,27 @@ StepLayout step_layout(int64_t O, int64_t K, int64_t T, bool chained) {
   return L;
 }
 
+// Workspace of faar_layer_step_gram: the guard first, as in every step workspace
+struct GramLayout {
+  size_t guard, delta, G, mse_partials, round_partials, cross_partials, total;
+  int n_split;
+};
+
+GramLayout gram_layout(int64_t O, int64_t K) {
+  GramLayout L{};
+  L.n_split = choose_split_gram(O, K);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align256(bytes); return r; };
+  L.guard = take((size_t)(kTagWords + 1) * 4);
+  L.delta = take((size_t)O * K * 2);
+  L.G = take((size_t)L.n_split * O * K * 4);
+  L.mse_partials = take((size_t)gemm_gram_partials(O, K) * 8);
+  L.round_partials = take((size_t)2 * kStepBwdMaxBlocks * 8);
+  L.cross_partials = take((size_t)2 * kStepBwdMaxBlocks * 8);
+  L.total = off;
+  return L;
+}
+
 // Tag of the forward pass "W_q - W (and W_q when dX is wanted) of step t of this layer at this beta".
 ForwardTag forward_tag(int32_t t, float beta, const void* V, const void* W, const void* scales, int64_t n, bool with_wq,
                        const void* H) {
@@ -176,7 +197,7 @@ int faar_version(void) { return 100; }
 int faar_last_hip_error(void) { return g_last_hip_error; }
 
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
-  if (which < FAAR_K_NONE || which > FAAR_K_ATTENTION_BWD || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
+  if (which < FAAR_K_NONE || which > FAAR_K_GEMM_GRAM || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
   g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
   return FAAR_OK;
@@ -218,6 +239,7 @@ int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out) {
     case FAAR_K_GEMM_DX: p = gemm_plan_info(kGemmEpiBf16, T, K, O); break;
     case FAAR_K_GEMM_C: p = gemm_plan_info(kGemmEpiSub, T, O, K); break;
     case FAAR_K_GEMM_FWD: p = gemm_plan_info(kGemmEpiBf16, T, O, K); break;
+    case FAAR_K_GEMM_GRAM: p = gemm_plan_info(kGemmEpiGram, O, K, K); break;
     default: return FAAR_E_ARG;
   }
   out[0] = p.kind; out[1] = p.bm; out[2] = p.bn; out[3] = p.n_split;
@@ -266,6 +288,11 @@ size_t faar_workspace_bytes(int op, int64_t O, int64_t K, int64_t T, uint32_t fl
     case FAAR_OP_LAYER_STEP:
       if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return 0;
       return step_layout(O, K, T, (flags & FAAR_WS_CHAINED) != 0).total;
+    case FAAR_OP_GRAM_PREPARE:              // the split partial products of the K x K matrix
+      if (T <= 0 || T > kMaxElems / K || K > kMaxElems / K) return 0;
+      return align256((size_t)choose_split(K, K, padded_tokens(T)) * K * K * 4);
+    case FAAR_OP_LAYER_STEP_GRAM:
+      return gram_layout(O, K).total;
     default:
       return 0;
   }
@@ -556,6 +583,98 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   a.guard_slot = guard_slot;
   a.next_tag = forward_tag(opt->t + 1, beta_next, V, W, scales, n, wq_full != nullptr, Hs);
   a.H = Hs; a.two_alpha_h = (Hs && !dY_ext) ? 2.0f * mse_scale : 0.0f;
+  a.cross_partials = cross_p; a.c_norm2 = c_norm2; a.cross_next = cross_next;
+  Bracket b(FAAR_K_BWD_ADAM, st);
+  return hip_status(launch_step_bwd_adam(a, st));
+}
+
+// ---- the step in its Gram-matrix form (constant activations) --------------------------------------------------------
+int faar_gram_prepare(const void* Xt, int64_t K, int64_t T, void* gram, float* gram_lo, void* ws, size_t ws_bytes,
+                      void* stream) {
+  if (!Xt || !gram || !gram_lo || !ws) return FAAR_E_NULL;
+  if (int e = check_shape(K, K)) return e;
+  if (T <= 0 || T > kMaxElems / K) return FAAR_E_SHAPE;
+  if (!aligned16(Xt) || !aligned16(gram) || !aligned16(ws) || (reinterpret_cast<uintptr_t>(gram_lo) & 3u)) return FAAR_E_ARG;
+  if (ws_bytes < faar_workspace_bytes(FAAR_OP_GRAM_PREPARE, K, K, T, 0)) return FAAR_E_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t Tp = padded_tokens(T);
+  const int n_split = choose_split(K, K, Tp);
+  const bf16_t* xt = static_cast<const bf16_t*>(Xt);
+  float* part = static_cast<float*>(ws);
+  if (int e = hip_status(launch_gemm_f32(xt, xt, GemmDims{K, K, Tp, Tp, Tp}, part, n_split, st))) return e;
+  return hip_status(launch_gram_finish(part, n_split, K, static_cast<bf16_t*>(gram), gram_lo, st));
+}
+
+int faar_layer_step_gram(const void* W, faar_dtype wdt, int64_t O, int64_t K, const float* s_global, const uint8_t* scales,
+                         float* V, float* adam_m, float* adam_v, const float* x_scale, const uint8_t* icodes, const float* H,
+                         const double* c_norm2, const void* gram, const float* gram_lo, float beta, float beta_next,
+                         float lambda_round, float mse_scale, const faar_adam* opt, float* losses, uint32_t flags, void* ws,
+                         size_t ws_bytes, void* stream) {
+  if (!W || !s_global || !scales || !V || !adam_m || !adam_v || !icodes || !H || !c_norm2 || !gram || !gram_lo || !opt || !losses)
+    return FAAR_E_NULL;
+  if (int e = check_wdt(wdt)) return e;
+  if (int e = check_shape(O, K)) return e;
+  if (K > kMaxElems / K) return FAAR_E_SHAPE;
+  if (flags & ~(uint32_t)FAAR_WS_FORWARD_READY) return FAAR_E_ARG;
+  if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
+    return FAAR_E_ARG;
+  if (!(beta_next >= 0.0f) || !std::isfinite(beta_next)) return FAAR_E_ARG;
+  if (!(opt->lr >= 0.0f) || !std::isfinite(opt->lr) || !(opt->beta1 >= 0.0f && opt->beta1 < 1.0f) ||
+      !(opt->beta2 >= 0.0f && opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) || !std::isfinite(opt->eps) || opt->t < 1)
+    return FAAR_E_ARG;
+  if (!aligned16(W) || !aligned16(V) || !aligned16(adam_m) || !aligned16(adam_v) || !aligned16(icodes) || !aligned16(H) ||
+      !aligned16(gram) || !aligned16(ws) || (reinterpret_cast<uintptr_t>(c_norm2) & 7u) ||
+      (reinterpret_cast<uintptr_t>(gram_lo) & 3u))
+    return FAAR_E_ARG;
+  const GramLayout L = gram_layout(O, K);
+  if (!ws || ws_bytes < L.total) return FAAR_E_WORKSPACE;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool bf = wdt == FAAR_BF16;
+  const int64_t n = O * K;
+  char* base = static_cast<char*>(ws);
+  bf16_t* delta = reinterpret_cast<bf16_t*>(base + L.delta);
+  float* G = reinterpret_cast<float*>(base + L.G);
+  double* mse_p = reinterpret_cast<double*>(base + L.mse_partials);
+  double* round_p = reinterpret_cast<double*>(base + L.round_partials) + (opt->t & 1) * kStepBwdMaxBlocks;
+  double* round_next = reinterpret_cast<double*>(base + L.round_partials) + ((opt->t + 1) & 1) * kStepBwdMaxBlocks;
+  double* cross_p = reinterpret_cast<double*>(base + L.cross_partials) + (opt->t & 1) * kStepBwdMaxBlocks;
+  double* cross_next = reinterpret_cast<double*>(base + L.cross_partials) + ((opt->t + 1) & 1) * kStepBwdMaxBlocks;
+  uint32_t* guard_slot = reinterpret_cast<uint32_t*>(base + L.guard);
+  ForwardGuard guard{nullptr, {}};
+  // s1: W_q - W (bf16), Round-Loss partials and <W_q - W, H> partials -- unless the previous step left them
+  if (!(flags & FAAR_WS_FORWARD_READY)) {
+    Bracket b(FAAR_K_SOFTQUANT_FWD, st);
+    if (int e = hip_status(launch_step_fwd(W, bf, n, s_global, scales, icodes, V, beta, delta, nullptr, round_p, guard_slot, H,
+                                           cross_p, st)))
+      return e;
+  } else {
+    guard.slot = guard_slot;
+    guard.expect = forward_tag(opt->t, beta, V, W, scales, n, false, H);
+  }
+  // s2 + s3 in one product: (W_q - W) Gm, with the quadratic term of the loss summed in the epilogue
+  int64_t n_mse = 0;
+  {
+    Bracket b(FAAR_K_GEMM_GRAM, st);
+    if (int e = hip_status(launch_gemm_gram(delta, static_cast<const bf16_t*>(gram), O, K, gram_lo, x_scale, 2.0f * mse_scale, G,
+                                            L.n_split, mse_p, &n_mse, guard, st)))
+      return e;
+  }
+  // s5 + s6 as in faar_layer_step
+  StepBwdArgs a{};
+  a.W = W; a.w_bf16 = bf; a.n = n;
+  a.s_global = s_global; a.scales = scales; a.icodes = icodes;
+  a.V = V; a.m = adam_m; a.u = adam_v;
+  a.beta = beta; a.G = G; a.n_split = L.n_split; a.split_stride = (int64_t)O * K; a.x_scale = x_scale;
+  a.lambda_round = lambda_round;
+  a.opt.lr = opt->lr; a.opt.beta1 = opt->beta1; a.opt.beta2 = opt->beta2; a.opt.eps = opt->eps;
+  a.opt.inv_bc1 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta1, (double)opt->t)));
+  a.opt.inv_bc2 = static_cast<float>(1.0 / (1.0 - std::pow((double)opt->beta2, (double)opt->t)));
+  a.mse_partials = mse_p; a.n_mse = n_mse; a.mse_scale = mse_scale; a.round_partials = round_p; a.losses = losses;
+  a.beta_next = beta_next; a.delta_next = delta; a.wq_full_next = nullptr; a.round_next = round_next;
+  a.guard_slot = guard_slot;
+  a.next_tag = forward_tag(opt->t + 1, beta_next, V, W, scales, n, false, H);
+  a.H = H; a.two_alpha_h = 2.0f * mse_scale;
   a.cross_partials = cross_p; a.c_norm2 = c_norm2; a.cross_next = cross_next;
   Bracket b(FAAR_K_BWD_ADAM, st);
   return hip_status(launch_step_bwd_adam(a, st));

@@ -802,6 +802,30 @@ k_accumulate_partials(float* __restrict__ H, const float* __restrict__ partials,
   reinterpret_cast<float4*>(H)[i] = a;
 }
 
+// The token Gram matrix of a layer, from the split partial products: rounded to bf16 for the matrix cores, with the
+// rounding error of each diagonal entry kept in float32
+__global__ void __launch_bounds__(kEltThreads)
+k_gram_finish(const float* __restrict__ partials, int n_split, int64_t K, bf16_t* __restrict__ gram,
+              float* __restrict__ diag_lo) {
+  const int64_t n4 = K * K / 4;
+  const int64_t i = blockIdx.x * (int64_t)kEltThreads + threadIdx.x;
+  if (i >= n4) return;
+  float4 a = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  for (int s = 0; s < n_split; ++s) {
+    const float4 p = *reinterpret_cast<const float4*>(partials + s * K * K + i * 4);
+    a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+  }
+  const float v[4] = {a.x, a.y, a.z, a.w};
+  uint32_t b[4];
+  const int64_t row = (i * 4) / K, col = (i * 4) % K;   // K is a multiple of 4: the four share a row
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    b[j] = f32_to_bf16(v[j]);
+    if (col + j == row) diag_lo[row] = v[j] - __uint_as_float(b[j] << 16);
+  }
+  *reinterpret_cast<uint2*>(gram + i * 4) = make_uint2(b[0] | (b[1] << 16), b[2] | (b[3] << 16));
+}
+
 // out[0] = sum of n doubles, in a fixed order (one workgroup)
 __global__ void __launch_bounds__(kEltThreads) k_sum_doubles(const double* __restrict__ p, int64_t n, double* __restrict__ out) {
   double a = 0.0;
@@ -1058,6 +1082,13 @@ hipError_t launch_accumulate_partials(float* H, const float* partials, int n_spl
   const int64_t n4 = n / 4;   // n = O * K is a multiple of 16
   hipLaunchKernelGGL(k_accumulate_partials, dim3(static_cast<unsigned>((n4 + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads),
                      0, st, H, partials, n_split, stride, n4, first);
+  return hipGetLastError();
+}
+
+hipError_t launch_gram_finish(const float* partials, int n_split, int64_t K, bf16_t* gram, float* diag_lo, hipStream_t st) {
+  const int64_t n4 = K * K / 4;
+  hipLaunchKernelGGL(k_gram_finish, dim3(static_cast<unsigned>((n4 + kEltThreads - 1) / kEltThreads)), dim3(kEltThreads), 0, st,
+                     partials, n_split, K, gram, diag_lo);
   return hipGetLastError();
 }
 

@@ -342,6 +342,48 @@ struct EpiBf16 {
   __device__ __forceinline__ void finish(int) {}
 };
 
+// Gram-matrix form of the step: A = W_q - W (M x N = O x K outputs, the contraction runs over K as well), B = bf16(Xq^T Xq).
+// t = acc + (split 0: A[m][n] * diag_lo[n]) restores what the rounding took from B's diagonal;
+// out[split][m][n] = two_alpha * x_scale * t  (what the dW GEMM of the token form leaves for the pass that updates V);
+// per work item the partial sum of x_scale^2 * t * A[m][n], which over all items is ||x_scale Xq (W_q - W)^T||^2.
+struct EpiGram {
+  static constexpr bool kTransposedOut = false;
+  static constexpr int kMode = 0;
+  const bf16_t* delta;     // the A operand, [M, N] row-major
+  const float* diag_lo;    // [N]
+  const float* x_scale;
+  float xs;
+  ForwardGuard guard;
+  float two_alpha;
+  float* out;
+  double* partials;
+  float sum;
+  __device__ __forceinline__ void once() {
+    if (guard.slot && blockIdx.x == 0 && threadIdx.x == 0) {
+      bool ok = true;
+      for (int i = 0; i < kTagWords; ++i) ok = ok && guard.slot[i] == guard.expect.w[i];
+      for (int i = 0; i < kTagWords; ++i) guard.slot[i] = 0u;
+      guard.slot[kTagWords] = ok ? 1u : 0u;
+    }
+  }
+  __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
+  __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int split, const GemmDims& d) {
+    if (n >= d.N) return;
+    float* o = out + (int64_t)split * d.M * d.N;
+    const float lo = split == 0 ? diag_lo[n] : 0.0f;
+    const float k_out = two_alpha * xs, k_sum = xs * xs;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (m + q < d.M) {
+        const float a = bf16_to_f32(delta[(m + q) * d.N + n]);
+        const float t = acc[q] + a * lo;
+        o[(m + q) * d.N + n] = k_out * t;
+        sum += k_sum * (t * a);
+      }
+  }
+  __device__ __forceinline__ void finish(int item) { finish_sum(sum, partials, item); }
+};
+
 // Measurement epilogue (faar_gemm_probe): no output; every work item reports how many shader-clock cycles and how
 // many ticks of the constant 100 MHz counter it took, so that the clock the compute units ran at can be read off.
 // kMode selects what the main loop of k_gemm_dma64 keeps: 0 everything, 1 only the matrix instructions and their
@@ -850,7 +892,7 @@ Plan plan_gemm(const GemmDims& d, bool may_split, EpiCost epi) {
   return best;
 }
 
-constexpr EpiCost kEpiResidual{4.0f, 2.0f}, kEpiF32{0.0f, 4.0f}, kEpiSub{4.0f, 4.0f}, kEpiBf16{0.0f, 2.0f}, kEpiNone{0.0f, 0.0f};
+constexpr EpiCost kEpiGram{2.0f, 4.0f}, kEpiResidual{4.0f, 2.0f}, kEpiF32{0.0f, 4.0f}, kEpiSub{4.0f, 4.0f}, kEpiBf16{0.0f, 2.0f}, kEpiNone{0.0f, 0.0f};
 
 template <class Epi>
 hipError_t run(const bf16_t* A, const bf16_t* B, GemmDims d, Plan p, Epi epi, hipStream_t st) {
@@ -913,6 +955,7 @@ GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd) {
                : epilogue == kGemmEpiF32    ? plan_gemm(d, true, kEpiF32)
                : epilogue == kGemmEpiSub    ? plan_gemm(d, false, kEpiSub)
                : epilogue == kGemmEpiNone   ? plan_gemm(d, false, kEpiNone)
+               : epilogue == kGemmEpiGram   ? plan_gemm(d, true, kEpiGram)
                                             : plan_gemm(d, false, kEpiBf16);
   const int bm = p.kind == KIND_S || p.kind == KIND_GENERIC ? 128 : 256;
   const int bn = p.kind == KIND_L || p.kind == KIND_L64 ? 256 : 128;
@@ -925,6 +968,20 @@ hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* 
   Plan p = plan_gemm(d, true, kEpiF32);
   if (p.n_split != n_split) return hipErrorInvalidValue;  // the caller sized its workspace with choose_split
   return run(A, B, d, p, e, st);
+}
+
+int choose_split_gram(int64_t O, int64_t K) { return plan_gemm(GemmDims{O, K, K, K, K}, true, kEpiGram).n_split; }
+int64_t gemm_gram_partials(int64_t O, int64_t K) { return plan_gemm(GemmDims{O, K, K, K, K}, true, kEpiGram).items(); }
+
+hipError_t launch_gemm_gram(const bf16_t* delta, const bf16_t* gram, int64_t O, int64_t K, const float* diag_lo,
+                            const float* x_scale, float two_alpha, float* out, int n_split, double* partials,
+                            int64_t* n_partials, const ForwardGuard& guard, hipStream_t st) {
+  const GemmDims d{O, K, K, K, K};
+  const Plan p = plan_gemm(d, true, kEpiGram);
+  if (p.n_split != n_split) return hipErrorInvalidValue;  // the caller sized its workspace with choose_split_gram
+  *n_partials = p.items();
+  EpiGram e{delta, diag_lo, x_scale, 1.0f, guard, two_alpha, out, partials, 0.0f};
+  return run(delta, gram, d, p, e, st);
 }
 
 hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,

@@ -114,6 +114,8 @@ hipError_t launch_c_term_transposed(const float* C, int64_t T, int64_t O, int te
 hipError_t launch_accumulate_partials(float* H, const float* partials, int n_split, int64_t stride, int64_t n, bool first,
                                       hipStream_t st);
 hipError_t launch_sum_doubles(const double* p, int64_t n, double* out, hipStream_t st);
+// gram[i] = bf16(sum_s partials[s * K * K + i]) for the K x K matrix; diag_lo[k] = that sum at (k, k) minus its bf16 rounding
+hipError_t launch_gram_finish(const float* partials, int n_split, int64_t K, bf16_t* gram, float* diag_lo, hipStream_t st);
 // float32 -> three bf16 terms hi + mid + lo (each the rounding of the running remainder).
 hipError_t launch_split_f32(const float* in, int64_t n, bf16_t* hi, bf16_t* mid, bf16_t* lo,
                             hipStream_t st);
@@ -187,7 +189,7 @@ int choose_split(int64_t M, int64_t N, int64_t Kd);
 // The kernel variant, tile shape and contraction split the launchers above pick for an M x N x Kd product
 // (kind: 0 generic, 1 / 2 / 3 the BK = 32 kernels with 256x256 / 256x128 / 128x128 tiles, 4 / 5 the BK = 64
 // kernels with 256x256 / 256x128 tiles).  Pure host function.
-enum { kGemmEpiResidual = 0, kGemmEpiF32 = 1, kGemmEpiSub = 2, kGemmEpiBf16 = 3, kGemmEpiNone = 4 };
+enum { kGemmEpiResidual = 0, kGemmEpiF32 = 1, kGemmEpiSub = 2, kGemmEpiBf16 = 3, kGemmEpiNone = 4, kGemmEpiGram = 5 };
 struct GemmPlanInfo { int kind, bm, bn, n_split; };
 GemmPlanInfo gemm_plan_info(int epilogue, int64_t M, int64_t N, int64_t Kd);
 // C_out(m, n) = (first ? Y[m][n] : C_out(m, n)) - x_scale * acc   (Y bf16 or float32 row-major; C_out interleaved)
@@ -197,6 +199,14 @@ hipError_t launch_gemm_sub(const bf16_t* A, const bf16_t* B, GemmDims d, const v
 // product, no output: clocks[2 i], clocks[2 i + 1] = shader-clock cycles and 100 MHz ticks of work item i.
 hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,
                              int64_t capacity, float* sink, int* kind, int64_t* items, hipStream_t st);
+// Gram-matrix form of a step: delta [O, K] times gram [K, K] (symmetric, so the NT product is delta * gram);
+// out[split][o][k] = two_alpha * x_scale * (acc + (split 0) delta[o][k] * diag_lo[k]); partials[item] = the item's share of
+// x_scale^2 <delta gram, delta>; n_split must be choose_split_gram(O, K); guard as in launch_gemm_residual
+int choose_split_gram(int64_t O, int64_t K);
+int64_t gemm_gram_partials(int64_t O, int64_t K);
+hipError_t launch_gemm_gram(const bf16_t* delta, const bf16_t* gram, int64_t O, int64_t K, const float* diag_lo,
+                            const float* x_scale, float two_alpha, float* out, int n_split, double* partials,
+                            int64_t* n_partials, const ForwardGuard& guard, hipStream_t st);
 // out[m][n] = bf16(scale * acc), scale a device scalar (null = 1)
 hipError_t launch_gemm_bf16(const bf16_t* A, const bf16_t* B, GemmDims d, bf16_t* out, const float* scale,
                             hipStream_t st);

@@ -283,3 +283,38 @@ def test_block_joint_step_validates_its_description_without_a_gpu():
     assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ctypes.c_void_p(0x10010), n, nul) == -6
     assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, ws, n - 1, nul) == -4
     assert f(ctypes.byref(good), P, P, 1.0, 4.0, 0.01, ctypes.byref(opt), P, P, nul, 0, nul) == -4
+
+
+def test_gram_form_calls_reject_bad_arguments_without_a_gpu():
+    L = fb.lib()
+    P, nul = ctypes.c_void_p(0x1000), None
+    O, K, T = 128, 256, 300
+    n_prep = L.faar_workspace_bytes(fb.OP_GRAM_PREPARE, K, K, T, 0)
+    n_step = L.faar_workspace_bytes(fb.OP_LAYER_STEP_GRAM, O, K, 1, 0)
+    assert n_prep >= K * K * 4 and n_prep % (K * K * 4) == 0          # whole float32 partial matrices
+    assert n_step > O * K * (2 + 4)                                   # W_q - W in bf16 and at least one float32 product
+    assert L.faar_workspace_bytes(fb.OP_GRAM_PREPARE, K, 100, T, 0) == 0   # K not a multiple of 16
+    ws = ctypes.c_void_p(0x10000)
+    g = L.faar_gram_prepare
+    assert g(nul, K, T, P, P, ws, n_prep, nul) == -1
+    assert g(P, K, T, P, nul, ws, n_prep, nul) == -1
+    assert g(P, 100, T, P, P, ws, n_prep, nul) == -2
+    assert g(P, K, 0, P, P, ws, n_prep, nul) == -2
+    assert g(ctypes.c_void_p(0x1008), K, T, P, P, ws, n_prep, nul) == -6
+    assert g(P, K, T, P, P, ws, n_prep - 1, nul) == -4
+    opt = fb.faar_adam(1e-3, 0.9, 0.999, 1e-8, 1)
+    f = L.faar_layer_step_gram
+
+    def call(W=P, wdt=1, O_=O, K_=K, H=P, cn=P, gram=P, lo=P, beta=4.0, beta_next=0.0, o=opt, flags=0, w=ws, n=n_step):
+        return f(W, wdt, O_, K_, P, P, P, P, P, nul, P, H, cn, gram, lo, beta, beta_next, 0.01, 1.0,
+                 ctypes.byref(o) if o is not None else nul, P, flags, w, n, nul)
+
+    assert call(W=nul) == -1 and call(H=nul) == -1 and call(cn=nul) == -1 and call(gram=nul) == -1 and call(lo=nul) == -1
+    assert call(o=None) == -1
+    assert call(wdt=9) == -3
+    assert call(K_=100) == -2 and call(O_=0) == -2
+    assert call(beta=0.0) == -6 and call(beta_next=-1.0) == -6
+    assert call(flags=fb.FAAR_STEP_JOINT) == -6 and call(flags=4) == -6      # only FAAR_WS_FORWARD_READY is meaningful here
+    assert call(o=fb.faar_adam(1e-3, 1.0, 0.999, 1e-8, 1)) == -6
+    assert call(cn=ctypes.c_void_p(0x1004)) == -6
+    assert call(n=n_step - 1) == -4 and call(w=nul, n=0) == -4

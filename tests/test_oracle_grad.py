@@ -223,6 +223,36 @@ def test_split_contract_mode_is_the_same_gradient_with_one_rounding_moved():
     assert np.array_equal(e["dV"], f["dV"])
 
 
+def test_gram_contract_mode_is_eq5_expanded_over_the_token_gram_matrix():
+    """||X d^T - C||^2 = <d Gm, d> - 2 <d, C^T X> + ||C||^2 and G = 2 alpha (d Gm - C^T X) with Gm = X^T X: the "gram"
+    contract must agree with the exact loss and gradient to the size of its two roundings (d and the off-diagonal of
+    Gm), and EXACTLY (to float64 summation order) when those roundings do nothing -- activations of small integers
+    make Gm a matrix of small integers, and the rounding of d is shared with the plain declared mode, whose loss
+    then has to coincide."""
+    W, sg, sb, V, X, Xq, Y = _tiny(O=16, K=64, T=64)
+    al = 1.0 / (64 * 16)
+    a = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al)
+    g = fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, declared_rounding="gram")
+    n = np.linalg.norm
+    assert g["L_mse"] == pytest.approx(a["L_mse"], rel=4e-3) and g["L_round"] == a["L_round"]
+    assert 0 < n(g["dV"] - a["dV"]) <= 1e-2 * n(a["dV"])
+    # activations in {-1, 0, 1}: every entry of Gm is an integer of magnitude <= T = 64, which bf16 holds exactly
+    rng = np.random.default_rng(5)
+    Xi = rng.integers(-1, 2, size=Xq.shape).astype(np.float32)
+    Gm = Xi.astype(np.float64).T @ Xi.astype(np.float64)
+    assert np.array_equal(fo.bf16_round(Gm.astype(np.float32)).astype(np.float64), Gm)
+    b = fo.stage1_loss_and_grads(W, sg, sb, V, Xi, Y, 8.0, 0.01, al, declared_rounding=True)
+    gi = fo.stage1_loss_and_grads(W, sg, sb, V, Xi, Y, 8.0, 0.01, al, declared_rounding="gram")
+    assert gi["L_mse"] == pytest.approx(b["L_mse"], rel=1e-11)
+    # the gradient of the plain declared mode rounds dY as well; undo that by hand: G = (2 alpha R)^T X with the same d
+    W64 = W.astype(np.float64)
+    d = fo.bf16_round((b["Wq"] - W64).astype(np.float32)).astype(np.float64)
+    R = Xi.astype(np.float64) @ d.T - (Y.astype(np.float64) - Xi.astype(np.float64) @ W64.T)
+    assert np.allclose(gi["G"], (2 * al * R).T @ Xi.astype(np.float64), rtol=1e-10, atol=1e-18)
+    with pytest.raises(ValueError):
+        fo.stage1_loss_and_grads(W, sg, sb, V, Xq, Y, 8.0, 0.01, al, want_dX=True, declared_rounding="gram")
+
+
 def test_brute_force_over_all_roundings_of_a_tiny_layer():
     """Eq. 1: enumerate every V in {0,1}^16 for one 16-weight row.  The oracle's hardened loss must
     agree with an independent evaluator (decode packed bytes -> dense matmul) at every assignment;
