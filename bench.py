@@ -108,24 +108,49 @@ class HipEvents:
 
 
 class KernelTimer:
-    """Average duration of one kernel of the path: HIP events recorded by the library around each of its launches, on
-    the stream it is launched on."""
+    """Average duration of one kernel of the path in steady state: the library brackets each of its launches with a pair
+    of HIP events out of a ring, on the stream it is launched on; the calls are issued back to back without host
+    synchronisation for long enough (BUSY_MS) that the chip runs at the clocks it holds during a real job (after idling,
+    and between synchronised single launches, it runs ~20 % slower for the first tens of milliseconds), and the last RING
+    launches are averaged."""
+    RING, BUSY_MS, MAX_CALLS = 32, 80.0, 1500
 
     def __init__(self):
         self.ev = HipEvents()
-        self.e0, self.e1 = self.ev.create(), self.ev.create()
+        self.events = [self.ev.create() for _ in range(2 * self.RING)]
 
-    def time(self, which, call, n):
+    def time(self, which, call, n, position=None):
+        """Average duration (ms) of the launches of kernel `which` made by call(0), call(1), ...  position: when every call
+        launches the kernel several times, average only the launches at that index within a call (-1 = the last)."""
+        import torch
+
         from paper_2603_22370_amd import binding as fb
-        ts = []
-        fb.faar_time_kernel(which, self.e0.value, self.e1.value)
+        handles = [e.value for e in self.events]
+        fb.faar_time_kernel_ring(which, handles)
         try:
-            for i in range(n):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            first = max(4, min(n, self.RING))
+            for i in range(first):
                 call(i)
-                ts.append(self.ev.elapsed_ms(self.e0, self.e1))
+            torch.cuda.synchronize()
+            per_call_ms = (time.perf_counter() - t0) * 1e3 / first
+            per_call = fb.faar_time_kernel_count() // first          # launches of the kernel per call
+            more = int(min(self.MAX_CALLS, max(self.RING + 8, self.BUSY_MS / max(per_call_ms, 1e-3))))
+            fb.faar_time_kernel_ring(which, handles)                 # restart the count: call boundaries stay aligned
+            for i in range(first, first + more):
+                call(i)
+            torch.cuda.synchronize()
+            count = fb.faar_time_kernel_count()
         finally:
-            fb.faar_time_kernel(fb.K_NONE)
-        ts = ts[2:] if len(ts) > 4 else ts
+            fb.faar_time_kernel_ring(fb.K_NONE, [])
+        if count < 1 or per_call < 1:
+            raise RuntimeError(f"kernel {which} was not launched by every timed call")
+        ts = []
+        for g in range(max(0, count - self.RING), count):            # the launches still held by the ring
+            if position is None or g % per_call == position % per_call:
+                k = g % self.RING
+                ts.append(self.ev.elapsed_ms(self.events[2 * k], self.events[2 * k + 1]))
         return sum(ts) / len(ts)
 
 
@@ -718,9 +743,9 @@ def run_mlp_joint(args) -> dict:
     kernels = {}
     flops = 2.0 * T * F * D
     for kname, kid in [("gemm_fwd", fb.K_GEMM_FWD), ("gemm_dw", fb.K_GEMM_DW), ("gemm_dx", fb.K_GEMM_DX), ("bwd_adam", fb.K_BWD_ADAM)]:
-        # three launches of each per block step, of equal size; the events keep the last one (down_proj's forward GEMM,
+        # three launches of each per block step, of equal size; the last one is timed (down_proj's forward GEMM,
         # up_proj's backward kernels)
-        ms = timer.time(kid, lambda i: block_step(), 4)
+        ms = timer.time(kid, lambda i: block_step(), 4, position=-1)
         if kname.startswith("gemm"):
             kernels[kname] = {"ms": round(ms, 5), "tflops": round(flops / (ms * 1e-3) / 1e12, 1),
                               "frac": round(flops / (ms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, 4)}
@@ -856,7 +881,7 @@ def run_block_joint(args) -> dict:
                                  ("gemm_dx", fb.K_GEMM_DX, 2.0 * T * n_kv * dh * D, "v_proj dX"), ("bwd_adam", fb.K_BWD_ADAM, 0.0, "v_proj"),
                                  ("attention_fwd", fb.K_ATTENTION_FWD, 2.0 * n_seq * n_q * S * S * dh, "causal: half the S x S scores count"),
                                  ("attention_bwd", fb.K_ATTENTION_BWD, 5.0 * n_seq * n_q * S * S * dh, "three kernels; causal half of five S x S x dh products")]:
-        ms = timer.time(kid, lambda i: block_step(), 4)     # the events keep the last bracketed launch of a block step
+        ms = timer.time(kid, lambda i: block_step(), 4, position=-1)     # the last launch of that kernel in a block step
         row = {"ms": round(ms, 5), "launch": what}
         if fl:
             row["tflops"] = round(fl / (ms * 1e-3) / 1e12, 1)

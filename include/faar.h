@@ -130,6 +130,14 @@ int faar_last_hip_error(void);
  * FAAR_K_NONE to switch it off.  Returns FAAR_E_ARG for an unknown kernel or missing events. */
 int faar_time_kernel(int which, void* start_event, void* stop_event);
 
+/* The same hook with a ring of n event pairs, so that a kernel can be timed over many launches issued back to back
+ * (no host synchronisation between them: the chip stays at the clocks it runs a real job at).  events: HOST array of
+ * 2 n hipEvent_t handles (start 0, stop 0, start 1, ...), copied by the call; bracket number i (counted from this call)
+ * uses pair i % n.  n in [1, 4096].  faar_time_kernel_count returns how many brackets were recorded since the hook was
+ * last set. */
+int faar_time_kernel_ring(int which, void* const* events, int n);
+int64_t faar_time_kernel_count(void);
+
 /* Workspace size in bytes that `op` needs for these sizes (T is ignored by ops that take no
  * activations; `flags` as passed to the op).  Pure host function; returns 0 for an unknown op or
  * invalid sizes. */

@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
         L.faar_workspace_bytes.argtypes = [c_int, c_int64, c_int64, c_int64, c_uint32]
         L.faar_time_kernel.restype = c_int
         L.faar_time_kernel.argtypes = [c_int, c_void_p, c_void_p]
+        L.faar_time_kernel_ring.restype = c_int
+        L.faar_time_kernel_ring.argtypes = [c_int, ctypes.POINTER(c_void_p), c_int]
+        L.faar_time_kernel_count.restype = c_int64
+        L.faar_time_kernel_count.argtypes = []
         L.faar_dw_split.restype = c_int
         L.faar_dw_split.argtypes = [c_int64, c_int64, c_int64]
         L.faar_gemm_plan.restype = c_int
@@ -197,6 +201,16 @@ K_NONE, K_SOFTQUANT_FWD, K_GEMM_RESIDUAL, K_GEMM_DW, K_GEMM_DX, K_BWD_ADAM, K_QU
 def faar_time_kernel(which: int, start_event=None, stop_event=None) -> None:
     """start_event / stop_event: raw hipEvent_t handles (integers)."""
     _check(lib().faar_time_kernel(which, c_void_p(start_event), c_void_p(stop_event)), "faar_time_kernel")
+
+
+def faar_time_kernel_ring(which: int, events) -> None:
+    """events: sequence of raw hipEvent_t handles (start 0, stop 0, start 1, ...); empty with K_NONE."""
+    arr = (c_void_p * max(1, len(events)))(*events)
+    _check(lib().faar_time_kernel_ring(which, arr, len(events) // 2), "faar_time_kernel_ring")
+
+
+def faar_time_kernel_count() -> int:
+    return int(lib().faar_time_kernel_count())
 
 
 def faar_dw_split(O: int, K: int, T: int) -> int:

@@ -1,7 +1,8 @@
 // extern "C" entry points of libfaar (declared and documented in include/faar.h): argument
-// validation, workspace carving and kernel sequencing.  Nothing here allocates or synchronises.
+// validation, workspace carving and kernel sequencing.  Nothing here allocates device memory or synchronises.
 #include <cmath>
 #include <mutex>
+#include <vector>
 
 #include "../../include/faar.h"
 #include "faar_internal.h"
@@ -28,13 +29,19 @@ inline int hip_status(hipError_t e) {
 }
 
 // Optional event bracket around one kernel of the path (faar_time_kernel).
-struct Probe { int which; hipEvent_t start, stop; };
-thread_local Probe g_probe{FAAR_K_NONE, nullptr, nullptr};
+struct Probe { int which = FAAR_K_NONE; std::vector<hipEvent_t> events; int64_t count = 0; };   // events: start 0, stop 0, ...
+thread_local Probe g_probe;
 struct Bracket {
   bool on;
   hipStream_t st;
-  Bracket(int id, hipStream_t s) : on(g_probe.which == id), st(s) { if (on) (void)hipEventRecord(g_probe.start, st); }
-  ~Bracket() { if (on) (void)hipEventRecord(g_probe.stop, st); }
+  hipEvent_t stop;
+  Bracket(int id, hipStream_t s) : on(g_probe.which == id), st(s), stop(nullptr) {
+    if (!on) return;
+    const size_t pair = static_cast<size_t>(g_probe.count++) % (g_probe.events.size() / 2);
+    stop = g_probe.events[2 * pair + 1];
+    (void)hipEventRecord(g_probe.events[2 * pair], st);
+  }
+  ~Bracket() { if (on) (void)hipEventRecord(stop, st); }
 };
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -199,9 +206,25 @@ int faar_last_hip_error(void) { return g_last_hip_error; }
 int faar_time_kernel(int which, void* start_event, void* stop_event) {
   if (which < FAAR_K_NONE || which > FAAR_K_GEMM_GRAM || which == FAAR_K_GEMM_C) return FAAR_E_ARG;  // FAAR_K_GEMM_C has no bracket
   if (which != FAAR_K_NONE && (!start_event || !stop_event)) return FAAR_E_ARG;
-  g_probe = Probe{which, static_cast<hipEvent_t>(start_event), static_cast<hipEvent_t>(stop_event)};
+  void* const pair[2] = {start_event, stop_event};
+  return faar_time_kernel_ring(which, pair, 1);
+}
+
+int faar_time_kernel_ring(int which, void* const* events, int n) {
+  if (which < FAAR_K_NONE || which > FAAR_K_GEMM_GRAM || which == FAAR_K_GEMM_C) return FAAR_E_ARG;
+  g_probe.which = FAAR_K_NONE;
+  g_probe.events.clear();
+  g_probe.count = 0;
+  if (which == FAAR_K_NONE) return FAAR_OK;
+  if (!events || n < 1 || n > 4096) return FAAR_E_ARG;
+  for (int i = 0; i < 2 * n; ++i)
+    if (!events[i]) return FAAR_E_ARG;
+  for (int i = 0; i < 2 * n; ++i) g_probe.events.push_back(static_cast<hipEvent_t>(events[i]));
+  g_probe.which = which;
   return FAAR_OK;
 }
+
+int64_t faar_time_kernel_count(void) { return g_probe.count; }
 
 int faar_dw_split(int64_t O, int64_t K, int64_t T) {
   if (check_shape(O, K) != FAAR_OK || T <= 0) return 0;
