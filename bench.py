@@ -1111,7 +1111,8 @@ def run_gemm_ceiling(args) -> dict:
     """What bounds the GEMM main loop, measured through the library's own kernel (faar_gemm_probe) on one product
     (default: the Llama3-1B-shaped gate_proj dW GEMM, 8192 x 2048 outputs, contraction over 4096 tokens), random bf16 operands: the
     loop with only its matrix instructions (operands read from LDS, nothing copied), with only its global->LDS copies,
-    and whole -- each with the core clock the compute units ran at (shader clock counter / constant 100 MHz counter)."""
+    and whole -- each with the core clock the compute units ran at (shader clock counter / constant 100 MHz counter), in
+    steady state; then with the operands evicted from the last-level cache before every launch, and the vendor library."""
     import torch
 
     from paper_2603_22370_amd import binding as fb
@@ -1123,32 +1124,63 @@ def run_gemm_ceiling(args) -> dict:
     B = torch.randn((N, Kd), generator=gen, device="cuda").to(torch.bfloat16)
     A0, B0 = torch.zeros_like(A), torch.zeros_like(B)
     flops = 2.0 * M * N * Kd
+    est_ms = flops / 1.0e12                                   # ~1 PFLOP/s: only sizes the loops below
+    n_warm, n_time = max(10, int(80.0 / est_ms)), max(10, int(25.0 / est_ms))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     rows = {}
-    for label, mode, a, b in (("whole loop", fb.PROBE_FULL, A, B), ("matrix instructions only", fb.PROBE_MFMA_ONLY, A, B),
-                              ("copies only", fb.PROBE_DMA_ONLY, A, B), ("whole loop, all-zero operands", fb.PROBE_FULL, A0, B0)):
-        for _ in range(3):
-            clocks, variant = fb.faar_gemm_probe(mode, a, b)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(10):
-            clocks, variant = fb.faar_gemm_probe(mode, a, b)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) / 10 * 1e3
+
+    def row_of(us, clocks, variant, with_flops=True):
         c = clocks.cpu().numpy().astype("float64")
         core, wall = c[:, 0], c[:, 1]
         mhz = float((core / (wall / 100.0)).mean())            # the constant counter ticks at 100 MHz
         row = {"us": round(us, 1), "core_mhz": round(mhz, 0), "core_cycles_per_item": round(float(core.mean()), 0), "variant": variant}
-        if mode != fb.PROBE_DMA_ONLY:
+        if with_flops:
             row["tflops"] = round(flops / us / 1e6, 1)
             row["frac_of_published_peak"] = round(flops / us / 1e6 / BF16_PEAK_TFLOPS, 4)
             # what the matrix cores can deliver at the clock they actually ran at
             row["frac_of_peak_at_measured_clock"] = round(flops / us / 1e6 / (BF16_PEAK_TFLOPS * mhz / 2400.0), 4)
-        rows[label] = row
+        return row
+
+    # steady state: ~80 ms of back-to-back launches before the timed ones (from idle the clocks take tens of ms to settle)
+    for label, mode, a, b in (("whole loop", fb.PROBE_FULL, A, B), ("matrix instructions only", fb.PROBE_MFMA_ONLY, A, B),
+                              ("copies only", fb.PROBE_DMA_ONLY, A, B), ("whole loop, all-zero operands", fb.PROBE_FULL, A0, B0)):
+        for _ in range(n_warm):
+            clocks, variant = fb.faar_gemm_probe(mode, a, b)
+        e0.record()
+        for _ in range(n_time):
+            clocks, variant = fb.faar_gemm_probe(mode, a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        rows[label] = row_of(e0.elapsed_time(e1) / n_time * 1e3, clocks, variant, mode != fb.PROBE_DMA_ONLY)
+    # the same loops when the operands are NOT in the 256 MB last-level cache, as a step's dW GEMM finds them: 512 MB are
+    # read (nothing written) before every launch; the events bracket the launch alone
+    evict = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").view(torch.int32)
+    n_cold = max(40, n_time)
+    for label, mode in (("whole loop, operands from HBM", fb.PROBE_FULL), ("copies only, operands from HBM", fb.PROBE_DMA_ONLY)):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_cold)]
+        for x, y in pairs:
+            evict.sum()
+            x.record()
+            clocks, variant = fb.faar_gemm_probe(mode, A, B)
+            y.record()
+        torch.cuda.synchronize()
+        ts = [x.elapsed_time(y) * 1e3 for x, y in pairs[n_cold // 2:]]
+        rows[label] = row_of(sum(ts) / len(ts), clocks, variant, mode != fb.PROBE_DMA_ONLY)
+    # the vendor GEMM library on the same operands (a plain product with a bf16 output), same schedule
+    Bt = B.t()
+    for _ in range(n_warm):
+        C = A @ Bt
+    e0.record()
+    for _ in range(n_time):
+        C = A @ Bt
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) / n_time * 1e3
+    rows["vendor library product (torch.matmul), with its bf16 output"] = {
+        "us": round(us, 1), "tflops": round(flops / us / 1e6, 1), "frac_of_published_peak": round(flops / us / 1e6 / BF16_PEAK_TFLOPS, 4)}
     whole = rows["whole loop"]
     return {
-        "metric": "GEMM main-loop ceiling", "value": whole["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": 10, "warmup": 3,
+        "metric": "GEMM main-loop ceiling", "value": whole["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": n_time, "warmup": n_warm,
         "ms_per_step": round(whole["us"] * 1e-3, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"gemm_ceiling: {M}x{N} outputs, contraction {Kd}, bf16 N(0,1) operands, float32 output", "M": M, "N": N, "Kd": Kd},

@@ -566,10 +566,14 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     }
   } else {
     Bracket b(FAAR_K_GEMM_RESIDUAL, st);
+    // X_q^T, which the dW GEMM reads next, was pushed out of the 256 MB last-level cache by the previous step's pass over
+    // V, m, u: the residual GEMM reads it on the side (when it is at most half that cache, and the dW GEMM will use it)
+    const int64_t xt_bytes = (int64_t)K * L.Tp * 2;
+    const bool warm_xt = xt_bytes <= ((int64_t)128 << 20);
     // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
     if (int e = hip_status(launch_gemm_residual(xq, delta, d1, Hs ? nullptr : C, x_scale, 2.0f * mse_scale,
                                                 (Hs && dY_ext) ? nullptr : dYt, L.Tp, need_local_dY ? dY : nullptr, mse_p,
-                                                &n_mse, guard, st)))
+                                                &n_mse, guard, warm_xt ? Xt : nullptr, xt_bytes, st)))
       return e;
   }
   const bf16_t* dY_used = dY;
@@ -1072,7 +1076,7 @@ int faar_hardened_loss(const void* W, faar_dtype wdt, int64_t O, int64_t K, cons
   int64_t n_mse = 0;
   const GemmDims d1{T, O, K, K, K};
   if (int e = hip_status(launch_gemm_residual(static_cast<const bf16_t*>(Xq), delta, d1, C, x_scale, 2.0f * mse_scale, dYt,
-                                              L.Tp, nullptr, mse_p, &n_mse, ForwardGuard{nullptr, {}}, st)))
+                                              L.Tp, nullptr, mse_p, &n_mse, ForwardGuard{nullptr, {}}, nullptr, 0, st)))
     return e;
   return hip_status(launch_finalize_losses(mse_p, n_mse, mse_scale, nullptr, 0, 0.0, 0.0f, loss, nullptr, nullptr, st));
 }

@@ -182,6 +182,10 @@ template <bool kWithC>
 struct EpiResidualT {
   static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
   static constexpr int kMode = 0;               // 0: the whole main loop (1, 2: measurement variants, see EpiProbe)
+  // The GEMM that follows (dW = dY^T X_q) reads X_q^T, which the pass that updates V has meanwhile pushed out of the
+  // last-level cache; with either operand coming from HBM that GEMM runs ~25 % slower.  The BK = 64 main loop of this
+  // kernel therefore reads `warm` (X_q^T, warm_chunks KB) on the side, 1 KB per wavefront and slice, and keeps nothing.
+  static constexpr bool kWarm = true;
   const float* C;
   const float* x_scale;  // device scalar multiplying the A operand (activations stored in units of it); null = 1
   float xs;
@@ -202,6 +206,8 @@ struct EpiResidualT {
   bf16_t* dY;
   double* partials;
   float sum;
+  const void* warm;      // null: nothing to read on the side
+  int64_t warm_chunks;   // its size in KB (whole 1 KB chunks)
   // C of rows m..m+3 (m a multiple of 4) of column n: one 16-byte load from the row-group-interleaved layout
   // [ceil(M/4)][N][4] (zero outside the matrix); kept separate from value4 so that a whole slab's loads can be
   // issued before the first dependent store
@@ -241,6 +247,7 @@ typedef EpiResidualT<false> EpiPerturbation;
 
 // sum of (x_scale * acc)^2 per work item and nothing else: the loss of a step whose dY comes from upstream
 struct EpiSumSq {
+  static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   const float* x_scale;
@@ -271,6 +278,7 @@ struct EpiSumSq {
 
 // out[split][m][n] = acc
 struct EpiF32 {
+  static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   float* out;
@@ -292,6 +300,7 @@ struct EpiF32 {
 // Rows M..4*ceil(M/4)-1 are written as zero.
 template <bool kYbf16>
 struct EpiSub {
+  static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   const void* Y;
@@ -326,6 +335,7 @@ struct EpiSub {
 
 // out[m][n] = bf16(scale * acc)
 struct EpiBf16 {
+  static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   bf16_t* out;
@@ -347,6 +357,7 @@ struct EpiBf16 {
 // out[split][m][n] = two_alpha * x_scale * t  (what the dW GEMM of the token form leaves for the pass that updates V);
 // per work item the partial sum of x_scale^2 * t * A[m][n], which over all items is ||x_scale Xq (W_q - W)^T||^2.
 struct EpiGram {
+  static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   const bf16_t* delta;     // the A operand, [M, N] row-major
@@ -391,6 +402,7 @@ struct EpiGram {
 template <int MODE>
 struct EpiProbe {
   static constexpr bool kTransposedOut = false;
+  static constexpr bool kWarm = false;
   static constexpr int kMode = MODE;
   unsigned long long* clocks;   // [items][2]
   float* sink;
@@ -662,6 +674,8 @@ __global__ void __launch_bounds__(C::THREADS)
 k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims d, int tiles_m, int tiles_n, int n_split,
              int ksteps_per_split, Epi epi) {
   __shared__ __attribute__((aligned(1024))) bf16_t lds[C::NS * C::STAGE];
+  // where the side reads of an epilogue with kWarm land: 1 KB per wavefront, never read
+  __shared__ __attribute__((aligned(1024))) uint32_t warm_sink[Epi::kWarm ? C::NW * 256 : 4];
   epi.once();
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / C::WGN) * C::WM, wn = (wave % C::WGN) * C::WN;
@@ -673,6 +687,10 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
   const int kend = kbeg + ksteps_per_split < ksteps ? kbeg + ksteps_per_split : ksteps;
   const int nk = kend - kbeg;
   constexpr int P = C::P, KK = C::KK, NF = C::NF, NM = C::NM, TM = C::TM, TN = C::TN;
+  // vector-memory instructions a wavefront issues per slice: the copies, and one side read with kWarm.  Loads complete
+  // in order, so the wait counts below are in units of this
+  constexpr int PW = P + (Epi::kWarm ? 1 : 0);
+  static_assert(PW * (C::NS - 1) < 64, "vmcnt is a 6-bit counter");
 
   f32x4 acc[TM][TN];
 #pragma unroll
@@ -699,6 +717,19 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
         gsrc[q] = B + n * d.ldb + chunk * 8;
       }
     }
+    // side read (kWarm) that goes with slice `rel` of this work item: the 1 KB chunk of the epilogue's buffer whose number
+    // counts (workgroup, slice, wavefront) triples from the END of the launch (workgroups are dispatched in the order of
+    // their ids), so that the buffer is read late, close to the kernel that wants it; triples beyond the buffer re-read one
+    // valid address (the instruction count per slice stays uniform)
+    const uint32_t warm_dst = __builtin_amdgcn_readfirstlane(lds_addr_of(warm_sink + (Epi::kWarm ? wave * 256 : 0)));
+    const int64_t warm_last = ((int64_t)gridDim.x - blockIdx.x) * nk - 1;   // triple number of slice 0, before the wavefront
+    static_assert(!Epi::kWarm || (P - 1) * C::DSTEP + 1 < NM, "room for the side read after the slice's last copy");
+#define FAAR_SIDE_READ(REL)                                                                                              \
+  if constexpr (Epi::kWarm) {                                                                                            \
+    const int64_t chunk_ = (warm_last - (REL)) * C::NW + wave;                                                           \
+    const bool in_ = epi.warm != nullptr && (REL) < nk && chunk_ < epi.warm_chunks;                                      \
+    dma16(in_ ? static_cast<const char*>(epi.warm) + chunk_ * 1024 + lane * 16 : reinterpret_cast<const char*>(A), warm_dst); \
+  }
 #pragma unroll
     for (int s = 0; s < C::NS; ++s) {
       const int t = kbeg + (s < nk ? s : nk - 1);
@@ -706,6 +737,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       for (int q = 0; q < P; ++q)
         dma16(gsrc[q] + (int64_t)t * DBK64,
               __builtin_amdgcn_readfirstlane(lds_addr_of(lds + s * C::STAGE + (wave * P + q) * C::RPI * DBK64)));
+      FAAR_SIDE_READ(s)
     }
 
     // fragment addresses: row = w? + i*16 + lane % 16, chunk = 4*kk + lane / 16, slot = chunk ^ ((row / RB) % CPR);
@@ -721,7 +753,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     }
     bf16x8 fa[2][TM], fb[2][TN];
 
-    FAAR_WAIT_VMCNT(P * (C::NS - 1));  // slice 0 has landed (mine); barrier: everybody's
+    FAAR_WAIT_VMCNT(PW * (C::NS - 1));  // slice 0 has landed (mine); barrier: everybody's
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -745,7 +777,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
         if (kk == KK - 1) {
           // this wavefront's copies of slice it+1 have landed and its reads of slice it are complete;
           // after the barrier that holds for the workgroup: stage `st` may be refilled, `sn` may be read
-          constexpr int kInFlight = P * (C::NS - 2);  // copies of later slices may stay in flight
+          constexpr int kInFlight = PW * (C::NS - 2);  // copies of later slices may stay in flight
           __builtin_amdgcn_s_waitcnt(0x0070 | (kInFlight & 0xF) | ((kInFlight >> 4) << 14));  // vmcnt(kInFlight) lgkmcnt(0)
           __builtin_amdgcn_s_barrier();
         }
@@ -769,11 +801,15 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
             const bf16_t* g = more ? gsrc[q] + goff : A;
             dma16(g, __builtin_amdgcn_readfirstlane(lds_addr_of(st + (wave * P + q) * C::RPI * DBK64)));
           }
+          if (Epi::kMode != 1 && kk == KK - 1 && m == (P - 1) * C::DSTEP + 1) {   // right after the slice's last copy
+            FAAR_SIDE_READ(it + C::NS)
+          }
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
     FAAR_WAIT_VMCNT(0);  // no copy may still be in flight into this workgroup's LDS when it retires
+#undef FAAR_SIDE_READ
   }
 
   // accumulator layout of the 16x16 tile: lane -> column lane % 16, rows 4 * (lane / 16) + 0..3
@@ -927,16 +963,18 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {  // the most 
 
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
-                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, hipStream_t st) {
+                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, const void* warm,
+                                int64_t warm_bytes, hipStream_t st) {
+  const int64_t warm_chunks = warm ? warm_bytes / 1024 : 0;
   if (C) {
-    EpiResidual e{C, x_scale, 1.0f, guard, two_alpha, dYt, ldt, dY, mse_partials, 0.0f};
+    EpiResidual e{C, x_scale, 1.0f, guard, two_alpha, dYt, ldt, dY, mse_partials, 0.0f, warm, warm_chunks};
     const Plan p = plan_gemm(d, false, kEpiResidual);
     *n_partials = p.items();
     return run(A, B, d, p, e, st);
   }
   if (dY) return hipErrorInvalidValue;   // the un-transposed dY exists only with the constant
   if (dYt) {
-    EpiPerturbation e{nullptr, x_scale, 1.0f, guard, two_alpha, dYt, ldt, nullptr, mse_partials, 0.0f};
+    EpiPerturbation e{nullptr, x_scale, 1.0f, guard, two_alpha, dYt, ldt, nullptr, mse_partials, 0.0f, warm, warm_chunks};
     const Plan p = plan_gemm(d, false, kEpiBf16);
     *n_partials = p.items();
     return run(A, B, d, p, e, st);

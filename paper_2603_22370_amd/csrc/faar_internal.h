@@ -177,9 +177,12 @@ struct GemmDims { int64_t M, N, Kd, lda, ldb; };
 // C == nullptr: the V-dependent part alone -- A = x_scale * acc, sum A^2 per tile, dYt = bf16(two_alpha * A) (dY must
 // be null); with dYt == nullptr too, only the sums are produced.
 // guard: when its slot is set, workgroup 0 first compares the stored forward tag with guard.expect (see ForwardTag)
+// warm (nullable), warm_bytes: a buffer the BK = 64 kernels read on the side during the main loop and discard, so that the
+// next kernel finds it in the last-level cache (X_q^T for the dW GEMM); 16-byte aligned, whole KB are read
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
-                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, hipStream_t st);
+                                double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, const void* warm,
+                                int64_t warm_bytes, hipStream_t st);
 // number of per-work-item loss partials the residual GEMM writes for these sizes
 int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 // Plain float32 output with the contraction split n_split ways: out[s][m][n] (split stride M*N).
