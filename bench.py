@@ -472,7 +472,8 @@ def run_linear(args) -> dict:
     X_h = synth.silu_gated_activations(T, K, seed=0) if gated else synth.activations(T, K, seed=0)
     W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
     Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
-    j = LinearJob(args.workload, O, K, T, W, Xq, args.quantised_acts)
+    j = LinearJob(args.workload, O, K, T, W, Xq, args.quantised_acts, args.form)
+    gram = args.form == "gram"
     torch.cuda.synchronize()
 
     def layer_job(n_steps):
@@ -496,7 +497,8 @@ def run_linear(args) -> dict:
         trial = torch.empty(args.stochastic_trials, dtype=torch.float32, device="cuda")
         for k in range(args.stochastic_trials):
             Vs = faar.faar_stochastic_v(W, s["sg"], s["scales"], 2603, k)
-            faar.faar_hardened_loss(W, s["sg"], s["scales"], Vs, j.Xq, s["C"], j.alpha, j.ws, x_scale=j.x_scale, loss=trial[k:k + 1])
+            faar.faar_hardened_loss(W, s["sg"], s["scales"], Vs, j.Xq, s["C"], j.alpha,
+                                    j.ws if not gram else faar.layer_step_workspace(O, K, T), x_scale=j.x_scale, loss=trial[k:k + 1])
         tl = trial.cpu().numpy()
         stochastic = {"trials": int(tl.size), "better_than_rtn": int((tl < loss_rtn).sum()), "best": float(tl.min()),
                       "mean": float(tl.mean()), "std": float(tl.std())}
@@ -517,7 +519,7 @@ def run_linear(args) -> dict:
     probe["softquant_fwd_bwd_call"] = te0.elapsed_time(te1) / n_probe
     del dWt
     kernels = j.kernel_table(probe)
-    dom = max(("gemm_residual", "gemm_dw", "bwd_adam"), key=lambda k: probe[k])
+    dom = max(("gemm_gram", "bwd_adam") if gram else ("gemm_residual", "gemm_dw", "bwd_adam"), key=lambda k: probe[k])
     roofline = {"kernel": dom, "bound": kernels[dom]["bound"], "achieved": kernels[dom]["achieved"],
                 "peak": BF16_PEAK_TFLOPS if kernels[dom]["bound"] == "mfma" else HBM_PEAK_GBS,
                 "unit": kernels[dom]["unit"], "frac": kernels[dom]["frac"], "traffic": kernels[dom]["traffic"],
@@ -530,12 +532,12 @@ def run_linear(args) -> dict:
         torch.cuda.synchronize()
 
     ms_per_step = elapsed / args.steps * 1e3
-    gemm_flops = 2.0 * T * O * K
+    gemm_flops = 2.0 * T * O * K if not gram else 1.0 * O * K * K      # per GEMM; two GEMMs (token form) or "half of two" (Gram form)
     out = {
         "metric": "FAAR layer steps/sec (fwd+bwd+Adam)", "value": round(args.steps / elapsed, 2), "unit": "steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} "
+        "config": {"workload": f"{args.workload}{' in the optional Gram-matrix form of the step (faar_layer_step_gram)' if gram else ''}: W {O}x{K} bf16 Student-t(4) std 0.02, X {T}x{K} "
                                f"{'NVFP4-quantised (W4A4)' if args.quantised_acts else 'bf16'}, NVFP4 block 16; "
                                "per-layer job = quant_rtn + init_v + prepare + K steps + harden_pack",
                    "O": O, "K": K, "T": T},
@@ -1206,6 +1208,8 @@ def main() -> int:
                     help="single-linear workloads: after the job, rank this many stochastic-rounding candidates by hardened reconstruction loss")
     ap.add_argument("--gemm-shape", default="8192,2048,4096",
                     help="gemm_ceiling: outputs M x N and contraction, default the Llama3-1B-shaped gate_proj dW GEMM")
+    ap.add_argument("--form", default="token", choices=["token", "gram"],
+                    help="single-linear workloads: faar_layer_step (token) or the optional faar_layer_step_gram (gram)")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
                     help="qwen_layer: HIP streams the seven independent per-linear jobs are issued on")
     ap.add_argument("--no-cpu-baseline", action="store_true")

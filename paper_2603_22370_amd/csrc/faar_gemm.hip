@@ -180,6 +180,7 @@ __device__ __forceinline__ void finish_sum(float sum, double* partials, int item
 //          dYt[n][m] = bf16(two_alpha A).  Nothing is read in the epilogue.
 template <bool kWithC>
 struct EpiResidualT {
+  static constexpr bool kRowStaged = false;
   static constexpr bool kTransposedOut = true;  // the fast kernel stages dYt through LDS for full-line stores
   static constexpr int kMode = 0;               // 0: the whole main loop (1, 2: measurement variants, see EpiProbe)
   // The GEMM that follows (dW = dY^T X_q) reads X_q^T, which the pass that updates V has meanwhile pushed out of the
@@ -247,6 +248,7 @@ typedef EpiResidualT<false> EpiPerturbation;
 
 // sum of (x_scale * acc)^2 per work item and nothing else: the loss of a step whose dY comes from upstream
 struct EpiSumSq {
+  static constexpr bool kRowStaged = false;
   static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
@@ -279,6 +281,7 @@ struct EpiSumSq {
 // out[split][m][n] = acc
 struct EpiF32 {
   static constexpr bool kWarm = false;
+  static constexpr bool kRowStaged = true;   // the BK = 64 kernel hands it runs of 8 columns of a row (run8)
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   float* out;
@@ -291,6 +294,13 @@ struct EpiF32 {
     for (int q = 0; q < 4; ++q)
       if (m + q < d.M) o[(m + q) * d.N + n] = acc[q];
   }
+  // columns n..n+7 of row m (n and N multiples of 8)
+  __device__ __forceinline__ void run8(const float (&r)[8], int64_t m, int64_t n, int split, const GemmDims& d) {
+    if (m >= d.M || n >= d.N) return;
+    float4* o = reinterpret_cast<float4*>(out + (int64_t)split * d.M * d.N + m * d.N + n);
+    o[0] = make_float4(r[0], r[1], r[2], r[3]);
+    o[1] = make_float4(r[4], r[5], r[6], r[7]);
+  }
   __device__ __forceinline__ void finish(int) {}
 };
 
@@ -300,6 +310,7 @@ struct EpiF32 {
 // Rows M..4*ceil(M/4)-1 are written as zero.
 template <bool kYbf16>
 struct EpiSub {
+  static constexpr bool kRowStaged = false;
   static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
@@ -335,6 +346,7 @@ struct EpiSub {
 
 // out[m][n] = bf16(scale * acc)
 struct EpiBf16 {
+  static constexpr bool kRowStaged = false;
   static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
@@ -358,6 +370,7 @@ struct EpiBf16 {
 // per work item the partial sum of x_scale^2 * t * A[m][n], which over all items is ||x_scale Xq (W_q - W)^T||^2.
 struct EpiGram {
   static constexpr bool kWarm = false;
+  static constexpr bool kRowStaged = true;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
   const bf16_t* delta;     // the A operand, [M, N] row-major
@@ -392,6 +405,29 @@ struct EpiGram {
         sum += k_sum * (t * a);
       }
   }
+  // columns n..n+7 of row m (n and N multiples of 8): one 16-byte load of delta, two of diag_lo, two 16-byte stores
+  __device__ __forceinline__ void run8(const float (&r)[8], int64_t m, int64_t n, int split, const GemmDims& d) {
+    if (m >= d.M || n >= d.N) return;
+    const uint4 dv = *reinterpret_cast<const uint4*>(delta + m * d.N + n);
+    const uint32_t dw[4] = {dv.x, dv.y, dv.z, dv.w};
+    float lo[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    if (split == 0) {
+      const float4 l0 = *reinterpret_cast<const float4*>(diag_lo + n), l1 = *reinterpret_cast<const float4*>(diag_lo + n + 4);
+      lo[0] = l0.x; lo[1] = l0.y; lo[2] = l0.z; lo[3] = l0.w; lo[4] = l1.x; lo[5] = l1.y; lo[6] = l1.z; lo[7] = l1.w;
+    }
+    const float k_out = two_alpha * xs, k_sum = xs * xs;
+    float o[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float a = __uint_as_float((j & 1) ? (dw[j >> 1] & 0xFFFF0000u) : (dw[j >> 1] << 16));
+      const float t = r[j] + a * lo[j];
+      o[j] = k_out * t;
+      sum += k_sum * (t * a);
+    }
+    float4* op = reinterpret_cast<float4*>(out + (int64_t)split * d.M * d.N + m * d.N + n);
+    op[0] = make_float4(o[0], o[1], o[2], o[3]);
+    op[1] = make_float4(o[4], o[5], o[6], o[7]);
+  }
   __device__ __forceinline__ void finish(int item) { finish_sum(sum, partials, item); }
 };
 
@@ -403,6 +439,7 @@ template <int MODE>
 struct EpiProbe {
   static constexpr bool kTransposedOut = false;
   static constexpr bool kWarm = false;
+  static constexpr bool kRowStaged = false;
   static constexpr int kMode = MODE;
   unsigned long long* clocks;   // [items][2]
   float* sink;
@@ -620,6 +657,37 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
         const uint2 lo = src[0], hi = src[1];
         epi.store_chunk(make_uint4(lo.x, lo.y, hi.x, hi.y), m0 + ch * 8, n0 + (row / 32) * C::WN + j * 32 + (row % 32), d);
       }
+    }
+  } else if constexpr (Epi::kRowStaged) {
+    // as in k_gemm_dma64: one 32 x WN row of accumulator tiles per wavefront at a time through its own piece of LDS, handed
+    // to the epilogue as runs of 8 consecutive columns of a row
+    constexpr int PITCH = C::WN + 4;
+    constexpr int RUNS = 32 * (C::WN / 8) / 64;
+    static_assert(C::NW * 32 * PITCH * 4 <= DNS * C::STAGE * 2 && (32 * (C::WN / 8)) % 64 == 0, "staging fits in the ring");
+    float* stg = reinterpret_cast<float*>(lds) + wave * 32 * PITCH;
+    __syncthreads();                                 // nobody reads the ring any more
+#pragma unroll
+    for (int i = 0; i < C::TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < C::TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) stg[(8 * g + 4 * hi2 + v) * PITCH + j * 32 + col] = acc[i][j][4 * g + v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int t = 0; t < RUNS; ++t) {
+        const int idx = lane + 64 * t, row = idx / (C::WN / 8), cg = idx % (C::WN / 8);
+        const float4 a = *reinterpret_cast<const float4*>(stg + row * PITCH + cg * 8);
+        const float4 b = *reinterpret_cast<const float4*>(stg + row * PITCH + cg * 8 + 4);
+        const float r[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        epi.run8(r, m0 + wm + i * 32 + row, n0 + wn + cg * 8, split, d);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   } else {
 #pragma unroll
@@ -849,6 +917,35 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
         const uint2 lo = src[0], hi = src[1];
         epi.store_chunk(make_uint4(lo.x, lo.y, hi.x, hi.y), m0 + ch * 8, n0 + (row / 32) * C::WN + jj * 32 + (row % 32), d);
       }
+    }
+  } else if constexpr (Epi::kRowStaged) {
+    // every wavefront stages one 16 x WN row of its accumulator tiles at a time through its own piece of LDS and hands the
+    // epilogue runs of 8 consecutive columns of a row: 16-byte operand loads and stores, a quarter of the instructions
+    constexpr int PITCH = C::WN + 4;                 // floats; 4 * PITCH = 16 mod 32: the two row groups of a half-wave miss each other
+    constexpr int RUNS = 16 * (C::WN / 8) / 64;      // runs per lane and staged row
+    static_assert(C::NW * 16 * PITCH * 4 <= C::NS * C::STAGE * 2 && (16 * (C::WN / 8)) % 64 == 0, "staging fits in the ring");
+    float* stg = reinterpret_cast<float*>(lds) + wave * 16 * PITCH;
+    __syncthreads();                                 // nobody reads the ring any more
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) stg[(4 * rq + v) * PITCH + j * 16 + col] = acc[i][j][v];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int t = 0; t < RUNS; ++t) {
+        const int idx = lane + 64 * t, row = idx / (C::WN / 8), cg = idx % (C::WN / 8);
+        const float4 a = *reinterpret_cast<const float4*>(stg + row * PITCH + cg * 8);
+        const float4 b = *reinterpret_cast<const float4*>(stg + row * PITCH + cg * 8 + 4);
+        const float r[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        epi.run8(r, m0 + wm + i * 16 + row, n0 + wn + cg * 8, split, d);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
   } else {
 #pragma unroll
