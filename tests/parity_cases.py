@@ -50,4 +50,12 @@ STEP_CASES = [
     StepCase("qwen_gate_proj_T16384", 6144, 2048, 16384, 4, chained=True, full_size=True),
 ]
 
-BY_NAME = {c.name: c for c in STEP_CASES}
+# Cases only the Gram-matrix form of the step runs (tests/test_gpu_gram.py, next to all of STEP_CASES): shapes whose
+# O x K x K product takes a kernel variant none of the above reaches with that epilogue
+GRAM_CASES = [
+    StepCase("gram_256x128_split", 1024, 2112, 256, 41),          # 256x128 tiles, 64-wide slices, contraction split
+    StepCase("gram_256x128_k64", 4096, 1088, 192, 42),            # 256x128 tiles, 64-wide slices, whole
+    StepCase("gram_256x128_k32", 4096, 1056, 192, 43),            # 256x128 tiles, 32-wide slices
+]
+
+BY_NAME = {c.name: c for c in STEP_CASES + GRAM_CASES}

@@ -318,3 +318,18 @@ def test_gram_form_calls_reject_bad_arguments_without_a_gpu():
     assert call(o=fb.faar_adam(1e-3, 1.0, 0.999, 1e-8, 1)) == -6
     assert call(cn=ctypes.c_void_p(0x1004)) == -6
     assert call(n=n_step - 1) == -4 and call(w=nul, n=0) == -4
+
+
+def test_timing_hook_ring_validates_its_arguments_without_a_gpu():
+    L = fb.lib()
+    ev = (ctypes.c_void_p * 8)(*[0x1000 + 16 * i for i in range(8)])
+    assert L.faar_time_kernel_ring(fb.K_GEMM_DW, ev, 4) == 0
+    assert L.faar_time_kernel_count() == 0
+    assert L.faar_time_kernel_ring(fb.K_GEMM_DW, ev, 0) == -6 and L.faar_time_kernel_ring(fb.K_GEMM_DW, ev, 4097) == -6
+    assert L.faar_time_kernel_ring(fb.K_GEMM_DW, None, 4) == -6
+    assert L.faar_time_kernel_ring(99, ev, 4) == -6 and L.faar_time_kernel_ring(fb.K_GEMM_C, ev, 4) == -6
+    holes = (ctypes.c_void_p * 8)(*[0x1000, 0, 0x1020, 0x1030, 0x1040, 0x1050, 0x1060, 0x1070])
+    assert L.faar_time_kernel_ring(fb.K_GEMM_DW, holes, 4) == -6
+    assert L.faar_time_kernel_ring(fb.K_NONE, None, 0) == 0       # off; the old single-pair form still works
+    assert L.faar_time_kernel(fb.K_GEMM_GRAM, ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1010)) == 0
+    assert L.faar_time_kernel(fb.K_NONE, None, None) == 0

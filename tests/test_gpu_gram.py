@@ -7,7 +7,7 @@ import torch
 from oracle import faar_oracle as fo
 from workloads import synth
 
-from parity_cases import BY_NAME, STEP_CASES
+from parity_cases import BY_NAME, GRAM_CASES, STEP_CASES
 import test_gpu_parity as tp
 
 pytestmark = pytest.mark.gpu
@@ -24,7 +24,7 @@ dev, host, HYP, U = tp.dev, tp.host, tp.HYP, tp.U
 TOL_LOSS_DECLARED = 2e-5
 TOL_GRAD_DECLARED = 5e-4
 
-SMALL = [c.name for c in STEP_CASES if not c.full_size]
+SMALL = [c.name for c in STEP_CASES + GRAM_CASES if not c.full_size]
 FULL = [c.name for c in STEP_CASES if c.full_size]
 
 

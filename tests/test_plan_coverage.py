@@ -8,7 +8,7 @@ import itertools
 
 from paper_2603_22370_amd import binding as fb
 
-from parity_cases import STEP_CASES
+from parity_cases import GRAM_CASES, STEP_CASES
 
 GEMMS = {"residual": fb.K_GEMM_RESIDUAL, "dw": fb.K_GEMM_DW, "dx": fb.K_GEMM_DX, "c": fb.K_GEMM_C}
 DIMS = [16, 32, 48, 64, 80, 96, 128, 160, 192, 224, 256, 288, 320, 384, 448, 512, 640, 768, 1024, 1280, 1536, 2048,
@@ -74,3 +74,22 @@ def test_forward_gemm_of_the_joint_step_runs_kernels_that_parity_cases_cover():
     for O, K in ((6144, 2048), (2048, 6144)):
         kind, bm, bn, _ = fb.faar_gemm_plan(fb.K_GEMM_FWD, O, K, 16384)
         assert (kind, bm, bn) in covered, (O, K, kind)
+
+
+def test_gram_form_product_runs_kernels_that_its_parity_cases_cover():
+    """The O x K x K product of faar_layer_step_gram: every (variant, tile, split or not) any layer shape can take is taken
+    by one of the cases tests/test_gpu_gram.py runs (all of STEP_CASES and GRAM_CASES), and the benchmark's layer shapes by full-size ones."""
+    def combo(O, K):
+        kind, bm, bn, split = fb.faar_gemm_plan(fb.K_GEMM_GRAM, O, K, 1)
+        return (kind, (bm, bn), "split" if split > 1 else "whole")
+
+    reachable = {}
+    for O, K in itertools.product(DIMS, DIMS):
+        if K % 16 == 0:
+            reachable.setdefault(combo(O, K), (O, K))
+    covered = {combo(c.O, c.K) for c in STEP_CASES + GRAM_CASES}
+    missing = {k: v for k, v in reachable.items() if k not in covered}
+    assert not missing, f"Gram-form variants no parity case reaches (with an example shape): {missing}"
+    full = {combo(c.O, c.K) for c in STEP_CASES if c.full_size}
+    for O, K in [(2048, 2048), (512, 2048), (8192, 2048), (2048, 8192), (1024, 2048), (6144, 2048), (2048, 6144)]:
+        assert combo(O, K) in full, (O, K, combo(O, K))
