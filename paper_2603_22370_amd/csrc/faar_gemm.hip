@@ -346,7 +346,7 @@ struct EpiSub {
 
 // out[m][n] = bf16(scale * acc)
 struct EpiBf16 {
-  static constexpr bool kRowStaged = false;
+  static constexpr bool kRowStaged = true;    // the DMA kernels hand it runs of 8 columns of a row (run8)
   static constexpr bool kWarm = false;
   static constexpr bool kTransposedOut = false;
   static constexpr int kMode = 0;
@@ -360,6 +360,19 @@ struct EpiBf16 {
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       if (m + q < d.M) out[(m + q) * d.N + n] = static_cast<bf16_t>(f32_to_bf16(sc * acc[q]));
+  }
+  // columns n..n+7 of row m (n a multiple of 8): one 16-byte store when the row pitch allows it
+  __device__ __forceinline__ void run8(const float (&r)[8], int64_t m, int64_t n, int, const GemmDims& d) {
+    if (m >= d.M || n >= d.N) return;
+    bf16_t* o = out + m * d.N + n;
+    if (n + 8 <= d.N && (d.N & 7) == 0) {
+      uint32_t w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) w[j] = f32_to_bf16(sc * r[2 * j]) | (f32_to_bf16(sc * r[2 * j + 1]) << 16);
+      *reinterpret_cast<uint4*>(o) = make_uint4(w[0], w[1], w[2], w[3]);
+    } else {
+      for (int j = 0; j < 8 && n + j < d.N; ++j) o[j] = static_cast<bf16_t>(f32_to_bf16(sc * r[j]));
+    }
   }
   __device__ __forceinline__ void finish(int) {}
 };
