@@ -98,7 +98,10 @@ def _layer(O, K, seed):
 
 def test_linear_forward():
     # the last shape takes the 256x256-tile kernel with 32 contraction slices (the benchmark's gate projection, a slice of its tokens)
-    for (O, K, T, seed) in ((96, 80, 100, 1), (640, 256, 300, 2), (2048, 512, 1024, 3), (6144, 2048, 2048, 4)):
+    # (100, 128) and (300, 64): output widths that are not multiples of 8 -- rows whose pitch rules out 16-byte stores, and a
+    # last run of columns that is cut short -- through the 128x128-tile kernel and (the last two) both 64-wide-slice kernels
+    for (O, K, T, seed) in ((96, 80, 100, 1), (640, 256, 300, 2), (2048, 512, 1024, 3), (6144, 2048, 2048, 4),
+                            (100, 128, 200, 5), (300, 64, 2048, 6), (1028, 64, 4096, 7), (2052, 64, 4096, 8)):
         W, sg, sb, V = _layer(O, K, seed)
         X = synth.activations(T, K, seed)
         Wd = dev(W)
