@@ -170,6 +170,12 @@ int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, c
  * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
 int64_t faar_padded_tokens(int64_t T);
 
+/* 1 when a step of an O x K layer over T tokens that is given an upstream gradient (dY_ext) runs its dW GEMM on the token-major
+ * operands as they are -- dY_ext [T, O] and Xq [T, K], no transposed copies -- else 0 (T not a multiple of 64, O or K not a
+ * multiple of 8, or a shape that takes other tiles than 256 x 256).  Such a step neither reads nor, with FAAR_STEP_JOINT, writes
+ * Xt.  Pure host function. */
+int faar_dw_token_major(int64_t O, int64_t K, int64_t T);
+
 /*
  * Round-to-nearest NVFP4 quantisation of a tensor -- the baseline rounding of Sec. 3.1/3.2 and
  * the two-level scaling of Table 2 step 2.
@@ -332,7 +338,9 @@ typedef struct {
  *                       C may be NULL, H must be).  The activations Xq are the quantised model's own and change with
  *                       every step: the call writes their transpose into Xt itself (Xt is then scratch of
  *                       K * faar_padded_tokens(T) bf16, not an input; with FAAR_STEP_XT_READY it is an input again: the
- *                       transpose of this very Xq, left by the joint step of a sibling linear).  dX is normally requested.
+ *                       transpose of this very Xq, left by the joint step of a sibling linear) -- unless
+ *                       faar_dw_token_major(O, K, T), in which case Xt is not touched at all: a sibling that follows such a
+ *                       step and does need Xt must not be given FAAR_STEP_XT_READY.  dX is normally requested.
  *                       FAAR_WS_CHAINED is accepted and has no effect on the computation.
  *                       FAAR_WS_FORWARD_READY: skip the forward kernel and use what ws holds.  That is valid
  *                       when the previous call on this ws was step opt->t - 1 of the same layer (same W, scales,

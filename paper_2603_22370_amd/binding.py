@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
         L.faar_gemm_probe.restype = c_int
         L.faar_gemm_probe.argtypes = [c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
                                       ctypes.POINTER(c_int32), c_void_p]
+        L.faar_dw_token_major.restype = c_int
+        L.faar_dw_token_major.argtypes = [c_int64, c_int64, c_int64]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -247,6 +249,10 @@ def faar_gemm_probe(mode: int, A, B):
     _check(lib().faar_gemm_probe(mode, M, N, Kd, _ptr(A), _ptr(B), _ptr(clocks), cap, _ptr(sink), info, _stream()),
            "faar_gemm_probe")
     return clocks[:info[0]], GEMM_KINDS[info[1]]
+
+
+def faar_dw_token_major(O: int, K: int, T: int) -> bool:
+    return bool(lib().faar_dw_token_major(O, K, T))
 
 
 def faar_padded_tokens(T: int) -> int:

@@ -233,6 +233,11 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T) {
 
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
+int faar_dw_token_major(int64_t O, int64_t K, int64_t T) {
+  if (check_shape(O, K) != FAAR_OK || T <= 0) return 0;
+  return gemm_tn_usable(O, K, T) ? 1 : 0;
+}
+
 int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
                     unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream) {
   if (!A || !B || !clocks || !sink || !info) return FAAR_E_NULL;
@@ -557,11 +562,14 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   int64_t n_mse = 0;
   const GemmDims d1{T, O, K, K, K};
   const bool need_local_dY = dX && !dY_ext;
+  // An upstream gradient arrives token-major, as the activations are: where the token-major form of the dW GEMM applies, it
+  // takes both as they are -- no dY^T, and X_q^T is neither read nor (in a joint step) written
+  const bool token_major = dY_ext && gemm_tn_usable(O, K, T);
   if (joint) {
     if (flags & FAAR_WS_FORWARD_READY) {   // nobody else consumes the tag: check it in a kernel of its own
       if (int e = hip_status(launch_check_forward_tag(guard, st))) return e;
     }
-    if (!(flags & FAAR_STEP_XT_READY)) {
+    if (!(flags & FAAR_STEP_XT_READY) && !token_major) {
       if (int e = hip_status(launch_transpose_bf16(xq, T, K, static_cast<bf16_t*>(const_cast<void*>(Xt)), L.Tp, st))) return e;
     }
   } else {
@@ -576,16 +584,22 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
                                                 &n_mse, guard, warm_xt ? Xt : nullptr, xt_bytes, st)))
       return e;
   }
+  // otherwise the upstream gradient is transposed over dY^T
   const bf16_t* dY_used = dY;
-  if (dY_ext) {  // upstream gradient replaces the local one: overwrite dY^T
+  if (dY_ext) {
     dY_used = static_cast<const bf16_t*>(dY_ext);
-    if (int e = hip_status(launch_transpose_bf16(dY_used, T, O, dYt, L.Tp, st))) return e;
+    if (!token_major)
+      if (int e = hip_status(launch_transpose_bf16(dY_used, T, O, dYt, L.Tp, st))) return e;
   }
   // s3: G = dY^T X_q, contraction over tokens, split for occupancy
-  const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
   {
     Bracket b(FAAR_K_GEMM_DW, st);
-    if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;
+    if (token_major) {
+      if (int e = hip_status(launch_gemm_f32_tn(dY_used, xq, GemmDims{O, K, T, O, K}, G, L.n_split, st))) return e;
+    } else {
+      const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
+      if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;
+    }
   }
   // s4: dX = dY W_q
   if (dX) {
@@ -978,10 +992,16 @@ int faar_block_joint_step(const faar_block* blk, const void* x, const void* y_fp
     return faar_linear_forward(l.W, blk->wdt, O, K, l.s_global, l.scales, l.V, beta, X, nullptr, T, Y, at(L.fwd_ws), L.fwd_bytes,
                                stream);
   };
-  auto backward = [&](int slot, const void* X, const void* dY, void* dX, bool xt_ready) {
+  // xt_shared: the linear reads the same activations as the one stepped just before it.  The transpose in the scratch is
+  // valid for it only if one of those earlier siblings needed it (a linear whose dW GEMM takes token-major operands
+  // neither reads nor writes it)
+  bool xt_valid = false;
+  auto backward = [&](int slot, const void* X, const void* dY, void* dX, bool xt_shared) {
     int64_t O, K;
     lin_shape(d, slot, O, K);
     const faar_block_linear& l = blk->lin[slot];
+    const bool xt_ready = xt_shared && xt_valid;
+    xt_valid = (xt_shared && xt_valid) || !gemm_tn_usable(O, K, T);
     const uint32_t flags = FAAR_WS_CHAINED | FAAR_STEP_JOINT | (xt_ready ? FAAR_STEP_XT_READY : 0u);
     return faar_layer_step(l.W, blk->wdt, O, K, l.s_global, l.scales, l.V, l.adam_m, l.adam_u, X, nullptr, at(L.xt), nullptr,
                            l.icodes, nullptr, nullptr, T, dY, dX, beta, 0.0f, lambda_round, 0.0f, opt, l.losses, flags,

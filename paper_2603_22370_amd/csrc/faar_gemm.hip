@@ -731,9 +731,15 @@ k_gemm_dma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDims 
 
 constexpr int DBK64 = 64;
 
-template <int BM_, int BN_, int WGM_, int WGN_, int NS_>
+// kTokenMajor_: both operands are stored with the contraction index as the ROW index (A [Kd, lda], B [Kd, ldb]; "TN" product
+// acc[m][n] = sum_t A[t][m] B[t][n]) -- activations and their gradients as the layers produce them, token-major.  A stage then
+// holds 64 rows (tokens) of BM + BN columns, and a wavefront gathers the 8 tokens x 1 column an MFMA lane needs with two of the
+// LDS transposing reads of this architecture (ds_read_b64_tr_b16) instead of one 16-byte read.
+template <int BM_, int BN_, int WGM_, int WGN_, int NS_, bool kTokenMajor_ = false>
 struct Dma64Cfg {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, NS = NS_;  // NS ring stages (2 or 3)
+  static constexpr bool kTokenMajor = kTokenMajor_;
+  static_assert(!kTokenMajor_ || (BM_ == 256 && BN_ == 256), "the token-major stage layout is written for 256 x 256 tiles");
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 16, TN = WN / 16;
@@ -749,6 +755,26 @@ struct Dma64Cfg {
   static_assert(NF * FSTEP <= NM && P * DSTEP <= NM && DSTEP >= 1, "phase schedule");
   static_assert((BM + BN) % (RPI * NW) == 0 && TN % 2 == 0 && (NS == 2 || NS == 3), "tile shape");
 };
+
+// Eight consecutive tokens of one column for every lane, from a token-major stage: two transposing reads of 4 tokens each.
+// Within a group of 16 lanes, lane r supplies the address of 4 consecutive columns of one token; lane i receives column
+// i % 4 of the tokens that lanes i / 4 + {0, 4, 8, 12} pointed at.  With lane r pointing at token r / 4, columns 4 (r % 4) ..,
+// lane i therefore receives column i of tokens 0..3: an MFMA operand row per lane.  `p`: this lane's address for the first
+// read; the second reads 4 tokens (4 * pitch elements) further on.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+template <int PITCH>
+__device__ __forceinline__ bf16x8 read_tokens8(const bf16_t* p) {
+  typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * PITCH));
+  const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+// XOR key of a token row's 16-byte chunk positions in a token-major stage (applied to bits 1..3 of the chunk index): the 16
+// token rows one transposing read touches (4 consecutive tokens in each of 4 groups 8 apart) fall into 8 different
+// 32-byte bank groups, two rows each -- the two cycles 512 bytes take anyway
+__device__ __forceinline__ int token_key(int t) { return (t & 3) | (((t >> 3) & 1) << 2); }
 
 template <class C, class Epi>
 __global__ void __launch_bounds__(C::THREADS)
@@ -786,16 +812,32 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     // stage: lane -> row = base + lane / CPR, LDS slot = lane % CPR, global chunk = slot ^ ((row / RB) % CPR).
     // Rows beyond M (or N) are clamped to the last valid row: their products are never stored.
     const bf16_t* gsrc[P];
+    int64_t gstep[P];   // elements from one slice to the next
 #pragma unroll
     for (int q = 0; q < P; ++q) {
-      const int trow = (wave * P + q) * C::RPI + lane / C::CPR;
-      const int chunk = (lane % C::CPR) ^ ((trow / C::RB) % C::CPR);
-      if (trow < C::BM) {
-        const int64_t m = m0 + trow < d.M ? m0 + trow : d.M - 1;
-        gsrc[q] = A + m * d.lda + chunk * 8;
+      if constexpr (C::kTokenMajor) {
+        // instruction u = wave * P + q fills 1 KB of the stage = two token rows of one operand's 256 columns: lane -> token
+        // 2 u' + lane / 32, LDS chunk lane % 32, global chunk = that ^ 2 key(token).  Columns beyond M (or N) are clamped to
+        // the last whole chunk: their products are never stored.
+        const int u = wave * P + q;
+        const bool is_a = u < C::BM / 8;
+        const int t = 2 * (is_a ? u : u - C::BM / 8) + lane / 32;
+        const int chunk = (lane % 32) ^ (2 * token_key(t));
+        const int64_t first = is_a ? m0 : n0, width = is_a ? d.M : d.N, ld = is_a ? d.lda : d.ldb;
+        const int64_t col = first + chunk * 8 <= width - 8 ? first + chunk * 8 : width - 8;
+        gsrc[q] = (is_a ? A : B) + t * ld + col;
+        gstep[q] = DBK64 * ld;
       } else {
-        const int64_t n = n0 + (trow - C::BM) < d.N ? n0 + (trow - C::BM) : d.N - 1;
-        gsrc[q] = B + n * d.ldb + chunk * 8;
+        const int trow = (wave * P + q) * C::RPI + lane / C::CPR;
+        const int chunk = (lane % C::CPR) ^ ((trow / C::RB) % C::CPR);
+        if (trow < C::BM) {
+          const int64_t m = m0 + trow < d.M ? m0 + trow : d.M - 1;
+          gsrc[q] = A + m * d.lda + chunk * 8;
+        } else {
+          const int64_t n = n0 + (trow - C::BM) < d.N ? n0 + (trow - C::BM) : d.N - 1;
+          gsrc[q] = B + n * d.ldb + chunk * 8;
+        }
+        gstep[q] = DBK64;
       }
     }
     // side read (kWarm) that goes with slice `rel` of this work item: the 1 KB chunk of the epilogue's buffer whose number
@@ -816,7 +858,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       const int t = kbeg + (s < nk ? s : nk - 1);
 #pragma unroll
       for (int q = 0; q < P; ++q)
-        dma16(gsrc[q] + (int64_t)t * DBK64,
+        dma16(gsrc[q] + (int64_t)t * gstep[q],
               __builtin_amdgcn_readfirstlane(lds_addr_of(lds + s * C::STAGE + (wave * P + q) * C::RPI * DBK64)));
       FAAR_SIDE_READ(s)
     }
@@ -832,18 +874,37 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       a_off[kk] = (wm + fr) * DBK64 + slot;
       b_off[kk] = C::BM * DBK64 + (wn + fr) * DBK64 + slot;
     }
+    // token-major stage: element offset of this lane's first transposing read for fragment i (A) / j (B) of phase 0.  The
+    // lane points at token 8 (lane / 16) + (lane % 16) / 4 of the phase's 32 and at columns w? + 16 i + 4 (lane % 4); that
+    // token's XOR key is the same in every phase and for both reads of a fragment
+    int a_tr[TM] = {}, b_tr[TN] = {};
+    if constexpr (C::kTokenMajor) {
+      const int tok = 8 * kc + (fr >> 2), key = (fr >> 2) | ((kc & 1) << 2);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a_tr[i] = tok * C::BM + wm + ((i ^ key) * 16) + (fr & 3) * 4;
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b_tr[j] = C::BM * DBK64 + tok * C::BN + (((wn / 8 + 2 * j) ^ (2 * key)) * 8) + (fr & 3) * 4;
+    }
+    // fragment i of the A rows (j of the B rows) for phase kk, from the stage at `src`
+#define FAAR_FRAG_A(SRC, KKI, I)                                                                                         \
+  (C::kTokenMajor ? read_tokens8<C::BM>((SRC) + a_tr[I] + 32 * (KKI) * C::BM)                                            \
+                  : *reinterpret_cast<const bf16x8*>((SRC) + a_off[KKI] + (I) * 16 * DBK64))
+#define FAAR_FRAG_B(SRC, KKI, J)                                                                                         \
+  (C::kTokenMajor ? read_tokens8<C::BN>((SRC) + b_tr[J] + 32 * (KKI) * C::BN)                                            \
+                  : *reinterpret_cast<const bf16x8*>((SRC) + b_off[KKI] + (J) * 16 * DBK64))
     bf16x8 fa[2][TM], fb[2][TN];
 
     FAAR_WAIT_VMCNT(PW * (C::NS - 1));  // slice 0 has landed (mine); barrier: everybody's
     __builtin_amdgcn_s_barrier();
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      fa[0][i] = *reinterpret_cast<const bf16x8*>(lds + a_off[0] + i * 16 * DBK64);
+      fa[0][i] = FAAR_FRAG_A(lds, 0, i);
       fa[1][i] = fa[0][i];
     }
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      fb[0][j] = *reinterpret_cast<const bf16x8*>(lds + b_off[0] + j * 16 * DBK64);
+      fb[0][j] = FAAR_FRAG_B(lds, 0, j);
       fb[1][j] = fb[0][j];
     }
 
@@ -851,7 +912,7 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
       bf16_t* st = lds + (it % C::NS) * C::STAGE;
       const bf16_t* sn = lds + ((it + 1) % C::NS) * C::STAGE;
       const bool more = it + C::NS < nk;
-      const int64_t goff = (int64_t)(kbeg + it + C::NS) * DBK64;
+      const int64_t gslice = kbeg + it + C::NS;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         const int cur = kk & 1;
@@ -872,14 +933,14 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
             acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
           if (Epi::kMode != 2 && m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
             const int f = m / C::FSTEP;
-            if (f == 0) fa[cur ^ 1][0] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk]);
-            else if (f <= TN) fb[cur ^ 1][f - 1] = *reinterpret_cast<const bf16x8*>(src + b_off[nkk] + (f - 1) * 16 * DBK64);
-            else fa[cur ^ 1][f - TN] = *reinterpret_cast<const bf16x8*>(src + a_off[nkk] + (f - TN) * 16 * DBK64);
+            if (f == 0) fa[cur ^ 1][0] = FAAR_FRAG_A(src, nkk, 0);
+            else if (f <= TN) fb[cur ^ 1][f - 1] = FAAR_FRAG_B(src, nkk, f - 1);
+            else fa[cur ^ 1][f - TN] = FAAR_FRAG_A(src, nkk, f - TN);
           }
           if (Epi::kMode != 1 && kk == KK - 1 && m % C::DSTEP == 0 && m / C::DSTEP < P) {
             // slice it+NS into the stage just released; past the end every lane re-reads one valid address
             const int q = m / C::DSTEP;
-            const bf16_t* g = more ? gsrc[q] + goff : A;
+            const bf16_t* g = more ? gsrc[q] + gslice * gstep[q] : A;
             dma16(g, __builtin_amdgcn_readfirstlane(lds_addr_of(st + (wave * P + q) * C::RPI * DBK64)));
           }
           if (Epi::kMode != 1 && kk == KK - 1 && m == (P - 1) * C::DSTEP + 1) {   // right after the slice's last copy
@@ -891,6 +952,8 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     }
     FAAR_WAIT_VMCNT(0);  // no copy may still be in flight into this workgroup's LDS when it retires
 #undef FAAR_SIDE_READ
+#undef FAAR_FRAG_A
+#undef FAAR_FRAG_B
   }
 
   // accumulator layout of the 16x16 tile: lane -> column lane % 16, rows 4 * (lane / 16) + 0..3
@@ -978,6 +1041,7 @@ typedef DmaCfg<256, 128, 4, 2> CfgM;  // one tile per compute unit at ~256 tiles
 typedef DmaCfg<128, 128, 2, 2> CfgS;  // small outputs, two workgroups per compute unit
 typedef Dma64Cfg<256, 256, 2, 4, 2> CfgL64;  // 2 x 64 KB
 typedef Dma64Cfg<256, 128, 4, 2, 3> CfgM64;  // 3 x 48 KB: copies stay in flight for two slices
+typedef Dma64Cfg<256, 256, 2, 4, 2, true> CfgT64;  // CfgL64 on token-major operands
 
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
@@ -1130,6 +1194,23 @@ hipError_t launch_gemm_gram(const bf16_t* delta, const bf16_t* gram, int64_t O, 
   *n_partials = p.items();
   EpiGram e{delta, diag_lo, x_scale, 1.0f, guard, two_alpha, out, partials, 0.0f};
   return run(delta, gram, d, p, e, st);
+}
+
+bool gemm_tn_usable(int64_t M, int64_t N, int64_t T) {
+  if (T <= 0 || T % DBK64 != 0 || M % 8 != 0 || N % 8 != 0) return false;
+  return plan_gemm(GemmDims{M, N, T, T, T}, true, kEpiF32).kind == KIND_L64;
+}
+
+hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, hipStream_t st) {
+  if (!gemm_tn_usable(d.M, d.N, d.Kd) || d.lda % 8 != 0 || d.ldb % 8 != 0) return hipErrorInvalidValue;
+  const Plan p = plan_gemm(GemmDims{d.M, d.N, d.Kd, d.Kd, d.Kd}, true, kEpiF32);
+  if (p.n_split != n_split) return hipErrorInvalidValue;
+  const int ksteps = static_cast<int>(d.Kd / DBK64);
+  const int per_split = (ksteps + p.n_split - 1) / p.n_split;
+  const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
+  hipLaunchKernelGGL((k_gemm_dma64<CfgT64, EpiF32>), grid, dim3(CfgT64::THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, p.n_split,
+                     per_split, EpiF32{out});
+  return hipGetLastError();
 }
 
 hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,

@@ -189,6 +189,11 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 hipError_t launch_gemm_f32(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split,
                            hipStream_t st);
 int choose_split(int64_t M, int64_t N, int64_t Kd);
+// The same product from token-major operands: out[s][m][n] = sum_t A[t][m] * B[t][n], A [T, lda], B [T, ldb] (the contraction
+// index is the row index; d.Kd = T).  Only where gemm_tn_usable says so (T a multiple of 64, M and N multiples of 8, a shape
+// the planner gives 256 x 256 tiles); n_split = choose_split(M, N, T) as for launch_gemm_f32.
+bool gemm_tn_usable(int64_t M, int64_t N, int64_t T);
+hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, hipStream_t st);
 // The kernel variant, tile shape and contraction split the launchers above pick for an M x N x Kd product
 // (kind: 0 generic, 1 / 2 / 3 the BK = 32 kernels with 256x256 / 256x128 / 128x128 tiles, 4 / 5 the BK = 64
 // kernels with 256x256 / 256x128 tiles).  Pure host function.
