@@ -173,7 +173,8 @@ int64_t faar_padded_tokens(int64_t T);
 /* 1 when a step of an O x K layer over T tokens that is given an upstream gradient (dY_ext) runs its dW GEMM on the token-major
  * operands as they are -- dY_ext [T, O] and Xq [T, K], no transposed copies -- else 0 (T not a multiple of 64, O or K not a
  * multiple of 8, or a shape that takes other tiles than 256 x 256).  Such a step neither reads nor, with FAAR_STEP_JOINT, writes
- * Xt.  Pure host function. */
+ * Xt.  The same holds for a step that derives its own gradient with the constant carried as H (faar_layer_prepare_h) and no dX
+ * requested: its residual GEMM then leaves dY token-major and Xt is not read either.  Pure host function. */
 int faar_dw_token_major(int64_t O, int64_t K, int64_t T);
 
 /*

@@ -241,7 +241,7 @@ int faar_dw_token_major(int64_t O, int64_t K, int64_t T) {
 int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
                     unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream) {
   if (!A || !B || !clocks || !sink || !info) return FAAR_E_NULL;
-  if (mode < 0 || mode > 2) return FAAR_E_ARG;
+  if (mode < 0 || mode > 6 || (mode & 3) == 3) return FAAR_E_ARG;
   if (M <= 0 || N <= 0 || Kd <= 0 || Kd % 64 != 0 || M > kMaxElems / Kd || N > kMaxElems / Kd) return FAAR_E_SHAPE;
   if (!aligned16(A) || !aligned16(B) || (reinterpret_cast<uintptr_t>(clocks) & 7u)) return FAAR_E_ARG;
   int kind = 0;
@@ -565,6 +565,9 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   // An upstream gradient arrives token-major, as the activations are: where the token-major form of the dW GEMM applies, it
   // takes both as they are -- no dY^T, and X_q^T is neither read nor (in a joint step) written
   const bool token_major = dY_ext && gemm_tn_usable(O, K, T);
+  // ... and so does the step's own gradient when the constant is carried separately (nothing but the GEMM's product goes
+  // into dY then) and no dX has to be derived from it
+  const bool rows_form = !joint && Hs && !dY_ext && !dX && gemm_tn_usable(O, K, T);
   if (joint) {
     if (flags & FAAR_WS_FORWARD_READY) {   // nobody else consumes the tag: check it in a kernel of its own
       if (int e = hip_status(launch_check_forward_tag(guard, st))) return e;
@@ -578,11 +581,17 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
     // V, m, u: the residual GEMM reads it on the side (when it is at most half that cache, and the dW GEMM will use it)
     const int64_t xt_bytes = (int64_t)K * L.Tp * 2;
     const bool warm_xt = xt_bytes <= ((int64_t)128 << 20);
-    // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
-    if (int e = hip_status(launch_gemm_residual(xq, delta, d1, Hs ? nullptr : C, x_scale, 2.0f * mse_scale,
-                                                (Hs && dY_ext) ? nullptr : dYt, L.Tp, need_local_dY ? dY : nullptr, mse_p,
-                                                &n_mse, guard, warm_xt ? Xt : nullptr, xt_bytes, st)))
+    if (rows_form) {
+      // with H and the token-major dW GEMM: dY stays token-major ([T, O], in the place of dY^T), no transposed staging,
+      // and the dW GEMM re-reads the X_q this GEMM has just read: nothing to fetch on the side
+      if (int e = hip_status(launch_gemm_residual_rows(xq, delta, d1, x_scale, 2.0f * mse_scale, dYt, mse_p, &n_mse, guard, st)))
+        return e;
+    } else if (int e = hip_status(launch_gemm_residual(xq, delta, d1, Hs ? nullptr : C, x_scale, 2.0f * mse_scale,
+                                                       (Hs && dY_ext) ? nullptr : dYt, L.Tp, need_local_dY ? dY : nullptr, mse_p,
+                                                       &n_mse, guard, warm_xt ? Xt : nullptr, xt_bytes, st))) {
+      // with H: no constant in the epilogue, and no dY^T at all when the gradient comes from upstream
       return e;
+    }
   }
   // otherwise the upstream gradient is transposed over dY^T
   const bf16_t* dY_used = dY;
@@ -594,8 +603,8 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   // s3: G = dY^T X_q, contraction over tokens, split for occupancy
   {
     Bracket b(FAAR_K_GEMM_DW, st);
-    if (token_major) {
-      if (int e = hip_status(launch_gemm_f32_tn(dY_used, xq, GemmDims{O, K, T, O, K}, G, L.n_split, st))) return e;
+    if (token_major || rows_form) {
+      if (int e = hip_status(launch_gemm_f32_tn(rows_form ? dYt : dY_used, xq, GemmDims{O, K, T, O, K}, G, L.n_split, st))) return e;
     } else {
       const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
       if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;

@@ -246,6 +246,54 @@ struct EpiResidualT {
 typedef EpiResidualT<true> EpiResidual;
 typedef EpiResidualT<false> EpiPerturbation;
 
+// The V-dependent part of the residual with dY stored TOKEN-major, for the token-major dW GEMM that follows:
+// A = x_scale * acc;  sum A^2 per work item;  dY[m][n] = bf16(two_alpha * A)  ([M, N] row-major, N a multiple of 8).
+struct EpiPerturbationRows {
+  static constexpr bool kTransposedOut = false;
+  static constexpr bool kRowStaged = true;
+  static constexpr bool kWarm = false;
+  static constexpr int kMode = 0;
+  const float* x_scale;
+  float xs;
+  ForwardGuard guard;
+  float two_alpha;
+  bf16_t* dY;
+  double* partials;
+  float sum;
+  __device__ __forceinline__ void once() {
+    if (guard.slot && blockIdx.x == 0 && threadIdx.x == 0) {
+      bool ok = true;
+      for (int i = 0; i < kTagWords; ++i) ok = ok && guard.slot[i] == guard.expect.w[i];
+      for (int i = 0; i < kTagWords; ++i) guard.slot[i] = 0u;
+      guard.slot[kTagWords] = ok ? 1u : 0u;
+    }
+  }
+  __device__ __forceinline__ void begin() { xs = x_scale ? *x_scale : 1.0f; }
+  __device__ __forceinline__ void rows4(const float (&acc)[4], int64_t m, int64_t n, int, const GemmDims& d) {
+    if (n >= d.N) return;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (m + q < d.M) {
+        const float r = xs * acc[q];
+        sum += r * r;
+        dY[(m + q) * d.N + n] = static_cast<bf16_t>(f32_to_bf16(two_alpha * r));
+      }
+  }
+  __device__ __forceinline__ void run8(const float (&acc)[8], int64_t m, int64_t n, int, const GemmDims& d) {
+    if (m >= d.M || n >= d.N) return;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float r0 = xs * acc[2 * j], r1 = xs * acc[2 * j + 1];
+      sum += r0 * r0;
+      sum += r1 * r1;
+      w[j] = f32_to_bf16(two_alpha * r0) | (f32_to_bf16(two_alpha * r1) << 16);
+    }
+    *reinterpret_cast<uint4*>(dY + m * d.N + n) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  __device__ __forceinline__ void finish(int item) { finish_sum(sum, partials, item); }
+};
+
 // sum of (x_scale * acc)^2 per work item and nothing else: the loss of a step whose dY comes from upstream
 struct EpiSumSq {
   static constexpr bool kRowStaged = false;
@@ -1135,6 +1183,16 @@ int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd) {  // the most 
                   std::max(plan_gemm(d, false, kEpiBf16).items(), plan_gemm(d, false, kEpiNone).items()));
 }
 
+hipError_t launch_gemm_residual_rows(const bf16_t* A, const bf16_t* B, GemmDims d, const float* x_scale, float two_alpha,
+                                     bf16_t* dY, double* mse_partials, int64_t* n_partials, const ForwardGuard& guard,
+                                     hipStream_t st) {
+  if (d.N % 8 != 0) return hipErrorInvalidValue;
+  EpiPerturbationRows e{x_scale, 1.0f, guard, two_alpha, dY, mse_partials, 0.0f};
+  const Plan p = plan_gemm(d, false, kEpiBf16);
+  *n_partials = p.items();
+  return run(A, B, d, p, e, st);
+}
+
 hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, const float* C, const float* x_scale,
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, const void* warm,
@@ -1220,6 +1278,20 @@ hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDim
   *items = p.items();
   if (p.kind != KIND_L64 && p.kind != KIND_M64) return hipErrorNotSupported;   // only the BK = 64 loop has the variants
   if (p.items() > capacity) return hipErrorInvalidValue;
+  if (mode & 4) {   // the same loops on token-major operands: the buffers are read as A [Kd, M], B [Kd, N]
+    if (!gemm_tn_usable(d.M, d.N, d.Kd)) return hipErrorNotSupported;
+    const GemmDims t{d.M, d.N, d.Kd, d.M, d.N};
+    const int ksteps = static_cast<int>(d.Kd / DBK64);
+    const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
+#define FAAR_PROBE_TN(MODE) \
+  hipLaunchKernelGGL((k_gemm_dma64<CfgT64, EpiProbe<MODE>>), grid, dim3(CfgT64::THREADS), 0, st, A, B, t, p.tiles_m, p.tiles_n, 1, \
+                     ksteps, EpiProbe<MODE>{clocks, sink, 0, 0, 0.0f})
+    if ((mode & 3) == 0) FAAR_PROBE_TN(0);
+    else if ((mode & 3) == 1) FAAR_PROBE_TN(1);
+    else FAAR_PROBE_TN(2);
+#undef FAAR_PROBE_TN
+    return hipGetLastError();
+  }
   if (mode == 0) return run(A, B, d, p, EpiProbe<0>{clocks, sink, 0, 0, 0.0f}, st);
   if (mode == 1) return run(A, B, d, p, EpiProbe<1>{clocks, sink, 0, 0, 0.0f}, st);
   return run(A, B, d, p, EpiProbe<2>{clocks, sink, 0, 0, 0.0f}, st);

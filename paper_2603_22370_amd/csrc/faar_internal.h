@@ -183,6 +183,11 @@ hipError_t launch_gemm_residual(const bf16_t* A, const bf16_t* B, GemmDims d, co
                                 float two_alpha, bf16_t* dYt, int64_t ldt, bf16_t* dY,
                                 double* mse_partials, int64_t* n_partials, const ForwardGuard& guard, const void* warm,
                                 int64_t warm_bytes, hipStream_t st);
+// The C == nullptr form with dY stored token-major instead of transposed: dY[m][n] = bf16(two_alpha * x_scale * acc), [M, N]
+// row-major, N a multiple of 8 (for the token-major dW GEMM); the same per-item sums and the same tile plan
+hipError_t launch_gemm_residual_rows(const bf16_t* A, const bf16_t* B, GemmDims d, const float* x_scale, float two_alpha,
+                                     bf16_t* dY, double* mse_partials, int64_t* n_partials, const ForwardGuard& guard,
+                                     hipStream_t st);
 // number of per-work-item loss partials the residual GEMM writes for these sizes
 int64_t gemm_residual_partials(int64_t M, int64_t N, int64_t Kd);
 // Plain float32 output with the contraction split n_split ways: out[s][m][n] (split stride M*N).

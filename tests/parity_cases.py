@@ -42,6 +42,8 @@ STEP_CASES = [
     StepCase("dw_one_slice", 288, 12288, 33, 31),                # dW GEMM: 256x128 tiles, a single 64-token slice
     # dW GEMM on token-major operands (upstream gradient given): last tiles 8 rows / 16 columns wide, 32 slices split 11 + 11 + 10
     StepCase("dw_token_major_ragged", 3592, 1040, 2048, 32, chained=True),
+    # token-major dY out of the residual GEMM (with H) on 256x256 tiles with 32-wide slices: K a multiple of 32 only
+    StepCase("rows_k160", 12288, 160, 4096, 33),
     # the shapes the benchmark times, at full size
     StepCase("llama_q_proj", 2048, 2048, 4096, 0, full_size=True),
     StepCase("llama_gate_proj", 8192, 2048, 4096, 1, chained=True, full_size=True),

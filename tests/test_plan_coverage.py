@@ -93,3 +93,25 @@ def test_gram_form_product_runs_kernels_that_its_parity_cases_cover():
     full = {combo(c.O, c.K) for c in STEP_CASES if c.full_size}
     for O, K in [(2048, 2048), (512, 2048), (8192, 2048), (2048, 8192), (1024, 2048), (6144, 2048), (2048, 6144)]:
         assert combo(O, K) in full, (O, K, combo(O, K))
+
+
+def test_token_major_residual_gemm_runs_kernels_that_parity_cases_cover():
+    """Where faar_dw_token_major holds, a step that carries the constant as H leaves dY token-major: its residual GEMM is the
+    T x O x K product planned like the forward GEMM, with an epilogue of its own.  Every variant that product can take on such
+    a shape is taken by a parity case (each runs once with H, no upstream gradient and no dX), and the benchmark's by
+    full-size ones."""
+    def combo(O, K, T):
+        kind, bm, bn, _ = fb.faar_gemm_plan(fb.K_GEMM_FWD, O, K, T)
+        return (kind, (bm, bn))
+
+    reachable = {}
+    for O, K, T in itertools.product(DIMS, DIMS, TOKENS):
+        if O * K * T <= 2 ** 40 and fb.faar_dw_token_major(O, K, T):
+            reachable.setdefault(combo(O, K, T), (O, K, T))
+    covered = {combo(c.O, c.K, c.T) for c in STEP_CASES if fb.faar_dw_token_major(c.O, c.K, c.T)}
+    missing = {k: v for k, v in reachable.items() if k not in covered}
+    assert not missing, f"token-major residual variants no parity case reaches (with an example shape): {missing}"
+    full = {combo(c.O, c.K, c.T) for c in STEP_CASES if c.full_size and fb.faar_dw_token_major(c.O, c.K, c.T)}
+    for O, K in [(2048, 2048), (1024, 2048), (6144, 2048), (2048, 6144)]:
+        assert not fb.faar_dw_token_major(O, K, 8192) or combo(O, K, 8192) in full, (O, K)
+    assert fb.faar_dw_token_major(6144, 2048, 8192) and fb.faar_dw_token_major(2048, 6144, 8192)
