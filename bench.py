@@ -208,6 +208,7 @@ class LinearJob:
         self.alpha = 1.0 / (T * O)
         self.losses = torch.zeros(3, dtype=torch.float32, device="cuda")
         self.form = form               # "token": faar_layer_step; "gram": faar_layer_step_gram
+        self.whole_device = False      # set when nothing runs beside this job's steps (one stream): tiles that fill every unit
         self.ws = faar.layer_step_workspace(O, K, T) if form == "token" else fb.layer_step_gram_workspace(O, K)
         self.ws_g = (torch.empty(faar.faar_workspace_bytes(fb.OP_GRAM_PREPARE, K, K, T), dtype=torch.uint8, device="cuda")
                      if form == "gram" else None)
@@ -259,7 +260,7 @@ class LinearJob:
             return
         faar.faar_layer_step(self.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], self.Xq, s["Xt"], s["C"], s["ic"], beta,
                              LAM, self.alpha, LR, 0.9, 0.999, 1e-8, t, self.losses, self.ws, beta_next=beta_next,
-                             forward_ready=ready, x_scale=self.x_scale, **s["hk"])
+                             forward_ready=ready, x_scale=self.x_scale, whole_device=self.whole_device, **s["hk"])
 
     def finish(self):
         import paper_2603_22370_amd as faar
@@ -365,6 +366,8 @@ def run_layer(args) -> dict:
     T = 8192
     gram = args.workload == "qwen_layer_gram"
     jobs = make_block_jobs(T, args.quantised_acts, "gram" if gram else "token")
+    for j in jobs:
+        j.whole_device = args.streams == 1
     torch.cuda.synchronize()
     # Stage 1 optimises every linear against frozen inputs: the seven jobs are independent, so they are issued on
     # several HIP streams (default priority).  While one job's workgroups sit in a GEMM epilogue or in the
@@ -478,6 +481,7 @@ def run_linear(args) -> dict:
     W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
     Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
     j = LinearJob(args.workload, O, K, T, W, Xq, args.quantised_acts, args.form)
+    j.whole_device = True
     gram = args.form == "gram"
     torch.cuda.synchronize()
 
@@ -593,7 +597,7 @@ def run_block_chained(args) -> dict:
         L["t"] += 1
         faar.faar_layer_step(j.W, s["sg"], s["scales"], s["V"], s["m"], s["u"], j.Xq, s["Xt"], s["C"], s["ic"], beta,
                              LAM, j.alpha, LR, 0.9, 0.999, 1e-8, L["t"], j.losses, L["ws"], dY_ext=L["dY"],
-                             dX=L["dX"], beta_next=beta, forward_ready=L["ready"], **s["hk"])
+                             dX=L["dX"], beta_next=beta, forward_ready=L["ready"], whole_device=True, **s["hk"])
         L["ready"] = True
 
     for _ in range(warmup):

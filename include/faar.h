@@ -64,6 +64,12 @@ enum {
   FAAR_STEP_JOINT = 1u << 6,    /* faar_layer_step: the layer is one link of a jointly optimised chain (see there) */
   FAAR_STEP_XT_READY = 1u << 7, /* faar_layer_step with FAAR_STEP_JOINT: Xt already holds the transpose of Xq (written by the
                                    joint step of another linear that reads the same activations): do not transpose again */
+  FAAR_STEP_WHOLE_DEVICE = 1u << 8, /* faar_layer_step: nothing else runs on the device beside this step.  The token-major
+                                   dW GEMM then takes the tile that fills every compute unit (192 x 256 or 256 x 192 where
+                                   256 x 256 tiles would leave units idle: 6144 x 2048 is 192 of those, but 256 of 192 x
+                                   256).  Without the flag it stays on 256 x 256 tiles, which do more work per byte moved:
+                                   what counts when kernels of other streams take up the idle units anyway.  Same sums in
+                                   the same order either way: results are identical bit for bit. */
   FAAR_WS_GRADIENT_CONSTANT = 1u << 5, /* faar_workspace_bytes(FAAR_OP_LAYER_PREPARE): size the workspace for a call that
                                    also produces H and c_norm2 */
   FAAR_DQ_IN_UNITS = 1u << 4    /* faar_quant_rtn: W_dq receives sign * node * E4M3 scale, i.e. the dequantised
@@ -170,12 +176,14 @@ int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, c
  * faar_layer_prepare and read by faar_layer_step: T rounded up to a multiple of 64. */
 int64_t faar_padded_tokens(int64_t T);
 
-/* 1 when a step of an O x K layer over T tokens that is given an upstream gradient (dY_ext) runs its dW GEMM on the token-major
- * operands as they are -- dY_ext [T, O] and Xq [T, K], no transposed copies -- else 0 (T not a multiple of 64, O or K not a
- * multiple of 8, or a shape that takes other tiles than 256 x 256).  Such a step neither reads nor, with FAAR_STEP_JOINT, writes
- * Xt.  The same holds for a step that derives its own gradient with the constant carried as H (faar_layer_prepare_h) and no dX
- * requested: its residual GEMM then leaves dY token-major and Xt is not read either.  Pure host function. */
-int faar_dw_token_major(int64_t O, int64_t K, int64_t T);
+/* Non-zero when a step of an O x K layer over T tokens that is given an upstream gradient (dY_ext) runs its dW GEMM on the
+ * token-major operands as they are -- dY_ext [T, O] and Xq [T, K], no transposed copies -- else 0 (T not a multiple of 64, O or
+ * K not a multiple of 8, or a shape too small for 256-wide tiles).  The value names the tile of that GEMM for a step with these
+ * `flags` (only FAAR_STEP_WHOLE_DEVICE matters): 1 256 x 256, 2 192 x 256, 3 256 x 192.  Such a step neither reads nor, with
+ * FAAR_STEP_JOINT, writes Xt.  The same holds for a step that derives its own gradient with the constant carried as H
+ * (faar_layer_prepare_h) and no dX requested: its residual GEMM then leaves dY token-major and Xt is not read either.  Pure
+ * host function. */
+int faar_dw_token_major(int64_t O, int64_t K, int64_t T, uint32_t flags);
 
 /*
  * Round-to-nearest NVFP4 quantisation of a tensor -- the baseline rounding of Sec. 3.1/3.2 and

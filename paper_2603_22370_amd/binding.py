@@ -16,6 +16,7 @@ FAAR_F32, FAAR_BF16 = 0, 1
 FAAR_SGLOBAL_GIVEN, FAAR_EMIT_DELTA, FAAR_WS_CHAINED, FAAR_WS_FORWARD_READY, FAAR_DQ_IN_UNITS = 1, 2, 4, 8, 16
 FAAR_WS_GRADIENT_CONSTANT = 32
 FAAR_STEP_JOINT = 64
+FAAR_STEP_WHOLE_DEVICE = 256
 OP_QUANT_RTN, OP_INIT_V, OP_SOFTQUANT, OP_LAYER_PREPARE, OP_LAYER_STEP, OP_HARDEN_PACK, OP_STAGE2_LOSSES, OP_QUANT_RTN_BATCH, OP_LINEAR_FORWARD, OP_BLOCK_OUTPUT_LOSS, OP_ATTENTION_FWD, OP_ATTENTION_BWD, OP_GRAM_PREPARE, OP_LAYER_STEP_GRAM = range(14)
 ERRORS = {-1: "FAAR_E_NULL", -2: "FAAR_E_SHAPE", -3: "FAAR_E_DTYPE", -4: "FAAR_E_WORKSPACE",
           -5: "FAAR_E_HIP", -6: "FAAR_E_ARG", -7: "FAAR_E_UNSUPPORTED"}
@@ -81,7 +82,7 @@ def lib() -> ctypes.CDLL:
         L.faar_gemm_probe.argtypes = [c_int, c_int64, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
                                       ctypes.POINTER(c_int32), c_void_p]
         L.faar_dw_token_major.restype = c_int
-        L.faar_dw_token_major.argtypes = [c_int64, c_int64, c_int64]
+        L.faar_dw_token_major.argtypes = [c_int64, c_int64, c_int64, c_uint32]
         L.faar_padded_tokens.restype = c_int64
         L.faar_padded_tokens.argtypes = [c_int64]
         L.faar_quant_rtn.restype = c_int
@@ -251,8 +252,10 @@ def faar_gemm_probe(mode: int, A, B):
     return clocks[:info[0]], GEMM_KINDS[info[1]]
 
 
-def faar_dw_token_major(O: int, K: int, T: int) -> bool:
-    return bool(lib().faar_dw_token_major(O, K, T))
+def faar_dw_token_major(O: int, K: int, T: int, whole_device: bool = False) -> int:
+    """0: the dW GEMM of such a step needs transposed operands; else the tile shape of its token-major form
+    (1: 256 x 256; with whole_device also 2: 192 x 256, 3: 256 x 192)."""
+    return int(lib().faar_dw_token_major(O, K, T, FAAR_STEP_WHOLE_DEVICE if whole_device else 0))
 
 
 def faar_padded_tokens(T: int) -> int:
@@ -380,11 +383,12 @@ def faar_layer_prepare(W, s_global, scales, Xq, Y_fp, ws=None, x_scale=None, gra
 
 def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, beta, lambda_round, mse_scale,
                     lr, beta1, beta2, eps, t, losses, ws, dY_ext=None, dX=None, beta_next=0.0, forward_ready=False,
-                    x_scale=None, H=None, c_norm2=None, joint=False):
+                    x_scale=None, H=None, c_norm2=None, joint=False, whole_device=False):
     """One step in place on (V, adam_m, adam_v); losses f32[3] receives (L_mse, L_round, L).
     beta_next > 0 leaves the next step's forward outputs in ws; forward_ready=True consumes them.
     H, c_norm2: the gradient constant of faar_layer_prepare(gradient_constant=True), or None.
-    joint: a Stage-2-style step (dY_ext required; no local loss; Xt is rewritten from Xq; C may be None)."""
+    joint: a Stage-2-style step (dY_ext required; no local loss; Xt is rewritten from Xq; C may be None).
+    whole_device: nothing else runs on the device beside the step (tiles that fill every compute unit)."""
     _dev(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, losses, ws, dY_ext, dX, x_scale, H, c_norm2)
     O, K = W.shape
     T = Xq.shape[0]
@@ -394,7 +398,8 @@ def faar_layer_step(W, s_global, scales, V, adam_m, adam_v, Xq, Xt, C, icodes, b
                                  _ptr(c_norm2), T, _ptr(dY_ext), _ptr(dX),
                                  float(beta), float(beta_next), float(lambda_round), float(mse_scale),
                                  ctypes.byref(opt), _ptr(losses),
-                                 (FAAR_WS_FORWARD_READY if forward_ready else 0) | (FAAR_STEP_JOINT if joint else 0),
+                                 (FAAR_WS_FORWARD_READY if forward_ready else 0) | (FAAR_STEP_JOINT if joint else 0)
+                                 | (FAAR_STEP_WHOLE_DEVICE if whole_device else 0),
                                  _ptr(ws), ws.numel(), _stream()), "faar_layer_step")
 
 

@@ -233,15 +233,15 @@ int faar_dw_split(int64_t O, int64_t K, int64_t T) {
 
 int64_t faar_padded_tokens(int64_t T) { return T > 0 ? padded_tokens(T) : 0; }
 
-int faar_dw_token_major(int64_t O, int64_t K, int64_t T) {
+int faar_dw_token_major(int64_t O, int64_t K, int64_t T, uint32_t flags) {
   if (check_shape(O, K) != FAAR_OK || T <= 0) return 0;
-  return gemm_tn_usable(O, K, T) ? 1 : 0;
+  return gemm_tn_tiles(O, K, T, (flags & FAAR_STEP_WHOLE_DEVICE) != 0);
 }
 
 int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
                     unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream) {
   if (!A || !B || !clocks || !sink || !info) return FAAR_E_NULL;
-  if (mode < 0 || mode > 6 || (mode & 3) == 3) return FAAR_E_ARG;
+  if (mode < 0 || mode > 12 || (mode & 3) == 3) return FAAR_E_ARG;
   if (M <= 0 || N <= 0 || Kd <= 0 || Kd % 64 != 0 || M > kMaxElems / Kd || N > kMaxElems / Kd) return FAAR_E_SHAPE;
   if (!aligned16(A) || !aligned16(B) || (reinterpret_cast<uintptr_t>(clocks) & 7u)) return FAAR_E_ARG;
   int kind = 0;
@@ -508,7 +508,8 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   if (T <= 0 || T > kMaxElems / (O > K ? O : K)) return FAAR_E_SHAPE;
   const bool chained = dY_ext || dX;
   if (chained && O % 8 != 0) return FAAR_E_SHAPE;
-  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY | FAAR_STEP_JOINT | FAAR_STEP_XT_READY)) return FAAR_E_ARG;
+  if (flags & ~(uint32_t)(FAAR_WS_CHAINED | FAAR_WS_FORWARD_READY | FAAR_STEP_JOINT | FAAR_STEP_XT_READY | FAAR_STEP_WHOLE_DEVICE))
+    return FAAR_E_ARG;
   if ((flags & FAAR_STEP_XT_READY) && !joint) return FAAR_E_ARG;
   if (!(beta > 0.0f) || !std::isfinite(beta) || !std::isfinite(lambda_round) || !std::isfinite(mse_scale))
     return FAAR_E_ARG;
@@ -604,7 +605,9 @@ int faar_layer_step(const void* W, faar_dtype wdt, int64_t O, int64_t K, const f
   {
     Bracket b(FAAR_K_GEMM_DW, st);
     if (token_major || rows_form) {
-      if (int e = hip_status(launch_gemm_f32_tn(rows_form ? dYt : dY_used, xq, GemmDims{O, K, T, O, K}, G, L.n_split, st))) return e;
+      if (int e = hip_status(launch_gemm_f32_tn(rows_form ? dYt : dY_used, xq, GemmDims{O, K, T, O, K}, G, L.n_split,
+                                                (flags & FAAR_STEP_WHOLE_DEVICE) != 0, st)))
+        return e;
     } else {
       const GemmDims d2{O, K, L.Tp, L.Tp, L.Tp};
       if (int e = hip_status(launch_gemm_f32(dYt, static_cast<const bf16_t*>(Xt), d2, G, L.n_split, st))) return e;

@@ -787,7 +787,8 @@ template <int BM_, int BN_, int WGM_, int WGN_, int NS_, bool kTokenMajor_ = fal
 struct Dma64Cfg {
   static constexpr int BM = BM_, BN = BN_, WGM = WGM_, WGN = WGN_, NS = NS_;  // NS ring stages (2 or 3)
   static constexpr bool kTokenMajor = kTokenMajor_;
-  static_assert(!kTokenMajor_ || (BM_ == 256 && BN_ == 256), "the token-major stage layout is written for 256 x 256 tiles");
+  static_assert(!kTokenMajor_ || ((BM_ == 256 || BM_ == 192) && (BN_ == 256 || BN_ == 192)),
+                "the token-major stage layout is written for 256 and 192 columns per operand");
   static constexpr int NW = WGM * WGN, THREADS = 64 * NW;
   static constexpr int WM = BM / WGM, WN = BN / WGN;
   static constexpr int TM = WM / 16, TN = WN / 16;
@@ -819,10 +820,17 @@ __device__ __forceinline__ bf16x8 read_tokens8(const bf16_t* p) {
   const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
 }
-// XOR key of a token row's 16-byte chunk positions in a token-major stage (applied to bits 1..3 of the chunk index): the 16
-// token rows one transposing read touches (4 consecutive tokens in each of 4 groups 8 apart) fall into 8 different
-// 32-byte bank groups, two rows each -- the two cycles 512 bytes take anyway
-__device__ __forceinline__ int token_key(int t) { return (t & 3) | (((t >> 3) & 1) << 2); }
+// XOR key of a token row's pairs of 16-byte chunks (32 bytes = the 16 columns one transposing read takes from a token) in a
+// token-major stage of COLS columns per token.  One read touches 16 token rows -- 4 consecutive tokens in each of 4 groups 8
+// apart -- and they must fall into the 8 different 32-byte bank groups, two rows each (the two cycles 512 bytes take anyway).
+// 256 columns: a row is 512 bytes, every row starts at bank 0, so the key has 3 bits (token bits 0, 1, 3) and permutes a row's
+// pairs within aligned groups of 8.  192 columns: a row is 384 bytes, odd rows start half-way round the banks, so token bit 0 is
+// taken care of and the key has 2 bits (token bits 1, 3), permuting pairs within aligned groups of 4 -- which 12 pairs divide into.
+template <int COLS>
+__device__ __forceinline__ int token_key(int t) {
+  static_assert(COLS == 256 || COLS == 192, "token-major operand width");
+  return COLS == 256 ? (t & 3) | (((t >> 3) & 1) << 2) : ((t >> 1) & 1) | (((t >> 3) & 1) << 1);
+}
 
 template <class C, class Epi>
 __global__ void __launch_bounds__(C::THREADS)
@@ -864,13 +872,21 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
 #pragma unroll
     for (int q = 0; q < P; ++q) {
       if constexpr (C::kTokenMajor) {
-        // instruction u = wave * P + q fills 1 KB of the stage = two token rows of one operand's 256 columns: lane -> token
-        // 2 u' + lane / 32, LDS chunk lane % 32, global chunk = that ^ 2 key(token).  Columns beyond M (or N) are clamped to
-        // the last whole chunk: their products are never stored.
+        // instruction u = wave * P + q fills 64 consecutive 16-byte slots of the stage; an operand of COLS columns owns
+        // 64 tokens x COLS / 8 slots (a whole number of instructions), slot -> token = slot / (COLS / 8), LDS chunk =
+        // slot % (COLS / 8), global chunk = that ^ 2 key(token).  Columns beyond M (or N) are clamped to the last whole chunk:
+        // their products are never stored.
         const int u = wave * P + q;
         const bool is_a = u < C::BM / 8;
-        const int t = 2 * (is_a ? u : u - C::BM / 8) + lane / 32;
-        const int chunk = (lane % 32) ^ (2 * token_key(t));
+        int t, chunk;
+        if constexpr (C::BM == 256 && C::BN == 256) {   // two whole token rows per instruction
+          t = 2 * (is_a ? u : u - C::BM / 8) + lane / 32;
+          chunk = (lane % 32) ^ (2 * token_key<256>(t));
+        } else {
+          const int slot = (is_a ? u : u - C::BM / 8) * 64 + lane;
+          t = is_a ? slot / (C::BM / 8) : slot / (C::BN / 8);
+          chunk = is_a ? (slot % (C::BM / 8)) ^ (2 * token_key<C::BM>(t)) : (slot % (C::BN / 8)) ^ (2 * token_key<C::BN>(t));
+        }
         const int64_t first = is_a ? m0 : n0, width = is_a ? d.M : d.N, ld = is_a ? d.lda : d.ldb;
         const int64_t col = first + chunk * 8 <= width - 8 ? first + chunk * 8 : width - 8;
         gsrc[q] = (is_a ? A : B) + t * ld + col;
@@ -924,15 +940,15 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
     }
     // token-major stage: element offset of this lane's first transposing read for fragment i (A) / j (B) of phase 0.  The
     // lane points at token 8 (lane / 16) + (lane % 16) / 4 of the phase's 32 and at columns w? + 16 i + 4 (lane % 4); that
-    // token's XOR key is the same in every phase and for both reads of a fragment
+    // token's XOR key is the same in every phase and for both reads of a fragment (no key uses token bits 2, 4 or 5)
     int a_tr[TM] = {}, b_tr[TN] = {};
     if constexpr (C::kTokenMajor) {
-      const int tok = 8 * kc + (fr >> 2), key = (fr >> 2) | ((kc & 1) << 2);
+      const int tok = 8 * kc + (fr >> 2);
+      const int key_a = token_key<C::BM>(tok), key_b = token_key<C::BN>(tok);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a_tr[i] = tok * C::BM + wm + ((i ^ key) * 16) + (fr & 3) * 4;
+      for (int i = 0; i < TM; ++i) a_tr[i] = tok * C::BM + (((wm / 16 + i) ^ key_a) * 16) + (fr & 3) * 4;
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        b_tr[j] = C::BM * DBK64 + tok * C::BN + (((wn / 8 + 2 * j) ^ (2 * key)) * 8) + (fr & 3) * 4;
+      for (int j = 0; j < TN; ++j) b_tr[j] = C::BM * DBK64 + tok * C::BN + (((wn / 16 + j) ^ key_b) * 16) + (fr & 3) * 4;
     }
     // fragment i of the A rows (j of the B rows) for phase kk, from the stage at `src`
 #define FAAR_FRAG_A(SRC, KKI, I)                                                                                         \
@@ -1090,6 +1106,10 @@ typedef DmaCfg<128, 128, 2, 2> CfgS;  // small outputs, two workgroups per compu
 typedef Dma64Cfg<256, 256, 2, 4, 2> CfgL64;  // 2 x 64 KB
 typedef Dma64Cfg<256, 128, 4, 2, 3> CfgM64;  // 3 x 48 KB: copies stay in flight for two slices
 typedef Dma64Cfg<256, 256, 2, 4, 2, true> CfgT64;  // CfgL64 on token-major operands
+// ... and with 192 rows (columns) per tile: 6144 x 2048 is 24 x 8 = 192 tiles of 256 x 256 -- a quarter of the 256 compute units
+// idle -- but 32 x 8 = 256 tiles of 192 x 256
+typedef Dma64Cfg<192, 256, 2, 4, 2, true> CfgT64A;
+typedef Dma64Cfg<256, 192, 4, 2, 2, true> CfgT64B;
 
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
@@ -1254,21 +1274,48 @@ hipError_t launch_gemm_gram(const bf16_t* delta, const bf16_t* gram, int64_t O, 
   return run(delta, gram, d, p, e, st);
 }
 
-bool gemm_tn_usable(int64_t M, int64_t N, int64_t T) {
-  if (T <= 0 || T % DBK64 != 0 || M % 8 != 0 || N % 8 != 0) return false;
-  return plan_gemm(GemmDims{M, N, T, T, T}, true, kEpiF32).kind == KIND_L64;
+// Tile shape of the token-major product: 0 not usable, 1 256 x 256, 2 192 x 256, 3 256 x 192.  The contraction split is the
+// one planned for 256 x 256 tiles.  fill_device: the kernel has the device to itself, so a 192-wide shape is taken when its
+// work items need fewer rounds of the 256 compute units, weighted by the tile's area (6144 x 2048, one split: 192 items of
+// 65536 -> one round at 65536; 256 items of 49152 -> one round at 49152).  Otherwise other kernels run on whatever units this
+// one leaves idle, and the tile with the most work per byte moved wins: 256 x 256.
+int gemm_tn_tiles(int64_t M, int64_t N, int64_t T, bool fill_device) {
+  if (T <= 0 || T % DBK64 != 0 || M % 8 != 0 || N % 8 != 0) return 0;
+  const Plan p = plan_gemm(GemmDims{M, N, T, T, T}, true, kEpiF32);
+  if (p.kind != KIND_L64) return 0;
+  if (!fill_device) return 1;
+  const int64_t cus = 256;
+  auto rounds_area = [&](int64_t bm, int64_t bn) {
+    const int64_t items = (int64_t)ceil_div(M, bm) * ceil_div(N, bn) * p.n_split;
+    return (items + cus - 1) / cus * bm * bn;
+  };
+  const int64_t c1 = rounds_area(256, 256), c2 = rounds_area(192, 256), c3 = rounds_area(256, 192);
+  if (c2 < c1 && c2 <= c3) return 2;
+  if (c3 < c1) return 3;
+  return 1;
+}
+bool gemm_tn_usable(int64_t M, int64_t N, int64_t T) { return gemm_tn_tiles(M, N, T, false) != 0; }
+
+template <class C, class Epi>
+static hipError_t run_tn(const bf16_t* A, const bf16_t* B, const GemmDims& d, int n_split, Epi epi, hipStream_t st) {
+  const int tiles_m = ceil_div(d.M, C::BM), tiles_n = ceil_div(d.N, C::BN);
+  const int ksteps = static_cast<int>(d.Kd / DBK64);
+  const int per_split = (ksteps + n_split - 1) / n_split;
+  const int64_t items = (int64_t)tiles_m * tiles_n * n_split;
+  const dim3 grid(static_cast<unsigned>((items + 7) / 8 * 8));
+  hipLaunchKernelGGL((k_gemm_dma64<C, Epi>), grid, dim3(C::THREADS), 0, st, A, B, d, tiles_m, tiles_n, n_split, per_split, epi);
+  return hipGetLastError();
 }
 
-hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, hipStream_t st) {
-  if (!gemm_tn_usable(d.M, d.N, d.Kd) || d.lda % 8 != 0 || d.ldb % 8 != 0) return hipErrorInvalidValue;
+hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, bool fill_device,
+                              hipStream_t st) {
+  const int tiles = gemm_tn_tiles(d.M, d.N, d.Kd, fill_device);
+  if (tiles == 0 || d.lda % 8 != 0 || d.ldb % 8 != 0) return hipErrorInvalidValue;
   const Plan p = plan_gemm(GemmDims{d.M, d.N, d.Kd, d.Kd, d.Kd}, true, kEpiF32);
   if (p.n_split != n_split) return hipErrorInvalidValue;
-  const int ksteps = static_cast<int>(d.Kd / DBK64);
-  const int per_split = (ksteps + p.n_split - 1) / p.n_split;
-  const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
-  hipLaunchKernelGGL((k_gemm_dma64<CfgT64, EpiF32>), grid, dim3(CfgT64::THREADS), 0, st, A, B, d, p.tiles_m, p.tiles_n, p.n_split,
-                     per_split, EpiF32{out});
-  return hipGetLastError();
+  if (tiles == 2) return run_tn<CfgT64A>(A, B, d, n_split, EpiF32{out}, st);
+  if (tiles == 3) return run_tn<CfgT64B>(A, B, d, n_split, EpiF32{out}, st);
+  return run_tn<CfgT64>(A, B, d, n_split, EpiF32{out}, st);
 }
 
 hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDims d, unsigned long long* clocks,
@@ -1281,17 +1328,19 @@ hipError_t launch_gemm_probe(int mode, const bf16_t* A, const bf16_t* B, GemmDim
   if (mode & 4) {   // the same loops on token-major operands: the buffers are read as A [Kd, M], B [Kd, N]
     if (!gemm_tn_usable(d.M, d.N, d.Kd)) return hipErrorNotSupported;
     const GemmDims t{d.M, d.N, d.Kd, d.M, d.N};
-    const int ksteps = static_cast<int>(d.Kd / DBK64);
-    const dim3 grid(static_cast<unsigned>((p.items() + 7) / 8 * 8));
-#define FAAR_PROBE_TN(MODE) \
-  hipLaunchKernelGGL((k_gemm_dma64<CfgT64, EpiProbe<MODE>>), grid, dim3(CfgT64::THREADS), 0, st, A, B, t, p.tiles_m, p.tiles_n, 1, \
-                     ksteps, EpiProbe<MODE>{clocks, sink, 0, 0, 0.0f})
-    if ((mode & 3) == 0) FAAR_PROBE_TN(0);
-    else if ((mode & 3) == 1) FAAR_PROBE_TN(1);
-    else FAAR_PROBE_TN(2);
-#undef FAAR_PROBE_TN
-    return hipGetLastError();
+    if (mode & 8) {   // ... on 192-wide tiles (whole loop only), whichever of the two shapes divides the product better
+      if ((mode & 3) != 0) return hipErrorNotSupported;
+      const bool a192 = ceil_div(d.M, 192) * (int64_t)ceil_div(d.N, 256) <= ceil_div(d.M, 256) * (int64_t)ceil_div(d.N, 192);
+      *items = a192 ? ceil_div(d.M, 192) * (int64_t)ceil_div(d.N, 256) : ceil_div(d.M, 256) * (int64_t)ceil_div(d.N, 192);
+      if (*items > capacity) return hipErrorInvalidValue;
+      const EpiProbe<0> e{clocks, sink, 0, 0, 0.0f};
+      return a192 ? run_tn<CfgT64A>(A, B, t, 1, e, st) : run_tn<CfgT64B>(A, B, t, 1, e, st);
+    }
+    if ((mode & 3) == 0) return run_tn<CfgT64>(A, B, t, 1, EpiProbe<0>{clocks, sink, 0, 0, 0.0f}, st);
+    if ((mode & 3) == 1) return run_tn<CfgT64>(A, B, t, 1, EpiProbe<1>{clocks, sink, 0, 0, 0.0f}, st);
+    return run_tn<CfgT64>(A, B, t, 1, EpiProbe<2>{clocks, sink, 0, 0, 0.0f}, st);
   }
+  if (mode & 8) return hipErrorNotSupported;
   if (mode == 0) return run(A, B, d, p, EpiProbe<0>{clocks, sink, 0, 0, 0.0f}, st);
   if (mode == 1) return run(A, B, d, p, EpiProbe<1>{clocks, sink, 0, 0, 0.0f}, st);
   return run(A, B, d, p, EpiProbe<2>{clocks, sink, 0, 0, 0.0f}, st);

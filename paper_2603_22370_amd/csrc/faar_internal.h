@@ -198,7 +198,10 @@ int choose_split(int64_t M, int64_t N, int64_t Kd);
 // index is the row index; d.Kd = T).  Only where gemm_tn_usable says so (T a multiple of 64, M and N multiples of 8, a shape
 // the planner gives 256 x 256 tiles); n_split = choose_split(M, N, T) as for launch_gemm_f32.
 bool gemm_tn_usable(int64_t M, int64_t N, int64_t T);
-hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, hipStream_t st);
+// 0 not usable, 1 256 x 256 tiles, 2 192 x 256, 3 256 x 192 (the last two only with fill_device: the kernel runs alone)
+int gemm_tn_tiles(int64_t M, int64_t N, int64_t T, bool fill_device);
+hipError_t launch_gemm_f32_tn(const bf16_t* A, const bf16_t* B, GemmDims d, float* out, int n_split, bool fill_device,
+                              hipStream_t st);
 // The kernel variant, tile shape and contraction split the launchers above pick for an M x N x Kd product
 // (kind: 0 generic, 1 / 2 / 3 the BK = 32 kernels with 256x256 / 256x128 / 128x128 tiles, 4 / 5 the BK = 64
 // kernels with 256x256 / 256x128 tiles).  Pure host function.

@@ -24,6 +24,7 @@ class StepCase:
     chained: bool = False           # dY_ext given and dX requested
     full_size: bool = False         # a benchmark shape at its real size: one beta, no repeated variants
     fp32_small: bool = False        # the 256x256 float32 parity configuration (own generator)
+    whole_device: bool = False      # stepped with FAAR_STEP_WHOLE_DEVICE: the token-major dW GEMM may take 192-wide tiles
 
 
 STEP_CASES = [
@@ -42,6 +43,12 @@ STEP_CASES = [
     StepCase("dw_one_slice", 288, 12288, 33, 31),                # dW GEMM: 256x128 tiles, a single 64-token slice
     # dW GEMM on token-major operands (upstream gradient given): last tiles 8 rows / 16 columns wide, 32 slices split 11 + 11 + 10
     StepCase("dw_token_major_ragged", 3592, 1040, 2048, 32, chained=True),
+    # ... with the device to itself: on 192 x 256 tiles (last tile 72 rows x 80 columns) and on 256 x 192 tiles (last 152 x 160),
+    # whole and split in three
+    StepCase("dw_token_major_192x256", 1032, 7248, 512, 34, chained=True, whole_device=True),
+    StepCase("dw_token_major_256x192", 8088, 1312, 512, 35, chained=True, whole_device=True),
+    StepCase("dw_token_major_192x256_split", 528, 6576, 2048, 36, whole_device=True),
+    StepCase("dw_token_major_256x192_split", 6576, 528, 2048, 37, whole_device=True),
     # token-major dY out of the residual GEMM (with H) on 256x256 tiles with 32-wide slices: K a multiple of 32 only
     StepCase("rows_k160", 12288, 160, 4096, 33),
     # the shapes the benchmark times, at full size
@@ -50,7 +57,8 @@ STEP_CASES = [
     StepCase("llama_down_proj", 2048, 8192, 4096, 2, gated_input=True, chained=True, full_size=True),
     StepCase("qwen_k_proj", 1024, 2048, 8192, 3, quantised_acts=True, chained=True, full_size=True),
     StepCase("qwen_q_proj", 2048, 2048, 8192, 5, full_size=True),                       # the default benchmark's q / o projection
-    StepCase("qwen_down_proj", 2048, 6144, 8192, 6, gated_input=True, full_size=True),  # ... and its down projection
+    StepCase("qwen_down_proj", 2048, 6144, 8192, 6, gated_input=True, full_size=True, whole_device=True),   # ... its down projection
+    StepCase("qwen_gate_proj", 6144, 2048, 8192, 7, full_size=True, whole_device=True),   # ... and its gate / up projection
     StepCase("qwen_gate_proj_T16384", 6144, 2048, 16384, 4, chained=True, full_size=True),
 ]
 

@@ -128,6 +128,19 @@ def test_token_split_of_the_dw_gemm_is_sane():
     assert fb.faar_dw_split(8192, 2048, 4096) == 1
 
 
+def test_token_major_dw_gemm_choice_is_sane():
+    """faar_dw_token_major is pure host logic: 0 where the token-major form does not apply, 256 x 256 tiles (1) beside other
+    streams, and a 192-wide tile only for a step that has the device to itself and only where it saves rounds of the units."""
+    assert fb.faar_dw_token_major(0, 16, 64) == 0 and fb.faar_dw_token_major(2048, 2048, 0) == 0    # invalid shapes
+    assert fb.faar_dw_token_major(2048, 2048, 8192 + 32) == 0                                       # T not a multiple of 64
+    assert fb.faar_dw_token_major(256, 256, 64) == 0                                                # too small for 256-wide tiles
+    for O, K in [(2048, 2048), (6144, 2048), (2048, 6144)]:
+        assert fb.faar_dw_token_major(O, K, 8192) == 1
+    assert fb.faar_dw_token_major(6144, 2048, 8192, whole_device=True) == 2      # 192 tiles of 256 x 256, 256 of 192 x 256
+    assert fb.faar_dw_token_major(2048, 6144, 8192, whole_device=True) == 3
+    assert fb.faar_dw_token_major(2048, 2048, 8192, whole_device=True) == 1      # 64 tiles x 4 splits fill the device already
+
+
 def test_batched_codec_calls_validate_every_descriptor_first():
     L = fb.lib()
     good = fb.faar_tensor(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 256)

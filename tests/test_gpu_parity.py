@@ -254,7 +254,7 @@ def upstream_gradient(c, seed):
     return synth.round_to_bf16((rng.standard_normal((c.T, c.O)) * 1e-3).astype(np.float32))
 
 
-def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False, split=False):
+def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False, split=False, whole_device=False):
     """split: the step is given the gradient constant H; its oracle of record is then the "split" contract."""
     Wd, sg, scales, q, Xq, Y, Xt, C, hk = _setup(c, h=split)
     alpha = 1.0 / (c.T * c.O)
@@ -267,7 +267,7 @@ def _one_step(c, beta, V0, t=1, m0=None, u0=None, dY_ext=None, want_dX=False, sp
     dX = torch.empty((c.T, c.K), dtype=torch.bfloat16, device="cuda") if want_dX else None
     faar.faar_layer_step(Wd, sg, scales, V, m, u, Xq, Xt, *C, beta, HYP["lambda_round"], alpha, HYP["lr"],
                          HYP["beta1"], HYP["beta2"], HYP["eps"], t, losses, ws,
-                         dY_ext=None if dY_ext is None else dev(dY_ext, True), dX=dX, **hk)
+                         dY_ext=None if dY_ext is None else dev(dY_ext, True), dX=dX, whole_device=whole_device, **hk)
     torch.cuda.synchronize()
     out = host(V), host(m), host(u), host(losses), (None if dX is None else host(dX))
     del Wd, Xq, Y, Xt, C, V, m, u, ws, dX, hk
@@ -342,7 +342,7 @@ def step_case_errors(name, beta, chained, split=False):
     q = fo.quant_rtn(c.W, c.w_is_bf16)
     V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
     dY_ext = upstream_gradient(c, p.seed) if chained else None
-    V, m, u, losses, dX, ref = _one_step(c, beta, V0, dY_ext=dY_ext, want_dX=chained, split=split)
+    V, m, u, losses, dX, ref = _one_step(c, beta, V0, dY_ext=dY_ext, want_dX=chained, split=split, whole_device=p.whole_device)
     ex, de = ref[False], ref[True]
     errs = {"loss_exact": abs(losses[0] - ex["L_mse"]) / ex["L_mse"], "loss_declared": abs(losses[0] - de["L_mse"]) / de["L_mse"],
             "round": abs(losses[1] - ex["L_round"]) / ex["L_round"],
@@ -416,6 +416,22 @@ def test_layer_step_chained_dY_ext_and_dX():
         _check_grad(m.astype(np.float64) / (1 - HYP["beta1"]), ref)
         _check_dx(dX, ref, "upstream" if ext is not None else "local")
         assert losses[0] == pytest.approx(ref[False]["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER)
+
+
+@pytest.mark.parametrize("name", ["dw_token_major_192x256_split", "dw_token_major_256x192"])
+def test_whole_device_tiles_change_no_bit(name):
+    """FAAR_STEP_WHOLE_DEVICE only changes which tile of the token-major dW GEMM an output element falls into: every sum runs
+    over the same terms in the same order, so the step's state and losses are identical with and without it."""
+    p = BY_NAME[name]
+    assert faar.faar_dw_token_major(p.O, p.K, p.T, True) in (2, 3) and faar.faar_dw_token_major(p.O, p.K, p.T, False) == 1
+    c = build_case(name)
+    q = fo.quant_rtn(c.W, c.w_is_bf16)
+    V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+    dY_ext = upstream_gradient(c, p.seed) if p.chained else None
+    a = _one_step(c, 8.0, V0, dY_ext=dY_ext, want_dX=p.chained, split=True, whole_device=False)
+    b = _one_step(c, 8.0, V0, dY_ext=dY_ext, want_dX=p.chained, split=True, whole_device=True)
+    for x, y in zip(a[:4], b[:4]):
+        assert np.array_equal(x, y)
 
 
 @pytest.mark.parametrize("split", [False, True], ids=["c_form", "h_form"])

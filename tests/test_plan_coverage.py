@@ -115,3 +115,31 @@ def test_token_major_residual_gemm_runs_kernels_that_parity_cases_cover():
     for O, K in [(2048, 2048), (1024, 2048), (6144, 2048), (2048, 6144)]:
         assert not fb.faar_dw_token_major(O, K, 8192) or combo(O, K, 8192) in full, (O, K)
     assert fb.faar_dw_token_major(6144, 2048, 8192) and fb.faar_dw_token_major(2048, 6144, 8192)
+
+
+def test_token_major_dw_gemm_tiles_are_all_reached_by_parity_cases():
+    """The token-major dW GEMM has three tile shapes (two of them only for a step that has the device to itself), each whole or
+    with the contraction split: every combination some layer shape takes is taken by a parity case (each runs it with H and
+    its own gradient; chained ones also with an upstream one)."""
+    def combo(O, K, T, whole_device):
+        return (fb.faar_dw_token_major(O, K, T, whole_device), "split" if fb.faar_gemm_plan(fb.K_GEMM_DW, O, K, T)[3] > 1 else "whole")
+
+    reachable = {}
+    dims = DIMS + [528, 1032, 1312, 6576, 7248, 8088]
+    for O, K, T in itertools.product(dims, dims, TOKENS):
+        if O * K * T <= 2 ** 40 and fb.faar_dw_token_major(O, K, T):
+            assert fb.faar_dw_token_major(O, K, T) == 1
+            for whole_device in (False, True):
+                reachable.setdefault(combo(O, K, T, whole_device), (O, K, T))
+    assert {k[0] for k in reachable} == {1, 2, 3}
+    token_major = [c for c in STEP_CASES if fb.faar_dw_token_major(c.O, c.K, c.T)]
+    covered = {combo(c.O, c.K, c.T, c.whole_device) for c in token_major}
+    missing = {k: v for k, v in reachable.items() if k not in covered}
+    assert not missing, f"token-major dW variants no parity case reaches (with an example shape): {missing}"
+    assert {combo(c.O, c.K, c.T, c.whole_device)[0] for c in token_major if c.chained} == {1, 2, 3}
+    # alone on the device, the default benchmark's two large shapes take the 192-wide tiles, and full-size parity cases run them
+    full = {combo(c.O, c.K, c.T, c.whole_device) for c in STEP_CASES if c.full_size}
+    assert combo(6144, 2048, 8192, True) == (2, "whole") and combo(2048, 6144, 8192, True) == (3, "whole")
+    assert combo(6144, 2048, 8192, True) in full and combo(2048, 6144, 8192, True) in full
+    # ... and beside other streams 256 x 256 ones, split or not, which full-size cases run as well
+    assert {(1, "whole"), (1, "split")} <= full
