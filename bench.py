@@ -1165,6 +1165,20 @@ def run_gemm_ceiling(args) -> dict:
         e1.record()
         torch.cuda.synchronize()
         rows[label] = row_of(e0.elapsed_time(e1) / n_time * 1e3, clocks, variant, mode != fb.PROBE_DMA_ONLY)
+    # the token-major form of the same product (the buffers read as [Kd, M] and [Kd, N]: same bytes, transposing LDS reads),
+    # on 256 x 256 tiles and on the 192-wide tiles a step that has the device to itself may take
+    if fb.faar_dw_token_major(M, N, Kd):
+        for label, mode in (("whole loop, token-major operands", fb.PROBE_FULL + fb.PROBE_TOKEN_MAJOR),
+                            ("matrix instructions only, token-major operands", fb.PROBE_MFMA_ONLY + fb.PROBE_TOKEN_MAJOR),
+                            ("whole loop, token-major operands, 192-wide tiles", fb.PROBE_TOKEN_MAJOR_192)):
+            for _ in range(n_warm):
+                clocks, variant = fb.faar_gemm_probe(mode, A, B)
+            e0.record()
+            for _ in range(n_time):
+                clocks, variant = fb.faar_gemm_probe(mode, A, B)
+            e1.record()
+            torch.cuda.synchronize()
+            rows[label] = row_of(e0.elapsed_time(e1) / n_time * 1e3, clocks, variant)
     # the same loops when the operands are NOT in the 256 MB last-level cache, as a step's dW GEMM finds them: 512 MB are
     # read (nothing written) before every launch; the events bracket the launch alone
     evict = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").view(torch.int32)

@@ -168,7 +168,11 @@ int faar_gemm_plan(int which, int64_t O, int64_t K, int64_t T, int32_t* out);
  * to clocks[2 i] and the ticks of the constant 100 MHz counter to clocks[2 i + 1]: their ratio is the clock the
  * compute units ran at.  info (HOST, out): [0] work items, [1] kernel variant (FAAR_GEMM_*).  capacity: pairs that
  * fit in clocks (FAAR_E_WORKSPACE if too few); sink: one device float, never written for real operands.
- * FAAR_E_UNSUPPORTED when the product would not run on the 64-wide-slice kernels. */
+ * mode + 4: the same three loops of the token-major kernel (the dW GEMM of a step whose operands are used as the layers
+ * produce them): the two buffers are then read as A [Kd, M] and B [Kd, N] -- the same bytes, the contraction index as the row
+ * index -- where faar_dw_token_major(M, N, Kd, 0) is non-zero.  mode 12: the whole token-major loop on 192 x 256 or 256 x 192
+ * tiles, whichever covers the M x N outputs with fewer tiles.
+ * FAAR_E_UNSUPPORTED when the product would not run on the 64-wide-slice kernels, or not in the token-major form asked for. */
 int faar_gemm_probe(int mode, int64_t M, int64_t N, int64_t Kd, const void* A, const void* B,
                     unsigned long long* clocks, int64_t capacity, float* sink, int32_t* info, void* stream);
 

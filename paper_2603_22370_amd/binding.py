@@ -232,6 +232,7 @@ def faar_gemm_plan(which: int, O: int, K: int, T: int):
 
 
 PROBE_FULL, PROBE_MFMA_ONLY, PROBE_DMA_ONLY = 0, 1, 2
+PROBE_TOKEN_MAJOR, PROBE_TOKEN_MAJOR_192 = 4, 12    # added to a mode / a mode of its own (whole loop on 192-wide tiles)
 _probe_buffers = {}
 
 
