@@ -321,7 +321,11 @@ class LinearJob:
                              "frac": round(ach / HBM_PEAK_GBS, 4)}
                 if step_bytes < 256e6:     # the step's working set fits the 256 MB Infinity Cache: not an HBM rate
                     out[name]["note"] = "effective rate: working set resident in the Infinity Cache"
-            out[name]["traffic"] = traffic_for(name, self.O, self.K, self.T)
+            # the dW GEMM has its own counter rows for the 192-wide tiles a step takes when it has the device to itself
+            from paper_2603_22370_amd import binding as fb
+            wide = (name == "gemm_dw" and self.form == "token" and self.whole_device
+                    and fb.faar_dw_token_major(self.O, self.K, self.T, True) in (2, 3))
+            out[name]["traffic"] = traffic_for(name + ("_whole_device" if wide else ""), self.O, self.K, self.T)
         return out
 
 
@@ -366,8 +370,8 @@ def run_layer(args) -> dict:
     T = 8192
     gram = args.workload == "qwen_layer_gram"
     jobs = make_block_jobs(T, args.quantised_acts, "gram" if gram else "token")
-    for j in jobs:
-        j.whole_device = args.streams == 1
+    for j in jobs:                           # one stream: nothing runs beside a step, so it may take tiles that fill every unit
+        j.whole_device = args.streams == 1 if args.whole_device == "auto" else args.whole_device == "on"
     torch.cuda.synchronize()
     # Stage 1 optimises every linear against frozen inputs: the seven jobs are independent, so they are issued on
     # several HIP streams (default priority).  While one job's workgroups sit in a GEMM epilogue or in the
@@ -443,7 +447,8 @@ def run_layer(args) -> dict:
                                " + K steps + harden_pack; one timed step = "
                                f"one step of every linear; value = linear-layer steps/s; the 7 independent jobs issued on {args.streams} "
                                "HIP stream(s)",
-                   "T": T, "linears": n_lin, "weights": weights, "streams": args.streams},
+                   "T": T, "linears": n_lin, "weights": weights, "streams": args.streams,
+                   "whole_device_tiles": bool(jobs[0].whole_device)},
         "weight_elems_per_sec": round(weights * args.steps / elapsed, 1),
         "step_gemm_tflops": round(flops_per_set / (ms_per_step * 1e-3) / 1e12, 1),
         "roofline": {"kernel": f"{dom_l}.{dom_k}", "bound": dom["bound"], "achieved": dom["achieved"],
@@ -481,7 +486,7 @@ def run_linear(args) -> dict:
     W = torch.from_numpy(W_h).cuda().to(torch.bfloat16)
     Xq = torch.from_numpy(X_h).cuda().to(torch.bfloat16)
     j = LinearJob(args.workload, O, K, T, W, Xq, args.quantised_acts, args.form)
-    j.whole_device = True
+    j.whole_device = args.whole_device != "off"
     gram = args.form == "gram"
     torch.cuda.synchronize()
 
@@ -1237,6 +1242,8 @@ def main() -> int:
                     help="single-linear workloads: faar_layer_step (token) or the optional faar_layer_step_gram (gram)")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3],
                     help="qwen_layer: HIP streams the seven independent per-linear jobs are issued on")
+    ap.add_argument("--whole-device", default="auto", choices=["auto", "on", "off"],
+                    help="layer jobs: step with FAAR_STEP_WHOLE_DEVICE (auto: when the jobs are issued on one stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--probe-steps", type=int, default=12)
