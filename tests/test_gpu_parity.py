@@ -647,6 +647,65 @@ def test_forward_ready_is_checked_on_the_device():
     assert nan3(s["losses"]) and unchanged(s, snap)
 
 
+def test_token_major_steps_chain_and_guard_their_prepared_forward():
+    """The same two properties on a shape whose step runs the token-major kernels (H form, own gradient: the residual GEMM leaves
+    dY token-major and carries the tag check, the dW GEMM reads dY and X_q as they are; 3 token slices, so the 2-stage ring
+    wraps): steps chained through beta_next / forward_ready give the plain sequence bit for bit, and a forward nobody
+    prepared, or one prepared at another beta, gives NaN losses and leaves the state untouched."""
+    O, K, T = 2560, 3328, 192
+    assert faar.faar_dw_token_major(O, K, T) == 1
+    c = synth.llm_linear("token_major_chain", O, K, T, 51)
+    Wd, sg, scales, q, Xq, Y, Xt, C, hk = _setup(c, h=True)
+    alpha = 1.0 / (T * O)
+    ws = faar.layer_step_workspace(O, K, T)
+    betas = [4.0, 7.5, 9.0, 16.0]
+
+    def run(fused):
+        V, _ = faar.faar_init_v(Wd, sg, scales)
+        state = [V, torch.zeros_like(V), torch.zeros_like(V)]
+        losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+        ws.zero_()
+        out = []
+        for i, beta in enumerate(betas):
+            nxt = betas[i + 1] if fused and i + 1 < len(betas) else 0.0
+            faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, beta, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, 1 + i, losses, ws,
+                                 beta_next=nxt, forward_ready=fused and i > 0, **hk)
+            out.append(losses.clone())
+        torch.cuda.synchronize()
+        return state, out
+
+    a, la = run(False)
+    b, lb = run(True)
+    for x, y in zip(a + la, b + lb):
+        assert torch.equal(x, y)
+    assert not torch.isnan(la[-1]).any()
+    # the first step agrees with the oracle (the later ones are covered bit for bit by the above and by the per-step cases)
+    V0 = fo.init_v(c.W, q["s_global"], q["scales"])["V"]
+    r = fo.layer_step(c.W, q["s_global"], q["scales"], V0, np.zeros_like(V0), np.zeros_like(V0), c.Xq, c.Y_fp, betas[0], 0.01,
+                      alpha, 5e-3, 0.9, 0.999, 1e-8, 1)
+    assert float(la[0][0]) == pytest.approx(r["L_mse"], rel=TOL_LOSS_EXACT_OUTLIER)
+    assert float(la[0][1]) == pytest.approx(r["L_round"], rel=1e-5)
+    # the guard
+    V, _ = faar.faar_init_v(Wd, sg, scales)
+    state = [V, torch.zeros_like(V), torch.zeros_like(V)]
+    losses = torch.zeros(3, dtype=torch.float32, device="cuda")
+    for fill in (0, 0xA5):
+        ws.fill_(fill)
+        snap = [x.clone() for x in state]
+        faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, 6.0, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, 2, losses, ws,
+                             forward_ready=True, **hk)
+        torch.cuda.synchronize()
+        assert torch.isnan(losses).all() and all(torch.equal(x, y) for x, y in zip(state, snap))
+    faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, 4.0, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, 1, losses, ws, beta_next=6.0, **hk)
+    torch.cuda.synchronize()
+    assert not torch.isnan(losses).any()
+    snap = [x.clone() for x in state]
+    faar.faar_layer_step(Wd, sg, scales, *state, Xq, Xt, *C, 7.0, 0.01, alpha, 5e-3, 0.9, 0.999, 1e-8, 2, losses, ws,
+                         forward_ready=True, **hk)                       # prepared at beta 6
+    torch.cuda.synchronize()
+    assert torch.isnan(losses).all() and all(torch.equal(x, y) for x, y in zip(state, snap))
+
+
 def test_nvfp4_activations_in_units_of_their_tensor_scale():
     """Activations quantised to NVFP4 by the same kernel (blocks along K, their own tensor scale): W_dq in units of
     s_global is the exact product node * block scale, and a step fed (Xq, x_scale) agrees with the oracle fed the
