@@ -5,7 +5,10 @@
 // Every product is computed as an "NT" GEMM  acc[m][n] = sum_k A[m][k] B[n][k]  with both operands
 // row-major and the contraction index contiguous; operands that the mathematics wants transposed
 // (X_q^T, dY^T, W_q^T) are produced in that layout by the kernel that writes them, so one tuned
-// main loop serves all of them.
+// main loop serves all of them.  The one exception is the weight gradient of LLM-sized layers, whose
+// contraction index is the token -- the row index of everything the layers produce: k_gemm_dma64 has a
+// token-major form (acc[m][n] = sum_t A[t][m] B[t][n], LDS transposing reads) that takes dY and X_q as
+// they are.
 //
 // Three main loops:
 //  * k_gemm_dma64 (contraction length a multiple of 64 -- every GEMM of an LLM-shaped layer): 256x256 or
