@@ -998,6 +998,32 @@ k_gemm_dma64(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B, GemmDim
           const int mi = m / TN, mj = (mi & 1) ? TN - 1 - m % TN : m % TN;
           if constexpr (Epi::kMode != 2)
             acc[mi][mj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[cur][mi], fb[cur][mj], acc[mi][mj], 0, 0, 0);
+          if constexpr (Epi::kMode != 2 && C::kTokenMajor && C::FSTEP == 2) {
+            // token-major: a fragment is two transposing reads; one of them per MFMA instead of both every other MFMA
+            // (in a slice's last phase, where the copies are issued too, spread over all of the phase's MFMAs: every
+            // SKIP-th one goes without; in the others the reads have to be complete at the next barrier, so they go first)
+            constexpr int SKIP = NM / (NM - 2 * NF);
+            static_assert(NM % (NM - 2 * NF) == 0, "read schedule");
+            const bool spread = kk == KK - 1;
+            const int r = spread ? m - m / SKIP : m;
+            if (r < 2 * NF && !(spread && m % SKIP == SKIP - 1)) {
+              const int f = r / 2, h = r % 2;
+              typedef __attribute__((address_space(3))) s16x4* lds_ptr;
+              if (f == 0 || f > TN) {
+                const int i = f == 0 ? 0 : f - TN;
+                const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src + a_tr[i] + 32 * nkk * C::BM + h * 4 * C::BM));
+                s16x8 t = __builtin_bit_cast(s16x8, fa[cur ^ 1][i]);
+                if (h == 0) t.lo = v; else t.hi = v;
+                fa[cur ^ 1][i] = __builtin_bit_cast(bf16x8, t);
+              } else {
+                const int j = f - 1;
+                const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(src + b_tr[j] + 32 * nkk * C::BN + h * 4 * C::BN));
+                s16x8 t = __builtin_bit_cast(s16x8, fb[cur ^ 1][j]);
+                if (h == 0) t.lo = v; else t.hi = v;
+                fb[cur ^ 1][j] = __builtin_bit_cast(bf16x8, t);
+              }
+            }
+          } else
           if (Epi::kMode != 2 && m % C::FSTEP == 0 && m / C::FSTEP < NF) {  // next phase's fragments: A0, B0..B(TN-1), A1..A(TM-1)
             const int f = m / C::FSTEP;
             if (f == 0) fa[cur ^ 1][0] = FAAR_FRAG_A(src, nkk, 0);
